@@ -1,0 +1,427 @@
+/*
+ * tdo.c -- plain CPU oracle (TEST INFRASTRUCTURE ONLY; see tdo.h).
+ *
+ * Scalar loops, one definition per function, no blocking or fusion.  The only
+ * parallelism is an OpenMP loop over agents.  Build: gcc -O2 -fopenmp
+ * -ffp-contract=off (no implicit fused multiply-adds: the fp32 path below pins
+ * its operation order explicitly).
+ */
+#include "tdo.h"
+
+#include <math.h>
+#include <stdlib.h>
+#include <string.h>
+#ifdef _OPENMP
+#include <omp.h>
+#endif
+
+/* ---- bf16 storage format: upper 16 bits of an IEEE fp32 ------------------ */
+
+static float bf16_to_f32(uint16_t h) {
+  uint32_t u = (uint32_t)h << 16;
+  float f;
+  memcpy(&f, &u, sizeof f);
+  return f;
+}
+
+/* round-to-nearest-even; NaN stays NaN (quieted) */
+static uint16_t f32_to_bf16(float f) {
+  uint32_t u;
+  memcpy(&u, &f, sizeof u);
+  if ((u & 0x7fffffffu) > 0x7f800000u) return (uint16_t)((u >> 16) | 0x0040u);
+  u += 0x7fffu + ((u >> 16) & 1u);
+  return (uint16_t)(u >> 16);
+}
+
+/* double -> bf16 with a single rounding: go through fp32, but when that first
+ * rounding was inexact and landed exactly on a bf16 tie, nudge the fp32 value
+ * off the tie towards the true value so the second rounding goes the right way. */
+static uint16_t f64_to_bf16(double d) {
+  float f = (float)d;
+  uint32_t u;
+  memcpy(&u, &f, sizeof u);
+  if ((u & 0x7fffffffu) >= 0x7f800000u) return f32_to_bf16(f);
+  if ((double)f != d && (u & 0xffffu) == 0x8000u) {
+    if (fabs((double)f) < fabs(d)) u |= 1u; else u -= 1u;
+    memcpy(&f, &u, sizeof f);
+  }
+  return f32_to_bf16(f);
+}
+
+/* ---- RoPE tables: phi_j = delta * theta^(-2j/D)  [Sec. 2.2] -------------- */
+
+int tdo_rope_table_f64(double theta, int32_t head_dim, int64_t delta, double* c, double* s) {
+  if (!c || !s || head_dim <= 0 || (head_dim & 1) || !(theta > 0.0)) return -1;
+  for (int32_t j = 0; j < head_dim / 2; ++j) {
+    double inv_freq = pow(theta, -(double)(2 * j) / (double)head_dim);
+    double phi = (double)delta * inv_freq;
+    c[j] = cos(phi);
+    s[j] = sin(phi);
+  }
+  return 0;
+}
+
+int tdo_rope_table_f32(double theta, int32_t head_dim, int64_t delta, float* c, float* s) {
+  if (!c || !s || head_dim <= 0 || (head_dim & 1) || !(theta > 0.0)) return -1;
+  double* t = (double*)malloc(sizeof(double) * (size_t)head_dim);
+  if (!t) return -2;
+  tdo_rope_table_f64(theta, head_dim, delta, t, t + head_dim / 2);
+  for (int32_t j = 0; j < head_dim / 2; ++j) {
+    c[j] = (float)t[j];
+    s[j] = (float)t[head_dim / 2 + j];
+  }
+  free(t);
+  return 0;
+}
+
+static int geom_ok(const tdo_geom* g) {
+  return g && g->num_kv_heads > 0 && g->head_dim > 0 && !(g->head_dim & 1) && g->page_tokens > 0 &&
+         (g->rope_style == TDO_ROPE_HALF || g->rope_style == TDO_ROPE_INTERLEAVED) &&
+         g->rope_theta > 0.0 && (g->math == TDO_MATH_F32 || g->math == TDO_MATH_F64);
+}
+
+typedef struct {
+  int32_t half;
+  float*  cf; float*  sf;   /* fp32 tables (TDO_MATH_F32) */
+  double* cd; double* sd;   /* fp64 tables (TDO_MATH_F64) */
+} rope_tab;
+
+static int tab_init(rope_tab* t, const tdo_geom* g, int64_t delta) {
+  t->half = g->head_dim / 2;
+  t->cd = (double*)malloc(sizeof(double) * 2 * (size_t)t->half);
+  t->cf = (float*)malloc(sizeof(float) * 2 * (size_t)t->half);
+  if (!t->cd || !t->cf) { free(t->cd); free(t->cf); return -2; }
+  t->sd = t->cd + t->half;
+  t->sf = t->cf + t->half;
+  tdo_rope_table_f64(g->rope_theta, g->head_dim, delta, t->cd, t->sd);
+  tdo_rope_table_f32(g->rope_theta, g->head_dim, delta, t->cf, t->sf);
+  return 0;
+}
+
+static void tab_free(rope_tab* t) { free(t->cd); free(t->cf); }
+
+/* index of the two members of pair j inside a head */
+static void pair_index(const tdo_geom* g, int32_t j, int32_t* a, int32_t* b) {
+  if (g->rope_style == TDO_ROPE_HALF) { *a = j; *b = j + g->head_dim / 2; }
+  else { *a = 2 * j; *b = 2 * j + 1; }
+}
+
+/* y_a = x_a cos - x_b sin ; y_b = x_b cos + x_a sin.
+ * fp32 path, fixed order: one rounded product, then one fused multiply-add. */
+static void rot_f32(float xa, float xb, float c, float s, float* ya, float* yb) {
+  float t = xb * s;
+  float u = xa * s;
+  *ya = fmaf(xa, c, -t);
+  *yb = fmaf(xb, c, u);
+}
+
+/* one [H][D] row, fp32 in / fp32 out */
+static void rotate_row_f32io(const tdo_geom* g, const rope_tab* t, const float* x, float* y) {
+  for (int32_t h = 0; h < g->num_kv_heads; ++h)
+    for (int32_t j = 0; j < t->half; ++j) {
+      int32_t a, b;
+      pair_index(g, j, &a, &b);
+      a += h * g->head_dim; b += h * g->head_dim;
+      if (g->math == TDO_MATH_F32) {
+        rot_f32(x[a], x[b], t->cf[j], t->sf[j], &y[a], &y[b]);
+      } else {
+        double xa = x[a], xb = x[b];
+        y[a] = (float)(xa * t->cd[j] - xb * t->sd[j]);
+        y[b] = (float)(xb * t->cd[j] + xa * t->sd[j]);
+      }
+    }
+}
+
+/* one [H][D] row, bf16 in / bf16 out */
+static void rotate_row_bf16(const tdo_geom* g, const rope_tab* t, const uint16_t* x, uint16_t* y) {
+  for (int32_t h = 0; h < g->num_kv_heads; ++h)
+    for (int32_t j = 0; j < t->half; ++j) {
+      int32_t a, b;
+      pair_index(g, j, &a, &b);
+      a += h * g->head_dim; b += h * g->head_dim;
+      float xa = bf16_to_f32(x[a]), xb = bf16_to_f32(x[b]);
+      if (g->math == TDO_MATH_F32) {
+        float ya, yb;
+        rot_f32(xa, xb, t->cf[j], t->sf[j], &ya, &yb);
+        y[a] = f32_to_bf16(ya);
+        y[b] = f32_to_bf16(yb);
+      } else {
+        y[a] = f64_to_bf16((double)xa * t->cd[j] - (double)xb * t->sd[j]);
+        y[b] = f64_to_bf16((double)xb * t->cd[j] + (double)xa * t->sd[j]);
+      }
+    }
+}
+
+int tdo_rotate_rows_f32(const tdo_geom* g, int64_t delta, int64_t n_rows, const float* in, float* out) {
+  if (!geom_ok(g) || n_rows < 0 || (n_rows && (!in || !out))) return -1;
+  rope_tab t;
+  if (tab_init(&t, g, delta)) return -2;
+  int64_t re = (int64_t)g->num_kv_heads * g->head_dim;
+  for (int64_t r = 0; r < n_rows; ++r) rotate_row_f32io(g, &t, in + r * re, out + r * re);
+  tab_free(&t);
+  return 0;
+}
+
+/* fp32 in, bf16 out: the rotation of tdo_rotate_rows_f32 followed by the storage rounding */
+int tdo_rotate_rows_f32_bf16(const tdo_geom* g, int64_t delta, int64_t n_rows, const float* in, uint16_t* out) {
+  if (!geom_ok(g) || n_rows < 0 || (n_rows && (!in || !out))) return -1;
+  rope_tab t;
+  if (tab_init(&t, g, delta)) return -2;
+  int64_t re = (int64_t)g->num_kv_heads * g->head_dim;
+  float* y = (float*)malloc((size_t)re * sizeof(float));
+  if (!y) { tab_free(&t); return -2; }
+  for (int64_t r = 0; r < n_rows; ++r) {
+    rotate_row_f32io(g, &t, in + r * re, y);
+    for (int64_t e = 0; e < re; ++e) out[r * re + e] = f32_to_bf16(y[e]);
+  }
+  free(y);
+  tab_free(&t);
+  return 0;
+}
+
+int tdo_rotate_rows_bf16(const tdo_geom* g, int64_t delta, int64_t n_rows, const uint16_t* in, uint16_t* out) {
+  if (!geom_ok(g) || n_rows < 0 || (n_rows && (!in || !out))) return -1;
+  rope_tab t;
+  if (tab_init(&t, g, delta)) return -2;
+  int64_t re = (int64_t)g->num_kv_heads * g->head_dim;
+  for (int64_t r = 0; r < n_rows; ++r) rotate_row_bf16(g, &t, in + r * re, out + r * re);
+  tab_free(&t);
+  return 0;
+}
+
+/* ---- round helpers ------------------------------------------------------- */
+
+static int round_ok(const tdo_geom* g, const tdo_round* r, int64_t pool_pages) {
+  if (!geom_ok(g) || !r || r->n_sessions < 0 || r->n_agents < 0 || pool_pages < 0) return 0;
+  if (r->n_sessions && (!r->span_tokens || !r->master_pos0)) return 0;
+  if (r->n_agents && (!r->agent_session || !r->agent_pos0 || !r->bt_flat || !r->bt_offset)) return 0;
+  for (int32_t s = 0; s < r->n_sessions; ++s) if (r->span_tokens[s] < 0) return 0;
+  for (int32_t i = 0; i < r->n_agents; ++i) {
+    int32_t s = r->agent_session[i];
+    if (s < 0 || s >= r->n_sessions || r->agent_pos0[i] < 0) return 0;
+    int64_t len = r->bt_offset[i + 1] - r->bt_offset[i];
+    int64_t S = r->span_tokens[s];
+    if (S > 0) {
+      int64_t need = (r->agent_pos0[i] + S - 1) / g->page_tokens + 1;
+      if (len < need) return 0;
+      for (int64_t lp = r->agent_pos0[i] / g->page_tokens; lp < need; ++lp) {
+        int32_t pp = r->bt_flat[r->bt_offset[i] + lp];
+        if (pp < 0 || pp >= pool_pages) return 0;
+      }
+    }
+  }
+  return 1;
+}
+
+static int64_t session_row0(const tdo_round* r, int32_t s) {
+  int64_t row = 0;
+  for (int32_t q = 0; q < s; ++q) row += r->span_tokens[q];
+  return row;
+}
+
+/* slot map: physical pool row of master token m for agent i  [Alg. 1, "slot map S"] */
+static int64_t slot_row(const tdo_geom* g, const tdo_round* r, int32_t i, int64_t m) {
+  int64_t a = r->agent_pos0[i] + m;
+  int64_t T = g->page_tokens;
+  return (int64_t)r->bt_flat[r->bt_offset[i] + a / T] * T + a % T;
+}
+
+static int64_t span_pages(const tdo_geom* g, int64_t S) { return (S + g->page_tokens - 1) / g->page_tokens; }
+
+/* ---- collective rerotate  [Sec. 4.2] ------------------------------------ */
+
+int tdo_rerotate_round(const tdo_geom* g, const tdo_round* r,
+                       const uint16_t* master_k, const uint16_t* master_v,
+                       uint16_t* pool_k, uint16_t* pool_v, int64_t pool_pages) {
+  if (!round_ok(g, r, pool_pages) || !master_k || !master_v || !pool_k || !pool_v) return -1;
+  const int64_t re = (int64_t)g->num_kv_heads * g->head_dim;
+  int err = 0;
+#pragma omp parallel for schedule(dynamic, 1)
+  for (int32_t i = 0; i < r->n_agents; ++i) {
+    int32_t s = r->agent_session[i];
+    int64_t S = r->span_tokens[s];
+    int64_t row0 = session_row0(r, s);
+    int64_t delta = r->agent_pos0[i] - r->master_pos0[s];
+    rope_tab t;
+    if (tab_init(&t, g, delta)) { err = 1; continue; }
+    for (int64_t m = 0; m < S; ++m) {
+      int64_t dst = slot_row(g, r, i, m);
+      rotate_row_bf16(g, &t, master_k + (row0 + m) * re, pool_k + dst * re);
+      memcpy(pool_v + dst * re, master_v + (row0 + m) * re, (size_t)re * sizeof(uint16_t));
+    }
+    tab_free(&t);
+  }
+  return err ? -2 : 0;
+}
+
+/* ---- block-sparse diff encode  [Sec. 4.3; Sec. 5] ------------------------ */
+
+/* differ  <=>  not (|a - ref| <= eps), evaluated in fp32; a NaN on either side differs */
+static int differs(uint16_t a, uint16_t ref, float eps) {
+  float d = fabsf(bf16_to_f32(a) - bf16_to_f32(ref));
+  return !(d <= eps);
+}
+
+int tdo_diff_encode(const tdo_geom* g, const tdo_round* r,
+                    const uint16_t* master_k, const uint16_t* master_v,
+                    const uint16_t* pool_k, const uint16_t* pool_v, int64_t pool_pages,
+                    float eps,
+                    int32_t* count, int64_t* offset, int32_t* idx, uint16_t* payload,
+                    int64_t capacity_pages, int32_t* overflow) {
+  if (!round_ok(g, r, pool_pages) || !master_k || !master_v || !pool_k || !pool_v) return -1;
+  if (!count || !offset || !overflow || capacity_pages < 0 || (capacity_pages && (!idx || !payload))) return -1;
+  if (!(eps >= 0.0f)) return -1;
+  const int64_t T = g->page_tokens;
+  const int64_t re = (int64_t)g->num_kv_heads * g->head_dim;
+  const int32_t A = r->n_agents;
+  int32_t** lists = (int32_t**)calloc((size_t)(A > 0 ? A : 1), sizeof(int32_t*));
+  if (!lists) return -2;
+  int err = 0;
+
+  /* 1. per-page compare of each Mirror against its Master (rotated to the Mirror's offset) */
+#pragma omp parallel for schedule(dynamic, 1)
+  for (int32_t i = 0; i < A; ++i) {
+    int32_t s = r->agent_session[i];
+    int64_t S = r->span_tokens[s];
+    int64_t P = span_pages(g, S);
+    int64_t row0 = session_row0(r, s);
+    int64_t delta = r->agent_pos0[i] - r->master_pos0[s];
+    rope_tab t;
+    uint16_t* ref = (uint16_t*)malloc((size_t)re * sizeof(uint16_t));
+    lists[i] = (int32_t*)malloc((size_t)(P > 0 ? P : 1) * sizeof(int32_t));
+    if (!ref || !lists[i] || tab_init(&t, g, delta)) { err = 1; free(ref); count[i] = 0; continue; }
+    int32_t n = 0;
+    for (int64_t p = 0; p < P; ++p) {
+      int flag = 0;
+      for (int64_t q = 0; q < T; ++q) {
+        int64_t m = p * T + q;
+        if (m >= S) break;                       /* rows past the span are not part of the page */
+        int64_t src = slot_row(g, r, i, m);
+        rotate_row_bf16(g, &t, master_k + (row0 + m) * re, ref);
+        for (int64_t e = 0; e < re; ++e) {
+          if (differs(pool_k[src * re + e], ref[e], eps)) flag = 1;
+          if (differs(pool_v[src * re + e], master_v[(row0 + m) * re + e], eps)) flag = 1;
+        }
+      }
+      if (flag) lists[i][n++] = (int32_t)p;
+    }
+    count[i] = n;
+    free(ref);
+    tab_free(&t);
+  }
+
+  /* 2. exclusive prefix over agents */
+  offset[0] = 0;
+  for (int32_t i = 0; i < A; ++i) offset[i + 1] = offset[i] + count[i];
+  *overflow = offset[A] > capacity_pages ? 1 : 0;
+
+  /* 3. index list and K/V values of the differing pages, as they sit in the agent's cache */
+  if (!err) {
+#pragma omp parallel for schedule(dynamic, 1)
+    for (int32_t i = 0; i < A; ++i) {
+      int64_t S = r->span_tokens[r->agent_session[i]];
+      for (int32_t k = 0; k < count[i]; ++k) {
+        int64_t slot = offset[i] + k;
+        if (slot >= capacity_pages) break;
+        int64_t p = lists[i][k];
+        idx[slot] = (int32_t)p;
+        uint16_t* pk = payload + slot * 2 * T * re;
+        uint16_t* pv = pk + T * re;
+        for (int64_t q = 0; q < T; ++q) {
+          int64_t m = p * T + q;
+          if (m < S) {
+            int64_t src = slot_row(g, r, i, m);
+            memcpy(pk + q * re, pool_k + src * re, (size_t)re * sizeof(uint16_t));
+            memcpy(pv + q * re, pool_v + src * re, (size_t)re * sizeof(uint16_t));
+          } else {
+            memset(pk + q * re, 0, (size_t)re * sizeof(uint16_t));
+            memset(pv + q * re, 0, (size_t)re * sizeof(uint16_t));
+          }
+        }
+      }
+    }
+  }
+  for (int32_t i = 0; i < A; ++i) free(lists[i]);
+  free(lists);
+  return err ? -2 : 0;
+}
+
+/* ---- fused diff restore  [Sec. 4.4, Alg. 1] ------------------------------ */
+
+int tdo_diff_decode(const tdo_geom* g, const tdo_round* r,
+                    const uint16_t* master_k, const uint16_t* master_v,
+                    uint16_t* pool_k, uint16_t* pool_v, int64_t pool_pages,
+                    const int32_t* count, const int64_t* offset, const int32_t* idx, const uint16_t* payload) {
+  if (!round_ok(g, r, pool_pages) || !master_k || !master_v || !pool_k || !pool_v) return -1;
+  if (!count || !offset) return -1;
+  const int64_t T = g->page_tokens;
+  const int64_t re = (int64_t)g->num_kv_heads * g->head_dim;
+  int err = 0;
+  for (int32_t i = 0; i < r->n_agents; ++i) {
+    int64_t P = span_pages(g, r->span_tokens[r->agent_session[i]]);
+    if (count[i] < 0 || (count[i] && (!idx || !payload))) return -1;
+    for (int32_t k = 0; k < count[i]; ++k) {
+      int32_t p = idx[offset[i] + k];
+      if (p < 0 || p >= P || (k && p <= idx[offset[i] + k - 1])) return -1;
+    }
+  }
+#pragma omp parallel for schedule(dynamic, 1)
+  for (int32_t i = 0; i < r->n_agents; ++i) {
+    int32_t s = r->agent_session[i];
+    int64_t S = r->span_tokens[s];
+    int64_t P = span_pages(g, S);
+    int64_t row0 = session_row0(r, s);
+    int64_t delta = r->agent_pos0[i] - r->master_pos0[s];
+    rope_tab t;
+    if (tab_init(&t, g, delta)) { err = 1; continue; }
+    for (int64_t p = 0; p < P; ++p) {
+      /* is page p in this Mirror's diff? (plain linear search of its index list) */
+      int64_t slot = -1;
+      for (int32_t k = 0; k < count[i]; ++k)
+        if (idx[offset[i] + k] == p) slot = offset[i] + k;
+      for (int64_t q = 0; q < T; ++q) {
+        int64_t m = p * T + q;
+        if (m >= S) break;
+        int64_t dst = slot_row(g, r, i, m);
+        if (slot >= 0) {
+          const uint16_t* pk = payload + slot * 2 * T * re;
+          const uint16_t* pv = pk + T * re;
+          memcpy(pool_k + dst * re, pk + q * re, (size_t)re * sizeof(uint16_t));
+          memcpy(pool_v + dst * re, pv + q * re, (size_t)re * sizeof(uint16_t));
+        } else {
+          rotate_row_bf16(g, &t, master_k + (row0 + m) * re, pool_k + dst * re);
+          memcpy(pool_v + dst * re, master_v + (row0 + m) * re, (size_t)re * sizeof(uint16_t));
+        }
+      }
+    }
+    tab_free(&t);
+  }
+  return err ? -2 : 0;
+}
+
+/* ---- storage arithmetic  [Sec. 6.4] -------------------------------------- */
+
+double tdo_dense_bytes(const tdo_geom* g, int64_t span_tokens) {
+  return (double)span_tokens * 2.0 * (double)g->num_kv_heads * (double)g->head_dim * 2.0;
+}
+
+double tdo_diff_bytes(const tdo_geom* g, int64_t diff_pages) {
+  double page = 2.0 * (double)g->page_tokens * (double)g->num_kv_heads * (double)g->head_dim * 2.0;
+  return (double)diff_pages * page + 4.0 * (double)diff_pages + 4.0 + 8.0;  /* values + idx + count + offset */
+}
+
+double tdo_mirror_ratio(const tdo_geom* g, int64_t span_tokens, int64_t diff_pages) {
+  return tdo_dense_bytes(g, span_tokens) / tdo_diff_bytes(g, diff_pages);
+}
+
+double tdo_family_cost(int64_t n_agents, double ratio) {
+  return 1.0 + (double)(n_agents - 1) / ratio;
+}
+
+int tdo_max_threads(void) {
+#ifdef _OPENMP
+  return omp_get_max_threads();
+#else
+  return 1;
+#endif
+}

@@ -1,0 +1,106 @@
+/*
+ * tdo -- plain CPU oracle for the collective KV-reuse step (TEST INFRASTRUCTURE ONLY).
+ *
+ * This is the slow, obviously-correct definition the HIP library is checked
+ * against.  It is not part of the product: nothing outside the test-suite, the
+ * smoke check and the benchmark's CPU-baseline leg may call it, and it shares no
+ * code, table or helper with the HIP path.
+ *
+ * What it defines (paper passages in brackets):
+ *   - RoPE re-rotation of cached keys by a position delta            [Sec. 2.2; Alg. 1 "RoPERecover"]
+ *   - one collective rerotate step for a whole round                 [Sec. 4.2 "Layerwise Collective Reuse"]
+ *   - the block-sparse Master/Mirror diff: indices + K/V values      [Sec. 4.3; Sec. 5 "Diff-Aware Storage"]
+ *   - restore of every Mirror from Master + diff via the slot map    [Sec. 4.4, Alg. 1]
+ *   - compression-ratio / capacity arithmetic                        [Sec. 6.4]
+ *
+ * All pointers are HOST pointers.  bf16 values are passed as uint16_t bit patterns.
+ * Every function returns 0 on success and a negative value on an invalid argument.
+ */
+#ifndef TDO_H
+#define TDO_H
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define TDO_ROPE_HALF        0   /* pair (j, j + D/2) inside a head   */
+#define TDO_ROPE_INTERLEAVED 1   /* pair (2j, 2j + 1) inside a head   */
+
+#define TDO_MATH_F32 0  /* tables rounded to fp32, fp32 products/fma in a fixed order (the kernel's precision) */
+#define TDO_MATH_F64 1  /* everything in double, one final rounding                                             */
+
+typedef struct {
+  int32_t num_kv_heads;   /* H */
+  int32_t head_dim;       /* D, even */
+  int32_t page_tokens;    /* T */
+  int32_t rope_style;     /* TDO_ROPE_* */
+  double  rope_theta;
+  int32_t math;           /* TDO_MATH_* */
+} tdo_geom;
+
+/* A round: n_sessions masters, n_agents mirrors.
+ *   span_tokens[s]   S_s, shared tokens of session s
+ *   master_pos0[s]   absolute position the master's token 0 was rotated for
+ *   agent_session[i] session of agent i
+ *   agent_pos0[i]    absolute position of agent i's first shared token (its history length)
+ *   bt_flat / bt_offset[i..i+1]  agent i's block table (logical page -> physical page),
+ *                    covering at least logical pages 0 .. (pos0+S-1)/T
+ * Master rows of session s start at row sum_{s'<s} S_s' of master_k / master_v
+ * ([rows][H][D] bf16).  Pools are [pool_pages][T][H][D] bf16. */
+typedef struct {
+  int32_t        n_sessions;
+  const int32_t* span_tokens;
+  const int64_t* master_pos0;
+  int32_t        n_agents;
+  const int32_t* agent_session;
+  const int64_t* agent_pos0;
+  const int32_t* bt_flat;
+  const int64_t* bt_offset;
+} tdo_round;
+
+/* cos/sin of phi_j = delta * theta^(-2j/D), j = 0 .. D/2-1 */
+int tdo_rope_table_f64(double theta, int32_t head_dim, int64_t delta, double* cos_out, double* sin_out);
+int tdo_rope_table_f32(double theta, int32_t head_dim, int64_t delta, float* cos_out, float* sin_out);
+
+/* Rotate n_rows rows of [H][D] by delta.  fp32 in/out (no storage rounding), fp32 in / bf16 out
+ * (rotation + storage rounding, TDO_MATH_F32 arithmetic) and bf16 in/out. */
+int tdo_rotate_rows_f32 (const tdo_geom* g, int64_t delta, int64_t n_rows, const float* in, float* out);
+int tdo_rotate_rows_f32_bf16(const tdo_geom* g, int64_t delta, int64_t n_rows, const float* in, uint16_t* out);
+int tdo_rotate_rows_bf16(const tdo_geom* g, int64_t delta, int64_t n_rows, const uint16_t* in, uint16_t* out);
+
+/* pool_k[slot_i(m)] = bf16(R(delta_i) master_k[m]); pool_v[slot_i(m)] = master_v[m]; nothing else is written. */
+int tdo_rerotate_round(const tdo_geom* g, const tdo_round* r,
+                       const uint16_t* master_k, const uint16_t* master_v,
+                       uint16_t* pool_k, uint16_t* pool_v, int64_t pool_pages);
+
+/* Block-sparse diff of every agent against its master.
+ *   count[n_agents], offset[n_agents+1] (exclusive prefix of count), idx[capacity_pages] (ascending master
+ *   page numbers, agent-major), payload[capacity_pages][2][T][H][D] (agent's K rows then V rows, rows past
+ *   the span zero).  *overflow = 1 if sum(count) > capacity_pages; count/offset stay complete, and nothing
+ *   at or beyond capacity_pages is written. */
+int tdo_diff_encode(const tdo_geom* g, const tdo_round* r,
+                    const uint16_t* master_k, const uint16_t* master_v,
+                    const uint16_t* pool_k, const uint16_t* pool_v, int64_t pool_pages,
+                    float eps,
+                    int32_t* count, int64_t* offset, int32_t* idx, uint16_t* payload,
+                    int64_t capacity_pages, int32_t* overflow);
+
+/* Restore every agent's shared span: diff pages from the payload, all other pages from the rotated master. */
+int tdo_diff_decode(const tdo_geom* g, const tdo_round* r,
+                    const uint16_t* master_k, const uint16_t* master_v,
+                    uint16_t* pool_k, uint16_t* pool_v, int64_t pool_pages,
+                    const int32_t* count, const int64_t* offset, const int32_t* idx, const uint16_t* payload);
+
+/* Sec. 6.4 arithmetic. */
+double tdo_dense_bytes (const tdo_geom* g, int64_t span_tokens);               /* one layer of one cache    */
+double tdo_diff_bytes  (const tdo_geom* g, int64_t diff_pages);                /* payload + index metadata  */
+double tdo_mirror_ratio(const tdo_geom* g, int64_t span_tokens, int64_t diff_pages);
+double tdo_family_cost (int64_t n_agents, double ratio);                       /* in full caches            */
+
+int tdo_max_threads(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif

@@ -1,0 +1,246 @@
+"""Seeded synthetic All-Gather rounds (inputs only).
+
+This module builds the *inputs* of one collective KV-reuse round: how many
+sessions and agents there are, how long each agent's private history is, where
+each agent's logical pages live in the paged pool, which master pages the model
+"refreshed" (perturbed) for each agent, and the random master K/V values.  It
+holds none of the method's arithmetic: no rotation, no compare, no compaction.
+Both the HIP path and the CPU oracle are fed from here and from nowhere else.
+
+Shape of a round (Section 2.1, Eq. 2): every agent's prompt is its private
+history followed by the same shared output blocks, so the shared span of S
+tokens starts at a different absolute position h_i for every agent.  The
+configurations below stand in for the replayed agent traces of Section 6.1 by
+shape and value distribution only.
+"""
+from __future__ import annotations
+
+from dataclasses import dataclass, field
+from typing import Dict, List, Optional
+
+import numpy as np
+
+SEED_BASE = 20260403
+
+
+@dataclass(frozen=True)
+class RoundSpec:
+    name: str
+    stream: int                 # RNG stream id (one per configuration)
+    num_layers: int
+    num_kv_heads: int
+    head_dim: int
+    page_tokens: int
+    rope_theta: float
+    n_sessions: int
+    agents_per_session: int
+    blocks: int                 # shared output blocks per session
+    block_tokens: int           # tokens per shared output block
+    hist_lo: int                # private history length, uniform in [lo, hi]
+    hist_hi: int
+    perturbed_frac: float       # fraction of master pages refreshed per agent
+    eps: float = 1e-2
+    noise_sigma: float = 0.05
+
+    @property
+    def span_tokens(self) -> int:
+        return self.blocks * self.block_tokens
+
+    @property
+    def span_pages(self) -> int:
+        return -(-self.span_tokens // self.page_tokens)
+
+    @property
+    def n_agents(self) -> int:
+        return self.n_sessions * self.agents_per_session
+
+    @property
+    def row_elems(self) -> int:
+        return self.num_kv_heads * self.head_dim
+
+    @property
+    def perturbed_pages_per_agent(self) -> int:
+        if self.perturbed_frac <= 0.0:
+            return 0
+        return max(1, int(round(self.perturbed_frac * self.span_pages)))
+
+
+CONFIGS: Dict[str, RoundSpec] = {
+    "tiny": RoundSpec("tiny", 1, 1, 8, 128, 16, 1.0e6, 1, 4, 4, 64, 32, 256, 0.06),
+    "session": RoundSpec("session", 2, 48, 8, 128, 16, 1.0e6, 1, 25, 25, 200, 1000, 4000, 0.06),
+    "batched250": RoundSpec("batched250", 3, 48, 8, 128, 16, 1.0e6, 10, 25, 25, 200, 1000, 4000, 0.06),
+    "long": RoundSpec("long", 4, 48, 8, 128, 16, 1.0e6, 1, 100, 100, 256, 4000, 8000, 0.03),
+    "llama70b": RoundSpec("llama70b", 5, 80, 8, 128, 16, 5.0e5, 1, 64, 64, 200, 2000, 6000, 0.10),
+}
+
+
+@dataclass
+class Round:
+    """Host-side structure of one round (no tensors)."""
+    spec: RoundSpec
+    span_tokens: np.ndarray        # int32 [n_sessions]
+    master_pos0: np.ndarray        # int64 [n_sessions]
+    master_row0: np.ndarray        # int64 [n_sessions+1], first master row of each session
+    agent_session: np.ndarray      # int32 [n_agents]
+    agent_pos0: np.ndarray         # int64 [n_agents], h_i
+    block_tables: List[np.ndarray]  # per agent int32 [ceil((h_i+S)/T)], logical -> physical page
+    pool_pages: int
+    dummy_page: int                # every history-only logical page maps here
+    canary_pages: np.ndarray       # int32 [2*n_agents], mapped by nobody
+    perturbed: List[np.ndarray]    # per agent sorted int32 master-page numbers
+    extra: dict = field(default_factory=dict)
+
+    @property
+    def n_agents(self) -> int:
+        return int(self.agent_session.shape[0])
+
+    @property
+    def n_sessions(self) -> int:
+        return int(self.span_tokens.shape[0])
+
+    @property
+    def total_master_rows(self) -> int:
+        return int(self.master_row0[-1])
+
+    def agent_tokens(self) -> int:
+        return int(sum(int(self.span_tokens[s]) for s in self.agent_session))
+
+    def dst_rows(self, agent: int, tokens: Optional[np.ndarray] = None) -> np.ndarray:
+        """Physical pool row of master token m for this agent (slot map)."""
+        T = self.spec.page_tokens
+        S = int(self.span_tokens[self.agent_session[agent]])
+        m = np.arange(S, dtype=np.int64) if tokens is None else np.asarray(tokens, dtype=np.int64)
+        a = int(self.agent_pos0[agent]) + m
+        bt = self.block_tables[agent]
+        return bt[a // T].astype(np.int64) * T + (a % T)
+
+
+def _rng(spec: RoundSpec, tag: int, extra: int = 0) -> np.random.Generator:
+    return np.random.default_rng([SEED_BASE, spec.stream, tag, extra])
+
+
+def make_round(spec: RoundSpec, hist: Optional[np.ndarray] = None,
+               perturbed_per_agent: Optional[int] = None,
+               clustered: bool = False) -> Round:
+    """Draw the structure of a round: histories, block tables, perturbed page sets."""
+    T = spec.page_tokens
+    A = spec.n_agents
+    S = spec.span_tokens
+    P = spec.span_pages
+    rs = _rng(spec, 1)
+    span_tokens = np.full(spec.n_sessions, S, dtype=np.int32)
+    master_pos0 = np.zeros(spec.n_sessions, dtype=np.int64)
+    master_row0 = np.concatenate([[0], np.cumsum(span_tokens, dtype=np.int64)]).astype(np.int64)
+    agent_session = np.repeat(np.arange(spec.n_sessions, dtype=np.int32), spec.agents_per_session)
+    if hist is None:
+        hist = rs.integers(spec.hist_lo, spec.hist_hi + 1, size=A, dtype=np.int64)
+    agent_pos0 = np.asarray(hist, dtype=np.int64).copy()
+    assert agent_pos0.shape == (A,)
+
+    first_lp = agent_pos0 // T
+    last_lp = (agent_pos0 + S - 1) // T
+    n_touch = (last_lp - first_lp + 1).astype(np.int64)
+    pool_pages = int(n_touch.sum()) + 2 * A + 1
+    perm = _rng(spec, 2).permutation(pool_pages).astype(np.int32)
+    dummy = int(perm[0])
+    canaries = perm[1:1 + 2 * A].copy()
+    cursor = 1 + 2 * A
+    tables: List[np.ndarray] = []
+    for i in range(A):
+        bt = np.full(int(last_lp[i]) + 1, dummy, dtype=np.int32)
+        n = int(n_touch[i])
+        bt[int(first_lp[i]):] = perm[cursor:cursor + n]
+        cursor += n
+        tables.append(bt)
+    assert cursor == pool_pages
+
+    k = spec.perturbed_pages_per_agent if perturbed_per_agent is None else perturbed_per_agent
+    k = min(k, P)
+    rp = _rng(spec, 3)
+    perturbed: List[np.ndarray] = []
+    for i in range(A):
+        if k == 0:
+            perturbed.append(np.zeros(0, dtype=np.int32))
+        elif not clustered:
+            perturbed.append(np.sort(rp.choice(P, size=k, replace=False)).astype(np.int32))
+        else:
+            # runs of 1-4 consecutive pages that start on a shared-block boundary
+            chosen: set = set()
+            guard = 0
+            while len(chosen) < k and guard < 100000:
+                guard += 1
+                b = int(rp.integers(0, spec.blocks))
+                start = (b * spec.block_tokens) // T
+                run = int(rp.integers(1, 5))
+                for q in range(start, min(P, start + run)):
+                    if len(chosen) < k:
+                        chosen.add(q)
+            perturbed.append(np.array(sorted(chosen), dtype=np.int32))
+    return Round(spec, span_tokens, master_pos0, master_row0, agent_session, agent_pos0,
+                 tables, pool_pages, dummy, canaries, perturbed)
+
+
+# ---------------------------------------------------------------------------
+# bf16 storage helpers (format conversion only)
+# ---------------------------------------------------------------------------
+
+def f32_to_bf16_bits(x: np.ndarray) -> np.ndarray:
+    """float32 -> bfloat16 bit patterns, round-to-nearest-even."""
+    u = np.ascontiguousarray(x, dtype=np.float32).view(np.uint32)
+    r = (u + np.uint32(0x7FFF) + ((u >> np.uint32(16)) & np.uint32(1))) >> np.uint32(16)
+    nan = (u & np.uint32(0x7FFFFFFF)) > np.uint32(0x7F800000)
+    r = np.where(nan, (u >> np.uint32(16)) | np.uint32(0x40), r)
+    return r.astype(np.uint16)
+
+
+def bf16_bits_to_f32(b: np.ndarray) -> np.ndarray:
+    return (np.ascontiguousarray(b, dtype=np.uint16).astype(np.uint32) << np.uint32(16)).view(np.float32)
+
+
+def master_host(rnd: Round, layer: int):
+    """Master K, V ~ N(0,1) as bf16 bit patterns, shape [total_master_rows, H*D]."""
+    spec = rnd.spec
+    g = _rng(spec, 10, layer)
+    shape = (rnd.total_master_rows, spec.row_elems)
+    k = f32_to_bf16_bits(g.standard_normal(shape, dtype=np.float32))
+    v = f32_to_bf16_bits(g.standard_normal(shape, dtype=np.float32))
+    return k, v
+
+
+def pool_host(rnd: Round, layer: int):
+    """A pool pre-filled with a seeded non-trivial pattern (so that untouched rows are detectable)."""
+    spec = rnd.spec
+    g = _rng(spec, 11, layer)
+    shape = (rnd.pool_pages * spec.page_tokens, spec.row_elems)
+    k = g.integers(0, 1 << 16, size=shape, dtype=np.uint16)
+    v = g.integers(0, 1 << 16, size=shape, dtype=np.uint16)
+    # keep the fill finite: clear the top exponent bit so no NaN/Inf patterns appear
+    k &= np.uint16(0xBFFF)
+    v &= np.uint16(0xBFFF)
+    return k, v
+
+
+def perturb_host(rnd: Round, layer: int, pool_k: np.ndarray, pool_v: np.ndarray,
+                 same_pages_all_layers: bool = True) -> None:
+    """Stand-in for the model's per-position refresh: on every perturbed master page of
+    every agent, each valid K and V element x becomes bf16(fp32(x) + n), n ~ N(0, sigma)."""
+    spec = rnd.spec
+    T = spec.page_tokens
+    g = _rng(spec, 12, layer)
+    for i in range(rnd.n_agents):
+        S = int(rnd.span_tokens[rnd.agent_session[i]])
+        for p in rnd.perturbed[i]:
+            toks = np.arange(int(p) * T, min(S, (int(p) + 1) * T), dtype=np.int64)
+            rows = rnd.dst_rows(i, toks)
+            for plane in (pool_k, pool_v):
+                x = bf16_bits_to_f32(plane[rows])
+                n = g.standard_normal(x.shape, dtype=np.float32) * np.float32(spec.noise_sigma)
+                plane[rows] = f32_to_bf16_bits(x + n)
+
+
+def shared_row_mask(rnd: Round) -> np.ndarray:
+    """Boolean [pool_rows]: True where some agent's shared span lands."""
+    mask = np.zeros(rnd.pool_pages * rnd.spec.page_tokens, dtype=bool)
+    for i in range(rnd.n_agents):
+        mask[rnd.dst_rows(i)] = True
+    return mask

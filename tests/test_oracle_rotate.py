@@ -1,0 +1,259 @@
+"""Pins for the oracle's RoPE re-rotation (Sec. 2.2: cached keys are aligned with their
+target positions by a rotation; Alg. 1 "RoPERecover").  None of these compares the oracle
+with itself through the same formula: they use closed forms, group invariants, complex
+multiplication from numpy, and plain PyTorch tensor ops."""
+import math
+
+import numpy as np
+import pytest
+import torch
+
+from paper_2604_03143_amd import workload as wl
+
+H, D = 8, 128
+THETAS = (1.0e6, 5.0e5)
+DELTAS = (1, 17, 255, 1000, 4000, 8000, 18800, 33600)
+
+
+def _randn(seed, rows=6, h=H, d=D):
+    return np.random.default_rng(seed).standard_normal((rows, h, d)).astype(np.float32)
+
+
+def test_identity_roundtrip_fp32(tdo):
+    """Rotating by d and then by -d is the identity within 1e-5 (fp32 in/out)."""
+    for theta in THETAS:
+        g = tdo.geom(H, D, 16, theta)
+        x = _randn(1)
+        for d in DELTAS:
+            y = tdo.rotate_rows_f32(g, d, x)
+            z = tdo.rotate_rows_f32(g, -d, y)
+            assert np.max(np.abs(z - x)) < 1e-5, (theta, d)
+            assert np.max(np.abs(y - x)) > 1e-2  # it did rotate
+
+
+def test_composition_is_additive(tdo):
+    g = tdo.geom(H, D, 16, 1.0e6)
+    x = _randn(2)
+    for a, b in ((3, 5), (1000, 3000), (4000, -1234), (20000, 13600)):
+        lhs = tdo.rotate_rows_f32(g, b, tdo.rotate_rows_f32(g, a, x))
+        rhs = tdo.rotate_rows_f32(g, a + b, x)
+        assert np.max(np.abs(lhs - rhs)) < 1e-5
+
+
+def test_pair_norm_preserved(tdo):
+    for style in (tdo.ROPE_HALF, tdo.ROPE_INTERLEAVED):
+        g = tdo.geom(H, D, 16, 1.0e6, style=style)
+        x = _randn(3)
+        y = tdo.rotate_rows_f32(g, 777, x)
+        if style == tdo.ROPE_HALF:
+            nx = x[..., : D // 2] ** 2 + x[..., D // 2:] ** 2
+            ny = y[..., : D // 2] ** 2 + y[..., D // 2:] ** 2
+        else:
+            nx = x[..., 0::2] ** 2 + x[..., 1::2] ** 2
+            ny = y[..., 0::2] ** 2 + y[..., 1::2] ** 2
+        assert np.max(np.abs(nx - ny) / (1.0 + nx)) < 1e-6
+
+
+def test_delta_zero_is_bit_identity(tdo):
+    for math_mode in (tdo.MATH_F32, tdo.MATH_F64):
+        g = tdo.geom(H, D, 16, 1.0e6, math=math_mode)
+        xb = wl.f32_to_bf16_bits(_randn(4))
+        assert np.array_equal(tdo.rotate_rows_bf16(g, 0, xb), xb)
+        x = _randn(5)
+        assert np.array_equal(tdo.rotate_rows_f32(g, 0, x), x)
+
+
+def test_closed_form_unit_vectors(tdo):
+    """A unit vector on the first member of pair j turns into (cos phi_j, sin phi_j) on the pair;
+    on the second member into (-sin phi_j, cos phi_j).  phi_j comes from libm, not from the oracle."""
+    for theta in THETAS:
+        g = tdo.geom(H, D, 16, theta)
+        for delta in (1, 1000, 33600):
+            for j in (0, 1, 31, 32, 63):
+                phi = delta * theta ** (-2.0 * j / D)
+                for head in (0, 5):
+                    x = np.zeros((1, H, D), np.float32)
+                    x[0, head, j] = 1.0
+                    y = tdo.rotate_rows_f32(g, delta, x)
+                    exp = np.zeros_like(x)
+                    exp[0, head, j] = math.cos(phi)
+                    exp[0, head, j + D // 2] = math.sin(phi)
+                    assert np.max(np.abs(y - exp)) < 2e-7
+                    x = np.zeros((1, H, D), np.float32)
+                    x[0, head, j + D // 2] = 1.0
+                    y = tdo.rotate_rows_f32(g, delta, x)
+                    exp = np.zeros_like(x)
+                    exp[0, head, j] = -math.sin(phi)
+                    exp[0, head, j + D // 2] = math.cos(phi)
+                    assert np.max(np.abs(y - exp)) < 2e-7
+    # the textbook value: delta = 1, j = 0 -> (cos 1, sin 1)
+    g = tdo.geom(H, D, 16, 1.0e6)
+    x = np.zeros((1, H, D), np.float32)
+    x[0, 0, 0] = 1.0
+    y = tdo.rotate_rows_f32(g, 1, x)
+    assert abs(y[0, 0, 0] - 0.5403023) < 1e-7 and abs(y[0, 0, 64] - 0.8414710) < 1e-7
+    # frequency schedule: theta = 1e6, D = 128, j = 32 has inverse frequency exactly 1e-3
+    c, s = tdo.rope_table(1.0e6, 128, 1000, f64=True)
+    assert abs(c[32] - math.cos(1.0)) < 1e-12 and abs(s[32] - math.sin(1.0)) < 1e-12
+    c, s = tdo.rope_table(1.0e4, 4, 100, f64=True)
+    assert abs(c[1] - math.cos(1.0)) < 1e-12 and abs(s[1] - math.sin(1.0)) < 1e-12
+
+
+def test_interleaved_closed_form(tdo):
+    g = tdo.geom(2, 8, 4, 1.0e4, style=tdo.ROPE_INTERLEAVED)
+    for j in range(4):
+        phi = 9 * 1.0e4 ** (-2.0 * j / 8)
+        x = np.zeros((1, 2, 8), np.float32)
+        x[0, 1, 2 * j] = 1.0
+        y = tdo.rotate_rows_f32(g, 9, x)
+        exp = np.zeros_like(x)
+        exp[0, 1, 2 * j] = math.cos(phi)
+        exp[0, 1, 2 * j + 1] = math.sin(phi)
+        assert np.max(np.abs(y - exp)) < 2e-7
+
+
+def test_equals_complex_multiplication(tdo):
+    """A planar rotation is a multiplication by exp(i phi): numpy's complex arithmetic in
+    double is the library routine this reduces to."""
+    for theta in THETAS:
+        x = _randn(6)
+        for delta in (5, 4000, 33600):
+            j = np.arange(D // 2)
+            w = np.exp(1j * (delta * np.power(theta, -2.0 * j / D)))
+            z = (x[..., : D // 2].astype(np.float64) + 1j * x[..., D // 2:].astype(np.float64)) * w
+            exp = np.concatenate([z.real, z.imag], axis=-1)
+            for mode, tol in ((tdo.MATH_F64, 3e-7), (tdo.MATH_F32, 2e-6)):
+                g = tdo.geom(H, D, 16, theta, math=mode)
+                y = tdo.rotate_rows_f32(g, delta, x)
+                assert np.max(np.abs(y - exp)) < tol, (theta, delta, mode)
+
+
+def test_equals_torch_rotate_half(tdo):
+    """x*cos + rotate_half(x)*sin with plain PyTorch fp32 CPU ops on libm-made angles."""
+    theta, delta = 1.0e6, 2345
+    g = tdo.geom(H, D, 16, theta)
+    x = _randn(7)
+    j = np.arange(D // 2)
+    phi = delta * np.power(theta, -2.0 * j / D)
+    cos = torch.tensor(np.concatenate([np.cos(phi), np.cos(phi)]), dtype=torch.float32)
+    sin = torch.tensor(np.concatenate([np.sin(phi), np.sin(phi)]), dtype=torch.float32)
+    xt = torch.from_numpy(x)
+    rot = torch.cat([-xt[..., D // 2:], xt[..., : D // 2]], dim=-1)
+    exp = (xt * cos + rot * sin).numpy()
+    y = tdo.rotate_rows_f32(g, delta, x)
+    assert np.max(np.abs(y - exp)) < 1e-6
+
+
+def test_position_independent_caching_premise(tdo):
+    """RoPE at p_new on raw keys == RoPE at p_old, then re-rotation by p_new - p_old (Sec. 2.2)."""
+    g = tdo.geom(H, D, 16, 1.0e6)
+    raw = _randn(8, rows=4)
+    j = np.arange(D // 2)
+
+    def textbook(x, pos):
+        w = np.exp(1j * (pos * np.power(1.0e6, -2.0 * j / D)))
+        z = (x[..., : D // 2].astype(np.float64) + 1j * x[..., D // 2:].astype(np.float64)) * w
+        return np.concatenate([z.real, z.imag], axis=-1)
+
+    for p_old, p_new in ((0, 1000), (37, 4037), (1200, 300), (5000, 33600)):
+        cached = textbook(raw, p_old).astype(np.float32)
+        moved = tdo.rotate_rows_f32(g, p_new - p_old, cached)
+        assert np.max(np.abs(moved - textbook(raw, p_new))) < 1e-5
+
+
+def test_theta_sensitivity(tdo):
+    c6, s6 = tdo.rope_table(1.0e6, D, 100)
+    c5, s5 = tdo.rope_table(5.0e5, D, 100)
+    assert c6[0] == c5[0] and s6[0] == s5[0]
+    assert np.all(np.abs(c6[1:] - c5[1:]) + np.abs(s6[1:] - s5[1:]) > 0)
+
+
+def test_table_precision_needs_double(tdo):
+    """fp32 tables are the correctly rounded double values, also at angles of 33 600 rad."""
+    for delta in (33600, 18800):
+        cd, sd = tdo.rope_table(1.0e6, D, delta, f64=True)
+        cf, sf = tdo.rope_table(1.0e6, D, delta)
+        assert np.array_equal(cd.astype(np.float32), cf) and np.array_equal(sd.astype(np.float32), sf)
+        assert abs(cd[0] - math.cos(float(delta))) < 1e-12
+
+
+def test_bf16_path_within_half_ulp_of_exact(tdo):
+    """bf16 output of the fp32-math path vs the double-math path: they may differ by one bf16
+    ulp only where the exact result sits next to a rounding boundary; and the fp32-math result is
+    within half a bf16 ulp (+ fp32 slack) of the exact value.  Bounds the 4e-3 bar: for |y| < 1
+    half an ulp is <= 2^-9 ~ 1.95e-3."""
+    x = wl.f32_to_bf16_bits(_randn(9, rows=32))
+    xf = wl.bf16_bits_to_f32(x).astype(np.float64)
+    j = np.arange(D // 2)
+    for delta in (1000, 33600):
+        w = np.exp(1j * (delta * np.power(1.0e6, -2.0 * j / D)))
+        z = (xf[..., : D // 2] + 1j * xf[..., D // 2:]) * w
+        exact = np.concatenate([z.real, z.imag], axis=-1)
+        y32 = wl.bf16_bits_to_f32(tdo.rotate_rows_bf16(tdo.geom(H, D, 16, 1.0e6, math=tdo.MATH_F32), delta, x))
+        y64 = wl.bf16_bits_to_f32(tdo.rotate_rows_bf16(tdo.geom(H, D, 16, 1.0e6, math=tdo.MATH_F64), delta, x))
+        ulp = np.exp2(np.floor(np.log2(np.maximum(np.abs(exact), 1e-30))) - 7)
+        assert np.all(np.abs(y64 - exact) <= 0.5 * ulp * (1 + 1e-9))
+        assert np.all(np.abs(y32 - exact) <= 0.5 * ulp + 1e-6)
+        small = np.abs(exact) < 1.0
+        assert np.max(np.abs(y32 - exact)[small]) <= 4e-3
+        mism = np.count_nonzero(y32 != y64)
+        assert mism <= 1e-3 * y32.size
+        assert np.all(np.abs(y32 - y64) <= ulp * 1.0001)
+
+
+def test_bf16_rounding_is_nearest_even(tdo):
+    """delta = 0 leaves bits alone, so feed fp32 rows through the bf16 entry by pre-rounding with an
+    independent numpy implementation and compare against torch's bf16 cast (also RNE)."""
+    x = _randn(10, rows=64)
+    ours = wl.f32_to_bf16_bits(x)
+    tb = torch.from_numpy(x).to(torch.bfloat16).view(torch.int16).numpy().view(np.uint16)
+    assert np.array_equal(ours, tb)
+    # and the oracle's own rounding, exercised through a rotation by 2*pi*k at j = 0 is not exact;
+    # instead use rotation of values whose exact result is a bf16 tie:
+    g = tdo.geom(1, 2, 4, 1.0e4)
+    # D = 2: one pair, phi = delta.  x = (a, 0) -> (a cos, a sin)
+    a = np.float32(1.0)
+    xb = wl.f32_to_bf16_bits(np.array([[a, 0.0]], np.float32))
+    for delta in (1, 2, 3, 11):
+        y = wl.bf16_bits_to_f32(tdo.rotate_rows_bf16(g, delta, xb))
+        exp = torch.tensor([np.float32(math.cos(delta)), np.float32(math.sin(delta))]).to(torch.bfloat16).float().numpy()
+        assert np.array_equal(y.ravel(), exp)
+
+
+def test_storage_rounding_ties_to_even(tdo):
+    """fp32 -> bf16 storage rounding at delta = 0 (rotation is then exact) against torch's cast,
+    on exact ties, near-ties, denormals, infinities and NaN."""
+    g = tdo.geom(1, 2, 4, 1.0e4)
+    bits = []
+    for hi in (0x3F80, 0x3F81, 0x4000, 0xC07F, 0x0001, 0x0000, 0x7F7F, 0x3EFF):
+        for lo in (0x0000, 0x0001, 0x7FFF, 0x8000, 0x8001, 0xFFFF):
+            bits.append((hi << 16) | lo)
+    bits += [0x7F800000, 0xFF800000, 0x7FC00000, 0x7F800001, 0x7FFFFFFF, 0x00000001, 0x80000001]
+    # each value sits alone in its pair (partner 0), so a NaN or Inf cannot leak into a neighbour
+    x = np.zeros((len(bits), 2), np.float32)
+    x[:, 0] = np.array(bits, dtype=np.uint32).view(np.float32)
+    got = tdo.rotate_rows_f32_bf16(g, 0, x)[:, 0]
+    exp = torch.from_numpy(x[:, 0].copy()).to(torch.bfloat16).view(torch.int16).numpy().view(np.uint16)
+    nan = np.isnan(x[:, 0])
+    assert np.array_equal(got[~nan], exp[~nan])
+    assert np.all(np.isnan(wl.bf16_bits_to_f32(got[nan])))
+    rnd = np.random.default_rng(13).integers(0, 1 << 32, size=20000, dtype=np.uint64).astype(np.uint32)
+    x = np.zeros((len(rnd), 2), np.float32)
+    x[:, 0] = rnd.view(np.float32)
+    ok = ~np.isnan(x[:, 0])
+    got = tdo.rotate_rows_f32_bf16(g, 0, x)[:, 0]
+    exp = torch.from_numpy(x[:, 0].copy()).to(torch.bfloat16).view(torch.int16).numpy().view(np.uint16)
+    assert np.array_equal(got[ok], exp[ok])
+
+
+@pytest.mark.parametrize("bad", ["odd_dim", "theta", "style"])
+def test_invalid_geometry_rejected(tdo, bad):
+    g = tdo.geom(2, 8, 4, 1.0e4)
+    if bad == "odd_dim":
+        g.head_dim = 7
+    elif bad == "theta":
+        g.rope_theta = 0.0
+    else:
+        g.rope_style = 5
+    with pytest.raises(ValueError):
+        tdo.rotate_rows_f32(g, 1, np.zeros(2 * g.head_dim, np.float32))

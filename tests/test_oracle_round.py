@@ -1,0 +1,389 @@
+"""Pins for the oracle's round functions: collective rerotate (Sec. 4.2), block-sparse diff
+encode (Sec. 4.3 / Sec. 5) and fused restore (Sec. 4.4, Alg. 1).  Brute-force evaluators here are
+written separately in numpy double precision and on tiny inputs."""
+import numpy as np
+import pytest
+
+from paper_2604_03143_amd import workload as wl
+from helpers import OracleRun, lists_of, small_spec, with_
+
+
+# ---------------------------------------------------------------------------
+# separate, tiny, double-precision evaluator (half-split pairs)
+# ---------------------------------------------------------------------------
+
+def brute_rotated_row(row_bits, delta, theta, H, D):
+    x = wl.bf16_bits_to_f32(row_bits).astype(np.float64).reshape(H, D)
+    out = np.empty_like(x)
+    for h in range(H):
+        for j in range(D // 2):
+            phi = delta * theta ** (-2.0 * j / D)
+            a, b = x[h, j], x[h, j + D // 2]
+            out[h, j] = a * np.cos(phi) - b * np.sin(phi)
+            out[h, j + D // 2] = b * np.cos(phi) + a * np.sin(phi)
+    return out.reshape(-1)
+
+
+def brute_slot(rnd, i, m):
+    T = rnd.spec.page_tokens
+    a = int(rnd.agent_pos0[i]) + m
+    return int(rnd.block_tables[i][a // T]) * T + a % T
+
+
+def bf16_ulp(x):
+    return np.exp2(np.floor(np.log2(np.maximum(np.abs(x), 1e-30))) - 7)
+
+
+# ---------------------------------------------------------------------------
+# rerotate_round
+# ---------------------------------------------------------------------------
+
+def test_rerotate_bruteforce_small(tdo):
+    spec = small_spec(H=2, D=8, T=4, agents=3, blocks=3, block_tokens=7, hist=(5, 40))
+    rnd = wl.make_round(spec)
+    run = OracleRun(tdo, rnd)
+    pk0, pv0 = run.pk.copy(), run.pv.copy()
+    run.rerotate()
+    S = spec.span_tokens
+    written = np.zeros(run.pk.shape[0], bool)
+    for i in range(rnd.n_agents):
+        for m in range(S):
+            row = brute_slot(rnd, i, m)
+            written[row] = True
+            exact = brute_rotated_row(run.mk[m], int(rnd.agent_pos0[i]), spec.rope_theta, 2, 8)
+            got = wl.bf16_bits_to_f32(run.pk[row]).astype(np.float64)
+            assert np.all(np.abs(got - exact) <= 0.5 * bf16_ulp(exact) + 1e-6)
+            assert np.array_equal(run.pv[row], run.mv[m])
+    # nothing else was written (history rows, dummy page, canary pages)
+    assert np.array_equal(run.pk[~written], pk0[~written])
+    assert np.array_equal(run.pv[~written], pv0[~written])
+    assert written.sum() == rnd.n_agents * S
+
+
+def test_rerotate_bruteforce_one_page_one_head(tdo):
+    spec = small_spec(H=1, D=4, T=4, agents=1, blocks=1, block_tokens=4, hist=(3, 3))
+    rnd = wl.make_round(spec)
+    run = OracleRun(tdo, rnd)
+    run.rerotate()
+    for m in range(4):
+        exact = brute_rotated_row(run.mk[m], 3, spec.rope_theta, 1, 4)
+        got = wl.bf16_bits_to_f32(run.pk[brute_slot(rnd, 0, m)])
+        assert np.all(np.abs(got - exact) <= 0.5 * bf16_ulp(exact) + 1e-6)
+
+
+def test_rerotate_batching_invariance(tdo):
+    """Grouping changes the execution order, not the result (Sec. 6.6): an N-agent call equals N
+    one-agent calls bit for bit."""
+    spec = small_spec(H=2, D=8, T=4, sessions=2, agents=3, blocks=2, block_tokens=9, hist=(1, 50))
+    rnd = wl.make_round(spec)
+    run = OracleRun(tdo, rnd)
+    run.rerotate()
+    pk, pv = wl.pool_host(rnd, 0)
+    g = run.g
+    for i in range(rnd.n_agents):
+        s = int(rnd.agent_session[i])
+        one = wl.Round(spec, rnd.span_tokens[s:s + 1], rnd.master_pos0[s:s + 1],
+                       np.array([0, rnd.span_tokens[s]], np.int64), np.zeros(1, np.int32),
+                       rnd.agent_pos0[i:i + 1], [rnd.block_tables[i]], rnd.pool_pages, rnd.dummy_page,
+                       rnd.canary_pages, [rnd.perturbed[i]])
+        hr = tdo.HostRound(one)
+        r0, r1 = int(rnd.master_row0[s]), int(rnd.master_row0[s + 1])
+        tdo.rerotate_round(g, hr, np.ascontiguousarray(run.mk[r0:r1]), np.ascontiguousarray(run.mv[r0:r1]), pk, pv)
+    assert np.array_equal(pk, run.pk) and np.array_equal(pv, run.pv)
+
+
+def test_rerotate_block_table_permutation_moves_rows_only(tdo):
+    spec = small_spec(H=2, D=8, T=4, agents=2, blocks=2, block_tokens=8, hist=(0, 30))
+    rnd = wl.make_round(spec)
+    a = OracleRun(tdo, rnd)
+    a.rerotate()
+    perm = np.random.default_rng(5).permutation(rnd.pool_pages).astype(np.int32)
+    rnd2 = wl.make_round(spec)
+    rnd2.block_tables = [perm[bt] for bt in rnd.block_tables]
+    b = OracleRun(tdo, rnd2)
+    b.rerotate()
+    for i in range(rnd.n_agents):
+        assert np.array_equal(a.pk[rnd.dst_rows(i)], b.pk[rnd2.dst_rows(i)])
+        assert np.array_equal(a.pv[rnd.dst_rows(i)], b.pv[rnd2.dst_rows(i)])
+
+
+@pytest.mark.parametrize("h", [0, 1, 15, 16, 17, 31])
+def test_rerotate_unaligned_offsets_and_tail(tdo, h):
+    """History lengths that are not page multiples: a master page straddles two physical pages."""
+    spec = wl.RoundSpec("edge", 98, 1, 2, 8, 16, 1.0e6, 1, 1, 1, 40, h, h, 0.1)  # S = 40: tail of 8 rows
+    rnd = wl.make_round(spec)
+    run = OracleRun(tdo, rnd)
+    pk0 = run.pk.copy()
+    run.rerotate()
+    rows = rnd.dst_rows(0)
+    assert len(set(rows.tolist())) == 40
+    ref = tdo.rotate_rows_bf16(run.g, h, run.mk)
+    assert np.array_equal(run.pk[rows], ref)
+    mask = np.ones(len(pk0), bool)
+    mask[rows] = False
+    assert np.array_equal(run.pk[mask], pk0[mask])
+
+
+# ---------------------------------------------------------------------------
+# diff_encode
+# ---------------------------------------------------------------------------
+
+def test_encode_identical_caches_is_empty(tdo):
+    rnd = wl.make_round(wl.CONFIGS["tiny"])
+    run = OracleRun(tdo, rnd)
+    run.rerotate()
+    d = run.encode()
+    assert np.all(d.count == 0) and np.all(d.offset == 0) and d.overflow[0] == 0
+    # also lossless mode
+    d = run.encode(eps=0.0)
+    assert np.all(d.count == 0)
+
+
+@pytest.mark.parametrize("clustered", [False, True])
+def test_encode_recovers_seeded_perturbed_set_tiny(tdo, clustered):
+    """idx must equal the generator's seeded page set: ground truth that needs no oracle."""
+    spec = wl.CONFIGS["tiny"]
+    rnd = wl.make_round(spec, perturbed_per_agent=3 if clustered else None, clustered=clustered)
+    run = OracleRun(tdo, rnd)
+    run.rerotate()
+    run.perturb()
+    d = run.encode()
+    got = lists_of(d, rnd.n_agents)
+    for i in range(rnd.n_agents):
+        assert np.array_equal(got[i], rnd.perturbed[i])
+    assert np.array_equal(d.offset, np.concatenate([[0], np.cumsum(d.count)]))
+    assert d.overflow[0] == 0
+    # payload = the agent's rows as they sit in its cache
+    T, re = spec.page_tokens, spec.row_elems
+    for i in range(rnd.n_agents):
+        for k, p in enumerate(got[i]):
+            slot = int(d.offset[i]) + k
+            page = d.payload[slot].reshape(2, T, re)
+            rows = rnd.dst_rows(i, np.arange(p * T, (p + 1) * T))
+            assert np.array_equal(page[0], run.pk[rows]) and np.array_equal(page[1], run.pv[rows])
+
+
+def test_encode_all_different(tdo):
+    spec = small_spec(H=2, D=8, T=4, agents=2, blocks=2, block_tokens=10)
+    rnd = wl.make_round(spec)
+    run = OracleRun(tdo, rnd)   # pool holds unrelated seeded bits: every page differs
+    d = run.encode()
+    P = spec.span_pages
+    for lst in lists_of(d, rnd.n_agents):
+        assert np.array_equal(lst, np.arange(P))
+    assert d.offset[-1] == rnd.n_agents * P
+
+
+def test_encode_eps0_single_bit(tdo):
+    spec = small_spec(H=2, D=8, T=4, agents=3, blocks=3, block_tokens=7)
+    rnd = wl.make_round(spec)
+    run = OracleRun(tdo, rnd)
+    run.rerotate()
+    rng = np.random.default_rng(3)
+    for trial in range(12):
+        i = int(rng.integers(rnd.n_agents))
+        m = int(rng.integers(spec.span_tokens))
+        e = int(rng.integers(spec.row_elems))
+        plane = run.pk if trial % 2 == 0 else run.pv
+        row = brute_slot(rnd, i, m)
+        old = plane[row, e]
+        plane[row, e] = old ^ np.uint16(1)          # lowest mantissa bit
+        d = run.encode(eps=0.0)
+        exp = np.zeros(rnd.n_agents, np.int32)
+        exp[i] = 1
+        assert np.array_equal(d.count, exp)
+        assert d.idx[int(d.offset[i])] == m // spec.page_tokens
+        plane[row, e] = old
+    assert np.all(run.encode(eps=0.0).count == 0)
+
+
+def _one_page(tdo, T=4, H=1, D=4, h=2):
+    spec = small_spec(H=H, D=D, T=T, agents=1, blocks=1, block_tokens=T, hist=(h, h))
+    rnd = wl.make_round(spec)
+    run = OracleRun(tdo, rnd)
+    run.mk[:] = 0          # rotating zeros gives zeros: reference K is exactly 0
+    run.mv[:] = 0x3F80     # reference V is exactly 1.0
+    run.rerotate()
+    return spec, rnd, run
+
+
+@pytest.mark.parametrize("plane", ["k", "v"])
+def test_encode_threshold_bruteforce_one_page(tdo, plane):
+    """Strict threshold: |a - ref| below / at / above eps -> no / no / yes.  eps = 2^-7 is
+    representable; bf16 neighbours of the reference give exactly representable differences."""
+    spec, rnd, run = _one_page(tdo)
+    eps = 2.0 ** -7
+    row = brute_slot(rnd, 0, 1)
+    if plane == "k":
+        cases = [(0x3BFF, 0), (0x3C00, 0), (0x3C01, 1), (0xBC00, 0), (0xBC01, 1)]  # ref 0: a = +-value
+        target = run.pk
+    else:
+        cases = [(0x3F80, 0), (0x3F81, 0), (0x3F82, 1), (0x3F7F, 0), (0x3F7E, 0), (0x3F7C, 1)]  # ref 1.0
+        target = run.pv
+    for bits, flagged in cases:
+        old = target[row, 2]
+        target[row, 2] = bits
+        d = run.encode(eps=eps)
+        assert int(d.count[0]) == flagged, hex(bits)
+        target[row, 2] = old
+    # eps = 1e-2 as fp32: 0x3C23 (0.0099487) is inside, 0x3C24 (0.0100098) is outside
+    if plane == "k":
+        for bits, flagged in [(0x3C23, 0), (0x3C24, 1)]:
+            run.pk[row, 0] = bits
+            assert int(run.encode(eps=1e-2).count[0]) == flagged
+            run.pk[row, 0] = 0
+
+
+def test_encode_nan_and_signed_zero(tdo):
+    spec, rnd, run = _one_page(tdo)
+    row = brute_slot(rnd, 0, 0)
+    run.pk[row, 1] = 0x8000           # -0 against +0: equal
+    assert int(run.encode(eps=0.0).count[0]) == 0
+    run.pk[row, 1] = 0x7FC0           # NaN differs, whatever eps is
+    assert int(run.encode(eps=1e30).count[0]) == 1
+    run.pk[row, 1] = 0
+    run.mv[0, 0] = 0x7FC0             # NaN in the master differs even from the same NaN bits
+    run.pv[row, 0] = 0x7FC0
+    assert int(run.encode(eps=1.0).count[0]) == 1
+
+
+def test_encode_k_only_and_v_only_flag(tdo):
+    spec = small_spec(H=2, D=8, T=4, agents=2, blocks=2, block_tokens=8)
+    rnd = wl.make_round(spec)
+    run = OracleRun(tdo, rnd)
+    run.rerotate()
+    run.pk[brute_slot(rnd, 0, 5), 3] ^= np.uint16(0x4000)   # agent 0, page 1, K only
+    run.pv[brute_slot(rnd, 1, 13), 0] ^= np.uint16(0x4000)  # agent 1, page 3, V only
+    d = run.encode()
+    got = lists_of(d, 2)
+    assert got[0].tolist() == [1] and got[1].tolist() == [3]
+
+
+def test_encode_tail_rows_never_flag_and_payload_tail_is_zero(tdo):
+    spec = small_spec(H=2, D=8, T=4, agents=1, blocks=1, block_tokens=10, hist=(2, 2))  # P = 3, tail of 2
+    rnd = wl.make_round(spec)
+    run = OracleRun(tdo, rnd)
+    run.rerotate()
+    # the two rows after the span (positions 12, 13) hold unrelated pool bits: no flag
+    assert np.all(run.encode().count == 0)
+    run.pk[brute_slot(rnd, 0, 9), 0] ^= np.uint16(0x4000)
+    d = run.encode()
+    assert lists_of(d, 1)[0].tolist() == [2]
+    page = d.payload[0].reshape(2, 4, spec.row_elems)
+    assert np.all(page[:, 2:] == 0)
+    assert np.array_equal(page[0, :2], run.pk[rnd.dst_rows(0, np.array([8, 9]))])
+
+
+def test_encode_capacity_overflow_keeps_counts(tdo):
+    spec = small_spec(H=2, D=8, T=4, agents=3, blocks=2, block_tokens=8)
+    rnd = wl.make_round(spec)
+    run = OracleRun(tdo, rnd)            # everything differs: 4 pages per agent
+    full = run.encode()
+    d = run.encode(capacity=5)
+    assert d.overflow[0] == 1
+    assert np.array_equal(d.count, full.count) and np.array_equal(d.offset, full.offset)
+    assert np.array_equal(d.idx[:5], full.idx[:5])
+    assert np.array_equal(d.payload[:5], full.payload[:5])
+
+
+# ---------------------------------------------------------------------------
+# diff_decode
+# ---------------------------------------------------------------------------
+
+@pytest.mark.parametrize("cfg", ["tiny", "small_unaligned"])
+def test_decode_of_encode_is_identity(tdo, cfg):
+    if cfg == "tiny":
+        rnd = wl.make_round(wl.CONFIGS["tiny"])
+    else:
+        rnd = wl.make_round(small_spec(H=2, D=8, T=4, sessions=2, agents=3, blocks=3, block_tokens=7, frac=0.3))
+    run = OracleRun(tdo, rnd)
+    run.rerotate()
+    run.perturb()
+    d = run.encode()
+    assert d.offset[-1] == sum(len(p) for p in rnd.perturbed)
+    pk, pv = wl.pool_host(rnd, 0)
+    run.decode(d, pk, pv)
+    mask = wl.shared_row_mask(rnd)
+    assert np.array_equal(pk[mask], run.pk[mask]) and np.array_equal(pv[mask], run.pv[mask])
+    pk0, pv0 = wl.pool_host(rnd, 0)
+    assert np.array_equal(pk[~mask], pk0[~mask]) and np.array_equal(pv[~mask], pv0[~mask])
+
+
+def test_decode_lossless_roundtrip_of_arbitrary_cache(tdo):
+    """eps = 0: any cache comes back bit for bit (pages equal to the reference are regenerated)."""
+    spec = small_spec(H=2, D=8, T=4, agents=2, blocks=2, block_tokens=9)
+    rnd = wl.make_round(spec)
+    run = OracleRun(tdo, rnd)
+    run.rerotate()
+    rng = np.random.default_rng(11)
+    rows = rnd.dst_rows(1)
+    run.pk[rows[3:11]] = rng.integers(0, 0x7F00, size=(8, spec.row_elems), dtype=np.uint16)
+    d = run.encode(eps=0.0)
+    pk, pv = wl.pool_host(rnd, 0)
+    run.decode(d, pk, pv)
+    mask = wl.shared_row_mask(rnd)
+    assert np.array_equal(pk[mask], run.pk[mask]) and np.array_equal(pv[mask], run.pv[mask])
+
+
+def test_decode_lossy_within_eps(tdo):
+    """Unflagged pages come back as the reference: error <= eps there, 0 on flagged pages."""
+    spec = small_spec(H=2, D=8, T=4, agents=2, blocks=3, block_tokens=8)
+    rnd = wl.make_round(spec)
+    run = OracleRun(tdo, rnd)
+    run.rerotate()
+    rng = np.random.default_rng(12)
+    for plane in (run.pk, run.pv):   # small wiggle everywhere: below eps = 0.25
+        x = wl.bf16_bits_to_f32(plane)
+        plane[:] = wl.f32_to_bf16_bits(x + rng.uniform(-0.1, 0.1, x.shape).astype(np.float32))
+    run.pk[brute_slot(rnd, 0, 4), 0] = 0x4500   # one big change: page 1 of agent 0
+    d = run.encode(eps=0.25)
+    assert lists_of(d, 2)[0].tolist() == [1] and d.count[1] == 0
+    pk, pv = wl.pool_host(rnd, 0)
+    run.decode(d, pk, pv)
+    for i in range(2):
+        rows = rnd.dst_rows(i)
+        err = np.abs(wl.bf16_bits_to_f32(pk[rows]) - wl.bf16_bits_to_f32(run.pk[rows]))
+        assert err.max() <= 0.25
+    rows = rnd.dst_rows(0, np.arange(4, 8))
+    assert np.array_equal(pk[rows], run.pk[rows]) and np.array_equal(pv[rows], run.pv[rows])
+
+
+def test_decode_empty_diff_equals_rerotate_and_is_idempotent(tdo):
+    rnd = wl.make_round(small_spec(H=2, D=8, T=4, agents=3, blocks=2, block_tokens=9))
+    run = OracleRun(tdo, rnd)
+    run.rerotate()
+    d = run.encode()
+    assert d.offset[-1] == 0
+    pk, pv = wl.pool_host(rnd, 0)
+    run.decode(d, pk, pv)
+    assert np.array_equal(pk, run.pk) and np.array_equal(pv, run.pv)
+    run.decode(d, pk, pv)
+    assert np.array_equal(pk, run.pk) and np.array_equal(pv, run.pv)
+
+
+def test_decode_rejects_bad_index_list(tdo):
+    rnd = wl.make_round(small_spec(H=2, D=8, T=4, agents=1, blocks=2, block_tokens=8))
+    run = OracleRun(tdo, rnd)
+    d = run.encode()
+    d.idx[1] = d.idx[0]          # not ascending
+    with pytest.raises(ValueError):
+        run.decode(d)
+    d = run.encode()
+    d.idx[0] = 99                # out of range
+    with pytest.raises(ValueError):
+        run.decode(d)
+
+
+# ---------------------------------------------------------------------------
+# fp32-math vs double-math flags: the decision precision matters only at the threshold
+# ---------------------------------------------------------------------------
+
+def test_flags_agree_between_math_modes_on_workload(tdo):
+    rnd = wl.make_round(wl.CONFIGS["tiny"])
+    a = OracleRun(tdo, rnd, math=tdo.MATH_F32)
+    a.rerotate(); a.perturb()
+    b = OracleRun(tdo, rnd, math=tdo.MATH_F64)
+    b.pk[:] = a.pk; b.pv[:] = a.pv
+    da, db = a.encode(eps=5e-2), b.encode(eps=5e-2)
+    # with eps above one bf16 ulp of the data range the two precisions take the same decisions
+    assert np.array_equal(da.count, db.count)
