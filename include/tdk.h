@@ -1,0 +1,179 @@
+/*
+ * tdk.h -- C ABI of libtdk: the data-parallel hot path of collective KV-cache reuse and
+ * diff-aware storage for multi-agent "All-Gather" rounds, for AMD MI355X (gfx950).
+ *
+ * One round = n_sessions masters (the K/V of the shared output blocks, cached once, rotated for
+ * positions master_pos0 ..) and n_agents mirrors (agent sub-requests).  Every agent's prompt is its
+ * private history followed by the shared blocks (Sec. 2.1, Eq. 2), so agent i sees the shared span
+ * at absolute positions dst_pos0_i .. dst_pos0_i + S - 1.  Per layer the library offers three
+ * collective steps over the whole round:
+ *
+ *   tdk_rerotate_round   Sec. 4.2 "Layerwise Collective Reuse": one batched RoPE pass for the
+ *                        group; cached K re-rotated by the position delta, V copied.
+ *   tdk_diff_encode      Sec. 4.3 "Block-Sparse Diff Representation", Sec. 5 "Diff-Aware Storage":
+ *                        each mirror becomes {touched page indices, K/V values of those pages}.
+ *   tdk_diff_decode      Sec. 4.4 / Algorithm 1 "Fused Diff Restore": apply diff, recover RoPE
+ *                        positions, write through the slot map; no dense mirror is materialised.
+ *
+ * Conventions
+ *   - Pointers marked DEV are device pointers owned by the caller; HOST are host pointers.  The
+ *     library borrows DEV buffers for the duration of the enqueued work and never frees them.
+ *   - The three step calls validate on the host, enqueue kernels on the given HIP stream
+ *     (hipStream_t passed as void*, NULL = default stream) and return without synchronising.
+ *     They allocate nothing.  tdk_round_create / tdk_round_destroy allocate / free the library's
+ *     own device memory (tables, descriptors, per-page flag scratch) and are synchronous.
+ *   - Errors are return codes; tdk_last_error() gives thread-local detail.  Anything the host can
+ *     detect fails before any work is enqueued.
+ *   - Results are deterministic: same inputs, same bits, including index order and payload placement.
+ *   - Not checked (preconditions): physical pages of different agents do not overlap (the paper's
+ *     "non-overlapping slot mappings", Sec. 4.2); buffers are not written concurrently.
+ *
+ * Arithmetic: bf16 storage; cos/sin of phi_j = delta * theta^(-2j/D) evaluated in double on the
+ * host and rounded once to fp32; per pair (a, b): y_a = fma(x_a, cos, -(x_b * sin)),
+ * y_b = fma(x_b, cos, x_a * sin) in fp32; round-to-nearest-even to bf16.
+ */
+#ifndef TDK_H
+#define TDK_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  TDK_OK = 0,
+  TDK_ERR_INVALID_ARG = 1,   /* NULL, out-of-range or inconsistent argument           */
+  TDK_ERR_UNSUPPORTED = 2,   /* a valid request this build has no kernel for          */
+  TDK_ERR_CAPACITY = 3,      /* reserved: capacity problems are reported on the device */
+  TDK_ERR_HIP = 4,           /* a HIP runtime call failed (no GPU, launch error, ...)  */
+  TDK_ERR_NOMEM = 5          /* host or device allocation failed                      */
+} tdk_status;
+
+#define TDK_BF16 0
+#define TDK_ROPE_HALF 0          /* pair (j, j + D/2) inside a head */
+#define TDK_ROPE_INTERLEAVED 1   /* pair (2j, 2j + 1) inside a head */
+
+const char* tdk_status_str(tdk_status s);   /* static string                                   */
+const char* tdk_last_error(void);           /* thread-local, valid until the next failing call */
+const char* tdk_version(void);
+
+/* Cache geometry.  Supported: dtype TDK_BF16; head_dim 128; 1 <= num_kv_heads <= 8;
+ * page_tokens 16 or 32; both rope styles. */
+typedef struct {
+  int32_t num_layers;
+  int32_t num_kv_heads;   /* H */
+  int32_t head_dim;       /* D */
+  int32_t page_tokens;    /* T: tokens per page = granularity of the diff (Sec. 4.3) */
+  int32_t dtype;          /* TDK_BF16 */
+  int32_t rope_style;     /* TDK_ROPE_* */
+  double  rope_theta;
+} tdk_model;
+
+/* One shared span = one master. */
+typedef struct {
+  int32_t span_tokens;    /* S >= 0 */
+  int64_t master_pos0;    /* absolute position the master's token 0 is rotated for */
+} tdk_session;
+
+/* One agent sub-request (a mirror of its session's master). */
+typedef struct {
+  int32_t        session;          /* index into sessions[]                                        */
+  int64_t        dst_pos0;         /* absolute position of its first shared token (history length) */
+  const int32_t* block_table;      /* HOST: logical page -> physical page of the agent's sequence  */
+  int32_t        block_table_len;  /* >= ceil((dst_pos0 + S) / T)                                  */
+} tdk_agent;
+
+typedef struct tdk_round tdk_round;   /* opaque: tables, descriptors, scratch on the current device */
+
+/* Builds the plan of a round on the current HIP device: rotation tables per agent, the slices of
+ * the block tables that cover the shared spans, the work list.  Copies everything it needs; the
+ * arguments may be freed on return.  Errors: INVALID_ARG (NULL, negative sizes or positions, bad
+ * session index, block table too short, negative page number, position beyond 2^31), UNSUPPORTED
+ * (geometry), NOMEM, HIP. */
+tdk_status tdk_round_create(const tdk_model* model,
+                            const tdk_session* sessions, int32_t n_sessions,
+                            const tdk_agent* agents, int32_t n_agents,
+                            tdk_round** out);
+void       tdk_round_destroy(tdk_round* r);             /* NULL-safe */
+size_t     tdk_scratch_bytes(const tdk_round* r);       /* device bytes the round owns */
+
+/* Launch shape: agents of one session that share one read of a master page (1..32), 0 = automatic.
+ * flags bit 0: use non-temporal stores for pool writes. */
+tdk_status tdk_round_tune(tdk_round* r, int32_t agents_per_group, int32_t flags);
+
+/* Per-layer views, all DEV.
+ *   master_k/v  [sum_s S_s][H][D] bf16, sessions concatenated in order (token-major rows)
+ *   pool_k/v    [pool_pages][T][H][D] bf16, the paged KV memory of this layer */
+typedef struct {
+  const void* master_k;
+  const void* master_v;
+  void*       pool_k;
+  void*       pool_v;
+  int64_t     pool_pages;
+} tdk_layer_io;
+
+/* The mirrors of one layer (block-sparse diff of every agent), all DEV, caller-owned.
+ *   count[n_agents]        pages in each agent's diff
+ *   offset[n_agents + 1]   exclusive prefix of count
+ *   idx[capacity_pages]    master-page numbers, ascending within an agent, agents in order
+ *   payload[capacity_pages][2][T][H][D]  the agent's own K rows then V rows of each listed page
+ *                          (values as they sit in the agent's cache; rows past the span are zero)
+ *   overflow[1]            set to 1 by encode when sum(count) > capacity_pages, else 0; count and
+ *                          offset are complete either way and nothing is written past capacity. */
+typedef struct {
+  int32_t* count;
+  int64_t* offset;
+  int32_t* idx;
+  void*    payload;
+  int64_t  capacity_pages;
+  int32_t* overflow;
+} tdk_diff;
+
+/* pool_k[slot_i(m)] = bf16(R(dst_pos0_i - master_pos0) master_k[m]), pool_v[slot_i(m)] = master_v[m]
+ * for every agent i and master token m, slot_i(m) = block_table_i[(dst_pos0_i+m)/T]*T + (dst_pos0_i+m)%T.
+ * No other pool row is written.  Errors: INVALID_ARG (NULL, layer out of range, pool_pages smaller
+ * than the largest mapped page + 1), HIP. */
+tdk_status tdk_rerotate_round(tdk_round* r, int32_t layer, const tdk_layer_io* io, void* hip_stream);
+
+/* Page p of agent i is in the diff iff some valid element of its K or V rows has
+ * !(|a - ref| <= eps) in fp32, ref = what tdk_rerotate_round would write.  eps >= 0, not NaN.
+ * Reads the pool, writes *out.  Errors as above plus INVALID_ARG for eps or NULL diff members. */
+tdk_status tdk_diff_encode(tdk_round* r, int32_t layer, const tdk_layer_io* io, float eps,
+                           const tdk_diff* out, void* hip_stream);
+
+/* Writes every agent's shared span: pages listed in the diff from the payload, all others from the
+ * re-rotated master.  `in` must hold what tdk_diff_encode produced for this round (ascending
+ * indices); entries at or past capacity_pages are ignored (those pages come from the master). */
+tdk_status tdk_diff_decode(tdk_round* r, int32_t layer, const tdk_layer_io* io, const tdk_diff* in,
+                           void* hip_stream);
+
+/* Kernel timing with HIP events on the caller's stream (off by default).  When on, every kernel
+ * launch of the step calls is bracketed by two events; tdk_timing_read waits for them. */
+#define TDK_KERNEL_REROTATE 0
+#define TDK_KERNEL_FLAG     1
+#define TDK_KERNEL_COUNT    2
+#define TDK_KERNEL_INDEX    3
+#define TDK_KERNEL_GATHER   4
+#define TDK_KERNEL_DECODE   5
+#define TDK_KERNEL_KINDS    6
+tdk_status tdk_timing_enable(tdk_round* r, int32_t on);
+tdk_status tdk_timing_read(tdk_round* r, int32_t kernel, double* total_ms, int64_t* launches);
+tdk_status tdk_timing_reset(tdk_round* r);
+const char* tdk_kernel_name(int32_t kernel);   /* device symbol name prefix, for profiler output */
+
+/* Storage arithmetic of Sec. 6.4 (host only). */
+double tdk_dense_bytes(const tdk_model* m, int64_t span_tokens);   /* one layer of one cache      */
+double tdk_diff_bytes(const tdk_model* m, int64_t diff_pages);     /* values + idx + count/offset */
+double tdk_family_cost(int64_t n_agents, double ratio);            /* 1 + (N-1)/R full caches     */
+
+/* Plain device copy / fill of `bytes` (multiple of 16) with 16-byte accesses: the measured HBM
+ * ceiling the step kernels are compared with, and the known-size reference for traffic counters. */
+tdk_status tdk_util_copy(void* dst, const void* src, size_t bytes, void* hip_stream);
+tdk_status tdk_util_fill(void* dst, uint32_t word, size_t bytes, void* hip_stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif

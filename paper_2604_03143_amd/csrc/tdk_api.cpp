@@ -1,0 +1,535 @@
+// Host side of libtdk: argument validation, the round planner (rotation tables, block-table
+// slices, work list), device memory owned by a round, event timing and the C ABI itself.
+#include <algorithm>
+#include <cmath>
+#include <cstdio>
+#include <cstring>
+#include <new>
+#include <string>
+#include <vector>
+
+#include "tdk_internal.h"
+
+using namespace tdk;
+
+namespace {
+
+thread_local std::string g_last_error;
+
+tdk_status fail(tdk_status st, const std::string& msg) {
+  g_last_error = msg;
+  return st;
+}
+
+tdk_status hip_fail(hipError_t e, const char* what) {
+  return fail(TDK_ERR_HIP, std::string(what) + ": " + hipGetErrorString(e));
+}
+
+size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+
+struct HostSession {
+  int32_t span, pages;
+  int64_t master_pos0, master_row0;
+  std::vector<int32_t> agents;   // ids of its agents, in descriptor order
+};
+
+struct EventPair {
+  hipEvent_t start, stop;
+  int kernel;
+};
+
+}  // namespace
+
+struct tdk_round {
+  tdk_model model{};
+  int device = -1;
+  std::vector<HostSession> sessions;
+  int32_t n_agents = 0;
+  int64_t max_phys_page = -1;      // largest page number any shared span maps to
+  int64_t total_pages = 0;         // sum over agents of their session's page count
+  int64_t total_master_pages = 0;  // sum over sessions of pages
+  int32_t group = 0;               // agents per work item (resolved)
+  int32_t flags = 1;
+
+  void*  blob = nullptr;           // one device allocation for everything below
+  size_t blob_bytes = 0;
+  size_t work_capacity = 0;        // WorkItems the work region can hold
+  RoundDev rd{};
+
+  bool timing = false;
+  std::vector<EventPair> pending;
+  std::vector<EventPair> free_events;
+  double  total_ms[TDK_KERNEL_KINDS] = {0};
+  int64_t launches[TDK_KERNEL_KINDS] = {0};
+};
+
+namespace {
+
+// Work list: one item per (master page, agent group).  Items that share a master page are given
+// workgroup ids that are congruent modulo 8, so that (with round-robin dispatch of workgroups to
+// the 8 XCDs) they run on the same XCD and the re-read of the master page hits that XCD's L2.
+void build_work(const tdk_round& r, int group, std::vector<WorkItem>& work) {
+  work.clear();
+  struct PageRef { int32_t session, page; };
+  std::vector<PageRef> pages;
+  std::vector<int32_t> order_begin(r.sessions.size(), 0);
+  int32_t cursor = 0;
+  for (size_t s = 0; s < r.sessions.size(); ++s) {
+    order_begin[s] = cursor;
+    cursor += (int32_t)r.sessions[s].agents.size();
+  }
+  // group the pages by their session's group count so that every block of 8 pages has one count
+  std::vector<int> ngroups(r.sessions.size(), 0);
+  for (size_t s = 0; s < r.sessions.size(); ++s) {
+    const int n = (int)r.sessions[s].agents.size();
+    ngroups[s] = n ? (n + group - 1) / group : 0;
+  }
+  for (size_t s = 0; s < r.sessions.size(); ++s) {
+    if (!ngroups[s]) continue;
+    pages.clear();
+    for (int32_t p = 0; p < r.sessions[s].pages; ++p) pages.push_back({(int32_t)s, p});
+    const int n = (int)r.sessions[s].agents.size();
+    const int G = ngroups[s];
+    for (size_t q0 = 0; q0 < pages.size(); q0 += 8) {
+      const size_t qn = std::min<size_t>(8, pages.size() - q0);
+      for (int g = 0; g < G; ++g) {
+        // balanced split: the first (n % G) groups get one agent more
+        const int base = n / G, extra = n % G;
+        const int begin = g * base + std::min(g, extra);
+        const int cnt = base + (g < extra ? 1 : 0);
+        for (size_t q = 0; q < qn; ++q)
+          work.push_back({pages[q0 + q].session, pages[q0 + q].page, order_begin[s] + begin, cnt});
+      }
+    }
+  }
+}
+
+int auto_group(const tdk_round& r) {
+  // enough work items to fill 256 CUs several times over, without splitting more than needed
+  const int64_t target = 256 * 8;
+  int best = kMaxGroup;
+  for (int g = kMaxGroup; g >= 1; --g) {
+    int64_t items = 0;
+    for (const auto& s : r.sessions) {
+      const int n = (int)s.agents.size();
+      if (n) items += (int64_t)s.pages * ((n + g - 1) / g);
+    }
+    best = g;
+    if (items >= target) break;
+  }
+  return best;
+}
+
+tdk_status upload_work(tdk_round* r, int group) {
+  std::vector<WorkItem> work;
+  build_work(*r, group, work);
+  if (work.size() > r->work_capacity) return fail(TDK_ERR_INVALID_ARG, "work list larger than reserved");
+  if (!work.empty()) {
+    hipError_t e = hipMemcpy(const_cast<WorkItem*>(r->rd.work), work.data(), work.size() * sizeof(WorkItem),
+                             hipMemcpyHostToDevice);
+    if (e != hipSuccess) return hip_fail(e, "hipMemcpy(work list)");
+  }
+  r->rd.n_work = (int32_t)work.size();
+  r->group = group;
+  return TDK_OK;
+}
+
+tdk_status check_model(const tdk_model* m) {
+  if (!m) return fail(TDK_ERR_INVALID_ARG, "model is NULL");
+  if (m->num_layers <= 0 || m->num_kv_heads <= 0 || m->head_dim <= 0 || m->page_tokens <= 0)
+    return fail(TDK_ERR_INVALID_ARG, "model: sizes must be positive");
+  if (!(m->rope_theta > 0.0) || !std::isfinite(m->rope_theta))
+    return fail(TDK_ERR_INVALID_ARG, "model: rope_theta must be positive and finite");
+  if (m->rope_style != TDK_ROPE_HALF && m->rope_style != TDK_ROPE_INTERLEAVED)
+    return fail(TDK_ERR_INVALID_ARG, "model: unknown rope_style");
+  if (m->dtype != TDK_BF16) return fail(TDK_ERR_UNSUPPORTED, "model: only bf16 caches are supported");
+  if (m->head_dim != kHeadDim) return fail(TDK_ERR_UNSUPPORTED, "model: only head_dim 128 is supported");
+  if (m->num_kv_heads > 8) return fail(TDK_ERR_UNSUPPORTED, "model: at most 8 KV heads per device are supported");
+  if (m->page_tokens != 16 && m->page_tokens != 32)
+    return fail(TDK_ERR_UNSUPPORTED, "model: page_tokens must be 16 or 32");
+  return TDK_OK;
+}
+
+tdk_status check_step(const tdk_round* r, int32_t layer, const tdk_layer_io* io) {
+  if (!r) return fail(TDK_ERR_INVALID_ARG, "round is NULL");
+  if (!io) return fail(TDK_ERR_INVALID_ARG, "layer io is NULL");
+  if (layer < 0 || layer >= r->model.num_layers) return fail(TDK_ERR_INVALID_ARG, "layer out of range");
+  if (io->pool_pages < 0) return fail(TDK_ERR_INVALID_ARG, "pool_pages is negative");
+  if (r->rd.n_work > 0) {
+    if (!io->master_k || !io->master_v || !io->pool_k || !io->pool_v)
+      return fail(TDK_ERR_INVALID_ARG, "layer io holds a NULL buffer");
+    if (io->pool_pages <= r->max_phys_page)
+      return fail(TDK_ERR_INVALID_ARG, "pool_pages is smaller than a page number in the block tables");
+    const uintptr_t bits = (uintptr_t)io->master_k | (uintptr_t)io->master_v | (uintptr_t)io->pool_k | (uintptr_t)io->pool_v;
+    if (bits & 15) return fail(TDK_ERR_INVALID_ARG, "layer io buffers must be 16-byte aligned");
+  }
+  return TDK_OK;
+}
+
+tdk_status check_diff(const tdk_round* r, const tdk_diff* d, bool for_encode) {
+  if (!d) return fail(TDK_ERR_INVALID_ARG, "diff is NULL");
+  if (!d->count || !d->offset) return fail(TDK_ERR_INVALID_ARG, "diff.count / diff.offset is NULL");
+  if (for_encode && !d->overflow) return fail(TDK_ERR_INVALID_ARG, "diff.overflow is NULL");
+  if (d->capacity_pages < 0) return fail(TDK_ERR_INVALID_ARG, "diff.capacity_pages is negative");
+  if (d->capacity_pages > 0 && (!d->idx || !d->payload))
+    return fail(TDK_ERR_INVALID_ARG, "diff.idx / diff.payload is NULL with capacity_pages > 0");
+  if ((uintptr_t)d->payload & 15) return fail(TDK_ERR_INVALID_ARG, "diff.payload must be 16-byte aligned");
+  if ((uintptr_t)d->offset & 7) return fail(TDK_ERR_INVALID_ARG, "diff.offset must be 8-byte aligned");
+  (void)r;
+  return TDK_OK;
+}
+
+LayerDev layer_dev(const tdk_layer_io* io) {
+  LayerDev l;
+  l.master_k = static_cast<const u32x4*>(io->master_k);
+  l.master_v = static_cast<const u32x4*>(io->master_v);
+  l.pool_k = static_cast<u32x4*>(io->pool_k);
+  l.pool_v = static_cast<u32x4*>(io->pool_v);
+  return l;
+}
+
+DiffDev diff_dev(const tdk_diff* d) {
+  DiffDev x;
+  x.count = d->count;
+  x.offset = d->offset;
+  x.idx = d->idx;
+  x.payload = static_cast<u32x4*>(d->payload);
+  x.capacity = d->capacity_pages;
+  x.overflow = d->overflow;
+  return x;
+}
+
+// brackets one kernel launch with events when timing is on
+struct Timed {
+  tdk_round* r;
+  hipStream_t st;
+  EventPair ev{};
+  bool on;
+  hipError_t err = hipSuccess;
+  Timed(tdk_round* r_, int kernel, hipStream_t st_) : r(r_), st(st_), on(r_->timing) {
+    if (!on) return;
+    if (!r->free_events.empty()) {
+      ev = r->free_events.back();
+      r->free_events.pop_back();
+    } else {
+      err = hipEventCreate(&ev.start);
+      if (err == hipSuccess) err = hipEventCreate(&ev.stop);
+      if (err != hipSuccess) { on = false; return; }
+    }
+    ev.kernel = kernel;
+    err = hipEventRecord(ev.start, st);
+  }
+  void done() {
+    if (!on) return;
+    hipError_t e = hipEventRecord(ev.stop, st);
+    if (err == hipSuccess) err = e;
+    r->pending.push_back(ev);
+  }
+};
+
+#define TDK_LAUNCH(R, KIND, ST, CALL)                                     \
+  do {                                                                    \
+    Timed timed_((R), (KIND), (ST));                                      \
+    hipError_t e_ = (CALL);                                               \
+    timed_.done();                                                        \
+    if (e_ != hipSuccess) return hip_fail(e_, "kernel launch " #KIND);     \
+    if (timed_.err != hipSuccess) return hip_fail(timed_.err, "event record"); \
+  } while (0)
+
+}  // namespace
+
+extern "C" {
+
+const char* tdk_status_str(tdk_status s) {
+  switch (s) {
+    case TDK_OK: return "ok";
+    case TDK_ERR_INVALID_ARG: return "invalid argument";
+    case TDK_ERR_UNSUPPORTED: return "unsupported";
+    case TDK_ERR_CAPACITY: return "capacity exceeded";
+    case TDK_ERR_HIP: return "HIP runtime error";
+    case TDK_ERR_NOMEM: return "out of memory";
+  }
+  return "unknown status";
+}
+
+const char* tdk_last_error(void) { return g_last_error.c_str(); }
+
+const char* tdk_version(void) { return "tdk 0.1 (gfx950)"; }
+
+const char* tdk_kernel_name(int32_t kernel) {
+  switch (kernel) {
+    case TDK_KERNEL_REROTATE: return "tdk_rerotate_kernel";
+    case TDK_KERNEL_FLAG: return "tdk_flag_kernel";
+    case TDK_KERNEL_COUNT: return "tdk_count_kernel";
+    case TDK_KERNEL_INDEX: return "tdk_index_kernel";
+    case TDK_KERNEL_GATHER: return "tdk_gather_kernel";
+    case TDK_KERNEL_DECODE: return "tdk_decode_kernel";
+  }
+  return "";
+}
+
+tdk_status tdk_round_create(const tdk_model* model, const tdk_session* sessions, int32_t n_sessions,
+                            const tdk_agent* agents, int32_t n_agents, tdk_round** out) {
+  if (!out) return fail(TDK_ERR_INVALID_ARG, "out is NULL");
+  *out = nullptr;
+  tdk_status st = check_model(model);
+  if (st != TDK_OK) return st;
+  if (n_sessions < 0 || n_agents < 0) return fail(TDK_ERR_INVALID_ARG, "negative session or agent count");
+  if ((n_sessions && !sessions) || (n_agents && !agents)) return fail(TDK_ERR_INVALID_ARG, "sessions / agents is NULL");
+
+  const int T = model->page_tokens;
+  tdk_round* r = new (std::nothrow) tdk_round();
+  if (!r) return fail(TDK_ERR_NOMEM, "host allocation failed");
+  r->model = *model;
+  r->n_agents = n_agents;
+
+  // ---- host-side validation and planning (no HIP call before this block is through) ----
+  std::vector<SessionDev> sess_dev(n_sessions);
+  std::vector<AgentDev> agent_dev(n_agents);
+  std::vector<int32_t> bt;
+  std::vector<float> tab((size_t)n_agents * 2 * kHalf);
+  r->sessions.resize(n_sessions);
+  int64_t row0 = 0;
+  for (int32_t s = 0; s < n_sessions; ++s) {
+    if (sessions[s].span_tokens < 0) { delete r; return fail(TDK_ERR_INVALID_ARG, "session: negative span_tokens"); }
+    if (sessions[s].master_pos0 < 0) { delete r; return fail(TDK_ERR_INVALID_ARG, "session: negative master_pos0"); }
+    HostSession& hs = r->sessions[s];
+    hs.span = sessions[s].span_tokens;
+    hs.pages = (hs.span + T - 1) / T;
+    hs.master_pos0 = sessions[s].master_pos0;
+    hs.master_row0 = row0;
+    row0 += hs.span;
+    sess_dev[s] = {hs.master_row0, hs.span, hs.pages};
+    r->total_master_pages += hs.pages;
+  }
+  int64_t flag_off = 0;
+  for (int32_t i = 0; i < n_agents; ++i) {
+    const tdk_agent& a = agents[i];
+    if (a.session < 0 || a.session >= n_sessions) { delete r; return fail(TDK_ERR_INVALID_ARG, "agent: session index out of range"); }
+    if (a.dst_pos0 < 0) { delete r; return fail(TDK_ERR_INVALID_ARG, "agent: negative dst_pos0"); }
+    HostSession& hs = r->sessions[a.session];
+    const int64_t S = hs.span;
+    if (a.dst_pos0 + S + T >= (int64_t)1 << 31) { delete r; return fail(TDK_ERR_INVALID_ARG, "agent: positions beyond 2^31"); }
+    const int64_t lp_first = a.dst_pos0 / T;
+    const int64_t lp_last = S > 0 ? (a.dst_pos0 + S - 1) / T : lp_first - 1;
+    if (S > 0) {
+      if (!a.block_table) { delete r; return fail(TDK_ERR_INVALID_ARG, "agent: block_table is NULL"); }
+      if ((int64_t)a.block_table_len <= lp_last) { delete r; return fail(TDK_ERR_INVALID_ARG, "agent: block_table too short for its span"); }
+    }
+    AgentDev& ad = agent_dev[i];
+    ad.pos0 = (int32_t)a.dst_pos0;
+    ad.bt_off = (int32_t)bt.size();
+    ad.lp_first = (int32_t)lp_first;
+    ad.bt_len = (int32_t)(lp_last - lp_first + 1);
+    ad.session = a.session;
+    ad.flag_off = (int32_t)flag_off;
+    ad.pad0 = ad.pad1 = 0;
+    for (int64_t lp = lp_first; lp <= lp_last; ++lp) {
+      const int32_t pg = a.block_table[lp];
+      if (pg < 0) { delete r; return fail(TDK_ERR_INVALID_ARG, "agent: negative page number in block_table"); }
+      r->max_phys_page = std::max<int64_t>(r->max_phys_page, pg);
+      bt.push_back(pg);
+    }
+    flag_off += hs.pages;
+    if (flag_off >= (int64_t)1 << 31 || bt.size() >= (size_t)1 << 31) { delete r; return fail(TDK_ERR_UNSUPPORTED, "round too large"); }
+    hs.agents.push_back(i);
+
+    // rotation table of this agent's position delta: angles in double, one rounding to fp32
+    const double delta = (double)(a.dst_pos0 - hs.master_pos0);
+    float* c = tab.data() + (size_t)i * 2 * kHalf;
+    float* sn = c + kHalf;
+    for (int j = 0; j < kHalf; ++j) {
+      const double inv_freq = std::pow(model->rope_theta, -(double)(2 * j) / (double)model->head_dim);
+      const double phi = delta * inv_freq;
+      c[j] = (float)std::cos(phi);
+      sn[j] = (float)std::sin(phi);
+    }
+  }
+  r->total_pages = flag_off;
+  std::vector<int32_t> order;
+  order.reserve(n_agents);
+  for (const auto& hs : r->sessions) order.insert(order.end(), hs.agents.begin(), hs.agents.end());
+
+  // worst case for the work list: every agent its own group
+  size_t work_cap = 0;
+  for (const auto& hs : r->sessions) work_cap += (size_t)hs.pages * hs.agents.size();
+  r->work_capacity = work_cap;
+
+  // ---- device memory: one allocation ----
+  size_t off = 0;
+  auto place = [&](size_t bytes) { size_t o = off; off = align_up(off + bytes, 256); return o; };
+  const size_t o_work = place(work_cap * sizeof(WorkItem));
+  const size_t o_sess = place(sess_dev.size() * sizeof(SessionDev));
+  const size_t o_agents = place(agent_dev.size() * sizeof(AgentDev));
+  const size_t o_order = place(order.size() * sizeof(int32_t));
+  const size_t o_bt = place(bt.size() * sizeof(int32_t));
+  const size_t o_tab = place(tab.size() * sizeof(float));
+  const size_t o_flags = place((size_t)flag_off);
+  r->blob_bytes = std::max<size_t>(off, 256);
+
+  hipError_t e = hipGetDevice(&r->device);
+  if (e != hipSuccess) { delete r; return hip_fail(e, "hipGetDevice"); }
+  e = hipMalloc(&r->blob, r->blob_bytes);
+  if (e != hipSuccess) { delete r; return e == hipErrorOutOfMemory ? fail(TDK_ERR_NOMEM, "device allocation failed") : hip_fail(e, "hipMalloc"); }
+  char* base = static_cast<char*>(r->blob);
+  auto up = [&](size_t o, const void* src, size_t bytes) -> hipError_t {
+    return bytes ? hipMemcpy(base + o, src, bytes, hipMemcpyHostToDevice) : hipSuccess;
+  };
+  e = up(o_sess, sess_dev.data(), sess_dev.size() * sizeof(SessionDev));
+  if (e == hipSuccess) e = up(o_agents, agent_dev.data(), agent_dev.size() * sizeof(AgentDev));
+  if (e == hipSuccess) e = up(o_order, order.data(), order.size() * sizeof(int32_t));
+  if (e == hipSuccess) e = up(o_bt, bt.data(), bt.size() * sizeof(int32_t));
+  if (e == hipSuccess) e = up(o_tab, tab.data(), tab.size() * sizeof(float));
+  if (e == hipSuccess && flag_off) e = hipMemset(base + o_flags, 0, (size_t)flag_off);
+  if (e != hipSuccess) { (void)hipFree(r->blob); delete r; return hip_fail(e, "upload of round descriptors"); }
+
+  r->rd.work = reinterpret_cast<const WorkItem*>(base + o_work);
+  r->rd.sess = reinterpret_cast<const SessionDev*>(base + o_sess);
+  r->rd.agents = reinterpret_cast<const AgentDev*>(base + o_agents);
+  r->rd.order = reinterpret_cast<const int32_t*>(base + o_order);
+  r->rd.bt = reinterpret_cast<const int32_t*>(base + o_bt);
+  r->rd.tab = reinterpret_cast<const float*>(base + o_tab);
+  r->rd.flags = reinterpret_cast<uint8_t*>(base + o_flags);
+  r->rd.n_agents = n_agents;
+  r->rd.n_sessions = n_sessions;
+  r->rd.heads = model->num_kv_heads;
+  r->rd.page_tokens = T;
+  r->rd.interleaved = model->rope_style == TDK_ROPE_INTERLEAVED;
+  r->rd.nontemporal = r->flags & 1;
+
+  st = upload_work(r, auto_group(*r));
+  if (st != TDK_OK) { (void)hipFree(r->blob); delete r; return st; }
+  *out = r;
+  return TDK_OK;
+}
+
+void tdk_round_destroy(tdk_round* r) {
+  if (!r) return;
+  for (auto& ev : r->pending) { (void)hipEventDestroy(ev.start); (void)hipEventDestroy(ev.stop); }
+  for (auto& ev : r->free_events) { (void)hipEventDestroy(ev.start); (void)hipEventDestroy(ev.stop); }
+  if (r->blob) (void)hipFree(r->blob);
+  delete r;
+}
+
+size_t tdk_scratch_bytes(const tdk_round* r) { return r ? r->blob_bytes : 0; }
+
+tdk_status tdk_round_tune(tdk_round* r, int32_t agents_per_group, int32_t flags) {
+  if (!r) return fail(TDK_ERR_INVALID_ARG, "round is NULL");
+  if (agents_per_group < 0 || agents_per_group > kMaxGroup)
+    return fail(TDK_ERR_INVALID_ARG, "agents_per_group must be 0 (automatic) or 1..32");
+  if (flags & ~1) return fail(TDK_ERR_INVALID_ARG, "unknown tuning flag");
+  // the work list is read by kernels already enqueued: wait for them before replacing it
+  hipError_t e = hipDeviceSynchronize();
+  if (e != hipSuccess) return hip_fail(e, "hipDeviceSynchronize");
+  r->flags = flags;
+  r->rd.nontemporal = flags & 1;
+  return upload_work(r, agents_per_group ? agents_per_group : auto_group(*r));
+}
+
+tdk_status tdk_rerotate_round(tdk_round* r, int32_t layer, const tdk_layer_io* io, void* hip_stream) {
+  tdk_status st = check_step(r, layer, io);
+  if (st != TDK_OK) return st;
+  hipStream_t s = static_cast<hipStream_t>(hip_stream);
+  TDK_LAUNCH(r, TDK_KERNEL_REROTATE, s, launch_rerotate(r->rd, layer_dev(io), s));
+  return TDK_OK;
+}
+
+tdk_status tdk_diff_encode(tdk_round* r, int32_t layer, const tdk_layer_io* io, float eps,
+                           const tdk_diff* out, void* hip_stream) {
+  tdk_status st = check_step(r, layer, io);
+  if (st != TDK_OK) return st;
+  st = check_diff(r, out, true);
+  if (st != TDK_OK) return st;
+  if (!(eps >= 0.0f) || !std::isfinite(eps)) return fail(TDK_ERR_INVALID_ARG, "eps must be finite and >= 0");
+  hipStream_t s = static_cast<hipStream_t>(hip_stream);
+  const LayerDev l = layer_dev(io);
+  const DiffDev d = diff_dev(out);
+  TDK_LAUNCH(r, TDK_KERNEL_FLAG, s, launch_flag(r->rd, l, eps, s));
+  TDK_LAUNCH(r, TDK_KERNEL_COUNT, s, launch_count(r->rd, d, s));
+  TDK_LAUNCH(r, TDK_KERNEL_INDEX, s, launch_index(r->rd, d, s));
+  // the number of listed pages is known on the device only: a fixed grid strides over them
+  const int64_t units = 2 * std::min<int64_t>(out->capacity_pages, r->total_pages);
+  const int grid = (int)std::min<int64_t>(units, 256 * 16);
+  TDK_LAUNCH(r, TDK_KERNEL_GATHER, s, launch_gather(r->rd, l, d, grid, s));
+  return TDK_OK;
+}
+
+tdk_status tdk_diff_decode(tdk_round* r, int32_t layer, const tdk_layer_io* io, const tdk_diff* in,
+                           void* hip_stream) {
+  tdk_status st = check_step(r, layer, io);
+  if (st != TDK_OK) return st;
+  st = check_diff(r, in, false);
+  if (st != TDK_OK) return st;
+  hipStream_t s = static_cast<hipStream_t>(hip_stream);
+  TDK_LAUNCH(r, TDK_KERNEL_DECODE, s, launch_decode(r->rd, layer_dev(io), diff_dev(in), s));
+  return TDK_OK;
+}
+
+tdk_status tdk_timing_enable(tdk_round* r, int32_t on) {
+  if (!r) return fail(TDK_ERR_INVALID_ARG, "round is NULL");
+  r->timing = on != 0;
+  return TDK_OK;
+}
+
+static tdk_status drain_events(tdk_round* r) {
+  for (auto& ev : r->pending) {
+    hipError_t e = hipEventSynchronize(ev.stop);
+    if (e != hipSuccess) return hip_fail(e, "hipEventSynchronize");
+    float ms = 0.f;
+    e = hipEventElapsedTime(&ms, ev.start, ev.stop);
+    if (e != hipSuccess) return hip_fail(e, "hipEventElapsedTime");
+    r->total_ms[ev.kernel] += ms;
+    r->launches[ev.kernel] += 1;
+    r->free_events.push_back(ev);
+  }
+  r->pending.clear();
+  return TDK_OK;
+}
+
+tdk_status tdk_timing_read(tdk_round* r, int32_t kernel, double* total_ms, int64_t* launches) {
+  if (!r || !total_ms || !launches) return fail(TDK_ERR_INVALID_ARG, "NULL argument");
+  if (kernel < 0 || kernel >= TDK_KERNEL_KINDS) return fail(TDK_ERR_INVALID_ARG, "kernel id out of range");
+  tdk_status st = drain_events(r);
+  if (st != TDK_OK) return st;
+  *total_ms = r->total_ms[kernel];
+  *launches = r->launches[kernel];
+  return TDK_OK;
+}
+
+tdk_status tdk_timing_reset(tdk_round* r) {
+  if (!r) return fail(TDK_ERR_INVALID_ARG, "round is NULL");
+  tdk_status st = drain_events(r);
+  if (st != TDK_OK) return st;
+  for (int k = 0; k < TDK_KERNEL_KINDS; ++k) { r->total_ms[k] = 0; r->launches[k] = 0; }
+  return TDK_OK;
+}
+
+double tdk_dense_bytes(const tdk_model* m, int64_t span_tokens) {
+  if (!m) return 0.0;
+  return (double)span_tokens * 2.0 * m->num_kv_heads * m->head_dim * 2.0;
+}
+
+double tdk_diff_bytes(const tdk_model* m, int64_t diff_pages) {
+  if (!m) return 0.0;
+  const double page = 2.0 * m->page_tokens * m->num_kv_heads * m->head_dim * 2.0;
+  return diff_pages * page + diff_pages * 4.0 + 12.0;
+}
+
+double tdk_family_cost(int64_t n_agents, double ratio) { return 1.0 + (double)(n_agents - 1) / ratio; }
+
+tdk_status tdk_util_copy(void* dst, const void* src, size_t bytes, void* hip_stream) {
+  if ((bytes && (!dst || !src)) || (bytes & 15) || (((uintptr_t)dst | (uintptr_t)src) & 15))
+    return fail(TDK_ERR_INVALID_ARG, "copy: NULL, misaligned or size not a multiple of 16");
+  hipError_t e = launch_copy(static_cast<u32x4*>(dst), static_cast<const u32x4*>(src), bytes / 16,
+                             static_cast<hipStream_t>(hip_stream));
+  return e == hipSuccess ? TDK_OK : hip_fail(e, "copy kernel");
+}
+
+tdk_status tdk_util_fill(void* dst, uint32_t word, size_t bytes, void* hip_stream) {
+  if ((bytes && !dst) || (bytes & 15) || ((uintptr_t)dst & 15))
+    return fail(TDK_ERR_INVALID_ARG, "fill: NULL, misaligned or size not a multiple of 16");
+  hipError_t e = launch_fill(static_cast<u32x4*>(dst), word, bytes / 16, static_cast<hipStream_t>(hip_stream));
+  return e == hipSuccess ? TDK_OK : hip_fail(e, "fill kernel");
+}
+
+}  // extern "C"

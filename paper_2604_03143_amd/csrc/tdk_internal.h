@@ -1,0 +1,84 @@
+// Internal declarations shared by the host planner (tdk_api.cpp) and the kernels (tdk_kernels.hip).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "tdk.h"
+
+namespace tdk {
+
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));   // one 16-byte access
+
+constexpr int kMaxGroup = 32;     // agents that share one read of a master page
+constexpr int kBlock = 256;       // threads per workgroup (4 wavefronts of 64)
+constexpr int kWaves = kBlock / 64;
+constexpr int kHeadDim = 128;
+constexpr int kHalf = kHeadDim / 2;
+
+// One unit of work of the page kernels: a master page and a group of agents of its session.
+struct WorkItem {
+  int32_t session;
+  int32_t page;        // master page number
+  int32_t ag_begin;    // range in RoundDev::order
+  int32_t ag_count;    // 1..kMaxGroup
+};
+
+struct SessionDev {
+  int64_t master_row0;  // first row of this session in master_k / master_v
+  int32_t span;         // S
+  int32_t pages;        // ceil(S / T)
+};
+
+struct AgentDev {
+  int32_t pos0;         // dst_pos0 (validated < 2^31)
+  int32_t bt_off;       // start of this agent's block-table slice in RoundDev::bt
+  int32_t lp_first;     // logical page number of slice entry 0 (= pos0 / T)
+  int32_t bt_len;       // entries in the slice
+  int32_t session;
+  int32_t flag_off;     // start of this agent's per-page flags in the flag scratch
+  int32_t pad0, pad1;
+};
+
+struct RoundDev {
+  const WorkItem*   work;
+  const SessionDev* sess;
+  const AgentDev*   agents;
+  const int32_t*    order;   // agent ids grouped by session
+  const int32_t*    bt;      // block-table slices, concatenated
+  const float*      tab;     // [n_agents][2][64]: cos then sin of the agent's delta
+  uint8_t*          flags;   // [sum_i pages_i] scratch of encode
+  int32_t n_work, n_agents, n_sessions;
+  int32_t heads;             // H
+  int32_t page_tokens;       // T
+  int32_t interleaved;       // rope style
+  int32_t nontemporal;
+};
+
+struct LayerDev {
+  const u32x4* master_k;
+  const u32x4* master_v;
+  u32x4*       pool_k;
+  u32x4*       pool_v;
+};
+
+struct DiffDev {
+  int32_t* count;
+  int64_t* offset;
+  int32_t* idx;
+  u32x4*   payload;
+  int64_t  capacity;
+  int32_t* overflow;
+};
+
+// launchers (tdk_kernels.hip); each enqueues exactly one kernel
+hipError_t launch_rerotate(const RoundDev& rd, const LayerDev& io, hipStream_t st);
+hipError_t launch_flag(const RoundDev& rd, const LayerDev& io, float eps, hipStream_t st);
+hipError_t launch_count(const RoundDev& rd, const DiffDev& d, hipStream_t st);
+hipError_t launch_index(const RoundDev& rd, const DiffDev& d, hipStream_t st);
+hipError_t launch_gather(const RoundDev& rd, const LayerDev& io, const DiffDev& d, int grid, hipStream_t st);
+hipError_t launch_decode(const RoundDev& rd, const LayerDev& io, const DiffDev& d, hipStream_t st);
+hipError_t launch_copy(u32x4* dst, const u32x4* src, size_t n16, hipStream_t st);
+hipError_t launch_fill(u32x4* dst, uint32_t word, size_t n16, hipStream_t st);
+
+}  // namespace tdk

@@ -1,0 +1,556 @@
+// HIP kernels of libtdk for gfx950 (MI355X): collective RoPE re-rotation, per-page compare,
+// ballot/prefix compaction, payload gather and fused diff restore.
+//
+// Data movement plan shared by the three page kernels (rerotate, flag, decode):
+//   - a workgroup of 4 wavefronts owns one master page (T rows of H*D bf16, K and V) and a group
+//     of up to 32 agents of that page's session;
+//   - the master page is read from HBM once, 16 bytes per lane, and stays in registers while the
+//     workgroup walks its agents (Sec. 4.2: the cost of a shared block is paid once per group);
+//   - the per-agent cos/sin tables, the two physical pages a master page can land on and the
+//     page's row offset are staged in LDS once per workgroup;
+//   - a wavefront always handles whole rows: lane l holds 8 consecutive elements of the low half
+//     and the 8 matching elements of the high half of head l/8, so both members of every rotation
+//     pair sit in the same lane and each load/store instruction covers whole 128-byte segments.
+#include "tdk_internal.h"
+
+namespace tdk {
+
+typedef float f32x2 __attribute__((ext_vector_type(2)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+
+// ---------------------------------------------------------------------------------------------
+// bf16 <-> fp32
+// ---------------------------------------------------------------------------------------------
+
+__device__ __forceinline__ float bf_lo(uint32_t w) { return __uint_as_float(w << 16); }
+__device__ __forceinline__ float bf_hi(uint32_t w) { return __uint_as_float(w & 0xffff0000u); }
+
+// two fp32 -> packed bf16 (a in the low half), round-to-nearest-even
+__device__ __forceinline__ uint32_t pack_bf16(float a, float b) {
+  f32x2 v = {a, b};
+  bf16x2 r = __builtin_convertvector(v, bf16x2);
+  return __builtin_bit_cast(uint32_t, r);
+}
+
+// y_a = fma(x_a, c, -(x_b * s)), y_b = fma(x_b, c, x_a * s): one rounded product, one fma.
+__device__ __forceinline__ void rot(float xa, float xb, float c, float s, float& ya, float& yb) {
+  float t = __fmul_rn(xb, s);
+  float u = __fmul_rn(xa, s);
+  ya = __builtin_fmaf(xa, c, -t);
+  yb = __builtin_fmaf(xb, c, u);
+}
+
+// Rotates the 16 elements a lane holds.  Half style: lo[e] pairs with hi[e], table entry e.
+// Interleaved style: each 32-bit word is one pair; lo uses entries 0..3, hi entries 4..7.
+template <bool IL>
+__device__ __forceinline__ void rotate16(const u32x4 lo, const u32x4 hi, const float (&c)[8],
+                                         const float (&s)[8], u32x4& olo, u32x4& ohi) {
+#pragma unroll
+  for (int w = 0; w < 4; ++w) {
+    if (!IL) {
+      float yl0, yh0, yl1, yh1;
+      rot(bf_lo(lo[w]), bf_lo(hi[w]), c[2 * w], s[2 * w], yl0, yh0);
+      rot(bf_hi(lo[w]), bf_hi(hi[w]), c[2 * w + 1], s[2 * w + 1], yl1, yh1);
+      olo[w] = pack_bf16(yl0, yl1);
+      ohi[w] = pack_bf16(yh0, yh1);
+    } else {
+      float ya, yb;
+      rot(bf_lo(lo[w]), bf_hi(lo[w]), c[w], s[w], ya, yb);
+      olo[w] = pack_bf16(ya, yb);
+      rot(bf_lo(hi[w]), bf_hi(hi[w]), c[4 + w], s[4 + w], ya, yb);
+      ohi[w] = pack_bf16(ya, yb);
+    }
+  }
+}
+
+template <bool NT>
+__device__ __forceinline__ void st16(u32x4* p, u32x4 v) {
+  if (NT) __builtin_nontemporal_store(v, p); else *p = v;
+}
+
+// ---------------------------------------------------------------------------------------------
+// per-workgroup staging
+// ---------------------------------------------------------------------------------------------
+
+struct GroupShared {
+  float   tab[kMaxGroup][2 * kHalf];  // cos[64], sin[64] of each agent of the group
+  int32_t pg0[kMaxGroup];             // physical page holding the master page's first token
+  int32_t pg1[kMaxGroup];             // the next logical page's physical page (or -1)
+  int32_t off[kMaxGroup];             // row of the first token inside pg0
+  int32_t aux[kMaxGroup];             // flag kernel: OR of the waves; decode: payload slot or -1
+  int32_t agent[kMaxGroup];
+};
+
+template <int T>
+__device__ __forceinline__ void stage_group(const RoundDev& rd, const WorkItem& w, GroupShared& sh) {
+  const int tid = threadIdx.x;
+  for (int i = tid; i < w.ag_count * 32; i += kBlock) {
+    const int g = i >> 5, q = i & 31;
+    const int a = rd.order[w.ag_begin + g];
+    reinterpret_cast<float4*>(sh.tab[g])[q] =
+        reinterpret_cast<const float4*>(rd.tab + (size_t)a * (2 * kHalf))[q];
+  }
+  if (tid < w.ag_count) {
+    const int a = rd.order[w.ag_begin + tid];
+    const AgentDev ad = rd.agents[a];
+    const int a0 = ad.pos0 + w.page * T;
+    const int lp = a0 / T - ad.lp_first;
+    sh.pg0[tid] = rd.bt[ad.bt_off + lp];
+    sh.pg1[tid] = (lp + 1 < ad.bt_len) ? rd.bt[ad.bt_off + lp + 1] : -1;
+    sh.off[tid] = a0 % T;
+    sh.aux[tid] = 0;
+    sh.agent[tid] = a;
+  }
+}
+
+// lane geometry inside a row of H heads x 128 bf16 (= H*16 chunks of 16 bytes)
+struct Lane {
+  int klo, khi;      // chunk index of this lane's low-half / high-half K chunk
+  int v0, v1;        // chunk indices of its two V chunks
+  bool kok, v0ok, v1ok;
+  int jb;            // which 8-element block of the half this lane rotates
+};
+
+__device__ __forceinline__ Lane lane_geometry(int H) {
+  const int lane = threadIdx.x & 63;
+  Lane L;
+  L.jb = lane & 7;
+  L.klo = (lane >> 3) * 16 + L.jb;
+  L.khi = L.klo + 8;
+  L.kok = (lane >> 3) < H;
+  L.v0 = lane;
+  L.v1 = lane + 64;
+  L.v0ok = L.v0 < H * 16;
+  L.v1ok = L.v1 < H * 16;
+  return L;
+}
+
+template <bool IL>
+__device__ __forceinline__ void load_tab(const GroupShared& sh, int g, int jb, float (&c)[8], float (&s)[8]) {
+  const float* t = sh.tab[g];
+  if (!IL) {
+#pragma unroll
+    for (int e = 0; e < 8; ++e) { c[e] = t[jb * 8 + e]; s[e] = t[kHalf + jb * 8 + e]; }
+  } else {
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      c[e] = t[jb * 4 + e];          s[e] = t[kHalf + jb * 4 + e];
+      c[4 + e] = t[32 + jb * 4 + e]; s[4 + e] = t[kHalf + 32 + jb * 4 + e];
+    }
+  }
+}
+
+template <int RPW>
+struct MasterRows {
+  u32x4 kl[RPW], kh[RPW], v0[RPW], v1[RPW];
+  bool  valid[RPW];
+};
+
+template <int RPW>
+__device__ __forceinline__ void load_master(const RoundDev& rd, const LayerDev& io, const WorkItem& w,
+                                            const Lane& L, MasterRows<RPW>& M) {
+  constexpr int T = RPW * kWaves;
+  const SessionDev sd = rd.sess[w.session];
+  const int wave = threadIdx.x >> 6;
+  const int64_t row_u4 = (int64_t)rd.heads * 16;
+#pragma unroll
+  for (int k = 0; k < RPW; ++k) {
+    const int m = w.page * T + wave + kWaves * k;
+    M.valid[k] = m < sd.span;
+    const u32x4 z = {0, 0, 0, 0};
+    M.kl[k] = z; M.kh[k] = z; M.v0[k] = z; M.v1[k] = z;
+    if (M.valid[k]) {
+      const u32x4* rk = io.master_k + (sd.master_row0 + m) * row_u4;
+      const u32x4* rv = io.master_v + (sd.master_row0 + m) * row_u4;
+      if (L.kok) { M.kl[k] = rk[L.klo]; M.kh[k] = rk[L.khi]; }
+      if (L.v0ok) M.v0[k] = rv[L.v0];
+      if (L.v1ok) M.v1[k] = rv[L.v1];
+    }
+  }
+}
+
+// physical pool row of row r (0..T-1) of the master page for agent g of the group
+template <int T>
+__device__ __forceinline__ int64_t dest_row(const GroupShared& sh, int g, int r) {
+  const int q = sh.off[g] + r;
+  const int pg = q < T ? sh.pg0[g] : sh.pg1[g];
+  return (int64_t)pg * T + (q & (T - 1));
+}
+
+// ---------------------------------------------------------------------------------------------
+// rerotate: pool_k <- bf16(R(delta_i) master_k), pool_v <- master_v       [Sec. 4.2]
+// ---------------------------------------------------------------------------------------------
+
+template <int RPW, bool IL, bool NT>
+__global__ __launch_bounds__(kBlock) void tdk_rerotate_kernel(const RoundDev rd, const LayerDev io) {
+  constexpr int T = RPW * kWaves;
+  __shared__ GroupShared sh;
+  const WorkItem w = rd.work[blockIdx.x];
+  const Lane L = lane_geometry(rd.heads);
+  stage_group<T>(rd, w, sh);
+  MasterRows<RPW> M;
+  load_master<RPW>(rd, io, w, L, M);
+  __syncthreads();
+  const int wave = threadIdx.x >> 6;
+  const int64_t row_u4 = (int64_t)rd.heads * 16;
+  u32x4* pk = io.pool_k;
+  u32x4* pv = io.pool_v;
+  for (int g = 0; g < w.ag_count; ++g) {
+    float c[8], s[8];
+    load_tab<IL>(sh, g, L.jb, c, s);
+#pragma unroll
+    for (int k = 0; k < RPW; ++k) {
+      if (!M.valid[k]) continue;
+      const int64_t base = dest_row<T>(sh, g, wave + kWaves * k) * row_u4;
+      if (L.kok) {
+        u32x4 olo, ohi;
+        rotate16<IL>(M.kl[k], M.kh[k], c, s, olo, ohi);
+        st16<NT>(pk + base + L.klo, olo);
+        st16<NT>(pk + base + L.khi, ohi);
+      }
+      if (L.v0ok) st16<NT>(pv + base + L.v0, M.v0[k]);
+      if (L.v1ok) st16<NT>(pv + base + L.v1, M.v1[k]);
+    }
+  }
+}
+
+// ---------------------------------------------------------------------------------------------
+// flag: per (agent, master page) compare against the re-rotated master     [Sec. 4.3]
+// ---------------------------------------------------------------------------------------------
+
+// differ <=> not (|a - ref| <= eps) in fp32; NaN on either side differs
+__device__ __forceinline__ bool word_differs(uint32_t a, uint32_t r, float eps) {
+  const bool lo = !(__builtin_fabsf(bf_lo(a) - bf_lo(r)) <= eps);
+  const bool hi = !(__builtin_fabsf(bf_hi(a) - bf_hi(r)) <= eps);
+  return lo | hi;
+}
+
+__device__ __forceinline__ bool chunk_differs(const u32x4 a, const u32x4 r, float eps) {
+  bool d = false;
+#pragma unroll
+  for (int w = 0; w < 4; ++w) d |= word_differs(a[w], r[w], eps);
+  return d;
+}
+
+template <int RPW, bool IL>
+__global__ __launch_bounds__(kBlock) void tdk_flag_kernel(const RoundDev rd, const LayerDev io, const float eps) {
+  constexpr int T = RPW * kWaves;
+  __shared__ GroupShared sh;
+  const WorkItem w = rd.work[blockIdx.x];
+  const Lane L = lane_geometry(rd.heads);
+  stage_group<T>(rd, w, sh);
+  MasterRows<RPW> M;
+  load_master<RPW>(rd, io, w, L, M);
+  __syncthreads();
+  const int wave = threadIdx.x >> 6;
+  const int64_t row_u4 = (int64_t)rd.heads * 16;
+  const u32x4* pk = io.pool_k;
+  const u32x4* pv = io.pool_v;
+  for (int g = 0; g < w.ag_count; ++g) {
+    float c[8], s[8];
+    load_tab<IL>(sh, g, L.jb, c, s);
+    u32x4 akl[RPW], akh[RPW], av0[RPW], av1[RPW];
+    const u32x4 z = {0, 0, 0, 0};
+#pragma unroll
+    for (int k = 0; k < RPW; ++k) {
+      akl[k] = z; akh[k] = z; av0[k] = z; av1[k] = z;
+      if (!M.valid[k]) continue;
+      const int64_t base = dest_row<T>(sh, g, wave + kWaves * k) * row_u4;
+      if (L.kok) { akl[k] = pk[base + L.klo]; akh[k] = pk[base + L.khi]; }
+      if (L.v0ok) av0[k] = pv[base + L.v0];
+      if (L.v1ok) av1[k] = pv[base + L.v1];
+    }
+    bool differs = false;
+#pragma unroll
+    for (int k = 0; k < RPW; ++k) {
+      if (!M.valid[k]) continue;
+      if (L.kok) {
+        u32x4 rlo, rhi;
+        rotate16<IL>(M.kl[k], M.kh[k], c, s, rlo, rhi);
+        differs |= chunk_differs(akl[k], rlo, eps) | chunk_differs(akh[k], rhi, eps);
+      }
+      if (L.v0ok) differs |= chunk_differs(av0[k], M.v0[k], eps);
+      if (L.v1ok) differs |= chunk_differs(av1[k], M.v1[k], eps);
+    }
+    if (__any(differs) && (threadIdx.x & 63) == 0) atomicOr(&sh.aux[g], 1);
+  }
+  __syncthreads();
+  if (threadIdx.x < w.ag_count) {
+    const AgentDev ad = rd.agents[sh.agent[threadIdx.x]];
+    rd.flags[ad.flag_off + w.page] = (uint8_t)sh.aux[threadIdx.x];
+  }
+}
+
+// ---------------------------------------------------------------------------------------------
+// compaction: count, exclusive prefix, ascending index list                [Sec. 5]
+// One wavefront per agent: ballot over 64 page flags at a time, popcount, prefix by lane mask.
+// ---------------------------------------------------------------------------------------------
+
+__global__ __launch_bounds__(kBlock) void tdk_count_kernel(const RoundDev rd, int32_t* __restrict__ count) {
+  const int a = blockIdx.x * kWaves + (threadIdx.x >> 6);
+  const int lane = threadIdx.x & 63;
+  if (a >= rd.n_agents) return;
+  const AgentDev ad = rd.agents[a];
+  const int P = rd.sess[ad.session].pages;
+  int n = 0;
+  for (int p0 = 0; p0 < P; p0 += 64) {
+    const int p = p0 + lane;
+    const bool f = p < P && rd.flags[ad.flag_off + p] != 0;
+    n += __popcll(__ballot(f));
+  }
+  if (lane == 0) count[a] = n;
+}
+
+__global__ __launch_bounds__(kBlock) void tdk_index_kernel(const RoundDev rd, const DiffDev d) {
+  const int a = blockIdx.x * kWaves + (threadIdx.x >> 6);
+  const int lane = threadIdx.x & 63;
+  if (rd.n_agents == 0) {
+    if (blockIdx.x == 0 && threadIdx.x == 0) { d.offset[0] = 0; d.overflow[0] = 0; }
+    return;
+  }
+  if (a >= rd.n_agents) return;
+  // exclusive prefix of the counts of all earlier agents
+  int64_t part = 0;
+  for (int b = lane; b < a; b += 64) part += d.count[b];
+#pragma unroll
+  for (int sft = 32; sft > 0; sft >>= 1) part += __shfl_xor(part, sft);
+  const int64_t base = part;
+  const AgentDev ad = rd.agents[a];
+  const int P = rd.sess[ad.session].pages;
+  if (lane == 0) {
+    d.offset[a] = base;
+    if (a == rd.n_agents - 1) {
+      const int64_t total = base + d.count[a];
+      d.offset[a + 1] = total;
+      d.overflow[0] = total > d.capacity ? 1 : 0;
+    }
+  }
+  int64_t run = base;
+  for (int p0 = 0; p0 < P; p0 += 64) {
+    const int p = p0 + lane;
+    const bool f = p < P && rd.flags[ad.flag_off + p] != 0;
+    const uint64_t b = __ballot(f);
+    const int rank = __popcll(b & ((1ull << lane) - 1ull));
+    if (f && run + rank < d.capacity) d.idx[run + rank] = p;
+    run += __popcll(b);
+  }
+}
+
+// ---------------------------------------------------------------------------------------------
+// gather: K/V values of the listed pages, as they sit in the agent's cache   [Sec. 5]
+// A workgroup copies one plane (K or V) of one payload slot; grid-stride over the slots that
+// exist, so the host never needs the count.
+// ---------------------------------------------------------------------------------------------
+
+__global__ __launch_bounds__(kBlock) void tdk_gather_kernel(const RoundDev rd, const LayerDev io, const DiffDev d) {
+  const int T = rd.page_tokens;
+  const int A = rd.n_agents;
+  if (A == 0) return;
+  int64_t total = d.offset[A];
+  if (total > d.capacity) total = d.capacity;
+  const int row_u4 = rd.heads * 16;
+  const int page_u4 = T * row_u4;
+  for (int64_t u = blockIdx.x; u < 2 * total; u += gridDim.x) {
+    const int64_t slot = u >> 1;
+    const int plane = (int)(u & 1);
+    // agent owning this slot: last a with offset[a] <= slot
+    int lo = 0, hi = A;
+    while (hi - lo > 1) {
+      const int mid = (lo + hi) >> 1;
+      if (d.offset[mid] <= slot) lo = mid; else hi = mid;
+    }
+    const AgentDev ad = rd.agents[lo];
+    const int S = rd.sess[ad.session].span;
+    const int p = d.idx[slot];
+    const u32x4* src = plane ? io.pool_v : io.pool_k;
+    u32x4* dst = d.payload + (slot * 2 + plane) * (int64_t)page_u4;
+    for (int i = threadIdx.x; i < page_u4; i += kBlock) {
+      const int r = i / row_u4, cc = i - r * row_u4;
+      const int m = p * T + r;
+      u32x4 v = {0, 0, 0, 0};
+      if (m < S) {
+        const int a0 = ad.pos0 + m;
+        const int pg = rd.bt[ad.bt_off + a0 / T - ad.lp_first];
+        v = src[((int64_t)pg * T + a0 % T) * row_u4 + cc];
+      }
+      dst[i] = v;
+    }
+  }
+}
+
+// ---------------------------------------------------------------------------------------------
+// decode: diff pages from the payload, all others from the re-rotated master   [Sec. 4.4, Alg. 1]
+// ---------------------------------------------------------------------------------------------
+
+template <int RPW, bool IL, bool NT>
+__global__ __launch_bounds__(kBlock) void tdk_decode_kernel(const RoundDev rd, const LayerDev io, const DiffDev d) {
+  constexpr int T = RPW * kWaves;
+  __shared__ GroupShared sh;
+  const WorkItem w = rd.work[blockIdx.x];
+  const Lane L = lane_geometry(rd.heads);
+  stage_group<T>(rd, w, sh);
+  MasterRows<RPW> M;
+  load_master<RPW>(rd, io, w, L, M);
+  if (threadIdx.x < w.ag_count) {
+    // skip-or-correct decision per block: is this page in the agent's index list?
+    const int a = rd.order[w.ag_begin + threadIdx.x];
+    int64_t lo = d.offset[a];
+    int64_t hi = lo + d.count[a];
+    if (lo < 0) lo = 0;
+    if (hi > d.capacity) hi = d.capacity;
+    int64_t slot = -1;
+    while (lo < hi) {
+      const int64_t mid = (lo + hi) >> 1;
+      const int v = d.idx[mid];
+      if (v == w.page) { slot = mid; break; }
+      if (v < w.page) lo = mid + 1; else hi = mid;
+    }
+    sh.aux[threadIdx.x] = (int32_t)slot;
+  }
+  __syncthreads();
+  const int wave = threadIdx.x >> 6;
+  const int64_t row_u4 = (int64_t)rd.heads * 16;
+  u32x4* pk = io.pool_k;
+  u32x4* pv = io.pool_v;
+  for (int g = 0; g < w.ag_count; ++g) {
+    const int slot = sh.aux[g];
+    if (slot >= 0) {
+      const u32x4* qk = d.payload + (int64_t)slot * 2 * T * row_u4;
+      const u32x4* qv = qk + T * row_u4;
+#pragma unroll
+      for (int k = 0; k < RPW; ++k) {
+        if (!M.valid[k]) continue;
+        const int r = wave + kWaves * k;
+        const int64_t base = dest_row<T>(sh, g, r) * row_u4;
+        if (L.kok) {
+          st16<NT>(pk + base + L.klo, qk[r * row_u4 + L.klo]);
+          st16<NT>(pk + base + L.khi, qk[r * row_u4 + L.khi]);
+        }
+        if (L.v0ok) st16<NT>(pv + base + L.v0, qv[r * row_u4 + L.v0]);
+        if (L.v1ok) st16<NT>(pv + base + L.v1, qv[r * row_u4 + L.v1]);
+      }
+    } else {
+      float c[8], s[8];
+      load_tab<IL>(sh, g, L.jb, c, s);
+#pragma unroll
+      for (int k = 0; k < RPW; ++k) {
+        if (!M.valid[k]) continue;
+        const int64_t base = dest_row<T>(sh, g, wave + kWaves * k) * row_u4;
+        if (L.kok) {
+          u32x4 olo, ohi;
+          rotate16<IL>(M.kl[k], M.kh[k], c, s, olo, ohi);
+          st16<NT>(pk + base + L.klo, olo);
+          st16<NT>(pk + base + L.khi, ohi);
+        }
+        if (L.v0ok) st16<NT>(pv + base + L.v0, M.v0[k]);
+        if (L.v1ok) st16<NT>(pv + base + L.v1, M.v1[k]);
+      }
+    }
+  }
+}
+
+// ---------------------------------------------------------------------------------------------
+// plain copy / fill (bandwidth ceiling and traffic-counter reference)
+// ---------------------------------------------------------------------------------------------
+
+__global__ __launch_bounds__(kBlock) void tdk_copy_kernel(u32x4* __restrict__ dst, const u32x4* __restrict__ src, size_t n) {
+  for (size_t i = (size_t)blockIdx.x * kBlock + threadIdx.x; i < n; i += (size_t)gridDim.x * kBlock) dst[i] = src[i];
+}
+
+__global__ __launch_bounds__(kBlock) void tdk_fill_kernel(u32x4* __restrict__ dst, uint32_t word, size_t n) {
+  const u32x4 v = {word, word, word, word};
+  for (size_t i = (size_t)blockIdx.x * kBlock + threadIdx.x; i < n; i += (size_t)gridDim.x * kBlock) dst[i] = v;
+}
+
+// ---------------------------------------------------------------------------------------------
+// launchers
+// ---------------------------------------------------------------------------------------------
+
+#define TDK_DISPATCH_RPW_IL(KERNEL, ...)                                                    \
+  do {                                                                                      \
+    const bool il = rd.interleaved != 0;                                                    \
+    if (rd.page_tokens == 16) {                                                             \
+      if (il) hipLaunchKernelGGL((KERNEL<4, true>), grid, dim3(kBlock), 0, st, __VA_ARGS__); \
+      else hipLaunchKernelGGL((KERNEL<4, false>), grid, dim3(kBlock), 0, st, __VA_ARGS__);   \
+    } else {                                                                                \
+      if (il) hipLaunchKernelGGL((KERNEL<8, true>), grid, dim3(kBlock), 0, st, __VA_ARGS__); \
+      else hipLaunchKernelGGL((KERNEL<8, false>), grid, dim3(kBlock), 0, st, __VA_ARGS__);   \
+    }                                                                                       \
+  } while (0)
+
+#define TDK_DISPATCH_RPW_IL_NT(KERNEL, ...)                                                          \
+  do {                                                                                               \
+    const bool il = rd.interleaved != 0;                                                             \
+    const bool nt = rd.nontemporal != 0;                                                             \
+    if (rd.page_tokens == 16) {                                                                      \
+      if (il) { if (nt) hipLaunchKernelGGL((KERNEL<4, true, true>), grid, dim3(kBlock), 0, st, __VA_ARGS__);   \
+                else hipLaunchKernelGGL((KERNEL<4, true, false>), grid, dim3(kBlock), 0, st, __VA_ARGS__); }   \
+      else    { if (nt) hipLaunchKernelGGL((KERNEL<4, false, true>), grid, dim3(kBlock), 0, st, __VA_ARGS__);  \
+                else hipLaunchKernelGGL((KERNEL<4, false, false>), grid, dim3(kBlock), 0, st, __VA_ARGS__); }  \
+    } else {                                                                                         \
+      if (il) { if (nt) hipLaunchKernelGGL((KERNEL<8, true, true>), grid, dim3(kBlock), 0, st, __VA_ARGS__);   \
+                else hipLaunchKernelGGL((KERNEL<8, true, false>), grid, dim3(kBlock), 0, st, __VA_ARGS__); }   \
+      else    { if (nt) hipLaunchKernelGGL((KERNEL<8, false, true>), grid, dim3(kBlock), 0, st, __VA_ARGS__);  \
+                else hipLaunchKernelGGL((KERNEL<8, false, false>), grid, dim3(kBlock), 0, st, __VA_ARGS__); }  \
+    }                                                                                                \
+  } while (0)
+
+hipError_t launch_rerotate(const RoundDev& rd, const LayerDev& io, hipStream_t st) {
+  if (rd.n_work == 0) return hipSuccess;
+  const dim3 grid(rd.n_work);
+  TDK_DISPATCH_RPW_IL_NT(tdk_rerotate_kernel, rd, io);
+  return hipGetLastError();
+}
+
+hipError_t launch_flag(const RoundDev& rd, const LayerDev& io, float eps, hipStream_t st) {
+  if (rd.n_work == 0) return hipSuccess;
+  const dim3 grid(rd.n_work);
+  TDK_DISPATCH_RPW_IL(tdk_flag_kernel, rd, io, eps);
+  return hipGetLastError();
+}
+
+hipError_t launch_count(const RoundDev& rd, const DiffDev& d, hipStream_t st) {
+  if (rd.n_agents == 0) return hipSuccess;
+  const dim3 grid((rd.n_agents + kWaves - 1) / kWaves);
+  hipLaunchKernelGGL(tdk_count_kernel, grid, dim3(kBlock), 0, st, rd, d.count);
+  return hipGetLastError();
+}
+
+hipError_t launch_index(const RoundDev& rd, const DiffDev& d, hipStream_t st) {
+  const dim3 grid(rd.n_agents ? (rd.n_agents + kWaves - 1) / kWaves : 1);
+  hipLaunchKernelGGL(tdk_index_kernel, grid, dim3(kBlock), 0, st, rd, d);
+  return hipGetLastError();
+}
+
+hipError_t launch_gather(const RoundDev& rd, const LayerDev& io, const DiffDev& d, int grid_size, hipStream_t st) {
+  if (rd.n_agents == 0 || d.capacity == 0 || grid_size <= 0) return hipSuccess;
+  hipLaunchKernelGGL(tdk_gather_kernel, dim3(grid_size), dim3(kBlock), 0, st, rd, io, d);
+  return hipGetLastError();
+}
+
+hipError_t launch_decode(const RoundDev& rd, const LayerDev& io, const DiffDev& d, hipStream_t st) {
+  if (rd.n_work == 0) return hipSuccess;
+  const dim3 grid(rd.n_work);
+  TDK_DISPATCH_RPW_IL_NT(tdk_decode_kernel, rd, io, d);
+  return hipGetLastError();
+}
+
+hipError_t launch_copy(u32x4* dst, const u32x4* src, size_t n16, hipStream_t st) {
+  if (n16 == 0) return hipSuccess;
+  size_t blocks = (n16 + kBlock - 1) / kBlock;
+  if (blocks > 256 * 32) blocks = 256 * 32;
+  hipLaunchKernelGGL(tdk_copy_kernel, dim3((unsigned)blocks), dim3(kBlock), 0, st,
+                     dst, src, n16);
+  return hipGetLastError();
+}
+
+hipError_t launch_fill(u32x4* dst, uint32_t word, size_t n16, hipStream_t st) {
+  if (n16 == 0) return hipSuccess;
+  size_t blocks = (n16 + kBlock - 1) / kBlock;
+  if (blocks > 256 * 32) blocks = 256 * 32;
+  hipLaunchKernelGGL(tdk_fill_kernel, dim3((unsigned)blocks), dim3(kBlock), 0, st,
+                     dst, word, n16);
+  return hipGetLastError();
+}
+
+}  // namespace tdk

@@ -1,0 +1,253 @@
+"""Thin ctypes binding over libtdk.so: same names as include/tdk.h, argument marshalling only.
+
+Device buffers are passed as anything with a ``data_ptr()`` (torch tensors) or as integer
+addresses; streams as integer ``hipStream_t`` handles (``torch.cuda.current_stream().cuda_stream``).
+There is no CPU fallback: if the library has not been built, loading fails.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import Optional, Sequence
+
+import numpy as np
+
+_PKG = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_PKG, "libtdk.so")
+
+OK, ERR_INVALID_ARG, ERR_UNSUPPORTED, ERR_CAPACITY, ERR_HIP, ERR_NOMEM = range(6)
+BF16 = 0
+ROPE_HALF, ROPE_INTERLEAVED = 0, 1
+KERNEL_REROTATE, KERNEL_FLAG, KERNEL_COUNT, KERNEL_INDEX, KERNEL_GATHER, KERNEL_DECODE = range(6)
+KERNEL_KINDS = 6
+
+EXPORTS = (
+    "tdk_status_str", "tdk_last_error", "tdk_version", "tdk_kernel_name",
+    "tdk_round_create", "tdk_round_destroy", "tdk_scratch_bytes", "tdk_round_tune",
+    "tdk_rerotate_round", "tdk_diff_encode", "tdk_diff_decode",
+    "tdk_timing_enable", "tdk_timing_read", "tdk_timing_reset",
+    "tdk_dense_bytes", "tdk_diff_bytes", "tdk_family_cost",
+    "tdk_util_copy", "tdk_util_fill",
+)
+
+
+class Model(C.Structure):
+    _fields_ = [("num_layers", C.c_int32), ("num_kv_heads", C.c_int32), ("head_dim", C.c_int32),
+                ("page_tokens", C.c_int32), ("dtype", C.c_int32), ("rope_style", C.c_int32),
+                ("rope_theta", C.c_double)]
+
+
+class Session(C.Structure):
+    _fields_ = [("span_tokens", C.c_int32), ("master_pos0", C.c_int64)]
+
+
+class Agent(C.Structure):
+    _fields_ = [("session", C.c_int32), ("dst_pos0", C.c_int64), ("block_table", C.c_void_p),
+                ("block_table_len", C.c_int32)]
+
+
+class LayerIO(C.Structure):
+    _fields_ = [("master_k", C.c_void_p), ("master_v", C.c_void_p), ("pool_k", C.c_void_p),
+                ("pool_v", C.c_void_p), ("pool_pages", C.c_int64)]
+
+
+class Diff(C.Structure):
+    _fields_ = [("count", C.c_void_p), ("offset", C.c_void_p), ("idx", C.c_void_p),
+                ("payload", C.c_void_p), ("capacity_pages", C.c_int64), ("overflow", C.c_void_p)]
+
+
+class TdkError(RuntimeError):
+    def __init__(self, status: int, what: str, detail: str):
+        super().__init__(f"{what}: status {status} ({detail})")
+        self.status = status
+        self.detail = detail
+
+
+_lib: Optional[C.CDLL] = None
+
+
+def load() -> C.CDLL:
+    """Loads the built library; raises if it is missing (build it with __graft_entry__.build())."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise FileNotFoundError(
+            f"{LIB_PATH} is not built; run `python -c 'import __graft_entry__ as g; g.build()'`")
+    L = C.CDLL(LIB_PATH)
+    L.tdk_status_str.restype = C.c_char_p
+    L.tdk_status_str.argtypes = [C.c_int]
+    L.tdk_last_error.restype = C.c_char_p
+    L.tdk_version.restype = C.c_char_p
+    L.tdk_kernel_name.restype = C.c_char_p
+    L.tdk_kernel_name.argtypes = [C.c_int32]
+    L.tdk_round_create.argtypes = [C.POINTER(Model), C.POINTER(Session), C.c_int32, C.POINTER(Agent),
+                                   C.c_int32, C.POINTER(C.c_void_p)]
+    L.tdk_round_destroy.argtypes = [C.c_void_p]
+    L.tdk_round_destroy.restype = None
+    L.tdk_scratch_bytes.argtypes = [C.c_void_p]
+    L.tdk_scratch_bytes.restype = C.c_size_t
+    L.tdk_round_tune.argtypes = [C.c_void_p, C.c_int32, C.c_int32]
+    L.tdk_rerotate_round.argtypes = [C.c_void_p, C.c_int32, C.POINTER(LayerIO), C.c_void_p]
+    L.tdk_diff_encode.argtypes = [C.c_void_p, C.c_int32, C.POINTER(LayerIO), C.c_float, C.POINTER(Diff), C.c_void_p]
+    L.tdk_diff_decode.argtypes = [C.c_void_p, C.c_int32, C.POINTER(LayerIO), C.POINTER(Diff), C.c_void_p]
+    L.tdk_timing_enable.argtypes = [C.c_void_p, C.c_int32]
+    L.tdk_timing_read.argtypes = [C.c_void_p, C.c_int32, C.POINTER(C.c_double), C.POINTER(C.c_int64)]
+    L.tdk_timing_reset.argtypes = [C.c_void_p]
+    for name in ("tdk_dense_bytes", "tdk_diff_bytes", "tdk_family_cost"):
+        getattr(L, name).restype = C.c_double
+    L.tdk_dense_bytes.argtypes = [C.POINTER(Model), C.c_int64]
+    L.tdk_diff_bytes.argtypes = [C.POINTER(Model), C.c_int64]
+    L.tdk_family_cost.argtypes = [C.c_int64, C.c_double]
+    L.tdk_util_copy.argtypes = [C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
+    L.tdk_util_fill.argtypes = [C.c_void_p, C.c_uint32, C.c_size_t, C.c_void_p]
+    _lib = L
+    return L
+
+
+def _ptr(x) -> Optional[int]:
+    if x is None:
+        return None
+    if hasattr(x, "data_ptr"):
+        return int(x.data_ptr())
+    return int(x)
+
+
+def _check(status: int, what: str) -> None:
+    if status != OK:
+        raise TdkError(status, what, load().tdk_last_error().decode())
+
+
+def tdk_status_str(status: int) -> str:
+    return load().tdk_status_str(status).decode()
+
+
+def tdk_last_error() -> str:
+    return load().tdk_last_error().decode()
+
+
+def tdk_version() -> str:
+    return load().tdk_version().decode()
+
+
+def tdk_kernel_name(kernel: int) -> str:
+    return load().tdk_kernel_name(kernel).decode()
+
+
+def model(num_layers, num_kv_heads=8, head_dim=128, page_tokens=16, rope_theta=1.0e6,
+          rope_style=ROPE_HALF, dtype=BF16) -> Model:
+    return Model(num_layers, num_kv_heads, head_dim, page_tokens, dtype, rope_style, float(rope_theta))
+
+
+class Round:
+    """Owns a tdk_round handle."""
+
+    def __init__(self, handle: int, n_agents: int, keep):
+        self.handle = C.c_void_p(handle)
+        self.n_agents = n_agents
+        self._keep = keep
+
+    def destroy(self) -> None:
+        if self.handle:
+            load().tdk_round_destroy(self.handle)
+            self.handle = C.c_void_p(None)
+
+    def __del__(self):
+        try:
+            self.destroy()
+        except Exception:
+            pass
+
+
+def tdk_round_create(mdl: Model, span_tokens: Sequence[int], master_pos0: Sequence[int],
+                     agent_session: Sequence[int], agent_pos0: Sequence[int],
+                     block_tables: Sequence[np.ndarray]) -> Round:
+    ns, na = len(span_tokens), len(agent_session)
+    sess = (Session * max(ns, 1))()
+    for s in range(ns):
+        sess[s] = Session(int(span_tokens[s]), int(master_pos0[s]))
+    ags = (Agent * max(na, 1))()
+    keep = []
+    for i in range(na):
+        bt = np.ascontiguousarray(block_tables[i], dtype=np.int32)
+        keep.append(bt)
+        ags[i] = Agent(int(agent_session[i]), int(agent_pos0[i]), bt.ctypes.data, len(bt))
+    out = C.c_void_p()
+    _check(load().tdk_round_create(C.byref(mdl), sess, ns, ags, na, C.byref(out)), "tdk_round_create")
+    return Round(out.value, na, None)
+
+
+def round_from_workload(rnd, style=ROPE_HALF) -> Round:
+    """Convenience: a tdk round for a workload.Round (marshalling only)."""
+    sp = rnd.spec
+    mdl = model(sp.num_layers, sp.num_kv_heads, sp.head_dim, sp.page_tokens, sp.rope_theta, style)
+    return tdk_round_create(mdl, rnd.span_tokens, rnd.master_pos0, rnd.agent_session, rnd.agent_pos0,
+                            rnd.block_tables)
+
+
+def tdk_round_destroy(r: Round) -> None:
+    r.destroy()
+
+
+def tdk_scratch_bytes(r: Round) -> int:
+    return int(load().tdk_scratch_bytes(r.handle))
+
+
+def tdk_round_tune(r: Round, agents_per_group: int = 0, flags: int = 1) -> None:
+    _check(load().tdk_round_tune(r.handle, agents_per_group, flags), "tdk_round_tune")
+
+
+def layer_io(master_k, master_v, pool_k, pool_v, pool_pages: int) -> LayerIO:
+    return LayerIO(_ptr(master_k), _ptr(master_v), _ptr(pool_k), _ptr(pool_v), int(pool_pages))
+
+
+def diff(count, offset, idx, payload, capacity_pages: int, overflow) -> Diff:
+    return Diff(_ptr(count), _ptr(offset), _ptr(idx), _ptr(payload), int(capacity_pages), _ptr(overflow))
+
+
+def tdk_rerotate_round(r: Round, layer: int, io: LayerIO, stream: int = 0) -> None:
+    _check(load().tdk_rerotate_round(r.handle, layer, C.byref(io), C.c_void_p(stream)), "tdk_rerotate_round")
+
+
+def tdk_diff_encode(r: Round, layer: int, io: LayerIO, eps: float, out: Diff, stream: int = 0) -> None:
+    _check(load().tdk_diff_encode(r.handle, layer, C.byref(io), C.c_float(eps), C.byref(out),
+                                  C.c_void_p(stream)), "tdk_diff_encode")
+
+
+def tdk_diff_decode(r: Round, layer: int, io: LayerIO, d: Diff, stream: int = 0) -> None:
+    _check(load().tdk_diff_decode(r.handle, layer, C.byref(io), C.byref(d), C.c_void_p(stream)),
+           "tdk_diff_decode")
+
+
+def tdk_timing_enable(r: Round, on: bool) -> None:
+    _check(load().tdk_timing_enable(r.handle, 1 if on else 0), "tdk_timing_enable")
+
+
+def tdk_timing_read(r: Round, kernel: int):
+    ms, n = C.c_double(), C.c_int64()
+    _check(load().tdk_timing_read(r.handle, kernel, C.byref(ms), C.byref(n)), "tdk_timing_read")
+    return ms.value, n.value
+
+
+def tdk_timing_reset(r: Round) -> None:
+    _check(load().tdk_timing_reset(r.handle), "tdk_timing_reset")
+
+
+def tdk_dense_bytes(mdl: Model, span_tokens: int) -> float:
+    return load().tdk_dense_bytes(C.byref(mdl), int(span_tokens))
+
+
+def tdk_diff_bytes(mdl: Model, pages: int) -> float:
+    return load().tdk_diff_bytes(C.byref(mdl), int(pages))
+
+
+def tdk_family_cost(n_agents: int, ratio: float) -> float:
+    return load().tdk_family_cost(int(n_agents), float(ratio))
+
+
+def tdk_util_copy(dst, src, nbytes: int, stream: int = 0) -> None:
+    _check(load().tdk_util_copy(_ptr(dst), _ptr(src), int(nbytes), C.c_void_p(stream)), "tdk_util_copy")
+
+
+def tdk_util_fill(dst, word: int, nbytes: int, stream: int = 0) -> None:
+    _check(load().tdk_util_fill(_ptr(dst), int(word) & 0xFFFFFFFF, int(nbytes), C.c_void_p(stream)), "tdk_util_fill")

@@ -244,3 +244,53 @@ def shared_row_mask(rnd: Round) -> np.ndarray:
     for i in range(rnd.n_agents):
         mask[rnd.dst_rows(i)] = True
     return mask
+
+
+# ---------------------------------------------------------------------------
+# device-side generators for rounds too large to draw on the host (torch is used for random
+# numbers and indexing only; still no method arithmetic)
+# ---------------------------------------------------------------------------
+
+def master_device(rnd: Round, layer: int, device="cuda"):
+    """Master K, V ~ N(0,1) in bf16 on the device, as int16 bit-pattern tensors [rows, H*D]."""
+    import torch
+    spec = rnd.spec
+    g = torch.Generator(device=device)
+    g.manual_seed(SEED_BASE * 1000 + spec.stream * 100003 + layer)
+    shape = (rnd.total_master_rows, spec.row_elems)
+    k = torch.randn(shape, generator=g, device=device, dtype=torch.float32).to(torch.bfloat16)
+    v = torch.randn(shape, generator=g, device=device, dtype=torch.float32).to(torch.bfloat16)
+    return k.view(torch.int16), v.view(torch.int16)
+
+
+def perturbed_rows(rnd: Round) -> np.ndarray:
+    """Physical pool rows of every valid token of every perturbed page (int64, all agents)."""
+    T = rnd.spec.page_tokens
+    out = []
+    for i in range(rnd.n_agents):
+        S = int(rnd.span_tokens[rnd.agent_session[i]])
+        if len(rnd.perturbed[i]) == 0:
+            continue
+        toks = (rnd.perturbed[i].astype(np.int64)[:, None] * T + np.arange(T, dtype=np.int64)[None, :]).ravel()
+        toks = toks[toks < S]
+        out.append(rnd.dst_rows(i, toks))
+    return np.concatenate(out) if out else np.zeros(0, np.int64)
+
+
+def perturb_device(rnd: Round, layer: int, pool_k, pool_v, rows=None) -> None:
+    """Device version of perturb_host: x <- bf16(fp32(x) + N(0, sigma)) on the perturbed pages."""
+    import torch
+    spec = rnd.spec
+    if rows is None:
+        rows = torch.from_numpy(perturbed_rows(rnd)).to(pool_k.device)
+    if rows.numel() == 0:
+        return
+    g = torch.Generator(device=pool_k.device)
+    g.manual_seed(SEED_BASE * 1000 + spec.stream * 100003 + 50000 + layer)
+    for plane in (pool_k, pool_v):
+        chunk = 16384
+        for c0 in range(0, rows.numel(), chunk):
+            r = rows[c0:c0 + chunk]
+            x = plane[r].view(torch.bfloat16).float()
+            n = torch.randn(x.shape, generator=g, device=x.device, dtype=torch.float32) * spec.noise_sigma
+            plane[r] = (x + n).to(torch.bfloat16).view(torch.int16)

@@ -1,0 +1,288 @@
+"""Parity of the HIP path (through the C ABI) with the CPU oracle, element by element, on the same
+seeded inputs.  Bar: bit-exact for counts, offsets, indices, payload and V; K bit-exact by design
+(same fp32 operation order), which is inside the stated 4e-3 max-abs-error bar."""
+import numpy as np
+import pytest
+
+from paper_2604_03143_amd import workload as wl
+from helpers import OracleRun, lists_of
+
+pytestmark = pytest.mark.gpu
+
+K_TOL = 4e-3
+
+
+def _gpu():
+    import torch
+    if not torch.cuda.is_available():
+        pytest.fail("GPU tests need a GPU (run with -m 'not gpu' on a CPU box)")
+    from paper_2604_03143_amd import tdk
+    tdk.load()
+    import gpu_helpers
+    return gpu_helpers
+
+
+def _k_report(got, ref):
+    """(bf16 mismatches, max abs error) of two bf16 bit arrays."""
+    mism = int(np.count_nonzero(got != ref))
+    err = float(np.max(np.abs(wl.bf16_bits_to_f32(got) - wl.bf16_bits_to_f32(ref)))) if got.size else 0.0
+    return mism, err
+
+
+def spec_of(name="edge", H=8, T=16, theta=1.0e6, sessions=1, agents=3, blocks=2, block_tokens=40,
+            hist=(0, 100), frac=0.2, stream=77):
+    return wl.RoundSpec(name, stream, 2, H, 128, T, theta, sessions, agents, blocks, block_tokens,
+                        hist[0], hist[1], frac)
+
+
+def run_pipeline(tdo, rnd, style=0, group=0, flags=1, eps=None, layer=0):
+    """rerotate -> perturb -> encode -> decode on both sides; every stage compared bit for bit."""
+    gh = _gpu()
+    o = OracleRun(tdo, rnd, layer=layer, style=style)
+    g = gh.GpuRun(rnd, layer=layer, style=style, group=group, flags=flags)
+    try:
+        o.rerotate()
+        g.rerotate()
+        gk, gv = g.pool()
+        mism, err = _k_report(gk, o.pk)
+        assert err <= K_TOL and mism == 0, (mism, err)
+        assert np.array_equal(gv, o.pv)
+
+        o.perturb()
+        g.set_pool(o.pk, o.pv)
+        od = o.encode(eps=eps)
+        gd = g.encode(eps=eps)
+        gh.assert_diff_equal(gd, od, rnd.n_agents)
+
+        fresh_k, fresh_v = wl.pool_host(rnd, layer)
+        g.set_pool(fresh_k, fresh_v)
+        g.decode(gd)
+        dk, dv = g.pool()
+        ok, ov = fresh_k.copy(), fresh_v.copy()
+        o.decode(od, ok, ov)
+        assert np.array_equal(dk, ok) and np.array_equal(dv, ov)
+        return o, od
+    finally:
+        g.close()
+
+
+def test_tiny_config_pipeline(tdo):
+    rnd = wl.make_round(wl.CONFIGS["tiny"])
+    o, od = run_pipeline(tdo, rnd)
+    for i, lst in enumerate(lists_of(od, rnd.n_agents)):
+        assert np.array_equal(lst, rnd.perturbed[i])
+
+
+@pytest.mark.parametrize("h", [0, 1, 15, 16, 17])
+def test_unaligned_history_and_ragged_tail(tdo, h):
+    spec = spec_of(agents=2, blocks=1, block_tokens=72, hist=(h, h))   # 4.5 pages: tail of 8 rows
+    rnd = wl.make_round(spec)
+    run_pipeline(tdo, rnd)
+
+
+@pytest.mark.parametrize("H", [1, 4, 8])
+def test_kv_head_counts(tdo, H):
+    run_pipeline(tdo, wl.make_round(spec_of(H=H)))
+
+
+def test_pages_of_32_tokens(tdo):
+    run_pipeline(tdo, wl.make_round(spec_of(T=32, block_tokens=100, hist=(0, 200))))
+
+
+@pytest.mark.parametrize("T", [16, 32])
+def test_interleaved_rope(tdo, T):
+    run_pipeline(tdo, wl.make_round(spec_of(T=T)), style=1)
+
+
+def test_theta_5e5_and_large_positions(tdo):
+    run_pipeline(tdo, wl.make_round(spec_of(theta=5.0e5, hist=(18000, 33600))))
+
+
+@pytest.mark.parametrize("group,flags", [(1, 1), (2, 0), (5, 1), (32, 0)])
+def test_launch_shapes_give_identical_results(tdo, group, flags):
+    rnd = wl.make_round(spec_of(sessions=3, agents=7, blocks=3, block_tokens=50))
+    run_pipeline(tdo, rnd, group=group, flags=flags)
+
+
+def test_more_agents_than_one_group(tdo):
+    run_pipeline(tdo, wl.make_round(spec_of(agents=70, blocks=1, block_tokens=50, frac=0.3)))
+
+
+def test_sessions_with_different_spans_and_master_offsets(tdo):
+    gh = _gpu()
+    spec = spec_of(sessions=3, agents=2)
+    rnd = wl.make_round(spec)
+    # rebuild with unequal spans and non-zero master positions
+    spans = np.array([80, 33, 16], np.int32)
+    rnd.span_tokens = spans
+    rnd.master_pos0 = np.array([0, 7, 1000], np.int64)
+    rnd.master_row0 = np.concatenate([[0], np.cumsum(spans)]).astype(np.int64)
+    rnd.agent_pos0 = np.array([5, 90, 7, 40, 1000, 2001], np.int64)
+    rnd.perturbed = [np.array([1], np.int32), np.array([0, 4], np.int32), np.array([2], np.int32),
+                     np.zeros(0, np.int32), np.array([0], np.int32), np.zeros(0, np.int32)]
+    T = 16
+    page = 0
+    tables = []
+    for i in range(6):
+        n = int((rnd.agent_pos0[i] + spans[rnd.agent_session[i]] - 1) // T + 1)
+        bt = np.zeros(n, np.int32)
+        first = int(rnd.agent_pos0[i] // T)
+        bt[first:] = np.arange(page + 1, page + 1 + n - first)
+        page += n - first
+        tables.append(bt)
+    rnd.block_tables = tables
+    rnd.pool_pages = page + 2
+    rnd.dummy_page = 0
+    o, od = run_pipeline(tdo, rnd)
+    for i, lst in enumerate(lists_of(od, 6)):
+        assert np.array_equal(lst, rnd.perturbed[i])
+
+
+def test_empty_round_and_empty_span(tdo):
+    gh = _gpu()
+    import torch
+    from paper_2604_03143_amd import tdk
+    r = tdk.tdk_round_create(tdk.model(1), [], [], [], [], [])
+    io = tdk.layer_io(None, None, None, None, 0)
+    tdk.tdk_rerotate_round(r, 0, io)
+    d = gh.DevDiff(0, 0, 16)
+    tdk.tdk_diff_encode(r, 0, io, 0.01, d.c)
+    tdk.tdk_diff_decode(r, 0, io, d.c)
+    torch.cuda.synchronize()
+    assert int(d.offset.cpu()[0]) == 0 and int(d.overflow.item()) == 0
+    r.destroy()
+    # two agents on a session whose span is empty
+    r = tdk.tdk_round_create(tdk.model(1), [0], [0], [0, 0], [3, 9], [np.zeros(1, np.int32)] * 2)
+    d = gh.DevDiff(2, 4, 2 * 16 * 1024)
+    tdk.tdk_rerotate_round(r, 0, io)
+    tdk.tdk_diff_encode(r, 0, io, 0.01, d.c)
+    tdk.tdk_diff_decode(r, 0, io, d.c)
+    torch.cuda.synchronize()
+    assert d.count.cpu().tolist() == [0, 0] and d.offset.cpu().tolist() == [0, 0, 0]
+    r.destroy()
+
+
+def test_threshold_cases_on_one_page(tdo):
+    """Strict threshold in fp32, NaN and signed zero: decisions identical to the oracle's."""
+    gh = _gpu()
+    spec = spec_of(agents=1, blocks=1, block_tokens=16, hist=(3, 3))
+    rnd = wl.make_round(spec)
+    mk, mv = wl.master_host(rnd, 0)
+    mk[:] = 0
+    mv[:] = 0x3F80
+    o = OracleRun(tdo, rnd)
+    o.mk[:] = mk; o.mv[:] = mv
+    o.rerotate()
+    g = gh.GpuRun(rnd, mk=mk, mv=mv)
+    row = int(rnd.dst_rows(0, np.array([5]))[0])
+    cases = [("k", 0x3BFF, 2.0 ** -7), ("k", 0x3C00, 2.0 ** -7), ("k", 0x3C01, 2.0 ** -7), ("k", 0xBC01, 2.0 ** -7),
+             ("v", 0x3F81, 2.0 ** -7), ("v", 0x3F82, 2.0 ** -7), ("v", 0x3F7E, 2.0 ** -7), ("v", 0x3F7C, 2.0 ** -7),
+             ("k", 0x3C23, 1e-2), ("k", 0x3C24, 1e-2), ("k", 0x8000, 0.0), ("k", 0x7FC0, 1e30), ("v", 0x7F80, 1e30),
+             ("k", 0x0001, 0.0)]
+    try:
+        for plane, bits, eps in cases:
+            pk, pv = o.pk.copy(), o.pv.copy()
+            (pk if plane == "k" else pv)[row, 517] = bits
+            exp = tdo.diff_encode(o.g, o.hr, o.mk, o.mv, pk, pv, eps, 1)
+            g.set_pool(pk, pv)
+            gd = g.encode(eps=eps, capacity=1)
+            gh.assert_diff_equal(gd, exp, 1)
+    finally:
+        g.close()
+
+
+def test_capacity_overflow_keeps_counts_and_guards(tdo):
+    gh = _gpu()
+    rnd = wl.make_round(spec_of(agents=4, blocks=1, block_tokens=64))
+    o = OracleRun(tdo, rnd)          # pool bits unrelated to the master: all 4 pages of all agents differ
+    g = gh.GpuRun(rnd)
+    try:
+        for cap in (0, 5, 16, 17):
+            od = o.encode(capacity=cap)
+            gd = g.encode(capacity=cap)
+            gh.assert_diff_equal(gd, od, rnd.n_agents)
+            assert int(gd.overflow.item()) == (1 if cap < 16 else 0)
+    finally:
+        g.close()
+
+
+def test_decode_empty_diff_equals_rerotate_and_is_idempotent(tdo):
+    gh = _gpu()
+    rnd = wl.make_round(spec_of(agents=5))
+    g = gh.GpuRun(rnd)
+    try:
+        g.rerotate()
+        a_k, a_v = g.pool()
+        d = g.encode()
+        assert int(d.offset.cpu()[-1]) == 0
+        fk, fv = wl.pool_host(rnd, 0)
+        g.set_pool(fk, fv)
+        g.decode(d)
+        b_k, b_v = g.pool()
+        assert np.array_equal(a_k, b_k) and np.array_equal(a_v, b_v)
+        g.decode(d)
+        c_k, c_v = g.pool()
+        assert np.array_equal(a_k, c_k) and np.array_equal(a_v, c_v)
+    finally:
+        g.close()
+
+
+def test_own_pipeline_recovers_seeded_set_and_roundtrips(tdo):
+    """Each side's siblings come from its own rerotate output; ground truth is the seeded page set."""
+    gh = _gpu()
+    import torch
+    rnd = wl.make_round(spec_of(sessions=2, agents=9, blocks=4, block_tokens=75, frac=0.1))
+    g = gh.GpuRun(rnd)
+    try:
+        g.rerotate()
+        wl.perturb_device(rnd, 0, g.pk, g.pv)
+        want_k, want_v = g.pool()
+        d = g.encode()
+        cnt, off, idx, pay, ovf = d.host(rnd.n_agents)
+        for i in range(rnd.n_agents):
+            assert np.array_equal(idx[off[i]:off[i + 1]], rnd.perturbed[i])
+        fk, fv = wl.pool_host(rnd, 0)
+        g.set_pool(fk, fv)
+        g.decode(d)
+        got_k, got_v = g.pool()
+        mask = wl.shared_row_mask(rnd)
+        assert np.array_equal(got_k[mask], want_k[mask]) and np.array_equal(got_v[mask], want_v[mask])
+        assert np.array_equal(got_k[~mask], fk[~mask]) and np.array_equal(got_v[~mask], fv[~mask])
+    finally:
+        g.close()
+
+
+def test_step_argument_errors(tdo):
+    gh = _gpu()
+    from paper_2604_03143_amd import tdk
+    rnd = wl.make_round(spec_of(agents=2))
+    g = gh.GpuRun(rnd)
+    try:
+        with pytest.raises(tdk.TdkError) as e:
+            tdk.tdk_rerotate_round(g.r, 2, g.io)
+        assert e.value.status == tdk.ERR_INVALID_ARG
+        with pytest.raises(tdk.TdkError) as e:
+            tdk.tdk_rerotate_round(g.r, 0, tdk.layer_io(g.mk, g.mv, g.pk, g.pv, 3))
+        assert e.value.status == tdk.ERR_INVALID_ARG and "pool_pages" in e.value.detail
+        with pytest.raises(tdk.TdkError):
+            tdk.tdk_rerotate_round(g.r, 0, tdk.layer_io(None, g.mv, g.pk, g.pv, rnd.pool_pages))
+        d = g.new_diff()
+        for eps in (-1.0, float("nan"), float("inf")):
+            with pytest.raises(tdk.TdkError):
+                tdk.tdk_diff_encode(g.r, 0, g.io, eps, d.c)
+        bad = tdk.diff(d.count, d.offset, None, d.payload, 4, d.overflow)
+        with pytest.raises(tdk.TdkError):
+            tdk.tdk_diff_encode(g.r, 0, g.io, 0.01, bad)
+        with pytest.raises(tdk.TdkError):
+            tdk.tdk_round_tune(g.r, 33, 1)
+        assert tdk.tdk_scratch_bytes(g.r) > 0
+    finally:
+        g.close()
+
+
+def test_session_config_layer0_full_oracle(tdo):
+    """The 25-agent Qwen2.5-14B-shaped session, one layer, oracle on everything."""
+    rnd = wl.make_round(wl.CONFIGS["session"])
+    o, od = run_pipeline(tdo, rnd)
+    for i, lst in enumerate(lists_of(od, rnd.n_agents)):
+        assert np.array_equal(lst, rnd.perturbed[i])
