@@ -1,0 +1,296 @@
+#!/usr/bin/env python3
+"""Benchmark of the collective KV-reuse hot path on one MI355X.
+
+A step is one pass of the whole path over one round: for every layer, tdk_rerotate_round (collect the
+shared blocks for all agents), tdk_diff_decode (restore every mirror from master + diff) and
+tdk_diff_encode (store every mirror as a block-sparse diff again).  Inputs are synthetic, seeded and
+resident in HBM before the timed region.  One JSON line is printed.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0   # MI355X published HBM3E bandwidth
+ROW_PAIR_BYTES = 4096    # K + V of one token at one layer (8 heads x 128 x bf16 x 2)
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=5)
+    ap.add_argument("--warmup", type=int, default=1)
+    ap.add_argument("--workload", default="batched250")
+    ap.add_argument("--ring", type=int, default=0, help="resident layer buffers (0 = automatic)")
+    ap.add_argument("--group", type=int, default=0, help="agents per work item (0 = automatic)")
+    ap.add_argument("--flags", type=int, default=0, help="bit 0: non-temporal pool stores")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-check", action="store_true")
+    ap.add_argument("--layers", type=int, default=0, help="override the layer count (for profiling runs only)")
+    return ap.parse_args()
+
+
+def main():
+    args = parse()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this path runs on one GPU only (every session, layer and KV head is independent; "
+              "no multi-GPU figure is produced).  Use --gpus 1.", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    from paper_2604_03143_amd import tdk, workload as wl
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(1)
+    tdk.load()   # fails loudly if the HIP library is not built
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    stream = torch.cuda.current_stream().cuda_stream
+
+    spec = wl.CONFIGS[args.workload]
+    L = args.layers or spec.num_layers
+    rnd = wl.make_round(spec)
+    A, T, RE = rnd.n_agents, spec.page_tokens, spec.row_elems
+    pool_rows = rnd.pool_pages * T
+    n_pert = sum(len(p) for p in rnd.perturbed)
+    capacity = n_pert + 64
+    page_elems = 2 * T * RE
+
+    per_slot = (2 * rnd.total_master_rows * RE + 2 * pool_rows * RE + 2 * capacity * page_elems) * 2
+    free_b, total_b = torch.cuda.mem_get_info()
+    ring = args.ring or int(max(1, min(L, 8, (0.8 * free_b) // per_slot)))
+    ring = min(ring, L)
+
+    r = tdk.round_from_workload(rnd)
+    if args.group or args.flags != 0:
+        tdk.tdk_round_tune(r, args.group, args.flags)
+
+    def new_diff():
+        d = dict(count=torch.zeros(A, dtype=torch.int32, device=dev),
+                 offset=torch.zeros(A + 1, dtype=torch.int64, device=dev),
+                 idx=torch.full((capacity,), -1, dtype=torch.int32, device=dev),
+                 payload=torch.zeros((capacity, page_elems), dtype=torch.int16, device=dev),
+                 overflow=torch.zeros(1, dtype=torch.int32, device=dev))
+        d["c"] = tdk.diff(d["count"], d["offset"], d["idx"], d["payload"], capacity, d["overflow"])
+        return d
+
+    # ---- resident inputs: a ring of layer buffers, each with its own data -------------------------
+    pert_rows = torch.from_numpy(wl.perturbed_rows(rnd)).to(dev)
+    slots = []
+    for s in range(ring):
+        mk, mv = wl.master_device(rnd, s, dev)
+        pk = torch.zeros((pool_rows, RE), dtype=torch.int16, device=dev)
+        pv = torch.zeros((pool_rows, RE), dtype=torch.int16, device=dev)
+        io = tdk.layer_io(mk, mv, pk, pv, rnd.pool_pages)
+        stored, fresh = new_diff(), new_diff()
+        # the mirrors this round stores: this side's own rerotate output, refreshed on the seeded pages
+        tdk.tdk_rerotate_round(r, s, io, stream)
+        wl.perturb_device(rnd, s, pk, pv, rows=pert_rows)
+        tdk.tdk_diff_encode(r, s, io, spec.eps, stored["c"], stream)
+        slots.append(dict(mk=mk, mv=mv, pk=pk, pv=pv, io=io, stored=stored, fresh=fresh))
+    torch.cuda.synchronize()
+    for s in slots:
+        assert int(s["stored"]["overflow"].item()) == 0
+        assert int(s["stored"]["offset"][-1].item()) == n_pert, "encode did not recover the seeded page set"
+
+    def step():
+        for layer in range(L):
+            s = slots[layer % ring]
+            tdk.tdk_rerotate_round(r, layer, s["io"], stream)
+            tdk.tdk_diff_decode(r, layer, s["io"], s["stored"]["c"], stream)
+            tdk.tdk_diff_encode(r, layer, s["io"], spec.eps, s["fresh"]["c"], stream)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    tdk.tdk_timing_reset(r)
+    tdk.tdk_timing_enable(r, True)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    tdk.tdk_timing_enable(r, False)
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+    agent_tokens = rnd.agent_tokens()
+    value = agent_tokens / (ms_per_step * 1e-3)
+
+    # ---- per-kernel durations (HIP events on the launch stream, recorded inside the timed region) ---
+    kt = {}
+    for k in range(tdk.KERNEL_KINDS):
+        ms, n = tdk.tdk_timing_read(r, k)
+        kt[tdk.tdk_kernel_name(k)] = dict(total_ms=ms, launches=n, avg_us=(ms / n * 1e3 if n else 0.0))
+
+    # ---- algorithmic bytes per layer-step ----------------------------------------------------------
+    master_b = sum(int(s) for s in rnd.span_tokens) * ROW_PAIR_BYTES
+    agents_b = agent_tokens * ROW_PAIR_BYTES
+    payload_b = n_pert * page_elems * 2
+    meta_b = 4 * n_pert + 12 * A
+    alg = dict(rerotate=master_b + agents_b,
+               flag=master_b + agents_b,
+               encode=master_b + agents_b + payload_b + meta_b,
+               decode=master_b + agents_b + payload_b + meta_b)
+
+    def gbps(nbytes, us):
+        return nbytes / (us * 1e-6) / 1e9 if us > 0 else 0.0
+
+    us = {k.replace("tdk_", "").replace("_kernel", ""): v["avg_us"] for k, v in kt.items()}
+    enc_us = us["flag"] + us["count"] + us["index"] + us["gather"]
+    dec_us = us["decode"] + us["scatter"]
+    rates = dict(rerotate_GBps=gbps(alg["rerotate"], us["rerotate"]),
+                 encode_GBps=gbps(alg["encode"], enc_us),
+                 decode_GBps=gbps(alg["decode"], dec_us),
+                 encode_decode_GBps=gbps(alg["encode"] + alg["decode"], enc_us + dec_us))
+    dom = max(("rerotate", "flag", "decode"), key=lambda k: kt[f"tdk_{k}_kernel"]["total_ms"])
+    achieved = gbps(alg[dom], us[dom])
+    traffic = None
+    tpath = os.path.join(ROOT, "profiles", "traffic.json")
+    if os.path.exists(tpath):
+        try:
+            traffic = json.load(open(tpath)).get(args.workload, {}).get(f"tdk_{dom}_kernel")
+        except Exception:
+            traffic = None
+    roofline = dict(bound="hbm", kernel=f"tdk_{dom}_kernel", achieved=round(achieved, 1), peak=HBM_PEAK_GBPS,
+                    unit="GB/s", frac=round(achieved / HBM_PEAK_GBPS, 4), traffic=traffic,
+                    algorithmic_bytes_per_launch=alg[dom], avg_launch_us=round(us[dom], 2))
+
+    # ---- plain copy ceiling on this machine -----------------------------------------------------------
+    n_copy = 1 << 31
+    src = torch.empty(n_copy, dtype=torch.uint8, device=dev)
+    dst = torch.empty(n_copy, dtype=torch.uint8, device=dev)
+    tdk.tdk_util_fill(src, 0x01020304, n_copy, stream)
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    tdk.tdk_util_copy(dst, src, n_copy, stream)
+    e0.record()
+    for _ in range(5):
+        tdk.tdk_util_copy(dst, src, n_copy, stream)
+    e1.record()
+    torch.cuda.synchronize()
+    copy_gbps = 2 * n_copy * 5 / (e0.elapsed_time(e1) * 1e-3) / 1e9
+    del src, dst
+
+    # ---- correctness at full size, outside the timed region ---------------------------------------
+    check = {}
+    if not args.no_check:
+        ok = True
+        for s in slots:
+            a, b = s["stored"], s["fresh"]
+            ok &= bool(torch.equal(a["count"], b["count"]) and torch.equal(a["offset"], b["offset"]))
+            ok &= bool(torch.equal(a["idx"][:n_pert], b["idx"][:n_pert]))
+            ok &= bool(torch.equal(a["payload"][:n_pert], b["payload"][:n_pert]))
+            ok &= int(b["overflow"].item()) == 0
+        off = slots[0]["fresh"]["offset"].cpu().numpy()
+        idx = slots[0]["fresh"]["idx"].cpu().numpy()
+        seeded = all(np.array_equal(idx[off[i]:off[i + 1]], rnd.perturbed[i]) for i in range(A))
+        check = dict(reencode_equals_stored_diff=ok, indices_equal_seeded_set=bool(seeded))
+
+    cpu = None
+    if not args.no_cpu_baseline:
+        cpu, par = cpu_baseline(rnd, slots[0], r, stream, L, tdk, wl, np, torch)
+        check.update(par)
+
+    out = dict(metric="shared-KV tokens collected/sec per round; diff encode+decode GB/s (% HBM peak)",
+               value=round(value, 1), unit="tokens/s", n_gpus=1, steps=args.steps, warmup=args.warmup,
+               ms_per_step=round(ms_per_step, 3), higher_is_better=True, scaling="weak", vs_baseline=None,
+               dtype="bf16", data="synthetic",
+               config=dict(workload=args.workload, layers=L, agents=A, sessions=rnd.n_sessions,
+                           span_tokens=int(spec.span_tokens), page_tokens=T, perturbed_pages=n_pert,
+                           ring_layers=ring, agents_per_group="auto" if not args.group else args.group,
+                           step="rerotate+decode+encode per layer, all layers"),
+               roofline=roofline, cpu_baseline=cpu,
+               rates={k: round(v, 1) for k, v in rates.items()},
+               pct_hbm_peak={k.replace("_GBps", ""): round(100 * v / HBM_PEAK_GBPS, 2) for k, v in rates.items()},
+               copy_ceiling_GBps=round(copy_gbps, 1),
+               tokens_per_s_rerotate_only=round(agent_tokens / (us["rerotate"] * 1e-6 * L), 1) if us["rerotate"] else None,
+               kernels={k: dict(avg_us=round(v["avg_us"], 2), launches=v["launches"]) for k, v in kt.items()},
+               check=check)
+    print(json.dumps(out))
+    r.destroy()
+
+
+def cpu_baseline(rnd, slot, r, stream, L, tdk, wl, np, torch):
+    """The CPU oracle as it stands, on one session of layer 0 (the first 25 agents): one layer-step
+    (rerotate + decode + encode).  Also serves as the full-size parity sample."""
+    from oracle import tdo
+    spec = rnd.spec
+    T, RE = spec.page_tokens, spec.row_elems
+    n = min(rnd.n_agents, spec.agents_per_session)
+    sub, page_map = wl.subround(rnd, range(n))
+    rows = (torch.from_numpy(page_map).to(slot["pk"].device)[:, None] * T +
+            torch.arange(T, device=slot["pk"].device)[None, :]).reshape(-1)
+
+    def pool_sample():
+        torch.cuda.synchronize()
+        return (slot["pk"][rows].cpu().numpy().view(np.uint16), slot["pv"][rows].cpu().numpy().view(np.uint16))
+
+    sess = sub.extra["sessions"]
+    r0, r1 = int(rnd.master_row0[sess[0]]), int(rnd.master_row0[sess[-1] + 1])
+    mk = slot["mk"][r0:r1].cpu().numpy().view(np.uint16)
+    mv = slot["mv"][r0:r1].cpu().numpy().view(np.uint16)
+    g = tdo.geom_of(spec)
+    hr = tdo.HostRound(sub)
+    cap = n * spec.span_pages
+
+    # state after the timed steps: the pool holds the restored (perturbed) mirrors
+    mir_k, mir_v = pool_sample()
+    gd = slot["fresh"]
+    off = gd["offset"].cpu().numpy()
+    cnt = gd["count"].cpu().numpy()
+
+    t = {}
+    ok, ov = mir_k.copy(), mir_v.copy()
+    t0 = time.perf_counter()
+    tdo.rerotate_round(g, hr, mk, mv, ok, ov)
+    t["rerotate"] = time.perf_counter() - t0
+    tdk.tdk_rerotate_round(r, 0, slot["io"], stream)
+    gk, gv = pool_sample()
+    shared = wl.shared_row_mask(sub)
+    par = dict(sample_rerotate_bitexact=bool(np.array_equal(gk[shared], ok[shared]) and np.array_equal(gv[shared], ov[shared])))
+
+    t0 = time.perf_counter()
+    od = tdo.diff_encode(g, hr, mk, mv, mir_k, mir_v, spec.eps, cap)
+    t["encode"] = time.perf_counter() - t0
+    m = int(od.offset[-1])
+    par["sample_encode_bitexact"] = bool(
+        np.array_equal(od.count, cnt[:n]) and np.array_equal(od.offset, off[:n + 1] - off[0]) and
+        np.array_equal(od.idx[:m], gd["idx"][int(off[0]):int(off[0]) + m].cpu().numpy()) and
+        np.array_equal(od.payload[:m], gd["payload"][int(off[0]):int(off[0]) + m].cpu().numpy().view(np.uint16)))
+
+    dk, dv = ok.copy(), ov.copy()
+    t0 = time.perf_counter()
+    tdo.diff_decode(g, hr, mk, mv, dk, dv, od)
+    t["decode"] = time.perf_counter() - t0
+    tdk.tdk_diff_decode(r, 0, slot["io"], slot["stored"]["c"], stream)
+    gk, gv = pool_sample()
+    par["sample_decode_bitexact"] = bool(np.array_equal(gk[shared], dk[shared]) and np.array_equal(gv[shared], dv[shared]))
+
+    # repeat the timed trio until about 10 s of CPU work are spent
+    reps, spent = 1, sum(t.values())
+    while spent < 10.0 and reps < 8:
+        t0 = time.perf_counter()
+        tdo.rerotate_round(g, hr, mk, mv, ok, ov)
+        tdo.diff_encode(g, hr, mk, mv, mir_k, mir_v, spec.eps, cap)
+        tdo.diff_decode(g, hr, mk, mv, dk, dv, od)
+        spent += time.perf_counter() - t0
+        reps += 1
+    layer_step_s = spent / reps
+    toks = sub.agent_tokens()
+    cpu = dict(value=round(toks / (layer_step_s * L), 1), unit="tokens/s", cores=tdo.max_threads(), kind="oracle",
+               sample=f"layer 0, session 0 ({n} agents x {int(sub.span_tokens[0])} tokens): rerotate+encode+decode, "
+                      f"{reps} repetitions, {spent:.1f} s; scaled to {L} layers",
+               layer_step_s=round(layer_step_s, 3),
+               first_rep_s={k: round(v, 3) for k, v in t.items()})
+    return cpu, par
+
+
+if __name__ == "__main__":
+    main()

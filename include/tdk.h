@@ -100,7 +100,7 @@ void       tdk_round_destroy(tdk_round* r);             /* NULL-safe */
 size_t     tdk_scratch_bytes(const tdk_round* r);       /* device bytes the round owns */
 
 /* Launch shape: agents of one session that share one read of a master page (1..32), 0 = automatic.
- * flags bit 0: use non-temporal stores for pool writes. */
+ * flags bit 0: use non-temporal stores for pool writes (default off: measured slower on MI355X). */
 tdk_status tdk_round_tune(tdk_round* r, int32_t agents_per_group, int32_t flags);
 
 /* Per-layer views, all DEV.
@@ -157,7 +157,8 @@ tdk_status tdk_diff_decode(tdk_round* r, int32_t layer, const tdk_layer_io* io, 
 #define TDK_KERNEL_INDEX    3
 #define TDK_KERNEL_GATHER   4
 #define TDK_KERNEL_DECODE   5
-#define TDK_KERNEL_KINDS    6
+#define TDK_KERNEL_SCATTER  6
+#define TDK_KERNEL_KINDS    7
 tdk_status tdk_timing_enable(tdk_round* r, int32_t on);
 tdk_status tdk_timing_read(tdk_round* r, int32_t kernel, double* total_ms, int64_t* launches);
 tdk_status tdk_timing_reset(tdk_round* r);

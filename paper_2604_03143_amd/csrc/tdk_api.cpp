@@ -49,7 +49,7 @@ struct tdk_round {
   int64_t total_pages = 0;         // sum over agents of their session's page count
   int64_t total_master_pages = 0;  // sum over sessions of pages
   int32_t group = 0;               // agents per work item (resolved)
-  int32_t flags = 1;
+  int32_t flags = 0;
 
   void*  blob = nullptr;           // one device allocation for everything below
   size_t blob_bytes = 0;
@@ -264,6 +264,7 @@ const char* tdk_kernel_name(int32_t kernel) {
     case TDK_KERNEL_INDEX: return "tdk_index_kernel";
     case TDK_KERNEL_GATHER: return "tdk_gather_kernel";
     case TDK_KERNEL_DECODE: return "tdk_decode_kernel";
+    case TDK_KERNEL_SCATTER: return "tdk_scatter_kernel";
   }
   return "";
 }
@@ -449,7 +450,7 @@ tdk_status tdk_diff_encode(tdk_round* r, int32_t layer, const tdk_layer_io* io, 
   TDK_LAUNCH(r, TDK_KERNEL_INDEX, s, launch_index(r->rd, d, s));
   // the number of listed pages is known on the device only: a fixed grid strides over them
   const int64_t units = 2 * std::min<int64_t>(out->capacity_pages, r->total_pages);
-  const int grid = (int)std::min<int64_t>(units, 256 * 16);
+  const int grid = (int)std::min<int64_t>(units, 1 << 20);
   TDK_LAUNCH(r, TDK_KERNEL_GATHER, s, launch_gather(r->rd, l, d, grid, s));
   return TDK_OK;
 }
@@ -461,7 +462,12 @@ tdk_status tdk_diff_decode(tdk_round* r, int32_t layer, const tdk_layer_io* io, 
   st = check_diff(r, in, false);
   if (st != TDK_OK) return st;
   hipStream_t s = static_cast<hipStream_t>(hip_stream);
-  TDK_LAUNCH(r, TDK_KERNEL_DECODE, s, launch_decode(r->rd, layer_dev(io), diff_dev(in), s));
+  const LayerDev l = layer_dev(io);
+  const DiffDev d = diff_dev(in);
+  TDK_LAUNCH(r, TDK_KERNEL_DECODE, s, launch_decode(r->rd, l, d, s));
+  const int64_t units = 2 * std::min<int64_t>(in->capacity_pages, r->total_pages);
+  const int grid = (int)std::min<int64_t>(units, 1 << 20);
+  TDK_LAUNCH(r, TDK_KERNEL_SCATTER, s, launch_scatter(r->rd, l, d, grid, s));
   return TDK_OK;
 }
 

@@ -78,6 +78,7 @@ hipError_t launch_count(const RoundDev& rd, const DiffDev& d, hipStream_t st);
 hipError_t launch_index(const RoundDev& rd, const DiffDev& d, hipStream_t st);
 hipError_t launch_gather(const RoundDev& rd, const LayerDev& io, const DiffDev& d, int grid, hipStream_t st);
 hipError_t launch_decode(const RoundDev& rd, const LayerDev& io, const DiffDev& d, hipStream_t st);
+hipError_t launch_scatter(const RoundDev& rd, const LayerDev& io, const DiffDev& d, int grid, hipStream_t st);
 hipError_t launch_copy(u32x4* dst, const u32x4* src, size_t n16, hipStream_t st);
 hipError_t launch_fill(u32x4* dst, uint32_t word, size_t n16, hipStream_t st);
 

@@ -232,6 +232,22 @@ __device__ __forceinline__ bool chunk_differs(const u32x4 a, const u32x4 r, floa
   return d;
 }
 
+__device__ __forceinline__ uint32_t chunk_xor(const u32x4 a, const u32x4 r) {
+  const u32x4 x = a ^ r;
+  return x[0] | x[1] | x[2] | x[3];
+}
+
+// true if some bf16 in the chunk is non-finite or so large (|x| >= 2^126) that a rotation could
+// overflow: only then can a reference that is bit-identical to the agent's value still "differ"
+// (|inf - inf| and NaN compare false), so such rows always take the full fp32 compare.
+__device__ __forceinline__ bool chunk_special(const u32x4 m) {
+  bool sp = false;
+#pragma unroll
+  for (int w = 0; w < 4; ++w)
+    sp |= ((m[w] & 0x7f80u) >= 0x7e80u) | ((m[w] & 0x7f800000u) >= 0x7e800000u);
+  return sp;
+}
+
 template <int RPW, bool IL>
 __global__ __launch_bounds__(kBlock) void tdk_flag_kernel(const RoundDev rd, const LayerDev io, const float eps) {
   constexpr int T = RPW * kWaves;
@@ -241,6 +257,10 @@ __global__ __launch_bounds__(kBlock) void tdk_flag_kernel(const RoundDev rd, con
   stage_group<T>(rd, w, sh);
   MasterRows<RPW> M;
   load_master<RPW>(rd, io, w, L, M);
+  bool special[RPW];
+#pragma unroll
+  for (int k = 0; k < RPW; ++k)
+    special[k] = chunk_special(M.kl[k]) | chunk_special(M.kh[k]) | chunk_special(M.v0[k]) | chunk_special(M.v1[k]);
   __syncthreads();
   const int wave = threadIdx.x >> 6;
   const int64_t row_u4 = (int64_t)rd.heads * 16;
@@ -264,13 +284,16 @@ __global__ __launch_bounds__(kBlock) void tdk_flag_kernel(const RoundDev rd, con
 #pragma unroll
     for (int k = 0; k < RPW; ++k) {
       if (!M.valid[k]) continue;
-      if (L.kok) {
-        u32x4 rlo, rhi;
-        rotate16<IL>(M.kl[k], M.kh[k], c, s, rlo, rhi);
-        differs |= chunk_differs(akl[k], rlo, eps) | chunk_differs(akh[k], rhi, eps);
+      u32x4 rlo = z, rhi = z;
+      if (L.kok) rotate16<IL>(M.kl[k], M.kh[k], c, s, rlo, rhi);
+      // rows whose bits all match the reference (the common case) need no fp32 compare
+      uint32_t x = chunk_xor(av0[k], M.v0[k]) | chunk_xor(av1[k], M.v1[k]);
+      if (L.kok) x |= chunk_xor(akl[k], rlo) | chunk_xor(akh[k], rhi);
+      if (__any((x != 0) | special[k])) {
+        if (L.kok) differs |= chunk_differs(akl[k], rlo, eps) | chunk_differs(akh[k], rhi, eps);
+        if (L.v0ok) differs |= chunk_differs(av0[k], M.v0[k], eps);
+        if (L.v1ok) differs |= chunk_differs(av1[k], M.v1[k], eps);
       }
-      if (L.v0ok) differs |= chunk_differs(av0[k], M.v0[k], eps);
-      if (L.v1ok) differs |= chunk_differs(av1[k], M.v1[k], eps);
     }
     if (__any(differs) && (threadIdx.x & 63) == 0) atomicOr(&sh.aux[g], 1);
   }
@@ -413,37 +436,57 @@ __global__ __launch_bounds__(kBlock) void tdk_decode_kernel(const RoundDev rd, c
   u32x4* pk = io.pool_k;
   u32x4* pv = io.pool_v;
   for (int g = 0; g < w.ag_count; ++g) {
-    const int slot = sh.aux[g];
-    if (slot >= 0) {
-      const u32x4* qk = d.payload + (int64_t)slot * 2 * T * row_u4;
-      const u32x4* qv = qk + T * row_u4;
+    if (sh.aux[g] >= 0) continue;   // listed in the diff: the scatter kernel writes this page
+    float c[8], s[8];
+    load_tab<IL>(sh, g, L.jb, c, s);
 #pragma unroll
-      for (int k = 0; k < RPW; ++k) {
-        if (!M.valid[k]) continue;
-        const int r = wave + kWaves * k;
-        const int64_t base = dest_row<T>(sh, g, r) * row_u4;
-        if (L.kok) {
-          st16<NT>(pk + base + L.klo, qk[r * row_u4 + L.klo]);
-          st16<NT>(pk + base + L.khi, qk[r * row_u4 + L.khi]);
-        }
-        if (L.v0ok) st16<NT>(pv + base + L.v0, qv[r * row_u4 + L.v0]);
-        if (L.v1ok) st16<NT>(pv + base + L.v1, qv[r * row_u4 + L.v1]);
+    for (int k = 0; k < RPW; ++k) {
+      if (!M.valid[k]) continue;
+      const int64_t base = dest_row<T>(sh, g, wave + kWaves * k) * row_u4;
+      if (L.kok) {
+        u32x4 olo, ohi;
+        rotate16<IL>(M.kl[k], M.kh[k], c, s, olo, ohi);
+        st16<NT>(pk + base + L.klo, olo);
+        st16<NT>(pk + base + L.khi, ohi);
       }
-    } else {
-      float c[8], s[8];
-      load_tab<IL>(sh, g, L.jb, c, s);
-#pragma unroll
-      for (int k = 0; k < RPW; ++k) {
-        if (!M.valid[k]) continue;
-        const int64_t base = dest_row<T>(sh, g, wave + kWaves * k) * row_u4;
-        if (L.kok) {
-          u32x4 olo, ohi;
-          rotate16<IL>(M.kl[k], M.kh[k], c, s, olo, ohi);
-          st16<NT>(pk + base + L.klo, olo);
-          st16<NT>(pk + base + L.khi, ohi);
-        }
-        if (L.v0ok) st16<NT>(pv + base + L.v0, M.v0[k]);
-        if (L.v1ok) st16<NT>(pv + base + L.v1, M.v1[k]);
+      if (L.v0ok) st16<NT>(pv + base + L.v0, M.v0[k]);
+      if (L.v1ok) st16<NT>(pv + base + L.v1, M.v1[k]);
+    }
+  }
+}
+
+// The "correct" half of skip-or-correct: pages listed in a diff are copied from the payload to the
+// agent's rows (the mirror image of the gather kernel).  Every pool row is written exactly once by
+// either this kernel or the page kernel above, so their order does not matter.
+__global__ __launch_bounds__(kBlock) void tdk_scatter_kernel(const RoundDev rd, const LayerDev io, const DiffDev d) {
+  const int T = rd.page_tokens;
+  const int A = rd.n_agents;
+  if (A == 0) return;
+  int64_t total = d.offset[A];
+  if (total > d.capacity) total = d.capacity;
+  const int row_u4 = rd.heads * 16;
+  const int page_u4 = T * row_u4;
+  for (int64_t u = blockIdx.x; u < 2 * total; u += gridDim.x) {
+    const int64_t slot = u >> 1;
+    const int plane = (int)(u & 1);
+    int lo = 0, hi = A;
+    while (hi - lo > 1) {
+      const int mid = (lo + hi) >> 1;
+      if (d.offset[mid] <= slot) lo = mid; else hi = mid;
+    }
+    const AgentDev ad = rd.agents[lo];
+    const SessionDev sd = rd.sess[ad.session];
+    const int p = d.idx[slot];
+    if (p < 0 || p >= sd.pages) continue;   // not an index this round could have produced
+    u32x4* dst = plane ? io.pool_v : io.pool_k;
+    const u32x4* src = d.payload + (slot * 2 + plane) * (int64_t)page_u4;
+    for (int i = threadIdx.x; i < page_u4; i += kBlock) {
+      const int r = i / row_u4, cc = i - r * row_u4;
+      const int m = p * T + r;
+      if (m < sd.span) {
+        const int a0 = ad.pos0 + m;
+        const int pg = rd.bt[ad.bt_off + a0 / T - ad.lp_first];
+        dst[((int64_t)pg * T + a0 % T) * row_u4 + cc] = src[i];
       }
     }
   }
@@ -532,6 +575,12 @@ hipError_t launch_decode(const RoundDev& rd, const LayerDev& io, const DiffDev& 
   if (rd.n_work == 0) return hipSuccess;
   const dim3 grid(rd.n_work);
   TDK_DISPATCH_RPW_IL_NT(tdk_decode_kernel, rd, io, d);
+  return hipGetLastError();
+}
+
+hipError_t launch_scatter(const RoundDev& rd, const LayerDev& io, const DiffDev& d, int grid_size, hipStream_t st) {
+  if (rd.n_agents == 0 || d.capacity == 0 || grid_size <= 0) return hipSuccess;
+  hipLaunchKernelGGL(tdk_scatter_kernel, dim3(grid_size), dim3(kBlock), 0, st, rd, io, d);
   return hipGetLastError();
 }
 

@@ -18,8 +18,8 @@ LIB_PATH = os.path.join(_PKG, "libtdk.so")
 OK, ERR_INVALID_ARG, ERR_UNSUPPORTED, ERR_CAPACITY, ERR_HIP, ERR_NOMEM = range(6)
 BF16 = 0
 ROPE_HALF, ROPE_INTERLEAVED = 0, 1
-KERNEL_REROTATE, KERNEL_FLAG, KERNEL_COUNT, KERNEL_INDEX, KERNEL_GATHER, KERNEL_DECODE = range(6)
-KERNEL_KINDS = 6
+KERNEL_REROTATE, KERNEL_FLAG, KERNEL_COUNT, KERNEL_INDEX, KERNEL_GATHER, KERNEL_DECODE, KERNEL_SCATTER = range(7)
+KERNEL_KINDS = 7
 
 EXPORTS = (
     "tdk_status_str", "tdk_last_error", "tdk_version", "tdk_kernel_name",
@@ -193,7 +193,7 @@ def tdk_scratch_bytes(r: Round) -> int:
     return int(load().tdk_scratch_bytes(r.handle))
 
 
-def tdk_round_tune(r: Round, agents_per_group: int = 0, flags: int = 1) -> None:
+def tdk_round_tune(r: Round, agents_per_group: int = 0, flags: int = 0) -> None:
     _check(load().tdk_round_tune(r.handle, agents_per_group, flags), "tdk_round_tune")
 
 

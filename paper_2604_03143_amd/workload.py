@@ -294,3 +294,32 @@ def perturb_device(rnd: Round, layer: int, pool_k, pool_v, rows=None) -> None:
             x = plane[r].view(torch.bfloat16).float()
             n = torch.randn(x.shape, generator=g, device=x.device, dtype=torch.float32) * spec.noise_sigma
             plane[r] = (x + n).to(torch.bfloat16).view(torch.int16)
+
+
+def subround(rnd: Round, agents) -> "tuple[Round, np.ndarray]":
+    """The sessions and block tables of a few agents, remapped onto a compact pool.
+
+    Returns (sub, page_map) where page_map[q] is the page of `rnd`'s pool that page q of the compact
+    pool stands for (page 0 of the compact pool is the dummy page).  Structure only."""
+    agents = [int(a) for a in agents]
+    T = rnd.spec.page_tokens
+    sess_ids = sorted({int(rnd.agent_session[a]) for a in agents})
+    smap = {s: k for k, s in enumerate(sess_ids)}
+    span = rnd.span_tokens[sess_ids].astype(np.int32)
+    page_map = [rnd.dummy_page]
+    tables = []
+    for a in agents:
+        bt = rnd.block_tables[a]
+        first = int(rnd.agent_pos0[a]) // T
+        nb = np.zeros(len(bt), dtype=np.int32)
+        for lp in range(first, len(bt)):
+            nb[lp] = len(page_map)
+            page_map.append(int(bt[lp]))
+        tables.append(nb)
+    sub = Round(rnd.spec, span, rnd.master_pos0[sess_ids].astype(np.int64),
+                np.concatenate([[0], np.cumsum(span, dtype=np.int64)]).astype(np.int64),
+                np.array([smap[int(rnd.agent_session[a])] for a in agents], dtype=np.int32),
+                rnd.agent_pos0[agents].astype(np.int64), tables, len(page_map), 0,
+                np.zeros(0, np.int32), [rnd.perturbed[a] for a in agents],
+                extra={"sessions": sess_ids, "agents": agents})
+    return sub, np.array(page_map, dtype=np.int64)

@@ -35,7 +35,7 @@ def spec_of(name="edge", H=8, T=16, theta=1.0e6, sessions=1, agents=3, blocks=2,
                         hist[0], hist[1], frac)
 
 
-def run_pipeline(tdo, rnd, style=0, group=0, flags=1, eps=None, layer=0):
+def run_pipeline(tdo, rnd, style=0, group=0, flags=0, eps=None, layer=0):
     """rerotate -> perturb -> encode -> decode on both sides; every stage compared bit for bit."""
     gh = _gpu()
     o = OracleRun(tdo, rnd, layer=layer, style=style)
@@ -187,6 +187,43 @@ def test_threshold_cases_on_one_page(tdo):
             g.set_pool(pk, pv)
             gd = g.encode(eps=eps, capacity=1)
             gh.assert_diff_equal(gd, exp, 1)
+    finally:
+        g.close()
+
+
+def test_non_finite_and_huge_master_values(tdo):
+    """Inf, NaN and near-overflow values in the master: a reference that is bit-identical to the agent's
+    value still differs when it is not finite (|inf - inf| and NaN never compare <= eps)."""
+    gh = _gpu()
+    spec = spec_of(agents=2, blocks=1, block_tokens=48, hist=(3, 21))
+    rnd = wl.make_round(spec)
+    mk, mv = wl.master_host(rnd, 0)
+    big = 0x7F7F                      # largest finite bf16: two of them rotate to +-inf in fp32
+    mk[2, 5] = 0x7F80                 # +inf in K (page 0)
+    mk[20, 64 + 9] = 0x7FC0           # NaN in K (page 1)
+    mk[40, 130] = big; mk[40, 130 + 64] = big    # finite, but the rotation overflows (page 2)
+    mv[3, 7] = 0xFF80                 # -inf in V (page 0)
+    o = OracleRun(tdo, rnd)
+    o.mk[:] = mk; o.mv[:] = mv
+    o.rerotate()
+    g = gh.GpuRun(rnd, mk=mk, mv=mv)
+    try:
+        g.rerotate()
+        gk, gv = g.pool()
+        # NaNs may carry different payload bits on the two sides: compare NaN-ness there, bits elsewhere
+        of, gf = wl.bf16_bits_to_f32(o.pk), wl.bf16_bits_to_f32(gk)
+        nan = np.isnan(of)
+        assert np.array_equal(np.isnan(gf), nan)
+        assert np.array_equal(gk[~nan], o.pk[~nan]) and np.array_equal(gv, o.pv)
+        for eps in (0.0, 1e-2, 1e30):
+            od = o.encode(eps=eps)
+            g.set_pool(o.pk, o.pv)
+            gd = g.encode(eps=eps)
+            cnt, off, idx, pay, ovf = gd.host(2)
+            assert np.array_equal(cnt, od.count) and np.array_equal(off, od.offset)
+            n = int(od.offset[-1])
+            assert np.array_equal(idx[:n], od.idx[:n]) and np.array_equal(pay[:n], od.payload[:n])
+            assert n >= 4          # the pages holding inf / NaN / overflow are listed for both agents
     finally:
         g.close()
 
