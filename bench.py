@@ -135,10 +135,12 @@ def main():
     agents_b = agent_tokens * ROW_PAIR_BYTES
     payload_b = n_pert * page_elems * 2
     meta_b = 4 * n_pert + 12 * A
+    # per call (the three ABI steps) and per page kernel (what that one launch must move)
     alg = dict(rerotate=master_b + agents_b,
-               flag=master_b + agents_b,
                encode=master_b + agents_b + payload_b + meta_b,
-               decode=master_b + agents_b + payload_b + meta_b)
+               decode=master_b + agents_b + payload_b + meta_b,
+               flag=master_b + agents_b,                  # kernel: reads every agent page + the master
+               decode_kernel=master_b + agents_b - payload_b)   # kernel: writes every page not in a diff
 
     def gbps(nbytes, us):
         return nbytes / (us * 1e-6) / 1e9 if us > 0 else 0.0
@@ -151,17 +153,12 @@ def main():
                  decode_GBps=gbps(alg["decode"], dec_us),
                  encode_decode_GBps=gbps(alg["encode"] + alg["decode"], enc_us + dec_us))
     dom = max(("rerotate", "flag", "decode"), key=lambda k: kt[f"tdk_{k}_kernel"]["total_ms"])
-    achieved = gbps(alg[dom], us[dom])
-    traffic = None
-    tpath = os.path.join(ROOT, "profiles", "traffic.json")
-    if os.path.exists(tpath):
-        try:
-            traffic = json.load(open(tpath)).get(args.workload, {}).get(f"tdk_{dom}_kernel")
-        except Exception:
-            traffic = None
+    dom_bytes = alg["decode_kernel"] if dom == "decode" else alg[dom]
+    achieved = gbps(dom_bytes, us[dom])
+    traffic = read_traffic(args.workload, f"tdk_{dom}_kernel")
     roofline = dict(bound="hbm", kernel=f"tdk_{dom}_kernel", achieved=round(achieved, 1), peak=HBM_PEAK_GBPS,
                     unit="GB/s", frac=round(achieved / HBM_PEAK_GBPS, 4), traffic=traffic,
-                    algorithmic_bytes_per_launch=alg[dom], avg_launch_us=round(us[dom], 2))
+                    algorithmic_bytes_per_launch=dom_bytes, avg_launch_us=round(us[dom], 2))
 
     # ---- plain copy ceiling on this machine -----------------------------------------------------------
     n_copy = 1 << 31
@@ -215,6 +212,19 @@ def main():
                check=check)
     print(json.dumps(out))
     r.destroy()
+
+
+def read_traffic(workload, kernel):
+    """HBM bytes per launch of `kernel` from the committed rocprofv3 counter summary (None if absent)."""
+    path = os.path.join(ROOT, "profiles", f"hbm_traffic_{workload}.txt")
+    try:
+        for line in open(path):
+            f = line.split()
+            if len(f) == 4 and f[0] == kernel:
+                return float(f[3])
+    except OSError:
+        pass
+    return None
 
 
 def cpu_baseline(rnd, slot, r, stream, L, tdk, wl, np, torch):
@@ -275,7 +285,7 @@ def cpu_baseline(rnd, slot, r, stream, L, tdk, wl, np, torch):
 
     # repeat the timed trio until about 10 s of CPU work are spent
     reps, spent = 1, sum(t.values())
-    while spent < 10.0 and reps < 8:
+    while spent < 12.0 and reps < 400:
         t0 = time.perf_counter()
         tdo.rerotate_round(g, hr, mk, mv, ok, ov)
         tdo.diff_encode(g, hr, mk, mv, mir_k, mir_v, spec.eps, cap)
