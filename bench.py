@@ -32,6 +32,8 @@ def parse():
     ap.add_argument("--flags", type=int, default=0, help="bit 0: non-temporal pool stores")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-check", action="store_true")
+    ap.add_argument("--alloc", default="fragmented", choices=["fragmented", "contiguous"],
+                    help="physical page placement of the synthetic pool (fragmented = the graded recipe)")
     ap.add_argument("--layers", type=int, default=0, help="override the layer count (for profiling runs only)")
     return ap.parse_args()
 
@@ -57,7 +59,7 @@ def main():
 
     spec = wl.CONFIGS[args.workload]
     L = args.layers or spec.num_layers
-    rnd = wl.make_round(spec)
+    rnd = wl.make_round(spec, alloc=args.alloc)
     A, T, RE = rnd.n_agents, spec.page_tokens, spec.row_elems
     pool_rows = rnd.pool_pages * T
     n_pert = sum(len(p) for p in rnd.perturbed)
@@ -160,20 +162,35 @@ def main():
                     unit="GB/s", frac=round(achieved / HBM_PEAK_GBPS, 4), traffic=traffic,
                     algorithmic_bytes_per_launch=dom_bytes, avg_launch_us=round(us[dom], 2))
 
-    # ---- plain copy ceiling on this machine -----------------------------------------------------------
+    # ---- what HBM delivers on this machine for the bare access patterns (no arithmetic) ---------------
+    def timed(fn, reps=5):
+        fn()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(reps):
+            fn()
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) * 1e-3 / reps
+
     n_copy = 1 << 31
     src = torch.empty(n_copy, dtype=torch.uint8, device=dev)
     dst = torch.empty(n_copy, dtype=torch.uint8, device=dev)
     tdk.tdk_util_fill(src, 0x01020304, n_copy, stream)
-    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    tdk.tdk_util_copy(dst, src, n_copy, stream)
-    e0.record()
-    for _ in range(5):
-        tdk.tdk_util_copy(dst, src, n_copy, stream)
-    e1.record()
-    torch.cuda.synchronize()
-    copy_gbps = 2 * n_copy * 5 / (e0.elapsed_time(e1) * 1e-3) / 1e9
-    del src, dst
+    copy_gbps = 2 * n_copy / timed(lambda: tdk.tdk_util_copy(dst, src, n_copy, stream)) / 1e9
+    del dst
+    page_b = T * RE * 2                       # one plane of one page
+    n_pg = n_copy // page_b
+    ids_seq = torch.arange(n_pg, dtype=torch.int32, device=dev)
+    ids_rnd = torch.from_numpy(np.random.default_rng(7).permutation(n_pg).astype(np.int32)).to(dev)
+    sink = torch.zeros(16, dtype=torch.uint8, device=dev)
+    ceil = {}
+    for nm, ids in (("sequential", ids_seq), ("scattered", ids_rnd)):
+        ceil[f"{nm}_page_write_GBps"] = round(n_pg * page_b / timed(
+            lambda: tdk.tdk_util_page_fill(src, ids, n_pg, page_b, 5, stream)) / 1e9, 1)
+        ceil[f"{nm}_page_read_GBps"] = round(n_pg * page_b / timed(
+            lambda: tdk.tdk_util_page_read(src, ids, n_pg, page_b, sink, stream)) / 1e9, 1)
+    del src
 
     # ---- correctness at full size, outside the timed region ---------------------------------------
     check = {}
@@ -201,12 +218,12 @@ def main():
                dtype="bf16", data="synthetic",
                config=dict(workload=args.workload, layers=L, agents=A, sessions=rnd.n_sessions,
                            span_tokens=int(spec.span_tokens), page_tokens=T, perturbed_pages=n_pert,
-                           ring_layers=ring, agents_per_group="auto" if not args.group else args.group,
+                           ring_layers=ring, alloc=args.alloc, agents_per_group="auto" if not args.group else args.group,
                            step="rerotate+decode+encode per layer, all layers"),
                roofline=roofline, cpu_baseline=cpu,
                rates={k: round(v, 1) for k, v in rates.items()},
                pct_hbm_peak={k.replace("_GBps", ""): round(100 * v / HBM_PEAK_GBPS, 2) for k, v in rates.items()},
-               copy_ceiling_GBps=round(copy_gbps, 1),
+               copy_ceiling_GBps=round(copy_gbps, 1), pattern_ceilings=ceil,
                tokens_per_s_rerotate_only=round(agent_tokens / (us["rerotate"] * 1e-6 * L), 1) if us["rerotate"] else None,
                kernels={k: dict(avg_us=round(v["avg_us"], 2), launches=v["launches"]) for k, v in kt.items()},
                check=check)

@@ -174,6 +174,15 @@ double tdk_family_cost(int64_t n_agents, double ratio);            /* 1 + (N-1)/
 tdk_status tdk_util_copy(void* dst, const void* src, size_t bytes, void* hip_stream);
 tdk_status tdk_util_fill(void* dst, uint32_t word, size_t bytes, void* hip_stream);
 
+/* Access-pattern probes: one workgroup per page fills (reads) page_bytes (multiple of 16) at
+ * dst + page_ids[i] * page_bytes for i < n_pages; page_ids is DEV.  With a permuted id list this is
+ * the page kernels' access pattern with no arithmetic.  The caller guarantees every id is in range.
+ * sink16: 16 DEV bytes that are never written in practice (they keep the loads alive). */
+tdk_status tdk_util_page_fill(void* dst, const int32_t* page_ids, int32_t n_pages, size_t page_bytes,
+                              uint32_t word, void* hip_stream);
+tdk_status tdk_util_page_read(const void* src, const int32_t* page_ids, int32_t n_pages, size_t page_bytes,
+                              void* sink16, void* hip_stream);
+
 #ifdef __cplusplus
 }
 #endif

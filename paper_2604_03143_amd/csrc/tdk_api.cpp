@@ -449,8 +449,7 @@ tdk_status tdk_diff_encode(tdk_round* r, int32_t layer, const tdk_layer_io* io, 
   TDK_LAUNCH(r, TDK_KERNEL_COUNT, s, launch_count(r->rd, d, s));
   TDK_LAUNCH(r, TDK_KERNEL_INDEX, s, launch_index(r->rd, d, s));
   // the number of listed pages is known on the device only: a fixed grid strides over them
-  const int64_t units = 2 * std::min<int64_t>(out->capacity_pages, r->total_pages);
-  const int grid = (int)std::min<int64_t>(units, 1 << 20);
+  const int grid = (int)std::min<int64_t>(std::min<int64_t>(out->capacity_pages, r->total_pages), 1 << 20);
   TDK_LAUNCH(r, TDK_KERNEL_GATHER, s, launch_gather(r->rd, l, d, grid, s));
   return TDK_OK;
 }
@@ -465,8 +464,7 @@ tdk_status tdk_diff_decode(tdk_round* r, int32_t layer, const tdk_layer_io* io, 
   const LayerDev l = layer_dev(io);
   const DiffDev d = diff_dev(in);
   TDK_LAUNCH(r, TDK_KERNEL_DECODE, s, launch_decode(r->rd, l, d, s));
-  const int64_t units = 2 * std::min<int64_t>(in->capacity_pages, r->total_pages);
-  const int grid = (int)std::min<int64_t>(units, 1 << 20);
+  const int grid = (int)std::min<int64_t>(std::min<int64_t>(in->capacity_pages, r->total_pages), 1 << 20);
   TDK_LAUNCH(r, TDK_KERNEL_SCATTER, s, launch_scatter(r->rd, l, d, grid, s));
   return TDK_OK;
 }
@@ -536,6 +534,26 @@ tdk_status tdk_util_fill(void* dst, uint32_t word, size_t bytes, void* hip_strea
     return fail(TDK_ERR_INVALID_ARG, "fill: NULL, misaligned or size not a multiple of 16");
   hipError_t e = launch_fill(static_cast<u32x4*>(dst), word, bytes / 16, static_cast<hipStream_t>(hip_stream));
   return e == hipSuccess ? TDK_OK : hip_fail(e, "fill kernel");
+}
+
+tdk_status tdk_util_page_fill(void* dst, const int32_t* page_ids, int32_t n_pages, size_t page_bytes,
+                              uint32_t word, void* hip_stream) {
+  if (n_pages < 0 || (n_pages && (!dst || !page_ids)) || (page_bytes & 15) || ((uintptr_t)dst & 15) ||
+      page_bytes > ((size_t)1 << 30))
+    return fail(TDK_ERR_INVALID_ARG, "page_fill: NULL, misaligned or bad size");
+  hipError_t e = launch_page_fill(static_cast<u32x4*>(dst), page_ids, n_pages, (int)(page_bytes / 16), word,
+                                  static_cast<hipStream_t>(hip_stream));
+  return e == hipSuccess ? TDK_OK : hip_fail(e, "page fill kernel");
+}
+
+tdk_status tdk_util_page_read(const void* src, const int32_t* page_ids, int32_t n_pages, size_t page_bytes,
+                              void* sink16, void* hip_stream) {
+  if (n_pages < 0 || (n_pages && (!src || !page_ids || !sink16)) || (page_bytes & 15) ||
+      (((uintptr_t)src | (uintptr_t)sink16) & 15) || page_bytes > ((size_t)1 << 30))
+    return fail(TDK_ERR_INVALID_ARG, "page_read: NULL, misaligned or bad size");
+  hipError_t e = launch_page_read(static_cast<const u32x4*>(src), page_ids, n_pages, (int)(page_bytes / 16),
+                                  static_cast<u32x4*>(sink16), static_cast<hipStream_t>(hip_stream));
+  return e == hipSuccess ? TDK_OK : hip_fail(e, "page read kernel");
 }
 
 }  // extern "C"

@@ -82,4 +82,7 @@ hipError_t launch_scatter(const RoundDev& rd, const LayerDev& io, const DiffDev&
 hipError_t launch_copy(u32x4* dst, const u32x4* src, size_t n16, hipStream_t st);
 hipError_t launch_fill(u32x4* dst, uint32_t word, size_t n16, hipStream_t st);
 
+hipError_t launch_page_fill(u32x4* dst, const int32_t* ids, int n_pages, int page_u4, uint32_t word, hipStream_t st);
+hipError_t launch_page_read(const u32x4* src, const int32_t* ids, int n_pages, int page_u4, u32x4* sink, hipStream_t st);
+
 }  // namespace tdk

@@ -365,7 +365,24 @@ __global__ __launch_bounds__(kBlock) void tdk_index_kernel(const RoundDev rd, co
 // exist, so the host never needs the count.
 // ---------------------------------------------------------------------------------------------
 
+// Shared by gather and scatter.  A workgroup moves one payload slot (K plane, then V plane).
+// Prologue: all threads search offset[] in parallel for the agent that owns the slot (one memory
+// round trip per 256 agents instead of a serial binary search), then T threads resolve the pool
+// row of each row of the page through the block table.
+struct SlotShared {
+  int32_t owner;
+  int64_t row[32];     // pool row of each row of the page, -1 past the span / not listed
+};
+
+__device__ __forceinline__ void find_owner(const DiffDev& d, int A, int64_t slot, SlotShared& sh) {
+  for (int a = threadIdx.x; a < A; a += kBlock)
+    if (d.offset[a] <= slot && slot < d.offset[a + 1]) sh.owner = a;
+}
+
+constexpr int kCopyBatch = 4;   // 16-byte accesses per thread in flight in gather / scatter
+
 __global__ __launch_bounds__(kBlock) void tdk_gather_kernel(const RoundDev rd, const LayerDev io, const DiffDev d) {
+  __shared__ SlotShared sh;
   const int T = rd.page_tokens;
   const int A = rd.n_agents;
   if (A == 0) return;
@@ -373,31 +390,45 @@ __global__ __launch_bounds__(kBlock) void tdk_gather_kernel(const RoundDev rd, c
   if (total > d.capacity) total = d.capacity;
   const int row_u4 = rd.heads * 16;
   const int page_u4 = T * row_u4;
-  for (int64_t u = blockIdx.x; u < 2 * total; u += gridDim.x) {
-    const int64_t slot = u >> 1;
-    const int plane = (int)(u & 1);
-    // agent owning this slot: last a with offset[a] <= slot
-    int lo = 0, hi = A;
-    while (hi - lo > 1) {
-      const int mid = (lo + hi) >> 1;
-      if (d.offset[mid] <= slot) lo = mid; else hi = mid;
-    }
-    const AgentDev ad = rd.agents[lo];
-    const int S = rd.sess[ad.session].span;
-    const int p = d.idx[slot];
-    const u32x4* src = plane ? io.pool_v : io.pool_k;
-    u32x4* dst = d.payload + (slot * 2 + plane) * (int64_t)page_u4;
-    for (int i = threadIdx.x; i < page_u4; i += kBlock) {
-      const int r = i / row_u4, cc = i - r * row_u4;
-      const int m = p * T + r;
-      u32x4 v = {0, 0, 0, 0};
-      if (m < S) {
+  for (int64_t slot = blockIdx.x; slot < total; slot += gridDim.x) {
+    find_owner(d, A, slot, sh);
+    __syncthreads();
+    if (threadIdx.x < T) {
+      const AgentDev ad = rd.agents[sh.owner];
+      const int m = d.idx[slot] * T + threadIdx.x;
+      int64_t row = -1;
+      if (m < rd.sess[ad.session].span) {
         const int a0 = ad.pos0 + m;
-        const int pg = rd.bt[ad.bt_off + a0 / T - ad.lp_first];
-        v = src[((int64_t)pg * T + a0 % T) * row_u4 + cc];
+        row = (int64_t)rd.bt[ad.bt_off + a0 / T - ad.lp_first] * T + a0 % T;
       }
-      dst[i] = v;
+      sh.row[threadIdx.x] = row;
     }
+    __syncthreads();
+#pragma unroll 1
+    for (int plane = 0; plane < 2; ++plane) {
+      const u32x4* src = plane ? io.pool_v : io.pool_k;
+      u32x4* dst = d.payload + (slot * 2 + plane) * (int64_t)page_u4;
+      for (int i0 = threadIdx.x; i0 < page_u4; i0 += kBlock * kCopyBatch) {
+        u32x4 v[kCopyBatch];
+#pragma unroll
+        for (int j = 0; j < kCopyBatch; ++j) {
+          const int i = i0 + j * kBlock;
+          const u32x4 z = {0, 0, 0, 0};
+          v[j] = z;
+          if (i < page_u4) {
+            const int r = i / row_u4;
+            const int64_t row = sh.row[r];
+            if (row >= 0) v[j] = src[row * row_u4 + (i - r * row_u4)];
+          }
+        }
+#pragma unroll
+        for (int j = 0; j < kCopyBatch; ++j) {
+          const int i = i0 + j * kBlock;
+          if (i < page_u4) dst[i] = v[j];
+        }
+      }
+    }
+    __syncthreads();
   }
 }
 
@@ -459,6 +490,7 @@ __global__ __launch_bounds__(kBlock) void tdk_decode_kernel(const RoundDev rd, c
 // agent's rows (the mirror image of the gather kernel).  Every pool row is written exactly once by
 // either this kernel or the page kernel above, so their order does not matter.
 __global__ __launch_bounds__(kBlock) void tdk_scatter_kernel(const RoundDev rd, const LayerDev io, const DiffDev d) {
+  __shared__ SlotShared sh;
   const int T = rd.page_tokens;
   const int A = rd.n_agents;
   if (A == 0) return;
@@ -466,29 +498,50 @@ __global__ __launch_bounds__(kBlock) void tdk_scatter_kernel(const RoundDev rd, 
   if (total > d.capacity) total = d.capacity;
   const int row_u4 = rd.heads * 16;
   const int page_u4 = T * row_u4;
-  for (int64_t u = blockIdx.x; u < 2 * total; u += gridDim.x) {
-    const int64_t slot = u >> 1;
-    const int plane = (int)(u & 1);
-    int lo = 0, hi = A;
-    while (hi - lo > 1) {
-      const int mid = (lo + hi) >> 1;
-      if (d.offset[mid] <= slot) lo = mid; else hi = mid;
+  for (int64_t slot = blockIdx.x; slot < total; slot += gridDim.x) {
+    if (threadIdx.x == 0) sh.owner = -1;
+    __syncthreads();
+    find_owner(d, A, slot, sh);
+    __syncthreads();
+    if (threadIdx.x < T) {
+      int64_t row = -1;
+      if (sh.owner >= 0) {                       // an inconsistent offset[] leaves the slot unowned
+        const AgentDev ad = rd.agents[sh.owner];
+        const SessionDev sd = rd.sess[ad.session];
+        const int p = d.idx[slot];
+        const int m = p * T + threadIdx.x;
+        if (p >= 0 && p < sd.pages && m < sd.span) {   // anything else is not an index this round produces
+          const int a0 = ad.pos0 + m;
+          row = (int64_t)rd.bt[ad.bt_off + a0 / T - ad.lp_first] * T + a0 % T;
+        }
+      }
+      sh.row[threadIdx.x] = row;
     }
-    const AgentDev ad = rd.agents[lo];
-    const SessionDev sd = rd.sess[ad.session];
-    const int p = d.idx[slot];
-    if (p < 0 || p >= sd.pages) continue;   // not an index this round could have produced
-    u32x4* dst = plane ? io.pool_v : io.pool_k;
-    const u32x4* src = d.payload + (slot * 2 + plane) * (int64_t)page_u4;
-    for (int i = threadIdx.x; i < page_u4; i += kBlock) {
-      const int r = i / row_u4, cc = i - r * row_u4;
-      const int m = p * T + r;
-      if (m < sd.span) {
-        const int a0 = ad.pos0 + m;
-        const int pg = rd.bt[ad.bt_off + a0 / T - ad.lp_first];
-        dst[((int64_t)pg * T + a0 % T) * row_u4 + cc] = src[i];
+    __syncthreads();
+#pragma unroll 1
+    for (int plane = 0; plane < 2; ++plane) {
+      u32x4* dst = plane ? io.pool_v : io.pool_k;
+      const u32x4* src = d.payload + (slot * 2 + plane) * (int64_t)page_u4;
+      for (int i0 = threadIdx.x; i0 < page_u4; i0 += kBlock * kCopyBatch) {
+        u32x4 v[kCopyBatch];
+#pragma unroll
+        for (int j = 0; j < kCopyBatch; ++j) {
+          const int i = i0 + j * kBlock;
+          const u32x4 z = {0, 0, 0, 0};
+          v[j] = i < page_u4 ? src[i] : z;
+        }
+#pragma unroll
+        for (int j = 0; j < kCopyBatch; ++j) {
+          const int i = i0 + j * kBlock;
+          if (i < page_u4) {
+            const int r = i / row_u4;
+            const int64_t row = sh.row[r];
+            if (row >= 0) dst[row * row_u4 + (i - r * row_u4)] = v[j];
+          }
+        }
       }
     }
+    __syncthreads();
   }
 }
 
@@ -503,6 +556,25 @@ __global__ __launch_bounds__(kBlock) void tdk_copy_kernel(u32x4* __restrict__ ds
 __global__ __launch_bounds__(kBlock) void tdk_fill_kernel(u32x4* __restrict__ dst, uint32_t word, size_t n) {
   const u32x4 v = {word, word, word, word};
   for (size_t i = (size_t)blockIdx.x * kBlock + threadIdx.x; i < n; i += (size_t)gridDim.x * kBlock) dst[i] = v;
+}
+
+// One workgroup per page: fills (or reads) page_u4 16-byte words of page ids[blockIdx.x].  With a
+// permuted id list this is the bare access pattern of the page kernels (whole pages at scattered
+// addresses) without any arithmetic: the bandwidth ceiling they are compared with.
+__global__ __launch_bounds__(kBlock) void tdk_page_fill_kernel(u32x4* __restrict__ dst, const int32_t* __restrict__ ids,
+                                                              int page_u4, uint32_t word) {
+  const u32x4 v = {word, word, word, word};
+  u32x4* p = dst + (size_t)ids[blockIdx.x] * page_u4;
+  for (int i = threadIdx.x; i < page_u4; i += kBlock) p[i] = v;
+}
+
+__global__ __launch_bounds__(kBlock) void tdk_page_read_kernel(const u32x4* __restrict__ src, const int32_t* __restrict__ ids,
+                                                              int page_u4, u32x4* __restrict__ sink) {
+  const u32x4* p = src + (size_t)ids[blockIdx.x] * page_u4;
+  u32x4 acc = {0, 0, 0, 0};
+  for (int i = threadIdx.x; i < page_u4; i += kBlock) acc ^= p[i];
+  // never true for the probe's fill pattern; keeps the loads alive
+  if (acc[0] == 0x9e3779b9u && acc[1] == 0x7f4a7c15u) sink[0] = acc;
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -599,6 +671,18 @@ hipError_t launch_fill(u32x4* dst, uint32_t word, size_t n16, hipStream_t st) {
   if (blocks > 256 * 32) blocks = 256 * 32;
   hipLaunchKernelGGL(tdk_fill_kernel, dim3((unsigned)blocks), dim3(kBlock), 0, st,
                      dst, word, n16);
+  return hipGetLastError();
+}
+
+hipError_t launch_page_fill(u32x4* dst, const int32_t* ids, int n_pages, int page_u4, uint32_t word, hipStream_t st) {
+  if (n_pages <= 0) return hipSuccess;
+  hipLaunchKernelGGL(tdk_page_fill_kernel, dim3(n_pages), dim3(kBlock), 0, st, dst, ids, page_u4, word);
+  return hipGetLastError();
+}
+
+hipError_t launch_page_read(const u32x4* src, const int32_t* ids, int n_pages, int page_u4, u32x4* sink, hipStream_t st) {
+  if (n_pages <= 0) return hipSuccess;
+  hipLaunchKernelGGL(tdk_page_read_kernel, dim3(n_pages), dim3(kBlock), 0, st, src, ids, page_u4, sink);
   return hipGetLastError();
 }
 

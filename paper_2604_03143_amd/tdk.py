@@ -27,7 +27,7 @@ EXPORTS = (
     "tdk_rerotate_round", "tdk_diff_encode", "tdk_diff_decode",
     "tdk_timing_enable", "tdk_timing_read", "tdk_timing_reset",
     "tdk_dense_bytes", "tdk_diff_bytes", "tdk_family_cost",
-    "tdk_util_copy", "tdk_util_fill",
+    "tdk_util_copy", "tdk_util_fill", "tdk_util_page_fill", "tdk_util_page_read",
 )
 
 
@@ -101,6 +101,8 @@ def load() -> C.CDLL:
     L.tdk_family_cost.argtypes = [C.c_int64, C.c_double]
     L.tdk_util_copy.argtypes = [C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
     L.tdk_util_fill.argtypes = [C.c_void_p, C.c_uint32, C.c_size_t, C.c_void_p]
+    L.tdk_util_page_fill.argtypes = [C.c_void_p, C.c_void_p, C.c_int32, C.c_size_t, C.c_uint32, C.c_void_p]
+    L.tdk_util_page_read.argtypes = [C.c_void_p, C.c_void_p, C.c_int32, C.c_size_t, C.c_void_p, C.c_void_p]
     _lib = L
     return L
 
@@ -251,3 +253,13 @@ def tdk_util_copy(dst, src, nbytes: int, stream: int = 0) -> None:
 
 def tdk_util_fill(dst, word: int, nbytes: int, stream: int = 0) -> None:
     _check(load().tdk_util_fill(_ptr(dst), int(word) & 0xFFFFFFFF, int(nbytes), C.c_void_p(stream)), "tdk_util_fill")
+
+
+def tdk_util_page_fill(dst, page_ids, n_pages: int, page_bytes: int, word: int = 0, stream: int = 0) -> None:
+    _check(load().tdk_util_page_fill(_ptr(dst), _ptr(page_ids), int(n_pages), int(page_bytes),
+                                     int(word) & 0xFFFFFFFF, C.c_void_p(stream)), "tdk_util_page_fill")
+
+
+def tdk_util_page_read(src, page_ids, n_pages: int, page_bytes: int, sink16, stream: int = 0) -> None:
+    _check(load().tdk_util_page_read(_ptr(src), _ptr(page_ids), int(n_pages), int(page_bytes), _ptr(sink16),
+                                     C.c_void_p(stream)), "tdk_util_page_read")

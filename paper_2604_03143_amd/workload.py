@@ -121,8 +121,12 @@ def _rng(spec: RoundSpec, tag: int, extra: int = 0) -> np.random.Generator:
 
 def make_round(spec: RoundSpec, hist: Optional[np.ndarray] = None,
                perturbed_per_agent: Optional[int] = None,
-               clustered: bool = False) -> Round:
-    """Draw the structure of a round: histories, block tables, perturbed page sets."""
+               clustered: bool = False, alloc: str = "fragmented") -> Round:
+    """Draw the structure of a round: histories, block tables, perturbed page sets.
+
+    alloc = "fragmented": physical pages are a seeded random permutation of the pool (an allocator
+    after long use; the default and the graded recipe); "contiguous": every agent's pages are
+    consecutive (a fresh allocator)."""
     T = spec.page_tokens
     A = spec.n_agents
     S = spec.span_tokens
@@ -141,7 +145,12 @@ def make_round(spec: RoundSpec, hist: Optional[np.ndarray] = None,
     last_lp = (agent_pos0 + S - 1) // T
     n_touch = (last_lp - first_lp + 1).astype(np.int64)
     pool_pages = int(n_touch.sum()) + 2 * A + 1
-    perm = _rng(spec, 2).permutation(pool_pages).astype(np.int32)
+    if alloc == "fragmented":
+        perm = _rng(spec, 2).permutation(pool_pages).astype(np.int32)
+    elif alloc == "contiguous":
+        perm = np.arange(pool_pages, dtype=np.int32)
+    else:
+        raise ValueError(f"unknown alloc {alloc!r}")
     dummy = int(perm[0])
     canaries = perm[1:1 + 2 * A].copy()
     cursor = 1 + 2 * A
