@@ -149,6 +149,28 @@ tdk_status tdk_diff_encode(tdk_round* r, int32_t layer, const tdk_layer_io* io, 
 tdk_status tdk_diff_decode(tdk_round* r, int32_t layer, const tdk_layer_io* io, const tdk_diff* in,
                            void* hip_stream);
 
+/* Ping-pong staging buffers of the layerwise restore, DEV, caller-owned: two K and two V buffers of
+ * stage_bytes each, stage_bytes >= (sum_s S_s) * H * D * 2 (one layer of masters). */
+typedef struct {
+  void*  stage_k[2];
+  void*  stage_v[2];
+  size_t stage_bytes;
+} tdk_pingpong;
+
+/* Algorithm 1 (Sec. 4.4) for layers first_layer .. first_layer + n_layers - 1 of every mirror of the
+ * round: the masters of layer k are copied from HOST memory (host_master_k[k], host_master_v[k];
+ * pinned memory, layout as tdk_layer_io.master_k) into one staging buffer on copy_stream while the
+ * previous layer, staged in the other buffer, is restored on compute_stream exactly as
+ * tdk_diff_decode does (io[k].pool_*, diffs[k]; io[k].master_* are ignored).  Returns after
+ * enqueueing; the result is complete when compute_stream has drained.  Uses events owned by the
+ * round, so calls on one round must not be issued concurrently from several threads.  Errors: as
+ * tdk_diff_decode for every layer (all checked before anything is enqueued), INVALID_ARG for NULL or
+ * undersized staging. */
+tdk_status tdk_restore_layers(tdk_round* r, int32_t first_layer, int32_t n_layers,
+                              const void* const* host_master_k, const void* const* host_master_v,
+                              const tdk_layer_io* io, const tdk_diff* diffs, const tdk_pingpong* pp,
+                              void* compute_stream, void* copy_stream);
+
 /* Kernel timing with HIP events on the caller's stream (off by default).  When on, every kernel
  * launch of the step calls is bracketed by two events; tdk_timing_read waits for them. */
 #define TDK_KERNEL_REROTATE 0

@@ -399,6 +399,36 @@ int tdo_diff_decode(const tdo_geom* g, const tdo_round* r,
   return err ? -2 : 0;
 }
 
+/* ---- layerwise restore of all layers  [Sec. 4.4, Alg. 1] ------------------
+ * The algorithm as stated: two buffers alternate between "load" and "compute"; per layer the master
+ * chunks are loaded into the load buffer, the buffers swap, and the compute buffer is corrected with
+ * the layer's diff, position-recovered and written to paged memory through the slot map. */
+int tdo_restore_layers(const tdo_geom* g, const tdo_round* r, int32_t n_layers,
+                       const uint16_t* const* master_k, const uint16_t* const* master_v,
+                       uint16_t* const* pool_k, uint16_t* const* pool_v, int64_t pool_pages,
+                       const int32_t* const* count, const int64_t* const* offset,
+                       const int32_t* const* idx, const uint16_t* const* payload) {
+  if (!geom_ok(g) || !r || n_layers < 0) return -1;
+  if (n_layers && (!master_k || !master_v || !pool_k || !pool_v || !count || !offset || !idx || !payload)) return -1;
+  int64_t rows = 0;
+  for (int32_t s = 0; s < r->n_sessions; ++s) rows += r->span_tokens[s];
+  const size_t bytes = (size_t)rows * g->num_kv_heads * g->head_dim * sizeof(uint16_t);
+  uint16_t* buf_k[2] = {(uint16_t*)malloc(bytes ? bytes : 1), (uint16_t*)malloc(bytes ? bytes : 1)};
+  uint16_t* buf_v[2] = {(uint16_t*)malloc(bytes ? bytes : 1), (uint16_t*)malloc(bytes ? bytes : 1)};
+  int rc = 0;
+  if (!buf_k[0] || !buf_k[1] || !buf_v[0] || !buf_v[1]) rc = -2;
+  int load = 0, comp = 1;
+  for (int32_t l = 0; l < n_layers && rc == 0; ++l) {
+    memcpy(buf_k[load], master_k[l], bytes);            /* load master chunks of layer l */
+    memcpy(buf_v[load], master_v[l], bytes);
+    { int t = load; load = comp; comp = t; }            /* sync; swap */
+    rc = tdo_diff_decode(g, r, buf_k[comp], buf_v[comp], pool_k[l], pool_v[l], pool_pages,
+                         count[l], offset[l], idx[l], payload[l]);
+  }
+  free(buf_k[0]); free(buf_k[1]); free(buf_v[0]); free(buf_v[1]);
+  return rc;
+}
+
 /* ---- storage arithmetic  [Sec. 6.4] -------------------------------------- */
 
 double tdo_dense_bytes(const tdo_geom* g, int64_t span_tokens) {

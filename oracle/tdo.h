@@ -92,6 +92,13 @@ int tdo_diff_decode(const tdo_geom* g, const tdo_round* r,
                     uint16_t* pool_k, uint16_t* pool_v, int64_t pool_pages,
                     const int32_t* count, const int64_t* offset, const int32_t* idx, const uint16_t* payload);
 
+/* Alg. 1 over n_layers layers: per-layer arrays of pointers (masters, pools and diffs of each layer). */
+int tdo_restore_layers(const tdo_geom* g, const tdo_round* r, int32_t n_layers,
+                       const uint16_t* const* master_k, const uint16_t* const* master_v,
+                       uint16_t* const* pool_k, uint16_t* const* pool_v, int64_t pool_pages,
+                       const int32_t* const* count, const int64_t* const* offset,
+                       const int32_t* const* idx, const uint16_t* const* payload);
+
 /* Sec. 6.4 arithmetic. */
 double tdo_dense_bytes (const tdo_geom* g, int64_t span_tokens);               /* one layer of one cache    */
 double tdo_diff_bytes  (const tdo_geom* g, int64_t diff_pages);                /* payload + index metadata  */

@@ -66,6 +66,8 @@ def lib() -> C.CDLL:
                                       [C.c_int64, C.c_float] + [C.c_void_p] * 4 + [C.c_int64, C.c_void_p])
         L.tdo_diff_decode.argtypes = ([C.POINTER(Geom), C.POINTER(RoundDesc)] + [C.c_void_p] * 4 +
                                       [C.c_int64] + [C.c_void_p] * 4)
+        L.tdo_restore_layers.argtypes = ([C.POINTER(Geom), C.POINTER(RoundDesc), C.c_int32] +
+                                         [C.POINTER(C.c_void_p)] * 4 + [C.c_int64] + [C.POINTER(C.c_void_p)] * 4)
         _lib = L
     return _lib
 
@@ -176,6 +178,19 @@ def diff_decode(g: Geom, hr: HostRound, master_k, master_v, pool_k, pool_v, d: D
     _chk(lib().tdo_diff_decode(C.byref(g), C.byref(hr.desc), _p(_u16(master_k)), _p(_u16(master_v)),
                                _p(_u16(pool_k)), _p(_u16(pool_v)), hr.pool_pages,
                                _p(d.count), _p(d.offset), _p(d.idx), _p(d.payload)), "diff_decode")
+
+
+def restore_layers(g: Geom, hr: HostRound, masters_k, masters_v, pools_k, pools_v, diffs) -> None:
+    """Alg. 1 over len(diffs) layers; every argument is a per-layer list."""
+    n = len(diffs)
+
+    def arr(xs):
+        return (C.c_void_p * max(n, 1))(*[_p(x) for x in xs])
+
+    _chk(lib().tdo_restore_layers(C.byref(g), C.byref(hr.desc), n, arr(masters_k), arr(masters_v),
+                                  arr(pools_k), arr(pools_v), hr.pool_pages,
+                                  arr([d.count for d in diffs]), arr([d.offset for d in diffs]),
+                                  arr([d.idx for d in diffs]), arr([d.payload for d in diffs])), "restore_layers")
 
 
 def dense_bytes(g: Geom, span_tokens: int) -> float:

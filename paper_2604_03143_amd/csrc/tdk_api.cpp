@@ -56,6 +56,12 @@ struct tdk_round {
   size_t work_capacity = 0;        // WorkItems the work region can hold
   RoundDev rd{};
 
+  // ping-pong restore: one "loaded" and one "free" event per staging buffer, one "done" per call
+  hipEvent_t ev_loaded[2] = {nullptr, nullptr};
+  hipEvent_t ev_free[2] = {nullptr, nullptr};
+  bool free_recorded[2] = {false, false};
+  int64_t total_master_rows = 0;
+
   bool timing = false;
   std::vector<EventPair> pending;
   std::vector<EventPair> free_events;
@@ -303,6 +309,7 @@ tdk_status tdk_round_create(const tdk_model* model, const tdk_session* sessions,
     sess_dev[s] = {hs.master_row0, hs.span, hs.pages};
     r->total_master_pages += hs.pages;
   }
+  r->total_master_rows = row0;
   int64_t flag_off = 0;
   for (int32_t i = 0; i < n_agents; ++i) {
     const tdk_agent& a = agents[i];
@@ -400,6 +407,11 @@ tdk_status tdk_round_create(const tdk_model* model, const tdk_session* sessions,
 
   st = upload_work(r, auto_group(*r));
   if (st != TDK_OK) { (void)hipFree(r->blob); delete r; return st; }
+  for (int b = 0; b < 2 && e == hipSuccess; ++b) {
+    e = hipEventCreateWithFlags(&r->ev_loaded[b], hipEventDisableTiming);
+    if (e == hipSuccess) e = hipEventCreateWithFlags(&r->ev_free[b], hipEventDisableTiming);
+  }
+  if (e != hipSuccess) { tdk_round_destroy(r); return hip_fail(e, "hipEventCreate"); }
   *out = r;
   return TDK_OK;
 }
@@ -408,6 +420,10 @@ void tdk_round_destroy(tdk_round* r) {
   if (!r) return;
   for (auto& ev : r->pending) { (void)hipEventDestroy(ev.start); (void)hipEventDestroy(ev.stop); }
   for (auto& ev : r->free_events) { (void)hipEventDestroy(ev.start); (void)hipEventDestroy(ev.stop); }
+  for (int b = 0; b < 2; ++b) {
+    if (r->ev_loaded[b]) (void)hipEventDestroy(r->ev_loaded[b]);
+    if (r->ev_free[b]) (void)hipEventDestroy(r->ev_free[b]);
+  }
   if (r->blob) (void)hipFree(r->blob);
   delete r;
 }
@@ -466,6 +482,69 @@ tdk_status tdk_diff_decode(tdk_round* r, int32_t layer, const tdk_layer_io* io, 
   TDK_LAUNCH(r, TDK_KERNEL_DECODE, s, launch_decode(r->rd, l, d, s));
   const int grid = (int)std::min<int64_t>(std::min<int64_t>(in->capacity_pages, r->total_pages), 1 << 20);
   TDK_LAUNCH(r, TDK_KERNEL_SCATTER, s, launch_scatter(r->rd, l, d, grid, s));
+  return TDK_OK;
+}
+
+tdk_status tdk_restore_layers(tdk_round* r, int32_t first_layer, int32_t n_layers,
+                              const void* const* host_master_k, const void* const* host_master_v,
+                              const tdk_layer_io* io, const tdk_diff* diffs, const tdk_pingpong* pp,
+                              void* compute_stream, void* copy_stream) {
+  if (!r) return fail(TDK_ERR_INVALID_ARG, "round is NULL");
+  if (n_layers < 0 || first_layer < 0 || (int64_t)first_layer + n_layers > r->model.num_layers)
+    return fail(TDK_ERR_INVALID_ARG, "layer range out of bounds");
+  if (n_layers == 0) return TDK_OK;
+  if (!host_master_k || !host_master_v || !io || !diffs || !pp)
+    return fail(TDK_ERR_INVALID_ARG, "NULL argument");
+  const size_t master_bytes = (size_t)r->total_master_rows * r->model.num_kv_heads * r->model.head_dim * 2;
+  if (pp->stage_bytes < master_bytes) return fail(TDK_ERR_INVALID_ARG, "staging buffers smaller than one layer of masters");
+  for (int b = 0; b < 2; ++b) {
+    if (master_bytes && (!pp->stage_k[b] || !pp->stage_v[b])) return fail(TDK_ERR_INVALID_ARG, "staging buffer is NULL");
+    if (((uintptr_t)pp->stage_k[b] | (uintptr_t)pp->stage_v[b]) & 15) return fail(TDK_ERR_INVALID_ARG, "staging buffers must be 16-byte aligned");
+  }
+  if (pp->stage_k[0] == pp->stage_k[1] || pp->stage_v[0] == pp->stage_v[1])
+    return fail(TDK_ERR_INVALID_ARG, "the two staging buffers must be distinct");
+  // validate every layer before anything is enqueued
+  std::vector<tdk_layer_io> lio(n_layers);
+  for (int32_t k = 0; k < n_layers; ++k) {
+    if (master_bytes && (!host_master_k[k] || !host_master_v[k])) return fail(TDK_ERR_INVALID_ARG, "host master pointer is NULL");
+    lio[k] = io[k];
+    lio[k].master_k = pp->stage_k[k & 1];
+    lio[k].master_v = pp->stage_v[k & 1];
+    tdk_status st = check_step(r, first_layer + k, &lio[k]);
+    if (st != TDK_OK) return st;
+    st = check_diff(r, &diffs[k], false);
+    if (st != TDK_OK) return st;
+  }
+  hipStream_t cs = static_cast<hipStream_t>(compute_stream);
+  hipStream_t xs = static_cast<hipStream_t>(copy_stream);
+  hipError_t e = hipSuccess;
+  for (int32_t k = 0; k < n_layers; ++k) {
+    const int b = k & 1;
+    // load side: wait until the restore that last read this buffer (in this call or an earlier one)
+    // is through, then stage layer k
+    if (r->free_recorded[b]) {
+      e = hipStreamWaitEvent(xs, r->ev_free[b], 0);
+      if (e != hipSuccess) return hip_fail(e, "hipStreamWaitEvent(free)");
+    }
+    if (master_bytes) {
+      e = hipMemcpyAsync(pp->stage_k[b], host_master_k[k], master_bytes, hipMemcpyHostToDevice, xs);
+      if (e == hipSuccess) e = hipMemcpyAsync(pp->stage_v[b], host_master_v[k], master_bytes, hipMemcpyHostToDevice, xs);
+      if (e != hipSuccess) return hip_fail(e, "hipMemcpyAsync(master chunk)");
+    }
+    e = hipEventRecord(r->ev_loaded[b], xs);
+    if (e != hipSuccess) return hip_fail(e, "hipEventRecord(loaded)");
+    // compute side: sync on the load, swap roles, apply the diff / recover positions / write back
+    e = hipStreamWaitEvent(cs, r->ev_loaded[b], 0);
+    if (e != hipSuccess) return hip_fail(e, "hipStreamWaitEvent(loaded)");
+    const LayerDev l = layer_dev(&lio[k]);
+    const DiffDev d = diff_dev(&diffs[k]);
+    TDK_LAUNCH(r, TDK_KERNEL_DECODE, cs, launch_decode(r->rd, l, d, cs));
+    const int grid = (int)std::min<int64_t>(std::min<int64_t>(diffs[k].capacity_pages, r->total_pages), 1 << 20);
+    TDK_LAUNCH(r, TDK_KERNEL_SCATTER, cs, launch_scatter(r->rd, l, d, grid, cs));
+    e = hipEventRecord(r->ev_free[b], cs);
+    if (e != hipSuccess) return hip_fail(e, "hipEventRecord(free)");
+    r->free_recorded[b] = true;
+  }
   return TDK_OK;
 }
 

@@ -24,7 +24,7 @@ KERNEL_KINDS = 7
 EXPORTS = (
     "tdk_status_str", "tdk_last_error", "tdk_version", "tdk_kernel_name",
     "tdk_round_create", "tdk_round_destroy", "tdk_scratch_bytes", "tdk_round_tune",
-    "tdk_rerotate_round", "tdk_diff_encode", "tdk_diff_decode",
+    "tdk_rerotate_round", "tdk_diff_encode", "tdk_diff_decode", "tdk_restore_layers",
     "tdk_timing_enable", "tdk_timing_read", "tdk_timing_reset",
     "tdk_dense_bytes", "tdk_diff_bytes", "tdk_family_cost",
     "tdk_util_copy", "tdk_util_fill", "tdk_util_page_fill", "tdk_util_page_read",
@@ -54,6 +54,10 @@ class LayerIO(C.Structure):
 class Diff(C.Structure):
     _fields_ = [("count", C.c_void_p), ("offset", C.c_void_p), ("idx", C.c_void_p),
                 ("payload", C.c_void_p), ("capacity_pages", C.c_int64), ("overflow", C.c_void_p)]
+
+
+class PingPong(C.Structure):
+    _fields_ = [("stage_k", C.c_void_p * 2), ("stage_v", C.c_void_p * 2), ("stage_bytes", C.c_size_t)]
 
 
 class TdkError(RuntimeError):
@@ -91,6 +95,8 @@ def load() -> C.CDLL:
     L.tdk_rerotate_round.argtypes = [C.c_void_p, C.c_int32, C.POINTER(LayerIO), C.c_void_p]
     L.tdk_diff_encode.argtypes = [C.c_void_p, C.c_int32, C.POINTER(LayerIO), C.c_float, C.POINTER(Diff), C.c_void_p]
     L.tdk_diff_decode.argtypes = [C.c_void_p, C.c_int32, C.POINTER(LayerIO), C.POINTER(Diff), C.c_void_p]
+    L.tdk_restore_layers.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.POINTER(C.c_void_p), C.POINTER(C.c_void_p),
+                                     C.POINTER(LayerIO), C.POINTER(Diff), C.POINTER(PingPong), C.c_void_p, C.c_void_p]
     L.tdk_timing_enable.argtypes = [C.c_void_p, C.c_int32]
     L.tdk_timing_read.argtypes = [C.c_void_p, C.c_int32, C.POINTER(C.c_double), C.POINTER(C.c_int64)]
     L.tdk_timing_reset.argtypes = [C.c_void_p]
@@ -219,6 +225,26 @@ def tdk_diff_encode(r: Round, layer: int, io: LayerIO, eps: float, out: Diff, st
 def tdk_diff_decode(r: Round, layer: int, io: LayerIO, d: Diff, stream: int = 0) -> None:
     _check(load().tdk_diff_decode(r.handle, layer, C.byref(io), C.byref(d), C.c_void_p(stream)),
            "tdk_diff_decode")
+
+
+def pingpong(stage_k0, stage_k1, stage_v0, stage_v1, stage_bytes: int) -> PingPong:
+    pp = PingPong()
+    pp.stage_k[0], pp.stage_k[1] = _ptr(stage_k0), _ptr(stage_k1)
+    pp.stage_v[0], pp.stage_v[1] = _ptr(stage_v0), _ptr(stage_v1)
+    pp.stage_bytes = int(stage_bytes)
+    return pp
+
+
+def tdk_restore_layers(r: Round, first_layer: int, host_master_k, host_master_v, ios, diffs, pp: PingPong,
+                       compute_stream: int = 0, copy_stream: int = 0) -> None:
+    """host_master_k/v: per-layer pinned host tensors (or addresses); ios / diffs: per-layer LayerIO / Diff."""
+    n = len(ios)
+    hk = (C.c_void_p * max(n, 1))(*[_ptr(x) for x in host_master_k])
+    hv = (C.c_void_p * max(n, 1))(*[_ptr(x) for x in host_master_v])
+    io_arr = (LayerIO * max(n, 1))(*ios)
+    d_arr = (Diff * max(n, 1))(*diffs)
+    _check(load().tdk_restore_layers(r.handle, first_layer, n, hk, hv, io_arr, d_arr, C.byref(pp),
+                                     C.c_void_p(compute_stream), C.c_void_p(copy_stream)), "tdk_restore_layers")
 
 
 def tdk_timing_enable(r: Round, on: bool) -> None:

@@ -387,3 +387,32 @@ def test_flags_agree_between_math_modes_on_workload(tdo):
     da, db = a.encode(eps=5e-2), b.encode(eps=5e-2)
     # with eps above one bf16 ulp of the data range the two precisions take the same decisions
     assert np.array_equal(da.count, db.count)
+
+
+# ---------------------------------------------------------------------------
+# layerwise restore (Alg. 1)
+# ---------------------------------------------------------------------------
+
+def test_restore_layers_gives_back_every_layer(tdo):
+    """Alg. 1 over several layers: every layer's mirrors come back bit for bit, each from its own
+    master and its own diff (a mix-up of layers or of the two buffers would break it)."""
+    spec = small_spec(H=2, D=8, T=4, sessions=2, agents=3, blocks=3, block_tokens=7, frac=0.3, layers=5)
+    rnd = wl.make_round(spec)
+    runs, diffs, want = [], [], []
+    for layer in range(5):
+        run = OracleRun(tdo, rnd, layer=layer)
+        run.rerotate()
+        run.perturb()
+        diffs.append(run.encode())
+        want.append((run.pk.copy(), run.pv.copy()))
+        runs.append(run)
+    pools = [wl.pool_host(rnd, layer) for layer in range(5)]
+    tdo.restore_layers(runs[0].g, runs[0].hr, [r.mk for r in runs], [r.mv for r in runs],
+                       [p[0] for p in pools], [p[1] for p in pools], diffs)
+    mask = wl.shared_row_mask(rnd)
+    for layer in range(5):
+        assert np.array_equal(pools[layer][0][mask], want[layer][0][mask])
+        assert np.array_equal(pools[layer][1][mask], want[layer][1][mask])
+        fresh = wl.pool_host(rnd, layer)
+        assert np.array_equal(pools[layer][0][~mask], fresh[0][~mask])
+    assert not np.array_equal(want[0][0], want[1][0])
