@@ -34,7 +34,7 @@ def parse():
     ap.add_argument("--no-check", action="store_true")
     ap.add_argument("--alloc", default="fragmented", choices=["fragmented", "contiguous"],
                     help="physical page placement of the synthetic pool (fragmented = the graded recipe)")
-    ap.add_argument("--mode", default="step", choices=["step", "restore"],
+    ap.add_argument("--mode", default="step", choices=["step", "restore", "check"],
                     help="step: the whole hot path (default, the headline metric); restore: layerwise ping-pong "
                          "restore from pinned host memory (Alg. 1) against a dense restore")
     ap.add_argument("--layers", type=int, default=0, help="override the layer count (for profiling runs only)")
@@ -62,6 +62,8 @@ def main():
 
     if args.mode == "restore":
         return restore_mode(args, tdk, wl, np, torch, dev)
+    if args.mode == "check":
+        return check_mode(args, tdk, wl, np, torch, dev)
 
     spec = wl.CONFIGS[args.workload]
     L = args.layers or spec.num_layers
@@ -346,6 +348,73 @@ def restore_mode(args, tdk, wl, np, torch, dev):
                check=dict(pingpong_roundtrip_bitexact=ok))
     print(json.dumps(out))
     r.destroy(); r_dense.destroy()
+
+
+def check_mode(args, tdk, wl, np, torch, dev):
+    """The check-layer pass (Sec. 4.2) on its own: batched key-difference over the whole group, selection
+    of the important positions (ratio 15 %), master choice.  Fresh keys = the refreshed mirrors."""
+    spec = wl.CONFIGS[args.workload]
+    rnd = wl.make_round(spec, alloc=args.alloc)
+    A, T, RE = rnd.n_agents, spec.page_tokens, spec.row_elems
+    rows = rnd.pool_pages * T
+    st = torch.cuda.current_stream().cuda_stream
+    r = tdk.round_from_workload(rnd)
+    if args.group or args.flags != 0:
+        tdk.tdk_round_tune(r, args.group, args.flags)
+    ring = args.ring or 4
+    ratio = 0.15
+    n_tok = rnd.agent_tokens()
+    kmax = int(np.ceil(float(np.float32(ratio)) * spec.span_tokens))
+    slots = []
+    pert_rows = torch.from_numpy(wl.perturbed_rows(rnd)).to(dev)
+    for s in range(ring):
+        mk, mv = wl.master_device(rnd, s, dev)
+        pk = torch.zeros((rows, RE), dtype=torch.int16, device=dev)
+        pv = torch.zeros((rows, RE), dtype=torch.int16, device=dev)
+        io = tdk.layer_io(mk, mv, pk, pv, rnd.pool_pages)
+        tdk.tdk_rerotate_round(r, s, io, st)
+        wl.perturb_device(rnd, s, pk, pv, rows=pert_rows)
+        plan = dict(score=torch.zeros(n_tok, dtype=torch.float32, device=dev),
+                    imp=torch.zeros((A, kmax), dtype=torch.int32, device=dev),
+                    n=torch.zeros(A, dtype=torch.int32, device=dev), total=torch.zeros(A, dtype=torch.float32, device=dev),
+                    master=torch.zeros(rnd.n_sessions, dtype=torch.int32, device=dev))
+        plan["c"] = tdk.reuse_plan(plan["score"], plan["imp"], kmax, plan["n"], plan["total"], plan["master"])
+        slots.append(dict(io=io, plan=plan, keep=(mk, mv, pk, pv)))
+    torch.cuda.synchronize()
+    reps = max(1, args.steps) * 4
+    for s in slots:
+        tdk.tdk_check_layer(r, 0, s["io"], ratio, 0.0, s["plan"]["c"], st)
+    torch.cuda.synchronize()
+    tdk.tdk_timing_reset(r); tdk.tdk_timing_enable(r, True)
+    t0 = time.perf_counter()
+    for i in range(reps):
+        s = slots[i % ring]
+        tdk.tdk_check_layer(r, 0, s["io"], ratio, 0.0, s["plan"]["c"], st)
+    torch.cuda.synchronize()
+    wall_ms = (time.perf_counter() - t0) * 1e3 / reps
+    tdk.tdk_timing_enable(r, False)
+    us = {}
+    for k in (tdk.KERNEL_KEYDIFF, tdk.KERNEL_SELECT, tdk.KERNEL_MASTER):
+        ms, n = tdk.tdk_timing_read(r, k)
+        us[tdk.tdk_kernel_name(k)] = round(ms / n * 1e3, 2)
+    alg = (sum(int(x) for x in rnd.span_tokens) + n_tok) * (ROW_PAIR_BYTES // 2) + 4 * n_tok
+    ach = alg / (us["tdk_keydiff_kernel"] * 1e-6) / 1e9
+    # the refreshed tokens carry all the deviation: every agent's list must be exactly those tokens (up to k)
+    p0 = slots[0]["plan"]
+    n_imp = p0["n"].cpu().numpy(); imp = p0["imp"].cpu().numpy()
+    good = True
+    for i in range(A):
+        toks = np.concatenate([np.arange(p * T, min(spec.span_tokens, (p + 1) * T)) for p in rnd.perturbed[i]])
+        good &= int(n_imp[i]) == min(kmax, len(toks)) and bool(np.all(np.isin(imp[i, :n_imp[i]], toks)))
+    out = dict(metric="check-layer pass: batched key-difference GB/s, important-position selection and master choice",
+               value=round(ach, 1), unit="GB/s", n_gpus=1, steps=reps, higher_is_better=True, dtype="bf16", data="synthetic",
+               vs_baseline=None, config=dict(workload=args.workload, agents=A, span_tokens=int(spec.span_tokens), ratio=ratio),
+               ms_per_call=round(wall_ms, 4), kernels_avg_us=us,
+               roofline=dict(bound="hbm", kernel="tdk_keydiff_kernel", achieved=round(ach, 1), peak=HBM_PEAK_GBPS, unit="GB/s",
+                             frac=round(ach / HBM_PEAK_GBPS, 4), traffic=None, algorithmic_bytes_per_launch=alg),
+               check=dict(important_positions_are_the_refreshed_tokens=bool(good)))
+    print(json.dumps(out))
+    r.destroy()
 
 
 def read_traffic(workload, kernel):

@@ -149,6 +149,33 @@ tdk_status tdk_diff_encode(tdk_round* r, int32_t layer, const tdk_layer_io* io, 
 tdk_status tdk_diff_decode(tdk_round* r, int32_t layer, const tdk_layer_io* io, const tdk_diff* in,
                            void* hip_stream);
 
+/* Reuse plan of the check layer (Sec. 4.2 "Layerwise Collective Reuse" and "Reuse Plan Output"), all DEV,
+ * caller-owned.
+ *   score[sum_i S_i]              per-token deviation of agent i at master token m, agents in order:
+ *                                 sum over the K row of (fresh - rotated cached)^2 in fp32, where fresh
+ *                                 is the agent's K row in the pool and rotated cached is what
+ *                                 tdk_rerotate_round would write there
+ *   important[n_agents][k_stride] the agent's important positions (master token numbers), ascending
+ *   n_important[n_agents]         how many there are: min(ceil(ratio * S), #tokens with !(score <= min_score))
+ *   total[n_agents]               the agent's accumulated deviation (sum of its scores)
+ *   master[n_sessions]            agent with the lowest total in each session (first one on ties, NaN
+ *                                 totals count as +inf, -1 for a session without agents) */
+typedef struct {
+  float*   score;
+  int32_t* important;
+  int32_t  k_stride;      /* >= ceil(ratio * S) of every session that has agents */
+  int32_t* n_important;
+  float*   total;
+  int32_t* master;
+} tdk_reuse_plan;
+
+/* One batched key-difference pass over the whole group on the check layer, selection of the
+ * important positions of every request (the ceil(ratio * S) largest scores among tokens with
+ * !(score <= min_score); ties go to the lower token number) and the choice of each session's master.
+ * Reads pool_k and master_k only.  0 < ratio <= 1, min_score finite and >= 0. */
+tdk_status tdk_check_layer(tdk_round* r, int32_t layer, const tdk_layer_io* io, float ratio, float min_score,
+                           const tdk_reuse_plan* out, void* hip_stream);
+
 /* Ping-pong staging buffers of the layerwise restore, DEV, caller-owned: two K and two V buffers of
  * stage_bytes each, stage_bytes >= (sum_s S_s) * H * D * 2 (one layer of masters). */
 typedef struct {
@@ -180,7 +207,10 @@ tdk_status tdk_restore_layers(tdk_round* r, int32_t first_layer, int32_t n_layer
 #define TDK_KERNEL_GATHER   4
 #define TDK_KERNEL_DECODE   5
 #define TDK_KERNEL_SCATTER  6
-#define TDK_KERNEL_KINDS    7
+#define TDK_KERNEL_KEYDIFF  7
+#define TDK_KERNEL_SELECT   8
+#define TDK_KERNEL_MASTER   9
+#define TDK_KERNEL_KINDS    10
 tdk_status tdk_timing_enable(tdk_round* r, int32_t on);
 tdk_status tdk_timing_read(tdk_round* r, int32_t kernel, double* total_ms, int64_t* launches);
 tdk_status tdk_timing_reset(tdk_round* r);

@@ -399,6 +399,97 @@ int tdo_diff_decode(const tdo_geom* g, const tdo_round* r,
   return err ? -2 : 0;
 }
 
+/* ---- check layer: key-difference pass, important positions, master  [Sec. 4.2; Sec. 2.2] -------- */
+
+/* deviation of agent i at master token m: sum over the K row of (fresh - rotated cached)^2,
+ * accumulated in double.  score is agent-major: agent i's S_i scores follow those of agent i-1. */
+int tdo_key_deviation(const tdo_geom* g, const tdo_round* r,
+                      const uint16_t* master_k, const uint16_t* pool_k, int64_t pool_pages, double* score) {
+  if (!round_ok(g, r, pool_pages) || !master_k || !pool_k || !score) return -1;
+  const int64_t re = (int64_t)g->num_kv_heads * g->head_dim;
+  int64_t* base = (int64_t*)malloc(sizeof(int64_t) * (size_t)(r->n_agents + 1));
+  if (!base) return -2;
+  base[0] = 0;
+  for (int32_t i = 0; i < r->n_agents; ++i) base[i + 1] = base[i] + r->span_tokens[r->agent_session[i]];
+  int err = 0;
+#pragma omp parallel for schedule(dynamic, 1)
+  for (int32_t i = 0; i < r->n_agents; ++i) {
+    int32_t s = r->agent_session[i];
+    int64_t S = r->span_tokens[s];
+    int64_t row0 = session_row0(r, s);
+    rope_tab t;
+    uint16_t* ref = (uint16_t*)malloc((size_t)re * sizeof(uint16_t));
+    if (!ref || tab_init(&t, g, r->agent_pos0[i] - r->master_pos0[s])) { err = 1; free(ref); continue; }
+    for (int64_t m = 0; m < S; ++m) {
+      rotate_row_bf16(g, &t, master_k + (row0 + m) * re, ref);
+      const uint16_t* fresh = pool_k + slot_row(g, r, i, m) * re;
+      double acc = 0.0;
+      for (int64_t e = 0; e < re; ++e) {
+        double d = (double)bf16_to_f32(fresh[e]) - (double)bf16_to_f32(ref[e]);
+        acc += d * d;
+      }
+      score[base[i] + m] = acc;
+    }
+    free(ref);
+    tab_free(&t);
+  }
+  free(base);
+  return err ? -2 : 0;
+}
+
+typedef struct { float v; int32_t m; } scored;
+
+static int by_score_desc_then_index(const void* a, const void* b) {
+  const scored* x = (const scored*)a; const scored* y = (const scored*)b;
+  /* NaN ranks above everything */
+  int xn = x->v != x->v, yn = y->v != y->v;
+  if (xn != yn) return yn - xn;
+  if (!xn && x->v != y->v) return x->v > y->v ? -1 : 1;
+  return x->m < y->m ? -1 : (x->m > y->m);
+}
+
+static int by_index(const void* a, const void* b) {
+  int32_t x = *(const int32_t*)a, y = *(const int32_t*)b;
+  return x < y ? -1 : (x > y);
+}
+
+/* the k = ceil(ratio * S) tokens with the largest score among those with !(score <= min_score),
+ * ties to the lower token number; written in ascending token order.  Plain sort. */
+int tdo_select_important(const float* score, int64_t S, float ratio, float min_score,
+                         int32_t* out, int32_t* n_out) {
+  if (S < 0 || (S && !score) || !n_out || !(ratio > 0.0f) || !(ratio <= 1.0f)) return -1;
+  int64_t k = (int64_t)ceil((double)ratio * (double)S);
+  if (k > S) k = S;
+  scored* c = (scored*)malloc(sizeof(scored) * (size_t)(S > 0 ? S : 1));
+  if (!c) return -2;
+  int64_t n = 0;
+  for (int64_t m = 0; m < S; ++m)
+    if (!(score[m] <= min_score)) { c[n].v = score[m]; c[n].m = (int32_t)m; ++n; }
+  qsort(c, (size_t)n, sizeof(scored), by_score_desc_then_index);
+  if (k > n) k = n;
+  for (int64_t q = 0; q < k; ++q) out[q] = c[q].m;
+  qsort(out, (size_t)k, sizeof(int32_t), by_index);
+  *n_out = (int32_t)k;
+  free(c);
+  return 0;
+}
+
+/* master of each session = the agent with the lowest total deviation (NaN = +inf, first on ties) */
+int tdo_choose_master(const tdo_round* r, const float* total, int32_t* master) {
+  if (!r || (r->n_agents && !total) || (r->n_sessions && !master)) return -1;
+  for (int32_t s = 0; s < r->n_sessions; ++s) {
+    master[s] = -1;
+    float best = INFINITY;
+    for (int32_t i = 0; i < r->n_agents; ++i) {
+      if (r->agent_session[i] != s) continue;
+      float t = total[i];
+      if (t != t) t = INFINITY;
+      if (master[s] < 0 || t < best) { best = t; master[s] = i; }
+    }
+  }
+  return 0;
+}
+
 /* ---- layerwise restore of all layers  [Sec. 4.4, Alg. 1] ------------------
  * The algorithm as stated: two buffers alternate between "load" and "compute"; per layer the master
  * chunks are loaded into the load buffer, the buffers swap, and the compute buffer is corrected with

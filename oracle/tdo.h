@@ -92,6 +92,14 @@ int tdo_diff_decode(const tdo_geom* g, const tdo_round* r,
                     uint16_t* pool_k, uint16_t* pool_v, int64_t pool_pages,
                     const int32_t* count, const int64_t* offset, const int32_t* idx, const uint16_t* payload);
 
+/* Check layer (Sec. 4.2): per-token key deviation of every agent (double, agent-major), the selection of
+ * important positions from fp32 scores, and the master choice from fp32 totals. */
+int tdo_key_deviation(const tdo_geom* g, const tdo_round* r,
+                      const uint16_t* master_k, const uint16_t* pool_k, int64_t pool_pages, double* score);
+int tdo_select_important(const float* score, int64_t S, float ratio, float min_score,
+                         int32_t* out, int32_t* n_out);
+int tdo_choose_master(const tdo_round* r, const float* total, int32_t* master);
+
 /* Alg. 1 over n_layers layers: per-layer arrays of pointers (masters, pools and diffs of each layer). */
 int tdo_restore_layers(const tdo_geom* g, const tdo_round* r, int32_t n_layers,
                        const uint16_t* const* master_k, const uint16_t* const* master_v,

@@ -66,6 +66,9 @@ def lib() -> C.CDLL:
                                       [C.c_int64, C.c_float] + [C.c_void_p] * 4 + [C.c_int64, C.c_void_p])
         L.tdo_diff_decode.argtypes = ([C.POINTER(Geom), C.POINTER(RoundDesc)] + [C.c_void_p] * 4 +
                                       [C.c_int64] + [C.c_void_p] * 4)
+        L.tdo_key_deviation.argtypes = [C.POINTER(Geom), C.POINTER(RoundDesc), C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p]
+        L.tdo_select_important.argtypes = [C.c_void_p, C.c_int64, C.c_float, C.c_float, C.c_void_p, C.c_void_p]
+        L.tdo_choose_master.argtypes = [C.POINTER(RoundDesc), C.c_void_p, C.c_void_p]
         L.tdo_restore_layers.argtypes = ([C.POINTER(Geom), C.POINTER(RoundDesc), C.c_int32] +
                                          [C.POINTER(C.c_void_p)] * 4 + [C.c_int64] + [C.POINTER(C.c_void_p)] * 4)
         _lib = L
@@ -178,6 +181,30 @@ def diff_decode(g: Geom, hr: HostRound, master_k, master_v, pool_k, pool_v, d: D
     _chk(lib().tdo_diff_decode(C.byref(g), C.byref(hr.desc), _p(_u16(master_k)), _p(_u16(master_v)),
                                _p(_u16(pool_k)), _p(_u16(pool_v)), hr.pool_pages,
                                _p(d.count), _p(d.offset), _p(d.idx), _p(d.payload)), "diff_decode")
+
+
+def key_deviation(g: Geom, hr: HostRound, master_k, pool_k) -> np.ndarray:
+    n = int(sum(int(hr.span_tokens[s]) for s in hr.agent_session))
+    score = np.zeros(n, dtype=np.float64)
+    _chk(lib().tdo_key_deviation(C.byref(g), C.byref(hr.desc), _p(_u16(master_k)), _p(_u16(pool_k)),
+                                 hr.pool_pages, _p(score)), "key_deviation")
+    return score
+
+
+def select_important(score: np.ndarray, ratio: float, min_score: float) -> np.ndarray:
+    score = np.ascontiguousarray(score, dtype=np.float32)
+    out = np.zeros(max(len(score), 1), dtype=np.int32)
+    n = np.zeros(1, dtype=np.int32)
+    _chk(lib().tdo_select_important(_p(score), len(score), C.c_float(ratio), C.c_float(min_score), _p(out), _p(n)),
+         "select_important")
+    return out[:int(n[0])].copy()
+
+
+def choose_master(hr: HostRound, total: np.ndarray) -> np.ndarray:
+    total = np.ascontiguousarray(total, dtype=np.float32)
+    master = np.zeros(max(hr.desc.n_sessions, 1), dtype=np.int32)
+    _chk(lib().tdo_choose_master(C.byref(hr.desc), _p(total), _p(master)), "choose_master")
+    return master[:hr.desc.n_sessions].copy()
 
 
 def restore_layers(g: Geom, hr: HostRound, masters_k, masters_v, pools_k, pools_v, diffs) -> None:

@@ -61,6 +61,7 @@ struct tdk_round {
   hipEvent_t ev_free[2] = {nullptr, nullptr};
   bool free_recorded[2] = {false, false};
   int64_t total_master_rows = 0;
+  int64_t total_tokens = 0;        // sum over agents of their session's span
 
   bool timing = false;
   std::vector<EventPair> pending;
@@ -271,6 +272,9 @@ const char* tdk_kernel_name(int32_t kernel) {
     case TDK_KERNEL_GATHER: return "tdk_gather_kernel";
     case TDK_KERNEL_DECODE: return "tdk_decode_kernel";
     case TDK_KERNEL_SCATTER: return "tdk_scatter_kernel";
+    case TDK_KERNEL_KEYDIFF: return "tdk_keydiff_kernel";
+    case TDK_KERNEL_SELECT: return "tdk_select_kernel";
+    case TDK_KERNEL_MASTER: return "tdk_master_kernel";
   }
   return "";
 }
@@ -306,11 +310,11 @@ tdk_status tdk_round_create(const tdk_model* model, const tdk_session* sessions,
     hs.master_pos0 = sessions[s].master_pos0;
     hs.master_row0 = row0;
     row0 += hs.span;
-    sess_dev[s] = {hs.master_row0, hs.span, hs.pages};
+    sess_dev[s] = {hs.master_row0, hs.span, hs.pages, 0, 0};
     r->total_master_pages += hs.pages;
   }
   r->total_master_rows = row0;
-  int64_t flag_off = 0;
+  int64_t flag_off = 0, score_off = 0;
   for (int32_t i = 0; i < n_agents; ++i) {
     const tdk_agent& a = agents[i];
     if (a.session < 0 || a.session >= n_sessions) { delete r; return fail(TDK_ERR_INVALID_ARG, "agent: session index out of range"); }
@@ -331,7 +335,9 @@ tdk_status tdk_round_create(const tdk_model* model, const tdk_session* sessions,
     ad.bt_len = (int32_t)(lp_last - lp_first + 1);
     ad.session = a.session;
     ad.flag_off = (int32_t)flag_off;
-    ad.pad0 = ad.pad1 = 0;
+    ad.score_off = (int32_t)score_off;
+    ad.pad1 = 0;
+    score_off += S;
     for (int64_t lp = lp_first; lp <= lp_last; ++lp) {
       const int32_t pg = a.block_table[lp];
       if (pg < 0) { delete r; return fail(TDK_ERR_INVALID_ARG, "agent: negative page number in block_table"); }
@@ -339,7 +345,7 @@ tdk_status tdk_round_create(const tdk_model* model, const tdk_session* sessions,
       bt.push_back(pg);
     }
     flag_off += hs.pages;
-    if (flag_off >= (int64_t)1 << 31 || bt.size() >= (size_t)1 << 31) { delete r; return fail(TDK_ERR_UNSUPPORTED, "round too large"); }
+    if (flag_off >= (int64_t)1 << 31 || score_off >= (int64_t)1 << 31 || bt.size() >= (size_t)1 << 31) { delete r; return fail(TDK_ERR_UNSUPPORTED, "round too large"); }
     hs.agents.push_back(i);
 
     // rotation table of this agent's position delta: angles in double, one rounding to fp32
@@ -356,7 +362,13 @@ tdk_status tdk_round_create(const tdk_model* model, const tdk_session* sessions,
   r->total_pages = flag_off;
   std::vector<int32_t> order;
   order.reserve(n_agents);
-  for (const auto& hs : r->sessions) order.insert(order.end(), hs.agents.begin(), hs.agents.end());
+  for (size_t q = 0; q < r->sessions.size(); ++q) {
+    const auto& hs = r->sessions[q];
+    sess_dev[q].order_begin = (int32_t)order.size();
+    sess_dev[q].n_agents = (int32_t)hs.agents.size();
+    order.insert(order.end(), hs.agents.begin(), hs.agents.end());
+  }
+  r->total_tokens = score_off;
 
   // worst case for the work list: every agent its own group
   size_t work_cap = 0;
@@ -482,6 +494,33 @@ tdk_status tdk_diff_decode(tdk_round* r, int32_t layer, const tdk_layer_io* io, 
   TDK_LAUNCH(r, TDK_KERNEL_DECODE, s, launch_decode(r->rd, l, d, s));
   const int grid = (int)std::min<int64_t>(std::min<int64_t>(in->capacity_pages, r->total_pages), 1 << 20);
   TDK_LAUNCH(r, TDK_KERNEL_SCATTER, s, launch_scatter(r->rd, l, d, grid, s));
+  return TDK_OK;
+}
+
+tdk_status tdk_check_layer(tdk_round* r, int32_t layer, const tdk_layer_io* io, float ratio, float min_score,
+                           const tdk_reuse_plan* out, void* hip_stream) {
+  tdk_status st = check_step(r, layer, io);
+  if (st != TDK_OK) return st;
+  if (!out) return fail(TDK_ERR_INVALID_ARG, "reuse plan is NULL");
+  if (!(ratio > 0.0f) || !(ratio <= 1.0f)) return fail(TDK_ERR_INVALID_ARG, "ratio must be in (0, 1]");
+  if (!(min_score >= 0.0f) || !std::isfinite(min_score)) return fail(TDK_ERR_INVALID_ARG, "min_score must be finite and >= 0");
+  if (out->k_stride < 0) return fail(TDK_ERR_INVALID_ARG, "k_stride is negative");
+  if (r->n_agents && (!out->n_important || !out->total)) return fail(TDK_ERR_INVALID_ARG, "plan.n_important / plan.total is NULL");
+  if (r->total_tokens && !out->score) return fail(TDK_ERR_INVALID_ARG, "plan.score is NULL");
+  if (r->n_agents && out->k_stride > 0 && !out->important) return fail(TDK_ERR_INVALID_ARG, "plan.important is NULL");
+  if (!r->sessions.empty() && !out->master) return fail(TDK_ERR_INVALID_ARG, "plan.master is NULL");
+  for (const auto& hs : r->sessions) {
+    const int64_t k = (int64_t)std::ceil((double)ratio * (double)hs.span);
+    if (!hs.agents.empty() && k > out->k_stride) return fail(TDK_ERR_INVALID_ARG, "k_stride is smaller than ceil(ratio * span)");
+  }
+  PlanDev pl;
+  pl.score = out->score; pl.important = out->important; pl.n_important = out->n_important;
+  pl.total = out->total; pl.master = out->master; pl.k_stride = out->k_stride;
+  pl.ratio = ratio; pl.min_score = min_score;
+  hipStream_t s = static_cast<hipStream_t>(hip_stream);
+  TDK_LAUNCH(r, TDK_KERNEL_KEYDIFF, s, launch_keydiff(r->rd, layer_dev(io), pl, s));
+  TDK_LAUNCH(r, TDK_KERNEL_SELECT, s, launch_select(r->rd, pl, s));
+  TDK_LAUNCH(r, TDK_KERNEL_MASTER, s, launch_master(r->rd, pl, s));
   return TDK_OK;
 }
 

@@ -28,6 +28,8 @@ struct SessionDev {
   int64_t master_row0;  // first row of this session in master_k / master_v
   int32_t span;         // S
   int32_t pages;        // ceil(S / T)
+  int32_t order_begin;  // its agents are RoundDev::order[order_begin .. order_begin + n_agents)
+  int32_t n_agents;
 };
 
 struct AgentDev {
@@ -37,7 +39,8 @@ struct AgentDev {
   int32_t bt_len;       // entries in the slice
   int32_t session;
   int32_t flag_off;     // start of this agent's per-page flags in the flag scratch
-  int32_t pad0, pad1;
+  int32_t score_off;    // start of this agent's per-token scores (sum of the spans of earlier agents)
+  int32_t pad1;
 };
 
 struct RoundDev {
@@ -71,6 +74,18 @@ struct DiffDev {
   int32_t* overflow;
 };
 
+// Outputs of the check-layer pass (all device pointers).
+struct PlanDev {
+  float*   score;        // [sum_i S_i]
+  int32_t* important;    // [n_agents][k_stride]
+  int32_t* n_important;  // [n_agents]
+  float*   total;        // [n_agents]
+  int32_t* master;       // [n_sessions]
+  int32_t  k_stride;
+  float    ratio;
+  float    min_score;
+};
+
 // launchers (tdk_kernels.hip); each enqueues exactly one kernel
 hipError_t launch_rerotate(const RoundDev& rd, const LayerDev& io, hipStream_t st);
 hipError_t launch_flag(const RoundDev& rd, const LayerDev& io, float eps, hipStream_t st);
@@ -79,6 +94,9 @@ hipError_t launch_index(const RoundDev& rd, const DiffDev& d, hipStream_t st);
 hipError_t launch_gather(const RoundDev& rd, const LayerDev& io, const DiffDev& d, int grid, hipStream_t st);
 hipError_t launch_decode(const RoundDev& rd, const LayerDev& io, const DiffDev& d, hipStream_t st);
 hipError_t launch_scatter(const RoundDev& rd, const LayerDev& io, const DiffDev& d, int grid, hipStream_t st);
+hipError_t launch_keydiff(const RoundDev& rd, const LayerDev& io, const PlanDev& pl, hipStream_t st);
+hipError_t launch_select(const RoundDev& rd, const PlanDev& pl, hipStream_t st);
+hipError_t launch_master(const RoundDev& rd, const PlanDev& pl, hipStream_t st);
 hipError_t launch_copy(u32x4* dst, const u32x4* src, size_t n16, hipStream_t st);
 hipError_t launch_fill(u32x4* dst, uint32_t word, size_t n16, hipStream_t st);
 

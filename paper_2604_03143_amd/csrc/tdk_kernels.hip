@@ -13,6 +13,8 @@
 //     pair sit in the same lane and each load/store instruction covers whole 128-byte segments.
 #include "tdk_internal.h"
 
+#include <type_traits>
+
 namespace tdk {
 
 typedef float f32x2 __attribute__((ext_vector_type(2)));
@@ -146,7 +148,7 @@ struct MasterRows {
   bool  valid[RPW];
 };
 
-template <int RPW>
+template <int RPW, bool LOADV = true>
 __device__ __forceinline__ void load_master(const RoundDev& rd, const LayerDev& io, const WorkItem& w,
                                             const Lane& L, MasterRows<RPW>& M) {
   constexpr int T = RPW * kWaves;
@@ -163,8 +165,8 @@ __device__ __forceinline__ void load_master(const RoundDev& rd, const LayerDev& 
       const u32x4* rk = io.master_k + (sd.master_row0 + m) * row_u4;
       const u32x4* rv = io.master_v + (sd.master_row0 + m) * row_u4;
       if (L.kok) { M.kl[k] = rk[L.klo]; M.kh[k] = rk[L.khi]; }
-      if (L.v0ok) M.v0[k] = rv[L.v0];
-      if (L.v1ok) M.v1[k] = rv[L.v1];
+      if (LOADV && L.v0ok) M.v0[k] = rv[L.v0];
+      if (LOADV && L.v1ok) M.v1[k] = rv[L.v1];
     }
   }
 }
@@ -558,6 +560,197 @@ __global__ __launch_bounds__(kBlock) void tdk_fill_kernel(u32x4* __restrict__ ds
   for (size_t i = (size_t)blockIdx.x * kBlock + threadIdx.x; i < n; i += (size_t)gridDim.x * kBlock) dst[i] = v;
 }
 
+// ---------------------------------------------------------------------------------------------
+// check layer: batched key-difference pass, important positions, master choice   [Sec. 4.2]
+// ---------------------------------------------------------------------------------------------
+
+// Sum of v over the 64 lanes of a wavefront with DPP row shifts and row broadcasts (no LDS
+// traffic); the total is valid in lane 63 only.
+__device__ __forceinline__ float wave_sum_to_lane63(float v) {
+  auto dpp = [](float x, auto ctrl, auto row_mask) {
+    return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, x), decltype(ctrl)::value,
+                                                                   decltype(row_mask)::value, 0xf, false));
+  };
+  v += dpp(v, std::integral_constant<int, 0x111>{}, std::integral_constant<int, 0xf>{});   // row_shr:1
+  v += dpp(v, std::integral_constant<int, 0x112>{}, std::integral_constant<int, 0xf>{});   // row_shr:2
+  v += dpp(v, std::integral_constant<int, 0x114>{}, std::integral_constant<int, 0xf>{});   // row_shr:4
+  v += dpp(v, std::integral_constant<int, 0x118>{}, std::integral_constant<int, 0xf>{});   // row_shr:8 -> lane 15 of each row
+  v += dpp(v, std::integral_constant<int, 0x142>{}, std::integral_constant<int, 0xa>{});   // row_bcast:15 into rows 1, 3
+  v += dpp(v, std::integral_constant<int, 0x143>{}, std::integral_constant<int, 0xc>{});   // row_bcast:31 into rows 2, 3
+  return v;
+}
+
+// Per (agent, token): sum over the row of (fresh K - rotated cached K)^2, fp32.  Same traversal as
+// the compare kernel, K plane only; one float per row leaves each wavefront.
+template <int RPW, bool IL>
+__global__ __launch_bounds__(kBlock) void tdk_keydiff_kernel(const RoundDev rd, const LayerDev io, const PlanDev pl) {
+  constexpr int T = RPW * kWaves;
+  __shared__ GroupShared sh;
+  const WorkItem w = rd.work[blockIdx.x];
+  const Lane L = lane_geometry(rd.heads);
+  stage_group<T>(rd, w, sh);
+  MasterRows<RPW> M;
+  load_master<RPW, false>(rd, io, w, L, M);
+  __syncthreads();
+  const int wave = threadIdx.x >> 6;
+  const int64_t row_u4 = (int64_t)rd.heads * 16;
+  const u32x4* pk = io.pool_k;
+  for (int g = 0; g < w.ag_count; ++g) {
+    float c[8], s[8];
+    load_tab<IL>(sh, g, L.jb, c, s);
+    u32x4 akl[RPW], akh[RPW];
+    const u32x4 z = {0, 0, 0, 0};
+#pragma unroll
+    for (int k = 0; k < RPW; ++k) {
+      akl[k] = z; akh[k] = z;
+      if (!M.valid[k] || !L.kok) continue;
+      const int64_t base = dest_row<T>(sh, g, wave + kWaves * k) * row_u4;
+      akl[k] = pk[base + L.klo]; akh[k] = pk[base + L.khi];
+    }
+    const int score_off = rd.agents[sh.agent[g]].score_off;
+#pragma unroll
+    for (int k = 0; k < RPW; ++k) {
+      if (!M.valid[k]) continue;
+      float acc = 0.f;
+      if (L.kok) {
+        u32x4 rlo, rhi;
+        rotate16<IL>(M.kl[k], M.kh[k], c, s, rlo, rhi);
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+          float d0 = bf_lo(akl[k][q]) - bf_lo(rlo[q]), d1 = bf_hi(akl[k][q]) - bf_hi(rlo[q]);
+          float d2 = bf_lo(akh[k][q]) - bf_lo(rhi[q]), d3 = bf_hi(akh[k][q]) - bf_hi(rhi[q]);
+          acc = __builtin_fmaf(d0, d0, acc); acc = __builtin_fmaf(d1, d1, acc);
+          acc = __builtin_fmaf(d2, d2, acc); acc = __builtin_fmaf(d3, d3, acc);
+        }
+      }
+      acc = wave_sum_to_lane63(acc);
+      if ((threadIdx.x & 63) == 63) pl.score[score_off + w.page * T + wave + kWaves * k] = acc;
+    }
+  }
+}
+
+// rank of a set flag among the set flags of the workgroup (threads in order) and their total
+__device__ __forceinline__ int block_rank(bool f, int* s_wave, int& total) {
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const uint64_t b = __ballot(f);
+  const int in_wave = __popcll(b & ((1ull << lane) - 1ull));
+  __syncthreads();
+  if (lane == 0) s_wave[wave] = __popcll(b);
+  __syncthreads();
+  int before = 0;
+  total = 0;
+#pragma unroll
+  for (int q = 0; q < kWaves; ++q) { const int c = s_wave[q]; if (q < wave) before += c; total += c; }
+  return before + in_wave;
+}
+
+// Important positions of one agent: the k = ceil(ratio * S) tokens with the largest score among those
+// with !(score <= min_score), ties towards the lower token index, listed in ascending token order.
+// Radix select on the fp32 bit patterns (non-negative floats order like unsigned integers; NaN sorts
+// above everything), then an ordered compaction.  Also the agent's total deviation.
+__global__ __launch_bounds__(kBlock) void tdk_select_kernel(const RoundDev rd, const PlanDev pl) {
+  __shared__ uint32_t hist[256];
+  __shared__ int s_wave[kWaves];
+  __shared__ float s_sum[kWaves];
+  __shared__ uint32_t s_prefix, s_need;
+  const int a = blockIdx.x;
+  const AgentDev ad = rd.agents[a];
+  const int S = rd.sess[ad.session].span;
+  const float* sc = pl.score + ad.score_off;
+  const float min_score = pl.min_score;
+  auto key_of = [&](int m) -> uint32_t {
+    const float v = sc[m];
+    return !(v <= min_score) ? (__float_as_uint(v) & 0x7fffffffu) : 0u;
+  };
+  // total deviation and the number of candidates
+  float part = 0.f;
+  int cand = 0;
+  for (int m = threadIdx.x; m < S; m += kBlock) { part += sc[m]; cand += key_of(m) != 0u; }
+#pragma unroll
+  for (int sft = 32; sft > 0; sft >>= 1) { part += __shfl_xor(part, sft); cand += __shfl_xor(cand, sft); }
+  if ((threadIdx.x & 63) == 0) { s_sum[threadIdx.x >> 6] = part; s_wave[threadIdx.x >> 6] = cand; }
+  __syncthreads();
+  float total = 0.f;
+  int n_cand = 0;
+#pragma unroll
+  for (int q = 0; q < kWaves; ++q) { total += s_sum[q]; n_cand += s_wave[q]; }
+  if (threadIdx.x == 0) pl.total[a] = total;
+  int64_t k = (int64_t)ceil((double)pl.ratio * (double)S);
+  if (k > S) k = S;
+  if (k > pl.k_stride) k = pl.k_stride;
+  if (k > n_cand) k = n_cand;
+  if (k <= 0) {
+    if (threadIdx.x == 0) pl.n_important[a] = 0;
+    return;
+  }
+  // radix select: the key of the k-th largest candidate, 8 bits at a time from the top
+  if (threadIdx.x == 0) { s_prefix = 0u; s_need = (uint32_t)k; }
+  uint32_t mask = 0u;
+  for (int shift = 24; shift >= 0; shift -= 8) {
+    hist[threadIdx.x] = 0u;
+    __syncthreads();
+    const uint32_t prefix = s_prefix;
+    for (int m = threadIdx.x; m < S; m += kBlock) {
+      const uint32_t key = key_of(m);
+      if (key != 0u && (key & mask) == prefix) atomicAdd(&hist[(key >> shift) & 255u], 1u);
+    }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+      uint32_t need = s_need, cum = 0u;
+      int b = 255;
+      for (; b > 0; --b) {
+        if (cum + hist[b] >= need) break;
+        cum += hist[b];
+      }
+      s_need = need - cum;
+      s_prefix = prefix | ((uint32_t)b << shift);
+    }
+    mask |= 255u << shift;
+    __syncthreads();
+  }
+  const uint32_t tkey = s_prefix;
+  const int need_eq = (int)s_need;     // how many tokens equal to the threshold key are taken (the first ones)
+  int done_eq = 0, done_sel = 0;
+  int32_t* out = pl.important + (int64_t)a * pl.k_stride;
+  for (int m0 = 0; m0 < S; m0 += kBlock) {
+    const int m = m0 + threadIdx.x;
+    const uint32_t key = m < S ? key_of(m) : 0u;
+    const bool gt = key > tkey, eq = key != 0u && key == tkey;
+    int tot_eq, tot_sel;
+    const int r_eq = block_rank(eq, s_wave, tot_eq);
+    const bool sel = gt | (eq && done_eq + r_eq < need_eq);
+    const int r_sel = block_rank(sel, s_wave, tot_sel);
+    if (sel) out[done_sel + r_sel] = m;
+    done_eq += tot_eq;
+    done_sel += tot_sel;
+  }
+  if (threadIdx.x == 0) pl.n_important[a] = done_sel;
+}
+
+// Master of each session: the agent with the lowest total deviation (NaN counts as +inf; ties go to
+// the agent listed first).  One wavefront per session.
+__global__ __launch_bounds__(kBlock) void tdk_master_kernel(const RoundDev rd, const PlanDev pl) {
+  const int s = blockIdx.x * kWaves + (threadIdx.x >> 6);
+  const int lane = threadIdx.x & 63;
+  if (s >= rd.n_sessions) return;
+  const SessionDev sd = rd.sess[s];
+  float best = __builtin_inff();
+  int best_i = 0x7fffffff;
+  for (int q = lane; q < sd.n_agents; q += 64) {
+    const int a = rd.order[sd.order_begin + q];
+    float t = pl.total[a];
+    if (t != t) t = __builtin_inff();
+    if (t < best || (t == best && a < best_i)) { best = t; best_i = a; }
+  }
+#pragma unroll
+  for (int sft = 32; sft > 0; sft >>= 1) {
+    const float ob = __shfl_xor(best, sft);
+    const int oi = __shfl_xor(best_i, sft);
+    if (ob < best || (ob == best && oi < best_i)) { best = ob; best_i = oi; }
+  }
+  if (lane == 0) pl.master[s] = sd.n_agents ? best_i : -1;
+}
+
 // One workgroup per page: fills (or reads) page_u4 16-byte words of page ids[blockIdx.x].  With a
 // permuted id list this is the bare access pattern of the page kernels (whole pages at scattered
 // addresses) without any arithmetic: the bandwidth ceiling they are compared with.
@@ -653,6 +846,25 @@ hipError_t launch_decode(const RoundDev& rd, const LayerDev& io, const DiffDev& 
 hipError_t launch_scatter(const RoundDev& rd, const LayerDev& io, const DiffDev& d, int grid_size, hipStream_t st) {
   if (rd.n_agents == 0 || d.capacity == 0 || grid_size <= 0) return hipSuccess;
   hipLaunchKernelGGL(tdk_scatter_kernel, dim3(grid_size), dim3(kBlock), 0, st, rd, io, d);
+  return hipGetLastError();
+}
+
+hipError_t launch_keydiff(const RoundDev& rd, const LayerDev& io, const PlanDev& pl, hipStream_t st) {
+  if (rd.n_work == 0) return hipSuccess;
+  const dim3 grid(rd.n_work);
+  TDK_DISPATCH_RPW_IL(tdk_keydiff_kernel, rd, io, pl);
+  return hipGetLastError();
+}
+
+hipError_t launch_select(const RoundDev& rd, const PlanDev& pl, hipStream_t st) {
+  if (rd.n_agents == 0) return hipSuccess;
+  hipLaunchKernelGGL(tdk_select_kernel, dim3(rd.n_agents), dim3(kBlock), 0, st, rd, pl);
+  return hipGetLastError();
+}
+
+hipError_t launch_master(const RoundDev& rd, const PlanDev& pl, hipStream_t st) {
+  if (rd.n_sessions == 0) return hipSuccess;
+  hipLaunchKernelGGL(tdk_master_kernel, dim3((rd.n_sessions + kWaves - 1) / kWaves), dim3(kBlock), 0, st, rd, pl);
   return hipGetLastError();
 }
 

@@ -18,13 +18,14 @@ LIB_PATH = os.path.join(_PKG, "libtdk.so")
 OK, ERR_INVALID_ARG, ERR_UNSUPPORTED, ERR_CAPACITY, ERR_HIP, ERR_NOMEM = range(6)
 BF16 = 0
 ROPE_HALF, ROPE_INTERLEAVED = 0, 1
-KERNEL_REROTATE, KERNEL_FLAG, KERNEL_COUNT, KERNEL_INDEX, KERNEL_GATHER, KERNEL_DECODE, KERNEL_SCATTER = range(7)
-KERNEL_KINDS = 7
+(KERNEL_REROTATE, KERNEL_FLAG, KERNEL_COUNT, KERNEL_INDEX, KERNEL_GATHER, KERNEL_DECODE, KERNEL_SCATTER,
+ KERNEL_KEYDIFF, KERNEL_SELECT, KERNEL_MASTER) = range(10)
+KERNEL_KINDS = 10
 
 EXPORTS = (
     "tdk_status_str", "tdk_last_error", "tdk_version", "tdk_kernel_name",
     "tdk_round_create", "tdk_round_destroy", "tdk_scratch_bytes", "tdk_round_tune",
-    "tdk_rerotate_round", "tdk_diff_encode", "tdk_diff_decode", "tdk_restore_layers",
+    "tdk_rerotate_round", "tdk_diff_encode", "tdk_diff_decode", "tdk_restore_layers", "tdk_check_layer",
     "tdk_timing_enable", "tdk_timing_read", "tdk_timing_reset",
     "tdk_dense_bytes", "tdk_diff_bytes", "tdk_family_cost",
     "tdk_util_copy", "tdk_util_fill", "tdk_util_page_fill", "tdk_util_page_read",
@@ -54,6 +55,11 @@ class LayerIO(C.Structure):
 class Diff(C.Structure):
     _fields_ = [("count", C.c_void_p), ("offset", C.c_void_p), ("idx", C.c_void_p),
                 ("payload", C.c_void_p), ("capacity_pages", C.c_int64), ("overflow", C.c_void_p)]
+
+
+class ReusePlan(C.Structure):
+    _fields_ = [("score", C.c_void_p), ("important", C.c_void_p), ("k_stride", C.c_int32),
+                ("n_important", C.c_void_p), ("total", C.c_void_p), ("master", C.c_void_p)]
 
 
 class PingPong(C.Structure):
@@ -95,6 +101,8 @@ def load() -> C.CDLL:
     L.tdk_rerotate_round.argtypes = [C.c_void_p, C.c_int32, C.POINTER(LayerIO), C.c_void_p]
     L.tdk_diff_encode.argtypes = [C.c_void_p, C.c_int32, C.POINTER(LayerIO), C.c_float, C.POINTER(Diff), C.c_void_p]
     L.tdk_diff_decode.argtypes = [C.c_void_p, C.c_int32, C.POINTER(LayerIO), C.POINTER(Diff), C.c_void_p]
+    L.tdk_check_layer.argtypes = [C.c_void_p, C.c_int32, C.POINTER(LayerIO), C.c_float, C.c_float,
+                                  C.POINTER(ReusePlan), C.c_void_p]
     L.tdk_restore_layers.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.POINTER(C.c_void_p), C.POINTER(C.c_void_p),
                                      C.POINTER(LayerIO), C.POINTER(Diff), C.POINTER(PingPong), C.c_void_p, C.c_void_p]
     L.tdk_timing_enable.argtypes = [C.c_void_p, C.c_int32]
@@ -225,6 +233,16 @@ def tdk_diff_encode(r: Round, layer: int, io: LayerIO, eps: float, out: Diff, st
 def tdk_diff_decode(r: Round, layer: int, io: LayerIO, d: Diff, stream: int = 0) -> None:
     _check(load().tdk_diff_decode(r.handle, layer, C.byref(io), C.byref(d), C.c_void_p(stream)),
            "tdk_diff_decode")
+
+
+def reuse_plan(score, important, k_stride: int, n_important, total, master) -> ReusePlan:
+    return ReusePlan(_ptr(score), _ptr(important), int(k_stride), _ptr(n_important), _ptr(total), _ptr(master))
+
+
+def tdk_check_layer(r: Round, layer: int, io: LayerIO, ratio: float, min_score: float, plan: ReusePlan,
+                    stream: int = 0) -> None:
+    _check(load().tdk_check_layer(r.handle, layer, C.byref(io), C.c_float(ratio), C.c_float(min_score),
+                                  C.byref(plan), C.c_void_p(stream)), "tdk_check_layer")
 
 
 def pingpong(stage_k0, stage_k1, stage_v0, stage_v1, stage_bytes: int) -> PingPong:
