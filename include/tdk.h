@@ -83,6 +83,11 @@ typedef struct {
   int64_t        dst_pos0;         /* absolute position of its first shared token (history length) */
   const int32_t* block_table;      /* HOST: logical page -> physical page of the agent's sequence  */
   int32_t        block_table_len;  /* >= ceil((dst_pos0 + S) / T)                                  */
+  int64_t        diff_pos0;        /* position of its first shared token when the diff that will be
+                                      given to tdk_diff_decode / tdk_restore_layers was encoded: equal
+                                      to dst_pos0 for a diff of this round; for a mirror stored in an
+                                      earlier round its K values are re-rotated by dst_pos0 - diff_pos0
+                                      on restore (Alg. 1, RoPERecover(P_old, P_new)).  Ignored by encode. */
 } tdk_agent;
 
 typedef struct tdk_round tdk_round;   /* opaque: tables, descriptors, scratch on the current device */

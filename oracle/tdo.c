@@ -199,6 +199,7 @@ static int round_ok(const tdo_geom* g, const tdo_round* r, int64_t pool_pages) {
   for (int32_t i = 0; i < r->n_agents; ++i) {
     int32_t s = r->agent_session[i];
     if (s < 0 || s >= r->n_sessions || r->agent_pos0[i] < 0) return 0;
+    if (r->agent_diff_pos0 && r->agent_diff_pos0[i] < 0) return 0;
     int64_t len = r->bt_offset[i + 1] - r->bt_offset[i];
     int64_t S = r->span_tokens[s];
     if (S > 0) {
@@ -372,8 +373,11 @@ int tdo_diff_decode(const tdo_geom* g, const tdo_round* r,
     int64_t P = span_pages(g, S);
     int64_t row0 = session_row0(r, s);
     int64_t delta = r->agent_pos0[i] - r->master_pos0[s];
-    rope_tab t;
+    /* the diff values sit in the frame of the position they were encoded at */
+    int64_t delta_diff = r->agent_diff_pos0 ? r->agent_pos0[i] - r->agent_diff_pos0[i] : 0;
+    rope_tab t, td;
     if (tab_init(&t, g, delta)) { err = 1; continue; }
+    if (tab_init(&td, g, delta_diff)) { err = 1; tab_free(&t); continue; }
     for (int64_t p = 0; p < P; ++p) {
       /* is page p in this Mirror's diff? (plain linear search of its index list) */
       int64_t slot = -1;
@@ -386,7 +390,8 @@ int tdo_diff_decode(const tdo_geom* g, const tdo_round* r,
         if (slot >= 0) {
           const uint16_t* pk = payload + slot * 2 * T * re;
           const uint16_t* pv = pk + T * re;
-          memcpy(pool_k + dst * re, pk + q * re, (size_t)re * sizeof(uint16_t));
+          if (delta_diff == 0) memcpy(pool_k + dst * re, pk + q * re, (size_t)re * sizeof(uint16_t));
+          else rotate_row_bf16(g, &td, pk + q * re, pool_k + dst * re);
           memcpy(pool_v + dst * re, pv + q * re, (size_t)re * sizeof(uint16_t));
         } else {
           rotate_row_bf16(g, &t, master_k + (row0 + m) * re, pool_k + dst * re);
@@ -395,6 +400,7 @@ int tdo_diff_decode(const tdo_geom* g, const tdo_round* r,
       }
     }
     tab_free(&t);
+    tab_free(&td);
   }
   return err ? -2 : 0;
 }

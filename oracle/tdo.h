@@ -57,6 +57,8 @@ typedef struct {
   const int64_t* agent_pos0;
   const int32_t* bt_flat;
   const int64_t* bt_offset;
+  const int64_t* agent_diff_pos0; /* optional (NULL = agent_pos0): position of the agent's first shared token
+                                     when the diff given to tdo_diff_decode was encoded (an earlier round) */
 } tdo_round;
 
 /* cos/sin of phi_j = delta * theta^(-2j/D), j = 0 .. D/2-1 */
@@ -86,7 +88,9 @@ int tdo_diff_encode(const tdo_geom* g, const tdo_round* r,
                     int32_t* count, int64_t* offset, int32_t* idx, uint16_t* payload,
                     int64_t capacity_pages, int32_t* overflow);
 
-/* Restore every agent's shared span: diff pages from the payload, all other pages from the rotated master. */
+/* Restore every agent's shared span: diff pages from the payload, all other pages from the rotated master.
+ * Payload K rows were stored at position agent_diff_pos0 + m; they are re-rotated by
+ * agent_pos0 - agent_diff_pos0 (Alg. 1 "RoPERecover(P_old, P_new)"; nothing to do when that is 0), V copied. */
 int tdo_diff_decode(const tdo_geom* g, const tdo_round* r,
                     const uint16_t* master_k, const uint16_t* master_v,
                     uint16_t* pool_k, uint16_t* pool_v, int64_t pool_pages,

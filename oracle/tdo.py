@@ -39,7 +39,7 @@ class Geom(C.Structure):
 class RoundDesc(C.Structure):
     _fields_ = [("n_sessions", C.c_int32), ("span_tokens", C.c_void_p), ("master_pos0", C.c_void_p),
                 ("n_agents", C.c_int32), ("agent_session", C.c_void_p), ("agent_pos0", C.c_void_p),
-                ("bt_flat", C.c_void_p), ("bt_offset", C.c_void_p)]
+                ("bt_flat", C.c_void_p), ("bt_offset", C.c_void_p), ("agent_diff_pos0", C.c_void_p)]
 
 
 _lib: Optional[C.CDLL] = None
@@ -95,7 +95,7 @@ def geom_of(spec, math=MATH_F32, style=ROPE_HALF) -> Geom:
 class HostRound:
     """Flattened, contiguous host arrays of a workload Round, kept alive for the C calls."""
 
-    def __init__(self, rnd):
+    def __init__(self, rnd, diff_pos0=None):
         self.span_tokens = np.ascontiguousarray(rnd.span_tokens, dtype=np.int32)
         self.master_pos0 = np.ascontiguousarray(rnd.master_pos0, dtype=np.int64)
         self.agent_session = np.ascontiguousarray(rnd.agent_session, dtype=np.int32)
@@ -106,7 +106,11 @@ class HostRound:
                         if len(rnd.block_tables) else np.zeros(0, np.int32))
         self.desc = RoundDesc(len(self.span_tokens), _p(self.span_tokens), _p(self.master_pos0),
                               len(self.agent_session), _p(self.agent_session), _p(self.agent_pos0),
-                              _p(self.bt_flat), _p(self.bt_offset))
+                              _p(self.bt_flat), _p(self.bt_offset), None)
+        self.diff_pos0 = None
+        if diff_pos0 is not None:
+            self.diff_pos0 = np.ascontiguousarray(diff_pos0, dtype=np.int64)
+            self.desc.agent_diff_pos0 = _p(self.diff_pos0)
         self.pool_pages = int(rnd.pool_pages)
 
 

@@ -299,6 +299,7 @@ tdk_status tdk_round_create(const tdk_model* model, const tdk_session* sessions,
   std::vector<AgentDev> agent_dev(n_agents);
   std::vector<int32_t> bt;
   std::vector<float> tab((size_t)n_agents * 2 * kHalf);
+  std::vector<float> tab_diff((size_t)n_agents * 2 * kHalf);
   r->sessions.resize(n_sessions);
   int64_t row0 = 0;
   for (int32_t s = 0; s < n_sessions; ++s) {
@@ -336,7 +337,8 @@ tdk_status tdk_round_create(const tdk_model* model, const tdk_session* sessions,
     ad.session = a.session;
     ad.flag_off = (int32_t)flag_off;
     ad.score_off = (int32_t)score_off;
-    ad.pad1 = 0;
+    if (a.diff_pos0 < 0) { delete r; return fail(TDK_ERR_INVALID_ARG, "agent: negative diff_pos0"); }
+    ad.diff_rot = a.diff_pos0 != a.dst_pos0;
     score_off += S;
     for (int64_t lp = lp_first; lp <= lp_last; ++lp) {
       const int32_t pg = a.block_table[lp];
@@ -348,15 +350,19 @@ tdk_status tdk_round_create(const tdk_model* model, const tdk_session* sessions,
     if (flag_off >= (int64_t)1 << 31 || score_off >= (int64_t)1 << 31 || bt.size() >= (size_t)1 << 31) { delete r; return fail(TDK_ERR_UNSUPPORTED, "round too large"); }
     hs.agents.push_back(i);
 
-    // rotation table of this agent's position delta: angles in double, one rounding to fp32
-    const double delta = (double)(a.dst_pos0 - hs.master_pos0);
-    float* c = tab.data() + (size_t)i * 2 * kHalf;
-    float* sn = c + kHalf;
-    for (int j = 0; j < kHalf; ++j) {
-      const double inv_freq = std::pow(model->rope_theta, -(double)(2 * j) / (double)model->head_dim);
-      const double phi = delta * inv_freq;
-      c[j] = (float)std::cos(phi);
-      sn[j] = (float)std::sin(phi);
+    // rotation tables of this agent: master frame -> its offset, and the frame its stored diff values
+    // were encoded in -> its offset.  Angles in double, one rounding to fp32.
+    const double deltas[2] = {(double)(a.dst_pos0 - hs.master_pos0), (double)(a.dst_pos0 - a.diff_pos0)};
+    float* tabs[2] = {tab.data() + (size_t)i * 2 * kHalf, tab_diff.data() + (size_t)i * 2 * kHalf};
+    for (int which = 0; which < 2; ++which) {
+      float* c = tabs[which];
+      float* sn = c + kHalf;
+      for (int j = 0; j < kHalf; ++j) {
+        const double inv_freq = std::pow(model->rope_theta, -(double)(2 * j) / (double)model->head_dim);
+        const double phi = deltas[which] * inv_freq;
+        c[j] = (float)std::cos(phi);
+        sn[j] = (float)std::sin(phi);
+      }
     }
   }
   r->total_pages = flag_off;
@@ -384,6 +390,7 @@ tdk_status tdk_round_create(const tdk_model* model, const tdk_session* sessions,
   const size_t o_order = place(order.size() * sizeof(int32_t));
   const size_t o_bt = place(bt.size() * sizeof(int32_t));
   const size_t o_tab = place(tab.size() * sizeof(float));
+  const size_t o_tab_diff = place(tab_diff.size() * sizeof(float));
   const size_t o_flags = place((size_t)flag_off);
   r->blob_bytes = std::max<size_t>(off, 256);
 
@@ -400,6 +407,7 @@ tdk_status tdk_round_create(const tdk_model* model, const tdk_session* sessions,
   if (e == hipSuccess) e = up(o_order, order.data(), order.size() * sizeof(int32_t));
   if (e == hipSuccess) e = up(o_bt, bt.data(), bt.size() * sizeof(int32_t));
   if (e == hipSuccess) e = up(o_tab, tab.data(), tab.size() * sizeof(float));
+  if (e == hipSuccess) e = up(o_tab_diff, tab_diff.data(), tab_diff.size() * sizeof(float));
   if (e == hipSuccess && flag_off) e = hipMemset(base + o_flags, 0, (size_t)flag_off);
   if (e != hipSuccess) { (void)hipFree(r->blob); delete r; return hip_fail(e, "upload of round descriptors"); }
 
@@ -409,6 +417,7 @@ tdk_status tdk_round_create(const tdk_model* model, const tdk_session* sessions,
   r->rd.order = reinterpret_cast<const int32_t*>(base + o_order);
   r->rd.bt = reinterpret_cast<const int32_t*>(base + o_bt);
   r->rd.tab = reinterpret_cast<const float*>(base + o_tab);
+  r->rd.tab_diff = reinterpret_cast<const float*>(base + o_tab_diff);
   r->rd.flags = reinterpret_cast<uint8_t*>(base + o_flags);
   r->rd.n_agents = n_agents;
   r->rd.n_sessions = n_sessions;

@@ -40,7 +40,7 @@ struct AgentDev {
   int32_t session;
   int32_t flag_off;     // start of this agent's per-page flags in the flag scratch
   int32_t score_off;    // start of this agent's per-token scores (sum of the spans of earlier agents)
-  int32_t pad1;
+  int32_t diff_rot;     // 1: payload K rows of this agent were stored at another position (re-rotate on restore)
 };
 
 struct RoundDev {
@@ -50,6 +50,7 @@ struct RoundDev {
   const int32_t*    order;   // agent ids grouped by session
   const int32_t*    bt;      // block-table slices, concatenated
   const float*      tab;     // [n_agents][2][64]: cos then sin of the agent's delta
+  const float*      tab_diff;  // [n_agents][2][64]: same for dst_pos0 - diff_pos0 (payload re-rotation)
   uint8_t*          flags;   // [sum_i pages_i] scratch of encode
   int32_t n_work, n_agents, n_sessions;
   int32_t heads;             // H

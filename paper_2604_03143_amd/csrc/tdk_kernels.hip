@@ -491,8 +491,10 @@ __global__ __launch_bounds__(kBlock) void tdk_decode_kernel(const RoundDev rd, c
 // The "correct" half of skip-or-correct: pages listed in a diff are copied from the payload to the
 // agent's rows (the mirror image of the gather kernel).  Every pool row is written exactly once by
 // either this kernel or the page kernel above, so their order does not matter.
+template <bool IL>
 __global__ __launch_bounds__(kBlock) void tdk_scatter_kernel(const RoundDev rd, const LayerDev io, const DiffDev d) {
   __shared__ SlotShared sh;
+  __shared__ float s_tab[2 * kHalf];       // cos/sin of the owner's payload re-rotation
   const int T = rd.page_tokens;
   const int A = rd.n_agents;
   if (A == 0) return;
@@ -500,11 +502,14 @@ __global__ __launch_bounds__(kBlock) void tdk_scatter_kernel(const RoundDev rd, 
   if (total > d.capacity) total = d.capacity;
   const int row_u4 = rd.heads * 16;
   const int page_u4 = T * row_u4;
+  const Lane L = lane_geometry(rd.heads);
   for (int64_t slot = blockIdx.x; slot < total; slot += gridDim.x) {
     if (threadIdx.x == 0) sh.owner = -1;
     __syncthreads();
     find_owner(d, A, slot, sh);
     __syncthreads();
+    bool rot = false;
+    if (sh.owner >= 0) rot = rd.agents[sh.owner].diff_rot != 0;
     if (threadIdx.x < T) {
       int64_t row = -1;
       if (sh.owner >= 0) {                       // an inconsistent offset[] leaves the slot unowned
@@ -519,11 +524,36 @@ __global__ __launch_bounds__(kBlock) void tdk_scatter_kernel(const RoundDev rd, 
       }
       sh.row[threadIdx.x] = row;
     }
+    if (rot && threadIdx.x < 2 * kHalf) s_tab[threadIdx.x] = rd.tab_diff[(size_t)sh.owner * (2 * kHalf) + threadIdx.x];
     __syncthreads();
 #pragma unroll 1
     for (int plane = 0; plane < 2; ++plane) {
       u32x4* dst = plane ? io.pool_v : io.pool_k;
       const u32x4* src = d.payload + (slot * 2 + plane) * (int64_t)page_u4;
+      if (plane == 0 && rot) {
+        // stored at another position: K rows are re-rotated, a wavefront per row, both members of a
+        // pair in one lane (the page kernels' lane layout)
+        float c[8], sn[8];
+        if (!IL) {
+#pragma unroll
+          for (int e = 0; e < 8; ++e) { c[e] = s_tab[L.jb * 8 + e]; sn[e] = s_tab[kHalf + L.jb * 8 + e]; }
+        } else {
+#pragma unroll
+          for (int e = 0; e < 4; ++e) {
+            c[e] = s_tab[L.jb * 4 + e];          sn[e] = s_tab[kHalf + L.jb * 4 + e];
+            c[4 + e] = s_tab[32 + L.jb * 4 + e]; sn[4 + e] = s_tab[kHalf + 32 + L.jb * 4 + e];
+          }
+        }
+        for (int r = threadIdx.x >> 6; r < T; r += kWaves) {
+          const int64_t row = sh.row[r];
+          if (row < 0 || !L.kok) continue;
+          u32x4 olo, ohi;
+          rotate16<IL>(src[r * row_u4 + L.klo], src[r * row_u4 + L.khi], c, sn, olo, ohi);
+          dst[row * row_u4 + L.klo] = olo;
+          dst[row * row_u4 + L.khi] = ohi;
+        }
+        continue;
+      }
       for (int i0 = threadIdx.x; i0 < page_u4; i0 += kBlock * kCopyBatch) {
         u32x4 v[kCopyBatch];
 #pragma unroll
@@ -845,7 +875,8 @@ hipError_t launch_decode(const RoundDev& rd, const LayerDev& io, const DiffDev& 
 
 hipError_t launch_scatter(const RoundDev& rd, const LayerDev& io, const DiffDev& d, int grid_size, hipStream_t st) {
   if (rd.n_agents == 0 || d.capacity == 0 || grid_size <= 0) return hipSuccess;
-  hipLaunchKernelGGL(tdk_scatter_kernel, dim3(grid_size), dim3(kBlock), 0, st, rd, io, d);
+  if (rd.interleaved) hipLaunchKernelGGL(tdk_scatter_kernel<true>, dim3(grid_size), dim3(kBlock), 0, st, rd, io, d);
+  else hipLaunchKernelGGL(tdk_scatter_kernel<false>, dim3(grid_size), dim3(kBlock), 0, st, rd, io, d);
   return hipGetLastError();
 }
 

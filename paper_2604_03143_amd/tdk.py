@@ -44,7 +44,7 @@ class Session(C.Structure):
 
 class Agent(C.Structure):
     _fields_ = [("session", C.c_int32), ("dst_pos0", C.c_int64), ("block_table", C.c_void_p),
-                ("block_table_len", C.c_int32)]
+                ("block_table_len", C.c_int32), ("diff_pos0", C.c_int64)]
 
 
 class LayerIO(C.Structure):
@@ -177,7 +177,7 @@ class Round:
 
 def tdk_round_create(mdl: Model, span_tokens: Sequence[int], master_pos0: Sequence[int],
                      agent_session: Sequence[int], agent_pos0: Sequence[int],
-                     block_tables: Sequence[np.ndarray]) -> Round:
+                     block_tables: Sequence[np.ndarray], agent_diff_pos0: Optional[Sequence[int]] = None) -> Round:
     ns, na = len(span_tokens), len(agent_session)
     sess = (Session * max(ns, 1))()
     for s in range(ns):
@@ -187,18 +187,19 @@ def tdk_round_create(mdl: Model, span_tokens: Sequence[int], master_pos0: Sequen
     for i in range(na):
         bt = np.ascontiguousarray(block_tables[i], dtype=np.int32)
         keep.append(bt)
-        ags[i] = Agent(int(agent_session[i]), int(agent_pos0[i]), bt.ctypes.data, len(bt))
+        dp = int(agent_pos0[i]) if agent_diff_pos0 is None else int(agent_diff_pos0[i])
+        ags[i] = Agent(int(agent_session[i]), int(agent_pos0[i]), bt.ctypes.data, len(bt), dp)
     out = C.c_void_p()
     _check(load().tdk_round_create(C.byref(mdl), sess, ns, ags, na, C.byref(out)), "tdk_round_create")
     return Round(out.value, na, None)
 
 
-def round_from_workload(rnd, style=ROPE_HALF) -> Round:
+def round_from_workload(rnd, style=ROPE_HALF, diff_pos0=None) -> Round:
     """Convenience: a tdk round for a workload.Round (marshalling only)."""
     sp = rnd.spec
     mdl = model(sp.num_layers, sp.num_kv_heads, sp.head_dim, sp.page_tokens, sp.rope_theta, style)
     return tdk_round_create(mdl, rnd.span_tokens, rnd.master_pos0, rnd.agent_session, rnd.agent_pos0,
-                            rnd.block_tables)
+                            rnd.block_tables, diff_pos0)
 
 
 def tdk_round_destroy(r: Round) -> None:

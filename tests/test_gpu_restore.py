@@ -83,3 +83,34 @@ def test_pingpong_restore_matches_oracle_per_layer(tdo):
     finally:
         torch.cuda.synchronize()
         r.destroy()
+
+
+@pytest.mark.parametrize("style,T", [(0, 16), (1, 16), (0, 32)])
+def test_restore_at_new_offsets_matches_oracle(tdo, style, T):
+    """A mirror stored in one round is restored in the next, where every history has grown: diff pages
+    are re-rotated from the position they were encoded at, the rest comes from the master."""
+    import torch
+    from paper_2604_03143_amd import tdk
+    import gpu_helpers as gh
+    spec = wl.RoundSpec("next", 56, 1, 8, 128, T, 1.0e6, 2, 4, 3, 70, 5, 300, 0.2)
+    old = wl.make_round(spec)
+    o = OracleRun(tdo, old, style=style)
+    o.rerotate(); o.perturb()
+    d = o.encode()
+    grow = np.array([0, 16, 7, 250, 1, 31, 1000, 64], np.int64)
+    new = wl.make_round(spec, hist=old.agent_pos0 + grow)
+    opk, opv = wl.pool_host(new, 0)
+    tdo.diff_decode(o.g, tdo.HostRound(new, diff_pos0=old.agent_pos0), o.mk, o.mv, opk, opv, d)
+    n = int(d.offset[-1])
+    g = gh.GpuRun(new, style=style, mk=o.mk, mv=o.mv)
+    g.r.destroy()
+    g.r = tdk.round_from_workload(new, style=style, diff_pos0=old.agent_pos0)
+    try:
+        cnt, off = torch.from_numpy(d.count).cuda(), torch.from_numpy(d.offset).cuda()
+        idx, pay = torch.from_numpy(d.idx[:n].copy()).cuda(), gh.up(d.payload[:n].copy())
+        dd = tdk.diff(cnt, off, idx, pay, n, torch.zeros(1, dtype=torch.int32, device="cuda"))
+        tdk.tdk_diff_decode(g.r, 0, g.io, dd, g.stream)
+        gk, gv = g.pool()
+        assert np.array_equal(gk, opk) and np.array_equal(gv, opv)
+    finally:
+        g.close()

@@ -416,3 +416,62 @@ def test_restore_layers_gives_back_every_layer(tdo):
         fresh = wl.pool_host(rnd, layer)
         assert np.array_equal(pools[layer][0][~mask], fresh[0][~mask])
     assert not np.array_equal(want[0][0], want[1][0])
+
+
+# ---------------------------------------------------------------------------
+# restore at a new round's offsets (Alg. 1: RoPERecover(P_old, P_new) on the stored values)
+# ---------------------------------------------------------------------------
+
+def _next_round(rnd, grow):
+    """The same agents one round later: histories grew, pages were re-allocated."""
+    spec = rnd.spec
+    new = wl.make_round(spec, hist=rnd.agent_pos0 + grow)
+    new.perturbed = rnd.perturbed
+    return new
+
+
+def test_restore_at_new_offsets(tdo):
+    spec = small_spec(H=2, D=8, T=4, sessions=2, agents=3, blocks=3, block_tokens=7, frac=0.3, theta=1.0e4)
+    old = wl.make_round(spec)
+    run = OracleRun(tdo, old)
+    run.rerotate(); run.perturb()
+    d = run.encode()
+    assert d.offset[-1] > 0
+    grow = np.array([5, 0, 17, 8, 33, 4], np.int64)       # agent 1 did not move
+    new = _next_round(old, grow)
+    g = run.g
+    hr_new = tdo.HostRound(new, diff_pos0=old.agent_pos0)
+    pk, pv = wl.pool_host(new, 0)
+    tdo.diff_decode(g, hr_new, run.mk, run.mv, pk, pv, d)
+    # what a plain collective rerotate writes at the new offsets
+    rk, rv = wl.pool_host(new, 0)
+    tdo.rerotate_round(g, tdo.HostRound(new), run.mk, run.mv, rk, rv)
+    T, re = spec.page_tokens, spec.row_elems
+    S = spec.span_tokens
+    j = np.arange(spec.head_dim // 2)
+    for i in range(new.n_agents):
+        listed = set(d.idx[int(d.offset[i]):int(d.offset[i + 1])].tolist())
+        assert listed == set(old.perturbed[i].tolist())
+        w = np.exp(1j * (int(grow[i]) * np.power(spec.rope_theta, -2.0 * j / spec.head_dim)))
+        for p in range(spec.span_pages):
+            toks = np.arange(p * T, min(S, (p + 1) * T))
+            rows_new = new.dst_rows(i, toks)
+            if p not in listed:
+                assert np.array_equal(pk[rows_new], rk[rows_new]) and np.array_equal(pv[rows_new], rv[rows_new])
+                continue
+            rows_old = old.dst_rows(i, toks)
+            assert np.array_equal(pv[rows_new], run.pv[rows_old])            # V: copied
+            stored = wl.bf16_bits_to_f32(run.pk[rows_old]).astype(np.float64).reshape(len(toks), 2, 8)
+            z = (stored[..., :4] + 1j * stored[..., 4:]) * w                   # separate evaluator
+            exact = np.concatenate([z.real, z.imag], axis=-1).reshape(len(toks), -1)
+            got = wl.bf16_bits_to_f32(pk[rows_new]).astype(np.float64)
+            if grow[i] == 0:
+                assert np.array_equal(pk[rows_new], run.pk[rows_old])        # same position: bit copy
+            else:
+                assert np.all(np.abs(got - exact) <= 0.5 * bf16_ulp(exact) + 1e-6)
+                assert np.max(np.abs(got - stored.reshape(len(toks), -1))) > 1e-3   # it did move
+    # diff_pos0 equal to the current positions is the plain restore
+    pk2, pv2 = wl.pool_host(old, 0)
+    tdo.diff_decode(g, tdo.HostRound(old, diff_pos0=old.agent_pos0), run.mk, run.mv, pk2, pv2, d)
+    mask = wl.shared_row_mask(old)
+    assert np.array_equal(pk2[mask], run.pk[mask]) and np.array_equal(pv2[mask], run.pv[mask])
