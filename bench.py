@@ -34,7 +34,7 @@ def parse():
     ap.add_argument("--no-check", action="store_true")
     ap.add_argument("--alloc", default="fragmented", choices=["fragmented", "contiguous"],
                     help="physical page placement of the synthetic pool (fragmented = the graded recipe)")
-    ap.add_argument("--mode", default="step", choices=["step", "restore", "check"],
+    ap.add_argument("--mode", default="step", choices=["step", "restore", "check", "planes"],
                     help="step: the whole hot path (default, the headline metric); restore: layerwise ping-pong "
                          "restore from pinned host memory (Alg. 1) against a dense restore")
     ap.add_argument("--layers", type=int, default=0, help="override the layer count (for profiling runs only)")
@@ -64,6 +64,8 @@ def main():
         return restore_mode(args, tdk, wl, np, torch, dev)
     if args.mode == "check":
         return check_mode(args, tdk, wl, np, torch, dev)
+    if args.mode == "planes":
+        return planes_mode(args, tdk, wl, np, torch, dev)
 
     spec = wl.CONFIGS[args.workload]
     L = args.layers or spec.num_layers
@@ -413,6 +415,78 @@ def check_mode(args, tdk, wl, np, torch, dev):
                roofline=dict(bound="hbm", kernel="tdk_keydiff_kernel", achieved=round(ach, 1), peak=HBM_PEAK_GBPS, unit="GB/s",
                              frac=round(ach / HBM_PEAK_GBPS, 4), traffic=None, algorithmic_bytes_per_launch=alg),
                check=dict(important_positions_are_the_refreshed_tokens=bool(good)))
+    print(json.dumps(out))
+    r.destroy()
+
+
+def planes_mode(args, tdk, wl, np, torch, dev):
+    """Single-plane diffs (separate K and V index lists, Sec. 5) against the paired diff: the same
+    mirrors encoded and restored plane by plane."""
+    spec = wl.CONFIGS[args.workload]
+    rnd = wl.make_round(spec, alloc=args.alloc)
+    A, T, RE = rnd.n_agents, spec.page_tokens, spec.row_elems
+    rows = rnd.pool_pages * T
+    st = torch.cuda.current_stream().cuda_stream
+    r = tdk.round_from_workload(rnd)
+    n_pert = sum(len(p) for p in rnd.perturbed)
+    cap = n_pert + 64
+    mk, mv = wl.master_device(rnd, 0, dev)
+    pk = torch.zeros((rows, RE), dtype=torch.int16, device=dev)
+    pv = torch.zeros((rows, RE), dtype=torch.int16, device=dev)
+    io = tdk.layer_io(mk, mv, pk, pv, rnd.pool_pages)
+    tdk.tdk_rerotate_round(r, 0, io, st)
+    wl.perturb_device(rnd, 0, pk, pv)
+    want_k, want_v = pk.clone(), pv.clone()
+
+    def new_diff(planes):
+        d = dict(count=torch.zeros(A, dtype=torch.int32, device=dev), offset=torch.zeros(A + 1, dtype=torch.int64, device=dev),
+                 idx=torch.full((cap,), -1, dtype=torch.int32, device=dev),
+                 payload=torch.zeros((cap, planes * T * RE), dtype=torch.int16, device=dev),
+                 overflow=torch.zeros(1, dtype=torch.int32, device=dev))
+        d["c"] = tdk.diff(d["count"], d["offset"], d["idx"], d["payload"], cap, d["overflow"])
+        return d
+
+    dp, dk, dv = new_diff(2), new_diff(1), new_diff(1)
+
+    def timed(fn, reps=10):
+        fn(); fn()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(reps):
+            fn()
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) * 1e3 / reps      # us
+
+    t = {}
+    t["encode_paired"] = timed(lambda: tdk.tdk_diff_encode(r, 0, io, spec.eps, dp["c"], st))
+    t["encode_K"] = timed(lambda: tdk.tdk_diff_encode_plane(r, 0, io, spec.eps, tdk.PLANE_K, dk["c"], st))
+    t["encode_V"] = timed(lambda: tdk.tdk_diff_encode_plane(r, 0, io, spec.eps, tdk.PLANE_V, dv["c"], st))
+    t["decode_paired"] = timed(lambda: tdk.tdk_diff_decode(r, 0, io, dp["c"], st))
+    t["decode_K"] = timed(lambda: tdk.tdk_diff_decode_plane(r, 0, io, tdk.PLANE_K, dk["c"], st))
+    t["decode_V"] = timed(lambda: tdk.tdk_diff_decode_plane(r, 0, io, tdk.PLANE_V, dv["c"], st))
+    pk.zero_(); pv.zero_()
+    tdk.tdk_diff_decode_plane(r, 0, io, tdk.PLANE_K, dk["c"], st)
+    tdk.tdk_diff_decode_plane(r, 0, io, tdk.PLANE_V, dv["c"], st)
+    torch.cuda.synchronize()
+    ok = bool(torch.equal(pk, want_k) and torch.equal(pv, want_v))
+    same_lists = bool(torch.equal(dk["idx"][:n_pert], dp["idx"][:n_pert]) and torch.equal(dv["idx"][:n_pert], dp["idx"][:n_pert]))
+    half = ROW_PAIR_BYTES // 2
+    master_b = sum(int(x) for x in rnd.span_tokens) * half
+    agents_b = rnd.agent_tokens() * half
+    payload_b = n_pert * T * RE * 2
+    one = master_b + agents_b + payload_b
+    gb = lambda nbytes, us: round(nbytes / (us * 1e-6) / 1e9, 1)
+    out = dict(metric="single-plane diff encode / decode GB/s (algorithmic bytes) against the paired diff",
+               value=gb(2 * one, t["encode_K"] + t["encode_V"]), unit="GB/s", n_gpus=1, higher_is_better=True,
+               dtype="bf16", data="synthetic", vs_baseline=None,
+               config=dict(workload=args.workload, agents=A, span_tokens=int(spec.span_tokens), listed_pages=n_pert),
+               us={k: round(v, 1) for k, v in t.items()},
+               GBps=dict(encode_paired=gb(2 * one, t["encode_paired"]), encode_K=gb(one, t["encode_K"]), encode_V=gb(one, t["encode_V"]),
+                         decode_paired=gb(2 * one, t["decode_paired"]), decode_K=gb(one, t["decode_K"]), decode_V=gb(one, t["decode_V"])),
+               paired_vs_split=dict(encode=round((t["encode_K"] + t["encode_V"]) / t["encode_paired"], 3),
+                                    decode=round((t["decode_K"] + t["decode_V"]) / t["decode_paired"], 3)),
+               check=dict(planewise_restore_bitexact=ok, lists_equal_shared_list=same_lists))
     print(json.dumps(out))
     r.destroy()
 

@@ -154,6 +154,17 @@ tdk_status tdk_diff_encode(tdk_round* r, int32_t layer, const tdk_layer_io* io, 
 tdk_status tdk_diff_decode(tdk_round* r, int32_t layer, const tdk_layer_io* io, const tdk_diff* in,
                            void* hip_stream);
 
+/* Single-plane diffs (Sec. 5: K and V keep separate block-index lists unless both touch the same
+ * blocks; the single-plane kernel of "Fused Sparse Restore").  plane = TDK_PLANE_K or TDK_PLANE_V.
+ * Same as tdk_diff_encode / tdk_diff_decode restricted to one plane: only that plane is compared,
+ * listed, stored and restored; payload is [capacity_pages][T][H][D] (one plane per slot). */
+#define TDK_PLANE_K 1
+#define TDK_PLANE_V 2
+tdk_status tdk_diff_encode_plane(tdk_round* r, int32_t layer, const tdk_layer_io* io, float eps, int32_t plane,
+                                 const tdk_diff* out, void* hip_stream);
+tdk_status tdk_diff_decode_plane(tdk_round* r, int32_t layer, const tdk_layer_io* io, int32_t plane,
+                                 const tdk_diff* in, void* hip_stream);
+
 /* Reuse plan of the check layer (Sec. 4.2 "Layerwise Collective Reuse" and "Reuse Plan Output"), all DEV,
  * caller-owned.
  *   score[sum_i S_i]              per-token deviation of agent i at master token m, agents in order:

@@ -263,12 +263,14 @@ static int differs(uint16_t a, uint16_t ref, float eps) {
   return !(d <= eps);
 }
 
-int tdo_diff_encode(const tdo_geom* g, const tdo_round* r,
-                    const uint16_t* master_k, const uint16_t* master_v,
-                    const uint16_t* pool_k, const uint16_t* pool_v, int64_t pool_pages,
-                    float eps,
-                    int32_t* count, int64_t* offset, int32_t* idx, uint16_t* payload,
-                    int64_t capacity_pages, int32_t* overflow) {
+/* planes: bit 0 = K, bit 1 = V.  3 = the paired diff (one list, both planes stored); 1 or 2 = a
+ * single-plane diff (only that plane is compared and stored, one plane per payload slot). */
+static int encode_impl(const tdo_geom* g, const tdo_round* r,
+                       const uint16_t* master_k, const uint16_t* master_v,
+                       const uint16_t* pool_k, const uint16_t* pool_v, int64_t pool_pages,
+                       float eps, int planes,
+                       int32_t* count, int64_t* offset, int32_t* idx, uint16_t* payload,
+                       int64_t capacity_pages, int32_t* overflow) {
   if (!round_ok(g, r, pool_pages) || !master_k || !master_v || !pool_k || !pool_v) return -1;
   if (!count || !offset || !overflow || capacity_pages < 0 || (capacity_pages && (!idx || !payload))) return -1;
   if (!(eps >= 0.0f)) return -1;
@@ -300,8 +302,8 @@ int tdo_diff_encode(const tdo_geom* g, const tdo_round* r,
         int64_t src = slot_row(g, r, i, m);
         rotate_row_bf16(g, &t, master_k + (row0 + m) * re, ref);
         for (int64_t e = 0; e < re; ++e) {
-          if (differs(pool_k[src * re + e], ref[e], eps)) flag = 1;
-          if (differs(pool_v[src * re + e], master_v[(row0 + m) * re + e], eps)) flag = 1;
+          if ((planes & 1) && differs(pool_k[src * re + e], ref[e], eps)) flag = 1;
+          if ((planes & 2) && differs(pool_v[src * re + e], master_v[(row0 + m) * re + e], eps)) flag = 1;
         }
       }
       if (flag) lists[i][n++] = (int32_t)p;
@@ -326,17 +328,18 @@ int tdo_diff_encode(const tdo_geom* g, const tdo_round* r,
         if (slot >= capacity_pages) break;
         int64_t p = lists[i][k];
         idx[slot] = (int32_t)p;
-        uint16_t* pk = payload + slot * 2 * T * re;
-        uint16_t* pv = pk + T * re;
+        const int n_planes = planes == 3 ? 2 : 1;
+        uint16_t* pk = payload + slot * n_planes * T * re;          /* K values (if stored) come first */
+        uint16_t* pv = planes == 3 ? pk + T * re : pk;
         for (int64_t q = 0; q < T; ++q) {
           int64_t m = p * T + q;
           if (m < S) {
             int64_t src = slot_row(g, r, i, m);
-            memcpy(pk + q * re, pool_k + src * re, (size_t)re * sizeof(uint16_t));
-            memcpy(pv + q * re, pool_v + src * re, (size_t)re * sizeof(uint16_t));
+            if (planes & 1) memcpy(pk + q * re, pool_k + src * re, (size_t)re * sizeof(uint16_t));
+            if (planes & 2) memcpy(pv + q * re, pool_v + src * re, (size_t)re * sizeof(uint16_t));
           } else {
-            memset(pk + q * re, 0, (size_t)re * sizeof(uint16_t));
-            memset(pv + q * re, 0, (size_t)re * sizeof(uint16_t));
+            if (planes & 1) memset(pk + q * re, 0, (size_t)re * sizeof(uint16_t));
+            if (planes & 2) memset(pv + q * re, 0, (size_t)re * sizeof(uint16_t));
           }
         }
       }
@@ -347,12 +350,33 @@ int tdo_diff_encode(const tdo_geom* g, const tdo_round* r,
   return err ? -2 : 0;
 }
 
+int tdo_diff_encode(const tdo_geom* g, const tdo_round* r,
+                    const uint16_t* master_k, const uint16_t* master_v,
+                    const uint16_t* pool_k, const uint16_t* pool_v, int64_t pool_pages,
+                    float eps,
+                    int32_t* count, int64_t* offset, int32_t* idx, uint16_t* payload,
+                    int64_t capacity_pages, int32_t* overflow) {
+  return encode_impl(g, r, master_k, master_v, pool_k, pool_v, pool_pages, eps, 3,
+                     count, offset, idx, payload, capacity_pages, overflow);
+}
+
+int tdo_diff_encode_plane(const tdo_geom* g, const tdo_round* r,
+                          const uint16_t* master_k, const uint16_t* master_v,
+                          const uint16_t* pool_k, const uint16_t* pool_v, int64_t pool_pages,
+                          float eps, int32_t plane,
+                          int32_t* count, int64_t* offset, int32_t* idx, uint16_t* payload,
+                          int64_t capacity_pages, int32_t* overflow) {
+  if (plane != 1 && plane != 2) return -1;
+  return encode_impl(g, r, master_k, master_v, pool_k, pool_v, pool_pages, eps, plane,
+                     count, offset, idx, payload, capacity_pages, overflow);
+}
+
 /* ---- fused diff restore  [Sec. 4.4, Alg. 1] ------------------------------ */
 
-int tdo_diff_decode(const tdo_geom* g, const tdo_round* r,
-                    const uint16_t* master_k, const uint16_t* master_v,
-                    uint16_t* pool_k, uint16_t* pool_v, int64_t pool_pages,
-                    const int32_t* count, const int64_t* offset, const int32_t* idx, const uint16_t* payload) {
+static int decode_impl(const tdo_geom* g, const tdo_round* r,
+                       const uint16_t* master_k, const uint16_t* master_v,
+                       uint16_t* pool_k, uint16_t* pool_v, int64_t pool_pages, int planes,
+                       const int32_t* count, const int64_t* offset, const int32_t* idx, const uint16_t* payload) {
   if (!round_ok(g, r, pool_pages) || !master_k || !master_v || !pool_k || !pool_v) return -1;
   if (!count || !offset) return -1;
   const int64_t T = g->page_tokens;
@@ -388,14 +412,17 @@ int tdo_diff_decode(const tdo_geom* g, const tdo_round* r,
         if (m >= S) break;
         int64_t dst = slot_row(g, r, i, m);
         if (slot >= 0) {
-          const uint16_t* pk = payload + slot * 2 * T * re;
-          const uint16_t* pv = pk + T * re;
-          if (delta_diff == 0) memcpy(pool_k + dst * re, pk + q * re, (size_t)re * sizeof(uint16_t));
-          else rotate_row_bf16(g, &td, pk + q * re, pool_k + dst * re);
-          memcpy(pool_v + dst * re, pv + q * re, (size_t)re * sizeof(uint16_t));
+          const int n_planes = planes == 3 ? 2 : 1;
+          const uint16_t* pk = payload + slot * n_planes * T * re;
+          const uint16_t* pv = planes == 3 ? pk + T * re : pk;
+          if (planes & 1) {
+            if (delta_diff == 0) memcpy(pool_k + dst * re, pk + q * re, (size_t)re * sizeof(uint16_t));
+            else rotate_row_bf16(g, &td, pk + q * re, pool_k + dst * re);
+          }
+          if (planes & 2) memcpy(pool_v + dst * re, pv + q * re, (size_t)re * sizeof(uint16_t));
         } else {
-          rotate_row_bf16(g, &t, master_k + (row0 + m) * re, pool_k + dst * re);
-          memcpy(pool_v + dst * re, master_v + (row0 + m) * re, (size_t)re * sizeof(uint16_t));
+          if (planes & 1) rotate_row_bf16(g, &t, master_k + (row0 + m) * re, pool_k + dst * re);
+          if (planes & 2) memcpy(pool_v + dst * re, master_v + (row0 + m) * re, (size_t)re * sizeof(uint16_t));
         }
       }
     }
@@ -403,6 +430,21 @@ int tdo_diff_decode(const tdo_geom* g, const tdo_round* r,
     tab_free(&td);
   }
   return err ? -2 : 0;
+}
+
+int tdo_diff_decode(const tdo_geom* g, const tdo_round* r,
+                    const uint16_t* master_k, const uint16_t* master_v,
+                    uint16_t* pool_k, uint16_t* pool_v, int64_t pool_pages,
+                    const int32_t* count, const int64_t* offset, const int32_t* idx, const uint16_t* payload) {
+  return decode_impl(g, r, master_k, master_v, pool_k, pool_v, pool_pages, 3, count, offset, idx, payload);
+}
+
+int tdo_diff_decode_plane(const tdo_geom* g, const tdo_round* r,
+                          const uint16_t* master_k, const uint16_t* master_v,
+                          uint16_t* pool_k, uint16_t* pool_v, int64_t pool_pages, int32_t plane,
+                          const int32_t* count, const int64_t* offset, const int32_t* idx, const uint16_t* payload) {
+  if (plane != 1 && plane != 2) return -1;
+  return decode_impl(g, r, master_k, master_v, pool_k, pool_v, pool_pages, plane, count, offset, idx, payload);
 }
 
 /* ---- check layer: key-difference pass, important positions, master  [Sec. 4.2; Sec. 2.2] -------- */

@@ -96,6 +96,19 @@ int tdo_diff_decode(const tdo_geom* g, const tdo_round* r,
                     uint16_t* pool_k, uint16_t* pool_v, int64_t pool_pages,
                     const int32_t* count, const int64_t* offset, const int32_t* idx, const uint16_t* payload);
 
+/* Single-plane diffs (Sec. 5: separate block-index lists for K and V unless both touch the same blocks).
+ * plane = 1 (K) or 2 (V): only that plane is compared, listed, stored (payload [capacity][T][H][D]) and restored. */
+int tdo_diff_encode_plane(const tdo_geom* g, const tdo_round* r,
+                          const uint16_t* master_k, const uint16_t* master_v,
+                          const uint16_t* pool_k, const uint16_t* pool_v, int64_t pool_pages,
+                          float eps, int32_t plane,
+                          int32_t* count, int64_t* offset, int32_t* idx, uint16_t* payload,
+                          int64_t capacity_pages, int32_t* overflow);
+int tdo_diff_decode_plane(const tdo_geom* g, const tdo_round* r,
+                          const uint16_t* master_k, const uint16_t* master_v,
+                          uint16_t* pool_k, uint16_t* pool_v, int64_t pool_pages, int32_t plane,
+                          const int32_t* count, const int64_t* offset, const int32_t* idx, const uint16_t* payload);
+
 /* Check layer (Sec. 4.2): per-token key deviation of every agent (double, agent-major), the selection of
  * important positions from fp32 scores, and the master choice from fp32 totals. */
 int tdo_key_deviation(const tdo_geom* g, const tdo_round* r,

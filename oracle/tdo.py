@@ -66,6 +66,10 @@ def lib() -> C.CDLL:
                                       [C.c_int64, C.c_float] + [C.c_void_p] * 4 + [C.c_int64, C.c_void_p])
         L.tdo_diff_decode.argtypes = ([C.POINTER(Geom), C.POINTER(RoundDesc)] + [C.c_void_p] * 4 +
                                       [C.c_int64] + [C.c_void_p] * 4)
+        L.tdo_diff_encode_plane.argtypes = ([C.POINTER(Geom), C.POINTER(RoundDesc)] + [C.c_void_p] * 4 +
+                                            [C.c_int64, C.c_float, C.c_int32] + [C.c_void_p] * 4 + [C.c_int64, C.c_void_p])
+        L.tdo_diff_decode_plane.argtypes = ([C.POINTER(Geom), C.POINTER(RoundDesc)] + [C.c_void_p] * 4 +
+                                            [C.c_int64, C.c_int32] + [C.c_void_p] * 4)
         L.tdo_key_deviation.argtypes = [C.POINTER(Geom), C.POINTER(RoundDesc), C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p]
         L.tdo_select_important.argtypes = [C.c_void_p, C.c_int64, C.c_float, C.c_float, C.c_void_p, C.c_void_p]
         L.tdo_choose_master.argtypes = [C.POINTER(RoundDesc), C.c_void_p, C.c_void_p]
@@ -179,6 +183,22 @@ def diff_encode(g: Geom, hr: HostRound, master_k, master_v, pool_k, pool_v, eps:
                                _p(d.count), _p(d.offset), _p(d.idx), _p(d.payload),
                                d.capacity_pages, _p(d.overflow)), "diff_encode")
     return d
+
+
+def diff_encode_plane(g: Geom, hr: HostRound, master_k, master_v, pool_k, pool_v, eps: float, plane: int,
+                      capacity_pages: int) -> Diff:
+    d = Diff(hr.desc.n_agents, capacity_pages, g.page_tokens * g.num_kv_heads * g.head_dim)
+    _chk(lib().tdo_diff_encode_plane(C.byref(g), C.byref(hr.desc), _p(_u16(master_k)), _p(_u16(master_v)),
+                                     _p(_u16(pool_k)), _p(_u16(pool_v)), hr.pool_pages, C.c_float(eps), plane,
+                                     _p(d.count), _p(d.offset), _p(d.idx), _p(d.payload),
+                                     d.capacity_pages, _p(d.overflow)), "diff_encode_plane")
+    return d
+
+
+def diff_decode_plane(g: Geom, hr: HostRound, master_k, master_v, pool_k, pool_v, plane: int, d: Diff) -> None:
+    _chk(lib().tdo_diff_decode_plane(C.byref(g), C.byref(hr.desc), _p(_u16(master_k)), _p(_u16(master_v)),
+                                     _p(_u16(pool_k)), _p(_u16(pool_v)), hr.pool_pages, plane,
+                                     _p(d.count), _p(d.offset), _p(d.idx), _p(d.payload)), "diff_decode_plane")
 
 
 def diff_decode(g: Geom, hr: HostRound, master_k, master_v, pool_k, pool_v, d: Diff) -> None:

@@ -472,8 +472,8 @@ tdk_status tdk_rerotate_round(tdk_round* r, int32_t layer, const tdk_layer_io* i
   return TDK_OK;
 }
 
-tdk_status tdk_diff_encode(tdk_round* r, int32_t layer, const tdk_layer_io* io, float eps,
-                           const tdk_diff* out, void* hip_stream) {
+static tdk_status encode_planes(tdk_round* r, int32_t layer, const tdk_layer_io* io, float eps, int planes,
+                                const tdk_diff* out, void* hip_stream) {
   tdk_status st = check_step(r, layer, io);
   if (st != TDK_OK) return st;
   st = check_diff(r, out, true);
@@ -482,17 +482,17 @@ tdk_status tdk_diff_encode(tdk_round* r, int32_t layer, const tdk_layer_io* io, 
   hipStream_t s = static_cast<hipStream_t>(hip_stream);
   const LayerDev l = layer_dev(io);
   const DiffDev d = diff_dev(out);
-  TDK_LAUNCH(r, TDK_KERNEL_FLAG, s, launch_flag(r->rd, l, eps, s));
+  TDK_LAUNCH(r, TDK_KERNEL_FLAG, s, launch_flag(r->rd, l, eps, planes, s));
   TDK_LAUNCH(r, TDK_KERNEL_COUNT, s, launch_count(r->rd, d, s));
   TDK_LAUNCH(r, TDK_KERNEL_INDEX, s, launch_index(r->rd, d, s));
   // the number of listed pages is known on the device only: a fixed grid strides over them
   const int grid = (int)std::min<int64_t>(std::min<int64_t>(out->capacity_pages, r->total_pages), 1 << 20);
-  TDK_LAUNCH(r, TDK_KERNEL_GATHER, s, launch_gather(r->rd, l, d, grid, s));
+  TDK_LAUNCH(r, TDK_KERNEL_GATHER, s, launch_gather(r->rd, l, d, planes, grid, s));
   return TDK_OK;
 }
 
-tdk_status tdk_diff_decode(tdk_round* r, int32_t layer, const tdk_layer_io* io, const tdk_diff* in,
-                           void* hip_stream) {
+static tdk_status decode_planes(tdk_round* r, int32_t layer, const tdk_layer_io* io, int planes,
+                                const tdk_diff* in, void* hip_stream) {
   tdk_status st = check_step(r, layer, io);
   if (st != TDK_OK) return st;
   st = check_diff(r, in, false);
@@ -500,10 +500,32 @@ tdk_status tdk_diff_decode(tdk_round* r, int32_t layer, const tdk_layer_io* io, 
   hipStream_t s = static_cast<hipStream_t>(hip_stream);
   const LayerDev l = layer_dev(io);
   const DiffDev d = diff_dev(in);
-  TDK_LAUNCH(r, TDK_KERNEL_DECODE, s, launch_decode(r->rd, l, d, s));
+  TDK_LAUNCH(r, TDK_KERNEL_DECODE, s, launch_decode(r->rd, l, d, planes, s));
   const int grid = (int)std::min<int64_t>(std::min<int64_t>(in->capacity_pages, r->total_pages), 1 << 20);
-  TDK_LAUNCH(r, TDK_KERNEL_SCATTER, s, launch_scatter(r->rd, l, d, grid, s));
+  TDK_LAUNCH(r, TDK_KERNEL_SCATTER, s, launch_scatter(r->rd, l, d, planes, grid, s));
   return TDK_OK;
+}
+
+tdk_status tdk_diff_encode(tdk_round* r, int32_t layer, const tdk_layer_io* io, float eps,
+                           const tdk_diff* out, void* hip_stream) {
+  return encode_planes(r, layer, io, eps, TDK_PLANE_K | TDK_PLANE_V, out, hip_stream);
+}
+
+tdk_status tdk_diff_decode(tdk_round* r, int32_t layer, const tdk_layer_io* io, const tdk_diff* in,
+                           void* hip_stream) {
+  return decode_planes(r, layer, io, TDK_PLANE_K | TDK_PLANE_V, in, hip_stream);
+}
+
+tdk_status tdk_diff_encode_plane(tdk_round* r, int32_t layer, const tdk_layer_io* io, float eps, int32_t plane,
+                                 const tdk_diff* out, void* hip_stream) {
+  if (plane != TDK_PLANE_K && plane != TDK_PLANE_V) return fail(TDK_ERR_INVALID_ARG, "plane must be TDK_PLANE_K or TDK_PLANE_V");
+  return encode_planes(r, layer, io, eps, plane, out, hip_stream);
+}
+
+tdk_status tdk_diff_decode_plane(tdk_round* r, int32_t layer, const tdk_layer_io* io, int32_t plane,
+                                 const tdk_diff* in, void* hip_stream) {
+  if (plane != TDK_PLANE_K && plane != TDK_PLANE_V) return fail(TDK_ERR_INVALID_ARG, "plane must be TDK_PLANE_K or TDK_PLANE_V");
+  return decode_planes(r, layer, io, plane, in, hip_stream);
 }
 
 tdk_status tdk_check_layer(tdk_round* r, int32_t layer, const tdk_layer_io* io, float ratio, float min_score,
@@ -586,9 +608,9 @@ tdk_status tdk_restore_layers(tdk_round* r, int32_t first_layer, int32_t n_layer
     if (e != hipSuccess) return hip_fail(e, "hipStreamWaitEvent(loaded)");
     const LayerDev l = layer_dev(&lio[k]);
     const DiffDev d = diff_dev(&diffs[k]);
-    TDK_LAUNCH(r, TDK_KERNEL_DECODE, cs, launch_decode(r->rd, l, d, cs));
+    TDK_LAUNCH(r, TDK_KERNEL_DECODE, cs, launch_decode(r->rd, l, d, 3, cs));
     const int grid = (int)std::min<int64_t>(std::min<int64_t>(diffs[k].capacity_pages, r->total_pages), 1 << 20);
-    TDK_LAUNCH(r, TDK_KERNEL_SCATTER, cs, launch_scatter(r->rd, l, d, grid, cs));
+    TDK_LAUNCH(r, TDK_KERNEL_SCATTER, cs, launch_scatter(r->rd, l, d, 3, grid, cs));
     e = hipEventRecord(r->ev_free[b], cs);
     if (e != hipSuccess) return hip_fail(e, "hipEventRecord(free)");
     r->free_recorded[b] = true;

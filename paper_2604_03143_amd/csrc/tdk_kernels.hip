@@ -148,7 +148,7 @@ struct MasterRows {
   bool  valid[RPW];
 };
 
-template <int RPW, bool LOADV = true>
+template <int RPW, bool LOADV = true, bool LOADK = true>
 __device__ __forceinline__ void load_master(const RoundDev& rd, const LayerDev& io, const WorkItem& w,
                                             const Lane& L, MasterRows<RPW>& M) {
   constexpr int T = RPW * kWaves;
@@ -164,7 +164,7 @@ __device__ __forceinline__ void load_master(const RoundDev& rd, const LayerDev& 
     if (M.valid[k]) {
       const u32x4* rk = io.master_k + (sd.master_row0 + m) * row_u4;
       const u32x4* rv = io.master_v + (sd.master_row0 + m) * row_u4;
-      if (L.kok) { M.kl[k] = rk[L.klo]; M.kh[k] = rk[L.khi]; }
+      if (LOADK && L.kok) { M.kl[k] = rk[L.klo]; M.kh[k] = rk[L.khi]; }
       if (LOADV && L.v0ok) M.v0[k] = rv[L.v0];
       if (LOADV && L.v1ok) M.v1[k] = rv[L.v1];
     }
@@ -250,15 +250,17 @@ __device__ __forceinline__ bool chunk_special(const u32x4 m) {
   return sp;
 }
 
-template <int RPW, bool IL>
+// PM: planes that take part (bit 0 = K, bit 1 = V); 3 is the paired diff, 1 / 2 the single-plane diffs
+template <int RPW, bool IL, int PM>
 __global__ __launch_bounds__(kBlock) void tdk_flag_kernel(const RoundDev rd, const LayerDev io, const float eps) {
   constexpr int T = RPW * kWaves;
+  constexpr bool DOK = (PM & 1) != 0, DOV = (PM & 2) != 0;
   __shared__ GroupShared sh;
   const WorkItem w = rd.work[blockIdx.x];
   const Lane L = lane_geometry(rd.heads);
   stage_group<T>(rd, w, sh);
   MasterRows<RPW> M;
-  load_master<RPW>(rd, io, w, L, M);
+  load_master<RPW, DOV, DOK>(rd, io, w, L, M);
   bool special[RPW];
 #pragma unroll
   for (int k = 0; k < RPW; ++k)
@@ -270,7 +272,7 @@ __global__ __launch_bounds__(kBlock) void tdk_flag_kernel(const RoundDev rd, con
   const u32x4* pv = io.pool_v;
   for (int g = 0; g < w.ag_count; ++g) {
     float c[8], s[8];
-    load_tab<IL>(sh, g, L.jb, c, s);
+    if (DOK) load_tab<IL>(sh, g, L.jb, c, s);
     u32x4 akl[RPW], akh[RPW], av0[RPW], av1[RPW];
     const u32x4 z = {0, 0, 0, 0};
 #pragma unroll
@@ -278,23 +280,24 @@ __global__ __launch_bounds__(kBlock) void tdk_flag_kernel(const RoundDev rd, con
       akl[k] = z; akh[k] = z; av0[k] = z; av1[k] = z;
       if (!M.valid[k]) continue;
       const int64_t base = dest_row<T>(sh, g, wave + kWaves * k) * row_u4;
-      if (L.kok) { akl[k] = pk[base + L.klo]; akh[k] = pk[base + L.khi]; }
-      if (L.v0ok) av0[k] = pv[base + L.v0];
-      if (L.v1ok) av1[k] = pv[base + L.v1];
+      if (DOK && L.kok) { akl[k] = pk[base + L.klo]; akh[k] = pk[base + L.khi]; }
+      if (DOV && L.v0ok) av0[k] = pv[base + L.v0];
+      if (DOV && L.v1ok) av1[k] = pv[base + L.v1];
     }
     bool differs = false;
 #pragma unroll
     for (int k = 0; k < RPW; ++k) {
       if (!M.valid[k]) continue;
       u32x4 rlo = z, rhi = z;
-      if (L.kok) rotate16<IL>(M.kl[k], M.kh[k], c, s, rlo, rhi);
+      if (DOK && L.kok) rotate16<IL>(M.kl[k], M.kh[k], c, s, rlo, rhi);
       // rows whose bits all match the reference (the common case) need no fp32 compare
-      uint32_t x = chunk_xor(av0[k], M.v0[k]) | chunk_xor(av1[k], M.v1[k]);
-      if (L.kok) x |= chunk_xor(akl[k], rlo) | chunk_xor(akh[k], rhi);
+      uint32_t x = 0;
+      if (DOV) x |= chunk_xor(av0[k], M.v0[k]) | chunk_xor(av1[k], M.v1[k]);
+      if (DOK && L.kok) x |= chunk_xor(akl[k], rlo) | chunk_xor(akh[k], rhi);
       if (__any((x != 0) | special[k])) {
-        if (L.kok) differs |= chunk_differs(akl[k], rlo, eps) | chunk_differs(akh[k], rhi, eps);
-        if (L.v0ok) differs |= chunk_differs(av0[k], M.v0[k], eps);
-        if (L.v1ok) differs |= chunk_differs(av1[k], M.v1[k], eps);
+        if (DOK && L.kok) differs |= chunk_differs(akl[k], rlo, eps) | chunk_differs(akh[k], rhi, eps);
+        if (DOV && L.v0ok) differs |= chunk_differs(av0[k], M.v0[k], eps);
+        if (DOV && L.v1ok) differs |= chunk_differs(av1[k], M.v1[k], eps);
       }
     }
     if (__any(differs) && (threadIdx.x & 63) == 0) atomicOr(&sh.aux[g], 1);
@@ -383,7 +386,9 @@ __device__ __forceinline__ void find_owner(const DiffDev& d, int A, int64_t slot
 
 constexpr int kCopyBatch = 4;   // 16-byte accesses per thread in flight in gather / scatter
 
-__global__ __launch_bounds__(kBlock) void tdk_gather_kernel(const RoundDev rd, const LayerDev io, const DiffDev d) {
+// planes: bit 0 = K, bit 1 = V; a slot holds the selected planes back to back
+__global__ __launch_bounds__(kBlock) void tdk_gather_kernel(const RoundDev rd, const LayerDev io, const DiffDev d,
+                                                            const int planes) {
   __shared__ SlotShared sh;
   const int T = rd.page_tokens;
   const int A = rd.n_agents;
@@ -406,10 +411,12 @@ __global__ __launch_bounds__(kBlock) void tdk_gather_kernel(const RoundDev rd, c
       sh.row[threadIdx.x] = row;
     }
     __syncthreads();
+    const int n_planes = planes == 3 ? 2 : 1;
 #pragma unroll 1
     for (int plane = 0; plane < 2; ++plane) {
+      if (!((planes >> plane) & 1)) continue;
       const u32x4* src = plane ? io.pool_v : io.pool_k;
-      u32x4* dst = d.payload + (slot * 2 + plane) * (int64_t)page_u4;
+      u32x4* dst = d.payload + (slot * n_planes + (planes == 3 ? plane : 0)) * (int64_t)page_u4;
       for (int i0 = threadIdx.x; i0 < page_u4; i0 += kBlock * kCopyBatch) {
         u32x4 v[kCopyBatch];
 #pragma unroll
@@ -438,7 +445,7 @@ __global__ __launch_bounds__(kBlock) void tdk_gather_kernel(const RoundDev rd, c
 // decode: diff pages from the payload, all others from the re-rotated master   [Sec. 4.4, Alg. 1]
 // ---------------------------------------------------------------------------------------------
 
-template <int RPW, bool IL, bool NT>
+template <int RPW, bool IL, bool NT, int PM>
 __global__ __launch_bounds__(kBlock) void tdk_decode_kernel(const RoundDev rd, const LayerDev io, const DiffDev d) {
   constexpr int T = RPW * kWaves;
   __shared__ GroupShared sh;
@@ -446,7 +453,8 @@ __global__ __launch_bounds__(kBlock) void tdk_decode_kernel(const RoundDev rd, c
   const Lane L = lane_geometry(rd.heads);
   stage_group<T>(rd, w, sh);
   MasterRows<RPW> M;
-  load_master<RPW>(rd, io, w, L, M);
+  constexpr bool DOK = (PM & 1) != 0, DOV = (PM & 2) != 0;
+  load_master<RPW, DOV, DOK>(rd, io, w, L, M);
   if (threadIdx.x < w.ag_count) {
     // skip-or-correct decision per block: is this page in the agent's index list?
     const int a = rd.order[w.ag_begin + threadIdx.x];
@@ -471,19 +479,19 @@ __global__ __launch_bounds__(kBlock) void tdk_decode_kernel(const RoundDev rd, c
   for (int g = 0; g < w.ag_count; ++g) {
     if (sh.aux[g] >= 0) continue;   // listed in the diff: the scatter kernel writes this page
     float c[8], s[8];
-    load_tab<IL>(sh, g, L.jb, c, s);
+    if (DOK) load_tab<IL>(sh, g, L.jb, c, s);
 #pragma unroll
     for (int k = 0; k < RPW; ++k) {
       if (!M.valid[k]) continue;
       const int64_t base = dest_row<T>(sh, g, wave + kWaves * k) * row_u4;
-      if (L.kok) {
+      if (DOK && L.kok) {
         u32x4 olo, ohi;
         rotate16<IL>(M.kl[k], M.kh[k], c, s, olo, ohi);
         st16<NT>(pk + base + L.klo, olo);
         st16<NT>(pk + base + L.khi, ohi);
       }
-      if (L.v0ok) st16<NT>(pv + base + L.v0, M.v0[k]);
-      if (L.v1ok) st16<NT>(pv + base + L.v1, M.v1[k]);
+      if (DOV && L.v0ok) st16<NT>(pv + base + L.v0, M.v0[k]);
+      if (DOV && L.v1ok) st16<NT>(pv + base + L.v1, M.v1[k]);
     }
   }
 }
@@ -492,7 +500,8 @@ __global__ __launch_bounds__(kBlock) void tdk_decode_kernel(const RoundDev rd, c
 // agent's rows (the mirror image of the gather kernel).  Every pool row is written exactly once by
 // either this kernel or the page kernel above, so their order does not matter.
 template <bool IL>
-__global__ __launch_bounds__(kBlock) void tdk_scatter_kernel(const RoundDev rd, const LayerDev io, const DiffDev d) {
+__global__ __launch_bounds__(kBlock) void tdk_scatter_kernel(const RoundDev rd, const LayerDev io, const DiffDev d,
+                                                             const int planes) {
   __shared__ SlotShared sh;
   __shared__ float s_tab[2 * kHalf];       // cos/sin of the owner's payload re-rotation
   const int T = rd.page_tokens;
@@ -526,10 +535,12 @@ __global__ __launch_bounds__(kBlock) void tdk_scatter_kernel(const RoundDev rd, 
     }
     if (rot && threadIdx.x < 2 * kHalf) s_tab[threadIdx.x] = rd.tab_diff[(size_t)sh.owner * (2 * kHalf) + threadIdx.x];
     __syncthreads();
+    const int n_planes = planes == 3 ? 2 : 1;
 #pragma unroll 1
     for (int plane = 0; plane < 2; ++plane) {
+      if (!((planes >> plane) & 1)) continue;
       u32x4* dst = plane ? io.pool_v : io.pool_k;
-      const u32x4* src = d.payload + (slot * 2 + plane) * (int64_t)page_u4;
+      const u32x4* src = d.payload + (slot * n_planes + (planes == 3 ? plane : 0)) * (int64_t)page_u4;
       if (plane == 0 && rot) {
         // stored at another position: K rows are re-rotated, a wavefront per row, both members of a
         // pair in one lane (the page kernels' lane layout)
@@ -804,46 +815,31 @@ __global__ __launch_bounds__(kBlock) void tdk_page_read_kernel(const u32x4* __re
 // launchers
 // ---------------------------------------------------------------------------------------------
 
-#define TDK_DISPATCH_RPW_IL(KERNEL, ...)                                                    \
-  do {                                                                                      \
-    const bool il = rd.interleaved != 0;                                                    \
-    if (rd.page_tokens == 16) {                                                             \
-      if (il) hipLaunchKernelGGL((KERNEL<4, true>), grid, dim3(kBlock), 0, st, __VA_ARGS__); \
-      else hipLaunchKernelGGL((KERNEL<4, false>), grid, dim3(kBlock), 0, st, __VA_ARGS__);   \
-    } else {                                                                                \
-      if (il) hipLaunchKernelGGL((KERNEL<8, true>), grid, dim3(kBlock), 0, st, __VA_ARGS__); \
-      else hipLaunchKernelGGL((KERNEL<8, false>), grid, dim3(kBlock), 0, st, __VA_ARGS__);   \
-    }                                                                                       \
-  } while (0)
+template <int V> using ic = std::integral_constant<int, V>;
 
-#define TDK_DISPATCH_RPW_IL_NT(KERNEL, ...)                                                          \
-  do {                                                                                               \
-    const bool il = rd.interleaved != 0;                                                             \
-    const bool nt = rd.nontemporal != 0;                                                             \
-    if (rd.page_tokens == 16) {                                                                      \
-      if (il) { if (nt) hipLaunchKernelGGL((KERNEL<4, true, true>), grid, dim3(kBlock), 0, st, __VA_ARGS__);   \
-                else hipLaunchKernelGGL((KERNEL<4, true, false>), grid, dim3(kBlock), 0, st, __VA_ARGS__); }   \
-      else    { if (nt) hipLaunchKernelGGL((KERNEL<4, false, true>), grid, dim3(kBlock), 0, st, __VA_ARGS__);  \
-                else hipLaunchKernelGGL((KERNEL<4, false, false>), grid, dim3(kBlock), 0, st, __VA_ARGS__); }  \
-    } else {                                                                                         \
-      if (il) { if (nt) hipLaunchKernelGGL((KERNEL<8, true, true>), grid, dim3(kBlock), 0, st, __VA_ARGS__);   \
-                else hipLaunchKernelGGL((KERNEL<8, true, false>), grid, dim3(kBlock), 0, st, __VA_ARGS__); }   \
-      else    { if (nt) hipLaunchKernelGGL((KERNEL<8, false, true>), grid, dim3(kBlock), 0, st, __VA_ARGS__);  \
-                else hipLaunchKernelGGL((KERNEL<8, false, false>), grid, dim3(kBlock), 0, st, __VA_ARGS__); }  \
-    }                                                                                                \
-  } while (0)
+template <class F> static void with_rpw(int page_tokens, F f) { if (page_tokens == 16) f(ic<4>{}); else f(ic<8>{}); }
+template <class F> static void with_bool(bool b, F f) { if (b) f(std::true_type{}); else f(std::false_type{}); }
+template <class F> static void with_planes(int planes, F f) {
+  if (planes == 1) f(ic<1>{}); else if (planes == 2) f(ic<2>{}); else f(ic<3>{});
+}
 
 hipError_t launch_rerotate(const RoundDev& rd, const LayerDev& io, hipStream_t st) {
   if (rd.n_work == 0) return hipSuccess;
   const dim3 grid(rd.n_work);
-  TDK_DISPATCH_RPW_IL_NT(tdk_rerotate_kernel, rd, io);
+  with_rpw(rd.page_tokens, [&](auto rpw) { with_bool(rd.interleaved != 0, [&](auto il) { with_bool(rd.nontemporal != 0, [&](auto nt) {
+    hipLaunchKernelGGL((tdk_rerotate_kernel<decltype(rpw)::value, decltype(il)::value, decltype(nt)::value>),
+                       grid, dim3(kBlock), 0, st, rd, io);
+  }); }); });
   return hipGetLastError();
 }
 
-hipError_t launch_flag(const RoundDev& rd, const LayerDev& io, float eps, hipStream_t st) {
+hipError_t launch_flag(const RoundDev& rd, const LayerDev& io, float eps, int planes, hipStream_t st) {
   if (rd.n_work == 0) return hipSuccess;
   const dim3 grid(rd.n_work);
-  TDK_DISPATCH_RPW_IL(tdk_flag_kernel, rd, io, eps);
+  with_rpw(rd.page_tokens, [&](auto rpw) { with_bool(rd.interleaved != 0, [&](auto il) { with_planes(planes, [&](auto pm) {
+    hipLaunchKernelGGL((tdk_flag_kernel<decltype(rpw)::value, decltype(il)::value, decltype(pm)::value>),
+                       grid, dim3(kBlock), 0, st, rd, io, eps);
+  }); }); });
   return hipGetLastError();
 }
 
@@ -860,30 +856,37 @@ hipError_t launch_index(const RoundDev& rd, const DiffDev& d, hipStream_t st) {
   return hipGetLastError();
 }
 
-hipError_t launch_gather(const RoundDev& rd, const LayerDev& io, const DiffDev& d, int grid_size, hipStream_t st) {
+hipError_t launch_gather(const RoundDev& rd, const LayerDev& io, const DiffDev& d, int planes, int grid_size, hipStream_t st) {
   if (rd.n_agents == 0 || d.capacity == 0 || grid_size <= 0) return hipSuccess;
-  hipLaunchKernelGGL(tdk_gather_kernel, dim3(grid_size), dim3(kBlock), 0, st, rd, io, d);
+  hipLaunchKernelGGL(tdk_gather_kernel, dim3(grid_size), dim3(kBlock), 0, st, rd, io, d, planes);
   return hipGetLastError();
 }
 
-hipError_t launch_decode(const RoundDev& rd, const LayerDev& io, const DiffDev& d, hipStream_t st) {
+hipError_t launch_decode(const RoundDev& rd, const LayerDev& io, const DiffDev& d, int planes, hipStream_t st) {
   if (rd.n_work == 0) return hipSuccess;
   const dim3 grid(rd.n_work);
-  TDK_DISPATCH_RPW_IL_NT(tdk_decode_kernel, rd, io, d);
+  with_rpw(rd.page_tokens, [&](auto rpw) { with_bool(rd.interleaved != 0, [&](auto il) { with_bool(rd.nontemporal != 0, [&](auto nt) {
+    with_planes(planes, [&](auto pm) {
+      hipLaunchKernelGGL((tdk_decode_kernel<decltype(rpw)::value, decltype(il)::value, decltype(nt)::value, decltype(pm)::value>),
+                         grid, dim3(kBlock), 0, st, rd, io, d);
+    });
+  }); }); });
   return hipGetLastError();
 }
 
-hipError_t launch_scatter(const RoundDev& rd, const LayerDev& io, const DiffDev& d, int grid_size, hipStream_t st) {
+hipError_t launch_scatter(const RoundDev& rd, const LayerDev& io, const DiffDev& d, int planes, int grid_size, hipStream_t st) {
   if (rd.n_agents == 0 || d.capacity == 0 || grid_size <= 0) return hipSuccess;
-  if (rd.interleaved) hipLaunchKernelGGL(tdk_scatter_kernel<true>, dim3(grid_size), dim3(kBlock), 0, st, rd, io, d);
-  else hipLaunchKernelGGL(tdk_scatter_kernel<false>, dim3(grid_size), dim3(kBlock), 0, st, rd, io, d);
+  if (rd.interleaved) hipLaunchKernelGGL(tdk_scatter_kernel<true>, dim3(grid_size), dim3(kBlock), 0, st, rd, io, d, planes);
+  else hipLaunchKernelGGL(tdk_scatter_kernel<false>, dim3(grid_size), dim3(kBlock), 0, st, rd, io, d, planes);
   return hipGetLastError();
 }
 
 hipError_t launch_keydiff(const RoundDev& rd, const LayerDev& io, const PlanDev& pl, hipStream_t st) {
   if (rd.n_work == 0) return hipSuccess;
   const dim3 grid(rd.n_work);
-  TDK_DISPATCH_RPW_IL(tdk_keydiff_kernel, rd, io, pl);
+  with_rpw(rd.page_tokens, [&](auto rpw) { with_bool(rd.interleaved != 0, [&](auto il) {
+    hipLaunchKernelGGL((tdk_keydiff_kernel<decltype(rpw)::value, decltype(il)::value>), grid, dim3(kBlock), 0, st, rd, io, pl);
+  }); });
   return hipGetLastError();
 }
 

@@ -18,6 +18,7 @@ LIB_PATH = os.path.join(_PKG, "libtdk.so")
 OK, ERR_INVALID_ARG, ERR_UNSUPPORTED, ERR_CAPACITY, ERR_HIP, ERR_NOMEM = range(6)
 BF16 = 0
 ROPE_HALF, ROPE_INTERLEAVED = 0, 1
+PLANE_K, PLANE_V = 1, 2
 (KERNEL_REROTATE, KERNEL_FLAG, KERNEL_COUNT, KERNEL_INDEX, KERNEL_GATHER, KERNEL_DECODE, KERNEL_SCATTER,
  KERNEL_KEYDIFF, KERNEL_SELECT, KERNEL_MASTER) = range(10)
 KERNEL_KINDS = 10
@@ -26,6 +27,7 @@ EXPORTS = (
     "tdk_status_str", "tdk_last_error", "tdk_version", "tdk_kernel_name",
     "tdk_round_create", "tdk_round_destroy", "tdk_scratch_bytes", "tdk_round_tune",
     "tdk_rerotate_round", "tdk_diff_encode", "tdk_diff_decode", "tdk_restore_layers", "tdk_check_layer",
+    "tdk_diff_encode_plane", "tdk_diff_decode_plane",
     "tdk_timing_enable", "tdk_timing_read", "tdk_timing_reset",
     "tdk_dense_bytes", "tdk_diff_bytes", "tdk_family_cost",
     "tdk_util_copy", "tdk_util_fill", "tdk_util_page_fill", "tdk_util_page_read",
@@ -101,6 +103,8 @@ def load() -> C.CDLL:
     L.tdk_rerotate_round.argtypes = [C.c_void_p, C.c_int32, C.POINTER(LayerIO), C.c_void_p]
     L.tdk_diff_encode.argtypes = [C.c_void_p, C.c_int32, C.POINTER(LayerIO), C.c_float, C.POINTER(Diff), C.c_void_p]
     L.tdk_diff_decode.argtypes = [C.c_void_p, C.c_int32, C.POINTER(LayerIO), C.POINTER(Diff), C.c_void_p]
+    L.tdk_diff_encode_plane.argtypes = [C.c_void_p, C.c_int32, C.POINTER(LayerIO), C.c_float, C.c_int32, C.POINTER(Diff), C.c_void_p]
+    L.tdk_diff_decode_plane.argtypes = [C.c_void_p, C.c_int32, C.POINTER(LayerIO), C.c_int32, C.POINTER(Diff), C.c_void_p]
     L.tdk_check_layer.argtypes = [C.c_void_p, C.c_int32, C.POINTER(LayerIO), C.c_float, C.c_float,
                                   C.POINTER(ReusePlan), C.c_void_p]
     L.tdk_restore_layers.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.POINTER(C.c_void_p), C.POINTER(C.c_void_p),
@@ -264,6 +268,16 @@ def tdk_restore_layers(r: Round, first_layer: int, host_master_k, host_master_v,
     d_arr = (Diff * max(n, 1))(*diffs)
     _check(load().tdk_restore_layers(r.handle, first_layer, n, hk, hv, io_arr, d_arr, C.byref(pp),
                                      C.c_void_p(compute_stream), C.c_void_p(copy_stream)), "tdk_restore_layers")
+
+
+def tdk_diff_encode_plane(r: Round, layer: int, io: LayerIO, eps: float, plane: int, out: Diff, stream: int = 0) -> None:
+    _check(load().tdk_diff_encode_plane(r.handle, layer, C.byref(io), C.c_float(eps), plane, C.byref(out),
+                                        C.c_void_p(stream)), "tdk_diff_encode_plane")
+
+
+def tdk_diff_decode_plane(r: Round, layer: int, io: LayerIO, plane: int, d: Diff, stream: int = 0) -> None:
+    _check(load().tdk_diff_decode_plane(r.handle, layer, C.byref(io), plane, C.byref(d), C.c_void_p(stream)),
+           "tdk_diff_decode_plane")
 
 
 def tdk_timing_enable(r: Round, on: bool) -> None:

@@ -475,3 +475,53 @@ def test_restore_at_new_offsets(tdo):
     tdo.diff_decode(g, tdo.HostRound(old, diff_pos0=old.agent_pos0), run.mk, run.mv, pk2, pv2, d)
     mask = wl.shared_row_mask(old)
     assert np.array_equal(pk2[mask], run.pk[mask]) and np.array_equal(pv2[mask], run.pv[mask])
+
+
+# ---------------------------------------------------------------------------
+# single-plane diffs (Sec. 5: separate K / V index lists)
+# ---------------------------------------------------------------------------
+
+def test_single_plane_lists_and_restore(tdo):
+    spec = small_spec(H=2, D=8, T=4, sessions=1, agents=3, blocks=4, block_tokens=8, frac=0.0)
+    rnd = wl.make_round(spec)
+    run = OracleRun(tdo, rnd)
+    run.rerotate()
+    P = spec.span_pages
+    rng = np.random.default_rng(17)
+    kset, vset = [], []
+    for i in range(3):
+        kp = np.sort(rng.choice(P, 3, replace=False)); vp = np.sort(rng.choice(P, 2, replace=False))
+        kset.append(kp); vset.append(vp)
+        for p in kp:
+            run.pk[brute_slot(rnd, i, int(p) * 4 + 1), 2] ^= np.uint16(0x0100)
+        for p in vp:
+            run.pv[brute_slot(rnd, i, int(p) * 4 + 2), 5] ^= np.uint16(0x0100)
+    cap = 3 * P
+    dk = tdo.diff_encode_plane(run.g, run.hr, run.mk, run.mv, run.pk, run.pv, 1e-3, 1, cap)
+    dv = tdo.diff_encode_plane(run.g, run.hr, run.mk, run.mv, run.pk, run.pv, 1e-3, 2, cap)
+    dp = run.encode(eps=1e-3)
+    lk, lv, lp = lists_of(dk, 3), lists_of(dv, 3), lists_of(dp, 3)
+    re, T = spec.row_elems, 4
+    for i in range(3):
+        assert np.array_equal(lk[i], kset[i]) and np.array_equal(lv[i], vset[i])
+        assert np.array_equal(lp[i], np.union1d(kset[i], vset[i]))          # the shared list is the union
+        for k, p in enumerate(lk[i]):
+            rows = rnd.dst_rows(i, np.arange(p * T, (p + 1) * T))
+            assert np.array_equal(dk.payload[int(dk.offset[i]) + k].reshape(T, re), run.pk[rows])
+        for k, p in enumerate(lv[i]):
+            rows = rnd.dst_rows(i, np.arange(p * T, (p + 1) * T))
+            assert np.array_equal(dv.payload[int(dv.offset[i]) + k].reshape(T, re), run.pv[rows])
+    # restoring K and V separately gives the same cache as the paired restore, and touches one plane each
+    pk, pv = wl.pool_host(rnd, 0)
+    pk0, pv0 = pk.copy(), pv.copy()
+    tdo.diff_decode_plane(run.g, run.hr, run.mk, run.mv, pk, pv, 1, dk)
+    assert np.array_equal(pv, pv0)
+    mask = wl.shared_row_mask(rnd)
+    assert np.array_equal(pk[mask], run.pk[mask])
+    tdo.diff_decode_plane(run.g, run.hr, run.mk, run.mv, pk, pv, 2, dv)
+    assert np.array_equal(pv[mask], run.pv[mask]) and np.array_equal(pk[~mask], pk0[~mask])
+    qk, qv = wl.pool_host(rnd, 0)
+    run.decode(dp, qk, qv)
+    assert np.array_equal(qk, pk) and np.array_equal(qv, pv)
+    # storage: the two lists together never take more than the shared one
+    assert int(dk.offset[-1]) + int(dv.offset[-1]) <= 2 * int(dp.offset[-1])
