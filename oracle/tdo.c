@@ -191,6 +191,59 @@ int tdo_rotate_rows_bf16(const tdo_geom* g, int64_t delta, int64_t n_rows, const
 
 /* ---- round helpers ------------------------------------------------------- */
 
+/* ---- layout of the shared blocks in an agent's prompt  [Sec. 2.1, Eq. 2] ---- */
+
+static int has_segments(const tdo_round* r, int32_t i) {
+  return r->seg_offset && r->seg_offset[i + 1] > r->seg_offset[i];
+}
+
+/* absolute position of master token m in agent i's prompt */
+static int64_t token_pos(const tdo_round* r, int32_t i, int64_t m) {
+  if (!has_segments(r, i)) return r->agent_pos0[i] + m;
+  for (int64_t q = r->seg_offset[i]; q < r->seg_offset[i + 1]; ++q)
+    if (m >= r->seg_src[q] && m < (int64_t)r->seg_src[q] + r->seg_len[q]) return r->seg_dst[q] + (m - r->seg_src[q]);
+  return -1;
+}
+
+/* the same at the time the stored diff was encoded */
+static int64_t token_diff_pos(const tdo_round* r, int32_t i, int64_t m) {
+  if (!has_segments(r, i)) return (r->agent_diff_pos0 ? r->agent_diff_pos0[i] : r->agent_pos0[i]) + m;
+  if (!r->seg_diff_dst) return token_pos(r, i, m);
+  for (int64_t q = r->seg_offset[i]; q < r->seg_offset[i + 1]; ++q)
+    if (m >= r->seg_src[q] && m < (int64_t)r->seg_src[q] + r->seg_len[q]) return r->seg_diff_dst[q] + (m - r->seg_src[q]);
+  return -1;
+}
+
+/* keeps *t equal to the table of `delta` (rebuilt only when delta changes: once per segment) */
+static int tab_for(rope_tab* t, int* have, int64_t* cur, const tdo_geom* g, int64_t delta) {
+  if (*have && *cur == delta) return 0;
+  if (*have) tab_free(t);
+  *have = 0;
+  if (tab_init(t, g, delta)) return -1;
+  *have = 1;
+  *cur = delta;
+  return 0;
+}
+
+static int segments_ok(const tdo_geom* g, const tdo_round* r, int32_t i, int64_t S, int64_t bt_len, int64_t pool_pages) {
+  const int64_t T = g->page_tokens;
+  int64_t next = 0;
+  for (int64_t q = r->seg_offset[i]; q < r->seg_offset[i + 1]; ++q) {
+    if (r->seg_src[q] != next || r->seg_len[q] <= 0 || r->seg_dst[q] < 0) return 0;
+    if (r->seg_diff_dst && r->seg_diff_dst[q] < 0) return 0;
+    next += r->seg_len[q];
+    for (int64_t p = r->seg_offset[i]; p < q; ++p)       /* destinations must not overlap */
+      if (r->seg_dst[q] < r->seg_dst[p] + r->seg_len[p] && r->seg_dst[p] < r->seg_dst[q] + r->seg_len[q]) return 0;
+    for (int64_t lp = r->seg_dst[q] / T; lp <= (r->seg_dst[q] + r->seg_len[q] - 1) / T; ++lp) {
+      if (lp >= bt_len) return 0;
+      int32_t pp = r->bt_flat[r->bt_offset[i] + lp];
+      if (pp < 0 || pp >= pool_pages) return 0;
+    }
+  }
+  return next == S;
+}
+
+
 static int round_ok(const tdo_geom* g, const tdo_round* r, int64_t pool_pages) {
   if (!geom_ok(g) || !r || r->n_sessions < 0 || r->n_agents < 0 || pool_pages < 0) return 0;
   if (r->n_sessions && (!r->span_tokens || !r->master_pos0)) return 0;
@@ -202,6 +255,10 @@ static int round_ok(const tdo_geom* g, const tdo_round* r, int64_t pool_pages) {
     if (r->agent_diff_pos0 && r->agent_diff_pos0[i] < 0) return 0;
     int64_t len = r->bt_offset[i + 1] - r->bt_offset[i];
     int64_t S = r->span_tokens[s];
+    if (has_segments(r, i)) {
+      if (!r->seg_src || !r->seg_len || !r->seg_dst || !segments_ok(g, r, i, S, len, pool_pages)) return 0;
+      continue;
+    }
     if (S > 0) {
       int64_t need = (r->agent_pos0[i] + S - 1) / g->page_tokens + 1;
       if (len < need) return 0;
@@ -222,7 +279,7 @@ static int64_t session_row0(const tdo_round* r, int32_t s) {
 
 /* slot map: physical pool row of master token m for agent i  [Alg. 1, "slot map S"] */
 static int64_t slot_row(const tdo_geom* g, const tdo_round* r, int32_t i, int64_t m) {
-  int64_t a = r->agent_pos0[i] + m;
+  int64_t a = token_pos(r, i, m);
   int64_t T = g->page_tokens;
   return (int64_t)r->bt_flat[r->bt_offset[i] + a / T] * T + a % T;
 }
@@ -242,15 +299,18 @@ int tdo_rerotate_round(const tdo_geom* g, const tdo_round* r,
     int32_t s = r->agent_session[i];
     int64_t S = r->span_tokens[s];
     int64_t row0 = session_row0(r, s);
-    int64_t delta = r->agent_pos0[i] - r->master_pos0[s];
     rope_tab t;
-    if (tab_init(&t, g, delta)) { err = 1; continue; }
+    int have = 0;
+    int64_t cur = 0;
     for (int64_t m = 0; m < S; ++m) {
+      /* position delta of this token: where it lands minus where the master holds it */
+      int64_t delta = token_pos(r, i, m) - (r->master_pos0[s] + m);
+      if (tab_for(&t, &have, &cur, g, delta)) { err = 1; break; }
       int64_t dst = slot_row(g, r, i, m);
       rotate_row_bf16(g, &t, master_k + (row0 + m) * re, pool_k + dst * re);
       memcpy(pool_v + dst * re, master_v + (row0 + m) * re, (size_t)re * sizeof(uint16_t));
     }
-    tab_free(&t);
+    if (have) tab_free(&t);
   }
   return err ? -2 : 0;
 }
@@ -288,11 +348,12 @@ static int encode_impl(const tdo_geom* g, const tdo_round* r,
     int64_t S = r->span_tokens[s];
     int64_t P = span_pages(g, S);
     int64_t row0 = session_row0(r, s);
-    int64_t delta = r->agent_pos0[i] - r->master_pos0[s];
     rope_tab t;
+    int have = 0;
+    int64_t cur = 0;
     uint16_t* ref = (uint16_t*)malloc((size_t)re * sizeof(uint16_t));
     lists[i] = (int32_t*)malloc((size_t)(P > 0 ? P : 1) * sizeof(int32_t));
-    if (!ref || !lists[i] || tab_init(&t, g, delta)) { err = 1; free(ref); count[i] = 0; continue; }
+    if (!ref || !lists[i]) { err = 1; free(ref); count[i] = 0; continue; }
     int32_t n = 0;
     for (int64_t p = 0; p < P; ++p) {
       int flag = 0;
@@ -300,6 +361,7 @@ static int encode_impl(const tdo_geom* g, const tdo_round* r,
         int64_t m = p * T + q;
         if (m >= S) break;                       /* rows past the span are not part of the page */
         int64_t src = slot_row(g, r, i, m);
+        if (tab_for(&t, &have, &cur, g, token_pos(r, i, m) - (r->master_pos0[s] + m))) { err = 1; break; }
         rotate_row_bf16(g, &t, master_k + (row0 + m) * re, ref);
         for (int64_t e = 0; e < re; ++e) {
           if ((planes & 1) && differs(pool_k[src * re + e], ref[e], eps)) flag = 1;
@@ -310,7 +372,7 @@ static int encode_impl(const tdo_geom* g, const tdo_round* r,
     }
     count[i] = n;
     free(ref);
-    tab_free(&t);
+    if (have) tab_free(&t);
   }
 
   /* 2. exclusive prefix over agents */
@@ -396,13 +458,10 @@ static int decode_impl(const tdo_geom* g, const tdo_round* r,
     int64_t S = r->span_tokens[s];
     int64_t P = span_pages(g, S);
     int64_t row0 = session_row0(r, s);
-    int64_t delta = r->agent_pos0[i] - r->master_pos0[s];
-    /* the diff values sit in the frame of the position they were encoded at */
-    int64_t delta_diff = r->agent_diff_pos0 ? r->agent_pos0[i] - r->agent_diff_pos0[i] : 0;
     rope_tab t, td;
-    if (tab_init(&t, g, delta)) { err = 1; continue; }
-    if (tab_init(&td, g, delta_diff)) { err = 1; tab_free(&t); continue; }
-    for (int64_t p = 0; p < P; ++p) {
+    int have = 0, have_d = 0;
+    int64_t cur = 0, cur_d = 0;
+    for (int64_t p = 0; p < P && !err; ++p) {
       /* is page p in this Mirror's diff? (plain linear search of its index list) */
       int64_t slot = -1;
       for (int32_t k = 0; k < count[i]; ++k)
@@ -411,6 +470,10 @@ static int decode_impl(const tdo_geom* g, const tdo_round* r,
         int64_t m = p * T + q;
         if (m >= S) break;
         int64_t dst = slot_row(g, r, i, m);
+        int64_t delta = token_pos(r, i, m) - (r->master_pos0[s] + m);
+        /* the diff values sit in the frame of the position they were encoded at */
+        int64_t delta_diff = token_pos(r, i, m) - token_diff_pos(r, i, m);
+        if (tab_for(&t, &have, &cur, g, delta) || tab_for(&td, &have_d, &cur_d, g, delta_diff)) { err = 1; break; }
         if (slot >= 0) {
           const int n_planes = planes == 3 ? 2 : 1;
           const uint16_t* pk = payload + slot * n_planes * T * re;
@@ -426,8 +489,8 @@ static int decode_impl(const tdo_geom* g, const tdo_round* r,
         }
       }
     }
-    tab_free(&t);
-    tab_free(&td);
+    if (have) tab_free(&t);
+    if (have_d) tab_free(&td);
   }
   return err ? -2 : 0;
 }
@@ -466,9 +529,12 @@ int tdo_key_deviation(const tdo_geom* g, const tdo_round* r,
     int64_t S = r->span_tokens[s];
     int64_t row0 = session_row0(r, s);
     rope_tab t;
+    int have = 0;
+    int64_t cur = 0;
     uint16_t* ref = (uint16_t*)malloc((size_t)re * sizeof(uint16_t));
-    if (!ref || tab_init(&t, g, r->agent_pos0[i] - r->master_pos0[s])) { err = 1; free(ref); continue; }
+    if (!ref) { err = 1; continue; }
     for (int64_t m = 0; m < S; ++m) {
+      if (tab_for(&t, &have, &cur, g, token_pos(r, i, m) - (r->master_pos0[s] + m))) { err = 1; break; }
       rotate_row_bf16(g, &t, master_k + (row0 + m) * re, ref);
       const uint16_t* fresh = pool_k + slot_row(g, r, i, m) * re;
       double acc = 0.0;
@@ -479,7 +545,7 @@ int tdo_key_deviation(const tdo_geom* g, const tdo_round* r,
       score[base[i] + m] = acc;
     }
     free(ref);
-    tab_free(&t);
+    if (have) tab_free(&t);
   }
   free(base);
   return err ? -2 : 0;

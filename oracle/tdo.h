@@ -59,6 +59,16 @@ typedef struct {
   const int64_t* bt_offset;
   const int64_t* agent_diff_pos0; /* optional (NULL = agent_pos0): position of the agent's first shared token
                                      when the diff given to tdo_diff_decode was encoded (an earlier round) */
+  /* optional layout of the shared blocks per agent (Eq. 2, the scheduler-defined layout Pi_i): agent i's
+   * segments are seg_*[seg_offset[i] .. seg_offset[i+1]); segment q places master tokens
+   * [seg_src[q], seg_src[q] + seg_len[q]) at positions seg_dst[q] ..; sorted by seg_src, covering
+   * [0, S) exactly once, destinations disjoint.  NULL seg_offset (or an empty range) = the identity
+   * layout agent_pos0 + m.  seg_diff_dst (optional) = the same for the stored diff's frame. */
+  const int64_t* seg_offset;
+  const int32_t* seg_src;
+  const int32_t* seg_len;
+  const int64_t* seg_dst;
+  const int64_t* seg_diff_dst;
 } tdo_round;
 
 /* cos/sin of phi_j = delta * theta^(-2j/D), j = 0 .. D/2-1 */

@@ -39,7 +39,9 @@ class Geom(C.Structure):
 class RoundDesc(C.Structure):
     _fields_ = [("n_sessions", C.c_int32), ("span_tokens", C.c_void_p), ("master_pos0", C.c_void_p),
                 ("n_agents", C.c_int32), ("agent_session", C.c_void_p), ("agent_pos0", C.c_void_p),
-                ("bt_flat", C.c_void_p), ("bt_offset", C.c_void_p), ("agent_diff_pos0", C.c_void_p)]
+                ("bt_flat", C.c_void_p), ("bt_offset", C.c_void_p), ("agent_diff_pos0", C.c_void_p),
+                ("seg_offset", C.c_void_p), ("seg_src", C.c_void_p), ("seg_len", C.c_void_p),
+                ("seg_dst", C.c_void_p), ("seg_diff_dst", C.c_void_p)]
 
 
 _lib: Optional[C.CDLL] = None
@@ -110,7 +112,18 @@ class HostRound:
                         if len(rnd.block_tables) else np.zeros(0, np.int32))
         self.desc = RoundDesc(len(self.span_tokens), _p(self.span_tokens), _p(self.master_pos0),
                               len(self.agent_session), _p(self.agent_session), _p(self.agent_pos0),
-                              _p(self.bt_flat), _p(self.bt_offset), None)
+                              _p(self.bt_flat), _p(self.bt_offset), None, None, None, None, None, None)
+        segs = getattr(rnd, "segments", None)
+        if segs is not None:
+            # per agent an int64 array [n_seg, 3] = (src_tok, dst_pos, len); empty = identity layout
+            n = np.array([len(x) for x in segs], dtype=np.int64)
+            self.seg_offset = np.concatenate([[0], np.cumsum(n)]).astype(np.int64)
+            flat = np.concatenate([np.asarray(x, dtype=np.int64).reshape(-1, 3) for x in segs]) if n.sum() else np.zeros((0, 3), np.int64)
+            self.seg_src = np.ascontiguousarray(flat[:, 0], dtype=np.int32)
+            self.seg_dst = np.ascontiguousarray(flat[:, 1], dtype=np.int64)
+            self.seg_len = np.ascontiguousarray(flat[:, 2], dtype=np.int32)
+            self.desc.seg_offset, self.desc.seg_src = _p(self.seg_offset), _p(self.seg_src)
+            self.desc.seg_len, self.desc.seg_dst = _p(self.seg_len), _p(self.seg_dst)
         self.diff_pos0 = None
         if diff_pos0 is not None:
             self.diff_pos0 = np.ascontiguousarray(diff_pos0, dtype=np.int64)

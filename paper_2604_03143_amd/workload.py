@@ -89,6 +89,9 @@ class Round:
     canary_pages: np.ndarray       # int32 [2*n_agents], mapped by nobody
     perturbed: List[np.ndarray]    # per agent sorted int32 master-page numbers
     extra: dict = field(default_factory=dict)
+    # optional layout of the shared blocks per agent (Eq. 2, Pi_i): int64 [n_seg, 3] rows of
+    # (first master token, absolute position it lands at, length); None = identity for every agent
+    segments: Optional[List[np.ndarray]] = None
 
     @property
     def n_agents(self) -> int:
@@ -110,9 +113,40 @@ class Round:
         T = self.spec.page_tokens
         S = int(self.span_tokens[self.agent_session[agent]])
         m = np.arange(S, dtype=np.int64) if tokens is None else np.asarray(tokens, dtype=np.int64)
-        a = int(self.agent_pos0[agent]) + m
+        a = self.token_pos(agent, m)
         bt = self.block_tables[agent]
         return bt[a // T].astype(np.int64) * T + (a % T)
+
+
+def _token_pos(self, agent: int, m: np.ndarray) -> np.ndarray:
+    """Absolute position of master tokens m in this agent's prompt."""
+    m = np.asarray(m, dtype=np.int64)
+    if self.segments is None or len(self.segments[agent]) == 0:
+        return int(self.agent_pos0[agent]) + m
+    seg = np.asarray(self.segments[agent], dtype=np.int64)
+    q = np.searchsorted(seg[:, 0], m, side="right") - 1
+    return seg[q, 1] + (m - seg[q, 0])
+
+
+Round.token_pos = _token_pos
+
+
+def permute_blocks(rnd: Round, seed_tag: int = 4) -> Round:
+    """Gives every agent its own order of the shared blocks (the scheduler-defined layout of Eq. 2):
+    block b of the master lands at h_i + rank_i(b) * block_tokens.  Block tables are unchanged (the
+    permuted span occupies the same positions)."""
+    spec = rnd.spec
+    g = _rng(spec, seed_tag)
+    segs = []
+    for i in range(rnd.n_agents):
+        order = g.permutation(spec.blocks)            # order[k] = block placed k-th
+        rank = np.empty(spec.blocks, dtype=np.int64)
+        rank[order] = np.arange(spec.blocks)
+        h = int(rnd.agent_pos0[i])
+        segs.append(np.array([[b * spec.block_tokens, h + int(rank[b]) * spec.block_tokens, spec.block_tokens]
+                              for b in range(spec.blocks)], dtype=np.int64))
+    rnd.segments = segs
+    return rnd
 
 
 def _rng(spec: RoundSpec, tag: int, extra: int = 0) -> np.random.Generator:
@@ -330,5 +364,6 @@ def subround(rnd: Round, agents) -> "tuple[Round, np.ndarray]":
                 np.array([smap[int(rnd.agent_session[a])] for a in agents], dtype=np.int32),
                 rnd.agent_pos0[agents].astype(np.int64), tables, len(page_map), 0,
                 np.zeros(0, np.int32), [rnd.perturbed[a] for a in agents],
-                extra={"sessions": sess_ids, "agents": agents})
+                extra={"sessions": sess_ids, "agents": agents},
+                segments=None if rnd.segments is None else [rnd.segments[a] for a in agents])
     return sub, np.array(page_map, dtype=np.int64)

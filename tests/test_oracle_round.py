@@ -525,3 +525,76 @@ def test_single_plane_lists_and_restore(tdo):
     assert np.array_equal(qk, pk) and np.array_equal(qv, pv)
     # storage: the two lists together never take more than the shared one
     assert int(dk.offset[-1]) + int(dv.offset[-1]) <= 2 * int(dp.offset[-1])
+
+
+# ---------------------------------------------------------------------------
+# permuted block order (Eq. 2: the scheduler-defined layout of the shared blocks)
+# ---------------------------------------------------------------------------
+
+def _brute_token(rnd, i, m):
+    """(absolute position, physical row) of master token m for agent i, from the segment list."""
+    T = rnd.spec.page_tokens
+    a = None
+    for src, dst, ln in rnd.segments[i]:
+        if src <= m < src + ln:
+            a = int(dst + (m - src))
+    return a, int(rnd.block_tables[i][a // T]) * T + a % T
+
+
+def test_permuted_layout_bruteforce(tdo):
+    spec = small_spec(H=2, D=8, T=4, agents=3, blocks=4, block_tokens=7, hist=(2, 30), theta=1.0e4)
+    rnd = wl.permute_blocks(wl.make_round(spec))
+    assert any(not np.array_equal(s[:, 1], np.sort(s[:, 1])) for s in rnd.segments)   # really permuted
+    run = OracleRun(tdo, rnd)
+    pk0 = run.pk.copy()
+    run.rerotate()
+    S = spec.span_tokens
+    written = np.zeros(len(pk0), bool)
+    for i in range(rnd.n_agents):
+        for m in range(S):
+            a, row = _brute_token(rnd, i, m)
+            assert not written[row]
+            written[row] = True
+            exact = brute_rotated_row(run.mk[m], a - m, spec.rope_theta, 2, 8)    # delta = position - master position
+            got = wl.bf16_bits_to_f32(run.pk[row]).astype(np.float64)
+            assert np.all(np.abs(got - exact) <= 0.5 * bf16_ulp(exact) + 1e-6)
+            assert np.array_equal(run.pv[row], run.mv[m])
+    assert np.array_equal(run.pk[~written], pk0[~written])
+    # pages straddle block boundaries (7-token blocks, 4-token pages): the diff still lists master pages
+    run.perturb()
+    d = run.encode()
+    for i, lst in enumerate(lists_of(d, rnd.n_agents)):
+        assert np.array_equal(lst, rnd.perturbed[i])
+    pk, pv = wl.pool_host(rnd, 0)
+    run.decode(d, pk, pv)
+    mask = wl.shared_row_mask(rnd)
+    assert np.array_equal(pk[mask], run.pk[mask]) and np.array_equal(pv[mask], run.pv[mask])
+    sc = tdo.key_deviation(run.g, run.hr, run.mk, run.pk).reshape(rnd.n_agents, S)
+    for i in range(rnd.n_agents):
+        hot = np.zeros(S, bool)
+        for p in rnd.perturbed[i]:
+            hot[p * 4:min(S, p * 4 + 4)] = True
+        assert np.all(sc[i][hot] > 0) and np.all(sc[i][~hot] == 0)
+
+
+def test_identity_segments_equal_no_segments(tdo):
+    spec = small_spec(H=2, D=8, T=4, agents=2, blocks=3, block_tokens=6)
+    a = wl.make_round(spec)
+    b = wl.make_round(spec)
+    b.segments = [np.array([[k * 6, int(b.agent_pos0[i]) + k * 6, 6] for k in range(3)], np.int64) for i in range(2)]
+    ra, rb = OracleRun(tdo, a), OracleRun(tdo, b)
+    ra.rerotate(); rb.rerotate()
+    assert np.array_equal(ra.pk, rb.pk) and np.array_equal(ra.pv, rb.pv)
+
+
+def test_bad_segments_rejected(tdo):
+    spec = small_spec(H=2, D=8, T=4, agents=1, blocks=2, block_tokens=6)
+    for segs in ([[0, 5, 6], [6, 8, 6]],            # destinations overlap
+                 [[0, 5, 6]],                        # does not cover the span
+                 [[6, 5, 6], [0, 11, 6]],            # not sorted by source
+                 [[0, 5, 6], [6, 400, 6]]):          # beyond the block table
+        rnd = wl.make_round(spec, hist=np.array([5]))
+        rnd.segments = [np.array(segs, np.int64)]
+        run = OracleRun(tdo, rnd)
+        with pytest.raises(ValueError):
+            run.rerotate()
