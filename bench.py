@@ -34,6 +34,8 @@ def parse():
     ap.add_argument("--no-check", action="store_true")
     ap.add_argument("--alloc", default="fragmented", choices=["fragmented", "contiguous"],
                     help="physical page placement of the synthetic pool (fragmented = the graded recipe)")
+    ap.add_argument("--layout", default="identity", choices=["identity", "permuted"],
+                    help="order of the shared blocks in every agent's prompt (identity = the graded recipe)")
     ap.add_argument("--mode", default="step", choices=["step", "restore", "check", "planes"],
                     help="step: the whole hot path (default, the headline metric); restore: layerwise ping-pong "
                          "restore from pinned host memory (Alg. 1) against a dense restore")
@@ -70,6 +72,8 @@ def main():
     spec = wl.CONFIGS[args.workload]
     L = args.layers or spec.num_layers
     rnd = wl.make_round(spec, alloc=args.alloc)
+    if args.layout == "permuted":
+        rnd = wl.permute_blocks(rnd)
     A, T, RE = rnd.n_agents, spec.page_tokens, spec.row_elems
     pool_rows = rnd.pool_pages * T
     n_pert = sum(len(p) for p in rnd.perturbed)
@@ -228,7 +232,7 @@ def main():
                dtype="bf16", data="synthetic",
                config=dict(workload=args.workload, layers=L, agents=A, sessions=rnd.n_sessions,
                            span_tokens=int(spec.span_tokens), page_tokens=T, perturbed_pages=n_pert,
-                           ring_layers=ring, alloc=args.alloc, agents_per_group="auto" if not args.group else args.group,
+                           ring_layers=ring, alloc=args.alloc, layout=args.layout, agents_per_group="auto" if not args.group else args.group,
                            step="rerotate+decode+encode per layer, all layers"),
                roofline=roofline, cpu_baseline=cpu,
                rates={k: round(v, 1) for k, v in rates.items()},

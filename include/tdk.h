@@ -77,6 +77,14 @@ typedef struct {
   int64_t master_pos0;    /* absolute position the master's token 0 is rotated for */
 } tdk_session;
 
+/* One run of consecutive master tokens in an agent's prompt: master tokens src_tok .. src_tok+len-1
+ * land at absolute positions dst_pos .. dst_pos+len-1. */
+typedef struct {
+  int32_t src_tok;
+  int32_t len;
+  int64_t dst_pos;
+} tdk_segment;
+
 /* One agent sub-request (a mirror of its session's master). */
 typedef struct {
   int32_t        session;          /* index into sessions[]                                        */
@@ -88,6 +96,13 @@ typedef struct {
                                       to dst_pos0 for a diff of this round; for a mirror stored in an
                                       earlier round its K values are re-rotated by dst_pos0 - diff_pos0
                                       on restore (Alg. 1, RoPERecover(P_old, P_new)).  Ignored by encode. */
+  int32_t        n_segments;       /* 0: identity layout (the shared span sits at dst_pos0 .. dst_pos0+S-1).
+                                      > 0: the scheduler-defined layout of the shared blocks for this agent
+                                      (Sec. 2.1, Eq. 2): segments sorted by src_tok, covering [0, S) exactly
+                                      once, destinations disjoint, every master page meeting at most two
+                                      segments (true whenever blocks are at least a page long); dst_pos0 is
+                                      then unused and diff_pos0 must equal dst_pos0. */
+  const tdk_segment* segments;     /* HOST */
 } tdk_agent;
 
 typedef struct tdk_round tdk_round;   /* opaque: tables, descriptors, scratch on the current device */

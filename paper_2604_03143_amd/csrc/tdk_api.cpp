@@ -316,15 +316,41 @@ tdk_status tdk_round_create(const tdk_model* model, const tdk_session* sessions,
   }
   r->total_master_rows = row0;
   int64_t flag_off = 0, score_off = 0;
+  bool any_segments = false;
+  for (int32_t i = 0; i < n_agents; ++i) any_segments |= agents[i].n_segments > 0;
+  std::vector<int32_t> rowmap;
+  std::vector<int4> pagetab;
+  std::vector<float> segtab;
   for (int32_t i = 0; i < n_agents; ++i) {
     const tdk_agent& a = agents[i];
     if (a.session < 0 || a.session >= n_sessions) { delete r; return fail(TDK_ERR_INVALID_ARG, "agent: session index out of range"); }
     if (a.dst_pos0 < 0) { delete r; return fail(TDK_ERR_INVALID_ARG, "agent: negative dst_pos0"); }
     HostSession& hs = r->sessions[a.session];
     const int64_t S = hs.span;
-    if (a.dst_pos0 + S + T >= (int64_t)1 << 31) { delete r; return fail(TDK_ERR_INVALID_ARG, "agent: positions beyond 2^31"); }
-    const int64_t lp_first = a.dst_pos0 / T;
-    const int64_t lp_last = S > 0 ? (a.dst_pos0 + S - 1) / T : lp_first - 1;
+    if (a.n_segments < 0 || (a.n_segments > 0 && !a.segments)) { delete r; return fail(TDK_ERR_INVALID_ARG, "agent: bad segment list"); }
+    // the logical pages the shared span touches: one range for the identity layout, the hull of the
+    // segments otherwise
+    int64_t pos_lo = a.dst_pos0, pos_hi = a.dst_pos0 + S;   // [lo, hi)
+    if (a.n_segments > 0) {
+      if (a.diff_pos0 != a.dst_pos0) { delete r; return fail(TDK_ERR_UNSUPPORTED, "agent: a segmented layout cannot restore a diff stored at other positions"); }
+      int64_t next = 0;
+      pos_lo = INT64_MAX; pos_hi = 0;
+      for (int32_t q = 0; q < a.n_segments; ++q) {
+        const tdk_segment& sg = a.segments[q];
+        if (sg.src_tok != next || sg.len <= 0 || sg.dst_pos < 0) { delete r; return fail(TDK_ERR_INVALID_ARG, "agent: segments must be sorted, contiguous in the master and non-empty"); }
+        for (int32_t o = 0; o < q; ++o) {
+          const tdk_segment& og = a.segments[o];
+          if (sg.dst_pos < og.dst_pos + og.len && og.dst_pos < sg.dst_pos + sg.len) { delete r; return fail(TDK_ERR_INVALID_ARG, "agent: segment destinations overlap"); }
+        }
+        next += sg.len;
+        pos_lo = std::min<int64_t>(pos_lo, sg.dst_pos);
+        pos_hi = std::max<int64_t>(pos_hi, sg.dst_pos + sg.len);
+      }
+      if (next != S) { delete r; return fail(TDK_ERR_INVALID_ARG, "agent: segments do not cover the span"); }
+    }
+    if (pos_hi + T >= (int64_t)1 << 31) { delete r; return fail(TDK_ERR_INVALID_ARG, "agent: positions beyond 2^31"); }
+    const int64_t lp_first = S > 0 ? pos_lo / T : a.dst_pos0 / T;
+    const int64_t lp_last = S > 0 ? (pos_hi - 1) / T : lp_first - 1;
     if (S > 0) {
       if (!a.block_table) { delete r; return fail(TDK_ERR_INVALID_ARG, "agent: block_table is NULL"); }
       if ((int64_t)a.block_table_len <= lp_last) { delete r; return fail(TDK_ERR_INVALID_ARG, "agent: block_table too short for its span"); }
@@ -340,11 +366,55 @@ tdk_status tdk_round_create(const tdk_model* model, const tdk_session* sessions,
     if (a.diff_pos0 < 0) { delete r; return fail(TDK_ERR_INVALID_ARG, "agent: negative diff_pos0"); }
     ad.diff_rot = a.diff_pos0 != a.dst_pos0;
     score_off += S;
-    for (int64_t lp = lp_first; lp <= lp_last; ++lp) {
-      const int32_t pg = a.block_table[lp];
-      if (pg < 0) { delete r; return fail(TDK_ERR_INVALID_ARG, "agent: negative page number in block_table"); }
-      r->max_phys_page = std::max<int64_t>(r->max_phys_page, pg);
-      bt.push_back(pg);
+    {
+      // only pages that hold shared tokens count (the hull of a permuted layout may contain others)
+      auto touch = [&](int64_t lo, int64_t hi) -> bool {
+        for (int64_t lp = lo / T; lp <= (hi - 1) / T; ++lp) {
+          if (a.block_table[lp] < 0) return false;
+          r->max_phys_page = std::max<int64_t>(r->max_phys_page, a.block_table[lp]);
+        }
+        return true;
+      };
+      bool ok = true;
+      if (S > 0 && a.n_segments == 0) ok = touch(pos_lo, pos_hi);
+      for (int32_t q = 0; q < a.n_segments && ok; ++q) ok = touch(a.segments[q].dst_pos, a.segments[q].dst_pos + a.segments[q].len);
+      if (!ok) { delete r; return fail(TDK_ERR_INVALID_ARG, "agent: negative page number in block_table"); }
+    }
+    for (int64_t lp = lp_first; lp <= lp_last; ++lp) bt.push_back(a.block_table[lp]);
+    // layout tables (only if some agent of the round has segments)
+    if (any_segments) {
+      tdk_segment whole{0, (int32_t)S, a.dst_pos0};
+      const tdk_segment* segs = a.n_segments ? a.segments : &whole;
+      const int32_t nseg = a.n_segments ? a.n_segments : (S > 0 ? 1 : 0);
+      const int32_t tab0 = (int32_t)(segtab.size() / (2 * kHalf));
+      for (int32_t q = 0; q < nseg; ++q) {
+        const double delta = (double)(segs[q].dst_pos - (hs.master_pos0 + segs[q].src_tok));
+        for (int j = 0; j < kHalf; ++j) {
+          const double inv_freq = std::pow(model->rope_theta, -(double)(2 * j) / (double)model->head_dim);
+          segtab.push_back((float)std::cos(delta * inv_freq));
+        }
+        for (int j = 0; j < kHalf; ++j) {
+          const double inv_freq = std::pow(model->rope_theta, -(double)(2 * j) / (double)model->head_dim);
+          segtab.push_back((float)std::sin(delta * inv_freq));
+        }
+        for (int32_t m = segs[q].src_tok; m < segs[q].src_tok + segs[q].len; ++m) {
+          const int64_t pos = segs[q].dst_pos + (m - segs[q].src_tok);
+          rowmap.push_back((int32_t)((int64_t)a.block_table[pos / T] * T + pos % T));
+        }
+      }
+      int32_t q = 0;
+      for (int32_t p = 0; p < hs.pages; ++p) {
+        const int32_t m_lo = p * T, m_hi = (int32_t)std::min<int64_t>(S, (int64_t)(p + 1) * T);
+        while (segs[q].src_tok + segs[q].len <= m_lo) ++q;
+        int4 e = make_int4(tab0 + q, tab0 + q, 0, 0);
+        int32_t q2 = q;
+        for (int32_t m = m_lo; m < m_hi; ++m) {
+          while (segs[q2].src_tok + segs[q2].len <= m) ++q2;
+          if (q2 > q + 1) { delete r; return fail(TDK_ERR_UNSUPPORTED, "agent: a master page meets more than two segments"); }
+          if (q2 == q + 1) { e.y = tab0 + q2; e.z |= 1 << (m - m_lo); }
+        }
+        pagetab.push_back(e);
+      }
     }
     flag_off += hs.pages;
     if (flag_off >= (int64_t)1 << 31 || score_off >= (int64_t)1 << 31 || bt.size() >= (size_t)1 << 31) { delete r; return fail(TDK_ERR_UNSUPPORTED, "round too large"); }
@@ -391,6 +461,9 @@ tdk_status tdk_round_create(const tdk_model* model, const tdk_session* sessions,
   const size_t o_bt = place(bt.size() * sizeof(int32_t));
   const size_t o_tab = place(tab.size() * sizeof(float));
   const size_t o_tab_diff = place(tab_diff.size() * sizeof(float));
+  const size_t o_rowmap = place(any_segments ? rowmap.size() * sizeof(int32_t) : 0);
+  const size_t o_pagetab = place(any_segments ? pagetab.size() * sizeof(int4) : 0);
+  const size_t o_segtab = place(any_segments ? segtab.size() * sizeof(float) : 0);
   const size_t o_flags = place((size_t)flag_off);
   r->blob_bytes = std::max<size_t>(off, 256);
 
@@ -408,6 +481,9 @@ tdk_status tdk_round_create(const tdk_model* model, const tdk_session* sessions,
   if (e == hipSuccess) e = up(o_bt, bt.data(), bt.size() * sizeof(int32_t));
   if (e == hipSuccess) e = up(o_tab, tab.data(), tab.size() * sizeof(float));
   if (e == hipSuccess) e = up(o_tab_diff, tab_diff.data(), tab_diff.size() * sizeof(float));
+  if (e == hipSuccess && any_segments) e = up(o_rowmap, rowmap.data(), rowmap.size() * sizeof(int32_t));
+  if (e == hipSuccess && any_segments) e = up(o_pagetab, pagetab.data(), pagetab.size() * sizeof(int4));
+  if (e == hipSuccess && any_segments) e = up(o_segtab, segtab.data(), segtab.size() * sizeof(float));
   if (e == hipSuccess && flag_off) e = hipMemset(base + o_flags, 0, (size_t)flag_off);
   if (e != hipSuccess) { (void)hipFree(r->blob); delete r; return hip_fail(e, "upload of round descriptors"); }
 
@@ -419,6 +495,10 @@ tdk_status tdk_round_create(const tdk_model* model, const tdk_session* sessions,
   r->rd.tab = reinterpret_cast<const float*>(base + o_tab);
   r->rd.tab_diff = reinterpret_cast<const float*>(base + o_tab_diff);
   r->rd.flags = reinterpret_cast<uint8_t*>(base + o_flags);
+  r->rd.seg = any_segments ? 1 : 0;
+  r->rd.rowmap = any_segments ? reinterpret_cast<const int32_t*>(base + o_rowmap) : nullptr;
+  r->rd.pagetab = any_segments ? reinterpret_cast<const int4*>(base + o_pagetab) : nullptr;
+  r->rd.segtab = any_segments ? reinterpret_cast<const float*>(base + o_segtab) : nullptr;
   r->rd.n_agents = n_agents;
   r->rd.n_sessions = n_sessions;
   r->rd.heads = model->num_kv_heads;

@@ -51,12 +51,17 @@ struct RoundDev {
   const int32_t*    bt;      // block-table slices, concatenated
   const float*      tab;     // [n_agents][2][64]: cos then sin of the agent's delta
   const float*      tab_diff;  // [n_agents][2][64]: same for dst_pos0 - diff_pos0 (payload re-rotation)
+  // general block layouts (some agent has its own order of the shared blocks); all NULL otherwise
+  const int32_t*    rowmap;    // [sum_i S_i]: pool row of (agent, master token), agents in order
+  const int4*       pagetab;   // [sum_i pages_i]: {first table, second table, row mask of the second, 0}
+  const float*      segtab;    // [n tables][2][64]: cos then sin, one table per (agent, segment)
   uint8_t*          flags;   // [sum_i pages_i] scratch of encode
   int32_t n_work, n_agents, n_sessions;
   int32_t heads;             // H
   int32_t page_tokens;       // T
   int32_t interleaved;       // rope style
   int32_t nontemporal;
+  int32_t seg;               // 1: rowmap / pagetab / segtab describe the layout
 };
 
 struct LayerDev {

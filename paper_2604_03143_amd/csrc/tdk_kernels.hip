@@ -83,6 +83,42 @@ struct GroupShared {
   int32_t agent[kMaxGroup];
 };
 
+// The same for rounds with per-agent block layouts: a master page can meet two segments of an agent
+// (two position deltas), and its rows can land anywhere, so the pool row of every row is staged.
+struct GroupSharedSeg {
+  float    tab[kMaxGroup][2][2 * kHalf];
+  int32_t  row[kMaxGroup][32];       // pool row of each row of the page
+  uint32_t sel[kMaxGroup];           // bit r set: row r uses the second table
+  int32_t  aux[kMaxGroup];
+  int32_t  agent[kMaxGroup];
+};
+
+template <int T>
+__device__ __forceinline__ void stage_group(const RoundDev& rd, const WorkItem& w, GroupSharedSeg& sh) {
+  const int tid = threadIdx.x;
+  for (int i = tid; i < w.ag_count * 64; i += kBlock) {
+    const int g = i >> 6, which = (i >> 5) & 1, q = i & 31;
+    const AgentDev ad = rd.agents[rd.order[w.ag_begin + g]];
+    const int4 pt = rd.pagetab[ad.flag_off + w.page];
+    const int t = which ? pt.y : pt.x;
+    reinterpret_cast<float4*>(sh.tab[g][which])[q] =
+        reinterpret_cast<const float4*>(rd.segtab + (size_t)t * (2 * kHalf))[q];
+  }
+  const SessionDev sd = rd.sess[w.session];
+  for (int i = tid; i < w.ag_count * T; i += kBlock) {
+    const int g = i / T, r = i - g * T;
+    const AgentDev ad = rd.agents[rd.order[w.ag_begin + g]];
+    const int m = w.page * T + r;
+    sh.row[g][r] = m < sd.span ? rd.rowmap[ad.score_off + m] : 0;
+  }
+  if (tid < w.ag_count) {
+    const int a = rd.order[w.ag_begin + tid];
+    sh.sel[tid] = (uint32_t)rd.pagetab[rd.agents[a].flag_off + w.page].z;
+    sh.aux[tid] = 0;
+    sh.agent[tid] = a;
+  }
+}
+
 template <int T>
 __device__ __forceinline__ void stage_group(const RoundDev& rd, const WorkItem& w, GroupShared& sh) {
   const int tid = threadIdx.x;
@@ -127,9 +163,15 @@ __device__ __forceinline__ Lane lane_geometry(int H) {
   return L;
 }
 
-template <bool IL>
-__device__ __forceinline__ void load_tab(const GroupShared& sh, int g, int jb, float (&c)[8], float (&s)[8]) {
-  const float* t = sh.tab[g];
+__device__ __forceinline__ const float* tab_of(const GroupShared& sh, int g, int) { return sh.tab[g]; }
+__device__ __forceinline__ const float* tab_of(const GroupSharedSeg& sh, int g, int r) {
+  return sh.tab[g][(sh.sel[g] >> r) & 1u];
+}
+
+// cos/sin a lane needs for row r of agent g (r matters only with per-agent block layouts)
+template <bool IL, class Shared>
+__device__ __forceinline__ void load_tab(const Shared& sh, int g, int r, int jb, float (&c)[8], float (&s)[8]) {
+  const float* t = tab_of(sh, g, r);
   if (!IL) {
 #pragma unroll
     for (int e = 0; e < 8; ++e) { c[e] = t[jb * 8 + e]; s[e] = t[kHalf + jb * 8 + e]; }
@@ -171,6 +213,9 @@ __device__ __forceinline__ void load_master(const RoundDev& rd, const LayerDev& 
   }
 }
 
+template <int T>
+__device__ __forceinline__ int64_t dest_row(const GroupSharedSeg& sh, int g, int r) { return sh.row[g][r]; }
+
 // physical pool row of row r (0..T-1) of the master page for agent g of the group
 template <int T>
 __device__ __forceinline__ int64_t dest_row(const GroupShared& sh, int g, int r) {
@@ -183,10 +228,10 @@ __device__ __forceinline__ int64_t dest_row(const GroupShared& sh, int g, int r)
 // rerotate: pool_k <- bf16(R(delta_i) master_k), pool_v <- master_v       [Sec. 4.2]
 // ---------------------------------------------------------------------------------------------
 
-template <int RPW, bool IL, bool NT>
+template <int RPW, bool IL, bool NT, bool SEG>
 __global__ __launch_bounds__(kBlock) void tdk_rerotate_kernel(const RoundDev rd, const LayerDev io) {
   constexpr int T = RPW * kWaves;
-  __shared__ GroupShared sh;
+  __shared__ std::conditional_t<SEG, GroupSharedSeg, GroupShared> sh;
   const WorkItem w = rd.work[blockIdx.x];
   const Lane L = lane_geometry(rd.heads);
   stage_group<T>(rd, w, sh);
@@ -199,12 +244,13 @@ __global__ __launch_bounds__(kBlock) void tdk_rerotate_kernel(const RoundDev rd,
   u32x4* pv = io.pool_v;
   for (int g = 0; g < w.ag_count; ++g) {
     float c[8], s[8];
-    load_tab<IL>(sh, g, L.jb, c, s);
+    if (!SEG) load_tab<IL>(sh, g, 0, L.jb, c, s);
 #pragma unroll
     for (int k = 0; k < RPW; ++k) {
       if (!M.valid[k]) continue;
       const int64_t base = dest_row<T>(sh, g, wave + kWaves * k) * row_u4;
       if (L.kok) {
+        if (SEG) load_tab<IL>(sh, g, wave + kWaves * k, L.jb, c, s);
         u32x4 olo, ohi;
         rotate16<IL>(M.kl[k], M.kh[k], c, s, olo, ohi);
         st16<NT>(pk + base + L.klo, olo);
@@ -251,11 +297,11 @@ __device__ __forceinline__ bool chunk_special(const u32x4 m) {
 }
 
 // PM: planes that take part (bit 0 = K, bit 1 = V); 3 is the paired diff, 1 / 2 the single-plane diffs
-template <int RPW, bool IL, int PM>
+template <int RPW, bool IL, int PM, bool SEG>
 __global__ __launch_bounds__(kBlock) void tdk_flag_kernel(const RoundDev rd, const LayerDev io, const float eps) {
   constexpr int T = RPW * kWaves;
   constexpr bool DOK = (PM & 1) != 0, DOV = (PM & 2) != 0;
-  __shared__ GroupShared sh;
+  __shared__ std::conditional_t<SEG, GroupSharedSeg, GroupShared> sh;
   const WorkItem w = rd.work[blockIdx.x];
   const Lane L = lane_geometry(rd.heads);
   stage_group<T>(rd, w, sh);
@@ -272,7 +318,7 @@ __global__ __launch_bounds__(kBlock) void tdk_flag_kernel(const RoundDev rd, con
   const u32x4* pv = io.pool_v;
   for (int g = 0; g < w.ag_count; ++g) {
     float c[8], s[8];
-    if (DOK) load_tab<IL>(sh, g, L.jb, c, s);
+    if (DOK && !SEG) load_tab<IL>(sh, g, 0, L.jb, c, s);
     u32x4 akl[RPW], akh[RPW], av0[RPW], av1[RPW];
     const u32x4 z = {0, 0, 0, 0};
 #pragma unroll
@@ -289,6 +335,7 @@ __global__ __launch_bounds__(kBlock) void tdk_flag_kernel(const RoundDev rd, con
     for (int k = 0; k < RPW; ++k) {
       if (!M.valid[k]) continue;
       u32x4 rlo = z, rhi = z;
+      if (DOK && SEG) load_tab<IL>(sh, g, wave + kWaves * k, L.jb, c, s);
       if (DOK && L.kok) rotate16<IL>(M.kl[k], M.kh[k], c, s, rlo, rhi);
       // rows whose bits all match the reference (the common case) need no fp32 compare
       uint32_t x = 0;
@@ -406,7 +453,8 @@ __global__ __launch_bounds__(kBlock) void tdk_gather_kernel(const RoundDev rd, c
       int64_t row = -1;
       if (m < rd.sess[ad.session].span) {
         const int a0 = ad.pos0 + m;
-        row = (int64_t)rd.bt[ad.bt_off + a0 / T - ad.lp_first] * T + a0 % T;
+        row = rd.seg ? (int64_t)rd.rowmap[ad.score_off + m]
+                     : (int64_t)rd.bt[ad.bt_off + a0 / T - ad.lp_first] * T + a0 % T;
       }
       sh.row[threadIdx.x] = row;
     }
@@ -445,10 +493,10 @@ __global__ __launch_bounds__(kBlock) void tdk_gather_kernel(const RoundDev rd, c
 // decode: diff pages from the payload, all others from the re-rotated master   [Sec. 4.4, Alg. 1]
 // ---------------------------------------------------------------------------------------------
 
-template <int RPW, bool IL, bool NT, int PM>
+template <int RPW, bool IL, bool NT, int PM, bool SEG>
 __global__ __launch_bounds__(kBlock) void tdk_decode_kernel(const RoundDev rd, const LayerDev io, const DiffDev d) {
   constexpr int T = RPW * kWaves;
-  __shared__ GroupShared sh;
+  __shared__ std::conditional_t<SEG, GroupSharedSeg, GroupShared> sh;
   const WorkItem w = rd.work[blockIdx.x];
   const Lane L = lane_geometry(rd.heads);
   stage_group<T>(rd, w, sh);
@@ -479,12 +527,13 @@ __global__ __launch_bounds__(kBlock) void tdk_decode_kernel(const RoundDev rd, c
   for (int g = 0; g < w.ag_count; ++g) {
     if (sh.aux[g] >= 0) continue;   // listed in the diff: the scatter kernel writes this page
     float c[8], s[8];
-    if (DOK) load_tab<IL>(sh, g, L.jb, c, s);
+    if (DOK && !SEG) load_tab<IL>(sh, g, 0, L.jb, c, s);
 #pragma unroll
     for (int k = 0; k < RPW; ++k) {
       if (!M.valid[k]) continue;
       const int64_t base = dest_row<T>(sh, g, wave + kWaves * k) * row_u4;
       if (DOK && L.kok) {
+        if (SEG) load_tab<IL>(sh, g, wave + kWaves * k, L.jb, c, s);
         u32x4 olo, ohi;
         rotate16<IL>(M.kl[k], M.kh[k], c, s, olo, ohi);
         st16<NT>(pk + base + L.klo, olo);
@@ -528,7 +577,8 @@ __global__ __launch_bounds__(kBlock) void tdk_scatter_kernel(const RoundDev rd, 
         const int m = p * T + threadIdx.x;
         if (p >= 0 && p < sd.pages && m < sd.span) {   // anything else is not an index this round produces
           const int a0 = ad.pos0 + m;
-          row = (int64_t)rd.bt[ad.bt_off + a0 / T - ad.lp_first] * T + a0 % T;
+          row = rd.seg ? (int64_t)rd.rowmap[ad.score_off + m]
+                       : (int64_t)rd.bt[ad.bt_off + a0 / T - ad.lp_first] * T + a0 % T;
         }
       }
       sh.row[threadIdx.x] = row;
@@ -623,10 +673,10 @@ __device__ __forceinline__ float wave_sum_to_lane63(float v) {
 
 // Per (agent, token): sum over the row of (fresh K - rotated cached K)^2, fp32.  Same traversal as
 // the compare kernel, K plane only; one float per row leaves each wavefront.
-template <int RPW, bool IL>
+template <int RPW, bool IL, bool SEG>
 __global__ __launch_bounds__(kBlock) void tdk_keydiff_kernel(const RoundDev rd, const LayerDev io, const PlanDev pl) {
   constexpr int T = RPW * kWaves;
-  __shared__ GroupShared sh;
+  __shared__ std::conditional_t<SEG, GroupSharedSeg, GroupShared> sh;
   const WorkItem w = rd.work[blockIdx.x];
   const Lane L = lane_geometry(rd.heads);
   stage_group<T>(rd, w, sh);
@@ -638,7 +688,7 @@ __global__ __launch_bounds__(kBlock) void tdk_keydiff_kernel(const RoundDev rd, 
   const u32x4* pk = io.pool_k;
   for (int g = 0; g < w.ag_count; ++g) {
     float c[8], s[8];
-    load_tab<IL>(sh, g, L.jb, c, s);
+    if (!SEG) load_tab<IL>(sh, g, 0, L.jb, c, s);
     u32x4 akl[RPW], akh[RPW];
     const u32x4 z = {0, 0, 0, 0};
 #pragma unroll
@@ -654,6 +704,7 @@ __global__ __launch_bounds__(kBlock) void tdk_keydiff_kernel(const RoundDev rd, 
       if (!M.valid[k]) continue;
       float acc = 0.f;
       if (L.kok) {
+        if (SEG) load_tab<IL>(sh, g, wave + kWaves * k, L.jb, c, s);
         u32x4 rlo, rhi;
         rotate16<IL>(M.kl[k], M.kh[k], c, s, rlo, rhi);
 #pragma unroll
@@ -827,8 +878,10 @@ hipError_t launch_rerotate(const RoundDev& rd, const LayerDev& io, hipStream_t s
   if (rd.n_work == 0) return hipSuccess;
   const dim3 grid(rd.n_work);
   with_rpw(rd.page_tokens, [&](auto rpw) { with_bool(rd.interleaved != 0, [&](auto il) { with_bool(rd.nontemporal != 0, [&](auto nt) {
-    hipLaunchKernelGGL((tdk_rerotate_kernel<decltype(rpw)::value, decltype(il)::value, decltype(nt)::value>),
-                       grid, dim3(kBlock), 0, st, rd, io);
+    with_bool(rd.seg != 0, [&](auto sg) {
+      hipLaunchKernelGGL((tdk_rerotate_kernel<decltype(rpw)::value, decltype(il)::value, decltype(nt)::value, decltype(sg)::value>),
+                         grid, dim3(kBlock), 0, st, rd, io);
+    });
   }); }); });
   return hipGetLastError();
 }
@@ -837,8 +890,10 @@ hipError_t launch_flag(const RoundDev& rd, const LayerDev& io, float eps, int pl
   if (rd.n_work == 0) return hipSuccess;
   const dim3 grid(rd.n_work);
   with_rpw(rd.page_tokens, [&](auto rpw) { with_bool(rd.interleaved != 0, [&](auto il) { with_planes(planes, [&](auto pm) {
-    hipLaunchKernelGGL((tdk_flag_kernel<decltype(rpw)::value, decltype(il)::value, decltype(pm)::value>),
-                       grid, dim3(kBlock), 0, st, rd, io, eps);
+    with_bool(rd.seg != 0, [&](auto sg) {
+      hipLaunchKernelGGL((tdk_flag_kernel<decltype(rpw)::value, decltype(il)::value, decltype(pm)::value, decltype(sg)::value>),
+                         grid, dim3(kBlock), 0, st, rd, io, eps);
+    });
   }); }); });
   return hipGetLastError();
 }
@@ -866,10 +921,10 @@ hipError_t launch_decode(const RoundDev& rd, const LayerDev& io, const DiffDev& 
   if (rd.n_work == 0) return hipSuccess;
   const dim3 grid(rd.n_work);
   with_rpw(rd.page_tokens, [&](auto rpw) { with_bool(rd.interleaved != 0, [&](auto il) { with_bool(rd.nontemporal != 0, [&](auto nt) {
-    with_planes(planes, [&](auto pm) {
-      hipLaunchKernelGGL((tdk_decode_kernel<decltype(rpw)::value, decltype(il)::value, decltype(nt)::value, decltype(pm)::value>),
-                         grid, dim3(kBlock), 0, st, rd, io, d);
-    });
+    with_planes(planes, [&](auto pm) { with_bool(rd.seg != 0, [&](auto sg) {
+      hipLaunchKernelGGL((tdk_decode_kernel<decltype(rpw)::value, decltype(il)::value, decltype(nt)::value, decltype(pm)::value,
+                                            decltype(sg)::value>), grid, dim3(kBlock), 0, st, rd, io, d);
+    }); });
   }); }); });
   return hipGetLastError();
 }
@@ -884,9 +939,10 @@ hipError_t launch_scatter(const RoundDev& rd, const LayerDev& io, const DiffDev&
 hipError_t launch_keydiff(const RoundDev& rd, const LayerDev& io, const PlanDev& pl, hipStream_t st) {
   if (rd.n_work == 0) return hipSuccess;
   const dim3 grid(rd.n_work);
-  with_rpw(rd.page_tokens, [&](auto rpw) { with_bool(rd.interleaved != 0, [&](auto il) {
-    hipLaunchKernelGGL((tdk_keydiff_kernel<decltype(rpw)::value, decltype(il)::value>), grid, dim3(kBlock), 0, st, rd, io, pl);
-  }); });
+  with_rpw(rd.page_tokens, [&](auto rpw) { with_bool(rd.interleaved != 0, [&](auto il) { with_bool(rd.seg != 0, [&](auto sg) {
+    hipLaunchKernelGGL((tdk_keydiff_kernel<decltype(rpw)::value, decltype(il)::value, decltype(sg)::value>),
+                       grid, dim3(kBlock), 0, st, rd, io, pl);
+  }); }); });
   return hipGetLastError();
 }
 

@@ -44,9 +44,14 @@ class Session(C.Structure):
     _fields_ = [("span_tokens", C.c_int32), ("master_pos0", C.c_int64)]
 
 
+class Segment(C.Structure):
+    _fields_ = [("src_tok", C.c_int32), ("len", C.c_int32), ("dst_pos", C.c_int64)]
+
+
 class Agent(C.Structure):
     _fields_ = [("session", C.c_int32), ("dst_pos0", C.c_int64), ("block_table", C.c_void_p),
-                ("block_table_len", C.c_int32), ("diff_pos0", C.c_int64)]
+                ("block_table_len", C.c_int32), ("diff_pos0", C.c_int64), ("n_segments", C.c_int32),
+                ("segments", C.c_void_p)]
 
 
 class LayerIO(C.Structure):
@@ -181,7 +186,9 @@ class Round:
 
 def tdk_round_create(mdl: Model, span_tokens: Sequence[int], master_pos0: Sequence[int],
                      agent_session: Sequence[int], agent_pos0: Sequence[int],
-                     block_tables: Sequence[np.ndarray], agent_diff_pos0: Optional[Sequence[int]] = None) -> Round:
+                     block_tables: Sequence[np.ndarray], agent_diff_pos0: Optional[Sequence[int]] = None,
+                     segments: Optional[Sequence[np.ndarray]] = None) -> Round:
+    """segments: per agent an int array [n_seg, 3] of (src_tok, dst_pos, len), empty = identity layout."""
     ns, na = len(span_tokens), len(agent_session)
     sess = (Session * max(ns, 1))()
     for s in range(ns):
@@ -192,7 +199,12 @@ def tdk_round_create(mdl: Model, span_tokens: Sequence[int], master_pos0: Sequen
         bt = np.ascontiguousarray(block_tables[i], dtype=np.int32)
         keep.append(bt)
         dp = int(agent_pos0[i]) if agent_diff_pos0 is None else int(agent_diff_pos0[i])
-        ags[i] = Agent(int(agent_session[i]), int(agent_pos0[i]), bt.ctypes.data, len(bt), dp)
+        nseg, segp = 0, None
+        if segments is not None and len(segments[i]):
+            sg = (Segment * len(segments[i]))(*[Segment(int(x[0]), int(x[2]), int(x[1])) for x in segments[i]])
+            keep.append(sg)
+            nseg, segp = len(segments[i]), C.cast(sg, C.c_void_p)
+        ags[i] = Agent(int(agent_session[i]), int(agent_pos0[i]), bt.ctypes.data, len(bt), dp, nseg, segp)
     out = C.c_void_p()
     _check(load().tdk_round_create(C.byref(mdl), sess, ns, ags, na, C.byref(out)), "tdk_round_create")
     return Round(out.value, na, None)
@@ -203,7 +215,7 @@ def round_from_workload(rnd, style=ROPE_HALF, diff_pos0=None) -> Round:
     sp = rnd.spec
     mdl = model(sp.num_layers, sp.num_kv_heads, sp.head_dim, sp.page_tokens, sp.rope_theta, style)
     return tdk_round_create(mdl, rnd.span_tokens, rnd.master_pos0, rnd.agent_session, rnd.agent_pos0,
-                            rnd.block_tables, diff_pos0)
+                            rnd.block_tables, diff_pos0, getattr(rnd, "segments", None))
 
 
 def tdk_round_destroy(r: Round) -> None:

@@ -132,3 +132,8 @@ def test_nan_scores_and_argument_errors(tdo):
                 tdk.tdk_check_layer(g.r, 0, g.io, ratio, ms, tdk.reuse_plan(z, zi, ks, zi, z, zi))
     finally:
         g.close()
+
+
+def test_check_layer_with_permuted_blocks(tdo):
+    rnd = wl.permute_blocks(wl.make_round(spec_of(blocks=4, block_tokens=45)))
+    run_case(tdo, rnd, 0.15, 0.0, noise_everywhere=0.02)

@@ -138,6 +138,37 @@ def test_sessions_with_different_spans_and_master_offsets(tdo):
         assert np.array_equal(lst, rnd.perturbed[i])
 
 
+@pytest.mark.parametrize("T,style,block_tokens", [(16, 0, 40), (16, 0, 23), (32, 0, 50), (16, 1, 40)])
+def test_permuted_block_order(tdo, T, style, block_tokens):
+    """Every agent has its own order of the shared blocks (Eq. 2): per-segment position deltas, pages
+    that straddle two blocks, rows of one page landing on unrelated physical pages."""
+    spec = spec_of(T=T, sessions=2, agents=5, blocks=5, block_tokens=block_tokens, hist=(0, 300), frac=0.25)
+    rnd = wl.permute_blocks(wl.make_round(spec))
+    o, od = run_pipeline(tdo, rnd, style=style)
+    for i, lst in enumerate(lists_of(od, rnd.n_agents)):
+        assert np.array_equal(lst, rnd.perturbed[i])
+
+
+def test_mixed_identity_and_permuted_agents_and_errors(tdo):
+    gh = _gpu()
+    from paper_2604_03143_amd import tdk
+    spec = spec_of(sessions=1, agents=4, blocks=4, block_tokens=30, hist=(0, 100))
+    rnd = wl.permute_blocks(wl.make_round(spec))
+    rnd.segments[1] = np.zeros((0, 3), np.int64)          # agent 1 keeps the identity layout
+    rnd.segments[3] = np.zeros((0, 3), np.int64)
+    run_pipeline(tdo, rnd)
+    # a page meeting three segments is refused, as are malformed segment lists
+    m = tdk.model(1)
+    bt = [np.arange(8, dtype=np.int32)]
+    for segs, status in (([[0, 0, 6], [6, 40, 6], [12, 20, 20]], tdk.ERR_UNSUPPORTED),
+                         ([[0, 0, 16], [16, 8, 16]], tdk.ERR_INVALID_ARG),       # overlapping destinations
+                         ([[0, 0, 16]], tdk.ERR_INVALID_ARG),                    # does not cover the span
+                         ([[0, 0, 16], [16, 200, 16]], tdk.ERR_INVALID_ARG)):    # past the block table
+        with pytest.raises(tdk.TdkError) as e:
+            tdk.tdk_round_create(m, [32], [0], [0], [0], bt, None, [np.array(segs, np.int64)])
+        assert e.value.status == status, segs
+
+
 def test_empty_round_and_empty_span(tdo):
     gh = _gpu()
     import torch
