@@ -239,7 +239,7 @@ def main():
                pct_hbm_peak={k.replace("_GBps", ""): round(100 * v / HBM_PEAK_GBPS, 2) for k, v in rates.items()},
                copy_ceiling_GBps=round(copy_gbps, 1), pattern_ceilings=ceil,
                tokens_per_s_rerotate_only=round(agent_tokens / (us["rerotate"] * 1e-6 * L), 1) if us["rerotate"] else None,
-               kernels={k: dict(avg_us=round(v["avg_us"], 2), launches=v["launches"]) for k, v in kt.items()},
+               kernels={k: dict(avg_us=round(v["avg_us"], 2), launches=v["launches"]) for k, v in kt.items() if v["launches"]},
                check=check)
     print(json.dumps(out))
     r.destroy()
