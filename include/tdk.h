@@ -26,7 +26,9 @@
  *     detect fails before any work is enqueued.
  *   - Results are deterministic: same inputs, same bits, including index order and payload placement.
  *   - Not checked (preconditions): physical pages of different agents do not overlap (the paper's
- *     "non-overlapping slot mappings", Sec. 4.2); buffers are not written concurrently.
+ *     "non-overlapping slot mappings", Sec. 4.2); buffers are not written concurrently; calls on one
+ *     round are issued in stream order on one stream at a time (encode uses the round's own flag
+ *     scratch, restore its events), different rounds are independent.
  *
  * Arithmetic: bf16 storage; cos/sin of phi_j = delta * theta^(-2j/D) evaluated in double on the
  * host and rounded once to fp32; per pair (a, b): y_a = fma(x_a, cos, -(x_b * sin)),

@@ -112,8 +112,9 @@ void build_work(const tdk_round& r, int group, std::vector<WorkItem>& work) {
 }
 
 int auto_group(const tdk_round& r) {
-  // enough work items to fill 256 CUs several times over, without splitting more than needed
-  const int64_t target = 256 * 8;
+  // enough work items to fill 256 CUs a few times over, without splitting more than needed (every
+  // split re-reads the master page; measured best near 1000 items on the 25-agent session)
+  const int64_t target = 256 * 4;
   int best = kMaxGroup;
   for (int g = kMaxGroup; g >= 1; --g) {
     int64_t items = 0;

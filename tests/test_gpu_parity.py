@@ -108,6 +108,27 @@ def test_more_agents_than_one_group(tdo):
     run_pipeline(tdo, wl.make_round(spec_of(agents=70, blocks=1, block_tokens=50, frac=0.3)))
 
 
+def test_many_agents_many_sessions_small_spans(tdo):
+    """300 agents in 40 sessions (up to 32 per group, several groups per page, sessions of 1 page)."""
+    gh = _gpu()
+    spec = spec_of(sessions=40, agents=1, blocks=1, block_tokens=16, hist=(0, 64), frac=0.5)
+    rnd = wl.make_round(spec)
+    # re-distribute: session 0 gets 261 agents, the others one each
+    import dataclasses
+    big = dataclasses.replace(spec, n_sessions=1, agents_per_session=261, stream=78)
+    rb = wl.make_round(big)
+    T = 16
+    off = rnd.pool_pages
+    rnd.agent_session = np.concatenate([rnd.agent_session, np.zeros(261, np.int32)])
+    rnd.agent_pos0 = np.concatenate([rnd.agent_pos0, rb.agent_pos0])
+    rnd.block_tables = rnd.block_tables + [np.where(np.arange(len(bt)) >= rb.agent_pos0[i] // T, bt + off, rnd.dummy_page).astype(np.int32)
+                                           for i, bt in enumerate(rb.block_tables)]
+    rnd.perturbed = rnd.perturbed + rb.perturbed
+    rnd.pool_pages = off + rb.pool_pages
+    o, od = run_pipeline(tdo, rnd)
+    assert int(od.offset[-1]) == sum(len(p) for p in rnd.perturbed)
+
+
 def test_sessions_with_different_spans_and_master_offsets(tdo):
     gh = _gpu()
     spec = spec_of(sessions=3, agents=2)
