@@ -63,8 +63,8 @@ def test_select_matches_stable_argsort(tdo):
         exp = np.sort(order[:k])
         assert np.array_equal(got, exp), (S, ratio, ms)
     # a tie across the cut: the lower token numbers win
-    assert tdo.select_important(np.full(10, 0.5, np.float32), 0.4, 0.0).tolist() == [0, 1, 2, 3]
-    assert tdo.select_important(np.array([1, 2, 1, 2, 1, 2], np.float32), 0.67, 0.0).tolist() == [0, 1, 3, 5]
+    assert tdo.select_important(np.full(8, 0.5, np.float32), 0.5, 0.0).tolist() == [0, 1, 2, 3]
+    assert tdo.select_important(np.array([1, 2, 1, 2, 1, 2, 1, 2], np.float32), 0.75, 0.0).tolist() == [0, 1, 2, 3, 5, 7]
     # NaN is the most important; nothing qualifies -> empty
     sc = np.array([0.1, np.nan, 0.3, 0.2], np.float32)
     assert tdo.select_important(sc, 0.5, 0.0).tolist() == [1, 2]
