@@ -121,8 +121,16 @@ tdk_status tdk_round_create(const tdk_model* model,
 void       tdk_round_destroy(tdk_round* r);             /* NULL-safe */
 size_t     tdk_scratch_bytes(const tdk_round* r);       /* device bytes the round owns */
 
-/* Launch shape: agents of one session that share one read of a master page (1..32), 0 = automatic.
- * flags bit 0: use non-temporal stores for pool writes (default off: measured slower on MI355X). */
+/* Launch shape and cache policy.  agents_per_group: agents of one session that share one read of a
+ * master page (1..32), 0 = automatic.  flags: which accesses carry the non-temporal hint (streamed
+ * through L2 and written back early instead of lingering as dirty lines that the next kernel has to
+ * flush); the default was measured best for the whole rerotate / decode / encode sequence. */
+#define TDK_TUNE_NT_REROTATE_STORES 1
+#define TDK_TUNE_NT_DECODE_STORES   2
+#define TDK_TUNE_NT_COMPARE_LOADS   4
+#define TDK_TUNE_NT_SCATTER         8
+#define TDK_TUNE_ALL                15
+#define TDK_TUNE_DEFAULT            15
 tdk_status tdk_round_tune(tdk_round* r, int32_t agents_per_group, int32_t flags);
 
 /* Per-layer views, all DEV.

@@ -49,7 +49,7 @@ struct tdk_round {
   int64_t total_pages = 0;         // sum over agents of their session's page count
   int64_t total_master_pages = 0;  // sum over sessions of pages
   int32_t group = 0;               // agents per work item (resolved)
-  int32_t flags = 0;
+  int32_t flags = TDK_TUNE_DEFAULT;
 
   void*  blob = nullptr;           // one device allocation for everything below
   size_t blob_bytes = 0;
@@ -112,11 +112,12 @@ void build_work(const tdk_round& r, int group, std::vector<WorkItem>& work) {
 }
 
 int auto_group(const tdk_round& r) {
-  // enough work items to fill 256 CUs a few times over, without splitting more than needed (every
-  // split re-reads the master page; measured best near 1000 items on the 25-agent session)
-  const int64_t target = 256 * 4;
-  int best = kMaxGroup;
-  for (int g = kMaxGroup; g >= 1; --g) {
+  // Measured on MI355X: about 9 agents per work item is the best trade between re-reads of the
+  // master page (one per work item, served by the XCD's L2) and the number of work items; rounds
+  // too small to give ~900 items that way are split further.
+  const int64_t target = 900;
+  int best = 9;
+  for (int g = 9; g >= 1; --g) {
     int64_t items = 0;
     for (const auto& s : r.sessions) {
       const int n = (int)s.agents.size();
@@ -505,7 +506,7 @@ tdk_status tdk_round_create(const tdk_model* model, const tdk_session* sessions,
   r->rd.heads = model->num_kv_heads;
   r->rd.page_tokens = T;
   r->rd.interleaved = model->rope_style == TDK_ROPE_INTERLEAVED;
-  r->rd.nontemporal = r->flags & 1;
+  r->rd.nontemporal = r->flags & TDK_TUNE_ALL;
 
   st = upload_work(r, auto_group(*r));
   if (st != TDK_OK) { (void)hipFree(r->blob); delete r; return st; }
@@ -536,12 +537,12 @@ tdk_status tdk_round_tune(tdk_round* r, int32_t agents_per_group, int32_t flags)
   if (!r) return fail(TDK_ERR_INVALID_ARG, "round is NULL");
   if (agents_per_group < 0 || agents_per_group > kMaxGroup)
     return fail(TDK_ERR_INVALID_ARG, "agents_per_group must be 0 (automatic) or 1..32");
-  if (flags & ~1) return fail(TDK_ERR_INVALID_ARG, "unknown tuning flag");
+  if (flags & ~TDK_TUNE_ALL) return fail(TDK_ERR_INVALID_ARG, "unknown tuning flag");
   // the work list is read by kernels already enqueued: wait for them before replacing it
   hipError_t e = hipDeviceSynchronize();
   if (e != hipSuccess) return hip_fail(e, "hipDeviceSynchronize");
   r->flags = flags;
-  r->rd.nontemporal = flags & 1;
+  r->rd.nontemporal = flags & TDK_TUNE_ALL;
   return upload_work(r, agents_per_group ? agents_per_group : auto_group(*r));
 }
 

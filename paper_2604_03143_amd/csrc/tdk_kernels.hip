@@ -65,9 +65,20 @@ __device__ __forceinline__ void rotate16(const u32x4 lo, const u32x4 hi, const f
   }
 }
 
+// Streaming store: system-scope, non-temporal (sc0 sc1 nt).  The line is written through instead of
+// staying dirty in L2 for a later kernel to flush; measured best for the page kernels' scattered
+// 32 KB writes when they run back to back with the compare kernel.
 template <bool NT>
 __device__ __forceinline__ void st16(u32x4* p, u32x4 v) {
-  if (NT) __builtin_nontemporal_store(v, p); else *p = v;
+  // The two idle cycles keep a following VALU write of the data registers clear of the store's read
+  // of them (16-byte stores need two wait states on gfx940+; the compiler cannot see into the asm).
+  if (NT) asm volatile("global_store_dwordx4 %0, %1, off sc0 sc1 nt\n\ts_nop 1" : : "v"(p), "v"(v) : "memory");
+  else *p = v;
+}
+
+template <bool NT>
+__device__ __forceinline__ u32x4 ld16(const u32x4* p) {
+  return NT ? __builtin_nontemporal_load(p) : *p;
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -297,7 +308,7 @@ __device__ __forceinline__ bool chunk_special(const u32x4 m) {
 }
 
 // PM: planes that take part (bit 0 = K, bit 1 = V); 3 is the paired diff, 1 / 2 the single-plane diffs
-template <int RPW, bool IL, int PM, bool SEG>
+template <int RPW, bool IL, int PM, bool SEG, bool NTL>
 __global__ __launch_bounds__(kBlock) void tdk_flag_kernel(const RoundDev rd, const LayerDev io, const float eps) {
   constexpr int T = RPW * kWaves;
   constexpr bool DOK = (PM & 1) != 0, DOV = (PM & 2) != 0;
@@ -326,9 +337,9 @@ __global__ __launch_bounds__(kBlock) void tdk_flag_kernel(const RoundDev rd, con
       akl[k] = z; akh[k] = z; av0[k] = z; av1[k] = z;
       if (!M.valid[k]) continue;
       const int64_t base = dest_row<T>(sh, g, wave + kWaves * k) * row_u4;
-      if (DOK && L.kok) { akl[k] = pk[base + L.klo]; akh[k] = pk[base + L.khi]; }
-      if (DOV && L.v0ok) av0[k] = pv[base + L.v0];
-      if (DOV && L.v1ok) av1[k] = pv[base + L.v1];
+      if (DOK && L.kok) { akl[k] = ld16<NTL>(pk + base + L.klo); akh[k] = ld16<NTL>(pk + base + L.khi); }
+      if (DOV && L.v0ok) av0[k] = ld16<NTL>(pv + base + L.v0);
+      if (DOV && L.v1ok) av1[k] = ld16<NTL>(pv + base + L.v1);
     }
     bool differs = false;
 #pragma unroll
@@ -621,7 +632,8 @@ __global__ __launch_bounds__(kBlock) void tdk_scatter_kernel(const RoundDev rd, 
         for (int j = 0; j < kCopyBatch; ++j) {
           const int i = i0 + j * kBlock;
           const u32x4 z = {0, 0, 0, 0};
-          v[j] = i < page_u4 ? src[i] : z;
+          v[j] = z;
+          if (i < page_u4) v[j] = (rd.nontemporal & 8) ? __builtin_nontemporal_load(src + i) : src[i];
         }
 #pragma unroll
         for (int j = 0; j < kCopyBatch; ++j) {
@@ -629,7 +641,10 @@ __global__ __launch_bounds__(kBlock) void tdk_scatter_kernel(const RoundDev rd, 
           if (i < page_u4) {
             const int r = i / row_u4;
             const int64_t row = sh.row[r];
-            if (row >= 0) dst[row * row_u4 + (i - r * row_u4)] = v[j];
+            if (row >= 0) {
+              if (rd.nontemporal & 8) st16<true>(dst + row * row_u4 + (i - r * row_u4), v[j]);
+              else dst[row * row_u4 + (i - r * row_u4)] = v[j];
+            }
           }
         }
       }
@@ -877,7 +892,7 @@ template <class F> static void with_planes(int planes, F f) {
 hipError_t launch_rerotate(const RoundDev& rd, const LayerDev& io, hipStream_t st) {
   if (rd.n_work == 0) return hipSuccess;
   const dim3 grid(rd.n_work);
-  with_rpw(rd.page_tokens, [&](auto rpw) { with_bool(rd.interleaved != 0, [&](auto il) { with_bool(rd.nontemporal != 0, [&](auto nt) {
+  with_rpw(rd.page_tokens, [&](auto rpw) { with_bool(rd.interleaved != 0, [&](auto il) { with_bool((rd.nontemporal & 1) != 0, [&](auto nt) {
     with_bool(rd.seg != 0, [&](auto sg) {
       hipLaunchKernelGGL((tdk_rerotate_kernel<decltype(rpw)::value, decltype(il)::value, decltype(nt)::value, decltype(sg)::value>),
                          grid, dim3(kBlock), 0, st, rd, io);
@@ -890,10 +905,10 @@ hipError_t launch_flag(const RoundDev& rd, const LayerDev& io, float eps, int pl
   if (rd.n_work == 0) return hipSuccess;
   const dim3 grid(rd.n_work);
   with_rpw(rd.page_tokens, [&](auto rpw) { with_bool(rd.interleaved != 0, [&](auto il) { with_planes(planes, [&](auto pm) {
-    with_bool(rd.seg != 0, [&](auto sg) {
-      hipLaunchKernelGGL((tdk_flag_kernel<decltype(rpw)::value, decltype(il)::value, decltype(pm)::value, decltype(sg)::value>),
-                         grid, dim3(kBlock), 0, st, rd, io, eps);
-    });
+    with_bool(rd.seg != 0, [&](auto sg) { with_bool((rd.nontemporal & 4) != 0, [&](auto ntl) {
+      hipLaunchKernelGGL((tdk_flag_kernel<decltype(rpw)::value, decltype(il)::value, decltype(pm)::value, decltype(sg)::value,
+                                          decltype(ntl)::value>), grid, dim3(kBlock), 0, st, rd, io, eps);
+    }); });
   }); }); });
   return hipGetLastError();
 }
@@ -920,7 +935,7 @@ hipError_t launch_gather(const RoundDev& rd, const LayerDev& io, const DiffDev& 
 hipError_t launch_decode(const RoundDev& rd, const LayerDev& io, const DiffDev& d, int planes, hipStream_t st) {
   if (rd.n_work == 0) return hipSuccess;
   const dim3 grid(rd.n_work);
-  with_rpw(rd.page_tokens, [&](auto rpw) { with_bool(rd.interleaved != 0, [&](auto il) { with_bool(rd.nontemporal != 0, [&](auto nt) {
+  with_rpw(rd.page_tokens, [&](auto rpw) { with_bool(rd.interleaved != 0, [&](auto il) { with_bool((rd.nontemporal & 2) != 0, [&](auto nt) {
     with_planes(planes, [&](auto pm) { with_bool(rd.seg != 0, [&](auto sg) {
       hipLaunchKernelGGL((tdk_decode_kernel<decltype(rpw)::value, decltype(il)::value, decltype(nt)::value, decltype(pm)::value,
                                             decltype(sg)::value>), grid, dim3(kBlock), 0, st, rd, io, d);

@@ -226,7 +226,7 @@ def tdk_scratch_bytes(r: Round) -> int:
     return int(load().tdk_scratch_bytes(r.handle))
 
 
-def tdk_round_tune(r: Round, agents_per_group: int = 0, flags: int = 0) -> None:
+def tdk_round_tune(r: Round, agents_per_group: int = 0, flags: int = 15) -> None:
     _check(load().tdk_round_tune(r.handle, agents_per_group, flags), "tdk_round_tune")
 
 
