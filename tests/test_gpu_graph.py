@@ -1,0 +1,64 @@
+"""The three step calls only enqueue kernels (no allocation, no synchronisation, no memset), so a
+caller can capture a whole multi-layer step in a HIP graph.  Every replay must give the eager result."""
+import numpy as np
+import pytest
+
+from paper_2604_03143_amd import workload as wl
+
+pytestmark = pytest.mark.gpu
+
+
+def test_step_captured_in_a_graph_replays_exactly(tdo):
+    import torch
+    from paper_2604_03143_amd import tdk
+    import gpu_helpers as gh
+    if not torch.cuda.is_available():
+        pytest.fail("GPU tests need a GPU")
+    spec = wl.RoundSpec("graph", 58, 3, 8, 128, 16, 1.0e6, 2, 6, 3, 70, 5, 300, 0.2)
+    rnd = wl.make_round(spec)
+    L = spec.num_layers
+    runs = [gh.GpuRun(rnd, layer=l) for l in range(L)]
+    r = runs[0].r
+    stored, fresh = [], []
+    for l, g in enumerate(runs):                     # eager set-up: the mirrors each layer stores
+        tdk.tdk_rerotate_round(r, l, g.io, g.stream)
+        wl.perturb_device(rnd, l, g.pk, g.pv)
+        stored.append(g.encode())
+        fresh.append(g.new_diff())
+    want = [(g.pk.clone(), g.pv.clone()) for g in runs]
+
+    def step(stream):
+        for l, g in enumerate(runs):
+            tdk.tdk_rerotate_round(r, l, g.io, stream)
+            tdk.tdk_diff_decode(r, l, g.io, stored[l].c, stream)
+            tdk.tdk_diff_encode(r, l, g.io, spec.eps, fresh[l].c, stream)
+
+    torch.cuda.synchronize()
+    side = torch.cuda.Stream()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        step(side.cuda_stream)                       # warm-up on the capture stream
+        side.synchronize()
+        with torch.cuda.graph(graph, stream=side):
+            step(torch.cuda.current_stream().cuda_stream)
+    torch.cuda.synchronize()
+    try:
+        for rep in range(3):
+            for l, g in enumerate(runs):             # eager work between replays: wipe what the step writes
+                g.pk.zero_(); g.pv.zero_()
+                fresh[l].idx.fill_(-1); fresh[l].payload.zero_(); fresh[l].count.zero_()
+            torch.cuda.synchronize()
+            graph.replay()
+            torch.cuda.synchronize()
+            mask = torch.from_numpy(wl.shared_row_mask(rnd)).cuda()
+            for l, g in enumerate(runs):
+                assert torch.equal(g.pk[mask], want[l][0][mask]) and torch.equal(g.pv[mask], want[l][1][mask]), (rep, l)
+                n = int(stored[l].offset.cpu()[-1])
+                assert torch.equal(fresh[l].count, stored[l].count) and torch.equal(fresh[l].offset, stored[l].offset)
+                assert torch.equal(fresh[l].idx[:n], stored[l].idx[:n])
+                assert torch.equal(fresh[l].payload[:n], stored[l].payload[:n])
+    finally:
+        torch.cuda.synchronize()
+        for g in runs[1:]:
+            g.r.destroy()
+        runs[0].close()
