@@ -32,6 +32,8 @@ def parse():
     ap.add_argument("--flags", type=int, default=15, help="cache-policy bits (TDK_TUNE_*), default 15")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-check", action="store_true")
+    ap.add_argument("--graph", action="store_true",
+                    help="step mode: also time the step replayed from one captured HIP graph (reported beside value)")
     ap.add_argument("--alloc", default="fragmented", choices=["fragmented", "contiguous"],
                     help="physical page placement of the synthetic pool (fragmented = the graded recipe)")
     ap.add_argument("--layout", default="identity", choices=["identity", "permuted"],
@@ -117,7 +119,7 @@ def main():
         assert int(s["stored"]["overflow"].item()) == 0
         assert int(s["stored"]["offset"][-1].item()) == n_pert, "encode did not recover the seeded page set"
 
-    def step():
+    def step(stream=stream):
         for layer in range(L):
             s = slots[layer % ring]
             tdk.tdk_rerotate_round(r, layer, s["io"], stream)
@@ -137,6 +139,27 @@ def main():
     agent_tokens = rnd.agent_tokens()
     value = agent_tokens / (ms_per_step * 1e-3)
 
+    graph_out = None
+    if args.graph:
+        # the calls only enqueue kernels, so one graph can hold a whole step; replays skip the per-launch host work
+        side = torch.cuda.Stream()
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.stream(side):
+            with torch.cuda.graph(g, stream=side):
+                step(torch.cuda.current_stream().cuda_stream)
+        torch.cuda.synchronize()
+        for _ in range(max(1, args.warmup)):
+            g.replay()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            g.replay()
+        torch.cuda.synchronize()
+        g_ms = (time.perf_counter() - t0) * 1e3 / args.steps
+        graph_out = dict(ms_per_step=round(g_ms, 3), value=round(agent_tokens / (g_ms * 1e-3), 1),
+                         kernels_per_graph=7 * L)
+        del g
+
     # the same steps once more with every kernel launch bracketed by HIP events on the launch stream
     # (the brackets cost about 2 % of wall time, so they stay out of the region `value` is taken from)
     tdk.tdk_timing_reset(r)
@@ -148,6 +171,24 @@ def main():
     torch.cuda.synchronize()
     ms_per_step_instrumented = (time.perf_counter() - t0) * 1e3 / args.steps
     tdk.tdk_timing_enable(r, False)
+
+    # ---- per-call durations: an event pair around each of the three calls of every layer-step --------
+    def ev():
+        return torch.cuda.Event(enable_timing=True)
+    pairs = {"rerotate": [], "decode": [], "encode": []}
+    for _ in range(args.steps):
+        for layer in range(L):
+            s = slots[layer % ring]
+            for name, call in (("rerotate", lambda: tdk.tdk_rerotate_round(r, layer, s["io"], stream)),
+                               ("decode", lambda: tdk.tdk_diff_decode(r, layer, s["io"], s["stored"]["c"], stream)),
+                               ("encode", lambda: tdk.tdk_diff_encode(r, layer, s["io"], spec.eps, s["fresh"]["c"], stream))):
+                a, b = ev(), ev()
+                a.record()
+                call()
+                b.record()
+                pairs[name].append((a, b))
+    torch.cuda.synchronize()
+    call_us = {k: np.array([a.elapsed_time(b) * 1e3 for a, b in v]) for k, v in pairs.items()}
 
     # ---- per-kernel durations (HIP events on the launch stream, recorded inside the timed region) ---
     kt = {}
@@ -177,6 +218,10 @@ def main():
                  encode_GBps=gbps(alg["encode"], enc_us),
                  decode_GBps=gbps(alg["decode"], dec_us),
                  encode_decode_GBps=gbps(alg["encode"] + alg["decode"], enc_us + dec_us))
+    calls = {k: dict(median_us=round(float(np.median(v)), 2), min_us=round(float(v.min()), 2), n=int(v.size),
+                     GBps_at_median=round(gbps(alg[k], float(np.median(v))), 1),
+                     pct_hbm_peak_at_median=round(100 * gbps(alg[k], float(np.median(v))) / HBM_PEAK_GBPS, 2))
+             for k, v in call_us.items()}
     dom = max(("rerotate", "flag", "decode"), key=lambda k: kt[f"tdk_{k}_kernel"]["total_ms"])
     dom_bytes = alg["decode_kernel"] if dom == "decode" else alg[dom]
     achieved = gbps(dom_bytes, us[dom])
@@ -251,7 +296,9 @@ def main():
                            ring_layers=ring, alloc=args.alloc, layout=args.layout, agents_per_group="auto" if not args.group else args.group,
                            step="rerotate+decode+encode per layer, all layers"),
                roofline=roofline, pipeline=pipeline, ms_per_step_instrumented=round(ms_per_step_instrumented, 3),
+               hip_graph=graph_out,
                cpu_baseline=cpu,
+               calls=calls,
                rates={k: round(v, 1) for k, v in rates.items()},
                pct_hbm_peak={k.replace("_GBps", ""): round(100 * v / HBM_PEAK_GBPS, 2) for k, v in rates.items()},
                copy_ceiling_GBps=round(copy_gbps, 1), pattern_ceilings=ceil,
@@ -592,10 +639,23 @@ def cpu_baseline(rnd, slot, r, stream, L, tdk, wl, np, torch):
         reps += 1
     layer_step_s = spent / reps
     toks = sub.agent_tokens()
-    cpu = dict(value=round(toks / (layer_step_s * L), 1), unit="tokens/s", cores=tdo.max_threads(), kind="oracle",
+    # algorithmic bytes of the sample's layer-step, by the same definition as the GPU figures
+    base_b = (int(sum(int(x) for x in sub.span_tokens)) + toks) * ROW_PAIR_BYTES
+    sample_bytes = 3 * base_b + 2 * (m * 2 * T * RE * 2 + 4 * m + 12 * n)
+    threads = tdo.max_threads()
+    tdo.set_threads(1)                       # the same trio once on one thread
+    t0 = time.perf_counter()
+    tdo.rerotate_round(g, hr, mk, mv, ok, ov)
+    tdo.diff_encode(g, hr, mk, mv, mir_k, mir_v, spec.eps, cap)
+    tdo.diff_decode(g, hr, mk, mv, dk, dv, od)
+    one_thread_s = time.perf_counter() - t0
+    tdo.set_threads(threads)
+    cpu = dict(value=round(toks / (layer_step_s * L), 1), unit="tokens/s", cores=threads, kind="oracle",
                sample=f"layer 0, session 0 ({n} agents x {int(sub.span_tokens[0])} tokens): rerotate+encode+decode, "
                       f"{reps} repetitions, {spent:.1f} s; scaled to {L} layers",
                layer_step_s=round(layer_step_s, 3),
+               one_thread=dict(value=round(toks / (one_thread_s * L), 1), layer_step_s=round(one_thread_s, 3)),
+               GBps=round(sample_bytes / layer_step_s / 1e9, 2),
                first_rep_s={k: round(v, 3) for k, v in t.items()})
     return cpu, par
 

@@ -660,3 +660,12 @@ int tdo_max_threads(void) {
   return 1;
 #endif
 }
+
+/* Number of threads the agent loops may use from now on (timing only; results do not depend on it). */
+void tdo_set_threads(int n) {
+#ifdef _OPENMP
+  if (n >= 1) omp_set_num_threads(n);
+#else
+  (void)n;
+#endif
+}

@@ -141,6 +141,7 @@ double tdo_mirror_ratio(const tdo_geom* g, int64_t span_tokens, int64_t diff_pag
 double tdo_family_cost (int64_t n_agents, double ratio);                       /* in full caches            */
 
 int tdo_max_threads(void);
+void tdo_set_threads(int n);   /* timing only: results do not depend on the thread count */
 
 #ifdef __cplusplus
 }

@@ -275,3 +275,8 @@ def family_cost(n_agents: int, ratio: float) -> float:
 
 def max_threads() -> int:
     return int(lib().tdo_max_threads())
+
+
+def set_threads(n: int) -> None:
+    """Threads the agent loops use from now on (for timing; results do not depend on it)."""
+    lib().tdo_set_threads(int(n))
