@@ -129,8 +129,9 @@ size_t     tdk_scratch_bytes(const tdk_round* r);       /* device bytes the roun
 #define TDK_TUNE_NT_DECODE_STORES   2
 #define TDK_TUNE_NT_COMPARE_LOADS   4
 #define TDK_TUNE_NT_SCATTER         8
-#define TDK_TUNE_ALL                15
-#define TDK_TUNE_DEFAULT            15
+#define TDK_TUNE_NT_GATHER          16
+#define TDK_TUNE_ALL                31
+#define TDK_TUNE_DEFAULT            31
 tdk_status tdk_round_tune(tdk_round* r, int32_t agents_per_group, int32_t flags);
 
 /* Per-layer views, all DEV.

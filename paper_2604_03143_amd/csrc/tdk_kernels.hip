@@ -486,13 +486,17 @@ __global__ __launch_bounds__(kBlock) void tdk_gather_kernel(const RoundDev rd, c
           if (i < page_u4) {
             const int r = i / row_u4;
             const int64_t row = sh.row[r];
-            if (row >= 0) v[j] = src[row * row_u4 + (i - r * row_u4)];
+            if (row >= 0) v[j] = (rd.nontemporal & 16) ? __builtin_nontemporal_load(src + row * row_u4 + (i - r * row_u4))
+                                                       : src[row * row_u4 + (i - r * row_u4)];
           }
         }
 #pragma unroll
         for (int j = 0; j < kCopyBatch; ++j) {
           const int i = i0 + j * kBlock;
-          if (i < page_u4) dst[i] = v[j];
+          if (i < page_u4) {
+            if (rd.nontemporal & 16) st16<true>(dst + i, v[j]);
+            else dst[i] = v[j];
+          }
         }
       }
     }

@@ -22,6 +22,7 @@ PLANE_K, PLANE_V = 1, 2
 (KERNEL_REROTATE, KERNEL_FLAG, KERNEL_COUNT, KERNEL_INDEX, KERNEL_GATHER, KERNEL_DECODE, KERNEL_SCATTER,
  KERNEL_KEYDIFF, KERNEL_SELECT, KERNEL_MASTER) = range(10)
 KERNEL_KINDS = 10
+TUNE_ALL, TUNE_DEFAULT = 31, 31
 
 EXPORTS = (
     "tdk_status_str", "tdk_last_error", "tdk_version", "tdk_kernel_name",
@@ -226,7 +227,7 @@ def tdk_scratch_bytes(r: Round) -> int:
     return int(load().tdk_scratch_bytes(r.handle))
 
 
-def tdk_round_tune(r: Round, agents_per_group: int = 0, flags: int = 15) -> None:
+def tdk_round_tune(r: Round, agents_per_group: int = 0, flags: int = TUNE_DEFAULT) -> None:
     _check(load().tdk_round_tune(r.handle, agents_per_group, flags), "tdk_round_tune")
 
 

@@ -34,7 +34,7 @@ class DevDiff:
 
 
 class GpuRun:
-    def __init__(self, rnd: wl.Round, layer: int = 0, style=tdk.ROPE_HALF, group: int = 0, flags: int = 15,
+    def __init__(self, rnd: wl.Round, layer: int = 0, style=tdk.ROPE_HALF, group: int = 0, flags=None,
                  mk=None, mv=None, pk=None, pv=None):
         self.rnd = rnd
         self.layer = layer
@@ -44,8 +44,8 @@ class GpuRun:
             pk, pv = wl.pool_host(rnd, layer)
         self.mk, self.mv, self.pk, self.pv = up(mk), up(mv), up(pk), up(pv)
         self.r = tdk.round_from_workload(rnd, style=style)
-        if group or flags != 15:
-            tdk.tdk_round_tune(self.r, group, flags)
+        if group or flags is not None:
+            tdk.tdk_round_tune(self.r, group, tdk.TUNE_DEFAULT if flags is None else flags)
         self.io = tdk.layer_io(self.mk, self.mv, self.pk, self.pv, rnd.pool_pages)
         self.stream = torch.cuda.current_stream().cuda_stream
 

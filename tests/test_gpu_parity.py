@@ -35,7 +35,7 @@ def spec_of(name="edge", H=8, T=16, theta=1.0e6, sessions=1, agents=3, blocks=2,
                         hist[0], hist[1], frac)
 
 
-def run_pipeline(tdo, rnd, style=0, group=0, flags=15, eps=None, layer=0):
+def run_pipeline(tdo, rnd, style=0, group=0, flags=None, eps=None, layer=0):
     """rerotate -> perturb -> encode -> decode on both sides; every stage compared bit for bit."""
     gh = _gpu()
     o = OracleRun(tdo, rnd, layer=layer, style=style)
@@ -98,7 +98,7 @@ def test_theta_5e5_and_large_positions(tdo):
     run_pipeline(tdo, wl.make_round(spec_of(theta=5.0e5, hist=(18000, 33600))))
 
 
-@pytest.mark.parametrize("group,flags", [(1, 1), (2, 0), (5, 6), (32, 15), (9, 8)])
+@pytest.mark.parametrize("group,flags", [(1, 1), (2, 0), (5, 6), (32, 15), (9, 8), (9, 31), (4, 16)])
 def test_launch_shapes_give_identical_results(tdo, group, flags):
     rnd = wl.make_round(spec_of(sessions=3, agents=7, blocks=3, block_tokens=50))
     run_pipeline(tdo, rnd, group=group, flags=flags)
@@ -365,7 +365,7 @@ def test_step_argument_errors(tdo):
         with pytest.raises(tdk.TdkError):
             tdk.tdk_round_tune(g.r, 33, 1)
         with pytest.raises(tdk.TdkError):
-            tdk.tdk_round_tune(g.r, 4, 16)
+            tdk.tdk_round_tune(g.r, 4, 32)
         assert tdk.tdk_scratch_bytes(g.r) > 0
     finally:
         g.close()
