@@ -4,6 +4,7 @@
 #include <cmath>
 #include <cstdio>
 #include <cstring>
+#include <memory>
 #include <new>
 #include <string>
 #include <vector>
@@ -26,6 +27,20 @@ tdk_status hip_fail(hipError_t e, const char* what) {
 }
 
 size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+
+// No exception leaves the library: host allocations that fail become TDK_ERR_NOMEM.
+template <typename F>
+tdk_status guarded(F&& body) {
+  try {
+    return body();
+  } catch (const std::bad_alloc&) {
+    try { g_last_error = "out of memory"; } catch (...) {}   // short enough to need no allocation
+    return TDK_ERR_NOMEM;
+  } catch (...) {
+    try { g_last_error = "internal error"; } catch (...) {}
+    return TDK_ERR_INVALID_ARG;
+  }
+}
 
 struct HostSession {
   int32_t span, pages;
@@ -163,6 +178,9 @@ tdk_status check_step(const tdk_round* r, int32_t layer, const tdk_layer_io* io)
   if (!r) return fail(TDK_ERR_INVALID_ARG, "round is NULL");
   if (!io) return fail(TDK_ERR_INVALID_ARG, "layer io is NULL");
   if (layer < 0 || layer >= r->model.num_layers) return fail(TDK_ERR_INVALID_ARG, "layer out of range");
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess || dev != r->device)
+    return fail(TDK_ERR_INVALID_ARG, "the round was created on another device than the current one");
   if (io->pool_pages < 0) return fail(TDK_ERR_INVALID_ARG, "pool_pages is negative");
   if (r->rd.n_work > 0) {
     if (!io->master_k || !io->master_v || !io->pool_k || !io->pool_v)
@@ -222,7 +240,10 @@ struct Timed {
       r->free_events.pop_back();
     } else {
       err = hipEventCreate(&ev.start);
-      if (err == hipSuccess) err = hipEventCreate(&ev.stop);
+      if (err == hipSuccess) {
+        err = hipEventCreate(&ev.stop);
+        if (err != hipSuccess) (void)hipEventDestroy(ev.start);
+      }
       if (err != hipSuccess) { on = false; return; }
     }
     ev.kernel = kernel;
@@ -281,8 +302,16 @@ const char* tdk_kernel_name(int32_t kernel) {
   return "";
 }
 
-tdk_status tdk_round_create(const tdk_model* model, const tdk_session* sessions, int32_t n_sessions,
-                            const tdk_agent* agents, int32_t n_agents, tdk_round** out) {
+}  // extern "C"
+
+namespace {
+
+struct RoundDeleter {
+  void operator()(tdk_round* r) const { tdk_round_destroy(r); }
+};
+
+tdk_status round_create(const tdk_model* model, const tdk_session* sessions, int32_t n_sessions,
+                        const tdk_agent* agents, int32_t n_agents, tdk_round** out) {
   if (!out) return fail(TDK_ERR_INVALID_ARG, "out is NULL");
   *out = nullptr;
   tdk_status st = check_model(model);
@@ -291,8 +320,8 @@ tdk_status tdk_round_create(const tdk_model* model, const tdk_session* sessions,
   if ((n_sessions && !sessions) || (n_agents && !agents)) return fail(TDK_ERR_INVALID_ARG, "sessions / agents is NULL");
 
   const int T = model->page_tokens;
-  tdk_round* r = new (std::nothrow) tdk_round();
-  if (!r) return fail(TDK_ERR_NOMEM, "host allocation failed");
+  std::unique_ptr<tdk_round, RoundDeleter> holder(new tdk_round());   // released on every early return
+  tdk_round* r = holder.get();
   r->model = *model;
   r->n_agents = n_agents;
 
@@ -305,8 +334,8 @@ tdk_status tdk_round_create(const tdk_model* model, const tdk_session* sessions,
   r->sessions.resize(n_sessions);
   int64_t row0 = 0;
   for (int32_t s = 0; s < n_sessions; ++s) {
-    if (sessions[s].span_tokens < 0) { delete r; return fail(TDK_ERR_INVALID_ARG, "session: negative span_tokens"); }
-    if (sessions[s].master_pos0 < 0) { delete r; return fail(TDK_ERR_INVALID_ARG, "session: negative master_pos0"); }
+    if (sessions[s].span_tokens < 0) { return fail(TDK_ERR_INVALID_ARG, "session: negative span_tokens"); }
+    if (sessions[s].master_pos0 < 0) { return fail(TDK_ERR_INVALID_ARG, "session: negative master_pos0"); }
     HostSession& hs = r->sessions[s];
     hs.span = sessions[s].span_tokens;
     hs.pages = (hs.span + T - 1) / T;
@@ -325,37 +354,38 @@ tdk_status tdk_round_create(const tdk_model* model, const tdk_session* sessions,
   std::vector<float> segtab;
   for (int32_t i = 0; i < n_agents; ++i) {
     const tdk_agent& a = agents[i];
-    if (a.session < 0 || a.session >= n_sessions) { delete r; return fail(TDK_ERR_INVALID_ARG, "agent: session index out of range"); }
-    if (a.dst_pos0 < 0) { delete r; return fail(TDK_ERR_INVALID_ARG, "agent: negative dst_pos0"); }
+    if (a.session < 0 || a.session >= n_sessions) { return fail(TDK_ERR_INVALID_ARG, "agent: session index out of range"); }
+    if (a.dst_pos0 < 0) { return fail(TDK_ERR_INVALID_ARG, "agent: negative dst_pos0"); }
+    if (a.dst_pos0 >= (int64_t)1 << 31) { return fail(TDK_ERR_INVALID_ARG, "agent: positions beyond 2^31"); }
     HostSession& hs = r->sessions[a.session];
     const int64_t S = hs.span;
-    if (a.n_segments < 0 || (a.n_segments > 0 && !a.segments)) { delete r; return fail(TDK_ERR_INVALID_ARG, "agent: bad segment list"); }
+    if (a.n_segments < 0 || (a.n_segments > 0 && !a.segments)) { return fail(TDK_ERR_INVALID_ARG, "agent: bad segment list"); }
     // the logical pages the shared span touches: one range for the identity layout, the hull of the
     // segments otherwise
     int64_t pos_lo = a.dst_pos0, pos_hi = a.dst_pos0 + S;   // [lo, hi)
     if (a.n_segments > 0) {
-      if (a.diff_pos0 != a.dst_pos0) { delete r; return fail(TDK_ERR_UNSUPPORTED, "agent: a segmented layout cannot restore a diff stored at other positions"); }
+      if (a.diff_pos0 != a.dst_pos0) { return fail(TDK_ERR_UNSUPPORTED, "agent: a segmented layout cannot restore a diff stored at other positions"); }
       int64_t next = 0;
       pos_lo = INT64_MAX; pos_hi = 0;
       for (int32_t q = 0; q < a.n_segments; ++q) {
         const tdk_segment& sg = a.segments[q];
-        if (sg.src_tok != next || sg.len <= 0 || sg.dst_pos < 0) { delete r; return fail(TDK_ERR_INVALID_ARG, "agent: segments must be sorted, contiguous in the master and non-empty"); }
+        if (sg.src_tok != next || sg.len <= 0 || sg.dst_pos < 0) { return fail(TDK_ERR_INVALID_ARG, "agent: segments must be sorted, contiguous in the master and non-empty"); }
         for (int32_t o = 0; o < q; ++o) {
           const tdk_segment& og = a.segments[o];
-          if (sg.dst_pos < og.dst_pos + og.len && og.dst_pos < sg.dst_pos + sg.len) { delete r; return fail(TDK_ERR_INVALID_ARG, "agent: segment destinations overlap"); }
+          if (sg.dst_pos < og.dst_pos + og.len && og.dst_pos < sg.dst_pos + sg.len) { return fail(TDK_ERR_INVALID_ARG, "agent: segment destinations overlap"); }
         }
         next += sg.len;
         pos_lo = std::min<int64_t>(pos_lo, sg.dst_pos);
         pos_hi = std::max<int64_t>(pos_hi, sg.dst_pos + sg.len);
       }
-      if (next != S) { delete r; return fail(TDK_ERR_INVALID_ARG, "agent: segments do not cover the span"); }
+      if (next != S) { return fail(TDK_ERR_INVALID_ARG, "agent: segments do not cover the span"); }
     }
-    if (pos_hi + T >= (int64_t)1 << 31) { delete r; return fail(TDK_ERR_INVALID_ARG, "agent: positions beyond 2^31"); }
+    if (pos_hi + T >= (int64_t)1 << 31) { return fail(TDK_ERR_INVALID_ARG, "agent: positions beyond 2^31"); }
     const int64_t lp_first = S > 0 ? pos_lo / T : a.dst_pos0 / T;
     const int64_t lp_last = S > 0 ? (pos_hi - 1) / T : lp_first - 1;
     if (S > 0) {
-      if (!a.block_table) { delete r; return fail(TDK_ERR_INVALID_ARG, "agent: block_table is NULL"); }
-      if ((int64_t)a.block_table_len <= lp_last) { delete r; return fail(TDK_ERR_INVALID_ARG, "agent: block_table too short for its span"); }
+      if (!a.block_table) { return fail(TDK_ERR_INVALID_ARG, "agent: block_table is NULL"); }
+      if ((int64_t)a.block_table_len <= lp_last) { return fail(TDK_ERR_INVALID_ARG, "agent: block_table too short for its span"); }
     }
     AgentDev& ad = agent_dev[i];
     ad.pos0 = (int32_t)a.dst_pos0;
@@ -365,7 +395,7 @@ tdk_status tdk_round_create(const tdk_model* model, const tdk_session* sessions,
     ad.session = a.session;
     ad.flag_off = (int32_t)flag_off;
     ad.score_off = (int32_t)score_off;
-    if (a.diff_pos0 < 0) { delete r; return fail(TDK_ERR_INVALID_ARG, "agent: negative diff_pos0"); }
+    if (a.diff_pos0 < 0) { return fail(TDK_ERR_INVALID_ARG, "agent: negative diff_pos0"); }
     ad.diff_rot = a.diff_pos0 != a.dst_pos0;
     score_off += S;
     {
@@ -380,7 +410,7 @@ tdk_status tdk_round_create(const tdk_model* model, const tdk_session* sessions,
       bool ok = true;
       if (S > 0 && a.n_segments == 0) ok = touch(pos_lo, pos_hi);
       for (int32_t q = 0; q < a.n_segments && ok; ++q) ok = touch(a.segments[q].dst_pos, a.segments[q].dst_pos + a.segments[q].len);
-      if (!ok) { delete r; return fail(TDK_ERR_INVALID_ARG, "agent: negative page number in block_table"); }
+      if (!ok) { return fail(TDK_ERR_INVALID_ARG, "agent: negative page number in block_table"); }
     }
     for (int64_t lp = lp_first; lp <= lp_last; ++lp) bt.push_back(a.block_table[lp]);
     // layout tables (only if some agent of the round has segments)
@@ -412,14 +442,14 @@ tdk_status tdk_round_create(const tdk_model* model, const tdk_session* sessions,
         int32_t q2 = q;
         for (int32_t m = m_lo; m < m_hi; ++m) {
           while (segs[q2].src_tok + segs[q2].len <= m) ++q2;
-          if (q2 > q + 1) { delete r; return fail(TDK_ERR_UNSUPPORTED, "agent: a master page meets more than two segments"); }
+          if (q2 > q + 1) { return fail(TDK_ERR_UNSUPPORTED, "agent: a master page meets more than two segments"); }
           if (q2 == q + 1) { e.y = tab0 + q2; e.z |= 1 << (m - m_lo); }
         }
         pagetab.push_back(e);
       }
     }
     flag_off += hs.pages;
-    if (flag_off >= (int64_t)1 << 31 || score_off >= (int64_t)1 << 31 || bt.size() >= (size_t)1 << 31) { delete r; return fail(TDK_ERR_UNSUPPORTED, "round too large"); }
+    if (flag_off >= (int64_t)1 << 31 || score_off >= (int64_t)1 << 31 || bt.size() >= (size_t)1 << 31) { return fail(TDK_ERR_UNSUPPORTED, "round too large"); }
     hs.agents.push_back(i);
 
     // rotation tables of this agent: master frame -> its offset, and the frame its stored diff values
@@ -438,6 +468,8 @@ tdk_status tdk_round_create(const tdk_model* model, const tdk_session* sessions,
     }
   }
   r->total_pages = flag_off;
+  if (any_segments && (r->max_phys_page + 1) * T >= (int64_t)1 << 31)
+    return fail(TDK_ERR_UNSUPPORTED, "segmented layouts address pool rows with 32 bits: page numbers too large");
   std::vector<int32_t> order;
   order.reserve(n_agents);
   for (size_t q = 0; q < r->sessions.size(); ++q) {
@@ -470,9 +502,9 @@ tdk_status tdk_round_create(const tdk_model* model, const tdk_session* sessions,
   r->blob_bytes = std::max<size_t>(off, 256);
 
   hipError_t e = hipGetDevice(&r->device);
-  if (e != hipSuccess) { delete r; return hip_fail(e, "hipGetDevice"); }
+  if (e != hipSuccess) { return hip_fail(e, "hipGetDevice"); }
   e = hipMalloc(&r->blob, r->blob_bytes);
-  if (e != hipSuccess) { delete r; return e == hipErrorOutOfMemory ? fail(TDK_ERR_NOMEM, "device allocation failed") : hip_fail(e, "hipMalloc"); }
+  if (e != hipSuccess) { return e == hipErrorOutOfMemory ? fail(TDK_ERR_NOMEM, "device allocation failed") : hip_fail(e, "hipMalloc"); }
   char* base = static_cast<char*>(r->blob);
   auto up = [&](size_t o, const void* src, size_t bytes) -> hipError_t {
     return bytes ? hipMemcpy(base + o, src, bytes, hipMemcpyHostToDevice) : hipSuccess;
@@ -487,7 +519,7 @@ tdk_status tdk_round_create(const tdk_model* model, const tdk_session* sessions,
   if (e == hipSuccess && any_segments) e = up(o_pagetab, pagetab.data(), pagetab.size() * sizeof(int4));
   if (e == hipSuccess && any_segments) e = up(o_segtab, segtab.data(), segtab.size() * sizeof(float));
   if (e == hipSuccess && flag_off) e = hipMemset(base + o_flags, 0, (size_t)flag_off);
-  if (e != hipSuccess) { (void)hipFree(r->blob); delete r; return hip_fail(e, "upload of round descriptors"); }
+  if (e != hipSuccess) return hip_fail(e, "upload of round descriptors");
 
   r->rd.work = reinterpret_cast<const WorkItem*>(base + o_work);
   r->rd.sess = reinterpret_cast<const SessionDev*>(base + o_sess);
@@ -509,14 +541,23 @@ tdk_status tdk_round_create(const tdk_model* model, const tdk_session* sessions,
   r->rd.nontemporal = r->flags & TDK_TUNE_ALL;
 
   st = upload_work(r, auto_group(*r));
-  if (st != TDK_OK) { (void)hipFree(r->blob); delete r; return st; }
+  if (st != TDK_OK) return st;
   for (int b = 0; b < 2 && e == hipSuccess; ++b) {
     e = hipEventCreateWithFlags(&r->ev_loaded[b], hipEventDisableTiming);
     if (e == hipSuccess) e = hipEventCreateWithFlags(&r->ev_free[b], hipEventDisableTiming);
   }
-  if (e != hipSuccess) { tdk_round_destroy(r); return hip_fail(e, "hipEventCreate"); }
-  *out = r;
+  if (e != hipSuccess) return hip_fail(e, "hipEventCreate");
+  *out = holder.release();
   return TDK_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+tdk_status tdk_round_create(const tdk_model* model, const tdk_session* sessions, int32_t n_sessions,
+                            const tdk_agent* agents, int32_t n_agents, tdk_round** out) {
+  return guarded([&] { return round_create(model, sessions, n_sessions, agents, n_agents, out); });
 }
 
 void tdk_round_destroy(tdk_round* r) {
@@ -534,58 +575,66 @@ void tdk_round_destroy(tdk_round* r) {
 size_t tdk_scratch_bytes(const tdk_round* r) { return r ? r->blob_bytes : 0; }
 
 tdk_status tdk_round_tune(tdk_round* r, int32_t agents_per_group, int32_t flags) {
-  if (!r) return fail(TDK_ERR_INVALID_ARG, "round is NULL");
-  if (agents_per_group < 0 || agents_per_group > kMaxGroup)
-    return fail(TDK_ERR_INVALID_ARG, "agents_per_group must be 0 (automatic) or 1..32");
-  if (flags & ~TDK_TUNE_ALL) return fail(TDK_ERR_INVALID_ARG, "unknown tuning flag");
-  // the work list is read by kernels already enqueued: wait for them before replacing it
-  hipError_t e = hipDeviceSynchronize();
-  if (e != hipSuccess) return hip_fail(e, "hipDeviceSynchronize");
-  r->flags = flags;
-  r->rd.nontemporal = flags & TDK_TUNE_ALL;
-  return upload_work(r, agents_per_group ? agents_per_group : auto_group(*r));
+  return guarded([&]() -> tdk_status {
+    if (!r) return fail(TDK_ERR_INVALID_ARG, "round is NULL");
+    if (agents_per_group < 0 || agents_per_group > kMaxGroup)
+      return fail(TDK_ERR_INVALID_ARG, "agents_per_group must be 0 (automatic) or 1..32");
+    if (flags & ~TDK_TUNE_ALL) return fail(TDK_ERR_INVALID_ARG, "unknown tuning flag");
+    // the work list is read by kernels already enqueued: wait for them before replacing it
+    hipError_t e = hipDeviceSynchronize();
+    if (e != hipSuccess) return hip_fail(e, "hipDeviceSynchronize");
+    r->flags = flags;
+    r->rd.nontemporal = flags & TDK_TUNE_ALL;
+    return upload_work(r, agents_per_group ? agents_per_group : auto_group(*r));
+  });
 }
 
 tdk_status tdk_rerotate_round(tdk_round* r, int32_t layer, const tdk_layer_io* io, void* hip_stream) {
-  tdk_status st = check_step(r, layer, io);
-  if (st != TDK_OK) return st;
-  hipStream_t s = static_cast<hipStream_t>(hip_stream);
-  TDK_LAUNCH(r, TDK_KERNEL_REROTATE, s, launch_rerotate(r->rd, layer_dev(io), s));
-  return TDK_OK;
+  return guarded([&]() -> tdk_status {
+    tdk_status st = check_step(r, layer, io);
+    if (st != TDK_OK) return st;
+    hipStream_t s = static_cast<hipStream_t>(hip_stream);
+    TDK_LAUNCH(r, TDK_KERNEL_REROTATE, s, launch_rerotate(r->rd, layer_dev(io), s));
+    return TDK_OK;
+  });
 }
 
 static tdk_status encode_planes(tdk_round* r, int32_t layer, const tdk_layer_io* io, float eps, int planes,
                                 const tdk_diff* out, void* hip_stream) {
-  tdk_status st = check_step(r, layer, io);
-  if (st != TDK_OK) return st;
-  st = check_diff(r, out, true);
-  if (st != TDK_OK) return st;
-  if (!(eps >= 0.0f) || !std::isfinite(eps)) return fail(TDK_ERR_INVALID_ARG, "eps must be finite and >= 0");
-  hipStream_t s = static_cast<hipStream_t>(hip_stream);
-  const LayerDev l = layer_dev(io);
-  const DiffDev d = diff_dev(out);
-  TDK_LAUNCH(r, TDK_KERNEL_FLAG, s, launch_flag(r->rd, l, eps, planes, s));
-  TDK_LAUNCH(r, TDK_KERNEL_COUNT, s, launch_count(r->rd, d, s));
-  TDK_LAUNCH(r, TDK_KERNEL_INDEX, s, launch_index(r->rd, d, s));
-  // the number of listed pages is known on the device only: a fixed grid strides over them
-  const int grid = (int)std::min<int64_t>(std::min<int64_t>(out->capacity_pages, r->total_pages), 1 << 20);
-  TDK_LAUNCH(r, TDK_KERNEL_GATHER, s, launch_gather(r->rd, l, d, planes, grid, s));
-  return TDK_OK;
+  return guarded([&]() -> tdk_status {
+    tdk_status st = check_step(r, layer, io);
+    if (st != TDK_OK) return st;
+    st = check_diff(r, out, true);
+    if (st != TDK_OK) return st;
+    if (!(eps >= 0.0f) || !std::isfinite(eps)) return fail(TDK_ERR_INVALID_ARG, "eps must be finite and >= 0");
+    hipStream_t s = static_cast<hipStream_t>(hip_stream);
+    const LayerDev l = layer_dev(io);
+    const DiffDev d = diff_dev(out);
+    TDK_LAUNCH(r, TDK_KERNEL_FLAG, s, launch_flag(r->rd, l, eps, planes, s));
+    TDK_LAUNCH(r, TDK_KERNEL_COUNT, s, launch_count(r->rd, d, s));
+    TDK_LAUNCH(r, TDK_KERNEL_INDEX, s, launch_index(r->rd, d, s));
+    // the number of listed pages is known on the device only: a fixed grid strides over them
+    const int grid = (int)std::min<int64_t>(std::min<int64_t>(out->capacity_pages, r->total_pages), 1 << 20);
+    TDK_LAUNCH(r, TDK_KERNEL_GATHER, s, launch_gather(r->rd, l, d, planes, grid, s));
+    return TDK_OK;
+  });
 }
 
 static tdk_status decode_planes(tdk_round* r, int32_t layer, const tdk_layer_io* io, int planes,
                                 const tdk_diff* in, void* hip_stream) {
-  tdk_status st = check_step(r, layer, io);
-  if (st != TDK_OK) return st;
-  st = check_diff(r, in, false);
-  if (st != TDK_OK) return st;
-  hipStream_t s = static_cast<hipStream_t>(hip_stream);
-  const LayerDev l = layer_dev(io);
-  const DiffDev d = diff_dev(in);
-  TDK_LAUNCH(r, TDK_KERNEL_DECODE, s, launch_decode(r->rd, l, d, planes, s));
-  const int grid = (int)std::min<int64_t>(std::min<int64_t>(in->capacity_pages, r->total_pages), 1 << 20);
-  TDK_LAUNCH(r, TDK_KERNEL_SCATTER, s, launch_scatter(r->rd, l, d, planes, grid, s));
-  return TDK_OK;
+  return guarded([&]() -> tdk_status {
+    tdk_status st = check_step(r, layer, io);
+    if (st != TDK_OK) return st;
+    st = check_diff(r, in, false);
+    if (st != TDK_OK) return st;
+    hipStream_t s = static_cast<hipStream_t>(hip_stream);
+    const LayerDev l = layer_dev(io);
+    const DiffDev d = diff_dev(in);
+    TDK_LAUNCH(r, TDK_KERNEL_DECODE, s, launch_decode(r->rd, l, d, planes, s));
+    const int grid = (int)std::min<int64_t>(std::min<int64_t>(in->capacity_pages, r->total_pages), 1 << 20);
+    TDK_LAUNCH(r, TDK_KERNEL_SCATTER, s, launch_scatter(r->rd, l, d, planes, grid, s));
+    return TDK_OK;
+  });
 }
 
 tdk_status tdk_diff_encode(tdk_round* r, int32_t layer, const tdk_layer_io* io, float eps,
@@ -612,92 +661,96 @@ tdk_status tdk_diff_decode_plane(tdk_round* r, int32_t layer, const tdk_layer_io
 
 tdk_status tdk_check_layer(tdk_round* r, int32_t layer, const tdk_layer_io* io, float ratio, float min_score,
                            const tdk_reuse_plan* out, void* hip_stream) {
-  tdk_status st = check_step(r, layer, io);
-  if (st != TDK_OK) return st;
-  if (!out) return fail(TDK_ERR_INVALID_ARG, "reuse plan is NULL");
-  if (!(ratio > 0.0f) || !(ratio <= 1.0f)) return fail(TDK_ERR_INVALID_ARG, "ratio must be in (0, 1]");
-  if (!(min_score >= 0.0f) || !std::isfinite(min_score)) return fail(TDK_ERR_INVALID_ARG, "min_score must be finite and >= 0");
-  if (out->k_stride < 0) return fail(TDK_ERR_INVALID_ARG, "k_stride is negative");
-  if (r->n_agents && (!out->n_important || !out->total)) return fail(TDK_ERR_INVALID_ARG, "plan.n_important / plan.total is NULL");
-  if (r->total_tokens && !out->score) return fail(TDK_ERR_INVALID_ARG, "plan.score is NULL");
-  if (r->n_agents && out->k_stride > 0 && !out->important) return fail(TDK_ERR_INVALID_ARG, "plan.important is NULL");
-  if (!r->sessions.empty() && !out->master) return fail(TDK_ERR_INVALID_ARG, "plan.master is NULL");
-  for (const auto& hs : r->sessions) {
-    const int64_t k = (int64_t)std::ceil((double)ratio * (double)hs.span);
-    if (!hs.agents.empty() && k > out->k_stride) return fail(TDK_ERR_INVALID_ARG, "k_stride is smaller than ceil(ratio * span)");
-  }
-  PlanDev pl;
-  pl.score = out->score; pl.important = out->important; pl.n_important = out->n_important;
-  pl.total = out->total; pl.master = out->master; pl.k_stride = out->k_stride;
-  pl.ratio = ratio; pl.min_score = min_score;
-  hipStream_t s = static_cast<hipStream_t>(hip_stream);
-  TDK_LAUNCH(r, TDK_KERNEL_KEYDIFF, s, launch_keydiff(r->rd, layer_dev(io), pl, s));
-  TDK_LAUNCH(r, TDK_KERNEL_SELECT, s, launch_select(r->rd, pl, s));
-  TDK_LAUNCH(r, TDK_KERNEL_MASTER, s, launch_master(r->rd, pl, s));
-  return TDK_OK;
+  return guarded([&]() -> tdk_status {
+    tdk_status st = check_step(r, layer, io);
+    if (st != TDK_OK) return st;
+    if (!out) return fail(TDK_ERR_INVALID_ARG, "reuse plan is NULL");
+    if (!(ratio > 0.0f) || !(ratio <= 1.0f)) return fail(TDK_ERR_INVALID_ARG, "ratio must be in (0, 1]");
+    if (!(min_score >= 0.0f) || !std::isfinite(min_score)) return fail(TDK_ERR_INVALID_ARG, "min_score must be finite and >= 0");
+    if (out->k_stride < 0) return fail(TDK_ERR_INVALID_ARG, "k_stride is negative");
+    if (r->n_agents && (!out->n_important || !out->total)) return fail(TDK_ERR_INVALID_ARG, "plan.n_important / plan.total is NULL");
+    if (r->total_tokens && !out->score) return fail(TDK_ERR_INVALID_ARG, "plan.score is NULL");
+    if (r->n_agents && out->k_stride > 0 && !out->important) return fail(TDK_ERR_INVALID_ARG, "plan.important is NULL");
+    if (!r->sessions.empty() && !out->master) return fail(TDK_ERR_INVALID_ARG, "plan.master is NULL");
+    for (const auto& hs : r->sessions) {
+      const int64_t k = (int64_t)std::ceil((double)ratio * (double)hs.span);
+      if (!hs.agents.empty() && k > out->k_stride) return fail(TDK_ERR_INVALID_ARG, "k_stride is smaller than ceil(ratio * span)");
+    }
+    PlanDev pl;
+    pl.score = out->score; pl.important = out->important; pl.n_important = out->n_important;
+    pl.total = out->total; pl.master = out->master; pl.k_stride = out->k_stride;
+    pl.ratio = ratio; pl.min_score = min_score;
+    hipStream_t s = static_cast<hipStream_t>(hip_stream);
+    TDK_LAUNCH(r, TDK_KERNEL_KEYDIFF, s, launch_keydiff(r->rd, layer_dev(io), pl, s));
+    TDK_LAUNCH(r, TDK_KERNEL_SELECT, s, launch_select(r->rd, pl, s));
+    TDK_LAUNCH(r, TDK_KERNEL_MASTER, s, launch_master(r->rd, pl, s));
+    return TDK_OK;
+  });
 }
 
 tdk_status tdk_restore_layers(tdk_round* r, int32_t first_layer, int32_t n_layers,
                               const void* const* host_master_k, const void* const* host_master_v,
                               const tdk_layer_io* io, const tdk_diff* diffs, const tdk_pingpong* pp,
                               void* compute_stream, void* copy_stream) {
-  if (!r) return fail(TDK_ERR_INVALID_ARG, "round is NULL");
-  if (n_layers < 0 || first_layer < 0 || (int64_t)first_layer + n_layers > r->model.num_layers)
-    return fail(TDK_ERR_INVALID_ARG, "layer range out of bounds");
-  if (n_layers == 0) return TDK_OK;
-  if (!host_master_k || !host_master_v || !io || !diffs || !pp)
-    return fail(TDK_ERR_INVALID_ARG, "NULL argument");
-  const size_t master_bytes = (size_t)r->total_master_rows * r->model.num_kv_heads * r->model.head_dim * 2;
-  if (pp->stage_bytes < master_bytes) return fail(TDK_ERR_INVALID_ARG, "staging buffers smaller than one layer of masters");
-  for (int b = 0; b < 2; ++b) {
-    if (master_bytes && (!pp->stage_k[b] || !pp->stage_v[b])) return fail(TDK_ERR_INVALID_ARG, "staging buffer is NULL");
-    if (((uintptr_t)pp->stage_k[b] | (uintptr_t)pp->stage_v[b]) & 15) return fail(TDK_ERR_INVALID_ARG, "staging buffers must be 16-byte aligned");
-  }
-  if (pp->stage_k[0] == pp->stage_k[1] || pp->stage_v[0] == pp->stage_v[1])
-    return fail(TDK_ERR_INVALID_ARG, "the two staging buffers must be distinct");
-  // validate every layer before anything is enqueued
-  std::vector<tdk_layer_io> lio(n_layers);
-  for (int32_t k = 0; k < n_layers; ++k) {
-    if (master_bytes && (!host_master_k[k] || !host_master_v[k])) return fail(TDK_ERR_INVALID_ARG, "host master pointer is NULL");
-    lio[k] = io[k];
-    lio[k].master_k = pp->stage_k[k & 1];
-    lio[k].master_v = pp->stage_v[k & 1];
-    tdk_status st = check_step(r, first_layer + k, &lio[k]);
-    if (st != TDK_OK) return st;
-    st = check_diff(r, &diffs[k], false);
-    if (st != TDK_OK) return st;
-  }
-  hipStream_t cs = static_cast<hipStream_t>(compute_stream);
-  hipStream_t xs = static_cast<hipStream_t>(copy_stream);
-  hipError_t e = hipSuccess;
-  for (int32_t k = 0; k < n_layers; ++k) {
-    const int b = k & 1;
-    // load side: wait until the restore that last read this buffer (in this call or an earlier one)
-    // is through, then stage layer k
-    if (r->free_recorded[b]) {
-      e = hipStreamWaitEvent(xs, r->ev_free[b], 0);
-      if (e != hipSuccess) return hip_fail(e, "hipStreamWaitEvent(free)");
+  return guarded([&]() -> tdk_status {
+    if (!r) return fail(TDK_ERR_INVALID_ARG, "round is NULL");
+    if (n_layers < 0 || first_layer < 0 || (int64_t)first_layer + n_layers > r->model.num_layers)
+      return fail(TDK_ERR_INVALID_ARG, "layer range out of bounds");
+    if (n_layers == 0) return TDK_OK;
+    if (!host_master_k || !host_master_v || !io || !diffs || !pp)
+      return fail(TDK_ERR_INVALID_ARG, "NULL argument");
+    const size_t master_bytes = (size_t)r->total_master_rows * r->model.num_kv_heads * r->model.head_dim * 2;
+    if (pp->stage_bytes < master_bytes) return fail(TDK_ERR_INVALID_ARG, "staging buffers smaller than one layer of masters");
+    for (int b = 0; b < 2; ++b) {
+      if (master_bytes && (!pp->stage_k[b] || !pp->stage_v[b])) return fail(TDK_ERR_INVALID_ARG, "staging buffer is NULL");
+      if (((uintptr_t)pp->stage_k[b] | (uintptr_t)pp->stage_v[b]) & 15) return fail(TDK_ERR_INVALID_ARG, "staging buffers must be 16-byte aligned");
     }
-    if (master_bytes) {
-      e = hipMemcpyAsync(pp->stage_k[b], host_master_k[k], master_bytes, hipMemcpyHostToDevice, xs);
-      if (e == hipSuccess) e = hipMemcpyAsync(pp->stage_v[b], host_master_v[k], master_bytes, hipMemcpyHostToDevice, xs);
-      if (e != hipSuccess) return hip_fail(e, "hipMemcpyAsync(master chunk)");
+    if (pp->stage_k[0] == pp->stage_k[1] || pp->stage_v[0] == pp->stage_v[1])
+      return fail(TDK_ERR_INVALID_ARG, "the two staging buffers must be distinct");
+    // validate every layer before anything is enqueued
+    std::vector<tdk_layer_io> lio(n_layers);
+    for (int32_t k = 0; k < n_layers; ++k) {
+      if (master_bytes && (!host_master_k[k] || !host_master_v[k])) return fail(TDK_ERR_INVALID_ARG, "host master pointer is NULL");
+      lio[k] = io[k];
+      lio[k].master_k = pp->stage_k[k & 1];
+      lio[k].master_v = pp->stage_v[k & 1];
+      tdk_status st = check_step(r, first_layer + k, &lio[k]);
+      if (st != TDK_OK) return st;
+      st = check_diff(r, &diffs[k], false);
+      if (st != TDK_OK) return st;
     }
-    e = hipEventRecord(r->ev_loaded[b], xs);
-    if (e != hipSuccess) return hip_fail(e, "hipEventRecord(loaded)");
-    // compute side: sync on the load, swap roles, apply the diff / recover positions / write back
-    e = hipStreamWaitEvent(cs, r->ev_loaded[b], 0);
-    if (e != hipSuccess) return hip_fail(e, "hipStreamWaitEvent(loaded)");
-    const LayerDev l = layer_dev(&lio[k]);
-    const DiffDev d = diff_dev(&diffs[k]);
-    TDK_LAUNCH(r, TDK_KERNEL_DECODE, cs, launch_decode(r->rd, l, d, 3, cs));
-    const int grid = (int)std::min<int64_t>(std::min<int64_t>(diffs[k].capacity_pages, r->total_pages), 1 << 20);
-    TDK_LAUNCH(r, TDK_KERNEL_SCATTER, cs, launch_scatter(r->rd, l, d, 3, grid, cs));
-    e = hipEventRecord(r->ev_free[b], cs);
-    if (e != hipSuccess) return hip_fail(e, "hipEventRecord(free)");
-    r->free_recorded[b] = true;
-  }
-  return TDK_OK;
+    hipStream_t cs = static_cast<hipStream_t>(compute_stream);
+    hipStream_t xs = static_cast<hipStream_t>(copy_stream);
+    hipError_t e = hipSuccess;
+    for (int32_t k = 0; k < n_layers; ++k) {
+      const int b = k & 1;
+      // load side: wait until the restore that last read this buffer (in this call or an earlier one)
+      // is through, then stage layer k
+      if (r->free_recorded[b]) {
+        e = hipStreamWaitEvent(xs, r->ev_free[b], 0);
+        if (e != hipSuccess) return hip_fail(e, "hipStreamWaitEvent(free)");
+      }
+      if (master_bytes) {
+        e = hipMemcpyAsync(pp->stage_k[b], host_master_k[k], master_bytes, hipMemcpyHostToDevice, xs);
+        if (e == hipSuccess) e = hipMemcpyAsync(pp->stage_v[b], host_master_v[k], master_bytes, hipMemcpyHostToDevice, xs);
+        if (e != hipSuccess) return hip_fail(e, "hipMemcpyAsync(master chunk)");
+      }
+      e = hipEventRecord(r->ev_loaded[b], xs);
+      if (e != hipSuccess) return hip_fail(e, "hipEventRecord(loaded)");
+      // compute side: sync on the load, swap roles, apply the diff / recover positions / write back
+      e = hipStreamWaitEvent(cs, r->ev_loaded[b], 0);
+      if (e != hipSuccess) return hip_fail(e, "hipStreamWaitEvent(loaded)");
+      const LayerDev l = layer_dev(&lio[k]);
+      const DiffDev d = diff_dev(&diffs[k]);
+      TDK_LAUNCH(r, TDK_KERNEL_DECODE, cs, launch_decode(r->rd, l, d, 3, cs));
+      const int grid = (int)std::min<int64_t>(std::min<int64_t>(diffs[k].capacity_pages, r->total_pages), 1 << 20);
+      TDK_LAUNCH(r, TDK_KERNEL_SCATTER, cs, launch_scatter(r->rd, l, d, 3, grid, cs));
+      e = hipEventRecord(r->ev_free[b], cs);
+      if (e != hipSuccess) return hip_fail(e, "hipEventRecord(free)");
+      r->free_recorded[b] = true;
+    }
+    return TDK_OK;
+  });
 }
 
 tdk_status tdk_timing_enable(tdk_round* r, int32_t on) {
@@ -707,18 +760,20 @@ tdk_status tdk_timing_enable(tdk_round* r, int32_t on) {
 }
 
 static tdk_status drain_events(tdk_round* r) {
-  for (auto& ev : r->pending) {
-    hipError_t e = hipEventSynchronize(ev.stop);
-    if (e != hipSuccess) return hip_fail(e, "hipEventSynchronize");
-    float ms = 0.f;
-    e = hipEventElapsedTime(&ms, ev.start, ev.stop);
-    if (e != hipSuccess) return hip_fail(e, "hipEventElapsedTime");
-    r->total_ms[ev.kernel] += ms;
-    r->launches[ev.kernel] += 1;
-    r->free_events.push_back(ev);
-  }
-  r->pending.clear();
-  return TDK_OK;
+  return guarded([&]() -> tdk_status {
+    for (auto& ev : r->pending) {
+      hipError_t e = hipEventSynchronize(ev.stop);
+      if (e != hipSuccess) return hip_fail(e, "hipEventSynchronize");
+      float ms = 0.f;
+      e = hipEventElapsedTime(&ms, ev.start, ev.stop);
+      if (e != hipSuccess) return hip_fail(e, "hipEventElapsedTime");
+      r->total_ms[ev.kernel] += ms;
+      r->launches[ev.kernel] += 1;
+      r->free_events.push_back(ev);
+    }
+    r->pending.clear();
+    return TDK_OK;
+  });
 }
 
 tdk_status tdk_timing_read(tdk_round* r, int32_t kernel, double* total_ms, int64_t* launches) {

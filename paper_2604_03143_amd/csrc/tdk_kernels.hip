@@ -321,7 +321,7 @@ __global__ __launch_bounds__(kBlock) void tdk_flag_kernel(const RoundDev rd, con
   bool special[RPW];
 #pragma unroll
   for (int k = 0; k < RPW; ++k)
-    special[k] = chunk_special(M.kl[k]) | chunk_special(M.kh[k]) | chunk_special(M.v0[k]) | chunk_special(M.v1[k]);
+    special[k] = ((int)chunk_special(M.kl[k]) | (int)chunk_special(M.kh[k]) | (int)chunk_special(M.v0[k]) | (int)chunk_special(M.v1[k])) != 0;
   __syncthreads();
   const int wave = threadIdx.x >> 6;
   const int64_t row_u4 = (int64_t)rd.heads * 16;
@@ -352,8 +352,11 @@ __global__ __launch_bounds__(kBlock) void tdk_flag_kernel(const RoundDev rd, con
       uint32_t x = 0;
       if (DOV) x |= chunk_xor(av0[k], M.v0[k]) | chunk_xor(av1[k], M.v1[k]);
       if (DOK && L.kok) x |= chunk_xor(akl[k], rlo) | chunk_xor(akh[k], rhi);
-      if (__any((x != 0) | special[k])) {
-        if (DOK && L.kok) differs |= chunk_differs(akl[k], rlo, eps) | chunk_differs(akh[k], rhi, eps);
+      if (__any((int)(x != 0) | (int)special[k])) {
+        if (DOK && L.kok) {
+          differs |= chunk_differs(akl[k], rlo, eps);
+          differs |= chunk_differs(akh[k], rhi, eps);
+        }
         if (DOV && L.v0ok) differs |= chunk_differs(av0[k], M.v0[k], eps);
         if (DOV && L.v1ok) differs |= chunk_differs(av1[k], M.v1[k], eps);
       }
