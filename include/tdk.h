@@ -80,11 +80,15 @@ typedef struct {
 } tdk_session;
 
 /* One run of consecutive master tokens in an agent's prompt: master tokens src_tok .. src_tok+len-1
- * land at absolute positions dst_pos .. dst_pos+len-1. */
+ * land at absolute positions dst_pos .. dst_pos+len-1.  diff_pos is the position the run started at
+ * when the diff that will be restored was encoded (the per-segment form of tdk_agent::diff_pos0):
+ * equal to dst_pos for a diff of this round; otherwise the K values of the run's payload rows are
+ * re-rotated by dst_pos - diff_pos on restore.  Ignored by encode. */
 typedef struct {
   int32_t src_tok;
   int32_t len;
   int64_t dst_pos;
+  int64_t diff_pos;
 } tdk_segment;
 
 /* One agent sub-request (a mirror of its session's master). */
@@ -102,8 +106,8 @@ typedef struct {
                                       > 0: the scheduler-defined layout of the shared blocks for this agent
                                       (Sec. 2.1, Eq. 2): segments sorted by src_tok, covering [0, S) exactly
                                       once, destinations disjoint, every master page meeting at most two
-                                      segments (true whenever blocks are at least a page long); dst_pos0 is
-                                      then unused and diff_pos0 must equal dst_pos0. */
+                                      segments (true whenever blocks are at least a page long); dst_pos0 and
+                                      diff_pos0 are then unused (each segment carries its own diff_pos). */
   const tdk_segment* segments;     /* HOST */
 } tdk_agent;
 

@@ -101,7 +101,7 @@ def geom_of(spec, math=MATH_F32, style=ROPE_HALF) -> Geom:
 class HostRound:
     """Flattened, contiguous host arrays of a workload Round, kept alive for the C calls."""
 
-    def __init__(self, rnd, diff_pos0=None):
+    def __init__(self, rnd, diff_pos0=None, segment_diff_pos=None):
         self.span_tokens = np.ascontiguousarray(rnd.span_tokens, dtype=np.int32)
         self.master_pos0 = np.ascontiguousarray(rnd.master_pos0, dtype=np.int64)
         self.agent_session = np.ascontiguousarray(rnd.agent_session, dtype=np.int32)
@@ -124,6 +124,13 @@ class HostRound:
             self.seg_len = np.ascontiguousarray(flat[:, 2], dtype=np.int32)
             self.desc.seg_offset, self.desc.seg_src = _p(self.seg_offset), _p(self.seg_src)
             self.desc.seg_len, self.desc.seg_dst = _p(self.seg_len), _p(self.seg_dst)
+        if segment_diff_pos is not None:
+            # per agent one position per segment: where the segment sat when the stored diff was encoded
+            self.seg_diff_dst = np.ascontiguousarray(
+                np.concatenate([np.asarray(x, dtype=np.int64).reshape(-1) for x in segment_diff_pos])
+                if len(segment_diff_pos) else np.zeros(0, np.int64), dtype=np.int64)
+            assert segs is not None and len(self.seg_diff_dst) == len(self.seg_dst)
+            self.desc.seg_diff_dst = _p(self.seg_diff_dst)
         self.diff_pos0 = None
         if diff_pos0 is not None:
             self.diff_pos0 = np.ascontiguousarray(diff_pos0, dtype=np.int64)

@@ -351,7 +351,7 @@ tdk_status round_create(const tdk_model* model, const tdk_session* sessions, int
   for (int32_t i = 0; i < n_agents; ++i) any_segments |= agents[i].n_segments > 0;
   std::vector<int32_t> rowmap;
   std::vector<int4> pagetab;
-  std::vector<float> segtab;
+  std::vector<float> segtab, segtab_diff;
   for (int32_t i = 0; i < n_agents; ++i) {
     const tdk_agent& a = agents[i];
     if (a.session < 0 || a.session >= n_sessions) { return fail(TDK_ERR_INVALID_ARG, "agent: session index out of range"); }
@@ -364,11 +364,11 @@ tdk_status round_create(const tdk_model* model, const tdk_session* sessions, int
     // segments otherwise
     int64_t pos_lo = a.dst_pos0, pos_hi = a.dst_pos0 + S;   // [lo, hi)
     if (a.n_segments > 0) {
-      if (a.diff_pos0 != a.dst_pos0) { return fail(TDK_ERR_UNSUPPORTED, "agent: a segmented layout cannot restore a diff stored at other positions"); }
       int64_t next = 0;
       pos_lo = INT64_MAX; pos_hi = 0;
       for (int32_t q = 0; q < a.n_segments; ++q) {
         const tdk_segment& sg = a.segments[q];
+        if (sg.diff_pos < 0 || sg.diff_pos >= (int64_t)1 << 31) { return fail(TDK_ERR_INVALID_ARG, "agent: segment diff_pos out of range"); }
         if (sg.src_tok != next || sg.len <= 0 || sg.dst_pos < 0) { return fail(TDK_ERR_INVALID_ARG, "agent: segments must be sorted, contiguous in the master and non-empty"); }
         for (int32_t o = 0; o < q; ++o) {
           const tdk_segment& og = a.segments[o];
@@ -395,8 +395,9 @@ tdk_status round_create(const tdk_model* model, const tdk_session* sessions, int
     ad.session = a.session;
     ad.flag_off = (int32_t)flag_off;
     ad.score_off = (int32_t)score_off;
-    if (a.diff_pos0 < 0) { return fail(TDK_ERR_INVALID_ARG, "agent: negative diff_pos0"); }
-    ad.diff_rot = a.diff_pos0 != a.dst_pos0;
+    if (a.n_segments == 0 && a.diff_pos0 < 0) { return fail(TDK_ERR_INVALID_ARG, "agent: negative diff_pos0"); }
+    ad.diff_rot = a.n_segments ? 0 : a.diff_pos0 != a.dst_pos0;
+    for (int32_t q = 0; q < a.n_segments; ++q) ad.diff_rot |= a.segments[q].diff_pos != a.segments[q].dst_pos;
     score_off += S;
     {
       // only pages that hold shared tokens count (the hull of a permuted layout may contain others)
@@ -415,7 +416,7 @@ tdk_status round_create(const tdk_model* model, const tdk_session* sessions, int
     for (int64_t lp = lp_first; lp <= lp_last; ++lp) bt.push_back(a.block_table[lp]);
     // layout tables (only if some agent of the round has segments)
     if (any_segments) {
-      tdk_segment whole{0, (int32_t)S, a.dst_pos0};
+      tdk_segment whole{0, (int32_t)S, a.dst_pos0, a.diff_pos0};
       const tdk_segment* segs = a.n_segments ? a.segments : &whole;
       const int32_t nseg = a.n_segments ? a.n_segments : (S > 0 ? 1 : 0);
       const int32_t tab0 = (int32_t)(segtab.size() / (2 * kHalf));
@@ -428,6 +429,15 @@ tdk_status round_create(const tdk_model* model, const tdk_session* sessions, int
         for (int j = 0; j < kHalf; ++j) {
           const double inv_freq = std::pow(model->rope_theta, -(double)(2 * j) / (double)model->head_dim);
           segtab.push_back((float)std::sin(delta * inv_freq));
+        }
+        const double moved = (double)(segs[q].dst_pos - segs[q].diff_pos);
+        for (int j = 0; j < kHalf; ++j) {
+          const double inv_freq = std::pow(model->rope_theta, -(double)(2 * j) / (double)model->head_dim);
+          segtab_diff.push_back((float)std::cos(moved * inv_freq));
+        }
+        for (int j = 0; j < kHalf; ++j) {
+          const double inv_freq = std::pow(model->rope_theta, -(double)(2 * j) / (double)model->head_dim);
+          segtab_diff.push_back((float)std::sin(moved * inv_freq));
         }
         for (int32_t m = segs[q].src_tok; m < segs[q].src_tok + segs[q].len; ++m) {
           const int64_t pos = segs[q].dst_pos + (m - segs[q].src_tok);
@@ -445,6 +455,9 @@ tdk_status round_create(const tdk_model* model, const tdk_session* sessions, int
           if (q2 > q + 1) { return fail(TDK_ERR_UNSUPPORTED, "agent: a master page meets more than two segments"); }
           if (q2 == q + 1) { e.y = tab0 + q2; e.z |= 1 << (m - m_lo); }
         }
+        // which of the two runs sat elsewhere when the stored diff was encoded
+        e.w = (segs[e.x - tab0].dst_pos != segs[e.x - tab0].diff_pos ? 1 : 0) |
+              (segs[e.y - tab0].dst_pos != segs[e.y - tab0].diff_pos ? 2 : 0);
         pagetab.push_back(e);
       }
     }
@@ -498,6 +511,7 @@ tdk_status round_create(const tdk_model* model, const tdk_session* sessions, int
   const size_t o_rowmap = place(any_segments ? rowmap.size() * sizeof(int32_t) : 0);
   const size_t o_pagetab = place(any_segments ? pagetab.size() * sizeof(int4) : 0);
   const size_t o_segtab = place(any_segments ? segtab.size() * sizeof(float) : 0);
+  const size_t o_segtab_diff = place(any_segments ? segtab_diff.size() * sizeof(float) : 0);
   const size_t o_flags = place((size_t)flag_off);
   r->blob_bytes = std::max<size_t>(off, 256);
 
@@ -518,6 +532,7 @@ tdk_status round_create(const tdk_model* model, const tdk_session* sessions, int
   if (e == hipSuccess && any_segments) e = up(o_rowmap, rowmap.data(), rowmap.size() * sizeof(int32_t));
   if (e == hipSuccess && any_segments) e = up(o_pagetab, pagetab.data(), pagetab.size() * sizeof(int4));
   if (e == hipSuccess && any_segments) e = up(o_segtab, segtab.data(), segtab.size() * sizeof(float));
+  if (e == hipSuccess && any_segments) e = up(o_segtab_diff, segtab_diff.data(), segtab_diff.size() * sizeof(float));
   if (e == hipSuccess && flag_off) e = hipMemset(base + o_flags, 0, (size_t)flag_off);
   if (e != hipSuccess) return hip_fail(e, "upload of round descriptors");
 
@@ -533,6 +548,7 @@ tdk_status round_create(const tdk_model* model, const tdk_session* sessions, int
   r->rd.rowmap = any_segments ? reinterpret_cast<const int32_t*>(base + o_rowmap) : nullptr;
   r->rd.pagetab = any_segments ? reinterpret_cast<const int4*>(base + o_pagetab) : nullptr;
   r->rd.segtab = any_segments ? reinterpret_cast<const float*>(base + o_segtab) : nullptr;
+  r->rd.segtab_diff = any_segments ? reinterpret_cast<const float*>(base + o_segtab_diff) : nullptr;
   r->rd.n_agents = n_agents;
   r->rd.n_sessions = n_sessions;
   r->rd.heads = model->num_kv_heads;

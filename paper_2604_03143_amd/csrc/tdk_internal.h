@@ -53,8 +53,10 @@ struct RoundDev {
   const float*      tab_diff;  // [n_agents][2][64]: same for dst_pos0 - diff_pos0 (payload re-rotation)
   // general block layouts (some agent has its own order of the shared blocks); all NULL otherwise
   const int32_t*    rowmap;    // [sum_i S_i]: pool row of (agent, master token), agents in order
-  const int4*       pagetab;   // [sum_i pages_i]: {first table, second table, row mask of the second, 0}
+  const int4*       pagetab;   // [sum_i pages_i]: {first table, second table, row mask of the second,
+                               //  bit t: table t's run moved since the stored diff was encoded}
   const float*      segtab;    // [n tables][2][64]: cos then sin, one table per (agent, segment)
+  const float*      segtab_diff;  // same indexing: dst_pos - diff_pos of the segment (payload re-rotation)
   uint8_t*          flags;   // [sum_i pages_i] scratch of encode
   int32_t n_work, n_agents, n_sessions;
   int32_t heads;             // H

@@ -570,7 +570,8 @@ template <bool IL>
 __global__ __launch_bounds__(kBlock) void tdk_scatter_kernel(const RoundDev rd, const LayerDev io, const DiffDev d,
                                                              const int planes) {
   __shared__ SlotShared sh;
-  __shared__ float s_tab[2 * kHalf];       // cos/sin of the owner's payload re-rotation
+  __shared__ float s_tab[2][2 * kHalf];    // cos/sin of the payload re-rotation: up to two segments meet a page
+  __shared__ uint32_t s_sel, s_moved;      // bit r of s_sel: row r uses table 1; bit t of s_moved: table t is not the identity
   const int T = rd.page_tokens;
   const int A = rd.n_agents;
   if (A == 0) return;
@@ -585,7 +586,25 @@ __global__ __launch_bounds__(kBlock) void tdk_scatter_kernel(const RoundDev rd, 
     find_owner(d, A, slot, sh);
     __syncthreads();
     bool rot = false;
-    if (sh.owner >= 0) rot = rd.agents[sh.owner].diff_rot != 0;
+    int t0 = 0, t1 = 0;
+    const float* tabs = rd.tab_diff;
+    if (sh.owner >= 0 && rd.agents[sh.owner].diff_rot != 0) {
+      // which stored-frame -> current-frame rotations this page needs
+      const AgentDev ad = rd.agents[sh.owner];
+      const int p = d.idx[slot];
+      uint32_t sel = 0, moved = 1;
+      t0 = t1 = sh.owner;
+      if (rd.seg) {
+        moved = 0;
+        if (p >= 0 && p < rd.sess[ad.session].pages) {
+          const int4 pt = rd.pagetab[ad.flag_off + p];
+          t0 = pt.x; t1 = pt.y; sel = (uint32_t)pt.z; moved = (uint32_t)pt.w;
+          tabs = rd.segtab_diff;
+        }
+      }
+      rot = moved != 0;
+      if (threadIdx.x == 0) { s_sel = sel; s_moved = moved; }
+    }
     if (threadIdx.x < T) {
       int64_t row = -1;
       if (sh.owner >= 0) {                       // an inconsistent offset[] leaves the slot unowned
@@ -601,7 +620,10 @@ __global__ __launch_bounds__(kBlock) void tdk_scatter_kernel(const RoundDev rd, 
       }
       sh.row[threadIdx.x] = row;
     }
-    if (rot && threadIdx.x < 2 * kHalf) s_tab[threadIdx.x] = rd.tab_diff[(size_t)sh.owner * (2 * kHalf) + threadIdx.x];
+    if (rot) {
+      const int which = threadIdx.x >> 7, e = threadIdx.x & (2 * kHalf - 1);
+      s_tab[which][e] = tabs[(size_t)(which ? t1 : t0) * (2 * kHalf) + e];
+    }
     __syncthreads();
     const int n_planes = planes == 3 ? 2 : 1;
 #pragma unroll 1
@@ -612,22 +634,26 @@ __global__ __launch_bounds__(kBlock) void tdk_scatter_kernel(const RoundDev rd, 
       if (plane == 0 && rot) {
         // stored at another position: K rows are re-rotated, a wavefront per row, both members of a
         // pair in one lane (the page kernels' lane layout)
-        float c[8], sn[8];
-        if (!IL) {
-#pragma unroll
-          for (int e = 0; e < 8; ++e) { c[e] = s_tab[L.jb * 8 + e]; sn[e] = s_tab[kHalf + L.jb * 8 + e]; }
-        } else {
-#pragma unroll
-          for (int e = 0; e < 4; ++e) {
-            c[e] = s_tab[L.jb * 4 + e];          sn[e] = s_tab[kHalf + L.jb * 4 + e];
-            c[4 + e] = s_tab[32 + L.jb * 4 + e]; sn[4 + e] = s_tab[kHalf + 32 + L.jb * 4 + e];
-          }
-        }
         for (int r = threadIdx.x >> 6; r < T; r += kWaves) {
           const int64_t row = sh.row[r];
           if (row < 0 || !L.kok) continue;
-          u32x4 olo, ohi;
-          rotate16<IL>(src[r * row_u4 + L.klo], src[r * row_u4 + L.khi], c, sn, olo, ohi);
+          const int which = (s_sel >> r) & 1u;
+          u32x4 olo = src[r * row_u4 + L.klo], ohi = src[r * row_u4 + L.khi];
+          if ((s_moved >> which) & 1u) {           // a run that did not move is a bit copy
+            const float* t = s_tab[which];
+            float c[8], sn[8];
+            if (!IL) {
+#pragma unroll
+              for (int e = 0; e < 8; ++e) { c[e] = t[L.jb * 8 + e]; sn[e] = t[kHalf + L.jb * 8 + e]; }
+            } else {
+#pragma unroll
+              for (int e = 0; e < 4; ++e) {
+                c[e] = t[L.jb * 4 + e];          sn[e] = t[kHalf + L.jb * 4 + e];
+                c[4 + e] = t[32 + L.jb * 4 + e]; sn[4 + e] = t[kHalf + 32 + L.jb * 4 + e];
+              }
+            }
+            rotate16<IL>(olo, ohi, c, sn, olo, ohi);
+          }
           dst[row * row_u4 + L.klo] = olo;
           dst[row * row_u4 + L.khi] = ohi;
         }

@@ -46,7 +46,7 @@ class Session(C.Structure):
 
 
 class Segment(C.Structure):
-    _fields_ = [("src_tok", C.c_int32), ("len", C.c_int32), ("dst_pos", C.c_int64)]
+    _fields_ = [("src_tok", C.c_int32), ("len", C.c_int32), ("dst_pos", C.c_int64), ("diff_pos", C.c_int64)]
 
 
 class Agent(C.Structure):
@@ -188,8 +188,11 @@ class Round:
 def tdk_round_create(mdl: Model, span_tokens: Sequence[int], master_pos0: Sequence[int],
                      agent_session: Sequence[int], agent_pos0: Sequence[int],
                      block_tables: Sequence[np.ndarray], agent_diff_pos0: Optional[Sequence[int]] = None,
-                     segments: Optional[Sequence[np.ndarray]] = None) -> Round:
-    """segments: per agent an int array [n_seg, 3] of (src_tok, dst_pos, len), empty = identity layout."""
+                     segments: Optional[Sequence[np.ndarray]] = None,
+                     segment_diff_pos: Optional[Sequence[np.ndarray]] = None) -> Round:
+    """segments: per agent an int array [n_seg, 3] of (src_tok, dst_pos, len), empty = identity layout.
+    segment_diff_pos: per agent the position of each segment when the diff to restore was encoded
+    (default: dst_pos, a diff of this round)."""
     ns, na = len(span_tokens), len(agent_session)
     sess = (Session * max(ns, 1))()
     for s in range(ns):
@@ -202,7 +205,11 @@ def tdk_round_create(mdl: Model, span_tokens: Sequence[int], master_pos0: Sequen
         dp = int(agent_pos0[i]) if agent_diff_pos0 is None else int(agent_diff_pos0[i])
         nseg, segp = 0, None
         if segments is not None and len(segments[i]):
-            sg = (Segment * len(segments[i]))(*[Segment(int(x[0]), int(x[2]), int(x[1])) for x in segments[i]])
+            dpos = [int(x[1]) for x in segments[i]] if segment_diff_pos is None else [int(v) for v in segment_diff_pos[i]]
+            if len(dpos) != len(segments[i]):
+                raise ValueError("segment_diff_pos must give one position per segment")
+            sg = (Segment * len(segments[i]))(*[Segment(int(x[0]), int(x[2]), int(x[1]), dpos[q])
+                                                for q, x in enumerate(segments[i])])
             keep.append(sg)
             nseg, segp = len(segments[i]), C.cast(sg, C.c_void_p)
         ags[i] = Agent(int(agent_session[i]), int(agent_pos0[i]), bt.ctypes.data, len(bt), dp, nseg, segp)
@@ -211,12 +218,12 @@ def tdk_round_create(mdl: Model, span_tokens: Sequence[int], master_pos0: Sequen
     return Round(out.value, na, None)
 
 
-def round_from_workload(rnd, style=ROPE_HALF, diff_pos0=None) -> Round:
+def round_from_workload(rnd, style=ROPE_HALF, diff_pos0=None, segment_diff_pos=None) -> Round:
     """Convenience: a tdk round for a workload.Round (marshalling only)."""
     sp = rnd.spec
     mdl = model(sp.num_layers, sp.num_kv_heads, sp.head_dim, sp.page_tokens, sp.rope_theta, style)
     return tdk_round_create(mdl, rnd.span_tokens, rnd.master_pos0, rnd.agent_session, rnd.agent_pos0,
-                            rnd.block_tables, diff_pos0, getattr(rnd, "segments", None))
+                            rnd.block_tables, diff_pos0, getattr(rnd, "segments", None), segment_diff_pos)
 
 
 def tdk_round_destroy(r: Round) -> None:

@@ -114,3 +114,39 @@ def test_restore_at_new_offsets_matches_oracle(tdo, style, T):
         assert np.array_equal(gk, opk) and np.array_equal(gv, opv)
     finally:
         g.close()
+
+
+@pytest.mark.parametrize("style,T,block_tokens", [(0, 16, 40), (1, 16, 23), (0, 32, 50)])
+def test_restore_at_new_offsets_with_reordered_blocks_matches_oracle(tdo, style, T, block_tokens):
+    """The next round orders the shared blocks differently as well (Eq. 2): every block of a stored
+    page is re-rotated by its own distance, pages hold rows of two blocks, blocks that did not move
+    are copied bit for bit; one agent keeps the identity layout in both rounds."""
+    import torch
+    from paper_2604_03143_amd import tdk
+    import gpu_helpers as gh
+    spec = wl.RoundSpec("next_perm", 57, 1, 8, 128, T, 1.0e6, 2, 4, 4, block_tokens, 5, 300, 0.3)
+    old = wl.permute_blocks(wl.make_round(spec), seed_tag=4)
+    old.segments[5] = np.zeros((0, 3), np.int64)
+    o = OracleRun(tdo, old, style=style)
+    o.rerotate(); o.perturb()
+    d = o.encode()
+    grow = np.array([0, 16, 7, 250, 1, 31, 1000, 64], np.int64)
+    new = wl.permute_blocks(wl.make_round(spec, hist=old.agent_pos0 + grow), seed_tag=9)
+    new.segments[5] = np.zeros((0, 3), np.int64)
+    new.segments[0] = old.segments[0].copy()              # agent 0: same order, same history: nothing moved
+    seg_diff = [sg[:, 1] if len(sg) else np.zeros(0, np.int64) for sg in old.segments]
+    opk, opv = wl.pool_host(new, 0)
+    tdo.diff_decode(o.g, tdo.HostRound(new, diff_pos0=old.agent_pos0, segment_diff_pos=seg_diff), o.mk, o.mv, opk, opv, d)
+    n = int(d.offset[-1])
+    g = gh.GpuRun(new, style=style, mk=o.mk, mv=o.mv)
+    g.r.destroy()
+    g.r = tdk.round_from_workload(new, style=style, diff_pos0=old.agent_pos0, segment_diff_pos=seg_diff)
+    try:
+        cnt, off = torch.from_numpy(d.count).cuda(), torch.from_numpy(d.offset).cuda()
+        idx, pay = torch.from_numpy(d.idx[:n].copy()).cuda(), gh.up(d.payload[:n].copy())
+        dd = tdk.diff(cnt, off, idx, pay, n, torch.zeros(1, dtype=torch.int32, device="cuda"))
+        tdk.tdk_diff_decode(g.r, 0, g.io, dd, g.stream)
+        gk, gv = g.pool()
+        assert np.array_equal(gk, opk) and np.array_equal(gv, opv)
+    finally:
+        g.close()

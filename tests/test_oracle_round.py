@@ -477,6 +477,59 @@ def test_restore_at_new_offsets(tdo):
     assert np.array_equal(pk2[mask], run.pk[mask]) and np.array_equal(pv2[mask], run.pv[mask])
 
 
+def test_restore_at_new_offsets_with_reordered_blocks(tdo):
+    """The next round also orders the shared blocks differently (Eq. 2): every block of a stored
+    page moves by its own distance, and a page can hold rows of two blocks."""
+    spec = small_spec(H=2, D=8, T=4, sessions=2, agents=3, blocks=3, block_tokens=7, frac=0.4, theta=1.0e4)
+    old = wl.permute_blocks(wl.make_round(spec), seed_tag=4)
+    run = OracleRun(tdo, old)
+    run.rerotate(); run.perturb()
+    d = run.encode()
+    assert d.offset[-1] > 0
+    grow = np.array([5, 0, 17, 8, 33, 4], np.int64)
+    new = wl.permute_blocks(_next_round(old, grow), seed_tag=9)
+    assert any(not np.array_equal(a[:, 1] - old.agent_pos0[i], b[:, 1] - new.agent_pos0[i])
+               for i, (a, b) in enumerate(zip(old.segments, new.segments)))       # the order did change
+    g = run.g
+    hr_new = tdo.HostRound(new, segment_diff_pos=[sg[:, 1] for sg in old.segments])
+    pk, pv = wl.pool_host(new, 0)
+    tdo.diff_decode(g, hr_new, run.mk, run.mv, pk, pv, d)
+    rk, rv = wl.pool_host(new, 0)
+    tdo.rerotate_round(g, tdo.HostRound(new), run.mk, run.mv, rk, rv)
+    T, S = spec.page_tokens, spec.span_tokens
+    j = np.arange(spec.head_dim // 2)
+    inv = np.power(spec.rope_theta, -2.0 * j / spec.head_dim)
+    moved_rows = copied_rows = 0
+    for i in range(new.n_agents):
+        listed = set(d.idx[int(d.offset[i]):int(d.offset[i + 1])].tolist())
+        for p in range(spec.span_pages):
+            toks = np.arange(p * T, min(S, (p + 1) * T))
+            rows_new = new.dst_rows(i, toks)
+            if p not in listed:
+                assert np.array_equal(pk[rows_new], rk[rows_new]) and np.array_equal(pv[rows_new], rv[rows_new])
+                continue
+            rows_old = old.dst_rows(i, toks)
+            assert np.array_equal(pv[rows_new], run.pv[rows_old])
+            dist = new.token_pos(i, toks) - old.token_pos(i, toks)                # per token, not per agent
+            for t in range(len(toks)):
+                if dist[t] == 0:
+                    assert np.array_equal(pk[rows_new[t]], run.pk[rows_old[t]])
+                    copied_rows += 1
+                    continue
+                stored = wl.bf16_bits_to_f32(run.pk[rows_old[t]]).astype(np.float64).reshape(2, 8)
+                z = (stored[:, :4] + 1j * stored[:, 4:]) * np.exp(1j * dist[t] * inv)
+                exact = np.concatenate([z.real, z.imag], axis=-1).reshape(-1)
+                got = wl.bf16_bits_to_f32(pk[rows_new[t]]).astype(np.float64)
+                assert np.all(np.abs(got - exact) <= 0.5 * bf16_ulp(exact) + 1e-6)
+                moved_rows += 1
+    assert moved_rows > 0
+    # the stored frame equal to the current one is the plain restore
+    pk2, pv2 = wl.pool_host(old, 0)
+    tdo.diff_decode(g, tdo.HostRound(old, segment_diff_pos=[sg[:, 1] for sg in old.segments]), run.mk, run.mv, pk2, pv2, d)
+    mask = wl.shared_row_mask(old)
+    assert np.array_equal(pk2[mask], run.pk[mask]) and np.array_equal(pv2[mask], run.pv[mask])
+
+
 # ---------------------------------------------------------------------------
 # single-plane diffs (Sec. 5: separate K / V index lists)
 # ---------------------------------------------------------------------------
