@@ -29,7 +29,7 @@ def parse():
     ap.add_argument("--workload", default="batched250")
     ap.add_argument("--ring", type=int, default=0, help="resident layer buffers (0 = automatic)")
     ap.add_argument("--group", type=int, default=0, help="agents per work item (0 = automatic)")
-    ap.add_argument("--flags", type=int, default=31, help="cache-policy bits (TDK_TUNE_*), default 31")
+    ap.add_argument("--flags", type=int, default=63, help="cache-policy bits (TDK_TUNE_*), default 63")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-check", action="store_true")
     ap.add_argument("--graph", action="store_true",
@@ -88,7 +88,7 @@ def main():
     ring = min(ring, L)
 
     r = tdk.round_from_workload(rnd)
-    if args.group or args.flags != 31:
+    if args.group or args.flags != 63:
         tdk.tdk_round_tune(r, args.group, args.flags)
 
     def new_diff():
@@ -429,7 +429,7 @@ def check_mode(args, tdk, wl, np, torch, dev):
     rows = rnd.pool_pages * T
     st = torch.cuda.current_stream().cuda_stream
     r = tdk.round_from_workload(rnd)
-    if args.group or args.flags != 31:
+    if args.group or args.flags != 63:
         tdk.tdk_round_tune(r, args.group, args.flags)
     ring = args.ring or 4
     ratio = 0.15

@@ -134,8 +134,12 @@ size_t     tdk_scratch_bytes(const tdk_round* r);       /* device bytes the roun
 #define TDK_TUNE_NT_COMPARE_LOADS   4
 #define TDK_TUNE_NT_SCATTER         8
 #define TDK_TUNE_NT_GATHER          16
-#define TDK_TUNE_ALL                31
-#define TDK_TUNE_DEFAULT            31
+#define TDK_TUNE_PREFETCH_MASTER    32   /* rerotate: the first workgroups sweep the masters into the
+                                            memory-side cache before anything is written           */
+#define TDK_TUNE_PREFETCH_MASTER_DECODE 64 /* the same in decode: worth 5 % when its masters were not just
+                                            read by another kernel, costs 0.6 % when they were    */
+#define TDK_TUNE_ALL                127
+#define TDK_TUNE_DEFAULT            63
 tdk_status tdk_round_tune(tdk_round* r, int32_t agents_per_group, int32_t flags);
 
 /* Per-layer views, all DEV.

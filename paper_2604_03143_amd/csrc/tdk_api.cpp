@@ -550,6 +550,7 @@ tdk_status round_create(const tdk_model* model, const tdk_session* sessions, int
   r->rd.segtab = any_segments ? reinterpret_cast<const float*>(base + o_segtab) : nullptr;
   r->rd.segtab_diff = any_segments ? reinterpret_cast<const float*>(base + o_segtab_diff) : nullptr;
   r->rd.n_agents = n_agents;
+  r->rd.master_rows = r->total_master_rows;
   r->rd.n_sessions = n_sessions;
   r->rd.heads = model->num_kv_heads;
   r->rd.page_tokens = T;

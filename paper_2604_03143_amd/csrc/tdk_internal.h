@@ -64,6 +64,7 @@ struct RoundDev {
   int32_t interleaved;       // rope style
   int32_t nontemporal;
   int32_t seg;               // 1: rowmap / pagetab / segtab describe the layout
+  int64_t master_rows;       // rows of master_k / master_v (all sessions)
 };
 
 struct LayerDev {

@@ -239,12 +239,31 @@ __device__ __forceinline__ int64_t dest_row(const GroupShared& sh, int g, int r)
 // rerotate: pool_k <- bf16(R(delta_i) master_k), pool_v <- master_v       [Sec. 4.2]
 // ---------------------------------------------------------------------------------------------
 
+constexpr int kPrefetchBlocks = 1024;   // workgroups that take part in the master sweep (about one dispatch wave)
+
+// The workgroups that start first sweep the masters once, in address order, before any of them
+// writes: the reads then come from DRAM as one sequential stream into the memory-side cache instead
+// of arriving one page at a time among the writes (a read among writes costs DRAM a bus turnaround;
+// measured at about twice its byte share).
+__device__ __forceinline__ void sweep_masters(const RoundDev& rd, const LayerDev& io, bool k, bool v) {
+  if (blockIdx.x >= kPrefetchBlocks) return;
+  const size_t n16 = (size_t)rd.master_rows * rd.heads * 16;
+  const unsigned nb = min((unsigned)gridDim.x, (unsigned)kPrefetchBlocks);
+  u32x4 acc = {0, 0, 0, 0};
+  for (size_t i = (size_t)blockIdx.x * kBlock + threadIdx.x; i < n16; i += (size_t)nb * kBlock) {
+    if (k) acc ^= io.master_k[i];
+    if (v) acc ^= io.master_v[i];
+  }
+  asm volatile("" : : "v"(acc));      // keeps the loads alive; the values are not used
+}
+
 template <int RPW, bool IL, bool NT, bool SEG>
 __global__ __launch_bounds__(kBlock) void tdk_rerotate_kernel(const RoundDev rd, const LayerDev io) {
   constexpr int T = RPW * kWaves;
   __shared__ std::conditional_t<SEG, GroupSharedSeg, GroupShared> sh;
   const WorkItem w = rd.work[blockIdx.x];
   const Lane L = lane_geometry(rd.heads);
+  if (rd.nontemporal & 32) sweep_masters(rd, io, true, true);
   stage_group<T>(rd, w, sh);
   MasterRows<RPW> M;
   load_master<RPW>(rd, io, w, L, M);
@@ -520,6 +539,7 @@ __global__ __launch_bounds__(kBlock) void tdk_decode_kernel(const RoundDev rd, c
   stage_group<T>(rd, w, sh);
   MasterRows<RPW> M;
   constexpr bool DOK = (PM & 1) != 0, DOV = (PM & 2) != 0;
+  if (rd.nontemporal & 64) sweep_masters(rd, io, DOK, DOV);
   load_master<RPW, DOV, DOK>(rd, io, w, L, M);
   if (threadIdx.x < w.ag_count) {
     // skip-or-correct decision per block: is this page in the agent's index list?

@@ -22,7 +22,7 @@ PLANE_K, PLANE_V = 1, 2
 (KERNEL_REROTATE, KERNEL_FLAG, KERNEL_COUNT, KERNEL_INDEX, KERNEL_GATHER, KERNEL_DECODE, KERNEL_SCATTER,
  KERNEL_KEYDIFF, KERNEL_SELECT, KERNEL_MASTER) = range(10)
 KERNEL_KINDS = 10
-TUNE_ALL, TUNE_DEFAULT = 31, 31
+TUNE_ALL, TUNE_DEFAULT = 127, 63
 
 EXPORTS = (
     "tdk_status_str", "tdk_last_error", "tdk_version", "tdk_kernel_name",
