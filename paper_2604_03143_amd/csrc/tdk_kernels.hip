@@ -742,9 +742,11 @@ __device__ __forceinline__ float wave_sum_to_lane63(float v) {
 }
 
 // Per (agent, token): sum over the row of (fresh K - rotated cached K)^2, fp32.  Same traversal as
-// the compare kernel, K plane only; one float per row leaves each wavefront.
-template <int RPW, bool IL, bool SEG>
-__global__ __launch_bounds__(kBlock) void tdk_keydiff_kernel(const RoundDev rd, const LayerDev io, const PlanDev pl) {
+// the compare kernel, K plane only; one float per row leaves each wavefront.  Only half a page per
+// agent is in flight per workgroup here, so the kernel needs occupancy to cover the memory latency:
+// with 16-token pages the register budget is held to 128 (4 waves per SIMD; 518 -> 478 us measured).
+template <int RPW, bool IL, bool SEG, bool NTL>
+__global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(RPW == 4 ? 4 : 1))) void tdk_keydiff_kernel(const RoundDev rd, const LayerDev io, const PlanDev pl) {
   constexpr int T = RPW * kWaves;
   __shared__ std::conditional_t<SEG, GroupSharedSeg, GroupShared> sh;
   const WorkItem w = rd.work[blockIdx.x];
@@ -766,7 +768,7 @@ __global__ __launch_bounds__(kBlock) void tdk_keydiff_kernel(const RoundDev rd, 
       akl[k] = z; akh[k] = z;
       if (!M.valid[k] || !L.kok) continue;
       const int64_t base = dest_row<T>(sh, g, wave + kWaves * k) * row_u4;
-      akl[k] = pk[base + L.klo]; akh[k] = pk[base + L.khi];
+      akl[k] = ld16<NTL>(pk + base + L.klo); akh[k] = ld16<NTL>(pk + base + L.khi);
     }
     const int score_off = rd.agents[sh.agent[g]].score_off;
 #pragma unroll
@@ -1010,8 +1012,10 @@ hipError_t launch_keydiff(const RoundDev& rd, const LayerDev& io, const PlanDev&
   if (rd.n_work == 0) return hipSuccess;
   const dim3 grid(rd.n_work);
   with_rpw(rd.page_tokens, [&](auto rpw) { with_bool(rd.interleaved != 0, [&](auto il) { with_bool(rd.seg != 0, [&](auto sg) {
-    hipLaunchKernelGGL((tdk_keydiff_kernel<decltype(rpw)::value, decltype(il)::value, decltype(sg)::value>),
-                       grid, dim3(kBlock), 0, st, rd, io, pl);
+    with_bool((rd.nontemporal & 4) != 0, [&](auto ntl) {
+      hipLaunchKernelGGL((tdk_keydiff_kernel<decltype(rpw)::value, decltype(il)::value, decltype(sg)::value, decltype(ntl)::value>),
+                         grid, dim3(kBlock), 0, st, rd, io, pl);
+    });
   }); }); });
   return hipGetLastError();
 }
