@@ -190,6 +190,15 @@ def test_mixed_identity_and_permuted_agents_and_errors(tdo):
         assert e.value.status == status, segs
 
 
+def test_positions_of_long_lived_agents(tdo):
+    """Histories of 10^8 tokens: angles of 10^8 rad need the double-precision tables, and page
+    numbers and row offsets are taken from far into the block tables."""
+    spec = spec_of(sessions=1, agents=3, blocks=2, block_tokens=40, frac=0.4, stream=83)
+    rnd = wl.make_round(spec, hist=np.array([(1 << 27) + 5, 99_999_999, (1 << 28) - 3], np.int64))
+    run_pipeline(tdo, rnd)
+    run_pipeline(tdo, rnd, style=1, group=2)
+
+
 def test_empty_round_and_empty_span(tdo):
     gh = _gpu()
     import torch
