@@ -386,3 +386,52 @@ def test_session_config_layer0_full_oracle(tdo):
     o, od = run_pipeline(tdo, rnd)
     for i, lst in enumerate(lists_of(od, rnd.n_agents)):
         assert np.array_equal(lst, rnd.perturbed[i])
+
+
+def test_two_runs_on_two_streams_are_bit_identical(tdo):
+    """Nothing in the outputs may depend on scheduling: the same round pushed through two independent
+    sets of buffers on two streams at once (several hundred workgroups each, ragged groups, clustered
+    differences) gives the same bytes everywhere, diff lists and check-layer scores included."""
+    gh = _gpu()
+    import torch
+    from paper_2604_03143_amd import tdk
+    spec = spec_of(sessions=3, agents=11, blocks=6, block_tokens=157, hist=(3, 2000), frac=0.1, stream=91)
+    rnd = wl.make_round(spec, clustered=True)
+    runs = [gh.GpuRun(rnd), gh.GpuRun(rnd)]
+    streams = [torch.cuda.Stream(), torch.cuda.Stream()]
+    n_tok = rnd.agent_tokens()
+    kmax = int(np.ceil(float(np.float32(0.2)) * spec.span_tokens))
+    try:
+        diffs, plans = [], []
+        for g in runs:
+            diffs.append(g.new_diff())
+            plans.append(dict(score=torch.zeros(n_tok, dtype=torch.float32, device="cuda"),
+                              imp=torch.full((rnd.n_agents, kmax), -1, dtype=torch.int32, device="cuda"),
+                              n=torch.zeros(rnd.n_agents, dtype=torch.int32, device="cuda"),
+                              total=torch.zeros(rnd.n_agents, dtype=torch.float32, device="cuda"),
+                              master=torch.zeros(rnd.n_sessions, dtype=torch.int32, device="cuda")))
+        rows = torch.from_numpy(wl.perturbed_rows(rnd)).cuda()
+        torch.cuda.synchronize()                             # buffers are filled on the default stream
+        for g, st, d, plan in zip(runs, streams, diffs, plans):
+            s = st.cuda_stream
+            pc = tdk.reuse_plan(plan["score"], plan["imp"], kmax, plan["n"], plan["total"], plan["master"])
+            tdk.tdk_rerotate_round(g.r, 0, g.io, s)
+            with torch.cuda.stream(st):
+                wl.perturb_device(rnd, 0, g.pk, g.pv, rows=rows)
+            tdk.tdk_check_layer(g.r, 0, g.io, 0.2, 0.0, pc, s)
+            tdk.tdk_diff_encode(g.r, 0, g.io, spec.eps, d.c, s)
+            tdk.tdk_rerotate_round(g.r, 0, g.io, s)          # wipe the mirrors, then restore them
+            tdk.tdk_diff_decode(g.r, 0, g.io, d.c, s)
+        torch.cuda.synchronize()
+        a, b = diffs
+        n = int(a.offset.cpu()[-1])
+        assert n == sum(len(p) for p in rnd.perturbed)
+        assert torch.equal(a.count, b.count) and torch.equal(a.offset, b.offset)
+        assert torch.equal(a.idx[:n], b.idx[:n]) and torch.equal(a.payload[:n], b.payload[:n])
+        assert torch.equal(runs[0].pk, runs[1].pk) and torch.equal(runs[0].pv, runs[1].pv)
+        for k in ("score", "imp", "n", "total", "master"):
+            assert torch.equal(plans[0][k], plans[1][k]), k
+    finally:
+        torch.cuda.synchronize()
+        for g in runs:
+            g.close()
