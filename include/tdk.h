@@ -23,7 +23,9 @@
  *     They allocate nothing.  tdk_round_create / tdk_round_destroy allocate / free the library's
  *     own device memory (tables, descriptors, per-page flag scratch) and are synchronous.
  *   - Errors are return codes; tdk_last_error() gives thread-local detail.  Anything the host can
- *     detect fails before any work is enqueued.
+ *     detect fails before any work is enqueued.  No exception leaves the library.  A round belongs to
+ *     the device that was current when it was created; step calls made with another device current
+ *     fail with INVALID_ARG.
  *   - Results are deterministic: same inputs, same bits, including index order and payload placement.
  *   - Not checked (preconditions): physical pages of different agents do not overlap (the paper's
  *     "non-overlapping slot mappings", Sec. 4.2); buffers are not written concurrently; calls on one
@@ -128,7 +130,9 @@ size_t     tdk_scratch_bytes(const tdk_round* r);       /* device bytes the roun
 /* Launch shape and cache policy.  agents_per_group: agents of one session that share one read of a
  * master page (1..32), 0 = automatic.  flags: which accesses carry the non-temporal hint (streamed
  * through L2 and written back early instead of lingering as dirty lines that the next kernel has to
- * flush); the default was measured best for the whole rerotate / decode / encode sequence. */
+ * flush); the default was measured best for the whole rerotate / decode / encode sequence.
+ * Synchronises the device (the work list it replaces may still be in use).  Results never depend on
+ * these settings. */
 #define TDK_TUNE_NT_REROTATE_STORES 1
 #define TDK_TUNE_NT_DECODE_STORES   2
 #define TDK_TUNE_NT_COMPARE_LOADS   4
