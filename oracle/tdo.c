@@ -510,6 +510,90 @@ int tdo_diff_decode_plane(const tdo_geom* g, const tdo_round* r,
   return decode_impl(g, r, master_k, master_v, pool_k, pool_v, pool_pages, plane, count, offset, idx, payload);
 }
 
+/* ---- attention over a Mirror that is never restored  [Sec. 4.4, last paragraphs: the diff applied as
+ * attention tiles are loaded; Fig. 9: skip-or-correct per block] ----------------------------------- */
+
+/* one [D] head of a key in double, rotated by delta (exact angles, no rounding of the result) */
+static void rotate_head_f64(const tdo_geom* g, int64_t delta, const double* x, double* y) {
+  for (int32_t j = 0; j < g->head_dim / 2; ++j) {
+    int32_t a, b;
+    pair_index(g, j, &a, &b);
+    double phi = (double)delta * pow(g->rope_theta, -(double)(2 * j) / (double)g->head_dim);
+    double c = cos(phi), sn = sin(phi);
+    y[a] = x[a] * c - x[b] * sn;
+    y[b] = x[b] * c + x[a] * sn;
+  }
+}
+
+/* For every agent i, query row (qi, hq): softmax(scale * q . K_i[m]) over the S tokens of the shared span,
+ * where the Mirror's K_i[m], V_i[m] are, token by token: the payload rows if page m / T is in the agent's diff
+ * (K brought from the position it was stored at to the current one), else the master's K rotated to the
+ * agent's offset (exactly: no bf16 rounding in between) and the master's V.  Query head hq reads KV head
+ * hq / (n_q_heads / H).  out = sum_m p_m V_i[m]; lse = log sum_m exp(scale * q . K_i[m]) (-inf, out 0 if S = 0). */
+int tdo_attend_shared(const tdo_geom* g, const tdo_round* r,
+                      const uint16_t* master_k, const uint16_t* master_v,
+                      const int32_t* count, const int64_t* offset, const int32_t* idx, const uint16_t* payload,
+                      const uint16_t* q, int32_t n_q, int32_t n_q_heads, double scale,
+                      double* out, double* lse) {
+  if (!round_ok(g, r, INT64_MAX) || !master_k || !master_v) return -1;   /* no pool here: any page number passes */
+  if (!count || !offset || !q || !out || !lse || n_q <= 0 || n_q_heads <= 0 || n_q_heads % g->num_kv_heads) return -1;
+  const int64_t T = g->page_tokens;
+  const int32_t D = g->head_dim;
+  const int64_t re = (int64_t)g->num_kv_heads * D;
+  const int32_t G = n_q_heads / g->num_kv_heads;
+  for (int32_t i = 0; i < r->n_agents; ++i)
+    if (count[i] < 0 || (count[i] && (!idx || !payload))) return -1;
+  int err = 0;
+#pragma omp parallel for schedule(dynamic, 1)
+  for (int32_t i = 0; i < r->n_agents; ++i) {
+    int32_t s = r->agent_session[i];
+    int64_t S = r->span_tokens[s];
+    int64_t row0 = session_row0(r, s);
+    double* kk = (double*)malloc(sizeof(double) * (size_t)(2 * D + (S > 0 ? S : 1)));
+    if (!kk) { err = 1; continue; }
+    double* kr = kk + D;            /* rotated key head */
+    double* sc = kk + 2 * D;        /* scores of one query row */
+    for (int32_t qi = 0; qi < n_q; ++qi)
+      for (int32_t hq = 0; hq < n_q_heads; ++hq) {
+        const int32_t h = hq / G;
+        const uint16_t* qrow = q + (((int64_t)i * n_q + qi) * n_q_heads + hq) * D;
+        double* o = out + (((int64_t)i * n_q + qi) * n_q_heads + hq) * D;
+        double* l = lse + ((int64_t)i * n_q + qi) * n_q_heads + hq;
+        for (int32_t d = 0; d < D; ++d) o[d] = 0.0;
+        double mx = -INFINITY;
+        for (int64_t m = 0; m < S; ++m) {
+          int64_t slot = -1;
+          for (int32_t k = 0; k < count[i]; ++k)
+            if (idx[offset[i] + k] == m / T) slot = offset[i] + k;
+          const uint16_t* krow = slot >= 0 ? payload + (slot * 2 * T + m % T) * re + (int64_t)h * D
+                                           : master_k + (row0 + m) * re + (int64_t)h * D;
+          int64_t delta = slot >= 0 ? token_pos(r, i, m) - token_diff_pos(r, i, m)
+                                    : token_pos(r, i, m) - (r->master_pos0[s] + m);
+          for (int32_t d = 0; d < D; ++d) kk[d] = (double)bf16_to_f32(krow[d]);
+          rotate_head_f64(g, delta, kk, kr);
+          double acc = 0.0;
+          for (int32_t d = 0; d < D; ++d) acc += (double)bf16_to_f32(qrow[d]) * kr[d];
+          sc[m] = scale * acc;
+          if (sc[m] > mx) mx = sc[m];
+        }
+        double sum = 0.0;
+        for (int64_t m = 0; m < S; ++m) sum += exp(sc[m] - mx);
+        *l = S > 0 ? mx + log(sum) : -INFINITY;
+        for (int64_t m = 0; m < S; ++m) {
+          int64_t slot = -1;
+          for (int32_t k = 0; k < count[i]; ++k)
+            if (idx[offset[i] + k] == m / T) slot = offset[i] + k;
+          const uint16_t* vrow = slot >= 0 ? payload + ((slot * 2 + 1) * T + m % T) * re + (int64_t)h * D
+                                           : master_v + (row0 + m) * re + (int64_t)h * D;
+          double pm = exp(sc[m] - mx) / sum;
+          for (int32_t d = 0; d < D; ++d) o[d] += pm * (double)bf16_to_f32(vrow[d]);
+        }
+      }
+    free(kk);
+  }
+  return err ? -2 : 0;
+}
+
 /* ---- check layer: key-difference pass, important positions, master  [Sec. 4.2; Sec. 2.2] -------- */
 
 /* deviation of agent i at master token m: sum over the K row of (fresh - rotated cached)^2,

@@ -119,6 +119,19 @@ int tdo_diff_decode_plane(const tdo_geom* g, const tdo_round* r,
                           uint16_t* pool_k, uint16_t* pool_v, int64_t pool_pages, int32_t plane,
                           const int32_t* count, const int64_t* offset, const int32_t* idx, const uint16_t* payload);
 
+/* Attention of new query tokens over the shared span of every Mirror, computed from Master + diff with no
+ * restored copy (Sec. 4.4: the diff applied as attention tiles are loaded; Fig. 9 skip-or-correct per block).
+ * q: bf16 [n_agents][n_q][n_q_heads][D], already rotated for the queries' own positions.  Keys of pages not in
+ * the diff are the master's, rotated exactly (double) to the agent's offset; pages in the diff come from the
+ * payload (paired layout; K moved from the position it was stored at).  out [n_agents][n_q][n_q_heads][D] and
+ * lse [n_agents][n_q][n_q_heads] in double: the normalised output over the span and the log of the softmax
+ * denominator, so that the caller can merge it with attention over the private tokens. */
+int tdo_attend_shared(const tdo_geom* g, const tdo_round* r,
+                      const uint16_t* master_k, const uint16_t* master_v,
+                      const int32_t* count, const int64_t* offset, const int32_t* idx, const uint16_t* payload,
+                      const uint16_t* q, int32_t n_q, int32_t n_q_heads, double scale,
+                      double* out, double* lse);
+
 /* Check layer (Sec. 4.2): per-token key deviation of every agent (double, agent-major), the selection of
  * important positions from fp32 scores, and the master choice from fp32 totals. */
 int tdo_key_deviation(const tdo_geom* g, const tdo_round* r,

@@ -77,6 +77,8 @@ def lib() -> C.CDLL:
         L.tdo_choose_master.argtypes = [C.POINTER(RoundDesc), C.c_void_p, C.c_void_p]
         L.tdo_restore_layers.argtypes = ([C.POINTER(Geom), C.POINTER(RoundDesc), C.c_int32] +
                                          [C.POINTER(C.c_void_p)] * 4 + [C.c_int64] + [C.POINTER(C.c_void_p)] * 4)
+        L.tdo_attend_shared.argtypes = ([C.POINTER(Geom), C.POINTER(RoundDesc)] + [C.c_void_p] * 7 +
+                                        [C.c_int32, C.c_int32, C.c_double, C.c_void_p, C.c_void_p])
         _lib = L
     return _lib
 
@@ -278,6 +280,20 @@ def mirror_ratio(g: Geom, span_tokens: int, pages: int) -> float:
 
 def family_cost(n_agents: int, ratio: float) -> float:
     return lib().tdo_family_cost(int(n_agents), float(ratio))
+
+
+def attend_shared(g: Geom, hr: HostRound, master_k, master_v, d: "Diff", q, n_q: int, n_q_heads: int, scale: float):
+    """Attention of q [A][n_q][n_q_heads][D] (bf16 bits) over every Mirror's shared span, from Master + diff.
+    Returns (out float64 [A][n_q][n_q_heads][D], lse float64 [A][n_q][n_q_heads])."""
+    A = int(hr.desc.n_agents)
+    q = np.ascontiguousarray(q, dtype=np.uint16)
+    assert q.size == A * n_q * n_q_heads * g.head_dim
+    out = np.zeros((A, n_q, n_q_heads, g.head_dim), np.float64)
+    lse = np.zeros((A, n_q, n_q_heads), np.float64)
+    _chk(lib().tdo_attend_shared(C.byref(g), C.byref(hr.desc), _p(_u16(master_k)), _p(_u16(master_v)),
+                                 _p(d.count), _p(d.offset), _p(d.idx), _p(d.payload), _p(q), n_q, n_q_heads,
+                                 float(scale), _p(out), _p(lse)), "attend_shared")
+    return out, lse
 
 
 def max_threads() -> int:
