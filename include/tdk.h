@@ -230,6 +230,43 @@ typedef struct {
 tdk_status tdk_check_layer(tdk_round* r, int32_t layer, const tdk_layer_io* io, float ratio, float min_score,
                            const tdk_reuse_plan* out, void* hip_stream);
 
+/* Attention of new query tokens over the shared span of every mirror, from master + diff, with no
+ * restored copy (Sec. 4.4, last paragraphs: applying the diff as attention tiles are loaded; Fig. 9:
+ * identical blocks go straight to attention, blocks with a diff are corrected first).  All DEV.
+ *   q          bf16 [n_agents][n_q][n_q_heads][D], rotated for the queries' own positions (all of them
+ *              after the shared span: no causal mask inside it); n_q_heads a multiple of H, query head
+ *              hq reads KV head hq / (n_q_heads / H)
+ *   out        fp32 [n_agents][n_q][n_q_heads][D]: softmax(scale * q . K_i) V_i over the S tokens of the
+ *              span, where (K_i, V_i) is the agent's mirror: payload rows on the pages its diff lists,
+ *              the master's K rotated to the agent's offset and the master's V everywhere else
+ *   lse        fp32 [n_agents][n_q][n_q_heads]: log of the softmax denominator, so that the caller can
+ *              merge `out` with attention over the agent's private tokens (-inf, out 0 for an empty span)
+ *   workspace  tdk_attend_workspace_bytes(r, n_q, n_q_heads) bytes, 256-byte aligned, contents undefined
+ * Arithmetic: each query row is rotated back by the agent's offset (fp32, rounded to bf16) so that all
+ * agents of a session multiply the same un-rotated master tiles (bf16 MFMA, fp32 accumulation, softmax
+ * weights rounded to bf16 for the second product); listed pages are handled in fp32.  The result
+ * agrees with the exact definition to about 1e-2 of the largest |V| (not bit for bit). */
+typedef struct {
+  const void* q;
+  int32_t     n_q;
+  int32_t     n_q_heads;
+  float       scale;
+  float*      out;
+  float*      lse;
+  void*       workspace;
+  size_t      workspace_bytes;
+} tdk_attend_io;
+
+size_t tdk_attend_workspace_bytes(const tdk_round* r, int32_t n_q, int32_t n_q_heads);   /* 0 on bad arguments */
+
+/* io: master_k / master_v of the layer (the pool is not touched and may be NULL); in: the mirrors'
+ * paired diff as tdk_diff_encode wrote it.  Identity layouts only (UNSUPPORTED for rounds with
+ * segments); a diff stored at other positions (diff_pos0) is handled.  Master values must be finite.
+ * Allocates nothing, enqueues four kernels, does not synchronise.  Errors: INVALID_ARG (NULL,
+ * misaligned, n_q < 1, n_q_heads not a multiple of H, scale not finite, workspace too small). */
+tdk_status tdk_attend_shared(tdk_round* r, int32_t layer, const tdk_layer_io* io, const tdk_diff* in,
+                             const tdk_attend_io* a, void* hip_stream);
+
 /* Ping-pong staging buffers of the layerwise restore, DEV, caller-owned: two K and two V buffers of
  * stage_bytes each, stage_bytes >= (sum_s S_s) * H * D * 2 (one layer of masters). */
 typedef struct {
@@ -264,7 +301,11 @@ tdk_status tdk_restore_layers(tdk_round* r, int32_t first_layer, int32_t n_layer
 #define TDK_KERNEL_KEYDIFF  7
 #define TDK_KERNEL_SELECT   8
 #define TDK_KERNEL_MASTER   9
-#define TDK_KERNEL_KINDS    10
+#define TDK_KERNEL_ATTEND_QROT   10
+#define TDK_KERNEL_ATTEND_MASTER 11
+#define TDK_KERNEL_ATTEND_DIFF   12
+#define TDK_KERNEL_ATTEND_MERGE  13
+#define TDK_KERNEL_KINDS    14
 tdk_status tdk_timing_enable(tdk_round* r, int32_t on);
 tdk_status tdk_timing_read(tdk_round* r, int32_t kernel, double* total_ms, int64_t* launches);
 tdk_status tdk_timing_reset(tdk_round* r);

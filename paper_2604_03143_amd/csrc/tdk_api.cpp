@@ -298,6 +298,10 @@ const char* tdk_kernel_name(int32_t kernel) {
     case TDK_KERNEL_KEYDIFF: return "tdk_keydiff_kernel";
     case TDK_KERNEL_SELECT: return "tdk_select_kernel";
     case TDK_KERNEL_MASTER: return "tdk_master_kernel";
+    case TDK_KERNEL_ATTEND_QROT: return "tdk_attend_qrot_kernel";
+    case TDK_KERNEL_ATTEND_MASTER: return "tdk_attend_master_kernel";
+    case TDK_KERNEL_ATTEND_DIFF: return "tdk_attend_diff_kernel";
+    case TDK_KERNEL_ATTEND_MERGE: return "tdk_attend_merge_kernel";
   }
   return "";
 }
@@ -701,6 +705,113 @@ tdk_status tdk_check_layer(tdk_round* r, int32_t layer, const tdk_layer_io* io, 
     TDK_LAUNCH(r, TDK_KERNEL_KEYDIFF, s, launch_keydiff(r->rd, layer_dev(io), pl, s));
     TDK_LAUNCH(r, TDK_KERNEL_SELECT, s, launch_select(r->rd, pl, s));
     TDK_LAUNCH(r, TDK_KERNEL_MASTER, s, launch_master(r->rd, pl, s));
+    return TDK_OK;
+  });
+}
+
+namespace {
+
+// Shape of the attention pass for a round: tokens per workgroup of the master pass, parts per query
+// row, and the layout of the caller's workspace.
+struct AttendPlan {
+  int32_t chunk_tokens = 0, n_chunks = 0, n_parts = 0, max_rows = 0;
+  int64_t rows = 0;
+  size_t o_qrot = 0, o_part_o = 0, o_part_m = 0, o_part_l = 0, bytes = 0;
+};
+
+bool attend_plan(const tdk_round* r, int32_t n_q, int32_t n_q_heads, AttendPlan& p) {
+  if (!r || n_q < 1 || n_q_heads < 1 || n_q_heads % r->model.num_kv_heads) return false;
+  const int32_t G = n_q_heads / r->model.num_kv_heads;
+  int64_t max_span = 0, max_agents = 0;
+  for (const auto& hs : r->sessions) {
+    if (hs.agents.empty()) continue;
+    max_span = std::max<int64_t>(max_span, hs.span);
+    max_agents = std::max<int64_t>(max_agents, (int64_t)hs.agents.size());
+  }
+  const int64_t max_rows = max_agents * n_q * G;
+  if (max_rows >= (int64_t)1 << 30) return false;
+  p.max_rows = (int32_t)max_rows;
+  p.rows = (int64_t)r->n_agents * n_q * n_q_heads;
+  // the largest chunk (fewest partial results) that still gives the chip about two workgroups per CU;
+  // a chunk covers at most 32 pages (one mask word per query row)
+  const int64_t row_blocks = std::max<int64_t>(1, (max_rows + 127) / 128);
+  int32_t chunk = 64;
+  for (int32_t c : {512, 256, 128, 64}) {
+    if (c / r->model.page_tokens > 32 || c % r->model.page_tokens) continue;
+    int64_t wgs = 0;
+    for (const auto& hs : r->sessions)
+      if (!hs.agents.empty()) wgs += ((int64_t)hs.span + c - 1) / c;
+    chunk = c;
+    if (wgs * r->model.num_kv_heads * row_blocks >= 512) break;
+  }
+  p.chunk_tokens = chunk;
+  p.n_chunks = (int32_t)((max_span + chunk - 1) / chunk);
+  p.n_parts = p.n_chunks + 1;
+  size_t off = 0;
+  auto place = [&](size_t bytes) { size_t o = off; off = align_up(off + bytes, 256); return o; };
+  p.o_qrot = place((size_t)p.rows * kHeadDim * 2);
+  p.o_part_o = place((size_t)p.rows * p.n_parts * kHeadDim * sizeof(float));
+  p.o_part_m = place((size_t)p.rows * p.n_parts * sizeof(float));
+  p.o_part_l = place((size_t)p.rows * p.n_parts * sizeof(float));
+  p.bytes = std::max<size_t>(off, 256);
+  return true;
+}
+
+}  // namespace
+
+size_t tdk_attend_workspace_bytes(const tdk_round* r, int32_t n_q, int32_t n_q_heads) {
+  AttendPlan p;
+  return attend_plan(r, n_q, n_q_heads, p) ? p.bytes : 0;
+}
+
+tdk_status tdk_attend_shared(tdk_round* r, int32_t layer, const tdk_layer_io* io, const tdk_diff* in,
+                             const tdk_attend_io* a, void* hip_stream) {
+  return guarded([&]() -> tdk_status {
+    if (!r) return fail(TDK_ERR_INVALID_ARG, "round is NULL");
+    if (!io || !a) return fail(TDK_ERR_INVALID_ARG, "layer io / attend io is NULL");
+    if (layer < 0 || layer >= r->model.num_layers) return fail(TDK_ERR_INVALID_ARG, "layer out of range");
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev != r->device)
+      return fail(TDK_ERR_INVALID_ARG, "the round was created on another device than the current one");
+    if (r->rd.seg) return fail(TDK_ERR_UNSUPPORTED, "attention over rounds with per-agent block layouts is not built");
+    tdk_status st = check_diff(r, in, false);
+    if (st != TDK_OK) return st;
+    AttendPlan p;
+    if (!attend_plan(r, a->n_q, a->n_q_heads, p))
+      return fail(TDK_ERR_INVALID_ARG, "n_q must be >= 1 and n_q_heads a positive multiple of the KV heads");
+    if (!std::isfinite(a->scale)) return fail(TDK_ERR_INVALID_ARG, "scale must be finite");
+    if (p.rows == 0) return TDK_OK;
+    if (!a->q || !a->out || !a->lse || !a->workspace) return fail(TDK_ERR_INVALID_ARG, "attend io holds a NULL buffer");
+    if (((uintptr_t)a->q & 15) || ((uintptr_t)a->out & 15) || ((uintptr_t)a->workspace & 255))
+      return fail(TDK_ERR_INVALID_ARG, "q / out must be 16-byte aligned, the workspace 256-byte aligned");
+    if (a->workspace_bytes < p.bytes) return fail(TDK_ERR_INVALID_ARG, "workspace smaller than tdk_attend_workspace_bytes()");
+    if (r->total_master_rows > 0) {
+      if (!io->master_k || !io->master_v) return fail(TDK_ERR_INVALID_ARG, "layer io holds a NULL master");
+      if (((uintptr_t)io->master_k | (uintptr_t)io->master_v) & 15) return fail(TDK_ERR_INVALID_ARG, "masters must be 16-byte aligned");
+    }
+    AttendDev at;
+    char* ws = static_cast<char*>(a->workspace);
+    at.q = a->q;
+    at.qrot = ws + p.o_qrot;
+    at.part_o = reinterpret_cast<float*>(ws + p.o_part_o);
+    at.part_m = reinterpret_cast<float*>(ws + p.o_part_m);
+    at.part_l = reinterpret_cast<float*>(ws + p.o_part_l);
+    at.out = a->out;
+    at.lse = a->lse;
+    at.n_q = a->n_q;
+    at.n_q_heads = a->n_q_heads;
+    at.group = a->n_q_heads / r->model.num_kv_heads;
+    at.chunk_tokens = p.chunk_tokens;
+    at.n_chunks = p.n_chunks;
+    at.n_parts = p.n_parts;
+    at.scale = a->scale;
+    hipStream_t s = static_cast<hipStream_t>(hip_stream);
+    const LayerDev l = layer_dev(io);
+    const DiffDev d = diff_dev(in);
+    TDK_LAUNCH(r, TDK_KERNEL_ATTEND_QROT, s, launch_attend_qrot(r->rd, at, s));
+    TDK_LAUNCH(r, TDK_KERNEL_ATTEND_MASTER, s, launch_attend_master(r->rd, l, d, at, p.max_rows, s));
+    TDK_LAUNCH(r, TDK_KERNEL_ATTEND_DIFF, s, launch_attend_diff(r->rd, d, at, s));
+    TDK_LAUNCH(r, TDK_KERNEL_ATTEND_MERGE, s, launch_attend_merge(r->rd, at, s));
     return TDK_OK;
   });
 }

@@ -95,6 +95,22 @@ struct PlanDev {
   float    min_score;
 };
 
+// Attention over the shared span from master + diff (tdk_attend.hip).
+struct AttendDev {
+  const void* q;        // bf16 [n_agents][n_q][n_q_heads][128]
+  void*       qrot;     // workspace: the same rows rotated back by each agent's offset
+  float*      part_o;   // workspace: [rows][n_parts][128] un-normalised partial outputs
+  float*      part_m;   // workspace: [rows][n_parts] running maxima
+  float*      part_l;   // workspace: [rows][n_parts] partial sums
+  float*      out;      // [rows][128]
+  float*      lse;      // [rows]
+  int32_t n_q, n_q_heads, group;     // group = query heads per KV head
+  int32_t chunk_tokens;              // master tokens per workgroup of the master pass (multiple of 32 and of T)
+  int32_t n_chunks;                  // chunks of the longest span
+  int32_t n_parts;                   // n_chunks + 1: the last part holds the listed pages
+  float   scale;
+};
+
 // launchers (tdk_kernels.hip); each enqueues exactly one kernel
 hipError_t launch_rerotate(const RoundDev& rd, const LayerDev& io, hipStream_t st);
 hipError_t launch_flag(const RoundDev& rd, const LayerDev& io, float eps, int planes, hipStream_t st);
@@ -108,6 +124,12 @@ hipError_t launch_select(const RoundDev& rd, const PlanDev& pl, hipStream_t st);
 hipError_t launch_master(const RoundDev& rd, const PlanDev& pl, hipStream_t st);
 hipError_t launch_copy(u32x4* dst, const u32x4* src, size_t n16, hipStream_t st);
 hipError_t launch_fill(u32x4* dst, uint32_t word, size_t n16, hipStream_t st);
+
+hipError_t launch_attend_qrot(const RoundDev& rd, const AttendDev& at, hipStream_t st);
+hipError_t launch_attend_master(const RoundDev& rd, const LayerDev& io, const DiffDev& d, const AttendDev& at,
+                                int max_rows, hipStream_t st);
+hipError_t launch_attend_diff(const RoundDev& rd, const DiffDev& d, const AttendDev& at, hipStream_t st);
+hipError_t launch_attend_merge(const RoundDev& rd, const AttendDev& at, hipStream_t st);
 
 hipError_t launch_page_fill(u32x4* dst, const int32_t* ids, int n_pages, int page_u4, uint32_t word, hipStream_t st);
 hipError_t launch_page_read(const u32x4* src, const int32_t* ids, int n_pages, int page_u4, u32x4* sink, hipStream_t st);

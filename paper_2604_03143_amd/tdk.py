@@ -20,15 +20,16 @@ BF16 = 0
 ROPE_HALF, ROPE_INTERLEAVED = 0, 1
 PLANE_K, PLANE_V = 1, 2
 (KERNEL_REROTATE, KERNEL_FLAG, KERNEL_COUNT, KERNEL_INDEX, KERNEL_GATHER, KERNEL_DECODE, KERNEL_SCATTER,
- KERNEL_KEYDIFF, KERNEL_SELECT, KERNEL_MASTER) = range(10)
-KERNEL_KINDS = 10
+ KERNEL_KEYDIFF, KERNEL_SELECT, KERNEL_MASTER, KERNEL_ATTEND_QROT, KERNEL_ATTEND_MASTER, KERNEL_ATTEND_DIFF,
+ KERNEL_ATTEND_MERGE) = range(14)
+KERNEL_KINDS = 14
 TUNE_ALL, TUNE_DEFAULT = 127, 63
 
 EXPORTS = (
     "tdk_status_str", "tdk_last_error", "tdk_version", "tdk_kernel_name",
     "tdk_round_create", "tdk_round_destroy", "tdk_scratch_bytes", "tdk_round_tune",
     "tdk_rerotate_round", "tdk_diff_encode", "tdk_diff_decode", "tdk_restore_layers", "tdk_check_layer",
-    "tdk_diff_encode_plane", "tdk_diff_decode_plane",
+    "tdk_diff_encode_plane", "tdk_diff_decode_plane", "tdk_attend_workspace_bytes", "tdk_attend_shared",
     "tdk_timing_enable", "tdk_timing_read", "tdk_timing_reset",
     "tdk_dense_bytes", "tdk_diff_bytes", "tdk_family_cost",
     "tdk_util_copy", "tdk_util_fill", "tdk_util_page_fill", "tdk_util_page_read",
@@ -68,6 +69,11 @@ class Diff(C.Structure):
 class ReusePlan(C.Structure):
     _fields_ = [("score", C.c_void_p), ("important", C.c_void_p), ("k_stride", C.c_int32),
                 ("n_important", C.c_void_p), ("total", C.c_void_p), ("master", C.c_void_p)]
+
+
+class AttendIO(C.Structure):
+    _fields_ = [("q", C.c_void_p), ("n_q", C.c_int32), ("n_q_heads", C.c_int32), ("scale", C.c_float),
+                ("out", C.c_void_p), ("lse", C.c_void_p), ("workspace", C.c_void_p), ("workspace_bytes", C.c_size_t)]
 
 
 class PingPong(C.Structure):
@@ -113,6 +119,9 @@ def load() -> C.CDLL:
     L.tdk_diff_decode_plane.argtypes = [C.c_void_p, C.c_int32, C.POINTER(LayerIO), C.c_int32, C.POINTER(Diff), C.c_void_p]
     L.tdk_check_layer.argtypes = [C.c_void_p, C.c_int32, C.POINTER(LayerIO), C.c_float, C.c_float,
                                   C.POINTER(ReusePlan), C.c_void_p]
+    L.tdk_attend_workspace_bytes.argtypes = [C.c_void_p, C.c_int32, C.c_int32]
+    L.tdk_attend_workspace_bytes.restype = C.c_size_t
+    L.tdk_attend_shared.argtypes = [C.c_void_p, C.c_int32, C.POINTER(LayerIO), C.POINTER(Diff), C.POINTER(AttendIO), C.c_void_p]
     L.tdk_restore_layers.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.POINTER(C.c_void_p), C.POINTER(C.c_void_p),
                                      C.POINTER(LayerIO), C.POINTER(Diff), C.POINTER(PingPong), C.c_void_p, C.c_void_p]
     L.tdk_timing_enable.argtypes = [C.c_void_p, C.c_int32]
@@ -268,6 +277,20 @@ def tdk_check_layer(r: Round, layer: int, io: LayerIO, ratio: float, min_score: 
                     stream: int = 0) -> None:
     _check(load().tdk_check_layer(r.handle, layer, C.byref(io), C.c_float(ratio), C.c_float(min_score),
                                   C.byref(plan), C.c_void_p(stream)), "tdk_check_layer")
+
+
+def tdk_attend_workspace_bytes(r: Round, n_q: int, n_q_heads: int) -> int:
+    return int(load().tdk_attend_workspace_bytes(r.handle, n_q, n_q_heads))
+
+
+def attend_io(q, n_q: int, n_q_heads: int, scale: float, out, lse, workspace, workspace_bytes: int) -> AttendIO:
+    return AttendIO(_ptr(q), int(n_q), int(n_q_heads), float(scale), _ptr(out), _ptr(lse), _ptr(workspace),
+                    int(workspace_bytes))
+
+
+def tdk_attend_shared(r: Round, layer: int, io: LayerIO, d: Diff, a: AttendIO, stream: int = 0) -> None:
+    _check(load().tdk_attend_shared(r.handle, layer, C.byref(io), C.byref(d), C.byref(a), C.c_void_p(stream)),
+           "tdk_attend_shared")
 
 
 def pingpong(stage_k0, stage_k1, stage_v0, stage_v1, stage_bytes: int) -> PingPong:

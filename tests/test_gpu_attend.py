@@ -1,0 +1,118 @@
+"""Attention over mirrors that are never restored (Sec. 4.4, the diff applied as attention tiles are loaded),
+through the C ABI against the oracle.  The GPU path rounds the back-rotated queries and the softmax weights
+to bf16 for its two MFMA products and accumulates in fp32, so the comparison is by tolerance: with |q|, |k|,
+|v| ~ 1 and D = 128 the scores carry an error of about 2^-9 * sqrt(D) * |q||k| * scale ~ 1e-3 and each
+weight one of 2^-9 relative; the normalised outputs then agree to a few 1e-3 of max |V| (bound used: 1e-2),
+the log-sum-exp to 5e-3.  A wrong table sign, head mapping, page mask or plane offset moves them by O(1)."""
+import numpy as np
+import pytest
+
+from paper_2604_03143_amd import workload as wl
+from helpers import OracleRun
+
+pytestmark = pytest.mark.gpu
+
+OUT_TOL, LSE_TOL = 1e-2, 5e-3
+
+
+def _case(tdo, spec, n_q, Hq, style=0, grow=None, seed=3):
+    import torch
+    from paper_2604_03143_amd import tdk
+    import gpu_helpers as gh
+    if not torch.cuda.is_available():
+        pytest.fail("GPU tests need a GPU")
+    old = wl.make_round(spec)
+    o = OracleRun(tdo, old, style=style)
+    o.rerotate(); o.perturb()
+    d = o.encode()
+    rnd, diff_pos0 = old, None
+    if grow is not None:
+        rnd = wl.make_round(spec, hist=old.agent_pos0 + np.asarray(grow, np.int64))
+        diff_pos0 = old.agent_pos0
+    g = np.random.default_rng([spec.stream, seed])
+    q = wl.f32_to_bf16_bits(g.standard_normal((rnd.n_agents, n_q, Hq, spec.head_dim)).astype(np.float32))
+    scale = 1.0 / np.sqrt(spec.head_dim)
+    want_o, want_l = tdo.attend_shared(o.g, tdo.HostRound(rnd, diff_pos0=diff_pos0), o.mk, o.mv, d, q, n_q, Hq, scale)
+
+    r = tdk.round_from_workload(rnd, style=style, diff_pos0=diff_pos0)
+    try:
+        n = int(d.offset[-1])
+        mk, mv = gh.up(o.mk), gh.up(o.mv)
+        cnt, off = torch.from_numpy(d.count).cuda(), torch.from_numpy(d.offset).cuda()
+        idx, pay = torch.from_numpy(d.idx[:max(n, 1)].copy()).cuda(), gh.up(d.payload[:max(n, 1)].copy())
+        dd = tdk.diff(cnt, off, idx, pay, n, torch.zeros(1, dtype=torch.int32, device="cuda"))
+        io = tdk.layer_io(mk, mv, None, None, 0)
+        nbytes = tdk.tdk_attend_workspace_bytes(r, n_q, Hq)
+        assert nbytes > 0
+        ws = torch.empty(nbytes + 256, dtype=torch.uint8, device="cuda")
+        ws.fill_(0xFF)                                   # NaN patterns: stale workspace must not leak into results
+        out = torch.full((rnd.n_agents, n_q, Hq, spec.head_dim), float("nan"), dtype=torch.float32, device="cuda")
+        lse = torch.full((rnd.n_agents, n_q, Hq), float("nan"), dtype=torch.float32, device="cuda")
+        a = tdk.attend_io(gh.up(q), n_q, Hq, scale, out, lse, ws, nbytes)
+        tdk.tdk_attend_shared(r, 0, io, dd, a, torch.cuda.current_stream().cuda_stream)
+        torch.cuda.synchronize()
+        got_o, got_l = out.cpu().numpy().astype(np.float64), lse.cpu().numpy().astype(np.float64)
+    finally:
+        r.destroy()
+    vmax = float(np.max(np.abs(wl.bf16_bits_to_f32(o.mv))))
+    err_o = float(np.max(np.abs(got_o - want_o)))
+    err_l = float(np.max(np.abs(got_l - want_l)))
+    assert np.all(np.isfinite(got_o)) and np.all(np.isfinite(got_l))
+    assert err_o <= OUT_TOL * max(1.0, vmax) and err_l <= LSE_TOL, (err_o, err_l)
+    return err_o, err_l
+
+
+def test_one_query_token_per_agent(tdo):
+    """Decode step: 1 query token, 40 query heads on 8 KV heads, ragged span, several tiles and chunks."""
+    spec = wl.RoundSpec("att", 61, 1, 8, 128, 16, 1.0e6, 2, 5, 4, 73, 5, 3000, 0.2)
+    _case(tdo, spec, 1, 40)
+
+
+@pytest.mark.parametrize("H,Hq,T,style,n_q", [(4, 28, 16, 0, 3), (8, 8, 32, 0, 2), (2, 4, 16, 1, 5), (1, 7, 16, 0, 1)])
+def test_head_counts_page_sizes_styles_and_several_query_tokens(tdo, H, Hq, T, style, n_q):
+    spec = wl.RoundSpec("att2", 62, 1, H, 128, T, 1.0e6, 1, 4, 3, 50, 0, 500, 0.3)
+    _case(tdo, spec, n_q, Hq, style=style)
+
+
+def test_more_query_rows_than_one_block_and_mirrors_stored_elsewhere(tdo):
+    """160 query rows per KV head (two row blocks), and a diff that was stored when the histories were shorter."""
+    spec = wl.RoundSpec("att3", 63, 1, 2, 128, 16, 5.0e5, 1, 8, 3, 40, 10, 200, 0.4)
+    _case(tdo, spec, 5, 8, grow=[0, 16, 7, 250, 1, 31, 1000, 64])
+
+
+def test_argument_errors(tdo):
+    import torch
+    from paper_2604_03143_amd import tdk
+    import gpu_helpers as gh
+    spec = wl.RoundSpec("att4", 64, 1, 2, 128, 16, 1.0e6, 1, 2, 2, 20, 0, 50, 0.5)
+    rnd = wl.make_round(spec)
+    r = tdk.round_from_workload(rnd)
+    try:
+        assert tdk.tdk_attend_workspace_bytes(r, 1, 3) == 0 and tdk.tdk_attend_workspace_bytes(r, 0, 2) == 0
+        nbytes = tdk.tdk_attend_workspace_bytes(r, 1, 2)
+        mk, mv = (gh.up(x) for x in wl.master_host(rnd, 0))      # kept alive: layer_io holds raw pointers
+        io = tdk.layer_io(mk, mv, None, None, 0)
+        d = gh.DevDiff(rnd.n_agents, 4, 2 * 16 * 256)
+        d.count.zero_(); d.offset.zero_()
+        q = torch.zeros((2, 1, 2, 128), dtype=torch.int16, device="cuda")
+        out = torch.zeros((2, 1, 2, 128), dtype=torch.float32, device="cuda")
+        lse = torch.zeros((2, 1, 2), dtype=torch.float32, device="cuda")
+        ws = torch.empty(nbytes, dtype=torch.uint8, device="cuda")
+        for bad in (tdk.attend_io(q, 1, 2, 1.0, out, lse, ws, nbytes - 1), tdk.attend_io(q, 1, 3, 1.0, out, lse, ws, nbytes),
+                    tdk.attend_io(None, 1, 2, 1.0, out, lse, ws, nbytes), tdk.attend_io(q, 1, 2, float("inf"), out, lse, ws, nbytes)):
+            with pytest.raises(tdk.TdkError):
+                tdk.tdk_attend_shared(r, 0, io, d.c, bad)
+        tdk.tdk_attend_shared(r, 0, io, d.c, tdk.attend_io(q, 1, 2, 1.0, out, lse, ws, nbytes))
+        torch.cuda.synchronize()
+        # zero queries: uniform weights, lse = log S
+        assert torch.allclose(lse, torch.full_like(lse, float(np.log(spec.span_tokens))), atol=1e-4)
+    finally:
+        r.destroy()
+    seg = wl.permute_blocks(wl.make_round(spec))
+    r2 = tdk.round_from_workload(seg)
+    try:
+        with pytest.raises(tdk.TdkError) as e:
+            tdk.tdk_attend_shared(r2, 0, io, d.c, tdk.attend_io(q, 1, 2, 1.0, out, lse, ws, nbytes))
+        assert e.value.status == tdk.ERR_UNSUPPORTED
+    finally:
+        r2.destroy()
