@@ -38,9 +38,11 @@ def parse():
                     help="physical page placement of the synthetic pool (fragmented = the graded recipe)")
     ap.add_argument("--layout", default="identity", choices=["identity", "permuted"],
                     help="order of the shared blocks in every agent's prompt (identity = the graded recipe)")
-    ap.add_argument("--mode", default="step", choices=["step", "restore", "check", "planes"],
+    ap.add_argument("--mode", default="step", choices=["step", "restore", "check", "planes", "attend"],
                     help="step: the whole hot path (default, the headline metric); restore: layerwise ping-pong "
                          "restore from pinned host memory (Alg. 1) against a dense restore")
+    ap.add_argument("--n-q", type=int, default=1, help="attend mode: query tokens per agent")
+    ap.add_argument("--q-heads", type=int, default=0, help="attend mode: query heads (0 = 5 per KV head)")
     ap.add_argument("--layers", type=int, default=0, help="override the layer count (for profiling runs only)")
     return ap.parse_args()
 
@@ -70,6 +72,8 @@ def main():
         return check_mode(args, tdk, wl, np, torch, dev)
     if args.mode == "planes":
         return planes_mode(args, tdk, wl, np, torch, dev)
+    if args.mode == "attend":
+        return attend_mode(args, tdk, wl, np, torch, dev)
 
     spec = wl.CONFIGS[args.workload]
     L = args.layers or spec.num_layers
@@ -556,6 +560,119 @@ def planes_mode(args, tdk, wl, np, torch, dev):
                                     decode=round((t["decode_K"] + t["decode_V"]) / t["decode_paired"], 3)),
                check=dict(planewise_restore_bitexact=ok, lists_equal_shared_list=same_lists))
     print(json.dumps(out))
+    r.destroy()
+
+
+def attend_mode(args, tdk, wl, np, torch, dev):
+    """Attention of new query tokens over the shared span of every mirror straight from master + diff
+    (Sec. 4.4, the diff applied as attention tiles are loaded), against what restoring the mirrors first
+    costs: the restore itself plus one read of the restored caches (the least an attention kernel over
+    them has to do)."""
+    spec = wl.CONFIGS[args.workload]
+    rnd = wl.make_round(spec, alloc=args.alloc)
+    A, T, RE, H, D = rnd.n_agents, spec.page_tokens, spec.row_elems, spec.num_kv_heads, spec.head_dim
+    Hq = args.q_heads or 5 * H
+    n_q = args.n_q
+    rows = rnd.pool_pages * T
+    st = torch.cuda.current_stream().cuda_stream
+    r = tdk.round_from_workload(rnd)
+    n_pert = sum(len(p) for p in rnd.perturbed)
+    cap = n_pert + 64
+    mk, mv = wl.master_device(rnd, 0, dev)
+    pk = torch.zeros((rows, RE), dtype=torch.int16, device=dev)
+    pv = torch.zeros((rows, RE), dtype=torch.int16, device=dev)
+    io = tdk.layer_io(mk, mv, pk, pv, rnd.pool_pages)
+    tdk.tdk_rerotate_round(r, 0, io, st)
+    wl.perturb_device(rnd, 0, pk, pv)
+    d = dict(count=torch.zeros(A, dtype=torch.int32, device=dev), offset=torch.zeros(A + 1, dtype=torch.int64, device=dev),
+             idx=torch.full((cap,), -1, dtype=torch.int32, device=dev),
+             payload=torch.zeros((cap, 2 * T * RE), dtype=torch.int16, device=dev),
+             overflow=torch.zeros(1, dtype=torch.int32, device=dev))
+    d["c"] = tdk.diff(d["count"], d["offset"], d["idx"], d["payload"], cap, d["overflow"])
+    tdk.tdk_diff_encode(r, 0, io, spec.eps, d["c"], st)
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(wl.SEED_BASE + 17)
+    q = torch.randn((A, n_q, Hq, D), generator=gen, device=dev, dtype=torch.float32).to(torch.bfloat16).view(torch.int16)
+    out = torch.zeros((A, n_q, Hq, D), dtype=torch.float32, device=dev)
+    lse = torch.zeros((A, n_q, Hq), dtype=torch.float32, device=dev)
+    nbytes = tdk.tdk_attend_workspace_bytes(r, n_q, Hq)
+    ws = torch.empty(nbytes, dtype=torch.uint8, device=dev)
+    scale = 1.0 / float(np.sqrt(D))
+    a = tdk.attend_io(q, n_q, Hq, scale, out, lse, ws, nbytes)
+    torch.cuda.synchronize()
+    assert int(d["offset"][-1].item()) == n_pert
+
+    def timed(fn, reps):
+        fn(); fn()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(reps):
+            fn()
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) * 1e3 / reps      # us
+
+    reps = max(1, args.steps) * 4
+    t_att = timed(lambda: tdk.tdk_attend_shared(r, 0, io, d["c"], a, st), reps)
+    tdk.tdk_timing_reset(r); tdk.tdk_timing_enable(r, True)
+    for _ in range(reps):
+        tdk.tdk_attend_shared(r, 0, io, d["c"], a, st)
+    torch.cuda.synchronize()
+    tdk.tdk_timing_enable(r, False)
+    us = {}
+    for k in (tdk.KERNEL_ATTEND_QROT, tdk.KERNEL_ATTEND_MASTER, tdk.KERNEL_ATTEND_DIFF, tdk.KERNEL_ATTEND_MERGE):
+        ms, n = tdk.tdk_timing_read(r, k)
+        us[tdk.tdk_kernel_name(k)] = round(ms / n * 1e3, 2)
+    # the other way: restore every mirror, then read the restored caches once
+    t_dec = timed(lambda: tdk.tdk_diff_decode(r, 0, io, d["c"], st), 5)
+    ids = torch.from_numpy(np.unique(np.concatenate([rnd.block_tables[i][int(rnd.agent_pos0[i]) // T:] for i in range(A)])
+                                     ).astype(np.int32)).to(dev)
+    sink = torch.zeros(16, dtype=torch.uint8, device=dev)
+    t_read = timed(lambda: (tdk.tdk_util_page_read(pk, ids, ids.numel(), T * RE * 2, sink, st),
+                            tdk.tdk_util_page_read(pv, ids, ids.numel(), T * RE * 2, sink, st)), 5)
+
+    # parity sample: the first three agents against the oracle (exact definition, double precision)
+    check = {}
+    if not args.no_check:
+        from oracle import tdo
+        n = 3
+        sub, _ = wl.subround(rnd, range(n))
+        off = d["offset"].cpu().numpy(); cnt = d["count"].cpu().numpy()
+        m = int(off[n])
+        od = tdo.Diff(n, max(m, 1), 2 * T * RE)
+        od.count[:] = cnt[:n]; od.offset[:] = off[:n + 1]
+        od.idx[:m] = d["idx"][:m].cpu().numpy(); od.payload[:m] = d["payload"][:m].cpu().numpy().view(np.uint16)
+        S0 = int(sub.span_tokens[0])
+        hmk, hmv = mk[:S0].cpu().numpy().view(np.uint16), mv[:S0].cpu().numpy().view(np.uint16)
+        t0 = time.perf_counter()
+        want_o, want_l = tdo.attend_shared(tdo.geom_of(spec), tdo.HostRound(sub), hmk, hmv, od,
+                                           q[:n].cpu().numpy().view(np.uint16), n_q, Hq, scale)
+        oracle_s = time.perf_counter() - t0
+        err_o = float(np.max(np.abs(out[:n].cpu().numpy().astype(np.float64) - want_o)))
+        err_l = float(np.max(np.abs(lse[:n].cpu().numpy().astype(np.float64) - want_l)))
+        check = dict(sample="agents 0-2 against the oracle", max_abs_err_out=err_o, max_abs_err_lse=err_l,
+                     within_tolerance=bool(err_o <= 1e-2 * max(1.0, float(np.abs(wl.bf16_bits_to_f32(hmv)).max())) and err_l <= 5e-3),
+                     oracle_seconds=round(oracle_s, 2), oracle_cores=tdo.max_threads())
+
+    master_b = sum(int(x) for x in rnd.span_tokens) * ROW_PAIR_BYTES
+    payload_b = n_pert * 2 * T * RE * 2
+    qo_b = A * n_q * Hq * D * (2 + 4) + A * n_q * Hq * 4
+    alg = master_b + payload_b + qo_b
+    flops = 4.0 * A * n_q * Hq * D * spec.span_tokens
+    ach = alg / (t_att * 1e-6) / 1e9
+    out_d = dict(metric="attention over the shared span of never-restored mirrors: query rows per second; GB/s of master + diff read",
+                 value=round(A * n_q * Hq / (t_att * 1e-6), 1), unit="query rows/s", n_gpus=1, steps=reps, higher_is_better=True,
+                 dtype="bf16", data="synthetic", vs_baseline=None,
+                 config=dict(workload=args.workload, agents=A, span_tokens=int(spec.span_tokens), n_q=n_q, q_heads=Hq,
+                             listed_pages=n_pert, workspace_bytes=nbytes),
+                 us_per_layer=round(t_att, 2), kernels_avg_us=us,
+                 roofline=dict(bound="hbm", kernel="tdk_attend_shared (4 kernels)", achieved=round(ach, 1), peak=HBM_PEAK_GBPS,
+                               unit="GB/s", frac=round(ach / HBM_PEAK_GBPS, 4), traffic=None, algorithmic_bytes_per_launch=alg),
+                 mfma_TFLOPs=round(flops / (t_att * 1e-6) / 1e12, 2),
+                 restore_first=dict(decode_us=round(t_dec, 2), read_restored_caches_us=round(t_read, 2),
+                                    speedup=round((t_dec + t_read) / t_att, 2)),
+                 check=check)
+    print(json.dumps(out_d))
     r.destroy()
 
 

@@ -716,7 +716,7 @@ namespace {
 struct AttendPlan {
   int32_t chunk_tokens = 0, n_chunks = 0, n_parts = 0, max_rows = 0;
   int64_t rows = 0;
-  size_t o_qrot = 0, o_part_o = 0, o_part_m = 0, o_part_l = 0, bytes = 0;
+  size_t o_qrot = 0, o_qdiff = 0, o_part_o = 0, o_part_m = 0, o_part_l = 0, bytes = 0;
 };
 
 bool attend_plan(const tdk_round* r, int32_t n_q, int32_t n_q_heads, AttendPlan& p) {
@@ -750,6 +750,7 @@ bool attend_plan(const tdk_round* r, int32_t n_q, int32_t n_q_heads, AttendPlan&
   size_t off = 0;
   auto place = [&](size_t bytes) { size_t o = off; off = align_up(off + bytes, 256); return o; };
   p.o_qrot = place((size_t)p.rows * kHeadDim * 2);
+  p.o_qdiff = place((size_t)p.rows * kHeadDim * 2);
   p.o_part_o = place((size_t)p.rows * p.n_parts * kHeadDim * sizeof(float));
   p.o_part_m = place((size_t)p.rows * p.n_parts * sizeof(float));
   p.o_part_l = place((size_t)p.rows * p.n_parts * sizeof(float));
@@ -793,6 +794,7 @@ tdk_status tdk_attend_shared(tdk_round* r, int32_t layer, const tdk_layer_io* io
     char* ws = static_cast<char*>(a->workspace);
     at.q = a->q;
     at.qrot = ws + p.o_qrot;
+    at.qdiff = ws + p.o_qdiff;
     at.part_o = reinterpret_cast<float*>(ws + p.o_part_o);
     at.part_m = reinterpret_cast<float*>(ws + p.o_part_m);
     at.part_l = reinterpret_cast<float*>(ws + p.o_part_l);

@@ -26,6 +26,8 @@ constexpr int kRowsPerWave = 32;     // query rows per wavefront (the N side of 
 constexpr int kRowsPerBlock = kRowsPerWave * kWaves;
 constexpr int kKsStride = kHeadDim + 8;   // bf16 elements per staged K row (+16 bytes: spreads LDS banks)
 constexpr int kVtStride = kTile + 4;      // bf16 elements per staged V^T row
+constexpr int kBigTile = 2 * kTile;       // tokens per step of the master pass
+constexpr int kBigVtStride = kBigTile + 4;
 
 __device__ __forceinline__ float bfl(uint32_t w) { return __uint_as_float(w << 16); }
 __device__ __forceinline__ float bfh(uint32_t w) { return __uint_as_float(w & 0xffff0000u); }
@@ -52,6 +54,97 @@ __device__ __forceinline__ RowRef row_ref(const RoundDev& rd, const SessionDev& 
   return r;
 }
 
+// Running softmax of one query row (the lane pair n, n + 32 shares a row) and its output accumulators:
+// oacc[b][i] is element 32 b + 8 (i / 4) + 4 hh + i % 4 of the row's un-normalised output.
+struct RowState {
+  float m_run, l_run;
+  f32x16 oacc[4];
+};
+
+__device__ __forceinline__ void row_state_init(RowState& st) {
+  st.m_run = -INFINITY;
+  st.l_run = 0.f;
+#pragma unroll
+  for (int b = 0; b < 4; ++b)
+#pragma unroll
+    for (int i = 0; i < 16; ++i) st.oacc[b][i] = 0.f;
+}
+
+// one staged token row (32 bytes of K and of V per thread) into the K tile and the transposed V tile
+template <int VT_STRIDE>
+__device__ __forceinline__ void stage_rows(uint16_t* Ks, uint16_t* Vt, int tok, int part, u32x4 k0, u32x4 k1, u32x4 v0, u32x4 v1) {
+  u32x4* kd = reinterpret_cast<u32x4*>(Ks + tok * kKsStride + part * 16);
+  kd[0] = k0; kd[1] = k1;
+#pragma unroll
+  for (int e = 0; e < 4; ++e) {
+    const int dd = part * 16 + 2 * e;
+    Vt[(dd + 0) * VT_STRIDE + tok] = (uint16_t)(v0[e] & 0xffffu);
+    Vt[(dd + 1) * VT_STRIDE + tok] = (uint16_t)(v0[e] >> 16);
+    Vt[(dd + 8) * VT_STRIDE + tok] = (uint16_t)(v1[e] & 0xffffu);
+    Vt[(dd + 9) * VT_STRIDE + tok] = (uint16_t)(v1[e] >> 16);
+  }
+}
+
+// One 32-token tile for the 32 query rows of a wavefront.
+//   S^T (tokens x rows) = K (tokens x d) * Q^T (d x rows): lane (n, hh) then holds, for row n, the
+//   scores of tokens 8 (i / 4) + 4 hh + i % 4; bit i of `live` says whether that token takes part.
+//   O^T (d x rows) += V^T (d x tokens) * P^T (tokens x rows), contracting over the tokens in the order
+//   the lane holds them, so the weights need no exchange between lanes.
+template <int VT_STRIDE>
+__device__ __forceinline__ void tile_compute(const uint16_t* Ks, const uint16_t* Vt, const bf16x8 (&qf)[8], float scale,
+                                             uint32_t live, int n, int hh, RowState& st) {
+  f32x16 sacc;
+#pragma unroll
+  for (int i = 0; i < 16; ++i) sacc[i] = 0.f;
+#pragma unroll
+  for (int kk = 0; kk < 8; ++kk) {
+    const u32x4 a = *reinterpret_cast<const u32x4*>(Ks + n * kKsStride + 16 * kk + 8 * hh);
+    sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a), qf[kk], sacc, 0, 0, 0);
+  }
+  float p[16];
+  float mx = -INFINITY;
+#pragma unroll
+  for (int i = 0; i < 16; ++i) {
+    p[i] = ((live >> i) & 1u) ? sacc[i] * scale : -INFINITY;
+    mx = fmaxf(mx, p[i]);
+  }
+  mx = fmaxf(mx, __shfl_xor(mx, 32));
+  // The reference point of the exponentials only has to keep them in range, so it follows the running
+  // maximum lazily: it moves when the maximum has grown by more than kLazy (weights stay below e^kLazy,
+  // far inside fp32 and bf16 range), and the accumulators are rescaled only then.
+  constexpr float kLazy = 8.f;
+  const float m_new = mx > st.m_run + kLazy || st.m_run == -INFINITY ? fmaxf(st.m_run, mx) : st.m_run;
+  const float m_ref = m_new == -INFINITY ? 0.f : m_new;
+  float sum = 0.f;
+#pragma unroll
+  for (int i = 0; i < 16; ++i) { p[i] = __expf(p[i] - m_ref); sum += p[i]; }
+  if (__any(m_new != st.m_run)) {
+    const float alpha = __expf(st.m_run - m_ref);      // 1 for the rows whose reference stays
+    st.l_run *= alpha;
+#pragma unroll
+    for (int b = 0; b < 4; ++b)
+#pragma unroll
+      for (int i = 0; i < 16; ++i) st.oacc[b][i] *= alpha;
+  }
+  st.l_run += sum;
+  st.m_run = m_new;
+#pragma unroll
+  for (int kk = 0; kk < 2; ++kk) {
+    u32x4 pw;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) pw[e] = pack2(p[8 * kk + 2 * e], p[8 * kk + 2 * e + 1]);
+    const bf16x8 pb = __builtin_bit_cast(bf16x8, pw);
+#pragma unroll
+    for (int b = 0; b < 4; ++b) {
+      const uint16_t* vr = Vt + (32 * b + n) * VT_STRIDE + 16 * kk + 4 * hh;
+      const uint2 lo = *reinterpret_cast<const uint2*>(vr);
+      const uint2 hi = *reinterpret_cast<const uint2*>(vr + 8);
+      const u32x4 a = {lo.x, lo.y, hi.x, hi.y};
+      st.oacc[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a), pb, st.oacc[b], 0, 0, 0);
+    }
+  }
+}
+
 }  // namespace
 
 // ---------------------------------------------------------------------------------------------
@@ -75,6 +168,18 @@ __global__ __launch_bounds__(kBlock) void tdk_attend_qrot_kernel(const RoundDev 
   const float yb = __builtin_fmaf(xb, c, -__fmul_rn(xa, s));
   dst[ia] = (uint16_t)(pack2(ya, 0.f) & 0xffffu);
   dst[ib] = (uint16_t)(pack2(yb, 0.f) & 0xffffu);
+  // the queries the listed pages meet: as they are, or turned back by the distance the stored values
+  // have moved since they were encoded
+  uint16_t* dst2 = reinterpret_cast<uint16_t*>(at.qdiff) + row * kHeadDim;
+  uint16_t za = src[ia], zb = src[ib];
+  if (rd.agents[agent].diff_rot) {
+    const float* td = rd.tab_diff + (size_t)agent * (2 * kHalf);
+    const float c2 = td[lane], s2 = td[kHalf + lane];
+    za = (uint16_t)(pack2(__builtin_fmaf(xa, c2, __fmul_rn(xb, s2)), 0.f) & 0xffffu);
+    zb = (uint16_t)(pack2(__builtin_fmaf(xb, c2, -__fmul_rn(xa, s2)), 0.f) & 0xffffu);
+  }
+  dst2[ia] = za;
+  dst2[ib] = zb;
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -83,8 +188,8 @@ __global__ __launch_bounds__(kBlock) void tdk_attend_qrot_kernel(const RoundDev 
 // ---------------------------------------------------------------------------------------------
 __global__ __launch_bounds__(kBlock) void tdk_attend_master_kernel(const RoundDev rd, const LayerDev io, const DiffDev d,
                                                                    const AttendDev at) {
-  __shared__ __attribute__((aligned(16))) uint16_t Ks[kTile * kKsStride];
-  __shared__ __attribute__((aligned(16))) uint16_t Vt[kHeadDim * kVtStride];
+  __shared__ __attribute__((aligned(16))) uint16_t Ks[kBigTile * kKsStride];
+  __shared__ __attribute__((aligned(16))) uint16_t Vt[kHeadDim * kBigVtStride];
   __shared__ uint32_t s_mask[kRowsPerBlock];    // bit p: page p of this chunk is listed in the row's agent's diff
 
   const int session = blockIdx.x / at.n_chunks, chunk = blockIdx.x - session * at.n_chunks;
@@ -137,94 +242,59 @@ __global__ __launch_bounds__(kBlock) void tdk_attend_master_kernel(const RoundDe
   __syncthreads();
   const uint32_t my_mask = s_mask[wave * kRowsPerWave + n];
 
-  f32x16 oacc[4];
-#pragma unroll
-  for (int b = 0; b < 4; ++b)
-#pragma unroll
-    for (int i = 0; i < 16; ++i) oacc[b][i] = 0.f;
-  float m_run = -INFINITY, l_run = 0.f;
+  RowState rs;
+  row_state_init(rs);
 
   const int64_t head_u4 = 16;                                  // 128 bf16 = 16 chunks of 16 bytes
   const int64_t row_u4 = (int64_t)rd.heads * head_u4;
   const int st_tok = threadIdx.x >> 3, st_part = threadIdx.x & 7;   // staging: 8 threads per token, 32 bytes each
 
-  for (int t0 = tok_begin; t0 < tok_end; t0 += kTile) {
-    __syncthreads();                                           // the previous tile has been consumed
-    {
-      const int m = t0 + st_tok;
-      u32x4 k0 = {0, 0, 0, 0}, k1 = k0, v0 = k0, v1 = k0;
+  // 64 tokens per step: the next step's rows travel from HBM to registers while this one is multiplied
+  u32x4 kv[2][4];
+  auto fetch = [&](int t0) {
+#pragma unroll
+    for (int half = 0; half < 2; ++half) {
+      const int m = t0 + half * kTile + st_tok;
+      const u32x4 z = {0, 0, 0, 0};
+      kv[half][0] = z; kv[half][1] = z; kv[half][2] = z; kv[half][3] = z;
       if (m < tok_end) {
         const int64_t base = (sd.master_row0 + m) * row_u4 + h * head_u4 + st_part * 2;
-        k0 = io.master_k[base]; k1 = io.master_k[base + 1];
-        v0 = io.master_v[base]; v1 = io.master_v[base + 1];
-      }
-      u32x4* kd = reinterpret_cast<u32x4*>(Ks + st_tok * kKsStride + st_part * 16);
-      kd[0] = k0; kd[1] = k1;
-#pragma unroll
-      for (int e = 0; e < 4; ++e) {
-        const int dd = st_part * 16 + 2 * e;
-        Vt[(dd + 0) * kVtStride + st_tok] = (uint16_t)(v0[e] & 0xffffu);
-        Vt[(dd + 1) * kVtStride + st_tok] = (uint16_t)(v0[e] >> 16);
-        Vt[(dd + 8) * kVtStride + st_tok] = (uint16_t)(v1[e] & 0xffffu);
-        Vt[(dd + 9) * kVtStride + st_tok] = (uint16_t)(v1[e] >> 16);
+        kv[half][0] = io.master_k[base]; kv[half][1] = io.master_k[base + 1];
+        kv[half][2] = io.master_v[base]; kv[half][3] = io.master_v[base + 1];
       }
     }
+  };
+  fetch(tok_begin);
+  for (int t0 = tok_begin; t0 < tok_end; t0 += kBigTile) {
+    __syncthreads();                                           // the previous step has been consumed
+#pragma unroll
+    for (int half = 0; half < 2; ++half)
+      stage_rows<kBigVtStride>(Ks, Vt, half * kTile + st_tok, st_part, kv[half][0], kv[half][1], kv[half][2], kv[half][3]);
     __syncthreads();
-
-    // S^T (tokens x rows) = K (tokens x d) * Q'^T (d x rows)
-    f32x16 sacc;
+    if (t0 + kBigTile < tok_end) fetch(t0 + kBigTile);
 #pragma unroll
-    for (int i = 0; i < 16; ++i) sacc[i] = 0.f;
-#pragma unroll
-    for (int kk = 0; kk < 8; ++kk) {
-      const u32x4 a = *reinterpret_cast<const u32x4*>(Ks + n * kKsStride + 16 * kk + 8 * hh);
-      sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a), qf[kk], sacc, 0, 0, 0);
-    }
-    // this lane holds, for its query row, the tokens 8 (i / 4) + 4 hh + i % 4 of the tile
-    float p[16];
-    float mx = -INFINITY;
-#pragma unroll
-    for (int i = 0; i < 16; ++i) {
-      const int m = t0 + 8 * (i >> 2) + 4 * hh + (i & 3);
-      const bool masked = m >= tok_end || ((my_mask >> ((m - tok_begin) / T)) & 1u) || mine.agent < 0;
-      p[i] = masked ? -INFINITY : sacc[i] * at.scale;
-      mx = fmaxf(mx, p[i]);
-    }
-    mx = fmaxf(mx, __shfl_xor(mx, 32));
-    const float m_new = fmaxf(m_run, mx);
-    const float m_ref = m_new == -INFINITY ? 0.f : m_new;
-    const float alpha = __expf(m_run - m_ref);
-    float sum = 0.f;
-#pragma unroll
-    for (int i = 0; i < 16; ++i) { p[i] = __expf(p[i] - m_ref); sum += p[i]; }
-    l_run = l_run * alpha + sum;
-    m_run = m_new;
-#pragma unroll
-    for (int b = 0; b < 4; ++b)
-#pragma unroll
-      for (int i = 0; i < 16; ++i) oacc[b][i] *= alpha;
-
-    // O^T (d x rows) += V^T (d x tokens) * P^T (tokens x rows); the contraction runs over the tokens in the
-    // order this lane holds them, so P^T needs no exchange between lanes
-#pragma unroll
-    for (int kk = 0; kk < 2; ++kk) {
-      u32x4 pw;
-#pragma unroll
-      for (int e = 0; e < 4; ++e) pw[e] = pack2(p[8 * kk + 2 * e], p[8 * kk + 2 * e + 1]);
-      const bf16x8 pb = __builtin_bit_cast(bf16x8, pw);
-#pragma unroll
-      for (int b = 0; b < 4; ++b) {
-        const uint16_t* vr = Vt + (32 * b + n) * kVtStride + 16 * kk + 4 * hh;
-        const uint2 lo = *reinterpret_cast<const uint2*>(vr);
-        const uint2 hi = *reinterpret_cast<const uint2*>(vr + 8);
-        const u32x4 a = {lo.x, lo.y, hi.x, hi.y};
-        oacc[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a), pb, oacc[b], 0, 0, 0);
+    for (int half = 0; half < 2; ++half) {
+      const int tb = t0 + half * kTile;
+      if (tb >= tok_end) break;
+      // scores i < 8 of a lane belong to tokens 0..15 of the tile, the others to tokens 16..31
+      uint32_t live;
+      if (T == 16) {
+        const uint32_t pg = (uint32_t)(tb - tok_begin) >> 4;
+        live = (((my_mask >> pg) & 1u) ? 0u : 0x00ffu) | (((my_mask >> (pg + 1)) & 1u) ? 0u : 0xff00u);
+      } else {
+        live = ((my_mask >> ((uint32_t)(tb - tok_begin) >> 5)) & 1u) ? 0u : 0xffffu;
       }
+      if (mine.agent < 0) live = 0;
+      if (tb + kTile > tok_end) {                                // ragged end of the span
+#pragma unroll
+        for (int i = 0; i < 16; ++i)
+          if (tb + 8 * (i >> 2) + 4 * hh + (i & 3) >= tok_end) live &= ~(1u << i);
+      }
+      tile_compute<kBigVtStride>(Ks + half * kTile * kKsStride, Vt + half * kTile, qf, at.scale, live, n, hh, rs);
     }
   }
 
-  // partial result of this chunk: un-normalised output, running maximum and sum
-  const float l_tot = l_run + __shfl_xor(l_run, 32);
+  const float l_tot = rs.l_run + __shfl_xor(rs.l_run, 32);
   if (mine.agent >= 0) {
     const int64_t slot = mine.out * at.n_parts + chunk;
     float4* po = reinterpret_cast<float4*>(at.part_o + slot * kHeadDim);
@@ -232,147 +302,142 @@ __global__ __launch_bounds__(kBlock) void tdk_attend_master_kernel(const RoundDe
     for (int b = 0; b < 4; ++b)
 #pragma unroll
       for (int q4 = 0; q4 < 4; ++q4)
-        po[(32 * b + 8 * q4 + 4 * hh) >> 2] = make_float4(oacc[b][4 * q4], oacc[b][4 * q4 + 1], oacc[b][4 * q4 + 2], oacc[b][4 * q4 + 3]);
-    if (hh == 0) { at.part_m[slot] = m_run; at.part_l[slot] = l_tot; }
+        po[(32 * b + 8 * q4 + 4 * hh) >> 2] = make_float4(rs.oacc[b][4 * q4], rs.oacc[b][4 * q4 + 1], rs.oacc[b][4 * q4 + 2], rs.oacc[b][4 * q4 + 3]);
+    if (hh == 0) { at.part_m[slot] = rs.m_run; at.part_l[slot] = l_tot; }
   }
 }
 
 // ---------------------------------------------------------------------------------------------
-// diff pass: the pages an agent's diff lists, from the payload (fp32 arithmetic, no MFMA: a few
-// hundred tokens per agent).  One workgroup per (agent, KV head, block of up to 8 query rows).
+// diff pass: the pages an agent's diff lists, from the payload (the "correct" half of skip-or-correct).
+// One workgroup per (agent, KV head); the listed tokens form tiles of 32, wavefront w takes tiles
+// w, w + 4, ... through its own staging area, and the four running results are combined at the end.
 // ---------------------------------------------------------------------------------------------
-constexpr int kDiffRows = 8;
+constexpr int kWaveLds = kTile * kKsStride + kHeadDim * kVtStride;      // bf16 elements of one wavefront's staging area
 
 __global__ __launch_bounds__(kBlock) void tdk_attend_diff_kernel(const RoundDev rd, const DiffDev d, const AttendDev at) {
-  __shared__ float s_q[kDiffRows][kHeadDim];
-  __shared__ float s_p[kDiffRows][kBlock];
-  __shared__ float s_red[kDiffRows][kWaves];
-  __shared__ float s_o[kDiffRows][kHeadDim];
+  // staging areas during the token loop, then (reused) the four wavefronts' results: [4][32 rows][128 + 2] floats
+  __shared__ __attribute__((aligned(16))) uint16_t lds[kWaves * kWaveLds];
+  static_assert(sizeof(uint16_t) * kWaves * kWaveLds >= sizeof(float) * kWaves * kRowsPerWave * (kHeadDim + 2), "result area");
 
   const int agent = blockIdx.x, h = blockIdx.y;
   const int per_agent = at.n_q * at.group;
-  const int r0 = blockIdx.z * kDiffRows;
-  if (r0 >= per_agent) return;
-  const int nrows = min(kDiffRows, per_agent - r0);
   const AgentDev ad = rd.agents[agent];
   const SessionDev sd = rd.sess[ad.session];
   const int T = rd.page_tokens;
   int64_t lo = d.offset[agent], hi = lo + d.count[agent];
   if (lo < 0) lo = 0;
   if (hi > d.capacity) hi = d.capacity;
-  const int64_t n_tok = hi > lo ? (hi - lo) * T : 0;
-  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
-
-  // query rows in fp32; if the stored values sit at another position than today's, the queries are
-  // rotated back by that distance instead of rotating every stored key forward
-  for (int i = tid; i < nrows * kHalf; i += kBlock) {
-    const int r = i / kHalf, j = i - r * kHalf;
-    const int rem = r0 + r, qi = rem / at.group, g = rem - qi * at.group;
-    const uint16_t* src = reinterpret_cast<const uint16_t*>(at.q) +
-                          (((int64_t)agent * at.n_q + qi) * at.n_q_heads + h * at.group + g) * kHeadDim;
-    const int ia = rd.interleaved ? 2 * j : j, ib = rd.interleaved ? 2 * j + 1 : j + kHalf;
-    float xa = __uint_as_float((uint32_t)src[ia] << 16), xb = __uint_as_float((uint32_t)src[ib] << 16);
-    if (ad.diff_rot) {
-      const float c = rd.tab_diff[(size_t)agent * (2 * kHalf) + j], s = rd.tab_diff[(size_t)agent * (2 * kHalf) + kHalf + j];
-      const float ya = __builtin_fmaf(xa, c, __fmul_rn(xb, s)), yb = __builtin_fmaf(xb, c, -__fmul_rn(xa, s));
-      xa = ya; xb = yb;
-    }
-    s_q[r][ia] = xa; s_q[r][ib] = xb;
-  }
-  float m_run[kDiffRows], l_run[kDiffRows], o0[kDiffRows];   // this thread: d = tid % 128, one half of each block of tokens
-#pragma unroll
-  for (int r = 0; r < kDiffRows; ++r) { m_run[r] = -INFINITY; l_run[r] = 0.f; o0[r] = 0.f; }
-  __syncthreads();
-
-  const int64_t row_e = (int64_t)rd.heads * kHeadDim;                  // bf16 elements per token row
-  const int64_t page_e = (int64_t)T * row_e;
+  const int n_tok = hi > lo ? (int)((hi - lo) * T) : 0;
+  const int n_tiles = (n_tok + kTile - 1) / kTile;
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, n = lane & 31, hh = lane >> 5;
+  uint16_t* Ks = lds + wave * kWaveLds;
+  uint16_t* Vt = Ks + kTile * kKsStride;
+  const int64_t row_e = (int64_t)rd.heads * kHeadDim, page_e = (int64_t)T * row_e;
   const uint16_t* pay = reinterpret_cast<const uint16_t*>(d.payload);
-  for (int64_t tb = 0; tb < n_tok; tb += kBlock) {
-    // scores of one token per thread
-    const int64_t t = tb + tid;
-    float sc[kDiffRows];
+
+  for (int r0 = 0; r0 < per_agent; r0 += kRowsPerWave) {
+    // this lane's query row of the block
+    const int rem = r0 + n;
+    const bool row_ok = rem < per_agent;
+    const int qi = row_ok ? rem / at.group : 0, g = row_ok ? rem - qi * at.group : 0;
+    const int64_t out = ((int64_t)agent * at.n_q + qi) * at.n_q_heads + h * at.group + g;
+    bf16x8 qf[8];
+    {
+      const u32x4* qp = reinterpret_cast<const u32x4*>(reinterpret_cast<const uint16_t*>(at.qdiff) + out * kHeadDim);
 #pragma unroll
-    for (int r = 0; r < kDiffRows; ++r) sc[r] = -INFINITY;
-    if (t < n_tok) {
-      const int64_t slot = lo + t / T;
-      const int rr = (int)(t % T);
-      const int p = d.idx[slot];
-      if (p >= 0 && p < sd.pages && p * T + rr < sd.span) {
-        const u32x4* kr = reinterpret_cast<const u32x4*>(pay + (slot * 2) * page_e + rr * row_e + h * kHeadDim);
-        float acc[kDiffRows];
+      for (int kk = 0; kk < 8; ++kk) {
+        u32x4 v = {0, 0, 0, 0};
+        if (row_ok) v = qp[2 * kk + hh];
+        qf[kk] = __builtin_bit_cast(bf16x8, v);
+      }
+    }
+    RowState rs;
+    row_state_init(rs);
+    // a wavefront's next tile travels from the payload to registers while its current one is multiplied:
+    // 32 tokens x 8 parts of 32 bytes, four (token, part) pairs per lane
+    u32x4 kv[4][4];
+    uint32_t valid_next = 0;                     // bit t: token t of the fetched tile exists and lies inside the span
+    auto fetch = [&](int tile) {
+      valid_next = 0;
 #pragma unroll
-        for (int r = 0; r < kDiffRows; ++r) acc[r] = 0.f;
-        for (int c = 0; c < 16; ++c) {
-          const u32x4 kv = kr[c];
-#pragma unroll
-          for (int w = 0; w < 4; ++w) {
-            const float k0 = bfl(kv[w]), k1 = bfh(kv[w]);
-#pragma unroll
-            for (int r = 0; r < kDiffRows; ++r)
-              if (r < nrows) acc[r] = __builtin_fmaf(s_q[r][c * 8 + 2 * w + 1], k1, __builtin_fmaf(s_q[r][c * 8 + 2 * w], k0, acc[r]));
+      for (int j = 0; j < 4; ++j) {
+        const int pr = j * 64 + lane, tok = pr >> 3, part = pr & 7;
+        const int t = tile * kTile + tok;
+        const u32x4 z = {0, 0, 0, 0};
+        kv[j][0] = z; kv[j][1] = z; kv[j][2] = z; kv[j][3] = z;
+        if (tile < n_tiles && t < n_tok) {
+          const int64_t slot = lo + t / T;
+          const int rr = t % T, p = d.idx[slot];
+          if (p >= 0 && p < sd.pages && p * T + rr < sd.span) {
+            const u32x4* kr = reinterpret_cast<const u32x4*>(pay + (slot * 2) * page_e + rr * row_e + h * kHeadDim) + part * 2;
+            const u32x4* vr = reinterpret_cast<const u32x4*>(pay + (slot * 2 + 1) * page_e + rr * row_e + h * kHeadDim) + part * 2;
+            kv[j][0] = kr[0]; kv[j][1] = kr[1]; kv[j][2] = vr[0]; kv[j][3] = vr[1];
+            if (part == 0) valid_next |= 1u << tok;
           }
         }
+      }
+    };
+    fetch(wave);
+    for (int it = 0; it * kWaves < n_tiles; ++it) {
+      const int tile = it * kWaves + wave;
+      __syncthreads();
+      uint32_t valid = valid_next;
+      if (tile < n_tiles) {
 #pragma unroll
-        for (int r = 0; r < kDiffRows; ++r)
-          if (r < nrows) sc[r] = acc[r] * at.scale;
+        for (int j = 0; j < 4; ++j) {
+          const int pr = j * 64 + lane;
+          stage_rows<kVtStride>(Ks, Vt, pr >> 3, pr & 7, kv[j][0], kv[j][1], kv[j][2], kv[j][3]);
+        }
+      }
+      // every lane needs the validity of all 32 tokens of the tile
+#pragma unroll
+      for (int sft = 1; sft < 64; sft <<= 1) valid |= __shfl_xor(valid, sft);
+      __syncthreads();
+      if ((it + 1) * kWaves < n_tiles) fetch(tile + kWaves);
+      if (tile < n_tiles) {
+        // score i of a lane belongs to token 8 (i / 4) + 4 hh + i % 4: four nibbles of `valid`
+        const uint32_t vs = valid >> (4 * hh);
+        uint32_t live = (vs & 0xfu) | ((vs >> 4) & 0xf0u) | ((vs >> 8) & 0xf00u) | ((vs >> 12) & 0xf000u);
+        if (!row_ok) live = 0;
+        tile_compute<kVtStride>(Ks, Vt, qf, at.scale, live, n, hh, rs);
       }
     }
-    // block-wide maximum per row, then the weights of this block of tokens
+    // combine the four wavefronts (the staging areas are free now)
+    __syncthreads();
+    float* res = reinterpret_cast<float*>(lds);                          // [4][32][130]: 128 outputs, m, l
+    {
+      float* mine = res + ((size_t)wave * kRowsPerWave + n) * (kHeadDim + 2);
 #pragma unroll
-    for (int r = 0; r < kDiffRows; ++r) {
-      float v = sc[r];
+      for (int b = 0; b < 4; ++b)
 #pragma unroll
-      for (int sft = 32; sft > 0; sft >>= 1) v = fmaxf(v, __shfl_xor(v, sft));
-      if (lane == 0) s_red[r][wave] = v;
+        for (int i = 0; i < 16; ++i) mine[32 * b + 8 * (i >> 2) + 4 * hh + (i & 3)] = rs.oacc[b][i];
+      const float l_tot = rs.l_run + __shfl_xor(rs.l_run, 32);
+      if (hh == 0) { mine[kHeadDim] = rs.m_run; mine[kHeadDim + 1] = l_tot; }
     }
     __syncthreads();
-    float alpha[kDiffRows];
+    for (int e = threadIdx.x; e < kRowsPerWave * kHeadDim; e += kBlock) {
+      const int row = e >> 7, dd = e & (kHeadDim - 1);
+      const int rem2 = r0 + row;
+      if (rem2 >= per_agent) continue;
+      float M = -INFINITY;
 #pragma unroll
-    for (int r = 0; r < kDiffRows; ++r) {
-      const float mx = fmaxf(fmaxf(s_red[r][0], s_red[r][1]), fmaxf(s_red[r][2], s_red[r][3]));
-      const float m_new = fmaxf(m_run[r], mx);
-      const float m_ref = m_new == -INFINITY ? 0.f : m_new;
-      alpha[r] = __expf(m_run[r] - m_ref);
-      m_run[r] = m_new;
-      s_p[r][tid] = __expf(sc[r] - m_ref);
-    }
-    __syncthreads();
-    // weighted V: thread = (element d, half of the block's tokens)
-    const int dd = tid & (kHeadDim - 1), half = tid >> 7;
+      for (int w = 0; w < kWaves; ++w) M = fmaxf(M, res[((size_t)w * kRowsPerWave + row) * (kHeadDim + 2) + kHeadDim]);
+      const float m_ref = M == -INFINITY ? 0.f : M;
+      float o = 0.f, l = 0.f;
 #pragma unroll
-    for (int r = 0; r < kDiffRows; ++r) { o0[r] *= alpha[r]; l_run[r] *= alpha[r]; }
-    const int64_t t_lo = tb + half * (kBlock / 2);
-    for (int j = 0; j < kBlock / 2; ++j) {
-      const int64_t tt = t_lo + j;
-      if (tt >= n_tok) break;
-      const int64_t slot = lo + tt / T;
-      const int rr = (int)(tt % T);
-      const float v = __uint_as_float((uint32_t)pay[(slot * 2 + 1) * page_e + rr * row_e + h * kHeadDim + dd] << 16);
-#pragma unroll
-      for (int r = 0; r < kDiffRows; ++r) {
-        const float w = s_p[r][half * (kBlock / 2) + j];
-        o0[r] = __builtin_fmaf(w, v, o0[r]);
-        l_run[r] += w;          // every thread of a half sums the same weights: l of that half
+      for (int w = 0; w < kWaves; ++w) {
+        const float* rw = res + ((size_t)w * kRowsPerWave + row) * (kHeadDim + 2);
+        const float wgt = __expf(rw[kHeadDim] - m_ref);
+        o = __builtin_fmaf(rw[dd], wgt, o);
+        l = __builtin_fmaf(rw[kHeadDim + 1], wgt, l);
       }
+      const int qi2 = rem2 / at.group, g2 = rem2 - qi2 * at.group;
+      const int64_t out2 = ((int64_t)agent * at.n_q + qi2) * at.n_q_heads + h * at.group + g2;
+      const int64_t slot = out2 * at.n_parts + (at.n_parts - 1);
+      at.part_o[slot * kHeadDim + dd] = o;
+      if (dd == 0) { at.part_m[slot] = M; at.part_l[slot] = l; }
     }
     __syncthreads();
-  }
-  // combine the two halves and store the partial result in the last slot of each row
-  if (tid >= kHeadDim) {
-#pragma unroll
-    for (int r = 0; r < kDiffRows; ++r) { s_o[r][tid - kHeadDim] = o0[r]; if (tid == kHeadDim) s_red[r][0] = l_run[r]; }
-  }
-  __syncthreads();
-  if (tid < kHeadDim) {
-#pragma unroll
-    for (int r = 0; r < kDiffRows; ++r) {
-      if (r >= nrows) continue;
-      const int rem = r0 + r, qi = rem / at.group, g = rem - qi * at.group;
-      const int64_t out = ((int64_t)agent * at.n_q + qi) * at.n_q_heads + h * at.group + g;
-      const int64_t slot = out * at.n_parts + (at.n_parts - 1);
-      at.part_o[slot * kHeadDim + tid] = o0[r] + s_o[r][tid];
-      if (tid == 0) { at.part_m[slot] = m_run[r]; at.part_l[slot] = l_run[r] + s_red[r][0]; }
-    }
   }
 }
 
@@ -387,24 +452,35 @@ __global__ __launch_bounds__(kBlock) void tdk_attend_merge_kernel(const RoundDev
   const int agent = (int)(row / ((int64_t)at.n_q * at.n_q_heads));
   const int span = rd.sess[rd.agents[agent].session].span;
   const int chunks = (span + at.chunk_tokens - 1) / at.chunk_tokens;
+  const int used = chunks + 1;                     // the chunks of this row's span, then the listed pages
+  const int64_t base = row * at.n_parts;
+  auto part_of = [&](int c) { return c < chunks ? c : at.n_parts - 1; };
+  // a lane per part for the maxima and the weights, then a lane per output element
   float M = -INFINITY;
-  for (int c = 0; c <= chunks; ++c) {
-    const int part = c < chunks ? c : at.n_parts - 1;
-    M = fmaxf(M, at.part_m[row * at.n_parts + part]);
+  for (int c0 = 0; c0 < used; c0 += 64) {
+    const int c = c0 + lane;
+    if (c < used) M = fmaxf(M, at.part_m[base + part_of(c)]);
   }
+#pragma unroll
+  for (int sft = 32; sft > 0; sft >>= 1) M = fmaxf(M, __shfl_xor(M, sft));
   float L = 0.f, a0 = 0.f, a1 = 0.f;
-  if (M != -INFINITY) {
-    for (int c = 0; c <= chunks; ++c) {
-      const int part = c < chunks ? c : at.n_parts - 1;
-      const int64_t slot = row * at.n_parts + part;
-      const float m = at.part_m[slot];
-      if (m == -INFINITY) continue;
-      const float w = __expf(m - M);
-      L = __builtin_fmaf(at.part_l[slot], w, L);
-      a0 = __builtin_fmaf(at.part_o[slot * kHeadDim + lane], w, a0);
-      a1 = __builtin_fmaf(at.part_o[slot * kHeadDim + 64 + lane], w, a1);
+  for (int c0 = 0; c0 < used; c0 += 64) {
+    const int c = c0 + lane;
+    float w = 0.f;
+    if (c < used) {
+      const float m = at.part_m[base + part_of(c)];
+      if (m != -INFINITY) { w = __expf(m - M); L = __builtin_fmaf(at.part_l[base + part_of(c)], w, L); }
+    }
+    const int cnt = min(64, used - c0);
+    for (int j = 0; j < cnt; ++j) {
+      const float wj = __shfl(w, j);
+      const float* po = at.part_o + (base + part_of(c0 + j)) * kHeadDim;
+      a0 = __builtin_fmaf(po[lane], wj, a0);
+      a1 = __builtin_fmaf(po[64 + lane], wj, a1);
     }
   }
+#pragma unroll
+  for (int sft = 32; sft > 0; sft >>= 1) L += __shfl_xor(L, sft);
   const float inv = L > 0.f ? 1.f / L : 0.f;
   at.out[row * kHeadDim + lane] = a0 * inv;
   at.out[row * kHeadDim + 64 + lane] = a1 * inv;
@@ -432,8 +508,7 @@ hipError_t launch_attend_master(const RoundDev& rd, const LayerDev& io, const Di
 
 hipError_t launch_attend_diff(const RoundDev& rd, const DiffDev& d, const AttendDev& at, hipStream_t st) {
   if (rd.n_agents == 0) return hipSuccess;
-  const int per_agent = at.n_q * at.group;
-  const dim3 grid((unsigned)rd.n_agents, (unsigned)rd.heads, (unsigned)((per_agent + kDiffRows - 1) / kDiffRows));
+  const dim3 grid((unsigned)rd.n_agents, (unsigned)rd.heads);
   hipLaunchKernelGGL(tdk_attend_diff_kernel, grid, dim3(kBlock), 0, st, rd, d, at);
   return hipGetLastError();
 }

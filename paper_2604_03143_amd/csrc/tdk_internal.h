@@ -99,6 +99,7 @@ struct PlanDev {
 struct AttendDev {
   const void* q;        // bf16 [n_agents][n_q][n_q_heads][128]
   void*       qrot;     // workspace: the same rows rotated back by each agent's offset
+  void*       qdiff;    // workspace: the rows as the listed pages meet them (turned back by dst - diff position)
   float*      part_o;   // workspace: [rows][n_parts][128] un-normalised partial outputs
   float*      part_m;   // workspace: [rows][n_parts] running maxima
   float*      part_l;   // workspace: [rows][n_parts] partial sums
