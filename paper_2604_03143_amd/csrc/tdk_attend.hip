@@ -247,29 +247,29 @@ __global__ __launch_bounds__(kBlock) void tdk_attend_master_kernel(const RoundDe
 
   const int64_t head_u4 = 16;                                  // 128 bf16 = 16 chunks of 16 bytes
   const int64_t row_u4 = (int64_t)rd.heads * head_u4;
-  const int st_tok = threadIdx.x >> 3, st_part = threadIdx.x & 7;   // staging: 8 threads per token, 32 bytes each
+  // staging: a lane per token of the 64-token step, a wavefront per 64 bytes of the 256-byte head row.  The
+  // transposed V tile is then written 64 consecutive tokens at a time (no LDS bank conflicts); with the
+  // tokens spread over the lanes' upper bits instead, those 2-byte writes serialise 8 to 16 deep.
+  const int st_tok = threadIdx.x & 63, st_pg = threadIdx.x >> 6;
 
   // 64 tokens per step: the next step's rows travel from HBM to registers while this one is multiplied
-  u32x4 kv[2][4];
+  u32x4 kv[8];
   auto fetch = [&](int t0) {
+    const int m = t0 + st_tok;
+    const u32x4 z = {0, 0, 0, 0};
 #pragma unroll
-    for (int half = 0; half < 2; ++half) {
-      const int m = t0 + half * kTile + st_tok;
-      const u32x4 z = {0, 0, 0, 0};
-      kv[half][0] = z; kv[half][1] = z; kv[half][2] = z; kv[half][3] = z;
-      if (m < tok_end) {
-        const int64_t base = (sd.master_row0 + m) * row_u4 + h * head_u4 + st_part * 2;
-        kv[half][0] = io.master_k[base]; kv[half][1] = io.master_k[base + 1];
-        kv[half][2] = io.master_v[base]; kv[half][3] = io.master_v[base + 1];
-      }
+    for (int e = 0; e < 8; ++e) kv[e] = z;
+    if (m < tok_end) {
+      const int64_t base = (sd.master_row0 + m) * row_u4 + h * head_u4 + st_pg * 4;
+#pragma unroll
+      for (int e = 0; e < 4; ++e) { kv[e] = io.master_k[base + e]; kv[4 + e] = io.master_v[base + e]; }
     }
   };
   fetch(tok_begin);
   for (int t0 = tok_begin; t0 < tok_end; t0 += kBigTile) {
     __syncthreads();                                           // the previous step has been consumed
-#pragma unroll
-    for (int half = 0; half < 2; ++half)
-      stage_rows<kBigVtStride>(Ks, Vt, half * kTile + st_tok, st_part, kv[half][0], kv[half][1], kv[half][2], kv[half][3]);
+    stage_rows<kBigVtStride>(Ks, Vt, st_tok, 2 * st_pg, kv[0], kv[1], kv[4], kv[5]);
+    stage_rows<kBigVtStride>(Ks, Vt, st_tok, 2 * st_pg + 1, kv[2], kv[3], kv[6], kv[7]);
     __syncthreads();
     if (t0 + kBigTile < tok_end) fetch(t0 + kBigTile);
 #pragma unroll
@@ -357,25 +357,25 @@ __global__ __launch_bounds__(kBlock) void tdk_attend_diff_kernel(const RoundDev 
     // 32 tokens x 8 parts of 32 bytes, four (token, part) pairs per lane
     u32x4 kv[4][4];
     uint32_t valid_next = 0;                     // bit t: token t of the fetched tile exists and lies inside the span
+    const int st_tok = lane & 31, st_pg = lane >> 5;      // this lane stages parts 4 st_pg .. 4 st_pg + 3 of one token
     auto fetch = [&](int tile) {
-      valid_next = 0;
+      const int t = tile * kTile + st_tok;
+      const u32x4 z = {0, 0, 0, 0};
 #pragma unroll
-      for (int j = 0; j < 4; ++j) {
-        const int pr = j * 64 + lane, tok = pr >> 3, part = pr & 7;
-        const int t = tile * kTile + tok;
-        const u32x4 z = {0, 0, 0, 0};
-        kv[j][0] = z; kv[j][1] = z; kv[j][2] = z; kv[j][3] = z;
-        if (tile < n_tiles && t < n_tok) {
-          const int64_t slot = lo + t / T;
-          const int rr = t % T, p = d.idx[slot];
-          if (p >= 0 && p < sd.pages && p * T + rr < sd.span) {
-            const u32x4* kr = reinterpret_cast<const u32x4*>(pay + (slot * 2) * page_e + rr * row_e + h * kHeadDim) + part * 2;
-            const u32x4* vr = reinterpret_cast<const u32x4*>(pay + (slot * 2 + 1) * page_e + rr * row_e + h * kHeadDim) + part * 2;
-            kv[j][0] = kr[0]; kv[j][1] = kr[1]; kv[j][2] = vr[0]; kv[j][3] = vr[1];
-            if (part == 0) valid_next |= 1u << tok;
-          }
+      for (int j = 0; j < 4; ++j) { kv[j][0] = z; kv[j][1] = z; kv[j][2] = z; kv[j][3] = z; }
+      bool ok = false;
+      if (tile < n_tiles && t < n_tok) {
+        const int64_t slot = lo + t / T;
+        const int rr = t % T, p = d.idx[slot];
+        if (p >= 0 && p < sd.pages && p * T + rr < sd.span) {
+          ok = true;
+          const u32x4* kr = reinterpret_cast<const u32x4*>(pay + (slot * 2) * page_e + rr * row_e + h * kHeadDim) + st_pg * 8;
+          const u32x4* vr = reinterpret_cast<const u32x4*>(pay + (slot * 2 + 1) * page_e + rr * row_e + h * kHeadDim) + st_pg * 8;
+#pragma unroll
+          for (int j = 0; j < 4; ++j) { kv[j][0] = kr[2 * j]; kv[j][1] = kr[2 * j + 1]; kv[j][2] = vr[2 * j]; kv[j][3] = vr[2 * j + 1]; }
         }
       }
+      valid_next = (uint32_t)__ballot(ok);       // lanes 0..31 carry the tokens (lanes 32..63 repeat them)
     };
     fetch(wave);
     for (int it = 0; it * kWaves < n_tiles; ++it) {
@@ -384,14 +384,8 @@ __global__ __launch_bounds__(kBlock) void tdk_attend_diff_kernel(const RoundDev 
       uint32_t valid = valid_next;
       if (tile < n_tiles) {
 #pragma unroll
-        for (int j = 0; j < 4; ++j) {
-          const int pr = j * 64 + lane;
-          stage_rows<kVtStride>(Ks, Vt, pr >> 3, pr & 7, kv[j][0], kv[j][1], kv[j][2], kv[j][3]);
-        }
+        for (int j = 0; j < 4; ++j) stage_rows<kVtStride>(Ks, Vt, st_tok, 4 * st_pg + j, kv[j][0], kv[j][1], kv[j][2], kv[j][3]);
       }
-      // every lane needs the validity of all 32 tokens of the tile
-#pragma unroll
-      for (int sft = 1; sft < 64; sft <<= 1) valid |= __shfl_xor(valid, sft);
       __syncthreads();
       if ((it + 1) * kWaves < n_tiles) fetch(tile + kWaves);
       if (tile < n_tiles) {
