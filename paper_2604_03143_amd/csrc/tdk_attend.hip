@@ -8,8 +8,8 @@
 // (agents x query tokens x query heads of one KV head) become the N side of one dense product with
 // the master's K and V tiles, which is MFMA work, and the master is read once per session instead of
 // once per agent.  Pages that an agent's diff lists are masked out of that product for that agent's
-// rows and handled by a second, small kernel from the payload (the "correct" half); a third kernel
-// merges the partial results with their log-sum-exp weights.
+// rows and handled by a second kernel from the payload (the "correct" half) with the same tile code; a
+// last kernel merges the partial results with their log-sum-exp weights.
 #include "tdk_internal.h"
 
 namespace tdk {
@@ -29,8 +29,6 @@ constexpr int kVtStride = kTile + 4;      // bf16 elements per staged V^T row
 constexpr int kBigTile = 2 * kTile;       // tokens per step of the master pass
 constexpr int kBigVtStride = kBigTile + 4;
 
-__device__ __forceinline__ float bfl(uint32_t w) { return __uint_as_float(w << 16); }
-__device__ __forceinline__ float bfh(uint32_t w) { return __uint_as_float(w & 0xffff0000u); }
 __device__ __forceinline__ uint32_t pack2(float a, float b) {
   f32x2a v = {a, b};
   return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2a));
