@@ -83,6 +83,14 @@ __device__ __forceinline__ void stage_rows(uint16_t* Ks, uint16_t* Vt, int tok, 
   }
 }
 
+// Orders the LDS traffic of one wavefront (its lanes exchange data through a staging area no other
+// wavefront touches): no hardware barrier, only a point the compiler may not move memory accesses across.
+__device__ __forceinline__ void wave_sync() {
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+  __builtin_amdgcn_wave_barrier();
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
+
 // One 32-token tile for the 32 query rows of a wavefront.
 //   S^T (tokens x rows) = K (tokens x d) * Q^T (d x rows): lane (n, hh) then holds, for row n, the
 //   scores of tokens 8 (i / 4) + 4 hh + i % 4; bit i of `live` says whether that token takes part.
@@ -128,6 +136,65 @@ __device__ __forceinline__ void tile_compute(const uint16_t* Ks, const uint16_t*
   st.m_run = m_new;
 #pragma unroll
   for (int kk = 0; kk < 2; ++kk) {
+    u32x4 pw;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) pw[e] = pack2(p[8 * kk + 2 * e], p[8 * kk + 2 * e + 1]);
+    const bf16x8 pb = __builtin_bit_cast(bf16x8, pw);
+#pragma unroll
+    for (int b = 0; b < 4; ++b) {
+      const uint16_t* vr = Vt + (32 * b + n) * VT_STRIDE + 16 * kk + 4 * hh;
+      const uint2 lo = *reinterpret_cast<const uint2*>(vr);
+      const uint2 hi = *reinterpret_cast<const uint2*>(vr + 8);
+      const u32x4 a = {lo.x, lo.y, hi.x, hi.y};
+      st.oacc[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a), pb, st.oacc[b], 0, 0, 0);
+    }
+  }
+}
+
+// The same for a 64-token step held in LDS (two independent score tiles): their MFMA chains interleave,
+// the LDS reads of one hide behind the products of the other, and the softmax bookkeeping (exchange with
+// the partner lane, reference point, rescale test) is paid once per 64 tokens.  Score i of a lane is token
+// 32 (i / 16) + 8 ((i % 16) / 4) + 4 hh + i % 4 of the step.
+template <int VT_STRIDE>
+__device__ __forceinline__ void tile_compute64(const uint16_t* Ks, const uint16_t* Vt, const bf16x8 (&qf)[8], float scale,
+                                               uint32_t live, int n, int hh, RowState& st) {
+  f32x16 s0, s1;
+#pragma unroll
+  for (int i = 0; i < 16; ++i) { s0[i] = 0.f; s1[i] = 0.f; }
+#pragma unroll
+  for (int kk = 0; kk < 8; ++kk) {
+    const u32x4 a0 = *reinterpret_cast<const u32x4*>(Ks + n * kKsStride + 16 * kk + 8 * hh);
+    const u32x4 a1 = *reinterpret_cast<const u32x4*>(Ks + (kTile + n) * kKsStride + 16 * kk + 8 * hh);
+    s0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a0), qf[kk], s0, 0, 0, 0);
+    s1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a1), qf[kk], s1, 0, 0, 0);
+  }
+  float p[32];
+  float mx = -INFINITY;
+#pragma unroll
+  for (int i = 0; i < 16; ++i) {
+    p[i] = ((live >> i) & 1u) ? s0[i] * scale : -INFINITY;
+    p[16 + i] = ((live >> (16 + i)) & 1u) ? s1[i] * scale : -INFINITY;
+    mx = fmaxf(mx, fmaxf(p[i], p[16 + i]));
+  }
+  mx = fmaxf(mx, __shfl_xor(mx, 32));
+  constexpr float kLazy = 8.f;
+  const float m_new = mx > st.m_run + kLazy || st.m_run == -INFINITY ? fmaxf(st.m_run, mx) : st.m_run;
+  const float m_ref = m_new == -INFINITY ? 0.f : m_new;
+  float sum = 0.f;
+#pragma unroll
+  for (int i = 0; i < 32; ++i) { p[i] = __expf(p[i] - m_ref); sum += p[i]; }
+  if (__any(m_new != st.m_run)) {
+    const float alpha = __expf(st.m_run - m_ref);
+    st.l_run *= alpha;
+#pragma unroll
+    for (int b = 0; b < 4; ++b)
+#pragma unroll
+      for (int i = 0; i < 16; ++i) st.oacc[b][i] *= alpha;
+  }
+  st.l_run += sum;
+  st.m_run = m_new;
+#pragma unroll
+  for (int kk = 0; kk < 4; ++kk) {
     u32x4 pw;
 #pragma unroll
     for (int e = 0; e < 4; ++e) pw[e] = pack2(p[8 * kk + 2 * e], p[8 * kk + 2 * e + 1]);
@@ -270,26 +337,26 @@ __global__ __launch_bounds__(kBlock) void tdk_attend_master_kernel(const RoundDe
     stage_rows<kBigVtStride>(Ks, Vt, st_tok, 2 * st_pg + 1, kv[2], kv[3], kv[6], kv[7]);
     __syncthreads();
     if (t0 + kBigTile < tok_end) fetch(t0 + kBigTile);
-#pragma unroll
-    for (int half = 0; half < 2; ++half) {
-      const int tb = t0 + half * kTile;
-      if (tb >= tok_end) break;
-      // scores i < 8 of a lane belong to tokens 0..15 of the tile, the others to tokens 16..31
-      uint32_t live;
+    // which of this lane's 32 scores take part: 16-token groups follow the page mask of the row's agent
+    uint32_t live;
+    {
+      const uint32_t rel = (uint32_t)(t0 - tok_begin);
       if (T == 16) {
-        const uint32_t pg = (uint32_t)(tb - tok_begin) >> 4;
-        live = (((my_mask >> pg) & 1u) ? 0u : 0x00ffu) | (((my_mask >> (pg + 1)) & 1u) ? 0u : 0xff00u);
+        const uint32_t m4 = ~(my_mask >> (rel >> 4)) & 0xfu;                 // four pages of 16 tokens
+        live = ((m4 & 1u) ? 0x000000ffu : 0u) | ((m4 & 2u) ? 0x0000ff00u : 0u) |
+               ((m4 & 4u) ? 0x00ff0000u : 0u) | ((m4 & 8u) ? 0xff000000u : 0u);
       } else {
-        live = ((my_mask >> ((uint32_t)(tb - tok_begin) >> 5)) & 1u) ? 0u : 0xffffu;
+        const uint32_t m2 = ~(my_mask >> (rel >> 5)) & 0x3u;                 // two pages of 32 tokens
+        live = ((m2 & 1u) ? 0x0000ffffu : 0u) | ((m2 & 2u) ? 0xffff0000u : 0u);
       }
       if (mine.agent < 0) live = 0;
-      if (tb + kTile > tok_end) {                                // ragged end of the span
+      if (t0 + kBigTile > tok_end) {                                         // ragged end of the span
 #pragma unroll
-        for (int i = 0; i < 16; ++i)
-          if (tb + 8 * (i >> 2) + 4 * hh + (i & 3) >= tok_end) live &= ~(1u << i);
+        for (int i = 0; i < 32; ++i)
+          if (t0 + 32 * (i >> 4) + 8 * ((i & 15) >> 2) + 4 * hh + (i & 3) >= tok_end) live &= ~(1u << i);
       }
-      tile_compute<kBigVtStride>(Ks + half * kTile * kKsStride, Vt + half * kTile, qf, at.scale, live, n, hh, rs);
     }
+    tile_compute64<kBigVtStride>(Ks, Vt, qf, at.scale, live, n, hh, rs);
   }
 
   const float l_tot = rs.l_run + __shfl_xor(rs.l_run, 32);
@@ -378,13 +445,13 @@ __global__ __launch_bounds__(kBlock) void tdk_attend_diff_kernel(const RoundDev 
     fetch(wave);
     for (int it = 0; it * kWaves < n_tiles; ++it) {
       const int tile = it * kWaves + wave;
-      __syncthreads();
+      wave_sync();                               // this wavefront's previous tile has been consumed
       uint32_t valid = valid_next;
       if (tile < n_tiles) {
 #pragma unroll
         for (int j = 0; j < 4; ++j) stage_rows<kVtStride>(Ks, Vt, st_tok, 4 * st_pg + j, kv[j][0], kv[j][1], kv[j][2], kv[j][3]);
       }
-      __syncthreads();
+      wave_sync();                               // the staging area belongs to this wavefront alone
       if ((it + 1) * kWaves < n_tiles) fetch(tile + kWaves);
       if (tile < n_tiles) {
         // score i of a lane belongs to token 8 (i / 4) + 4 hh + i % 4: four nibbles of `valid`
