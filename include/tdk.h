@@ -262,6 +262,8 @@ size_t tdk_attend_workspace_bytes(const tdk_round* r, int32_t n_q, int32_t n_q_h
 /* io: master_k / master_v of the layer (the pool is not touched and may be NULL); in: the mirrors'
  * paired diff as tdk_diff_encode wrote it.  Identity layouts only (UNSUPPORTED for rounds with
  * segments); a diff stored at other positions (diff_pos0) is handled.  Master values must be finite.
+ * Shaped for decode-like calls (a few query tokens per agent): every block of 128 query rows of a
+ * session and KV head reads the tiles again and owns its partial results in the workspace.
  * Allocates nothing, enqueues four kernels, does not synchronise.  Errors: INVALID_ARG (NULL,
  * misaligned, n_q < 1, n_q_heads not a multiple of H, scale not finite, workspace too small). */
 tdk_status tdk_attend_shared(tdk_round* r, int32_t layer, const tdk_layer_io* io, const tdk_diff* in,
