@@ -27,8 +27,8 @@
  *     the device that was current when it was created; step calls made with another device current
  *     fail with INVALID_ARG.
  *   - Results are deterministic: same inputs, same bits, including index order and payload placement.
- *   - Not checked (preconditions): physical pages of different agents do not overlap (the paper's
- *     "non-overlapping slot mappings", Sec. 4.2); buffers are not written concurrently; calls on one
+ *   - Not checked (preconditions): physical pages of different agents do not overlap (a precondition of
+ *     grouping requests, Sec. 4.2); buffers are not written concurrently; calls on one
  *     round are issued in stream order on one stream at a time (encode uses the round's own flag
  *     scratch, restore its events), different rounds are independent.
  *
