@@ -269,6 +269,31 @@ size_t tdk_attend_workspace_bytes(const tdk_round* r, int32_t n_q, int32_t n_q_h
 tdk_status tdk_attend_shared(tdk_round* r, int32_t layer, const tdk_layer_io* io, const tdk_diff* in,
                              const tdk_attend_io* a, void* hip_stream);
 
+/* Round-aware prompt interface (Sec. 4.1) and segment-based index (Sec. 5), HOST only.  Prompts are
+ * split at a reserved separator token; a block is identified by its content (64-bit hash index,
+ * every hit confirmed by comparison), so a shared update is recognised at whatever position it sits.
+ * A content held by at least two prompts is shared; prompts that hold the same set of shared contents
+ * (at least two prompts) form a session, numbered by first prompt; the session's master lists the
+ * shared blocks in the order of its first prompt (span = their total length); each member gets the
+ * segment list tdk_agent takes (src_tok in that master, dst_pos = position in the member's prompt,
+ * diff_pos = dst_pos).  Other prompts get session -1 (the single-request path).  Empty blocks are
+ * ignored; of a content repeated inside one prompt the first occurrence counts.  Token arrays are
+ * borrowed during the call only. */
+typedef struct {
+  const int32_t* tokens;   /* HOST */
+  int32_t        n_tokens;
+} tdk_prompt;
+typedef struct tdk_prompt_plan tdk_prompt_plan;   /* opaque, host memory */
+tdk_status tdk_prompt_plan_create(const tdk_prompt* prompts, int32_t n_prompts, int32_t separator,
+                                  tdk_prompt_plan** out);   /* INVALID_ARG, NOMEM, UNSUPPORTED (span >= 2^31) */
+void       tdk_prompt_plan_destroy(tdk_prompt_plan* p);     /* NULL-safe */
+int32_t    tdk_prompt_plan_n_sessions(const tdk_prompt_plan* p);
+int32_t    tdk_prompt_plan_span(const tdk_prompt_plan* p, int32_t session);         /* -1 if out of range */
+int32_t    tdk_prompt_plan_session_of(const tdk_prompt_plan* p, int32_t prompt);    /* -1: none */
+/* number of segments of a prompt (0 if it has no session, -1 if out of range); *out points into the
+ * plan and stays valid until the plan is destroyed */
+int32_t    tdk_prompt_plan_segments(const tdk_prompt_plan* p, int32_t prompt, const tdk_segment** out);
+
 /* Ping-pong staging buffers of the layerwise restore, DEV, caller-owned: two K and two V buffers of
  * stage_bytes each, stage_bytes >= (sum_s S_s) * H * D * 2 (one layer of masters). */
 typedef struct {

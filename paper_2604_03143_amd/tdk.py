@@ -30,6 +30,8 @@ EXPORTS = (
     "tdk_round_create", "tdk_round_destroy", "tdk_scratch_bytes", "tdk_round_tune",
     "tdk_rerotate_round", "tdk_diff_encode", "tdk_diff_decode", "tdk_restore_layers", "tdk_check_layer",
     "tdk_diff_encode_plane", "tdk_diff_decode_plane", "tdk_attend_workspace_bytes", "tdk_attend_shared",
+    "tdk_prompt_plan_create", "tdk_prompt_plan_destroy", "tdk_prompt_plan_n_sessions", "tdk_prompt_plan_span",
+    "tdk_prompt_plan_session_of", "tdk_prompt_plan_segments",
     "tdk_timing_enable", "tdk_timing_read", "tdk_timing_reset",
     "tdk_dense_bytes", "tdk_diff_bytes", "tdk_family_cost",
     "tdk_util_copy", "tdk_util_fill", "tdk_util_page_fill", "tdk_util_page_read",
@@ -74,6 +76,10 @@ class ReusePlan(C.Structure):
 class AttendIO(C.Structure):
     _fields_ = [("q", C.c_void_p), ("n_q", C.c_int32), ("n_q_heads", C.c_int32), ("scale", C.c_float),
                 ("out", C.c_void_p), ("lse", C.c_void_p), ("workspace", C.c_void_p), ("workspace_bytes", C.c_size_t)]
+
+
+class Prompt(C.Structure):
+    _fields_ = [("tokens", C.c_void_p), ("n_tokens", C.c_int32)]
 
 
 class PingPong(C.Structure):
@@ -122,6 +128,13 @@ def load() -> C.CDLL:
     L.tdk_attend_workspace_bytes.argtypes = [C.c_void_p, C.c_int32, C.c_int32]
     L.tdk_attend_workspace_bytes.restype = C.c_size_t
     L.tdk_attend_shared.argtypes = [C.c_void_p, C.c_int32, C.POINTER(LayerIO), C.POINTER(Diff), C.POINTER(AttendIO), C.c_void_p]
+    L.tdk_prompt_plan_create.argtypes = [C.POINTER(Prompt), C.c_int32, C.c_int32, C.POINTER(C.c_void_p)]
+    L.tdk_prompt_plan_destroy.argtypes = [C.c_void_p]
+    L.tdk_prompt_plan_destroy.restype = None
+    L.tdk_prompt_plan_n_sessions.argtypes = [C.c_void_p]
+    L.tdk_prompt_plan_span.argtypes = [C.c_void_p, C.c_int32]
+    L.tdk_prompt_plan_session_of.argtypes = [C.c_void_p, C.c_int32]
+    L.tdk_prompt_plan_segments.argtypes = [C.c_void_p, C.c_int32, C.POINTER(C.POINTER(Segment))]
     L.tdk_restore_layers.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.POINTER(C.c_void_p), C.POINTER(C.c_void_p),
                                      C.POINTER(LayerIO), C.POINTER(Diff), C.POINTER(PingPong), C.c_void_p, C.c_void_p]
     L.tdk_timing_enable.argtypes = [C.c_void_p, C.c_int32]
@@ -291,6 +304,29 @@ def attend_io(q, n_q: int, n_q_heads: int, scale: float, out, lse, workspace, wo
 def tdk_attend_shared(r: Round, layer: int, io: LayerIO, d: Diff, a: AttendIO, stream: int = 0) -> None:
     _check(load().tdk_attend_shared(r.handle, layer, C.byref(io), C.byref(d), C.byref(a), C.c_void_p(stream)),
            "tdk_attend_shared")
+
+
+def tdk_prompt_plan(prompts: Sequence[Sequence[int]], separator: int):
+    """Marshals token lists through tdk_prompt_plan_create and returns (spans per session, session per
+    prompt, segments per prompt as lists of (src_tok, dst_pos, len))."""
+    arrs = [np.ascontiguousarray(p, dtype=np.int32) for p in prompts]
+    ps = (Prompt * max(len(arrs), 1))()
+    for i, a in enumerate(arrs):
+        ps[i] = Prompt(a.ctypes.data if a.size else None, int(a.size))
+    plan = C.c_void_p()
+    L = load()
+    _check(L.tdk_prompt_plan_create(ps, len(arrs), int(separator), C.byref(plan)), "tdk_prompt_plan_create")
+    try:
+        spans = [int(L.tdk_prompt_plan_span(plan, s)) for s in range(int(L.tdk_prompt_plan_n_sessions(plan)))]
+        session_of, segments = [], []
+        for i in range(len(arrs)):
+            session_of.append(int(L.tdk_prompt_plan_session_of(plan, i)))
+            sp = C.POINTER(Segment)()
+            n = int(L.tdk_prompt_plan_segments(plan, i, C.byref(sp)))
+            segments.append([(int(sp[k].src_tok), int(sp[k].dst_pos), int(sp[k].len)) for k in range(n)])
+        return spans, session_of, segments
+    finally:
+        L.tdk_prompt_plan_destroy(plan)
 
 
 def pingpong(stage_k0, stage_k1, stage_v0, stage_v1, stage_bytes: int) -> PingPong:
