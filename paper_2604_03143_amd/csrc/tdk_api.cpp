@@ -77,6 +77,8 @@ struct tdk_round {
   bool free_recorded[2] = {false, false};
   int64_t total_master_rows = 0;
   int64_t total_tokens = 0;        // sum over agents of their session's span
+  int32_t max_segments = 1;        // most segments any agent has (1 for identity layouts)
+  bool seg_moved = false;          // a segmented agent's stored diff sits at other positions
 
   bool timing = false;
   std::vector<EventPair> pending;
@@ -356,6 +358,8 @@ tdk_status round_create(const tdk_model* model, const tdk_session* sessions, int
   std::vector<int32_t> rowmap;
   std::vector<int4> pagetab;
   std::vector<float> segtab, segtab_diff;
+  std::vector<int32_t> seg_off, seg_src;   // per agent the range of its segments (= its tables in segtab), their first master tokens
+  bool seg_moved = false;                  // some segment's stored diff sits at another position
   for (int32_t i = 0; i < n_agents; ++i) {
     const tdk_agent& a = agents[i];
     if (a.session < 0 || a.session >= n_sessions) { return fail(TDK_ERR_INVALID_ARG, "agent: session index out of range"); }
@@ -424,7 +428,10 @@ tdk_status round_create(const tdk_model* model, const tdk_session* sessions, int
       const tdk_segment* segs = a.n_segments ? a.segments : &whole;
       const int32_t nseg = a.n_segments ? a.n_segments : (S > 0 ? 1 : 0);
       const int32_t tab0 = (int32_t)(segtab.size() / (2 * kHalf));
+      seg_off.push_back(tab0);
       for (int32_t q = 0; q < nseg; ++q) {
+        seg_src.push_back(segs[q].src_tok);
+        seg_moved |= segs[q].dst_pos != segs[q].diff_pos;
         const double delta = (double)(segs[q].dst_pos - (hs.master_pos0 + segs[q].src_tok));
         for (int j = 0; j < kHalf; ++j) {
           const double inv_freq = std::pow(model->rope_theta, -(double)(2 * j) / (double)model->head_dim);
@@ -485,6 +492,9 @@ tdk_status round_create(const tdk_model* model, const tdk_session* sessions, int
     }
   }
   r->total_pages = flag_off;
+  if (any_segments) seg_off.push_back((int32_t)seg_src.size());
+  r->seg_moved = seg_moved;
+  for (int32_t i = 0; any_segments && i < n_agents; ++i) r->max_segments = std::max(r->max_segments, seg_off[i + 1] - seg_off[i]);
   if (any_segments && (r->max_phys_page + 1) * T >= (int64_t)1 << 31)
     return fail(TDK_ERR_UNSUPPORTED, "segmented layouts address pool rows with 32 bits: page numbers too large");
   std::vector<int32_t> order;
@@ -516,6 +526,8 @@ tdk_status round_create(const tdk_model* model, const tdk_session* sessions, int
   const size_t o_pagetab = place(any_segments ? pagetab.size() * sizeof(int4) : 0);
   const size_t o_segtab = place(any_segments ? segtab.size() * sizeof(float) : 0);
   const size_t o_segtab_diff = place(any_segments ? segtab_diff.size() * sizeof(float) : 0);
+  const size_t o_seg_off = place(any_segments ? seg_off.size() * sizeof(int32_t) : 0);
+  const size_t o_seg_src = place(any_segments ? seg_src.size() * sizeof(int32_t) : 0);
   const size_t o_flags = place((size_t)flag_off);
   r->blob_bytes = std::max<size_t>(off, 256);
 
@@ -537,6 +549,8 @@ tdk_status round_create(const tdk_model* model, const tdk_session* sessions, int
   if (e == hipSuccess && any_segments) e = up(o_pagetab, pagetab.data(), pagetab.size() * sizeof(int4));
   if (e == hipSuccess && any_segments) e = up(o_segtab, segtab.data(), segtab.size() * sizeof(float));
   if (e == hipSuccess && any_segments) e = up(o_segtab_diff, segtab_diff.data(), segtab_diff.size() * sizeof(float));
+  if (e == hipSuccess && any_segments) e = up(o_seg_off, seg_off.data(), seg_off.size() * sizeof(int32_t));
+  if (e == hipSuccess && any_segments) e = up(o_seg_src, seg_src.data(), seg_src.size() * sizeof(int32_t));
   if (e == hipSuccess && flag_off) e = hipMemset(base + o_flags, 0, (size_t)flag_off);
   if (e != hipSuccess) return hip_fail(e, "upload of round descriptors");
 
@@ -553,6 +567,8 @@ tdk_status round_create(const tdk_model* model, const tdk_session* sessions, int
   r->rd.pagetab = any_segments ? reinterpret_cast<const int4*>(base + o_pagetab) : nullptr;
   r->rd.segtab = any_segments ? reinterpret_cast<const float*>(base + o_segtab) : nullptr;
   r->rd.segtab_diff = any_segments ? reinterpret_cast<const float*>(base + o_segtab_diff) : nullptr;
+  r->rd.seg_off = any_segments ? reinterpret_cast<const int32_t*>(base + o_seg_off) : nullptr;
+  r->rd.seg_src = any_segments ? reinterpret_cast<const int32_t*>(base + o_seg_src) : nullptr;
   r->rd.n_agents = n_agents;
   r->rd.master_rows = r->total_master_rows;
   r->rd.n_sessions = n_sessions;
@@ -749,7 +765,7 @@ bool attend_plan(const tdk_round* r, int32_t n_q, int32_t n_q_heads, AttendPlan&
   p.n_parts = p.n_chunks + 1;
   size_t off = 0;
   auto place = [&](size_t bytes) { size_t o = off; off = align_up(off + bytes, 256); return o; };
-  p.o_qrot = place((size_t)p.rows * kHeadDim * 2);
+  p.o_qrot = place((size_t)p.rows * r->max_segments * kHeadDim * 2);
   p.o_qdiff = place((size_t)p.rows * kHeadDim * 2);
   p.o_part_o = place((size_t)p.rows * p.n_parts * kHeadDim * sizeof(float));
   p.o_part_m = place((size_t)p.rows * p.n_parts * sizeof(float));
@@ -774,7 +790,8 @@ tdk_status tdk_attend_shared(tdk_round* r, int32_t layer, const tdk_layer_io* io
     int dev = -1;
     if (hipGetDevice(&dev) != hipSuccess || dev != r->device)
       return fail(TDK_ERR_INVALID_ARG, "the round was created on another device than the current one");
-    if (r->rd.seg) return fail(TDK_ERR_UNSUPPORTED, "attention over rounds with per-agent block layouts is not built");
+    if (r->rd.seg && r->seg_moved)
+      return fail(TDK_ERR_UNSUPPORTED, "attention over per-agent block layouts takes diffs stored at the current positions only");
     tdk_status st = check_diff(r, in, false);
     if (st != TDK_OK) return st;
     AttendPlan p;
@@ -807,6 +824,7 @@ tdk_status tdk_attend_shared(tdk_round* r, int32_t layer, const tdk_layer_io* io
     at.n_chunks = p.n_chunks;
     at.n_parts = p.n_parts;
     at.scale = a->scale;
+    at.max_seg = r->max_segments;
     hipStream_t s = static_cast<hipStream_t>(hip_stream);
     const LayerDev l = layer_dev(io);
     const DiffDev d = diff_dev(in);

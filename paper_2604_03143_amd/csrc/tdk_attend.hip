@@ -155,10 +155,8 @@ __device__ __forceinline__ void tile_compute(const uint16_t* Ks, const uint16_t*
 // the LDS reads of one hide behind the products of the other, and the softmax bookkeeping (exchange with
 // the partner lane, reference point, rescale test) is paid once per 64 tokens.  Score i of a lane is token
 // 32 (i / 16) + 8 ((i % 16) / 4) + 4 hh + i % 4 of the step.
-template <int VT_STRIDE>
-__device__ __forceinline__ void tile_compute64(const uint16_t* Ks, const uint16_t* Vt, const bf16x8 (&qf)[8], float scale,
-                                               uint32_t live, int n, int hh, RowState& st) {
-  f32x16 s0, s1;
+// scores of a 64-token step for the wavefront's 32 rows: two independent MFMA chains
+__device__ __forceinline__ void scores64(const uint16_t* Ks, const bf16x8 (&qf)[8], int n, int hh, f32x16& s0, f32x16& s1) {
 #pragma unroll
   for (int i = 0; i < 16; ++i) { s0[i] = 0.f; s1[i] = 0.f; }
 #pragma unroll
@@ -168,6 +166,11 @@ __device__ __forceinline__ void tile_compute64(const uint16_t* Ks, const uint16_
     s0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a0), qf[kk], s0, 0, 0, 0);
     s1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a1), qf[kk], s1, 0, 0, 0);
   }
+}
+
+template <int VT_STRIDE>
+__device__ __forceinline__ void softmax_pv64(const uint16_t* Vt, const f32x16& s0, const f32x16& s1, float scale,
+                                             uint32_t live, int n, int hh, RowState& st) {
   float p[32];
   float mx = -INFINITY;
 #pragma unroll
@@ -210,6 +213,14 @@ __device__ __forceinline__ void tile_compute64(const uint16_t* Ks, const uint16_
   }
 }
 
+template <int VT_STRIDE>
+__device__ __forceinline__ void tile_compute64(const uint16_t* Ks, const uint16_t* Vt, const bf16x8 (&qf)[8], float scale,
+                                               uint32_t live, int n, int hh, RowState& st) {
+  f32x16 s0, s1;
+  scores64(Ks, qf, n, hh, s0, s1);
+  softmax_pv64<VT_STRIDE>(Vt, s0, s1, scale, live, n, hh, st);
+}
+
 }  // namespace
 
 // ---------------------------------------------------------------------------------------------
@@ -221,23 +232,27 @@ __global__ __launch_bounds__(kBlock) void tdk_attend_qrot_kernel(const RoundDev 
   if (row >= n_rows) return;
   const int lane = threadIdx.x & 63;
   const int agent = (int)(row / ((int64_t)at.n_q * at.n_q_heads));
-  const float* tab = rd.tab + (size_t)agent * (2 * kHalf);
   const uint16_t* src = reinterpret_cast<const uint16_t*>(at.q) + row * kHeadDim;
-  uint16_t* dst = reinterpret_cast<uint16_t*>(at.qrot) + row * kHeadDim;
   const int ia = rd.interleaved ? 2 * lane : lane;
   const int ib = rd.interleaved ? 2 * lane + 1 : lane + kHalf;
   const float xa = __uint_as_float((uint32_t)src[ia] << 16), xb = __uint_as_float((uint32_t)src[ib] << 16);
-  const float c = tab[lane], s = tab[kHalf + lane];
-  // rotation by -delta: y_a = x_a cos + x_b sin, y_b = x_b cos - x_a sin
-  const float ya = __builtin_fmaf(xa, c, __fmul_rn(xb, s));
-  const float yb = __builtin_fmaf(xb, c, -__fmul_rn(xa, s));
-  dst[ia] = (uint16_t)(pack2(ya, 0.f) & 0xffffu);
-  dst[ib] = (uint16_t)(pack2(yb, 0.f) & 0xffffu);
+  // one copy per segment of the agent's layout (one for an identity layout): every segment has its own offset
+  const int seg0 = rd.seg ? rd.seg_off[agent] : agent;
+  const int nseg = rd.seg ? rd.seg_off[agent + 1] - seg0 : 1;
+  const float* tabs = rd.seg ? rd.segtab : rd.tab;
+  for (int k = 0; k < nseg; ++k) {
+    const float* tab = tabs + (size_t)(seg0 + k) * (2 * kHalf);
+    uint16_t* dst = reinterpret_cast<uint16_t*>(at.qrot) + (row * at.max_seg + k) * kHeadDim;
+    const float c = tab[lane], s = tab[kHalf + lane];
+    // rotation by -delta: y_a = x_a cos + x_b sin, y_b = x_b cos - x_a sin
+    dst[ia] = (uint16_t)(pack2(__builtin_fmaf(xa, c, __fmul_rn(xb, s)), 0.f) & 0xffffu);
+    dst[ib] = (uint16_t)(pack2(__builtin_fmaf(xb, c, -__fmul_rn(xa, s)), 0.f) & 0xffffu);
+  }
   // the queries the listed pages meet: as they are, or turned back by the distance the stored values
-  // have moved since they were encoded
+  // have moved since they were encoded (identity layouts; segmented layouts are restored where stored)
   uint16_t* dst2 = reinterpret_cast<uint16_t*>(at.qdiff) + row * kHeadDim;
   uint16_t za = src[ia], zb = src[ib];
-  if (rd.agents[agent].diff_rot) {
+  if (!rd.seg && rd.agents[agent].diff_rot) {
     const float* td = rd.tab_diff + (size_t)agent * (2 * kHalf);
     const float c2 = td[lane], s2 = td[kHalf + lane];
     za = (uint16_t)(pack2(__builtin_fmaf(xa, c2, __fmul_rn(xb, s2)), 0.f) & 0xffffu);
@@ -251,6 +266,7 @@ __global__ __launch_bounds__(kBlock) void tdk_attend_qrot_kernel(const RoundDev 
 // master pass: S^T = K Q'^T and O^T += V^T P^T per 32-token tile, online softmax per query row
 // grid: x = session * n_chunks + chunk, y = KV head, z = block of 128 query rows
 // ---------------------------------------------------------------------------------------------
+template <bool SEG>
 __global__ __launch_bounds__(kBlock) void tdk_attend_master_kernel(const RoundDev rd, const LayerDev io, const DiffDev d,
                                                                    const AttendDev at) {
   __shared__ __attribute__((aligned(16))) uint16_t Ks[kBigTile * kKsStride];
@@ -292,10 +308,28 @@ __global__ __launch_bounds__(kBlock) void tdk_attend_master_kernel(const RoundDe
     s_mask[threadIdx.x] = mask;
   }
 
-  // this lane's query row: its B operands (8 steps of 16 along the head dimension) stay in registers
+  // this lane's query row: its B operands (8 steps of 16 along the head dimension) stay in registers.
+  // With per-agent block layouts every segment has its own copy of the row (rotated back by that
+  // segment's offset); seg_k follows the segment that holds the current token.
   const RowRef mine = row_ref(rd, sd, at, h, row_begin + wave * kRowsPerWave + n);
+  const uint16_t* q_rows = reinterpret_cast<const uint16_t*>(at.qrot) + mine.out * at.max_seg * kHeadDim;
+  auto load_q = [&](int k, bool on, bf16x8 (&f)[8]) {
+    const u32x4* qp = reinterpret_cast<const u32x4*>(q_rows + (size_t)k * kHeadDim);
+#pragma unroll
+    for (int kk = 0; kk < 8; ++kk) {
+      u32x4 v = {0, 0, 0, 0};
+      if (on) v = qp[2 * kk + hh];
+      f[kk] = __builtin_bit_cast(bf16x8, v);
+    }
+  };
   bf16x8 qf[8];
-  {
+  int seg_base = 0, seg_n = 1, seg_k = 0;
+  if (SEG && mine.agent >= 0) {
+    seg_base = rd.seg_off[mine.agent];
+    seg_n = rd.seg_off[mine.agent + 1] - seg_base;
+    while (seg_k + 1 < seg_n && rd.seg_src[seg_base + seg_k + 1] <= tok_begin) ++seg_k;
+  }
+  if (!SEG) {
     const u32x4* qp = reinterpret_cast<const u32x4*>(reinterpret_cast<const uint16_t*>(at.qrot) + mine.out * kHeadDim);
 #pragma unroll
     for (int kk = 0; kk < 8; ++kk) {
@@ -356,7 +390,37 @@ __global__ __launch_bounds__(kBlock) void tdk_attend_master_kernel(const RoundDe
           if (t0 + 32 * (i >> 4) + 8 * ((i & 15) >> 2) + 4 * hh + (i & 3) >= tok_end) live &= ~(1u << i);
       }
     }
-    tile_compute64<kBigVtStride>(Ks, Vt, qf, at.scale, live, n, hh, rs);
+    if (!SEG) {
+      tile_compute64<kBigVtStride>(Ks, Vt, qf, at.scale, live, n, hh, rs);
+    } else {
+      // The step may run over several segments of this row's agent: the scores are computed once per
+      // segment met (each with that segment's copy of the query row) and every token keeps the one of the
+      // segment it belongs to.  Rows differ in where their segments end; the loop runs while any row has one left.
+      f32x16 s0, s1;
+#pragma unroll
+      for (int i = 0; i < 16; ++i) { s0[i] = 0.f; s1[i] = 0.f; }
+      const int t_end = t0 + kBigTile;
+      bool more = mine.agent >= 0;
+      int k = seg_k;
+      while (__any(more)) {
+        load_q(k, more, qf);
+        f32x16 p0, p1;
+        scores64(Ks, qf, n, hh, p0, p1);
+        const int lo = more ? rd.seg_src[seg_base + k] : 0;
+        const int hi = more ? (k + 1 < seg_n ? rd.seg_src[seg_base + k + 1] : sd.span) : 0;
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+          const int ta = t0 + 8 * (i >> 2) + 4 * hh + (i & 3), tb2 = ta + kTile;
+          if (ta >= lo && ta < hi) s0[i] = p0[i];
+          if (tb2 >= lo && tb2 < hi) s1[i] = p1[i];
+        }
+        more = more && hi < t_end && k + 1 < seg_n;
+        if (more) ++k;
+      }
+      seg_k = k;                                  // the segment that holds the last token of this step
+      if (mine.agent >= 0 && seg_k + 1 < seg_n && rd.seg_src[seg_base + seg_k + 1] <= t_end) ++seg_k;
+      softmax_pv64<kBigVtStride>(Vt, s0, s1, at.scale, live, n, hh, rs);
+    }
   }
 
   const float l_tot = rs.l_run + __shfl_xor(rs.l_run, 32);
@@ -561,7 +625,8 @@ hipError_t launch_attend_master(const RoundDev& rd, const LayerDev& io, const Di
   if (rd.n_sessions == 0 || at.n_chunks == 0 || max_rows == 0) return hipSuccess;
   const dim3 grid((unsigned)(rd.n_sessions * at.n_chunks), (unsigned)rd.heads,
                   (unsigned)((max_rows + kRowsPerBlock - 1) / kRowsPerBlock));
-  hipLaunchKernelGGL(tdk_attend_master_kernel, grid, dim3(kBlock), 0, st, rd, io, d, at);
+  if (rd.seg) hipLaunchKernelGGL(tdk_attend_master_kernel<true>, grid, dim3(kBlock), 0, st, rd, io, d, at);
+  else hipLaunchKernelGGL(tdk_attend_master_kernel<false>, grid, dim3(kBlock), 0, st, rd, io, d, at);
   return hipGetLastError();
 }
 

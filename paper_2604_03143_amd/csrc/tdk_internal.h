@@ -57,6 +57,8 @@ struct RoundDev {
                                //  bit t: table t's run moved since the stored diff was encoded}
   const float*      segtab;    // [n tables][2][64]: cos then sin, one table per (agent, segment)
   const float*      segtab_diff;  // same indexing: dst_pos - diff_pos of the segment (payload re-rotation)
+  const int32_t*    seg_off;   // [n_agents + 1]: agent i's segments (and tables) are seg_off[i] .. seg_off[i + 1]
+  const int32_t*    seg_src;   // first master token of each segment (ascending within an agent, first is 0)
   uint8_t*          flags;   // [sum_i pages_i] scratch of encode
   int32_t n_work, n_agents, n_sessions;
   int32_t heads;             // H
@@ -109,6 +111,7 @@ struct AttendDev {
   int32_t chunk_tokens;              // master tokens per workgroup of the master pass (multiple of 32 and of T)
   int32_t n_chunks;                  // chunks of the longest span
   int32_t n_parts;                   // n_chunks + 1: the last part holds the listed pages
+  int32_t max_seg;                   // copies of every query row in qrot: one per segment of its agent's layout
   float   scale;
 };
 

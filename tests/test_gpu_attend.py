@@ -80,6 +80,47 @@ def test_more_query_rows_than_one_block_and_mirrors_stored_elsewhere(tdo):
     _case(tdo, spec, 5, 8, grow=[0, 16, 7, 250, 1, 31, 1000, 64])
 
 
+@pytest.mark.parametrize("T,style,block_tokens,n_q,Hq", [(16, 0, 40, 1, 10), (16, 1, 23, 2, 4), (32, 0, 50, 1, 2), (16, 0, 157, 3, 6)])
+def test_agents_with_their_own_block_order(tdo, T, style, block_tokens, n_q, Hq):
+    """Every agent orders the shared blocks its own way (Eq. 2): each block has its own offset per agent,
+    steps of 64 tokens run over block borders that differ from row to row; two agents keep the identity layout."""
+    import torch
+    from paper_2604_03143_amd import tdk
+    import gpu_helpers as gh
+    spec = wl.RoundSpec("att5", 65, 1, 2, 128, T, 1.0e6, 2, 6, 5, block_tokens, 3, 700, 0.25)
+    rnd = wl.permute_blocks(wl.make_round(spec), seed_tag=6)
+    rnd.segments[1] = np.zeros((0, 3), np.int64)
+    rnd.segments[8] = np.zeros((0, 3), np.int64)
+    o = OracleRun(tdo, rnd, style=style)
+    o.rerotate(); o.perturb()
+    d = o.encode()
+    g = np.random.default_rng([spec.stream, block_tokens])
+    q = wl.f32_to_bf16_bits(g.standard_normal((rnd.n_agents, n_q, Hq, 128)).astype(np.float32))
+    scale = 1.0 / np.sqrt(128.0)
+    want_o, want_l = tdo.attend_shared(o.g, o.hr, o.mk, o.mv, d, q, n_q, Hq, scale)
+    r = tdk.round_from_workload(rnd, style=style)
+    try:
+        n = int(d.offset[-1])
+        mk, mv = gh.up(o.mk), gh.up(o.mv)
+        cnt, off = torch.from_numpy(d.count).cuda(), torch.from_numpy(d.offset).cuda()
+        idx, pay = torch.from_numpy(d.idx[:max(n, 1)].copy()).cuda(), gh.up(d.payload[:max(n, 1)].copy())
+        dd = tdk.diff(cnt, off, idx, pay, n, torch.zeros(1, dtype=torch.int32, device="cuda"))
+        nbytes = tdk.tdk_attend_workspace_bytes(r, n_q, Hq)
+        ws = torch.empty(nbytes, dtype=torch.uint8, device="cuda")
+        ws.fill_(0xFF)
+        out = torch.full((rnd.n_agents, n_q, Hq, 128), float("nan"), dtype=torch.float32, device="cuda")
+        lse = torch.full((rnd.n_agents, n_q, Hq), float("nan"), dtype=torch.float32, device="cuda")
+        tdk.tdk_attend_shared(r, 0, tdk.layer_io(mk, mv, None, None, 0), dd,
+                              tdk.attend_io(gh.up(q), n_q, Hq, scale, out, lse, ws, nbytes))
+        torch.cuda.synchronize()
+        vmax = float(np.max(np.abs(wl.bf16_bits_to_f32(o.mv))))
+        err_o = float(np.max(np.abs(out.cpu().numpy() - want_o)))
+        err_l = float(np.max(np.abs(lse.cpu().numpy() - want_l)))
+        assert err_o <= OUT_TOL * max(1.0, vmax) and err_l <= LSE_TOL, (err_o, err_l)
+    finally:
+        r.destroy()
+
+
 def test_argument_errors(tdo):
     import torch
     from paper_2604_03143_amd import tdk
@@ -109,7 +150,8 @@ def test_argument_errors(tdo):
     finally:
         r.destroy()
     seg = wl.permute_blocks(wl.make_round(spec))
-    r2 = tdk.round_from_workload(seg)
+    # a segmented layout whose stored diff sits at other positions is refused
+    r2 = tdk.round_from_workload(seg, segment_diff_pos=[sg[:, 1] + 16 for sg in seg.segments])
     try:
         with pytest.raises(tdk.TdkError) as e:
             tdk.tdk_attend_shared(r2, 0, io, d.c, tdk.attend_io(q, 1, 2, 1.0, out, lse, ws, nbytes))
