@@ -260,9 +260,9 @@ typedef struct {
 size_t tdk_attend_workspace_bytes(const tdk_round* r, int32_t n_q, int32_t n_q_heads);   /* 0 on bad arguments */
 
 /* io: master_k / master_v of the layer (the pool is not touched and may be NULL); in: the mirrors'
- * paired diff as tdk_diff_encode wrote it.  Identity layouts may bring a diff stored at other positions
- * (diff_pos0); rounds with segments take every segment's own offset (one rotated copy of a query row per
- * segment) but only diffs stored at the current positions (else UNSUPPORTED).  Master values must be finite.
+ * paired diff as tdk_diff_encode wrote it.  All layouts: identity or per-agent segments (one rotated copy
+ * of a query row per segment), diffs stored at the current or at other positions (diff_pos0 / diff_pos).
+ * Master values must be finite.
  * Shaped for decode-like calls (a few query tokens per agent): every block of 128 query rows of a
  * session and KV head reads the tiles again and owns its partial results in the workspace.
  * Allocates nothing, enqueues four kernels, does not synchronise.  Errors: INVALID_ARG (NULL,

@@ -766,7 +766,7 @@ bool attend_plan(const tdk_round* r, int32_t n_q, int32_t n_q_heads, AttendPlan&
   size_t off = 0;
   auto place = [&](size_t bytes) { size_t o = off; off = align_up(off + bytes, 256); return o; };
   p.o_qrot = place((size_t)p.rows * r->max_segments * kHeadDim * 2);
-  p.o_qdiff = place((size_t)p.rows * kHeadDim * 2);
+  p.o_qdiff = place((size_t)p.rows * (r->rd.seg && r->seg_moved ? r->max_segments : 1) * kHeadDim * 2);
   p.o_part_o = place((size_t)p.rows * p.n_parts * kHeadDim * sizeof(float));
   p.o_part_m = place((size_t)p.rows * p.n_parts * sizeof(float));
   p.o_part_l = place((size_t)p.rows * p.n_parts * sizeof(float));
@@ -790,8 +790,6 @@ tdk_status tdk_attend_shared(tdk_round* r, int32_t layer, const tdk_layer_io* io
     int dev = -1;
     if (hipGetDevice(&dev) != hipSuccess || dev != r->device)
       return fail(TDK_ERR_INVALID_ARG, "the round was created on another device than the current one");
-    if (r->rd.seg && r->seg_moved)
-      return fail(TDK_ERR_UNSUPPORTED, "attention over per-agent block layouts takes diffs stored at the current positions only");
     tdk_status st = check_diff(r, in, false);
     if (st != TDK_OK) return st;
     AttendPlan p;
@@ -825,6 +823,7 @@ tdk_status tdk_attend_shared(tdk_round* r, int32_t layer, const tdk_layer_io* io
     at.n_parts = p.n_parts;
     at.scale = a->scale;
     at.max_seg = r->max_segments;
+    at.diff_seg = r->rd.seg && r->seg_moved ? r->max_segments : 1;
     hipStream_t s = static_cast<hipStream_t>(hip_stream);
     const LayerDev l = layer_dev(io);
     const DiffDev d = diff_dev(in);

@@ -96,10 +96,7 @@ __device__ __forceinline__ void wave_sync() {
 //   scores of tokens 8 (i / 4) + 4 hh + i % 4; bit i of `live` says whether that token takes part.
 //   O^T (d x rows) += V^T (d x tokens) * P^T (tokens x rows), contracting over the tokens in the order
 //   the lane holds them, so the weights need no exchange between lanes.
-template <int VT_STRIDE>
-__device__ __forceinline__ void tile_compute(const uint16_t* Ks, const uint16_t* Vt, const bf16x8 (&qf)[8], float scale,
-                                             uint32_t live, int n, int hh, RowState& st) {
-  f32x16 sacc;
+__device__ __forceinline__ void scores32(const uint16_t* Ks, const bf16x8 (&qf)[8], int n, int hh, f32x16& sacc) {
 #pragma unroll
   for (int i = 0; i < 16; ++i) sacc[i] = 0.f;
 #pragma unroll
@@ -107,6 +104,11 @@ __device__ __forceinline__ void tile_compute(const uint16_t* Ks, const uint16_t*
     const u32x4 a = *reinterpret_cast<const u32x4*>(Ks + n * kKsStride + 16 * kk + 8 * hh);
     sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a), qf[kk], sacc, 0, 0, 0);
   }
+}
+
+template <int VT_STRIDE>
+__device__ __forceinline__ void softmax_pv32(const uint16_t* Vt, const f32x16& sacc, float scale, uint32_t live, int n, int hh,
+                                             RowState& st) {
   float p[16];
   float mx = -INFINITY;
 #pragma unroll
@@ -149,6 +151,14 @@ __device__ __forceinline__ void tile_compute(const uint16_t* Ks, const uint16_t*
       st.oacc[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a), pb, st.oacc[b], 0, 0, 0);
     }
   }
+}
+
+template <int VT_STRIDE>
+__device__ __forceinline__ void tile_compute(const uint16_t* Ks, const uint16_t* Vt, const bf16x8 (&qf)[8], float scale,
+                                             uint32_t live, int n, int hh, RowState& st) {
+  f32x16 sacc;
+  scores32(Ks, qf, n, hh, sacc);
+  softmax_pv32<VT_STRIDE>(Vt, sacc, scale, live, n, hh, st);
 }
 
 // The same for a 64-token step held in LDS (two independent score tiles): their MFMA chains interleave,
@@ -249,17 +259,24 @@ __global__ __launch_bounds__(kBlock) void tdk_attend_qrot_kernel(const RoundDev 
     dst[ib] = (uint16_t)(pack2(__builtin_fmaf(xb, c, -__fmul_rn(xa, s)), 0.f) & 0xffffu);
   }
   // the queries the listed pages meet: as they are, or turned back by the distance the stored values
-  // have moved since they were encoded (identity layouts; segmented layouts are restored where stored)
-  uint16_t* dst2 = reinterpret_cast<uint16_t*>(at.qdiff) + row * kHeadDim;
-  uint16_t za = src[ia], zb = src[ib];
-  if (!rd.seg && rd.agents[agent].diff_rot) {
-    const float* td = rd.tab_diff + (size_t)agent * (2 * kHalf);
-    const float c2 = td[lane], s2 = td[kHalf + lane];
-    za = (uint16_t)(pack2(__builtin_fmaf(xa, c2, __fmul_rn(xb, s2)), 0.f) & 0xffffu);
-    zb = (uint16_t)(pack2(__builtin_fmaf(xb, c2, -__fmul_rn(xa, s2)), 0.f) & 0xffffu);
+  // have moved since they were encoded
+  // (a segmented round whose stored diffs moved keeps one such copy per segment: diff_seg copies per row)
+  for (int k = 0; k < (at.diff_seg > 1 ? nseg : 1); ++k) {
+    uint16_t* dst2 = reinterpret_cast<uint16_t*>(at.qdiff) + (row * at.diff_seg + k) * kHeadDim;
+    uint16_t za = src[ia], zb = src[ib];
+    const float* td = nullptr;
+    if (!rd.seg && rd.agents[agent].diff_rot) td = rd.tab_diff + (size_t)agent * (2 * kHalf);
+    if (rd.seg && at.diff_seg > 1) td = rd.segtab_diff + (size_t)(seg0 + k) * (2 * kHalf);   // identity tables copy exactly
+    if (td) {
+      const float c2 = td[lane], s2 = td[kHalf + lane];
+      if (c2 != 1.f || s2 != 0.f || !rd.seg) {
+        za = (uint16_t)(pack2(__builtin_fmaf(xa, c2, __fmul_rn(xb, s2)), 0.f) & 0xffffu);
+        zb = (uint16_t)(pack2(__builtin_fmaf(xb, c2, -__fmul_rn(xa, s2)), 0.f) & 0xffffu);
+      }
+    }
+    dst2[ia] = za;
+    dst2[ib] = zb;
   }
-  dst2[ia] = za;
-  dst2[ib] = zb;
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -443,6 +460,7 @@ __global__ __launch_bounds__(kBlock) void tdk_attend_master_kernel(const RoundDe
 // ---------------------------------------------------------------------------------------------
 constexpr int kWaveLds = kTile * kKsStride + kHeadDim * kVtStride;      // bf16 elements of one wavefront's staging area
 
+template <bool SEGMOVED>
 __global__ __launch_bounds__(kBlock) void tdk_attend_diff_kernel(const RoundDev rd, const DiffDev d, const AttendDev at) {
   // staging areas during the token loop, then (reused) the four wavefronts' results: [4][32 rows][128 + 2] floats
   __shared__ __attribute__((aligned(16))) uint16_t lds[kWaves * kWaveLds];
@@ -471,15 +489,20 @@ __global__ __launch_bounds__(kBlock) void tdk_attend_diff_kernel(const RoundDev 
     const int qi = row_ok ? rem / at.group : 0, g = row_ok ? rem - qi * at.group : 0;
     const int64_t out = ((int64_t)agent * at.n_q + qi) * at.n_q_heads + h * at.group + g;
     bf16x8 qf[8];
-    {
-      const u32x4* qp = reinterpret_cast<const u32x4*>(reinterpret_cast<const uint16_t*>(at.qdiff) + out * kHeadDim);
+    auto load_q = [&](int k) {
+      const u32x4* qp = reinterpret_cast<const u32x4*>(reinterpret_cast<const uint16_t*>(at.qdiff) +
+                                                         (out * at.diff_seg + k) * kHeadDim);
 #pragma unroll
       for (int kk = 0; kk < 8; ++kk) {
         u32x4 v = {0, 0, 0, 0};
         if (row_ok) v = qp[2 * kk + hh];
         qf[kk] = __builtin_bit_cast(bf16x8, v);
       }
-    }
+    };
+    if (!SEGMOVED) load_q(0);
+    const int seg_base = SEGMOVED ? rd.seg_off[agent] : 0;
+    const int seg_n = SEGMOVED ? rd.seg_off[agent + 1] - seg_base : 1;
+    int seg_next = 0;                            // segment of the token this lane fetched (SEGMOVED only)
     RowState rs;
     row_state_init(rs);
     // a wavefront's next tile travels from the payload to registers while its current one is multiplied:
@@ -498,6 +521,10 @@ __global__ __launch_bounds__(kBlock) void tdk_attend_diff_kernel(const RoundDev 
         const int rr = t % T, p = d.idx[slot];
         if (p >= 0 && p < sd.pages && p * T + rr < sd.span) {
           ok = true;
+          if (SEGMOVED) {
+            seg_next = 0;
+            while (seg_next + 1 < seg_n && rd.seg_src[seg_base + seg_next + 1] <= p * T + rr) ++seg_next;
+          }
           const u32x4* kr = reinterpret_cast<const u32x4*>(pay + (slot * 2) * page_e + rr * row_e + h * kHeadDim) + st_pg * 8;
           const u32x4* vr = reinterpret_cast<const u32x4*>(pay + (slot * 2 + 1) * page_e + rr * row_e + h * kHeadDim) + st_pg * 8;
 #pragma unroll
@@ -511,6 +538,7 @@ __global__ __launch_bounds__(kBlock) void tdk_attend_diff_kernel(const RoundDev 
       const int tile = it * kWaves + wave;
       wave_sync();                               // this wavefront's previous tile has been consumed
       uint32_t valid = valid_next;
+      const int seg_cur = seg_next;
       if (tile < n_tiles) {
 #pragma unroll
         for (int j = 0; j < 4; ++j) stage_rows<kVtStride>(Ks, Vt, st_tok, 4 * st_pg + j, kv[j][0], kv[j][1], kv[j][2], kv[j][3]);
@@ -522,7 +550,34 @@ __global__ __launch_bounds__(kBlock) void tdk_attend_diff_kernel(const RoundDev 
         const uint32_t vs = valid >> (4 * hh);
         uint32_t live = (vs & 0xfu) | ((vs >> 4) & 0xf0u) | ((vs >> 8) & 0xf00u) | ((vs >> 12) & 0xf000u);
         if (!row_ok) live = 0;
-        tile_compute<kVtStride>(Ks, Vt, qf, at.scale, live, n, hh, rs);
+        if (!SEGMOVED) {
+          tile_compute<kVtStride>(Ks, Vt, qf, at.scale, live, n, hh, rs);
+        } else {
+          // the tile's tokens come from up to four segments (two pages, two segments each), stored at
+          // different distances from today's positions: the scores are computed once per segment present,
+          // with the queries turned back by that segment's distance, and every token keeps its own
+          int sid[16];
+#pragma unroll
+          for (int i = 0; i < 16; ++i) sid[i] = __shfl(seg_cur, 8 * (i >> 2) + 4 * hh + (i & 3));
+          f32x16 sacc;
+#pragma unroll
+          for (int i = 0; i < 16; ++i) sacc[i] = 0.f;
+          int done = -1;
+          while (true) {
+            int cand = (lane < kTile && ((valid >> lane) & 1u) && seg_cur > done) ? seg_cur : 0x7fffffff;
+#pragma unroll
+            for (int sft = 32; sft > 0; sft >>= 1) cand = min(cand, __shfl_xor(cand, sft));
+            if (cand == 0x7fffffff) break;
+            load_q(cand);
+            f32x16 pacc;
+            scores32(Ks, qf, n, hh, pacc);
+#pragma unroll
+            for (int i = 0; i < 16; ++i)
+              if (sid[i] == cand) sacc[i] = pacc[i];
+            done = cand;
+          }
+          softmax_pv32<kVtStride>(Vt, sacc, at.scale, live, n, hh, rs);
+        }
       }
     }
     // combine the four wavefronts (the staging areas are free now)
@@ -633,7 +688,8 @@ hipError_t launch_attend_master(const RoundDev& rd, const LayerDev& io, const Di
 hipError_t launch_attend_diff(const RoundDev& rd, const DiffDev& d, const AttendDev& at, hipStream_t st) {
   if (rd.n_agents == 0) return hipSuccess;
   const dim3 grid((unsigned)rd.n_agents, (unsigned)rd.heads);
-  hipLaunchKernelGGL(tdk_attend_diff_kernel, grid, dim3(kBlock), 0, st, rd, d, at);
+  if (at.diff_seg > 1) hipLaunchKernelGGL(tdk_attend_diff_kernel<true>, grid, dim3(kBlock), 0, st, rd, d, at);
+  else hipLaunchKernelGGL(tdk_attend_diff_kernel<false>, grid, dim3(kBlock), 0, st, rd, d, at);
   return hipGetLastError();
 }
 

@@ -112,6 +112,8 @@ struct AttendDev {
   int32_t n_chunks;                  // chunks of the longest span
   int32_t n_parts;                   // n_chunks + 1: the last part holds the listed pages
   int32_t max_seg;                   // copies of every query row in qrot: one per segment of its agent's layout
+  int32_t diff_seg;                  // copies of every query row in qdiff: max_seg if a segmented round's stored
+                                     // diffs sit at other positions (each segment moved by its own distance), else 1
   float   scale;
 };
 
