@@ -231,6 +231,81 @@ __device__ __forceinline__ void tile_compute64(const uint16_t* Ks, const uint16_
   softmax_pv64<VT_STRIDE>(Vt, s0, s1, scale, live, n, hh, st);
 }
 
+// ---- the same tile for 16 query rows per wavefront (v_mfma_f32_16x16x32_bf16): for passes whose row
+// blocks are nearly empty (the listed pages of one agent meet only its own few rows), a quarter of the
+// scores per lane.  Lane (n, g) = (lane % 16, lane / 16) owns row n; of a 32-token tile it holds the scores
+// of tokens 16 tt + 4 g + i (tt = 0, 1; i = 0..3) as p[4 tt + i], and elements 16 b + 4 g + i of the output.
+typedef float f32x4a __attribute__((ext_vector_type(4)));
+
+struct RowState16 {
+  float m_run, l_run;
+  f32x4a oacc[8];
+};
+
+__device__ __forceinline__ void row_state16_init(RowState16& st) {
+  st.m_run = -INFINITY;
+  st.l_run = 0.f;
+#pragma unroll
+  for (int b = 0; b < 8; ++b)
+#pragma unroll
+    for (int i = 0; i < 4; ++i) st.oacc[b][i] = 0.f;
+}
+
+__device__ __forceinline__ void scores16(const uint16_t* Ks, const bf16x8 (&qf)[4], int n, int g, f32x4a& s0, f32x4a& s1) {
+#pragma unroll
+  for (int i = 0; i < 4; ++i) { s0[i] = 0.f; s1[i] = 0.f; }
+#pragma unroll
+  for (int kk = 0; kk < 4; ++kk) {
+    const u32x4 a0 = *reinterpret_cast<const u32x4*>(Ks + n * kKsStride + 32 * kk + 8 * g);
+    const u32x4 a1 = *reinterpret_cast<const u32x4*>(Ks + (16 + n) * kKsStride + 32 * kk + 8 * g);
+    s0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a0), qf[kk], s0, 0, 0, 0);
+    s1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a1), qf[kk], s1, 0, 0, 0);
+  }
+}
+
+template <int VT_STRIDE>
+__device__ __forceinline__ void softmax_pv16(const uint16_t* Vt, const f32x4a& s0, const f32x4a& s1, float scale, uint32_t live,
+                                             int n, int g, RowState16& st) {
+  float p[8];
+  float mx = -INFINITY;
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    p[i] = ((live >> i) & 1u) ? s0[i] * scale : -INFINITY;
+    p[4 + i] = ((live >> (4 + i)) & 1u) ? s1[i] * scale : -INFINITY;
+    mx = fmaxf(mx, fmaxf(p[i], p[4 + i]));
+  }
+  mx = fmaxf(mx, __shfl_xor(mx, 16));
+  mx = fmaxf(mx, __shfl_xor(mx, 32));
+  constexpr float kLazy = 8.f;
+  const float m_new = mx > st.m_run + kLazy || st.m_run == -INFINITY ? fmaxf(st.m_run, mx) : st.m_run;
+  const float m_ref = m_new == -INFINITY ? 0.f : m_new;
+  float sum = 0.f;
+#pragma unroll
+  for (int i = 0; i < 8; ++i) { p[i] = __expf(p[i] - m_ref); sum += p[i]; }
+  if (__any(m_new != st.m_run)) {
+    const float alpha = __expf(st.m_run - m_ref);
+    st.l_run *= alpha;
+#pragma unroll
+    for (int b = 0; b < 8; ++b)
+#pragma unroll
+      for (int i = 0; i < 4; ++i) st.oacc[b][i] *= alpha;
+  }
+  st.l_run += sum;
+  st.m_run = m_new;
+  u32x4 pw;
+#pragma unroll
+  for (int e = 0; e < 4; ++e) pw[e] = pack2(p[2 * e], p[2 * e + 1]);
+  const bf16x8 pb = __builtin_bit_cast(bf16x8, pw);
+#pragma unroll
+  for (int b = 0; b < 8; ++b) {
+    const uint16_t* vr = Vt + (16 * b + n) * VT_STRIDE + 4 * g;
+    const uint2 lo = *reinterpret_cast<const uint2*>(vr);
+    const uint2 hi = *reinterpret_cast<const uint2*>(vr + 16);
+    const u32x4 a = {lo.x, lo.y, hi.x, hi.y};
+    st.oacc[b] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a), pb, st.oacc[b], 0, 0, 0);
+  }
+}
+
 }  // namespace
 
 // ---------------------------------------------------------------------------------------------
@@ -619,6 +694,169 @@ __global__ __launch_bounds__(kBlock) void tdk_attend_diff_kernel(const RoundDev 
   }
 }
 
+// The same pass with 16 query rows per wavefront: used when an agent brings at most 16 rows per KV head
+// (decode: query tokens x heads per KV head), where the 32-row tiles would be five sixths padding.
+template <bool SEGMOVED>
+__global__ __launch_bounds__(kBlock) void tdk_attend_diff16_kernel(const RoundDev rd, const DiffDev d, const AttendDev at) {
+  // staging areas during the token loop, then (reused) the four wavefronts' results: [4][32 rows][128 + 2] floats
+  __shared__ __attribute__((aligned(16))) uint16_t lds[kWaves * kWaveLds];
+  constexpr int kRows = 16;                    // query rows per wavefront
+
+  const int agent = blockIdx.x, h = blockIdx.y;
+  const int per_agent = at.n_q * at.group;
+  const AgentDev ad = rd.agents[agent];
+  const SessionDev sd = rd.sess[ad.session];
+  const int T = rd.page_tokens;
+  int64_t lo = d.offset[agent], hi = lo + d.count[agent];
+  if (lo < 0) lo = 0;
+  if (hi > d.capacity) hi = d.capacity;
+  const int n_tok = hi > lo ? (int)((hi - lo) * T) : 0;
+  const int n_tiles = (n_tok + kTile - 1) / kTile;
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, n = lane & 15, g4 = lane >> 4;
+  uint16_t* Ks = lds + wave * kWaveLds;
+  uint16_t* Vt = Ks + kTile * kKsStride;
+  const int64_t row_e = (int64_t)rd.heads * kHeadDim, page_e = (int64_t)T * row_e;
+  const uint16_t* pay = reinterpret_cast<const uint16_t*>(d.payload);
+
+  for (int r0 = 0; r0 < per_agent; r0 += kRows) {
+    // this lane's query row of the block
+    const int rem = r0 + n;
+    const bool row_ok = rem < per_agent;
+    const int qi = row_ok ? rem / at.group : 0, g = row_ok ? rem - qi * at.group : 0;
+    const int64_t out = ((int64_t)agent * at.n_q + qi) * at.n_q_heads + h * at.group + g;
+    bf16x8 qf[4];
+    auto load_q = [&](int k) {
+      const u32x4* qp = reinterpret_cast<const u32x4*>(reinterpret_cast<const uint16_t*>(at.qdiff) +
+                                                         (out * at.diff_seg + k) * kHeadDim);
+#pragma unroll
+      for (int kk = 0; kk < 4; ++kk) {
+        u32x4 v = {0, 0, 0, 0};
+        if (row_ok) v = qp[4 * kk + g4];
+        qf[kk] = __builtin_bit_cast(bf16x8, v);
+      }
+    };
+    if (!SEGMOVED) load_q(0);
+    const int seg_base = SEGMOVED ? rd.seg_off[agent] : 0;
+    const int seg_n = SEGMOVED ? rd.seg_off[agent + 1] - seg_base : 1;
+    int seg_next = 0;                            // segment of the token this lane fetched (SEGMOVED only)
+    RowState16 rs;
+    row_state16_init(rs);
+    // a wavefront's next tile travels from the payload to registers while its current one is multiplied:
+    // 32 tokens x 8 parts of 32 bytes, four (token, part) pairs per lane
+    u32x4 kv[4][4];
+    uint32_t valid_next = 0;                     // bit t: token t of the fetched tile exists and lies inside the span
+    const int st_tok = lane & 31, st_pg = lane >> 5;      // this lane stages parts 4 st_pg .. 4 st_pg + 3 of one token
+    auto fetch = [&](int tile) {
+      const int t = tile * kTile + st_tok;
+      const u32x4 z = {0, 0, 0, 0};
+#pragma unroll
+      for (int j = 0; j < 4; ++j) { kv[j][0] = z; kv[j][1] = z; kv[j][2] = z; kv[j][3] = z; }
+      bool ok = false;
+      if (tile < n_tiles && t < n_tok) {
+        const int64_t slot = lo + t / T;
+        const int rr = t % T, p = d.idx[slot];
+        if (p >= 0 && p < sd.pages && p * T + rr < sd.span) {
+          ok = true;
+          if (SEGMOVED) {
+            seg_next = 0;
+            while (seg_next + 1 < seg_n && rd.seg_src[seg_base + seg_next + 1] <= p * T + rr) ++seg_next;
+          }
+          const u32x4* kr = reinterpret_cast<const u32x4*>(pay + (slot * 2) * page_e + rr * row_e + h * kHeadDim) + st_pg * 8;
+          const u32x4* vr = reinterpret_cast<const u32x4*>(pay + (slot * 2 + 1) * page_e + rr * row_e + h * kHeadDim) + st_pg * 8;
+#pragma unroll
+          for (int j = 0; j < 4; ++j) { kv[j][0] = kr[2 * j]; kv[j][1] = kr[2 * j + 1]; kv[j][2] = vr[2 * j]; kv[j][3] = vr[2 * j + 1]; }
+        }
+      }
+      valid_next = (uint32_t)__ballot(ok);       // lanes 0..31 carry the tokens (lanes 32..63 repeat them)
+    };
+    fetch(wave);
+    for (int it = 0; it * kWaves < n_tiles; ++it) {
+      const int tile = it * kWaves + wave;
+      wave_sync();                               // this wavefront's previous tile has been consumed
+      uint32_t valid = valid_next;
+      const int seg_cur = seg_next;
+      if (tile < n_tiles) {
+#pragma unroll
+        for (int j = 0; j < 4; ++j) stage_rows<kVtStride>(Ks, Vt, st_tok, 4 * st_pg + j, kv[j][0], kv[j][1], kv[j][2], kv[j][3]);
+      }
+      wave_sync();                               // the staging area belongs to this wavefront alone
+      if ((it + 1) * kWaves < n_tiles) fetch(tile + kWaves);
+      if (tile < n_tiles) {
+        // scores 0..3 of a lane belong to tokens 4 g + i, scores 4..7 to tokens 16 + 4 g + i
+        const uint32_t vs = valid >> (4 * g4);
+        uint32_t live = (vs & 0xfu) | ((vs >> 12) & 0xf0u);
+        if (!row_ok) live = 0;
+        f32x4a s0, s1;
+        if (!SEGMOVED) {
+          scores16(Ks, qf, n, g4, s0, s1);
+        } else {
+          // the tile's tokens come from up to four segments stored at different distances from today's
+          // positions: scores once per segment present, with the queries turned back by that distance
+          int sid[8];
+#pragma unroll
+          for (int i = 0; i < 4; ++i) { sid[i] = __shfl(seg_cur, 4 * g4 + i); sid[4 + i] = __shfl(seg_cur, 16 + 4 * g4 + i); }
+#pragma unroll
+          for (int i = 0; i < 4; ++i) { s0[i] = 0.f; s1[i] = 0.f; }
+          int done = -1;
+          while (true) {
+            int cand = (lane < kTile && ((valid >> lane) & 1u) && seg_cur > done) ? seg_cur : 0x7fffffff;
+#pragma unroll
+            for (int sft = 32; sft > 0; sft >>= 1) cand = min(cand, __shfl_xor(cand, sft));
+            if (cand == 0x7fffffff) break;
+            load_q(cand);
+            f32x4a p0, p1;
+            scores16(Ks, qf, n, g4, p0, p1);
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+              if (sid[i] == cand) s0[i] = p0[i];
+              if (sid[4 + i] == cand) s1[i] = p1[i];
+            }
+            done = cand;
+          }
+        }
+        softmax_pv16<kVtStride>(Vt, s0, s1, at.scale, live, n, g4, rs);
+      }
+    }
+    // combine the four wavefronts (the staging areas are free now)
+    __syncthreads();
+    float* res = reinterpret_cast<float*>(lds);                          // [4][16][130]: 128 outputs, m, l
+    {
+      float* mine = res + ((size_t)wave * kRows + n) * (kHeadDim + 2);
+#pragma unroll
+      for (int b = 0; b < 8; ++b)
+#pragma unroll
+        for (int i = 0; i < 4; ++i) mine[16 * b + 4 * g4 + i] = rs.oacc[b][i];
+      float l_tot = rs.l_run + __shfl_xor(rs.l_run, 16);
+      l_tot += __shfl_xor(l_tot, 32);
+      if (g4 == 0) { mine[kHeadDim] = rs.m_run; mine[kHeadDim + 1] = l_tot; }
+    }
+    __syncthreads();
+    for (int e = threadIdx.x; e < kRows * kHeadDim; e += kBlock) {
+      const int row = e >> 7, dd = e & (kHeadDim - 1);
+      const int rem2 = r0 + row;
+      if (rem2 >= per_agent) continue;
+      float M = -INFINITY;
+#pragma unroll
+      for (int w = 0; w < kWaves; ++w) M = fmaxf(M, res[((size_t)w * kRows + row) * (kHeadDim + 2) + kHeadDim]);
+      const float m_ref = M == -INFINITY ? 0.f : M;
+      float o = 0.f, l = 0.f;
+#pragma unroll
+      for (int w = 0; w < kWaves; ++w) {
+        const float* rw = res + ((size_t)w * kRows + row) * (kHeadDim + 2);
+        const float wgt = __expf(rw[kHeadDim] - m_ref);
+        o = __builtin_fmaf(rw[dd], wgt, o);
+        l = __builtin_fmaf(rw[kHeadDim + 1], wgt, l);
+      }
+      const int qi2 = rem2 / at.group, g2 = rem2 - qi2 * at.group;
+      const int64_t out2 = ((int64_t)agent * at.n_q + qi2) * at.n_q_heads + h * at.group + g2;
+      const int64_t slot = out2 * at.n_parts + (at.n_parts - 1);
+      at.part_o[slot * kHeadDim + dd] = o;
+      if (dd == 0) { at.part_m[slot] = M; at.part_l[slot] = l; }
+    }
+    __syncthreads();
+  }
+}
+
 // ---------------------------------------------------------------------------------------------
 // merge: out = sum_c o_c e^(m_c - M) / sum_c l_c e^(m_c - M), lse = M + log(that sum); one wavefront per row
 // ---------------------------------------------------------------------------------------------
@@ -688,8 +926,14 @@ hipError_t launch_attend_master(const RoundDev& rd, const LayerDev& io, const Di
 hipError_t launch_attend_diff(const RoundDev& rd, const DiffDev& d, const AttendDev& at, hipStream_t st) {
   if (rd.n_agents == 0) return hipSuccess;
   const dim3 grid((unsigned)rd.n_agents, (unsigned)rd.heads);
-  if (at.diff_seg > 1) hipLaunchKernelGGL(tdk_attend_diff_kernel<true>, grid, dim3(kBlock), 0, st, rd, d, at);
-  else hipLaunchKernelGGL(tdk_attend_diff_kernel<false>, grid, dim3(kBlock), 0, st, rd, d, at);
+  const bool few_rows = at.n_q * at.group <= 16;
+  if (few_rows) {
+    if (at.diff_seg > 1) hipLaunchKernelGGL(tdk_attend_diff16_kernel<true>, grid, dim3(kBlock), 0, st, rd, d, at);
+    else hipLaunchKernelGGL(tdk_attend_diff16_kernel<false>, grid, dim3(kBlock), 0, st, rd, d, at);
+  } else {
+    if (at.diff_seg > 1) hipLaunchKernelGGL(tdk_attend_diff_kernel<true>, grid, dim3(kBlock), 0, st, rd, d, at);
+    else hipLaunchKernelGGL(tdk_attend_diff_kernel<false>, grid, dim3(kBlock), 0, st, rd, d, at);
+  }
   return hipGetLastError();
 }
 

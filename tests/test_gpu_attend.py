@@ -121,8 +121,8 @@ def test_agents_with_their_own_block_order(tdo, T, style, block_tokens, n_q, Hq)
         r.destroy()
 
 
-@pytest.mark.parametrize("T,style,block_tokens", [(16, 0, 40), (16, 1, 23), (32, 0, 50)])
-def test_own_block_order_and_mirrors_stored_under_another_order(tdo, T, style, block_tokens):
+@pytest.mark.parametrize("T,style,block_tokens,n_q", [(16, 0, 40, 2), (16, 1, 23, 2), (32, 0, 50, 2), (16, 0, 40, 6)])
+def test_own_block_order_and_mirrors_stored_under_another_order(tdo, T, style, block_tokens, n_q):
     """The mirrors were stored in an earlier round, under another block order and shorter histories: every
     block of a listed page meets the queries turned back by its own distance; one agent did not move at all."""
     import torch
@@ -139,7 +139,7 @@ def test_own_block_order_and_mirrors_stored_under_another_order(tdo, T, style, b
     new.segments[5] = np.zeros((0, 3), np.int64)
     new.segments[0] = old.segments[0].copy()
     seg_diff = [sg[:, 1] if len(sg) else np.zeros(0, np.int64) for sg in old.segments]
-    n_q, Hq, scale = 2, 6, 1.0 / np.sqrt(128.0)
+    Hq, scale = 6, 1.0 / np.sqrt(128.0)            # 3 query heads per KV head: 6 or 18 rows per agent and KV head
     g = np.random.default_rng([spec.stream, T, block_tokens])
     q = wl.f32_to_bf16_bits(g.standard_normal((new.n_agents, n_q, Hq, 128)).astype(np.float32))
     hr = tdo.HostRound(new, diff_pos0=old.agent_pos0, segment_diff_pos=seg_diff)
