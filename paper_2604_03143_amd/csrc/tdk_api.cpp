@@ -58,6 +58,7 @@ struct EventPair {
 struct tdk_round {
   tdk_model model{};
   int device = -1;
+  int32_t n_cus = 256;             // compute units of that device
   std::vector<HostSession> sessions;
   int32_t n_agents = 0;
   int64_t max_phys_page = -1;      // largest page number any shared span maps to
@@ -533,6 +534,10 @@ tdk_status round_create(const tdk_model* model, const tdk_session* sessions, int
 
   hipError_t e = hipGetDevice(&r->device);
   if (e != hipSuccess) { return hip_fail(e, "hipGetDevice"); }
+  {
+    int cus = 0;
+    if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, r->device) == hipSuccess && cus > 0) r->n_cus = cus;
+  }
   e = hipMalloc(&r->blob, r->blob_bytes);
   if (e != hipSuccess) { return e == hipErrorOutOfMemory ? fail(TDK_ERR_NOMEM, "device allocation failed") : hip_fail(e, "hipMalloc"); }
   char* base = static_cast<char*>(r->blob);
@@ -748,17 +753,24 @@ bool attend_plan(const tdk_round* r, int32_t n_q, int32_t n_q_heads, AttendPlan&
   if (max_rows >= (int64_t)1 << 30) return false;
   p.max_rows = (int32_t)max_rows;
   p.rows = (int64_t)r->n_agents * n_q * n_q_heads;
-  // the largest chunk (fewest partial results) that still gives the chip about two workgroups per CU;
-  // a chunk covers at most 32 pages (one mask word per query row)
+  // Tokens per workgroup of the master pass.  A workgroup walks its chunk in steps of 64 tokens; two
+  // workgroups fit a compute unit at a time, so the pass takes about ceil(workgroups / slots) rounds of
+  // (steps per chunk + a fixed start-up cost of about two steps).  Of the chunk sizes that a 64-bit page
+  // mask per query row can cover, the one with the lowest such cost wins; ties go to the larger chunk
+  // (fewer partial results to merge).
   const int64_t row_blocks = std::max<int64_t>(1, (max_rows + 127) / 128);
+  const int64_t slots = 2 * (int64_t)r->n_cus;
+  const int32_t max_chunk = std::min<int32_t>(64 * r->model.page_tokens, 2048);
   int32_t chunk = 64;
-  for (int32_t c : {512, 256, 128, 64}) {
-    if (c / r->model.page_tokens > 32 || c % r->model.page_tokens) continue;
+  int64_t best = -1;
+  for (int32_t c = max_chunk; c >= 64; c -= 64) {
     int64_t wgs = 0;
     for (const auto& hs : r->sessions)
       if (!hs.agents.empty()) wgs += ((int64_t)hs.span + c - 1) / c;
-    chunk = c;
-    if (wgs * r->model.num_kv_heads * row_blocks >= 512) break;
+    wgs *= r->model.num_kv_heads * row_blocks;
+    if (wgs == 0) break;
+    const int64_t cost = ((wgs + slots - 1) / slots) * (std::min<int64_t>(c, max_span + 63) / 64 + 2);
+    if (best < 0 || cost < best) { best = cost; chunk = c; }
   }
   p.chunk_tokens = chunk;
   p.n_chunks = (int32_t)((max_span + chunk - 1) / chunk);
@@ -821,7 +833,10 @@ tdk_status tdk_attend_shared(tdk_round* r, int32_t layer, const tdk_layer_io* io
     at.chunk_tokens = p.chunk_tokens;
     at.n_chunks = p.n_chunks;
     at.n_parts = p.n_parts;
-    at.scale = a->scale;
+    // the kernels take a positive scale: the sign travels with the query copies, and a zero scale (uniform
+    // weights) becomes one so small that every scaled score rounds to zero
+    at.scale = std::fmax(std::fabs(a->scale), 1e-30f);
+    at.q_flip = std::signbit(a->scale) ? 1 : 0;
     at.max_seg = r->max_segments;
     at.diff_seg = r->rd.seg && r->seg_moved ? r->max_segments : 1;
     hipStream_t s = static_cast<hipStream_t>(hip_stream);

@@ -12,6 +12,8 @@
 // last kernel merges the partial results with their log-sum-exp weights.
 #include "tdk_internal.h"
 
+#include <type_traits>
+
 namespace tdk {
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
@@ -27,7 +29,8 @@ constexpr int kRowsPerBlock = kRowsPerWave * kWaves;
 constexpr int kKsStride = kHeadDim + 8;   // bf16 elements per staged K row (+16 bytes: spreads LDS banks)
 constexpr int kVtStride = kTile + 4;      // bf16 elements per staged V^T row
 constexpr int kBigTile = 2 * kTile;       // tokens per step of the master pass
-constexpr int kBigVtStride = kBigTile + 4;
+constexpr int kVsStride = kHeadDim + 16;  // bf16 elements per staged V row (+32 bytes: four consecutive rows' 32-byte
+                                          // pieces then fall into different LDS banks for the transposing reads)
 
 __device__ __forceinline__ uint32_t pack2(float a, float b) {
   f32x2a v = {a, b};
@@ -166,21 +169,74 @@ __device__ __forceinline__ void tile_compute(const uint16_t* Ks, const uint16_t*
 // the partner lane, reference point, rescale test) is paid once per 64 tokens.  Score i of a lane is token
 // 32 (i / 16) + 8 ((i % 16) / 4) + 4 hh + i % 4 of the step.
 // scores of a 64-token step for the wavefront's 32 rows: two independent MFMA chains
+template <bool AHEAD>
 __device__ __forceinline__ void scores64(const uint16_t* Ks, const bf16x8 (&qf)[8], int n, int hh, f32x16& s0, f32x16& s1) {
 #pragma unroll
   for (int i = 0; i < 16; ++i) { s0[i] = 0.f; s1[i] = 0.f; }
+  if (!AHEAD) {                                             // the form that needs few registers
+#pragma unroll
+    for (int kk = 0; kk < 8; ++kk) {
+      const u32x4 a0 = *reinterpret_cast<const u32x4*>(Ks + n * kKsStride + 16 * kk + 8 * hh);
+      const u32x4 a1 = *reinterpret_cast<const u32x4*>(Ks + (kTile + n) * kKsStride + 16 * kk + 8 * hh);
+      s0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a0), qf[kk], s0, 0, 0, 0);
+      s1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a1), qf[kk], s1, 0, 0, 0);
+    }
+    return;
+  }
+  // all sixteen A operands are requested before the first product: the LDS round trips overlap instead of
+  // each pair of products waiting for its own
+  u32x4 a[16];
 #pragma unroll
   for (int kk = 0; kk < 8; ++kk) {
-    const u32x4 a0 = *reinterpret_cast<const u32x4*>(Ks + n * kKsStride + 16 * kk + 8 * hh);
-    const u32x4 a1 = *reinterpret_cast<const u32x4*>(Ks + (kTile + n) * kKsStride + 16 * kk + 8 * hh);
-    s0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a0), qf[kk], s0, 0, 0, 0);
-    s1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a1), qf[kk], s1, 0, 0, 0);
+    a[2 * kk] = *reinterpret_cast<const u32x4*>(Ks + n * kKsStride + 16 * kk + 8 * hh);
+    a[2 * kk + 1] = *reinterpret_cast<const u32x4*>(Ks + (kTile + n) * kKsStride + 16 * kk + 8 * hh);
+  }
+  __builtin_amdgcn_sched_group_barrier(0x100, 16, 0);       // the 16 LDS reads first
+#pragma unroll
+  for (int kk = 0; kk < 8; ++kk) {
+    s0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a[2 * kk]), qf[kk], s0, 0, 0, 0);
+    s1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a[2 * kk + 1]), qf[kk], s1, 0, 0, 0);
+  }
+  __builtin_amdgcn_sched_group_barrier(0x008, 16, 0);       // then the 16 products
+}
+
+// O^T += V^T P^T for a 64-token step whose V rows sit row-major in LDS (Vs[token][d]).  The A operand of
+// product (kk, b) is V^T[d = 32 b + n][tokens 16 kk + 8 hf + 4 hh + j], hf = 0, 1, j = 0..3: each half comes from
+// one ds_read_b64_tr_b16.  Within a block of 16 lanes that instruction treats the 8-byte pieces the lanes
+// address as the rows of a 16 x 4 matrix of 16-bit values and hands lane i the values (i / 4 + 4 j, i % 4),
+// j = 0..3; with lane i addressing (token i / 4 of the four, d-quad i % 4 of its block's sixteen d) lane i gets
+// element d = 16 (block % 2) + i of tokens 0..3 -- its own row of V^T.  p[i] is the weight of token
+// 32 (i / 16) + 8 ((i % 16) / 4) + 4 hh + i % 4.
+typedef short s16x4 __attribute__((ext_vector_type(4)));
+typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
+
+__device__ __forceinline__ void pv64_tr(const uint16_t* Vs, const float (&p)[32], int lane, RowState& st) {
+  const int i16 = lane & 15, blk = lane >> 4;
+  const uint16_t* base = Vs + (4 * (blk >> 1) + (i16 >> 2)) * kVsStride + 16 * (blk & 1) + 4 * (i16 & 3);
+  u32x4 va[16];
+#pragma unroll
+  for (int kk = 0; kk < 4; ++kk)
+#pragma unroll
+    for (int b = 0; b < 4; ++b) {
+      const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(base + (16 * kk) * kVsStride + 32 * b));
+      const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(base + (16 * kk + 8) * kVsStride + 32 * b));
+      const uint2 l2 = __builtin_bit_cast(uint2, lo), h2 = __builtin_bit_cast(uint2, hi);
+      va[4 * kk + b] = u32x4{l2.x, l2.y, h2.x, h2.y};
+    }
+#pragma unroll
+  for (int kk = 0; kk < 4; ++kk) {
+    u32x4 pw;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) pw[e] = pack2(p[8 * kk + 2 * e], p[8 * kk + 2 * e + 1]);
+    const bf16x8 pb = __builtin_bit_cast(bf16x8, pw);
+#pragma unroll
+    for (int b = 0; b < 4; ++b)
+      st.oacc[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, va[4 * kk + b]), pb, st.oacc[b], 0, 0, 0);
   }
 }
 
-template <int VT_STRIDE>
-__device__ __forceinline__ void softmax_pv64(const uint16_t* Vt, const f32x16& s0, const f32x16& s1, float scale,
-                                             uint32_t live, int n, int hh, RowState& st) {
+__device__ __forceinline__ void softmax_pv64(const uint16_t* Vs, const f32x16& s0, const f32x16& s1, float scale,
+                                             uint32_t live, int lane, RowState& st) {
   float p[32];
   float mx = -INFINITY;
 #pragma unroll
@@ -206,29 +262,44 @@ __device__ __forceinline__ void softmax_pv64(const uint16_t* Vt, const f32x16& s
   }
   st.l_run += sum;
   st.m_run = m_new;
-#pragma unroll
-  for (int kk = 0; kk < 4; ++kk) {
-    u32x4 pw;
-#pragma unroll
-    for (int e = 0; e < 4; ++e) pw[e] = pack2(p[8 * kk + 2 * e], p[8 * kk + 2 * e + 1]);
-    const bf16x8 pb = __builtin_bit_cast(bf16x8, pw);
-#pragma unroll
-    for (int b = 0; b < 4; ++b) {
-      const uint16_t* vr = Vt + (32 * b + n) * VT_STRIDE + 16 * kk + 4 * hh;
-      const uint2 lo = *reinterpret_cast<const uint2*>(vr);
-      const uint2 hi = *reinterpret_cast<const uint2*>(vr + 8);
-      const u32x4 a = {lo.x, lo.y, hi.x, hi.y};
-      st.oacc[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a), pb, st.oacc[b], 0, 0, 0);
-    }
-  }
+  pv64_tr(Vs, p, lane, st);
 }
 
-template <int VT_STRIDE>
-__device__ __forceinline__ void tile_compute64(const uint16_t* Ks, const uint16_t* Vt, const bf16x8 (&qf)[8], float scale,
-                                               uint32_t live, int n, int hh, RowState& st) {
-  f32x16 s0, s1;
-  scores64(Ks, qf, n, hh, s0, s1);
-  softmax_pv64<VT_STRIDE>(Vt, s0, s1, scale, live, n, hh, st);
+// The same with whole 16-token groups switched off instead of single tokens, for a positive scale: score i
+// of a lane belongs to group i / 8 and bit g of m4 says whether group g takes part (four lane masks, one
+// select per score); the scale and the reference point go into one fused multiply-add in base-2 units in
+// front of v_exp_f32.  m_run stays in natural-log units of the scaled scores.
+__device__ __forceinline__ void softmax_pv64_groups(const uint16_t* Vs, const f32x16& s0, const f32x16& s1, float scale,
+                                                    uint32_t m4, int lane, RowState& st) {
+  constexpr float kLog2e = 1.4426950408889634f;
+  const bool on[4] = {(m4 & 1u) != 0, (m4 & 2u) != 0, (m4 & 4u) != 0, (m4 & 8u) != 0};
+  float p[32];
+  float mx = -INFINITY;
+#pragma unroll
+  for (int i = 0; i < 16; ++i) {
+    p[i] = on[i >> 3] ? s0[i] : -INFINITY;
+    p[16 + i] = on[2 + (i >> 3)] ? s1[i] : -INFINITY;
+    mx = fmaxf(mx, fmaxf(p[i], p[16 + i]));
+  }
+  mx = fmaxf(mx, __shfl_xor(mx, 32)) * scale;
+  constexpr float kLazy = 8.f;
+  const float m_new = mx > st.m_run + kLazy || st.m_run == -INFINITY ? fmaxf(st.m_run, mx) : st.m_run;
+  const float m_ref = m_new == -INFINITY ? 0.f : m_new;
+  const float c2 = scale * kLog2e, m2 = -m_ref * kLog2e;
+  float sum = 0.f;
+#pragma unroll
+  for (int i = 0; i < 32; ++i) { p[i] = __builtin_amdgcn_exp2f(__builtin_fmaf(p[i], c2, m2)); sum += p[i]; }
+  if (__any(m_new != st.m_run)) {
+    const float alpha = __expf(st.m_run - m_ref);
+    st.l_run *= alpha;
+#pragma unroll
+    for (int b = 0; b < 4; ++b)
+#pragma unroll
+      for (int i = 0; i < 16; ++i) st.oacc[b][i] *= alpha;
+  }
+  st.l_run += sum;
+  st.m_run = m_new;
+  pv64_tr(Vs, p, lane, st);
 }
 
 // ---- the same tile for 16 query rows per wavefront (v_mfma_f32_16x16x32_bf16): for passes whose row
@@ -263,8 +334,9 @@ __device__ __forceinline__ void scores16(const uint16_t* Ks, const bf16x8 (&qf)[
   }
 }
 
-template <int VT_STRIDE>
-__device__ __forceinline__ void softmax_pv16(const uint16_t* Vt, const f32x4a& s0, const f32x4a& s1, float scale, uint32_t live,
+// Vs holds the tile's V rows row-major (kVsStride); the A operands come from transposing reads as in pv64_tr:
+// lane i of a block of 16 addresses (token i / 4 of the block's four, d-quad i % 4) and receives d = 16 b + i.
+__device__ __forceinline__ void softmax_pv16(const uint16_t* Vs, const f32x4a& s0, const f32x4a& s1, float scale, uint32_t live,
                                              int n, int g, RowState16& st) {
   float p[8];
   float mx = -INFINITY;
@@ -296,12 +368,13 @@ __device__ __forceinline__ void softmax_pv16(const uint16_t* Vt, const f32x4a& s
 #pragma unroll
   for (int e = 0; e < 4; ++e) pw[e] = pack2(p[2 * e], p[2 * e + 1]);
   const bf16x8 pb = __builtin_bit_cast(bf16x8, pw);
+  const uint16_t* base = Vs + (4 * g + (n >> 2)) * kVsStride + 4 * (n & 3);
 #pragma unroll
   for (int b = 0; b < 8; ++b) {
-    const uint16_t* vr = Vt + (16 * b + n) * VT_STRIDE + 4 * g;
-    const uint2 lo = *reinterpret_cast<const uint2*>(vr);
-    const uint2 hi = *reinterpret_cast<const uint2*>(vr + 16);
-    const u32x4 a = {lo.x, lo.y, hi.x, hi.y};
+    const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(base + 16 * b));
+    const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(base + 16 * kVsStride + 16 * b));
+    const uint2 l2 = __builtin_bit_cast(uint2, lo), h2 = __builtin_bit_cast(uint2, hi);
+    const u32x4 a = {l2.x, l2.y, h2.x, h2.y};
     st.oacc[b] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a), pb, st.oacc[b], 0, 0, 0);
   }
 }
@@ -320,7 +393,9 @@ __global__ __launch_bounds__(kBlock) void tdk_attend_qrot_kernel(const RoundDev 
   const uint16_t* src = reinterpret_cast<const uint16_t*>(at.q) + row * kHeadDim;
   const int ia = rd.interleaved ? 2 * lane : lane;
   const int ib = rd.interleaved ? 2 * lane + 1 : lane + kHalf;
-  const float xa = __uint_as_float((uint32_t)src[ia] << 16), xb = __uint_as_float((uint32_t)src[ib] << 16);
+  // the kernels after this one work with |scale|: a negative scale flips the sign of every query copy (exact)
+  const uint32_t flip = at.q_flip ? 0x8000u : 0u;
+  const float xa = __uint_as_float((uint32_t)(src[ia] ^ flip) << 16), xb = __uint_as_float((uint32_t)(src[ib] ^ flip) << 16);
   // one copy per segment of the agent's layout (one for an identity layout): every segment has its own offset
   const int seg0 = rd.seg ? rd.seg_off[agent] : agent;
   const int nseg = rd.seg ? rd.seg_off[agent + 1] - seg0 : 1;
@@ -338,7 +413,7 @@ __global__ __launch_bounds__(kBlock) void tdk_attend_qrot_kernel(const RoundDev 
   // (a segmented round whose stored diffs moved keeps one such copy per segment: diff_seg copies per row)
   for (int k = 0; k < (at.diff_seg > 1 ? nseg : 1); ++k) {
     uint16_t* dst2 = reinterpret_cast<uint16_t*>(at.qdiff) + (row * at.diff_seg + k) * kHeadDim;
-    uint16_t za = src[ia], zb = src[ib];
+    uint16_t za = (uint16_t)(src[ia] ^ flip), zb = (uint16_t)(src[ib] ^ flip);
     const float* td = nullptr;
     if (!rd.seg && rd.agents[agent].diff_rot) td = rd.tab_diff + (size_t)agent * (2 * kHalf);
     if (rd.seg && at.diff_seg > 1) td = rd.segtab_diff + (size_t)(seg0 + k) * (2 * kHalf);   // identity tables copy exactly
@@ -359,11 +434,11 @@ __global__ __launch_bounds__(kBlock) void tdk_attend_qrot_kernel(const RoundDev 
 // grid: x = session * n_chunks + chunk, y = KV head, z = block of 128 query rows
 // ---------------------------------------------------------------------------------------------
 template <bool SEG>
-__global__ __launch_bounds__(kBlock) void tdk_attend_master_kernel(const RoundDev rd, const LayerDev io, const DiffDev d,
+__global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(2, 2))) void tdk_attend_master_kernel(const RoundDev rd, const LayerDev io, const DiffDev d,
                                                                    const AttendDev at) {
   __shared__ __attribute__((aligned(16))) uint16_t Ks[kBigTile * kKsStride];
-  __shared__ __attribute__((aligned(16))) uint16_t Vt[kHeadDim * kBigVtStride];
-  __shared__ uint32_t s_mask[kRowsPerBlock];    // bit p: page p of this chunk is listed in the row's agent's diff
+  __shared__ __attribute__((aligned(16))) uint16_t Vs[kBigTile * kVsStride];
+  __shared__ uint64_t s_mask[kRowsPerBlock];    // bit p: page p of this chunk is listed in the row's agent's diff
 
   const int session = blockIdx.x / at.n_chunks, chunk = blockIdx.x - session * at.n_chunks;
   const SessionDev sd = rd.sess[session];
@@ -379,7 +454,7 @@ __global__ __launch_bounds__(kBlock) void tdk_attend_master_kernel(const RoundDe
 
   // which pages of this chunk each row's agent lists in its diff (those tokens belong to the other kernel)
   if (threadIdx.x < kRowsPerBlock) {
-    uint32_t mask = 0;
+    uint64_t mask = 0;
     const RowRef rr = row_ref(rd, sd, at, h, row_begin + threadIdx.x);
     if (rr.agent >= 0) {
       int64_t lo = d.offset[rr.agent], hi = lo + d.count[rr.agent];
@@ -394,7 +469,7 @@ __global__ __launch_bounds__(kBlock) void tdk_attend_master_kernel(const RoundDe
       for (; a < hi; ++a) {
         const int p = d.idx[a];
         if (p > pg1 || p < pg0) break;
-        mask |= 1u << (p - pg0);
+        mask |= (uint64_t)1 << (p - pg0);
       }
     }
     s_mask[threadIdx.x] = mask;
@@ -431,64 +506,63 @@ __global__ __launch_bounds__(kBlock) void tdk_attend_master_kernel(const RoundDe
     }
   }
   __syncthreads();
-  const uint32_t my_mask = s_mask[wave * kRowsPerWave + n];
+  const uint64_t my_mask = s_mask[wave * kRowsPerWave + n];
 
   RowState rs;
   row_state_init(rs);
 
   const int64_t head_u4 = 16;                                  // 128 bf16 = 16 chunks of 16 bytes
   const int64_t row_u4 = (int64_t)rd.heads * head_u4;
-  // staging: a lane per token of the 64-token step, a wavefront per 64 bytes of the 256-byte head row.  The
-  // transposed V tile is then written 64 consecutive tokens at a time (no LDS bank conflicts); with the
-  // tokens spread over the lanes' upper bits instead, those 2-byte writes serialise 8 to 16 deep.
-  const int st_tok = threadIdx.x & 63, st_pg = threadIdx.x >> 6;
+  // staging: sixteen lanes per token row (coalesced 256-byte reads of one head's K and V), four rows per
+  // wavefront instruction; both tiles are kept row-major in LDS (the V operands are read with transposing loads)
+  const int st_tok = threadIdx.x >> 4, st_pc = threadIdx.x & 15;
 
   // 64 tokens per step: the next step's rows travel from HBM to registers while this one is multiplied
   u32x4 kv[8];
   auto fetch = [&](int t0) {
-    const int m = t0 + st_tok;
     const u32x4 z = {0, 0, 0, 0};
 #pragma unroll
-    for (int e = 0; e < 8; ++e) kv[e] = z;
-    if (m < tok_end) {
-      const int64_t base = (sd.master_row0 + m) * row_u4 + h * head_u4 + st_pg * 4;
-#pragma unroll
-      for (int e = 0; e < 4; ++e) { kv[e] = io.master_k[base + e]; kv[4 + e] = io.master_v[base + e]; }
+    for (int e = 0; e < 4; ++e) {
+      const int m = t0 + 16 * e + st_tok;
+      kv[e] = z; kv[4 + e] = z;
+      if (m < tok_end) {
+        const int64_t at_u4 = (sd.master_row0 + m) * row_u4 + h * head_u4 + st_pc;
+        kv[e] = io.master_k[at_u4]; kv[4 + e] = io.master_v[at_u4];
+      }
     }
   };
   fetch(tok_begin);
-  for (int t0 = tok_begin; t0 < tok_end; t0 += kBigTile) {
+  // one 64-token step; WHOLE: all 64 tokens lie inside the span (every step but a ragged last one)
+  auto step = [&](int t0, auto whole_tag) {
+    constexpr bool WHOLE = decltype(whole_tag)::value;
     __syncthreads();                                           // the previous step has been consumed
-    stage_rows<kBigVtStride>(Ks, Vt, st_tok, 2 * st_pg, kv[0], kv[1], kv[4], kv[5]);
-    stage_rows<kBigVtStride>(Ks, Vt, st_tok, 2 * st_pg + 1, kv[2], kv[3], kv[6], kv[7]);
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      *reinterpret_cast<u32x4*>(Ks + (16 * e + st_tok) * kKsStride + 8 * st_pc) = kv[e];
+      *reinterpret_cast<u32x4*>(Vs + (16 * e + st_tok) * kVsStride + 8 * st_pc) = kv[4 + e];
+    }
     __syncthreads();
-    if (t0 + kBigTile < tok_end) fetch(t0 + kBigTile);
+    if (WHOLE && t0 + kBigTile < tok_end) fetch(t0 + kBigTile);
     // which of this lane's 32 scores take part: 16-token groups follow the page mask of the row's agent
-    uint32_t live;
+    // (m4: bit g set = the g-th group of 16 tokens of this step takes part)
+    uint32_t m4;
     {
       const uint32_t rel = (uint32_t)(t0 - tok_begin);
       if (T == 16) {
-        const uint32_t m4 = ~(my_mask >> (rel >> 4)) & 0xfu;                 // four pages of 16 tokens
-        live = ((m4 & 1u) ? 0x000000ffu : 0u) | ((m4 & 2u) ? 0x0000ff00u : 0u) |
-               ((m4 & 4u) ? 0x00ff0000u : 0u) | ((m4 & 8u) ? 0xff000000u : 0u);
+        m4 = ~(uint32_t)(my_mask >> (rel >> 4)) & 0xfu;                      // four pages of 16 tokens
       } else {
-        const uint32_t m2 = ~(my_mask >> (rel >> 5)) & 0x3u;                 // two pages of 32 tokens
-        live = ((m2 & 1u) ? 0x0000ffffu : 0u) | ((m2 & 2u) ? 0xffff0000u : 0u);
+        const uint32_t m2 = ~(uint32_t)(my_mask >> (rel >> 5)) & 0x3u;       // two pages of 32 tokens
+        m4 = ((m2 & 1u) ? 0x3u : 0u) | ((m2 & 2u) ? 0xcu : 0u);
       }
-      if (mine.agent < 0) live = 0;
-      if (t0 + kBigTile > tok_end) {                                         // ragged end of the span
-#pragma unroll
-        for (int i = 0; i < 32; ++i)
-          if (t0 + 32 * (i >> 4) + 8 * ((i & 15) >> 2) + 4 * hh + (i & 3) >= tok_end) live &= ~(1u << i);
-      }
+      if (mine.agent < 0) m4 = 0;
     }
+    f32x16 s0, s1;
     if (!SEG) {
-      tile_compute64<kBigVtStride>(Ks, Vt, qf, at.scale, live, n, hh, rs);
+      scores64<true>(Ks, qf, n, hh, s0, s1);
     } else {
       // The step may run over several segments of this row's agent: the scores are computed once per
       // segment met (each with that segment's copy of the query row) and every token keeps the one of the
       // segment it belongs to.  Rows differ in where their segments end; the loop runs while any row has one left.
-      f32x16 s0, s1;
 #pragma unroll
       for (int i = 0; i < 16; ++i) { s0[i] = 0.f; s1[i] = 0.f; }
       const int t_end = t0 + kBigTile;
@@ -497,7 +571,7 @@ __global__ __launch_bounds__(kBlock) void tdk_attend_master_kernel(const RoundDe
       while (__any(more)) {
         load_q(k, more, qf);
         f32x16 p0, p1;
-        scores64(Ks, qf, n, hh, p0, p1);
+        scores64<false>(Ks, qf, n, hh, p0, p1);
         const int lo = more ? rd.seg_src[seg_base + k] : 0;
         const int hi = more ? (k + 1 < seg_n ? rd.seg_src[seg_base + k + 1] : sd.span) : 0;
 #pragma unroll
@@ -511,9 +585,21 @@ __global__ __launch_bounds__(kBlock) void tdk_attend_master_kernel(const RoundDe
       }
       seg_k = k;                                  // the segment that holds the last token of this step
       if (mine.agent >= 0 && seg_k + 1 < seg_n && rd.seg_src[seg_base + seg_k + 1] <= t_end) ++seg_k;
-      softmax_pv64<kBigVtStride>(Vt, s0, s1, at.scale, live, n, hh, rs);
     }
-  }
+    if (WHOLE) {
+      softmax_pv64_groups(Vs, s0, s1, at.scale, m4, lane, rs);
+    } else {
+      uint32_t live = ((m4 & 1u) ? 0x000000ffu : 0u) | ((m4 & 2u) ? 0x0000ff00u : 0u) |
+                      ((m4 & 4u) ? 0x00ff0000u : 0u) | ((m4 & 8u) ? 0xff000000u : 0u);
+#pragma unroll
+      for (int i = 0; i < 32; ++i)                                           // ragged end of the span
+        if (t0 + 32 * (i >> 4) + 8 * ((i & 15) >> 2) + 4 * hh + (i & 3) >= tok_end) live &= ~(1u << i);
+      softmax_pv64(Vs, s0, s1, at.scale, live, lane, rs);
+    }
+  };
+  const int whole_end = tok_begin + (tok_end - tok_begin) / kBigTile * kBigTile;
+  for (int t0 = tok_begin; t0 < whole_end; t0 += kBigTile) step(t0, std::true_type{});
+  if (whole_end < tok_end) step(whole_end, std::false_type{});
 
   const float l_tot = rs.l_run + __shfl_xor(rs.l_run, 32);
   if (mine.agent >= 0) {
@@ -534,9 +620,10 @@ __global__ __launch_bounds__(kBlock) void tdk_attend_master_kernel(const RoundDe
 // w, w + 4, ... through its own staging area, and the four running results are combined at the end.
 // ---------------------------------------------------------------------------------------------
 constexpr int kWaveLds = kTile * kKsStride + kHeadDim * kVtStride;      // bf16 elements of one wavefront's staging area
+static_assert(kTile * kVsStride <= kHeadDim * kVtStride, "a row-major V tile fits where the transposed one does");
 
 template <bool SEGMOVED>
-__global__ __launch_bounds__(kBlock) void tdk_attend_diff_kernel(const RoundDev rd, const DiffDev d, const AttendDev at) {
+__global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(2, 2))) void tdk_attend_diff_kernel(const RoundDev rd, const DiffDev d, const AttendDev at) {
   // staging areas during the token loop, then (reused) the four wavefronts' results: [4][32 rows][128 + 2] floats
   __shared__ __attribute__((aligned(16))) uint16_t lds[kWaves * kWaveLds];
   static_assert(sizeof(uint16_t) * kWaves * kWaveLds >= sizeof(float) * kWaves * kRowsPerWave * (kHeadDim + 2), "result area");
@@ -697,7 +784,7 @@ __global__ __launch_bounds__(kBlock) void tdk_attend_diff_kernel(const RoundDev 
 // The same pass with 16 query rows per wavefront: used when an agent brings at most 16 rows per KV head
 // (decode: query tokens x heads per KV head), where the 32-row tiles would be five sixths padding.
 template <bool SEGMOVED>
-__global__ __launch_bounds__(kBlock) void tdk_attend_diff16_kernel(const RoundDev rd, const DiffDev d, const AttendDev at) {
+__global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(2, 2))) void tdk_attend_diff16_kernel(const RoundDev rd, const DiffDev d, const AttendDev at) {
   // staging areas during the token loop, then (reused) the four wavefronts' results: [4][32 rows][128 + 2] floats
   __shared__ __attribute__((aligned(16))) uint16_t lds[kWaves * kWaveLds];
   constexpr int kRows = 16;                    // query rows per wavefront
@@ -714,7 +801,7 @@ __global__ __launch_bounds__(kBlock) void tdk_attend_diff16_kernel(const RoundDe
   const int n_tiles = (n_tok + kTile - 1) / kTile;
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, n = lane & 15, g4 = lane >> 4;
   uint16_t* Ks = lds + wave * kWaveLds;
-  uint16_t* Vt = Ks + kTile * kKsStride;
+  uint16_t* Vs = Ks + kTile * kKsStride;       // [32 tokens][kVsStride], row-major like the K tile
   const int64_t row_e = (int64_t)rd.heads * kHeadDim, page_e = (int64_t)T * row_e;
   const uint16_t* pay = reinterpret_cast<const uint16_t*>(d.payload);
 
@@ -738,46 +825,59 @@ __global__ __launch_bounds__(kBlock) void tdk_attend_diff16_kernel(const RoundDe
     if (!SEGMOVED) load_q(0);
     const int seg_base = SEGMOVED ? rd.seg_off[agent] : 0;
     const int seg_n = SEGMOVED ? rd.seg_off[agent + 1] - seg_base : 1;
-    int seg_next = 0;                            // segment of the token this lane fetched (SEGMOVED only)
     RowState16 rs;
     row_state16_init(rs);
     // a wavefront's next tile travels from the payload to registers while its current one is multiplied:
-    // 32 tokens x 8 parts of 32 bytes, four (token, part) pairs per lane
-    u32x4 kv[4][4];
-    uint32_t valid_next = 0;                     // bit t: token t of the fetched tile exists and lies inside the span
-    const int st_tok = lane & 31, st_pg = lane >> 5;      // this lane stages parts 4 st_pg .. 4 st_pg + 3 of one token
+    // sixteen lanes per 256-byte row of K and of V (coalesced), four token rows per instruction, eight of each
+    u32x4 kreg[8], vreg[8];
+    int p_next = -1;                             // master page of token lane % 32 of the fetched tile (-1: no such token)
+    const int st_row = lane >> 4, st_pc = lane & 15;
+    // The payload address of a listed token depends on its place in the list alone, so the rows are requested
+    // together with the page number; what the page number decides (does the token lie inside the span, which
+    // segment holds it) is settled when the tile is used.
     auto fetch = [&](int tile) {
-      const int t = tile * kTile + st_tok;
+      const int t = tile * kTile + (lane & 31);
+      p_next = tile < n_tiles && t < n_tok ? d.idx[lo + t / T] : -1;
       const u32x4 z = {0, 0, 0, 0};
 #pragma unroll
-      for (int j = 0; j < 4; ++j) { kv[j][0] = z; kv[j][1] = z; kv[j][2] = z; kv[j][3] = z; }
-      bool ok = false;
-      if (tile < n_tiles && t < n_tok) {
-        const int64_t slot = lo + t / T;
-        const int rr = t % T, p = d.idx[slot];
-        if (p >= 0 && p < sd.pages && p * T + rr < sd.span) {
-          ok = true;
-          if (SEGMOVED) {
-            seg_next = 0;
-            while (seg_next + 1 < seg_n && rd.seg_src[seg_base + seg_next + 1] <= p * T + rr) ++seg_next;
-          }
-          const u32x4* kr = reinterpret_cast<const u32x4*>(pay + (slot * 2) * page_e + rr * row_e + h * kHeadDim) + st_pg * 8;
-          const u32x4* vr = reinterpret_cast<const u32x4*>(pay + (slot * 2 + 1) * page_e + rr * row_e + h * kHeadDim) + st_pg * 8;
-#pragma unroll
-          for (int j = 0; j < 4; ++j) { kv[j][0] = kr[2 * j]; kv[j][1] = kr[2 * j + 1]; kv[j][2] = vr[2 * j]; kv[j][3] = vr[2 * j + 1]; }
+      for (int j = 0; j < 8; ++j) {
+        const int t2 = tile * kTile + 4 * j + st_row;
+        kreg[j] = z; vreg[j] = z;
+        if (tile < n_tiles && t2 < n_tok) {
+          const int64_t at_e = ((lo + t2 / T) * 2) * page_e + (t2 % T) * row_e + h * kHeadDim + 8 * st_pc;
+          kreg[j] = *reinterpret_cast<const u32x4*>(pay + at_e);
+          vreg[j] = *reinterpret_cast<const u32x4*>(pay + at_e + page_e);
         }
       }
-      valid_next = (uint32_t)__ballot(ok);       // lanes 0..31 carry the tokens (lanes 32..63 repeat them)
     };
     fetch(wave);
     for (int it = 0; it * kWaves < n_tiles; ++it) {
       const int tile = it * kWaves + wave;
       wave_sync();                               // this wavefront's previous tile has been consumed
-      uint32_t valid = valid_next;
-      const int seg_cur = seg_next;
+      // bit t of valid: token t of the tile exists and lies inside the span (lanes 32..63 repeat lanes 0..31)
+      int seg_cur = 0;
+      bool ok = false;
+      {
+        const int rr = (tile * kTile + (lane & 31)) % T, p = p_next;
+        if (p >= 0 && p < sd.pages && p * T + rr < sd.span) {
+          ok = true;
+          if (SEGMOVED)
+            while (seg_cur + 1 < seg_n && rd.seg_src[seg_base + seg_cur + 1] <= p * T + rr) ++seg_cur;
+        }
+      }
+      const uint32_t valid = (uint32_t)__ballot(ok);
       if (tile < n_tiles) {
+        if (valid != 0xffffffffu) {              // rows of tokens that do not count are staged as zeros
+          const u32x4 z = {0, 0, 0, 0};
 #pragma unroll
-        for (int j = 0; j < 4; ++j) stage_rows<kVtStride>(Ks, Vt, st_tok, 4 * st_pg + j, kv[j][0], kv[j][1], kv[j][2], kv[j][3]);
+          for (int j = 0; j < 8; ++j)
+            if (!((valid >> (4 * j + st_row)) & 1u)) { kreg[j] = z; vreg[j] = z; }
+        }
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+          *reinterpret_cast<u32x4*>(Ks + (4 * j + st_row) * kKsStride + 8 * st_pc) = kreg[j];
+          *reinterpret_cast<u32x4*>(Vs + (4 * j + st_row) * kVsStride + 8 * st_pc) = vreg[j];
+        }
       }
       wave_sync();                               // the staging area belongs to this wavefront alone
       if ((it + 1) * kWaves < n_tiles) fetch(tile + kWaves);
@@ -814,7 +914,7 @@ __global__ __launch_bounds__(kBlock) void tdk_attend_diff16_kernel(const RoundDe
             done = cand;
           }
         }
-        softmax_pv16<kVtStride>(Vt, s0, s1, at.scale, live, n, g4, rs);
+        softmax_pv16(Vs, s0, s1, at.scale, live, n, g4, rs);
       }
     }
     // combine the four wavefronts (the staging areas are free now)

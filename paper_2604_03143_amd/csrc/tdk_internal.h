@@ -114,7 +114,8 @@ struct AttendDev {
   int32_t max_seg;                   // copies of every query row in qrot: one per segment of its agent's layout
   int32_t diff_seg;                  // copies of every query row in qdiff: max_seg if a segmented round's stored
                                      // diffs sit at other positions (each segment moved by its own distance), else 1
-  float   scale;
+  float   scale;                     // magnitude of the caller's scale, at least 1e-30
+  int32_t q_flip;                    // the caller's scale was negative: the query copies carry the sign
 };
 
 // launchers (tdk_kernels.hip); each enqueues exactly one kernel

@@ -15,7 +15,7 @@ pytestmark = pytest.mark.gpu
 OUT_TOL, LSE_TOL = 1e-2, 5e-3
 
 
-def _case(tdo, spec, n_q, Hq, style=0, grow=None, seed=3):
+def _case(tdo, spec, n_q, Hq, style=0, grow=None, seed=3, scale=None):
     import torch
     from paper_2604_03143_amd import tdk
     import gpu_helpers as gh
@@ -31,7 +31,7 @@ def _case(tdo, spec, n_q, Hq, style=0, grow=None, seed=3):
         diff_pos0 = old.agent_pos0
     g = np.random.default_rng([spec.stream, seed])
     q = wl.f32_to_bf16_bits(g.standard_normal((rnd.n_agents, n_q, Hq, spec.head_dim)).astype(np.float32))
-    scale = 1.0 / np.sqrt(spec.head_dim)
+    scale = 1.0 / np.sqrt(spec.head_dim) if scale is None else scale
     want_o, want_l = tdo.attend_shared(o.g, tdo.HostRound(rnd, diff_pos0=diff_pos0), o.mk, o.mv, d, q, n_q, Hq, scale)
 
     r = tdk.round_from_workload(rnd, style=style, diff_pos0=diff_pos0)
@@ -58,7 +58,9 @@ def _case(tdo, spec, n_q, Hq, style=0, grow=None, seed=3):
     err_o = float(np.max(np.abs(got_o - want_o)))
     err_l = float(np.max(np.abs(got_l - want_l)))
     assert np.all(np.isfinite(got_o)) and np.all(np.isfinite(got_l))
-    assert err_o <= OUT_TOL * max(1.0, vmax) and err_l <= LSE_TOL, (err_o, err_l)
+    # the score errors grow with the scale: the bounds above are those of scale = 1 / sqrt(D)
+    k = max(1.0, abs(scale) * np.sqrt(spec.head_dim))
+    assert err_o <= k * OUT_TOL * max(1.0, vmax) and err_l <= k * LSE_TOL, (err_o, err_l)
     return err_o, err_l
 
 
@@ -66,6 +68,21 @@ def test_one_query_token_per_agent(tdo):
     """Decode step: 1 query token, 40 query heads on 8 KV heads, ragged span, several tiles and chunks."""
     spec = wl.RoundSpec("att", 61, 1, 8, 128, 16, 1.0e6, 2, 5, 4, 73, 5, 3000, 0.2)
     _case(tdo, spec, 1, 40)
+
+
+@pytest.mark.parametrize("scale", [-0.11, 0.0, 0.25])
+def test_negative_zero_and_large_scales(tdo, scale):
+    """The kernels work with the magnitude of the scale and carry its sign in the query copies; a zero scale
+    gives uniform weights (out = mean of V over the span, lse = log S)."""
+    spec = wl.RoundSpec("att6", 66, 1, 2, 128, 16, 1.0e6, 1, 3, 3, 50, 0, 300, 0.3)
+    _case(tdo, spec, 2, 6, scale=scale)
+
+
+def test_long_span_with_chunks_above_512_tokens(tdo):
+    """Four sessions of 10280 tokens on 8 KV heads: on a 256-CU device the planner gives every workgroup of the
+    master pass 704 tokens = 44 pages (the page mask of a row is 64 bits wide)."""
+    spec = wl.RoundSpec("att7", 67, 1, 8, 128, 16, 1.0e6, 4, 3, 40, 257, 5, 900, 0.1)
+    _case(tdo, spec, 1, 8)
 
 
 @pytest.mark.parametrize("H,Hq,T,style,n_q", [(4, 28, 16, 0, 3), (8, 8, 32, 0, 2), (2, 4, 16, 1, 5), (1, 7, 16, 0, 1)])
