@@ -735,7 +735,7 @@ namespace {
 // Shape of the attention pass for a round: tokens per workgroup of the master pass, parts per query
 // row, and the layout of the caller's workspace.
 struct AttendPlan {
-  int32_t chunk_tokens = 0, n_chunks = 0, n_parts = 0, max_rows = 0;
+  int32_t chunk_tokens = 0, n_chunks = 0, n_parts = 0, max_rows = 0, n_pieces = 1, piece_tokens = 0;
   int64_t rows = 0;
   size_t o_qrot = 0, o_qdiff = 0, o_part_o = 0, o_part_m = 0, o_part_l = 0, bytes = 0;
 };
@@ -774,7 +774,16 @@ bool attend_plan(const tdk_round* r, int32_t n_q, int32_t n_q_heads, AttendPlan&
   }
   p.chunk_tokens = chunk;
   p.n_chunks = (int32_t)((max_span + chunk - 1) / chunk);
-  p.n_parts = p.n_chunks + 1;
+  // the listed-pages pass: with at most 16 query rows per agent and KV head one wavefront takes a piece of an
+  // agent's list and every piece has its own partial result; else one workgroup takes the whole list
+  if ((int64_t)n_q * G <= 16) {
+    int64_t max_pages = 0;
+    for (const auto& hs : r->sessions)
+      if (!hs.agents.empty()) max_pages = std::max<int64_t>(max_pages, hs.pages);
+    p.piece_tokens = attend_piece_tokens();
+    p.n_pieces = (int32_t)std::max<int64_t>(1, (max_pages * r->model.page_tokens + p.piece_tokens - 1) / p.piece_tokens);
+  }
+  p.n_parts = p.n_chunks + p.n_pieces;
   size_t off = 0;
   auto place = [&](size_t bytes) { size_t o = off; off = align_up(off + bytes, 256); return o; };
   p.o_qrot = place((size_t)p.rows * r->max_segments * kHeadDim * 2);
@@ -833,6 +842,8 @@ tdk_status tdk_attend_shared(tdk_round* r, int32_t layer, const tdk_layer_io* io
     at.chunk_tokens = p.chunk_tokens;
     at.n_chunks = p.n_chunks;
     at.n_parts = p.n_parts;
+    at.n_pieces = p.n_pieces;
+    at.piece_tokens = p.piece_tokens;
     // the kernels take a positive scale: the sign travels with the query copies, and a zero scale (uniform
     // weights) becomes one so small that every scaled score rounds to zero
     at.scale = std::fmax(std::fabs(a->scale), 1e-30f);
@@ -845,7 +856,7 @@ tdk_status tdk_attend_shared(tdk_round* r, int32_t layer, const tdk_layer_io* io
     TDK_LAUNCH(r, TDK_KERNEL_ATTEND_QROT, s, launch_attend_qrot(r->rd, at, s));
     TDK_LAUNCH(r, TDK_KERNEL_ATTEND_MASTER, s, launch_attend_master(r->rd, l, d, at, p.max_rows, s));
     TDK_LAUNCH(r, TDK_KERNEL_ATTEND_DIFF, s, launch_attend_diff(r->rd, d, at, s));
-    TDK_LAUNCH(r, TDK_KERNEL_ATTEND_MERGE, s, launch_attend_merge(r->rd, at, s));
+    TDK_LAUNCH(r, TDK_KERNEL_ATTEND_MERGE, s, launch_attend_merge(r->rd, d, at, s));
     return TDK_OK;
   });
 }

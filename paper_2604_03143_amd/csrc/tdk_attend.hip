@@ -322,15 +322,14 @@ __device__ __forceinline__ void row_state16_init(RowState16& st) {
     for (int i = 0; i < 4; ++i) st.oacc[b][i] = 0.f;
 }
 
-__device__ __forceinline__ void scores16(const uint16_t* Ks, const bf16x8 (&qf)[4], int n, int g, f32x4a& s0, f32x4a& s1) {
+// k[2 kk + tt] holds, for lane (n, g), elements 32 kk + 8 g .. + 7 of the K row of token 16 tt + n
+__device__ __forceinline__ void scores16(const u32x4 (&k)[8], const bf16x8 (&qf)[4], f32x4a& s0, f32x4a& s1) {
 #pragma unroll
   for (int i = 0; i < 4; ++i) { s0[i] = 0.f; s1[i] = 0.f; }
 #pragma unroll
   for (int kk = 0; kk < 4; ++kk) {
-    const u32x4 a0 = *reinterpret_cast<const u32x4*>(Ks + n * kKsStride + 32 * kk + 8 * g);
-    const u32x4 a1 = *reinterpret_cast<const u32x4*>(Ks + (16 + n) * kKsStride + 32 * kk + 8 * g);
-    s0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a0), qf[kk], s0, 0, 0, 0);
-    s1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a1), qf[kk], s1, 0, 0, 0);
+    s0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, k[2 * kk]), qf[kk], s0, 0, 0, 0);
+    s1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, k[2 * kk + 1]), qf[kk], s1, 0, 0, 0);
   }
 }
 
@@ -431,7 +430,7 @@ __global__ __launch_bounds__(kBlock) void tdk_attend_qrot_kernel(const RoundDev 
 
 // ---------------------------------------------------------------------------------------------
 // master pass: S^T = K Q'^T and O^T += V^T P^T per 32-token tile, online softmax per query row
-// grid: x = session * n_chunks + chunk, y = KV head, z = block of 128 query rows
+// grid: x = KV head, y = session * n_chunks + chunk, z = block of 128 query rows
 // ---------------------------------------------------------------------------------------------
 template <bool SEG>
 __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(2, 2))) void tdk_attend_master_kernel(const RoundDev rd, const LayerDev io, const DiffDev d,
@@ -440,14 +439,14 @@ __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(2, 2))) 
   __shared__ __attribute__((aligned(16))) uint16_t Vs[kBigTile * kVsStride];
   __shared__ uint64_t s_mask[kRowsPerBlock];    // bit p: page p of this chunk is listed in the row's agent's diff
 
-  const int session = blockIdx.x / at.n_chunks, chunk = blockIdx.x - session * at.n_chunks;
+  const int session = blockIdx.y / at.n_chunks, chunk = blockIdx.y - session * at.n_chunks;
   const SessionDev sd = rd.sess[session];
   const int tok_begin = chunk * at.chunk_tokens;
   if (tok_begin >= sd.span || sd.n_agents == 0) return;
   const int rows = sd.n_agents * at.n_q * at.group;
   const int row_begin = blockIdx.z * kRowsPerBlock;
   if (row_begin >= rows) return;
-  const int h = blockIdx.y;
+  const int h = blockIdx.x;
   const int T = rd.page_tokens;
   const int tok_end = min(sd.span, tok_begin + at.chunk_tokens);
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, n = lane & 31, hh = lane >> 5;
@@ -527,7 +526,7 @@ __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(2, 2))) 
       kv[e] = z; kv[4 + e] = z;
       if (m < tok_end) {
         const int64_t at_u4 = (sd.master_row0 + m) * row_u4 + h * head_u4 + st_pc;
-        kv[e] = io.master_k[at_u4]; kv[4 + e] = io.master_v[at_u4];
+        kv[e] = __builtin_nontemporal_load(io.master_k + at_u4); kv[4 + e] = __builtin_nontemporal_load(io.master_v + at_u4);
       }
     }
   };
@@ -783,184 +782,163 @@ __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(2, 2))) 
 
 // The same pass with 16 query rows per wavefront: used when an agent brings at most 16 rows per KV head
 // (decode: query tokens x heads per KV head), where the 32-row tiles would be five sixths padding.
-template <bool SEGMOVED>
-__global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(2, 2))) void tdk_attend_diff16_kernel(const RoundDev rd, const DiffDev d, const AttendDev at) {
-  // staging areas during the token loop, then (reused) the four wavefronts' results: [4][32 rows][128 + 2] floats
-  __shared__ __attribute__((aligned(16))) uint16_t lds[kWaves * kWaveLds];
-  constexpr int kRows = 16;                    // query rows per wavefront
+// One wavefront per (agent, KV head, piece): a piece is kPieceTiles consecutive tiles of the agent's listed
+// tokens and has its own partial result, so there is nothing to combine inside the kernel; workgroups whose
+// piece lies past the end of the agent's list leave at once (the merge knows how many pieces an agent has).
+constexpr int kPieceTiles = 16;                // 512 listed tokens per piece
 
-  const int agent = blockIdx.x, h = blockIdx.y;
-  const int per_agent = at.n_q * at.group;
-  const AgentDev ad = rd.agents[agent];
-  const SessionDev sd = rd.sess[ad.session];
+template <bool SEGMOVED>
+__global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2, 2))) void tdk_attend_diff16_kernel(const RoundDev rd, const DiffDev d, const AttendDev at) {
+  // the V tile (the K rows go straight from the payload into the MFMA operand registers)
+  __shared__ __attribute__((aligned(16))) uint16_t Vs[kTile * kVsStride];
+
+  const int h = blockIdx.x, agent = blockIdx.y, piece = blockIdx.z;
   const int T = rd.page_tokens;
   int64_t lo = d.offset[agent], hi = lo + d.count[agent];
   if (lo < 0) lo = 0;
   if (hi > d.capacity) hi = d.capacity;
   const int n_tok = hi > lo ? (int)((hi - lo) * T) : 0;
   const int n_tiles = (n_tok + kTile - 1) / kTile;
-  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, n = lane & 15, g4 = lane >> 4;
-  uint16_t* Ks = lds + wave * kWaveLds;
-  uint16_t* Vs = Ks + kTile * kKsStride;       // [32 tokens][kVsStride], row-major like the K tile
+  const int tile_begin = piece * kPieceTiles, tile_end = min(n_tiles, tile_begin + kPieceTiles);
+  if (tile_begin >= tile_end) return;
+  const int per_agent = at.n_q * at.group;     // at most 16: one row block
+  const AgentDev ad = rd.agents[agent];
+  const SessionDev sd = rd.sess[ad.session];
+  const int lane = threadIdx.x, n = lane & 15, g4 = lane >> 4;
   const int64_t row_e = (int64_t)rd.heads * kHeadDim, page_e = (int64_t)T * row_e;
   const uint16_t* pay = reinterpret_cast<const uint16_t*>(d.payload);
 
-  for (int r0 = 0; r0 < per_agent; r0 += kRows) {
-    // this lane's query row of the block
-    const int rem = r0 + n;
-    const bool row_ok = rem < per_agent;
-    const int qi = row_ok ? rem / at.group : 0, g = row_ok ? rem - qi * at.group : 0;
-    const int64_t out = ((int64_t)agent * at.n_q + qi) * at.n_q_heads + h * at.group + g;
-    bf16x8 qf[4];
-    auto load_q = [&](int k) {
-      const u32x4* qp = reinterpret_cast<const u32x4*>(reinterpret_cast<const uint16_t*>(at.qdiff) +
-                                                         (out * at.diff_seg + k) * kHeadDim);
+  // this lane's query row
+  const bool row_ok = n < per_agent;
+  const int qi = row_ok ? n / at.group : 0, g = row_ok ? n - qi * at.group : 0;
+  const int64_t out = ((int64_t)agent * at.n_q + qi) * at.n_q_heads + h * at.group + g;
+  bf16x8 qf[4];
+  auto load_q = [&](int k) {
+    const u32x4* qp = reinterpret_cast<const u32x4*>(reinterpret_cast<const uint16_t*>(at.qdiff) +
+                                                       (out * at.diff_seg + k) * kHeadDim);
+#pragma unroll
+    for (int kk = 0; kk < 4; ++kk) {
+      u32x4 v = {0, 0, 0, 0};
+      if (row_ok) v = qp[4 * kk + g4];
+      qf[kk] = __builtin_bit_cast(bf16x8, v);
+    }
+  };
+  if (!SEGMOVED) load_q(0);
+  const int seg_base = SEGMOVED ? rd.seg_off[agent] : 0;
+  const int seg_n = SEGMOVED ? rd.seg_off[agent + 1] - seg_base : 1;
+  RowState16 rs;
+  row_state16_init(rs);
+  // The next tile travels from the payload to registers while the current one is multiplied.
+  // K: lane (n, g) loads what it multiplies -- elements 32 kk + 8 g .. + 7 of the rows of tokens n and 16 + n
+  // (the A operands of the two 16-token score products).  V: sixteen lanes per 256-byte row, four rows per
+  // instruction, staged row-major in LDS for the transposing reads.
+  u32x4 kreg[8], vreg[8];
+  int p_next = -1;                             // master page of token lane % 32 of the fetched tile (-1: no such token)
+  const int st_row = lane >> 4, st_pc = lane & 15;
+  // The payload address of a listed token depends on its place in the list alone, so the rows are requested
+  // together with the page number; what the page number decides (does the token lie inside the span, which
+  // segment holds it) is settled when the tile is used.
+  // (offsets inside the agent's part of the payload fit 32 bits: at most 2 P pages of 64 KB or less)
+  const uint16_t* apay = pay + lo * 2 * page_e;
+  const uint32_t row_u = (uint32_t)row_e, page_u = (uint32_t)page_e, tile_u = (uint32_t)(kTile / T) * 2u * page_u;
+  auto tok_off = [&](int tk) { return (uint32_t)(tk / T) * 2u * page_u + (uint32_t)(tk % T) * row_u + (uint32_t)(h * kHeadDim); };
+  auto fetch = [&](int tile) {
+    const int t = tile * kTile + (lane & 31);
+    p_next = t < n_tok ? d.idx[lo + t / T] : -1;
+    const u32x4 z = {0, 0, 0, 0};
+    const uint32_t tile_off = (uint32_t)tile * tile_u;
+#pragma unroll
+    for (int tt = 0; tt < 2; ++tt) {
+      const bool there = tile * kTile + 16 * tt + n < n_tok;
+      const uint32_t off = tile_off + tok_off(16 * tt + n) + 8u * g4;
 #pragma unroll
       for (int kk = 0; kk < 4; ++kk) {
-        u32x4 v = {0, 0, 0, 0};
-        if (row_ok) v = qp[4 * kk + g4];
-        qf[kk] = __builtin_bit_cast(bf16x8, v);
+        kreg[2 * kk + tt] = z;
+        if (there) kreg[2 * kk + tt] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(apay + off + 32 * kk));
       }
-    };
-    if (!SEGMOVED) load_q(0);
-    const int seg_base = SEGMOVED ? rd.seg_off[agent] : 0;
-    const int seg_n = SEGMOVED ? rd.seg_off[agent + 1] - seg_base : 1;
-    RowState16 rs;
-    row_state16_init(rs);
-    // a wavefront's next tile travels from the payload to registers while its current one is multiplied:
-    // sixteen lanes per 256-byte row of K and of V (coalesced), four token rows per instruction, eight of each
-    u32x4 kreg[8], vreg[8];
-    int p_next = -1;                             // master page of token lane % 32 of the fetched tile (-1: no such token)
-    const int st_row = lane >> 4, st_pc = lane & 15;
-    // The payload address of a listed token depends on its place in the list alone, so the rows are requested
-    // together with the page number; what the page number decides (does the token lie inside the span, which
-    // segment holds it) is settled when the tile is used.
-    auto fetch = [&](int tile) {
-      const int t = tile * kTile + (lane & 31);
-      p_next = tile < n_tiles && t < n_tok ? d.idx[lo + t / T] : -1;
+    }
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+      vreg[j] = z;
+      if (tile * kTile + 4 * j + st_row < n_tok)
+        vreg[j] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(apay + tile_off + tok_off(4 * j + st_row) + page_u + 8u * st_pc));
+    }
+  };
+  fetch(tile_begin);
+  for (int tile = tile_begin; tile < tile_end; ++tile) {
+    wave_sync();                               // the previous tile has been consumed
+    // bit t of valid: token t of the tile exists and lies inside the span (lanes 32..63 repeat lanes 0..31)
+    int seg_cur = 0;
+    bool ok = false;
+    {
+      const int rr = (tile * kTile + (lane & 31)) % T, p = p_next;
+      if (p >= 0 && p < sd.pages && p * T + rr < sd.span) {
+        ok = true;
+        if (SEGMOVED)
+          while (seg_cur + 1 < seg_n && rd.seg_src[seg_base + seg_cur + 1] <= p * T + rr) ++seg_cur;
+      }
+    }
+    const uint32_t valid = (uint32_t)__ballot(ok);
+    if (valid != 0xffffffffu) {                // rows of tokens that do not count are staged as zeros
       const u32x4 z = {0, 0, 0, 0};
 #pragma unroll
-      for (int j = 0; j < 8; ++j) {
-        const int t2 = tile * kTile + 4 * j + st_row;
-        kreg[j] = z; vreg[j] = z;
-        if (tile < n_tiles && t2 < n_tok) {
-          const int64_t at_e = ((lo + t2 / T) * 2) * page_e + (t2 % T) * row_e + h * kHeadDim + 8 * st_pc;
-          kreg[j] = *reinterpret_cast<const u32x4*>(pay + at_e);
-          vreg[j] = *reinterpret_cast<const u32x4*>(pay + at_e + page_e);
+      for (int j = 0; j < 8; ++j)
+        if (!((valid >> (4 * j + st_row)) & 1u)) vreg[j] = z;       // (their scores are switched off below)
+    }
+#pragma unroll
+    for (int j = 0; j < 8; ++j) *reinterpret_cast<u32x4*>(Vs + (4 * j + st_row) * kVsStride + 8 * st_pc) = vreg[j];
+    // scores 0..3 of a lane belong to tokens 4 g + i, scores 4..7 to tokens 16 + 4 g + i
+    f32x4a s0, s1;
+    if (!SEGMOVED) {
+      scores16(kreg, qf, s0, s1);
+    } else {
+      // the tile's tokens come from up to four segments stored at different distances from today's
+      // positions: scores once per segment present, with the queries turned back by that distance
+      int sid[8];
+#pragma unroll
+      for (int i = 0; i < 4; ++i) { sid[i] = __shfl(seg_cur, 4 * g4 + i); sid[4 + i] = __shfl(seg_cur, 16 + 4 * g4 + i); }
+#pragma unroll
+      for (int i = 0; i < 4; ++i) { s0[i] = 0.f; s1[i] = 0.f; }
+      int done = -1;
+      while (true) {
+        int cand = (lane < kTile && ((valid >> lane) & 1u) && seg_cur > done) ? seg_cur : 0x7fffffff;
+#pragma unroll
+        for (int sft = 32; sft > 0; sft >>= 1) cand = min(cand, __shfl_xor(cand, sft));
+        if (cand == 0x7fffffff) break;
+        load_q(cand);
+        f32x4a p0, p1;
+        scores16(kreg, qf, p0, p1);
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          if (sid[i] == cand) s0[i] = p0[i];
+          if (sid[4 + i] == cand) s1[i] = p1[i];
         }
-      }
-    };
-    fetch(wave);
-    for (int it = 0; it * kWaves < n_tiles; ++it) {
-      const int tile = it * kWaves + wave;
-      wave_sync();                               // this wavefront's previous tile has been consumed
-      // bit t of valid: token t of the tile exists and lies inside the span (lanes 32..63 repeat lanes 0..31)
-      int seg_cur = 0;
-      bool ok = false;
-      {
-        const int rr = (tile * kTile + (lane & 31)) % T, p = p_next;
-        if (p >= 0 && p < sd.pages && p * T + rr < sd.span) {
-          ok = true;
-          if (SEGMOVED)
-            while (seg_cur + 1 < seg_n && rd.seg_src[seg_base + seg_cur + 1] <= p * T + rr) ++seg_cur;
-        }
-      }
-      const uint32_t valid = (uint32_t)__ballot(ok);
-      if (tile < n_tiles) {
-        if (valid != 0xffffffffu) {              // rows of tokens that do not count are staged as zeros
-          const u32x4 z = {0, 0, 0, 0};
-#pragma unroll
-          for (int j = 0; j < 8; ++j)
-            if (!((valid >> (4 * j + st_row)) & 1u)) { kreg[j] = z; vreg[j] = z; }
-        }
-#pragma unroll
-        for (int j = 0; j < 8; ++j) {
-          *reinterpret_cast<u32x4*>(Ks + (4 * j + st_row) * kKsStride + 8 * st_pc) = kreg[j];
-          *reinterpret_cast<u32x4*>(Vs + (4 * j + st_row) * kVsStride + 8 * st_pc) = vreg[j];
-        }
-      }
-      wave_sync();                               // the staging area belongs to this wavefront alone
-      if ((it + 1) * kWaves < n_tiles) fetch(tile + kWaves);
-      if (tile < n_tiles) {
-        // scores 0..3 of a lane belong to tokens 4 g + i, scores 4..7 to tokens 16 + 4 g + i
-        const uint32_t vs = valid >> (4 * g4);
-        uint32_t live = (vs & 0xfu) | ((vs >> 12) & 0xf0u);
-        if (!row_ok) live = 0;
-        f32x4a s0, s1;
-        if (!SEGMOVED) {
-          scores16(Ks, qf, n, g4, s0, s1);
-        } else {
-          // the tile's tokens come from up to four segments stored at different distances from today's
-          // positions: scores once per segment present, with the queries turned back by that distance
-          int sid[8];
-#pragma unroll
-          for (int i = 0; i < 4; ++i) { sid[i] = __shfl(seg_cur, 4 * g4 + i); sid[4 + i] = __shfl(seg_cur, 16 + 4 * g4 + i); }
-#pragma unroll
-          for (int i = 0; i < 4; ++i) { s0[i] = 0.f; s1[i] = 0.f; }
-          int done = -1;
-          while (true) {
-            int cand = (lane < kTile && ((valid >> lane) & 1u) && seg_cur > done) ? seg_cur : 0x7fffffff;
-#pragma unroll
-            for (int sft = 32; sft > 0; sft >>= 1) cand = min(cand, __shfl_xor(cand, sft));
-            if (cand == 0x7fffffff) break;
-            load_q(cand);
-            f32x4a p0, p1;
-            scores16(Ks, qf, n, g4, p0, p1);
-#pragma unroll
-            for (int i = 0; i < 4; ++i) {
-              if (sid[i] == cand) s0[i] = p0[i];
-              if (sid[4 + i] == cand) s1[i] = p1[i];
-            }
-            done = cand;
-          }
-        }
-        softmax_pv16(Vs, s0, s1, at.scale, live, n, g4, rs);
+        done = cand;
       }
     }
-    // combine the four wavefronts (the staging areas are free now)
-    __syncthreads();
-    float* res = reinterpret_cast<float*>(lds);                          // [4][16][130]: 128 outputs, m, l
-    {
-      float* mine = res + ((size_t)wave * kRows + n) * (kHeadDim + 2);
+    wave_sync();                               // the V tile is complete
+    if (tile + 1 < tile_end) fetch(tile + 1);  // the K registers are free: the scores are taken
+    const uint32_t vs = valid >> (4 * g4);
+    uint32_t live = (vs & 0xfu) | ((vs >> 12) & 0xf0u);
+    if (!row_ok) live = 0;
+    softmax_pv16(Vs, s0, s1, at.scale, live, n, g4, rs);
+  }
+  // this piece's partial result: lane (n, g) holds elements 16 b + 4 g + i of row n
+  float l_tot = rs.l_run + __shfl_xor(rs.l_run, 16);
+  l_tot += __shfl_xor(l_tot, 32);
+  if (row_ok) {
+    const int64_t slot = out * at.n_parts + at.n_chunks + piece;
+    float4* po = reinterpret_cast<float4*>(at.part_o + slot * kHeadDim);
 #pragma unroll
-      for (int b = 0; b < 8; ++b)
-#pragma unroll
-        for (int i = 0; i < 4; ++i) mine[16 * b + 4 * g4 + i] = rs.oacc[b][i];
-      float l_tot = rs.l_run + __shfl_xor(rs.l_run, 16);
-      l_tot += __shfl_xor(l_tot, 32);
-      if (g4 == 0) { mine[kHeadDim] = rs.m_run; mine[kHeadDim + 1] = l_tot; }
-    }
-    __syncthreads();
-    for (int e = threadIdx.x; e < kRows * kHeadDim; e += kBlock) {
-      const int row = e >> 7, dd = e & (kHeadDim - 1);
-      const int rem2 = r0 + row;
-      if (rem2 >= per_agent) continue;
-      float M = -INFINITY;
-#pragma unroll
-      for (int w = 0; w < kWaves; ++w) M = fmaxf(M, res[((size_t)w * kRows + row) * (kHeadDim + 2) + kHeadDim]);
-      const float m_ref = M == -INFINITY ? 0.f : M;
-      float o = 0.f, l = 0.f;
-#pragma unroll
-      for (int w = 0; w < kWaves; ++w) {
-        const float* rw = res + ((size_t)w * kRows + row) * (kHeadDim + 2);
-        const float wgt = __expf(rw[kHeadDim] - m_ref);
-        o = __builtin_fmaf(rw[dd], wgt, o);
-        l = __builtin_fmaf(rw[kHeadDim + 1], wgt, l);
-      }
-      const int qi2 = rem2 / at.group, g2 = rem2 - qi2 * at.group;
-      const int64_t out2 = ((int64_t)agent * at.n_q + qi2) * at.n_q_heads + h * at.group + g2;
-      const int64_t slot = out2 * at.n_parts + (at.n_parts - 1);
-      at.part_o[slot * kHeadDim + dd] = o;
-      if (dd == 0) { at.part_m[slot] = M; at.part_l[slot] = l; }
-    }
-    __syncthreads();
+    for (int b = 0; b < 8; ++b) po[4 * b + g4] = make_float4(rs.oacc[b][0], rs.oacc[b][1], rs.oacc[b][2], rs.oacc[b][3]);
+    if (g4 == 0) { at.part_m[slot] = rs.m_run; at.part_l[slot] = l_tot; }
   }
 }
 
 // ---------------------------------------------------------------------------------------------
 // merge: out = sum_c o_c e^(m_c - M) / sum_c l_c e^(m_c - M), lse = M + log(that sum); one wavefront per row
 // ---------------------------------------------------------------------------------------------
-__global__ __launch_bounds__(kBlock) void tdk_attend_merge_kernel(const RoundDev rd, const AttendDev at) {
+__global__ __launch_bounds__(kBlock) void tdk_attend_merge_kernel(const RoundDev rd, const DiffDev d, const AttendDev at) {
   const int64_t row = (int64_t)blockIdx.x * kWaves + (threadIdx.x >> 6);
   const int64_t n_rows = (int64_t)rd.n_agents * at.n_q * at.n_q_heads;
   if (row >= n_rows) return;
@@ -968,9 +946,19 @@ __global__ __launch_bounds__(kBlock) void tdk_attend_merge_kernel(const RoundDev
   const int agent = (int)(row / ((int64_t)at.n_q * at.n_q_heads));
   const int span = rd.sess[rd.agents[agent].session].span;
   const int chunks = (span + at.chunk_tokens - 1) / at.chunk_tokens;
-  const int used = chunks + 1;                     // the chunks of this row's span, then the listed pages
+  // the chunks of this row's span, then the pieces of its agent's listed pages (one piece that is always
+  // written when the listed-pages pass does not split the lists)
+  int pieces = 1;
+  if (at.piece_tokens > 0) {
+    int64_t lo = d.offset[agent], hi = lo + d.count[agent];
+    if (lo < 0) lo = 0;
+    if (hi > d.capacity) hi = d.capacity;
+    const int64_t n_tok = hi > lo ? (hi - lo) * rd.page_tokens : 0;
+    pieces = (int)((n_tok + at.piece_tokens - 1) / at.piece_tokens);
+  }
+  const int used = chunks + pieces;
   const int64_t base = row * at.n_parts;
-  auto part_of = [&](int c) { return c < chunks ? c : at.n_parts - 1; };
+  auto part_of = [&](int c) { return c < chunks ? c : at.n_chunks + (c - chunks); };
   // a lane per part for the maxima and the weights, then a lane per output element
   float M = -INFINITY;
   for (int c0 = 0; c0 < used; c0 += 64) {
@@ -991,8 +979,8 @@ __global__ __launch_bounds__(kBlock) void tdk_attend_merge_kernel(const RoundDev
     for (int j = 0; j < cnt; ++j) {
       const float wj = __shfl(w, j);
       const float* po = at.part_o + (base + part_of(c0 + j)) * kHeadDim;
-      a0 = __builtin_fmaf(po[lane], wj, a0);
-      a1 = __builtin_fmaf(po[64 + lane], wj, a1);
+      a0 = __builtin_fmaf(__builtin_nontemporal_load(po + lane), wj, a0);
+      a1 = __builtin_fmaf(__builtin_nontemporal_load(po + 64 + lane), wj, a1);
     }
   }
 #pragma unroll
@@ -1016,7 +1004,9 @@ hipError_t launch_attend_qrot(const RoundDev& rd, const AttendDev& at, hipStream
 hipError_t launch_attend_master(const RoundDev& rd, const LayerDev& io, const DiffDev& d, const AttendDev& at,
                                 int max_rows, hipStream_t st) {
   if (rd.n_sessions == 0 || at.n_chunks == 0 || max_rows == 0) return hipSuccess;
-  const dim3 grid((unsigned)(rd.n_sessions * at.n_chunks), (unsigned)rd.heads,
+  // the KV heads of one chunk get consecutive workgroup ids: they start together and read neighbouring
+  // 256-byte pieces of the same master rows
+  const dim3 grid((unsigned)rd.heads, (unsigned)(rd.n_sessions * at.n_chunks),
                   (unsigned)((max_rows + kRowsPerBlock - 1) / kRowsPerBlock));
   if (rd.seg) hipLaunchKernelGGL(tdk_attend_master_kernel<true>, grid, dim3(kBlock), 0, st, rd, io, d, at);
   else hipLaunchKernelGGL(tdk_attend_master_kernel<false>, grid, dim3(kBlock), 0, st, rd, io, d, at);
@@ -1026,10 +1016,10 @@ hipError_t launch_attend_master(const RoundDev& rd, const LayerDev& io, const Di
 hipError_t launch_attend_diff(const RoundDev& rd, const DiffDev& d, const AttendDev& at, hipStream_t st) {
   if (rd.n_agents == 0) return hipSuccess;
   const dim3 grid((unsigned)rd.n_agents, (unsigned)rd.heads);
-  const bool few_rows = at.n_q * at.group <= 16;
-  if (few_rows) {
-    if (at.diff_seg > 1) hipLaunchKernelGGL(tdk_attend_diff16_kernel<true>, grid, dim3(kBlock), 0, st, rd, d, at);
-    else hipLaunchKernelGGL(tdk_attend_diff16_kernel<false>, grid, dim3(kBlock), 0, st, rd, d, at);
+  if (at.piece_tokens > 0) {                   // few rows per agent: one wavefront per piece of an agent's list
+    const dim3 grid16((unsigned)rd.heads, (unsigned)rd.n_agents, (unsigned)at.n_pieces);
+    if (at.diff_seg > 1) hipLaunchKernelGGL(tdk_attend_diff16_kernel<true>, grid16, dim3(64), 0, st, rd, d, at);
+    else hipLaunchKernelGGL(tdk_attend_diff16_kernel<false>, grid16, dim3(64), 0, st, rd, d, at);
   } else {
     if (at.diff_seg > 1) hipLaunchKernelGGL(tdk_attend_diff_kernel<true>, grid, dim3(kBlock), 0, st, rd, d, at);
     else hipLaunchKernelGGL(tdk_attend_diff_kernel<false>, grid, dim3(kBlock), 0, st, rd, d, at);
@@ -1037,10 +1027,12 @@ hipError_t launch_attend_diff(const RoundDev& rd, const DiffDev& d, const Attend
   return hipGetLastError();
 }
 
-hipError_t launch_attend_merge(const RoundDev& rd, const AttendDev& at, hipStream_t st) {
+int attend_piece_tokens() { return kPieceTiles * kTile; }
+
+hipError_t launch_attend_merge(const RoundDev& rd, const DiffDev& d, const AttendDev& at, hipStream_t st) {
   const int64_t rows = (int64_t)rd.n_agents * at.n_q * at.n_q_heads;
   if (rows == 0) return hipSuccess;
-  hipLaunchKernelGGL(tdk_attend_merge_kernel, dim3((unsigned)((rows + kWaves - 1) / kWaves)), dim3(kBlock), 0, st, rd, at);
+  hipLaunchKernelGGL(tdk_attend_merge_kernel, dim3((unsigned)((rows + kWaves - 1) / kWaves)), dim3(kBlock), 0, st, rd, d, at);
   return hipGetLastError();
 }
 
