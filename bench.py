@@ -622,7 +622,8 @@ def attend_mode(args, tdk, wl, np, torch, dev):
     us = {}
     for k in (tdk.KERNEL_ATTEND_QROT, tdk.KERNEL_ATTEND_MASTER, tdk.KERNEL_ATTEND_DIFF, tdk.KERNEL_ATTEND_MERGE):
         ms, n = tdk.tdk_timing_read(r, k)
-        us[tdk.tdk_kernel_name(k)] = round(ms / n * 1e3, 2)
+        if n:          # (the master and the listed-pages pass share one launch, timed as the master pass, when the round allows)
+            us[tdk.tdk_kernel_name(k)] = round(ms / n * 1e3, 2)
     # the other way: restore every mirror, then read the restored caches once
     t_dec = timed(lambda: tdk.tdk_diff_decode(r, 0, io, d["c"], st), 5)
     ids = torch.from_numpy(np.unique(np.concatenate([rnd.block_tables[i][int(rnd.agent_pos0[i]) // T:] for i in range(A)])

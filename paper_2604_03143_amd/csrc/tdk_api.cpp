@@ -854,8 +854,15 @@ tdk_status tdk_attend_shared(tdk_round* r, int32_t layer, const tdk_layer_io* io
     const LayerDev l = layer_dev(io);
     const DiffDev d = diff_dev(in);
     TDK_LAUNCH(r, TDK_KERNEL_ATTEND_QROT, s, launch_attend_qrot(r->rd, at, s));
-    TDK_LAUNCH(r, TDK_KERNEL_ATTEND_MASTER, s, launch_attend_master(r->rd, l, d, at, p.max_rows, s));
-    TDK_LAUNCH(r, TDK_KERNEL_ATTEND_DIFF, s, launch_attend_diff(r->rd, d, at, s));
+    // blocks of the two passes share one launch when the round allows it (timed as the master pass)
+    const int64_t fused_blocks = (int64_t)r->model.num_kv_heads * r->rd.n_sessions * p.n_chunks * ((p.max_rows + 127) / 128) +
+                                 (int64_t)r->n_agents * ((r->model.num_kv_heads + 3) / 4) * p.n_pieces;
+    if (!r->rd.seg && at.diff_seg == 1 && p.piece_tokens > 0 && r->total_master_rows > 0 && fused_blocks < (1 << 30)) {
+      TDK_LAUNCH(r, TDK_KERNEL_ATTEND_MASTER, s, launch_attend_fused(r->rd, l, d, at, p.max_rows, s));
+    } else {
+      TDK_LAUNCH(r, TDK_KERNEL_ATTEND_MASTER, s, launch_attend_master(r->rd, l, d, at, p.max_rows, s));
+      TDK_LAUNCH(r, TDK_KERNEL_ATTEND_DIFF, s, launch_attend_diff(r->rd, d, at, s));
+    }
     TDK_LAUNCH(r, TDK_KERNEL_ATTEND_MERGE, s, launch_attend_merge(r->rd, d, at, s));
     return TDK_OK;
   });

@@ -432,21 +432,25 @@ __global__ __launch_bounds__(kBlock) void tdk_attend_qrot_kernel(const RoundDev 
 // master pass: S^T = K Q'^T and O^T += V^T P^T per 32-token tile, online softmax per query row
 // grid: x = KV head, y = session * n_chunks + chunk, z = block of 128 query rows
 // ---------------------------------------------------------------------------------------------
-template <bool SEG>
-__global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(2, 2))) void tdk_attend_master_kernel(const RoundDev rd, const LayerDev io, const DiffDev d,
-                                                                   const AttendDev at) {
-  __shared__ __attribute__((aligned(16))) uint16_t Ks[kBigTile * kKsStride];
-  __shared__ __attribute__((aligned(16))) uint16_t Vs[kBigTile * kVsStride];
-  __shared__ uint64_t s_mask[kRowsPerBlock];    // bit p: page p of this chunk is listed in the row's agent's diff
+constexpr int kMasterKs = kBigTile * kKsStride, kMasterVs = kBigTile * kVsStride;      // bf16 elements of the two tiles
+constexpr int kMasterLds = (kMasterKs + kMasterVs) * 2 + kRowsPerBlock * 8;            // bytes, with the page masks
 
-  const int session = blockIdx.y / at.n_chunks, chunk = blockIdx.y - session * at.n_chunks;
+// One workgroup of the master pass: KV head h, chunk number `sc` = session * n_chunks + chunk, row block zb.
+// lds: kMasterLds bytes, 16-byte aligned.
+template <bool SEG>
+__device__ __forceinline__ void attend_master_body(const RoundDev& rd, const LayerDev& io, const DiffDev& d, const AttendDev& at,
+                                                   unsigned char* lds, int h, int sc, int zb) {
+  uint16_t* Ks = reinterpret_cast<uint16_t*>(lds);
+  uint16_t* Vs = Ks + kMasterKs;
+  uint64_t* s_mask = reinterpret_cast<uint64_t*>(Vs + kMasterVs);   // bit p: page p of this chunk is listed in the row's agent's diff
+
+  const int session = sc / at.n_chunks, chunk = sc - session * at.n_chunks;
   const SessionDev sd = rd.sess[session];
   const int tok_begin = chunk * at.chunk_tokens;
   if (tok_begin >= sd.span || sd.n_agents == 0) return;
   const int rows = sd.n_agents * at.n_q * at.group;
-  const int row_begin = blockIdx.z * kRowsPerBlock;
+  const int row_begin = zb * kRowsPerBlock;
   if (row_begin >= rows) return;
-  const int h = blockIdx.x;
   const int T = rd.page_tokens;
   const int tok_end = min(sd.span, tok_begin + at.chunk_tokens);
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, n = lane & 31, hh = lane >> 5;
@@ -516,21 +520,32 @@ __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(2, 2))) 
   // wavefront instruction; both tiles are kept row-major in LDS (the V operands are read with transposing loads)
   const int st_tok = threadIdx.x >> 4, st_pc = threadIdx.x & 15;
 
-  // 64 tokens per step: the next step's rows travel from HBM to registers while this one is multiplied
+  // 64 tokens per step: the next step's rows travel from HBM to registers while this one is multiplied.
+  // kp / vp follow this thread's piece of the rows of the chunk (thread t: token t / 16 of each group of 16,
+  // piece t % 16); a step whose 64 tokens all lie inside the span needs no bounds checks.
   u32x4 kv[8];
-  auto fetch = [&](int t0) {
-    const u32x4 z = {0, 0, 0, 0};
+  const int64_t row16 = 16 * row_u4;                           // sixteen token rows, in 16-byte units
+  const u32x4* kp = io.master_k + (sd.master_row0 + tok_begin + st_tok) * row_u4 + h * head_u4 + st_pc;
+  const u32x4* vp = io.master_v + (sd.master_row0 + tok_begin + st_tok) * row_u4 + h * head_u4 + st_pc;
+  auto fetch = [&](int t0) {                                   // advances kp / vp past the step
+    if (t0 + kBigTile <= tok_end) {
 #pragma unroll
-    for (int e = 0; e < 4; ++e) {
-      const int m = t0 + 16 * e + st_tok;
-      kv[e] = z; kv[4 + e] = z;
-      if (m < tok_end) {
-        const int64_t at_u4 = (sd.master_row0 + m) * row_u4 + h * head_u4 + st_pc;
-        kv[e] = __builtin_nontemporal_load(io.master_k + at_u4); kv[4 + e] = __builtin_nontemporal_load(io.master_v + at_u4);
+      for (int e = 0; e < 4; ++e) { kv[e] = __builtin_nontemporal_load(kp + e * row16); kv[4 + e] = __builtin_nontemporal_load(vp + e * row16); }
+    } else {
+      const u32x4 z = {0, 0, 0, 0};
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        kv[e] = z; kv[4 + e] = z;
+        if (t0 + 16 * e + st_tok < tok_end) { kv[e] = __builtin_nontemporal_load(kp + e * row16); kv[4 + e] = __builtin_nontemporal_load(vp + e * row16); }
       }
     }
+    kp += 4 * row16; vp += 4 * row16;
   };
   fetch(tok_begin);
+  uint32_t touch = 0;
+  // thread t looks after line t % 2 of the K (t % 4 < 2) or V row of token t / 4, two steps ahead
+  const u32x4* tp = ((threadIdx.x & 2) ? io.master_v : io.master_k) +
+                    (sd.master_row0 + tok_begin + 2 * kBigTile + (threadIdx.x >> 2)) * row_u4 + h * head_u4 + (threadIdx.x & 1) * 8;
   // one 64-token step; WHOLE: all 64 tokens lie inside the span (every step but a ragged last one)
   auto step = [&](int t0, auto whole_tag) {
     constexpr bool WHOLE = decltype(whole_tag)::value;
@@ -542,6 +557,13 @@ __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(2, 2))) 
     }
     __syncthreads();
     if (WHOLE && t0 + kBigTile < tok_end) fetch(t0 + kBigTile);
+    // The step after that is called into the caches now: one 4-byte read per 128-byte line of its K and V
+    // rows (64 tokens x 2 lines x 2 planes = one line per thread), so that its rows, fetched a step from
+    // now, come from L2 instead of HBM.  The value is not used.
+    if (WHOLE) {
+      if (t0 + 2 * kBigTile + (int)(threadIdx.x >> 2) < tok_end) touch = *reinterpret_cast<const uint32_t*>(tp);
+      tp += 4 * row16;
+    }
     // which of this lane's 32 scores take part: 16-token groups follow the page mask of the row's agent
     // (m4: bit g set = the g-th group of 16 tokens of this step takes part)
     uint32_t m4;
@@ -599,6 +621,7 @@ __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(2, 2))) 
   const int whole_end = tok_begin + (tok_end - tok_begin) / kBigTile * kBigTile;
   for (int t0 = tok_begin; t0 < whole_end; t0 += kBigTile) step(t0, std::true_type{});
   if (whole_end < tok_end) step(whole_end, std::false_type{});
+  asm volatile("" : : "v"(touch));                             // keeps the reads above alive
 
   const float l_tot = rs.l_run + __shfl_xor(rs.l_run, 32);
   if (mine.agent >= 0) {
@@ -611,6 +634,13 @@ __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(2, 2))) 
         po[(32 * b + 8 * q4 + 4 * hh) >> 2] = make_float4(rs.oacc[b][4 * q4], rs.oacc[b][4 * q4 + 1], rs.oacc[b][4 * q4 + 2], rs.oacc[b][4 * q4 + 3]);
     if (hh == 0) { at.part_m[slot] = rs.m_run; at.part_l[slot] = l_tot; }
   }
+}
+
+template <bool SEG>
+__global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(2, 2))) void tdk_attend_master_kernel(const RoundDev rd, const LayerDev io, const DiffDev d,
+                                                                   const AttendDev at) {
+  __shared__ __attribute__((aligned(16))) unsigned char lds[kMasterLds];
+  attend_master_body<SEG>(rd, io, d, at, lds, blockIdx.x, blockIdx.y, blockIdx.z);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -787,12 +817,11 @@ __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(2, 2))) 
 // piece lies past the end of the agent's list leave at once (the merge knows how many pieces an agent has).
 constexpr int kPieceTiles = 16;                // 512 listed tokens per piece
 
+// Vs: this wavefront's V tile, kTile * kVsStride bf16 elements (the K rows go straight from the payload into
+// the MFMA operand registers); lane: 0..63
 template <bool SEGMOVED>
-__global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2, 2))) void tdk_attend_diff16_kernel(const RoundDev rd, const DiffDev d, const AttendDev at) {
-  // the V tile (the K rows go straight from the payload into the MFMA operand registers)
-  __shared__ __attribute__((aligned(16))) uint16_t Vs[kTile * kVsStride];
-
-  const int h = blockIdx.x, agent = blockIdx.y, piece = blockIdx.z;
+__device__ __forceinline__ void attend_diff16_body(const RoundDev& rd, const DiffDev& d, const AttendDev& at, uint16_t* Vs,
+                                                   int h, int agent, int piece, int lane) {
   const int T = rd.page_tokens;
   int64_t lo = d.offset[agent], hi = lo + d.count[agent];
   if (lo < 0) lo = 0;
@@ -804,7 +833,7 @@ __global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2, 2))) void
   const int per_agent = at.n_q * at.group;     // at most 16: one row block
   const AgentDev ad = rd.agents[agent];
   const SessionDev sd = rd.sess[ad.session];
-  const int lane = threadIdx.x, n = lane & 15, g4 = lane >> 4;
+  const int n = lane & 15, g4 = lane >> 4;
   const int64_t row_e = (int64_t)rd.heads * kHeadDim, page_e = (int64_t)T * row_e;
   const uint16_t* pay = reinterpret_cast<const uint16_t*>(d.payload);
 
@@ -935,6 +964,54 @@ __global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2, 2))) void
   }
 }
 
+template <bool SEGMOVED>
+__global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2, 2))) void tdk_attend_diff16_kernel(const RoundDev rd, const DiffDev d, const AttendDev at) {
+  __shared__ __attribute__((aligned(16))) uint16_t Vs[kTile * kVsStride];
+  attend_diff16_body<SEGMOVED>(rd, d, at, Vs, blockIdx.x, blockIdx.y, blockIdx.z, threadIdx.x);
+}
+
+// Both passes in one launch, for rounds with identity layouts whose stored diffs have not moved and few query
+// rows per agent: the master pass is bound by arithmetic and LDS latency, the listed-pages pass by HBM, and
+// sharing the compute units lets each fill the other's gaps.  Workgroup ids alternate between the two kinds
+// while both last (a workgroup of the listed-pages kind = four wavefronts = four KV heads of one agent's
+// piece 0), then come the rest of the longer kind and last the pieces past 0, most of which leave at once.
+struct FusedGrid {
+  int32_t n_master;      // workgroups of the master pass: heads * (sessions * chunks) * row blocks
+  int32_t master_y;      // sessions * chunks
+  int32_t n_diff0;       // workgroups of the listed-pages pass per piece: agents * head_groups
+  int32_t head_groups;   // ceil(heads / 4)
+};
+
+constexpr int kFusedLds = kMasterLds > kWaves * kTile * kVsStride * 2 ? kMasterLds : kWaves * kTile * kVsStride * 2;
+
+__global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(2, 2))) void tdk_attend_fused_kernel(const RoundDev rd, const LayerDev io, const DiffDev d,
+                                                                  const AttendDev at, const FusedGrid fg) {
+  __shared__ __attribute__((aligned(16))) unsigned char lds[kFusedLds];
+  const int bid = blockIdx.x;
+  const int both = 2 * min(fg.n_master, fg.n_diff0);
+  int m_id = -1, d_id = -1;
+  if (bid < both) {
+    if (bid & 1) d_id = bid >> 1; else m_id = bid >> 1;
+  } else {
+    const int r = bid - both;
+    if (fg.n_master > fg.n_diff0) {
+      if (r < fg.n_master - fg.n_diff0) m_id = fg.n_diff0 + r; else d_id = fg.n_diff0 + (r - (fg.n_master - fg.n_diff0));
+    } else {
+      d_id = fg.n_master + r;
+    }
+  }
+  if (m_id >= 0) {
+    const int h = m_id % rd.heads, rest = m_id / rd.heads;
+    attend_master_body<false>(rd, io, d, at, lds, h, rest % fg.master_y, rest / fg.master_y);
+  } else {
+    const int piece = d_id / fg.n_diff0, rem = d_id - piece * fg.n_diff0;
+    const int agent = rem / fg.head_groups, h = (rem - agent * fg.head_groups) * kWaves + (threadIdx.x >> 6);
+    if (h >= rd.heads) return;
+    uint16_t* Vs = reinterpret_cast<uint16_t*>(lds) + (threadIdx.x >> 6) * (kTile * kVsStride);
+    attend_diff16_body<false>(rd, d, at, Vs, h, agent, piece, threadIdx.x & 63);
+  }
+}
+
 // ---------------------------------------------------------------------------------------------
 // merge: out = sum_c o_c e^(m_c - M) / sum_c l_c e^(m_c - M), lse = M + log(that sum); one wavefront per row
 // ---------------------------------------------------------------------------------------------
@@ -1028,6 +1105,19 @@ hipError_t launch_attend_diff(const RoundDev& rd, const DiffDev& d, const Attend
 }
 
 int attend_piece_tokens() { return kPieceTiles * kTile; }
+
+hipError_t launch_attend_fused(const RoundDev& rd, const LayerDev& io, const DiffDev& d, const AttendDev& at,
+                               int max_rows, hipStream_t st) {
+  FusedGrid fg;
+  fg.master_y = rd.n_sessions * at.n_chunks;
+  fg.n_master = rd.heads * fg.master_y * ((max_rows + kRowsPerBlock - 1) / kRowsPerBlock);
+  fg.head_groups = (rd.heads + kWaves - 1) / kWaves;
+  fg.n_diff0 = rd.n_agents * fg.head_groups;
+  const int64_t blocks = (int64_t)fg.n_master + (int64_t)fg.n_diff0 * at.n_pieces;
+  if (blocks == 0) return hipSuccess;
+  hipLaunchKernelGGL(tdk_attend_fused_kernel, dim3((unsigned)blocks), dim3(kBlock), 0, st, rd, io, d, at, fg);
+  return hipGetLastError();
+}
 
 hipError_t launch_attend_merge(const RoundDev& rd, const DiffDev& d, const AttendDev& at, hipStream_t st) {
   const int64_t rows = (int64_t)rd.n_agents * at.n_q * at.n_q_heads;

@@ -139,6 +139,9 @@ hipError_t launch_attend_master(const RoundDev& rd, const LayerDev& io, const Di
                                 int max_rows, hipStream_t st);
 hipError_t launch_attend_diff(const RoundDev& rd, const DiffDev& d, const AttendDev& at, hipStream_t st);
 hipError_t launch_attend_merge(const RoundDev& rd, const DiffDev& d, const AttendDev& at, hipStream_t st);
+// master pass and listed-pages pass in one launch (identity layouts, stored diffs not moved, few rows per agent)
+hipError_t launch_attend_fused(const RoundDev& rd, const LayerDev& io, const DiffDev& d, const AttendDev& at,
+                               int max_rows, hipStream_t st);
 int attend_piece_tokens();   // listed tokens per piece of the listed-pages pass when it splits the lists
 
 hipError_t launch_page_fill(u32x4* dst, const int32_t* ids, int n_pages, int page_u4, uint32_t word, hipStream_t st);
