@@ -80,6 +80,7 @@ struct tdk_round {
   int64_t total_tokens = 0;        // sum over agents of their session's span
   int32_t max_segments = 1;        // most segments any agent has (1 for identity layouts)
   bool seg_moved = false;          // a segmented agent's stored diff sits at other positions
+  bool diff_moved = false;         // some agent's stored diff sits at other positions (segmented or not)
 
   bool timing = false;
   std::vector<EventPair> pending;
@@ -407,6 +408,7 @@ tdk_status round_create(const tdk_model* model, const tdk_session* sessions, int
     if (a.n_segments == 0 && a.diff_pos0 < 0) { return fail(TDK_ERR_INVALID_ARG, "agent: negative diff_pos0"); }
     ad.diff_rot = a.n_segments ? 0 : a.diff_pos0 != a.dst_pos0;
     for (int32_t q = 0; q < a.n_segments; ++q) ad.diff_rot |= a.segments[q].diff_pos != a.segments[q].dst_pos;
+    if (ad.diff_rot) r->diff_moved = true;
     score_off += S;
     {
       // only pages that hold shared tokens count (the hull of a permuted layout may contain others)
@@ -853,13 +855,14 @@ tdk_status tdk_attend_shared(tdk_round* r, int32_t layer, const tdk_layer_io* io
     hipStream_t s = static_cast<hipStream_t>(hip_stream);
     const LayerDev l = layer_dev(io);
     const DiffDev d = diff_dev(in);
-    TDK_LAUNCH(r, TDK_KERNEL_ATTEND_QROT, s, launch_attend_qrot(r->rd, at, s));
     // blocks of the two passes share one launch when the round allows it (timed as the master pass)
     const int64_t fused_blocks = (int64_t)r->model.num_kv_heads * r->rd.n_sessions * p.n_chunks * ((p.max_rows + 127) / 128) +
                                  (int64_t)r->n_agents * ((r->model.num_kv_heads + 3) / 4) * p.n_pieces;
-    if (!r->rd.seg && at.diff_seg == 1 && p.piece_tokens > 0 && r->total_master_rows > 0 && fused_blocks < (1 << 30)) {
+    if (!r->rd.seg && !r->diff_moved && p.piece_tokens > 0 && r->total_master_rows > 0 && fused_blocks < (1 << 30)) {
+      // (this launch rotates the query rows itself: no qrot kernel)
       TDK_LAUNCH(r, TDK_KERNEL_ATTEND_MASTER, s, launch_attend_fused(r->rd, l, d, at, p.max_rows, s));
     } else {
+      TDK_LAUNCH(r, TDK_KERNEL_ATTEND_QROT, s, launch_attend_qrot(r->rd, at, s));
       TDK_LAUNCH(r, TDK_KERNEL_ATTEND_MASTER, s, launch_attend_master(r->rd, l, d, at, p.max_rows, s));
       TDK_LAUNCH(r, TDK_KERNEL_ATTEND_DIFF, s, launch_attend_diff(r->rd, d, at, s));
     }

@@ -437,9 +437,12 @@ constexpr int kMasterLds = (kMasterKs + kMasterVs) * 2 + kRowsPerBlock * 8;     
 
 // One workgroup of the master pass: KV head h, chunk number `sc` = session * n_chunks + chunk, row block zb.
 // lds: kMasterLds bytes, 16-byte aligned.
-template <bool SEG>
+// QDIRECT (identity layouts only): the query rows are rotated back here, from the caller's q, instead of
+// being read from the copies the qrot kernel leaves (same arithmetic, so the same bits).
+template <bool SEG, bool QDIRECT = false>
 __device__ __forceinline__ void attend_master_body(const RoundDev& rd, const LayerDev& io, const DiffDev& d, const AttendDev& at,
                                                    unsigned char* lds, int h, int sc, int zb) {
+  static_assert(!(SEG && QDIRECT), "one rotation per row only");
   uint16_t* Ks = reinterpret_cast<uint16_t*>(lds);
   uint16_t* Vs = Ks + kMasterKs;
   uint64_t* s_mask = reinterpret_cast<uint64_t*>(Vs + kMasterVs);   // bit p: page p of this chunk is listed in the row's agent's diff
@@ -499,7 +502,7 @@ __device__ __forceinline__ void attend_master_body(const RoundDev& rd, const Lay
     seg_n = rd.seg_off[mine.agent + 1] - seg_base;
     while (seg_k + 1 < seg_n && rd.seg_src[seg_base + seg_k + 1] <= tok_begin) ++seg_k;
   }
-  if (!SEG) {
+  if (!SEG && !QDIRECT) {
     const u32x4* qp = reinterpret_cast<const u32x4*>(reinterpret_cast<const uint16_t*>(at.qrot) + mine.out * kHeadDim);
 #pragma unroll
     for (int kk = 0; kk < 8; ++kk) {
@@ -507,6 +510,53 @@ __device__ __forceinline__ void attend_master_body(const RoundDev& rd, const Lay
       if (mine.agent >= 0) v = qp[2 * kk + hh];
       qf[kk] = __builtin_bit_cast(bf16x8, v);
     }
+  }
+  if (QDIRECT) {
+    // fragment kk of a lane = elements 16 kk + 8 hh .. + 7 of its row.  Rotation by -delta of the pair (a, b):
+    // y_a = x_a cos + x_b sin, y_b = x_b cos - x_a sin, with pair j = (j, j + 64) or (2 j, 2 j + 1).
+    u32x4 raw[8];
+    const u32x4* qp = reinterpret_cast<const u32x4*>(reinterpret_cast<const uint16_t*>(at.q) + mine.out * kHeadDim);
+    const uint32_t flip = at.q_flip ? 0x80008000u : 0u;
+#pragma unroll
+    for (int kk = 0; kk < 8; ++kk) {
+      u32x4 v = {0, 0, 0, 0};
+      if (mine.agent >= 0) v = qp[2 * kk + hh];
+      raw[kk] = u32x4{v.x ^ flip, v.y ^ flip, v.z ^ flip, v.w ^ flip};
+    }
+    const float* tab = rd.tab + (size_t)(mine.agent >= 0 ? mine.agent : 0) * (2 * kHalf);
+    auto lo16 = [](uint32_t w) { return __uint_as_float(w << 16); };
+    auto hi16 = [](uint32_t w) { return __uint_as_float(w & 0xffff0000u); };
+    u32x4 rot[8];
+    if (!rd.interleaved) {
+#pragma unroll
+      for (int kk = 0; kk < 4; ++kk) {           // fragments kk (elements a) and kk + 4 (elements b = a + 64)
+        u32x4 ya, yb;
+#pragma unroll
+        for (int w = 0; w < 4; ++w) {
+          const int j = 16 * kk + 8 * hh + 2 * w;
+          const float c0 = tab[j], s0 = tab[kHalf + j], c1 = tab[j + 1], s1 = tab[kHalf + j + 1];
+          const float a0 = lo16(raw[kk][w]), a1 = hi16(raw[kk][w]), b0 = lo16(raw[kk + 4][w]), b1 = hi16(raw[kk + 4][w]);
+          ya[w] = pack2(__builtin_fmaf(a0, c0, __fmul_rn(b0, s0)), __builtin_fmaf(a1, c1, __fmul_rn(b1, s1)));
+          yb[w] = pack2(__builtin_fmaf(b0, c0, -__fmul_rn(a0, s0)), __builtin_fmaf(b1, c1, -__fmul_rn(a1, s1)));
+        }
+        rot[kk] = ya; rot[kk + 4] = yb;
+      }
+    } else {
+#pragma unroll
+      for (int kk = 0; kk < 8; ++kk) {           // word w of a fragment holds the pair j = 8 kk + 4 hh + w
+        u32x4 y;
+#pragma unroll
+        for (int w = 0; w < 4; ++w) {
+          const int j = 8 * kk + 4 * hh + w;
+          const float c = tab[j], sn = tab[kHalf + j];
+          const float a = lo16(raw[kk][w]), b = hi16(raw[kk][w]);
+          y[w] = pack2(__builtin_fmaf(a, c, __fmul_rn(b, sn)), __builtin_fmaf(b, c, -__fmul_rn(a, sn)));
+        }
+        rot[kk] = y;
+      }
+    }
+#pragma unroll
+    for (int kk = 0; kk < 8; ++kk) qf[kk] = __builtin_bit_cast(bf16x8, rot[kk]);
   }
   __syncthreads();
   const uint64_t my_mask = s_mask[wave * kRowsPerWave + n];
@@ -819,7 +869,7 @@ constexpr int kPieceTiles = 16;                // 512 listed tokens per piece
 
 // Vs: this wavefront's V tile, kTile * kVsStride bf16 elements (the K rows go straight from the payload into
 // the MFMA operand registers); lane: 0..63
-template <bool SEGMOVED>
+template <bool SEGMOVED, bool QDIRECT = false>
 __device__ __forceinline__ void attend_diff16_body(const RoundDev& rd, const DiffDev& d, const AttendDev& at, uint16_t* Vs,
                                                    int h, int agent, int piece, int lane) {
   const int T = rd.page_tokens;
@@ -843,13 +893,16 @@ __device__ __forceinline__ void attend_diff16_body(const RoundDev& rd, const Dif
   const int64_t out = ((int64_t)agent * at.n_q + qi) * at.n_q_heads + h * at.group + g;
   bf16x8 qf[4];
   auto load_q = [&](int k) {
-    const u32x4* qp = reinterpret_cast<const u32x4*>(reinterpret_cast<const uint16_t*>(at.qdiff) +
-                                                       (out * at.diff_seg + k) * kHeadDim);
+    // QDIRECT (stored diffs not moved): the listed pages meet the caller's rows as they are (but for the sign)
+    const u32x4* qp = QDIRECT ? reinterpret_cast<const u32x4*>(reinterpret_cast<const uint16_t*>(at.q) + out * kHeadDim)
+                              : reinterpret_cast<const u32x4*>(reinterpret_cast<const uint16_t*>(at.qdiff) +
+                                                               (out * at.diff_seg + k) * kHeadDim);
+    const uint32_t flip = QDIRECT && at.q_flip ? 0x80008000u : 0u;
 #pragma unroll
     for (int kk = 0; kk < 4; ++kk) {
       u32x4 v = {0, 0, 0, 0};
       if (row_ok) v = qp[4 * kk + g4];
-      qf[kk] = __builtin_bit_cast(bf16x8, v);
+      qf[kk] = __builtin_bit_cast(bf16x8, u32x4{v.x ^ flip, v.y ^ flip, v.z ^ flip, v.w ^ flip});
     }
   };
   if (!SEGMOVED) load_q(0);
@@ -1002,13 +1055,13 @@ __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(2, 2))) 
   }
   if (m_id >= 0) {
     const int h = m_id % rd.heads, rest = m_id / rd.heads;
-    attend_master_body<false>(rd, io, d, at, lds, h, rest % fg.master_y, rest / fg.master_y);
+    attend_master_body<false, true>(rd, io, d, at, lds, h, rest % fg.master_y, rest / fg.master_y);
   } else {
     const int piece = d_id / fg.n_diff0, rem = d_id - piece * fg.n_diff0;
     const int agent = rem / fg.head_groups, h = (rem - agent * fg.head_groups) * kWaves + (threadIdx.x >> 6);
     if (h >= rd.heads) return;
     uint16_t* Vs = reinterpret_cast<uint16_t*>(lds) + (threadIdx.x >> 6) * (kTile * kVsStride);
-    attend_diff16_body<false>(rd, d, at, Vs, h, agent, piece, threadIdx.x & 63);
+    attend_diff16_body<false, true>(rd, d, at, Vs, h, agent, piece, threadIdx.x & 63);
   }
 }
 
