@@ -1097,6 +1097,7 @@ __global__ __launch_bounds__(kBlock) void tdk_attend_merge_kernel(const RoundDev
   }
 #pragma unroll
   for (int sft = 32; sft > 0; sft >>= 1) M = fmaxf(M, __shfl_xor(M, sft));
+  // lane l keeps output elements 2 l and 2 l + 1; the parts' rows are requested eight at a time, before any is used
   float L = 0.f, a0 = 0.f, a1 = 0.f;
   for (int c0 = 0; c0 < used; c0 += 64) {
     const int c = c0 + lane;
@@ -1106,18 +1107,28 @@ __global__ __launch_bounds__(kBlock) void tdk_attend_merge_kernel(const RoundDev
       if (m != -INFINITY) { w = __expf(m - M); L = __builtin_fmaf(at.part_l[base + part_of(c)], w, L); }
     }
     const int cnt = min(64, used - c0);
-    for (int j = 0; j < cnt; ++j) {
-      const float wj = __shfl(w, j);
-      const float* po = at.part_o + (base + part_of(c0 + j)) * kHeadDim;
-      a0 = __builtin_fmaf(__builtin_nontemporal_load(po + lane), wj, a0);
-      a1 = __builtin_fmaf(__builtin_nontemporal_load(po + 64 + lane), wj, a1);
+    for (int j0 = 0; j0 < cnt; j0 += 8) {
+      f32x2a v[8];
+#pragma unroll
+      for (int j = 0; j < 8; ++j) {
+        v[j] = f32x2a{0.f, 0.f};
+        if (j0 + j < cnt)
+          v[j] = __builtin_nontemporal_load(reinterpret_cast<const f32x2a*>(at.part_o + (base + part_of(c0 + j0 + j)) * kHeadDim) + lane);
+      }
+#pragma unroll
+      for (int j = 0; j < 8; ++j) {
+        const float wj = __shfl(w, (j0 + j) & 63);           // 0 for a part that does not exist or is empty
+        if (j0 + j < cnt && wj != 0.f) {                     // (an empty part's row was never written)
+          a0 = __builtin_fmaf(v[j].x, wj, a0);
+          a1 = __builtin_fmaf(v[j].y, wj, a1);
+        }
+      }
     }
   }
 #pragma unroll
   for (int sft = 32; sft > 0; sft >>= 1) L += __shfl_xor(L, sft);
   const float inv = L > 0.f ? 1.f / L : 0.f;
-  at.out[row * kHeadDim + lane] = a0 * inv;
-  at.out[row * kHeadDim + 64 + lane] = a1 * inv;
+  reinterpret_cast<float2*>(at.out + row * kHeadDim)[lane] = make_float2(a0 * inv, a1 * inv);
   if (lane == 0) at.lse[row] = L > 0.f ? M + __logf(L) : -INFINITY;
 }
 
