@@ -1025,9 +1025,8 @@ __global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2, 2))) void
 
 // Both passes in one launch, for rounds with identity layouts whose stored diffs have not moved and few query
 // rows per agent: the master pass is bound by arithmetic and LDS latency, the listed-pages pass by HBM, and
-// sharing the compute units lets each fill the other's gaps.  Workgroup ids alternate between the two kinds
-// while both last (a workgroup of the listed-pages kind = four wavefronts = four KV heads of one agent's
-// piece 0), then come the rest of the longer kind and last the pieces past 0, most of which leave at once.
+// sharing the compute units lets each fill the other's gaps.  A workgroup of the listed-pages kind = four
+// wavefronts = four KV heads of one agent's piece; the pieces past 0, most of which leave at once, come last.
 struct FusedGrid {
   int32_t n_master;      // workgroups of the master pass: heads * (sessions * chunks) * row blocks
   int32_t master_y;      // sessions * chunks
@@ -1041,17 +1040,16 @@ __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(2, 2))) 
                                                                   const AttendDev at, const FusedGrid fg) {
   __shared__ __attribute__((aligned(16))) unsigned char lds[kFusedLds];
   const int bid = blockIdx.x;
-  const int both = 2 * min(fg.n_master, fg.n_diff0);
+  // ids alternate between the kinds in groups of eight while both last (consecutive ids go to different XCDs,
+  // so both kinds reach every XCD), then come the master workgroups that are left, then the other kind's
+  const int groups = min(fg.n_master, fg.n_diff0) >> 3;
   int m_id = -1, d_id = -1;
-  if (bid < both) {
-    if (bid & 1) d_id = bid >> 1; else m_id = bid >> 1;
+  if (bid < 16 * groups) {
+    const int at8 = (bid >> 4) * 8 + (bid & 7);
+    if (bid & 8) d_id = at8; else m_id = at8;
   } else {
-    const int r = bid - both;
-    if (fg.n_master > fg.n_diff0) {
-      if (r < fg.n_master - fg.n_diff0) m_id = fg.n_diff0 + r; else d_id = fg.n_diff0 + (r - (fg.n_master - fg.n_diff0));
-    } else {
-      d_id = fg.n_master + r;
-    }
+    const int r = bid - 16 * groups, m_left = fg.n_master - 8 * groups;
+    if (r < m_left) m_id = 8 * groups + r; else d_id = 8 * groups + (r - m_left);
   }
   if (m_id >= 0) {
     const int h = m_id % rd.heads, rest = m_id / rd.heads;
