@@ -667,7 +667,7 @@ def attend_mode(args, tdk, wl, np, torch, dev):
                  config=dict(workload=args.workload, agents=A, span_tokens=int(spec.span_tokens), n_q=n_q, q_heads=Hq,
                              listed_pages=n_pert, workspace_bytes=nbytes),
                  us_per_layer=round(t_att, 2), kernels_avg_us=us,
-                 roofline=dict(bound="hbm", kernel="tdk_attend_shared (4 kernels)", achieved=round(ach, 1), peak=HBM_PEAK_GBPS,
+                 roofline=dict(bound="hbm", kernel="tdk_attend_shared (all its launches)", achieved=round(ach, 1), peak=HBM_PEAK_GBPS,
                                unit="GB/s", frac=round(ach / HBM_PEAK_GBPS, 4), traffic=None, algorithmic_bytes_per_launch=alg),
                  mfma_TFLOPs=round(flops / (t_att * 1e-6) / 1e12, 2),
                  restore_first=dict(decode_us=round(t_dec, 2), read_restored_caches_us=round(t_read, 2),

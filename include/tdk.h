@@ -244,8 +244,10 @@ tdk_status tdk_check_layer(tdk_round* r, int32_t layer, const tdk_layer_io* io, 
  *   workspace  tdk_attend_workspace_bytes(r, n_q, n_q_heads) bytes, 256-byte aligned, contents undefined
  * Arithmetic: each query row is rotated back by the agent's offset (fp32, rounded to bf16) so that all
  * agents of a session multiply the same un-rotated master tiles (bf16 MFMA, fp32 accumulation, softmax
- * weights rounded to bf16 for the second product); listed pages are handled in fp32.  The result
- * agrees with the exact definition to about 1e-2 of the largest |V| (not bit for bit). */
+ * weights rounded to bf16 for the second product); the listed pages go through the same products
+ * from the payload.  The result agrees with the exact definition to about 1e-2 of the largest |V| at
+ * scale = 1 / sqrt(128), in proportion for larger scales (not bit for bit).  Any finite scale is taken:
+ * the kernels work with its magnitude and the query copies carry its sign; zero gives uniform weights. */
 typedef struct {
   const void* q;
   int32_t     n_q;
@@ -265,7 +267,7 @@ size_t tdk_attend_workspace_bytes(const tdk_round* r, int32_t n_q, int32_t n_q_h
  * Master values must be finite.
  * Shaped for decode-like calls (a few query tokens per agent): every block of 128 query rows of a
  * session and KV head reads the tiles again and owns its partial results in the workspace.
- * Allocates nothing, enqueues four kernels, does not synchronise.  Errors: INVALID_ARG (NULL,
+ * Allocates nothing, enqueues two to four kernels, does not synchronise.  Errors: INVALID_ARG (NULL,
  * misaligned, n_q < 1, n_q_heads not a multiple of H, scale not finite, workspace too small). */
 tdk_status tdk_attend_shared(tdk_round* r, int32_t layer, const tdk_layer_io* io, const tdk_diff* in,
                              const tdk_attend_io* a, void* hip_stream);
@@ -330,8 +332,8 @@ tdk_status tdk_restore_layers(tdk_round* r, int32_t first_layer, int32_t n_layer
 #define TDK_KERNEL_SELECT   8
 #define TDK_KERNEL_MASTER   9
 #define TDK_KERNEL_ATTEND_QROT   10
-#define TDK_KERNEL_ATTEND_MASTER 11
-#define TDK_KERNEL_ATTEND_DIFF   12
+#define TDK_KERNEL_ATTEND_MASTER 11   /* also the launch that holds the master and the listed-pages pass together */
+#define TDK_KERNEL_ATTEND_DIFF   12   /* (no launches of its own when that shared launch is used)                  */
 #define TDK_KERNEL_ATTEND_MERGE  13
 #define TDK_KERNEL_KINDS    14
 tdk_status tdk_timing_enable(tdk_round* r, int32_t on);
