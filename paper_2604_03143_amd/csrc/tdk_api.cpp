@@ -776,9 +776,8 @@ bool attend_plan(const tdk_round* r, int32_t n_q, int32_t n_q_heads, AttendPlan&
   }
   p.chunk_tokens = chunk;
   p.n_chunks = (int32_t)((max_span + chunk - 1) / chunk);
-  // the listed-pages pass: with at most 16 query rows per agent and KV head one wavefront takes a piece of an
-  // agent's list and every piece has its own partial result; else one workgroup takes the whole list
-  if ((int64_t)n_q * G <= 16) {
+  // the listed-pages pass: one wavefront takes a piece of an agent's list and every piece has its own partial result
+  {
     int64_t max_pages = 0;
     for (const auto& hs : r->sessions)
       if (!hs.agents.empty()) max_pages = std::max<int64_t>(max_pages, hs.pages);
@@ -858,7 +857,7 @@ tdk_status tdk_attend_shared(tdk_round* r, int32_t layer, const tdk_layer_io* io
     // blocks of the two passes share one launch when the round allows it (timed as the master pass)
     const int64_t fused_blocks = (int64_t)r->model.num_kv_heads * r->rd.n_sessions * p.n_chunks * ((p.max_rows + 127) / 128) +
                                  (int64_t)r->n_agents * ((r->model.num_kv_heads + 3) / 4) * p.n_pieces;
-    if (!r->rd.seg && !r->diff_moved && p.piece_tokens > 0 && r->total_master_rows > 0 && fused_blocks < (1 << 30)) {
+    if (!r->rd.seg && !r->diff_moved && (int64_t)a->n_q * at.group <= 16 && r->total_master_rows > 0 && fused_blocks < (1 << 30)) {
       // (this launch rotates the query rows itself: no qrot kernel)
       TDK_LAUNCH(r, TDK_KERNEL_ATTEND_MASTER, s, launch_attend_fused(r->rd, l, d, at, p.max_rows, s));
     } else {

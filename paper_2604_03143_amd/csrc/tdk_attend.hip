@@ -27,7 +27,6 @@ constexpr int kTile = 32;            // tokens per MFMA tile
 constexpr int kRowsPerWave = 32;     // query rows per wavefront (the N side of the 32x32 MFMA)
 constexpr int kRowsPerBlock = kRowsPerWave * kWaves;
 constexpr int kKsStride = kHeadDim + 8;   // bf16 elements per staged K row (+16 bytes: spreads LDS banks)
-constexpr int kVtStride = kTile + 4;      // bf16 elements per staged V^T row
 constexpr int kBigTile = 2 * kTile;       // tokens per step of the master pass
 constexpr int kVsStride = kHeadDim + 16;  // bf16 elements per staged V row (+32 bytes: four consecutive rows' 32-byte
                                           // pieces then fall into different LDS banks for the transposing reads)
@@ -71,97 +70,12 @@ __device__ __forceinline__ void row_state_init(RowState& st) {
     for (int i = 0; i < 16; ++i) st.oacc[b][i] = 0.f;
 }
 
-// one staged token row (32 bytes of K and of V per thread) into the K tile and the transposed V tile
-template <int VT_STRIDE>
-__device__ __forceinline__ void stage_rows(uint16_t* Ks, uint16_t* Vt, int tok, int part, u32x4 k0, u32x4 k1, u32x4 v0, u32x4 v1) {
-  u32x4* kd = reinterpret_cast<u32x4*>(Ks + tok * kKsStride + part * 16);
-  kd[0] = k0; kd[1] = k1;
-#pragma unroll
-  for (int e = 0; e < 4; ++e) {
-    const int dd = part * 16 + 2 * e;
-    Vt[(dd + 0) * VT_STRIDE + tok] = (uint16_t)(v0[e] & 0xffffu);
-    Vt[(dd + 1) * VT_STRIDE + tok] = (uint16_t)(v0[e] >> 16);
-    Vt[(dd + 8) * VT_STRIDE + tok] = (uint16_t)(v1[e] & 0xffffu);
-    Vt[(dd + 9) * VT_STRIDE + tok] = (uint16_t)(v1[e] >> 16);
-  }
-}
-
 // Orders the LDS traffic of one wavefront (its lanes exchange data through a staging area no other
 // wavefront touches): no hardware barrier, only a point the compiler may not move memory accesses across.
 __device__ __forceinline__ void wave_sync() {
   __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
   __builtin_amdgcn_wave_barrier();
   __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-}
-
-// One 32-token tile for the 32 query rows of a wavefront.
-//   S^T (tokens x rows) = K (tokens x d) * Q^T (d x rows): lane (n, hh) then holds, for row n, the
-//   scores of tokens 8 (i / 4) + 4 hh + i % 4; bit i of `live` says whether that token takes part.
-//   O^T (d x rows) += V^T (d x tokens) * P^T (tokens x rows), contracting over the tokens in the order
-//   the lane holds them, so the weights need no exchange between lanes.
-__device__ __forceinline__ void scores32(const uint16_t* Ks, const bf16x8 (&qf)[8], int n, int hh, f32x16& sacc) {
-#pragma unroll
-  for (int i = 0; i < 16; ++i) sacc[i] = 0.f;
-#pragma unroll
-  for (int kk = 0; kk < 8; ++kk) {
-    const u32x4 a = *reinterpret_cast<const u32x4*>(Ks + n * kKsStride + 16 * kk + 8 * hh);
-    sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a), qf[kk], sacc, 0, 0, 0);
-  }
-}
-
-template <int VT_STRIDE>
-__device__ __forceinline__ void softmax_pv32(const uint16_t* Vt, const f32x16& sacc, float scale, uint32_t live, int n, int hh,
-                                             RowState& st) {
-  float p[16];
-  float mx = -INFINITY;
-#pragma unroll
-  for (int i = 0; i < 16; ++i) {
-    p[i] = ((live >> i) & 1u) ? sacc[i] * scale : -INFINITY;
-    mx = fmaxf(mx, p[i]);
-  }
-  mx = fmaxf(mx, __shfl_xor(mx, 32));
-  // The reference point of the exponentials only has to keep them in range, so it follows the running
-  // maximum lazily: it moves when the maximum has grown by more than kLazy (weights stay below e^kLazy,
-  // far inside fp32 and bf16 range), and the accumulators are rescaled only then.
-  constexpr float kLazy = 8.f;
-  const float m_new = mx > st.m_run + kLazy || st.m_run == -INFINITY ? fmaxf(st.m_run, mx) : st.m_run;
-  const float m_ref = m_new == -INFINITY ? 0.f : m_new;
-  float sum = 0.f;
-#pragma unroll
-  for (int i = 0; i < 16; ++i) { p[i] = __expf(p[i] - m_ref); sum += p[i]; }
-  if (__any(m_new != st.m_run)) {
-    const float alpha = __expf(st.m_run - m_ref);      // 1 for the rows whose reference stays
-    st.l_run *= alpha;
-#pragma unroll
-    for (int b = 0; b < 4; ++b)
-#pragma unroll
-      for (int i = 0; i < 16; ++i) st.oacc[b][i] *= alpha;
-  }
-  st.l_run += sum;
-  st.m_run = m_new;
-#pragma unroll
-  for (int kk = 0; kk < 2; ++kk) {
-    u32x4 pw;
-#pragma unroll
-    for (int e = 0; e < 4; ++e) pw[e] = pack2(p[8 * kk + 2 * e], p[8 * kk + 2 * e + 1]);
-    const bf16x8 pb = __builtin_bit_cast(bf16x8, pw);
-#pragma unroll
-    for (int b = 0; b < 4; ++b) {
-      const uint16_t* vr = Vt + (32 * b + n) * VT_STRIDE + 16 * kk + 4 * hh;
-      const uint2 lo = *reinterpret_cast<const uint2*>(vr);
-      const uint2 hi = *reinterpret_cast<const uint2*>(vr + 8);
-      const u32x4 a = {lo.x, lo.y, hi.x, hi.y};
-      st.oacc[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a), pb, st.oacc[b], 0, 0, 0);
-    }
-  }
-}
-
-template <int VT_STRIDE>
-__device__ __forceinline__ void tile_compute(const uint16_t* Ks, const uint16_t* Vt, const bf16x8 (&qf)[8], float scale,
-                                             uint32_t live, int n, int hh, RowState& st) {
-  f32x16 sacc;
-  scores32(Ks, qf, n, hh, sacc);
-  softmax_pv32<VT_STRIDE>(Vt, sacc, scale, live, n, hh, st);
 }
 
 // The same for a 64-token step held in LDS (two independent score tiles): their MFMA chains interleave,
@@ -210,12 +124,13 @@ __device__ __forceinline__ void scores64(const uint16_t* Ks, const bf16x8 (&qf)[
 typedef short s16x4 __attribute__((ext_vector_type(4)));
 typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
 
-__device__ __forceinline__ void pv64_tr(const uint16_t* Vs, const float (&p)[32], int lane, RowState& st) {
+template <int NK>                             // NK products of 16 tokens each: 4 for a 64-token step, 2 for a 32-token tile
+__device__ __forceinline__ void pv_tr(const uint16_t* Vs, const float (&p)[8 * NK], int lane, RowState& st) {
   const int i16 = lane & 15, blk = lane >> 4;
   const uint16_t* base = Vs + (4 * (blk >> 1) + (i16 >> 2)) * kVsStride + 16 * (blk & 1) + 4 * (i16 & 3);
-  u32x4 va[16];
+  u32x4 va[4 * NK];
 #pragma unroll
-  for (int kk = 0; kk < 4; ++kk)
+  for (int kk = 0; kk < NK; ++kk)
 #pragma unroll
     for (int b = 0; b < 4; ++b) {
       const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(base + (16 * kk) * kVsStride + 32 * b));
@@ -224,7 +139,7 @@ __device__ __forceinline__ void pv64_tr(const uint16_t* Vs, const float (&p)[32]
       va[4 * kk + b] = u32x4{l2.x, l2.y, h2.x, h2.y};
     }
 #pragma unroll
-  for (int kk = 0; kk < 4; ++kk) {
+  for (int kk = 0; kk < NK; ++kk) {
     u32x4 pw;
 #pragma unroll
     for (int e = 0; e < 4; ++e) pw[e] = pack2(p[8 * kk + 2 * e], p[8 * kk + 2 * e + 1]);
@@ -233,6 +148,46 @@ __device__ __forceinline__ void pv64_tr(const uint16_t* Vs, const float (&p)[32]
     for (int b = 0; b < 4; ++b)
       st.oacc[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, va[4 * kk + b]), pb, st.oacc[b], 0, 0, 0);
   }
+}
+
+// One 32-token tile for the 32 query rows of a wavefront, K rows in registers: k[kk] holds, for lane (n, hh),
+// elements 16 kk + 8 hh .. + 7 of the K row of token n.  S^T (tokens x rows) = K Q^T: lane (n, hh) then holds,
+// for query row n, the scores of tokens 8 (i / 4) + 4 hh + i % 4; bit i of `live` says whether that token counts.
+__device__ __forceinline__ void scores32(const u32x4 (&k)[8], const bf16x8 (&qf)[8], f32x16& sacc) {
+#pragma unroll
+  for (int i = 0; i < 16; ++i) sacc[i] = 0.f;
+#pragma unroll
+  for (int kk = 0; kk < 8; ++kk)
+    sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, k[kk]), qf[kk], sacc, 0, 0, 0);
+}
+
+__device__ __forceinline__ void softmax_pv32(const uint16_t* Vs, const f32x16& sacc, float scale, uint32_t live, int lane,
+                                             RowState& st) {
+  float p[16];
+  float mx = -INFINITY;
+#pragma unroll
+  for (int i = 0; i < 16; ++i) {
+    p[i] = ((live >> i) & 1u) ? sacc[i] * scale : -INFINITY;
+    mx = fmaxf(mx, p[i]);
+  }
+  mx = fmaxf(mx, __shfl_xor(mx, 32));
+  constexpr float kLazy = 8.f;
+  const float m_new = mx > st.m_run + kLazy || st.m_run == -INFINITY ? fmaxf(st.m_run, mx) : st.m_run;
+  const float m_ref = m_new == -INFINITY ? 0.f : m_new;
+  float sum = 0.f;
+#pragma unroll
+  for (int i = 0; i < 16; ++i) { p[i] = __expf(p[i] - m_ref); sum += p[i]; }
+  if (__any(m_new != st.m_run)) {
+    const float alpha = __expf(st.m_run - m_ref);      // 1 for the rows whose reference stays
+    st.l_run *= alpha;
+#pragma unroll
+    for (int b = 0; b < 4; ++b)
+#pragma unroll
+      for (int i = 0; i < 16; ++i) st.oacc[b][i] *= alpha;
+  }
+  st.l_run += sum;
+  st.m_run = m_new;
+  pv_tr<2>(Vs, p, lane, st);
 }
 
 __device__ __forceinline__ void softmax_pv64(const uint16_t* Vs, const f32x16& s0, const f32x16& s1, float scale,
@@ -262,7 +217,7 @@ __device__ __forceinline__ void softmax_pv64(const uint16_t* Vs, const f32x16& s
   }
   st.l_run += sum;
   st.m_run = m_new;
-  pv64_tr(Vs, p, lane, st);
+  pv_tr<4>(Vs, p, lane, st);
 }
 
 // The same with whole 16-token groups switched off instead of single tokens, for a positive scale: score i
@@ -299,7 +254,7 @@ __device__ __forceinline__ void softmax_pv64_groups(const uint16_t* Vs, const f3
   }
   st.l_run += sum;
   st.m_run = m_new;
-  pv64_tr(Vs, p, lane, st);
+  pv_tr<4>(Vs, p, lane, st);
 }
 
 // ---- the same tile for 16 query rows per wavefront (v_mfma_f32_16x16x32_bf16): for passes whose row
@@ -333,7 +288,7 @@ __device__ __forceinline__ void scores16(const u32x4 (&k)[8], const bf16x8 (&qf)
   }
 }
 
-// Vs holds the tile's V rows row-major (kVsStride); the A operands come from transposing reads as in pv64_tr:
+// Vs holds the tile's V rows row-major (kVsStride); the A operands come from transposing reads as in pv_tr:
 // lane i of a block of 16 addresses (token i / 4 of the block's four, d-quad i % 4) and receives d = 16 b + i.
 __device__ __forceinline__ void softmax_pv16(const uint16_t* Vs, const f32x4a& s0, const f32x4a& s1, float scale, uint32_t live,
                                              int n, int g, RowState16& st) {
@@ -695,33 +650,40 @@ __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(2, 2))) 
 
 // ---------------------------------------------------------------------------------------------
 // diff pass: the pages an agent's diff lists, from the payload (the "correct" half of skip-or-correct).
-// One workgroup per (agent, KV head); the listed tokens form tiles of 32, wavefront w takes tiles
-// w, w + 4, ... through its own staging area, and the four running results are combined at the end.
+// One wavefront per (agent, KV head, piece): a piece is kPieceTiles consecutive 32-token tiles of the agent's
+// listed tokens and has its own partial result, so there is nothing to combine inside the kernel; workgroups
+// whose piece lies past the end of the agent's list leave at once (the merge knows how many pieces an agent
+// has).  The K rows go straight from the payload into the MFMA operand registers, the V rows through one
+// row-major tile in LDS.  32 query rows at a time; more rows walk the piece again.
 // ---------------------------------------------------------------------------------------------
-constexpr int kWaveLds = kTile * kKsStride + kHeadDim * kVtStride;      // bf16 elements of one wavefront's staging area
-static_assert(kTile * kVsStride <= kHeadDim * kVtStride, "a row-major V tile fits where the transposed one does");
+constexpr int kPieceTiles = 16;                // 512 listed tokens per piece
 
 template <bool SEGMOVED>
-__global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(2, 2))) void tdk_attend_diff_kernel(const RoundDev rd, const DiffDev d, const AttendDev at) {
-  // staging areas during the token loop, then (reused) the four wavefronts' results: [4][32 rows][128 + 2] floats
-  __shared__ __attribute__((aligned(16))) uint16_t lds[kWaves * kWaveLds];
-  static_assert(sizeof(uint16_t) * kWaves * kWaveLds >= sizeof(float) * kWaves * kRowsPerWave * (kHeadDim + 2), "result area");
+__global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2, 2))) void tdk_attend_diff_kernel(const RoundDev rd, const DiffDev d, const AttendDev at) {
+  __shared__ __attribute__((aligned(16))) uint16_t Vs[kTile * kVsStride];
 
-  const int agent = blockIdx.x, h = blockIdx.y;
-  const int per_agent = at.n_q * at.group;
-  const AgentDev ad = rd.agents[agent];
-  const SessionDev sd = rd.sess[ad.session];
+  const int h = blockIdx.x, agent = blockIdx.y, piece = blockIdx.z;
   const int T = rd.page_tokens;
   int64_t lo = d.offset[agent], hi = lo + d.count[agent];
   if (lo < 0) lo = 0;
   if (hi > d.capacity) hi = d.capacity;
   const int n_tok = hi > lo ? (int)((hi - lo) * T) : 0;
   const int n_tiles = (n_tok + kTile - 1) / kTile;
-  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, n = lane & 31, hh = lane >> 5;
-  uint16_t* Ks = lds + wave * kWaveLds;
-  uint16_t* Vt = Ks + kTile * kKsStride;
+  const int tile_begin = piece * kPieceTiles, tile_end = min(n_tiles, tile_begin + kPieceTiles);
+  if (tile_begin >= tile_end) return;
+  const int per_agent = at.n_q * at.group;
+  const AgentDev ad = rd.agents[agent];
+  const SessionDev sd = rd.sess[ad.session];
+  const int lane = threadIdx.x, n = lane & 31, hh = lane >> 5;
   const int64_t row_e = (int64_t)rd.heads * kHeadDim, page_e = (int64_t)T * row_e;
   const uint16_t* pay = reinterpret_cast<const uint16_t*>(d.payload);
+  const int seg_base = SEGMOVED ? rd.seg_off[agent] : 0;
+  const int seg_n = SEGMOVED ? rd.seg_off[agent + 1] - seg_base : 1;
+  // (offsets inside the agent's part of the payload fit 32 bits: at most 2 P pages of 64 KB or less)
+  const uint16_t* apay = pay + lo * 2 * page_e;
+  const uint32_t row_u = (uint32_t)row_e, page_u = (uint32_t)page_e, tile_u = (uint32_t)(kTile / T) * 2u * page_u;
+  auto tok_off = [&](int tk) { return (uint32_t)(tk / T) * 2u * page_u + (uint32_t)(tk % T) * row_u + (uint32_t)(h * kHeadDim); };
+  const int st_row = lane >> 4, st_pc = lane & 15;
 
   for (int r0 = 0; r0 < per_agent; r0 += kRowsPerWave) {
     // this lane's query row of the block
@@ -741,131 +703,110 @@ __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(2, 2))) 
       }
     };
     if (!SEGMOVED) load_q(0);
-    const int seg_base = SEGMOVED ? rd.seg_off[agent] : 0;
-    const int seg_n = SEGMOVED ? rd.seg_off[agent + 1] - seg_base : 1;
-    int seg_next = 0;                            // segment of the token this lane fetched (SEGMOVED only)
     RowState rs;
     row_state_init(rs);
-    // a wavefront's next tile travels from the payload to registers while its current one is multiplied:
-    // 32 tokens x 8 parts of 32 bytes, four (token, part) pairs per lane
-    u32x4 kv[4][4];
-    uint32_t valid_next = 0;                     // bit t: token t of the fetched tile exists and lies inside the span
-    const int st_tok = lane & 31, st_pg = lane >> 5;      // this lane stages parts 4 st_pg .. 4 st_pg + 3 of one token
+    // The next tile travels from the payload to registers while the current one is multiplied.  K: lane
+    // (n, hh) loads what it multiplies, elements 16 kk + 8 hh .. + 7 of the row of token n.  V: sixteen lanes
+    // per 256-byte row, four rows per instruction.  The payload address of a listed token depends on its place
+    // in the list alone, so the rows are requested together with the page number; what the page number decides
+    // (does the token lie inside the span, which segment holds it) is settled when the tile is used.
+    u32x4 kreg[8], vreg[8];
+    int p_next = -1;                             // master page of token lane % 32 of the fetched tile (-1: no such token)
     auto fetch = [&](int tile) {
-      const int t = tile * kTile + st_tok;
+      const int t = tile * kTile + n;
+      const bool there = t < n_tok;
+      p_next = there ? d.idx[lo + t / T] : -1;
       const u32x4 z = {0, 0, 0, 0};
+      const uint32_t tile_off = (uint32_t)tile * tile_u;
+      const uint32_t off = tile_off + tok_off(n) + 8u * hh;
 #pragma unroll
-      for (int j = 0; j < 4; ++j) { kv[j][0] = z; kv[j][1] = z; kv[j][2] = z; kv[j][3] = z; }
+      for (int kk = 0; kk < 8; ++kk) {
+        kreg[kk] = z;
+        if (there) kreg[kk] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(apay + off + 16 * kk));
+      }
+#pragma unroll
+      for (int j = 0; j < 8; ++j) {
+        vreg[j] = z;
+        if (tile * kTile + 4 * j + st_row < n_tok)
+          vreg[j] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(apay + tile_off + tok_off(4 * j + st_row) + page_u + 8u * st_pc));
+      }
+    };
+    fetch(tile_begin);
+    for (int tile = tile_begin; tile < tile_end; ++tile) {
+      wave_sync();                               // the previous tile has been consumed
+      // bit t of valid: token t of the tile exists and lies inside the span (lanes 32..63 repeat lanes 0..31)
+      int seg_cur = 0;
       bool ok = false;
-      if (tile < n_tiles && t < n_tok) {
-        const int64_t slot = lo + t / T;
-        const int rr = t % T, p = d.idx[slot];
+      {
+        const int rr = (tile * kTile + n) % T, p = p_next;
         if (p >= 0 && p < sd.pages && p * T + rr < sd.span) {
           ok = true;
-          if (SEGMOVED) {
-            seg_next = 0;
-            while (seg_next + 1 < seg_n && rd.seg_src[seg_base + seg_next + 1] <= p * T + rr) ++seg_next;
-          }
-          const u32x4* kr = reinterpret_cast<const u32x4*>(pay + (slot * 2) * page_e + rr * row_e + h * kHeadDim) + st_pg * 8;
-          const u32x4* vr = reinterpret_cast<const u32x4*>(pay + (slot * 2 + 1) * page_e + rr * row_e + h * kHeadDim) + st_pg * 8;
-#pragma unroll
-          for (int j = 0; j < 4; ++j) { kv[j][0] = kr[2 * j]; kv[j][1] = kr[2 * j + 1]; kv[j][2] = vr[2 * j]; kv[j][3] = vr[2 * j + 1]; }
+          if (SEGMOVED)
+            while (seg_cur + 1 < seg_n && rd.seg_src[seg_base + seg_cur + 1] <= p * T + rr) ++seg_cur;
         }
       }
-      valid_next = (uint32_t)__ballot(ok);       // lanes 0..31 carry the tokens (lanes 32..63 repeat them)
-    };
-    fetch(wave);
-    for (int it = 0; it * kWaves < n_tiles; ++it) {
-      const int tile = it * kWaves + wave;
-      wave_sync();                               // this wavefront's previous tile has been consumed
-      uint32_t valid = valid_next;
-      const int seg_cur = seg_next;
-      if (tile < n_tiles) {
+      const uint32_t valid = (uint32_t)__ballot(ok);
+      if (valid != 0xffffffffu) {                // rows of tokens that do not count are staged as zeros
+        const u32x4 z = {0, 0, 0, 0};
 #pragma unroll
-        for (int j = 0; j < 4; ++j) stage_rows<kVtStride>(Ks, Vt, st_tok, 4 * st_pg + j, kv[j][0], kv[j][1], kv[j][2], kv[j][3]);
+        for (int j = 0; j < 8; ++j)
+          if (!((valid >> (4 * j + st_row)) & 1u)) vreg[j] = z;     // (their scores are switched off below)
       }
-      wave_sync();                               // the staging area belongs to this wavefront alone
-      if ((it + 1) * kWaves < n_tiles) fetch(tile + kWaves);
-      if (tile < n_tiles) {
-        // score i of a lane belongs to token 8 (i / 4) + 4 hh + i % 4: four nibbles of `valid`
-        const uint32_t vs = valid >> (4 * hh);
-        uint32_t live = (vs & 0xfu) | ((vs >> 4) & 0xf0u) | ((vs >> 8) & 0xf00u) | ((vs >> 12) & 0xf000u);
-        if (!row_ok) live = 0;
-        if (!SEGMOVED) {
-          tile_compute<kVtStride>(Ks, Vt, qf, at.scale, live, n, hh, rs);
-        } else {
-          // the tile's tokens come from up to four segments (two pages, two segments each), stored at
-          // different distances from today's positions: the scores are computed once per segment present,
-          // with the queries turned back by that segment's distance, and every token keeps its own
-          int sid[16];
 #pragma unroll
-          for (int i = 0; i < 16; ++i) sid[i] = __shfl(seg_cur, 8 * (i >> 2) + 4 * hh + (i & 3));
-          f32x16 sacc;
+      for (int j = 0; j < 8; ++j) *reinterpret_cast<u32x4*>(Vs + (4 * j + st_row) * kVsStride + 8 * st_pc) = vreg[j];
+      f32x16 sacc;
+      if (!SEGMOVED) {
+        scores32(kreg, qf, sacc);
+      } else {
+        // the tile's tokens come from up to four segments (two pages, two segments each), stored at
+        // different distances from today's positions: the scores are computed once per segment present,
+        // with the queries turned back by that segment's distance, and every token keeps its own
+        int sid[16];
 #pragma unroll
-          for (int i = 0; i < 16; ++i) sacc[i] = 0.f;
-          int done = -1;
-          while (true) {
-            int cand = (lane < kTile && ((valid >> lane) & 1u) && seg_cur > done) ? seg_cur : 0x7fffffff;
+        for (int i = 0; i < 16; ++i) sid[i] = __shfl(seg_cur, 8 * (i >> 2) + 4 * hh + (i & 3));
 #pragma unroll
-            for (int sft = 32; sft > 0; sft >>= 1) cand = min(cand, __shfl_xor(cand, sft));
-            if (cand == 0x7fffffff) break;
-            load_q(cand);
-            f32x16 pacc;
-            scores32(Ks, qf, n, hh, pacc);
+        for (int i = 0; i < 16; ++i) sacc[i] = 0.f;
+        int done = -1;
+        while (true) {
+          int cand = (lane < kTile && ((valid >> lane) & 1u) && seg_cur > done) ? seg_cur : 0x7fffffff;
 #pragma unroll
-            for (int i = 0; i < 16; ++i)
-              if (sid[i] == cand) sacc[i] = pacc[i];
-            done = cand;
-          }
-          softmax_pv32<kVtStride>(Vt, sacc, at.scale, live, n, hh, rs);
+          for (int sft = 32; sft > 0; sft >>= 1) cand = min(cand, __shfl_xor(cand, sft));
+          if (cand == 0x7fffffff) break;
+          load_q(cand);
+          f32x16 pacc;
+          scores32(kreg, qf, pacc);
+#pragma unroll
+          for (int i = 0; i < 16; ++i)
+            if (sid[i] == cand) sacc[i] = pacc[i];
+          done = cand;
         }
       }
+      wave_sync();                               // the V tile is complete
+      if (tile + 1 < tile_end) fetch(tile + 1);  // the K registers are free: the scores are taken
+      // score i of a lane belongs to token 8 (i / 4) + 4 hh + i % 4: four nibbles of `valid`
+      const uint32_t vs = valid >> (4 * hh);
+      uint32_t live = (vs & 0xfu) | ((vs >> 4) & 0xf0u) | ((vs >> 8) & 0xf00u) | ((vs >> 12) & 0xf000u);
+      if (!row_ok) live = 0;
+      softmax_pv32(Vs, sacc, at.scale, live, lane, rs);
     }
-    // combine the four wavefronts (the staging areas are free now)
-    __syncthreads();
-    float* res = reinterpret_cast<float*>(lds);                          // [4][32][130]: 128 outputs, m, l
-    {
-      float* mine = res + ((size_t)wave * kRowsPerWave + n) * (kHeadDim + 2);
+    // this piece's partial result for the block's rows: lane (n, hh) holds elements 32 b + 8 q + 4 hh + (0..3) of row n
+    const float l_tot = rs.l_run + __shfl_xor(rs.l_run, 32);
+    if (row_ok) {
+      const int64_t slot = out * at.n_parts + at.n_chunks + piece;
+      float4* po = reinterpret_cast<float4*>(at.part_o + slot * kHeadDim);
 #pragma unroll
       for (int b = 0; b < 4; ++b)
 #pragma unroll
-        for (int i = 0; i < 16; ++i) mine[32 * b + 8 * (i >> 2) + 4 * hh + (i & 3)] = rs.oacc[b][i];
-      const float l_tot = rs.l_run + __shfl_xor(rs.l_run, 32);
-      if (hh == 0) { mine[kHeadDim] = rs.m_run; mine[kHeadDim + 1] = l_tot; }
+        for (int q4 = 0; q4 < 4; ++q4)
+          po[(32 * b + 8 * q4 + 4 * hh) >> 2] = make_float4(rs.oacc[b][4 * q4], rs.oacc[b][4 * q4 + 1], rs.oacc[b][4 * q4 + 2], rs.oacc[b][4 * q4 + 3]);
+      if (hh == 0) { at.part_m[slot] = rs.m_run; at.part_l[slot] = l_tot; }
     }
-    __syncthreads();
-    for (int e = threadIdx.x; e < kRowsPerWave * kHeadDim; e += kBlock) {
-      const int row = e >> 7, dd = e & (kHeadDim - 1);
-      const int rem2 = r0 + row;
-      if (rem2 >= per_agent) continue;
-      float M = -INFINITY;
-#pragma unroll
-      for (int w = 0; w < kWaves; ++w) M = fmaxf(M, res[((size_t)w * kRowsPerWave + row) * (kHeadDim + 2) + kHeadDim]);
-      const float m_ref = M == -INFINITY ? 0.f : M;
-      float o = 0.f, l = 0.f;
-#pragma unroll
-      for (int w = 0; w < kWaves; ++w) {
-        const float* rw = res + ((size_t)w * kRowsPerWave + row) * (kHeadDim + 2);
-        const float wgt = __expf(rw[kHeadDim] - m_ref);
-        o = __builtin_fmaf(rw[dd], wgt, o);
-        l = __builtin_fmaf(rw[kHeadDim + 1], wgt, l);
-      }
-      const int qi2 = rem2 / at.group, g2 = rem2 - qi2 * at.group;
-      const int64_t out2 = ((int64_t)agent * at.n_q + qi2) * at.n_q_heads + h * at.group + g2;
-      const int64_t slot = out2 * at.n_parts + (at.n_parts - 1);
-      at.part_o[slot * kHeadDim + dd] = o;
-      if (dd == 0) { at.part_m[slot] = M; at.part_l[slot] = l; }
-    }
-    __syncthreads();
+    wave_sync();                                 // before the next block's first tile overwrites the V tile
   }
 }
 
 // The same pass with 16 query rows per wavefront: used when an agent brings at most 16 rows per KV head
 // (decode: query tokens x heads per KV head), where the 32-row tiles would be five sixths padding.
-// One wavefront per (agent, KV head, piece): a piece is kPieceTiles consecutive tiles of the agent's listed
-// tokens and has its own partial result, so there is nothing to combine inside the kernel; workgroups whose
-// piece lies past the end of the agent's list leave at once (the merge knows how many pieces an agent has).
-constexpr int kPieceTiles = 16;                // 512 listed tokens per piece
 
 // Vs: this wavefront's V tile, kTile * kVsStride bf16 elements (the K rows go straight from the payload into
 // the MFMA operand registers); lane: 0..63
@@ -1074,10 +1015,9 @@ __global__ __launch_bounds__(kBlock) void tdk_attend_merge_kernel(const RoundDev
   const int agent = (int)(row / ((int64_t)at.n_q * at.n_q_heads));
   const int span = rd.sess[rd.agents[agent].session].span;
   const int chunks = (span + at.chunk_tokens - 1) / at.chunk_tokens;
-  // the chunks of this row's span, then the pieces of its agent's listed pages (one piece that is always
-  // written when the listed-pages pass does not split the lists)
-  int pieces = 1;
-  if (at.piece_tokens > 0) {
+  // the chunks of this row's span, then the pieces of its agent's listed pages
+  int pieces;
+  {
     int64_t lo = d.offset[agent], hi = lo + d.count[agent];
     if (lo < 0) lo = 0;
     if (hi > d.capacity) hi = d.capacity;
@@ -1154,14 +1094,13 @@ hipError_t launch_attend_master(const RoundDev& rd, const LayerDev& io, const Di
 
 hipError_t launch_attend_diff(const RoundDev& rd, const DiffDev& d, const AttendDev& at, hipStream_t st) {
   if (rd.n_agents == 0) return hipSuccess;
-  const dim3 grid((unsigned)rd.n_agents, (unsigned)rd.heads);
-  if (at.piece_tokens > 0) {                   // few rows per agent: one wavefront per piece of an agent's list
-    const dim3 grid16((unsigned)rd.heads, (unsigned)rd.n_agents, (unsigned)at.n_pieces);
-    if (at.diff_seg > 1) hipLaunchKernelGGL(tdk_attend_diff16_kernel<true>, grid16, dim3(64), 0, st, rd, d, at);
-    else hipLaunchKernelGGL(tdk_attend_diff16_kernel<false>, grid16, dim3(64), 0, st, rd, d, at);
+  const dim3 grid((unsigned)rd.heads, (unsigned)rd.n_agents, (unsigned)at.n_pieces);    // one wavefront per piece of a list
+  if (at.n_q * at.group <= 16) {
+    if (at.diff_seg > 1) hipLaunchKernelGGL(tdk_attend_diff16_kernel<true>, grid, dim3(64), 0, st, rd, d, at);
+    else hipLaunchKernelGGL(tdk_attend_diff16_kernel<false>, grid, dim3(64), 0, st, rd, d, at);
   } else {
-    if (at.diff_seg > 1) hipLaunchKernelGGL(tdk_attend_diff_kernel<true>, grid, dim3(kBlock), 0, st, rd, d, at);
-    else hipLaunchKernelGGL(tdk_attend_diff_kernel<false>, grid, dim3(kBlock), 0, st, rd, d, at);
+    if (at.diff_seg > 1) hipLaunchKernelGGL(tdk_attend_diff_kernel<true>, grid, dim3(64), 0, st, rd, d, at);
+    else hipLaunchKernelGGL(tdk_attend_diff_kernel<false>, grid, dim3(64), 0, st, rd, d, at);
   }
   return hipGetLastError();
 }
