@@ -661,6 +661,12 @@ def attend_mode(args, tdk, wl, np, torch, dev):
     alg = master_b + payload_b + qo_b
     flops = 4.0 * A * n_q * Hq * D * spec.span_tokens
     ach = alg / (t_att * 1e-6) / 1e9
+    # counter figures exist for the default shape only (one query token, the shared launch + the merge)
+    traffic = None
+    if n_q == 1 and args.q_heads == 0:
+        parts = [read_traffic(args.workload, k, "hbm_traffic_attend") for k in ("tdk_attend_fused_kernel", "tdk_attend_merge_kernel")]
+        if all(x is not None for x in parts):
+            traffic = sum(parts)
     out_d = dict(metric="attention over the shared span of never-restored mirrors: query rows per second; GB/s of master + diff read",
                  value=round(A * n_q * Hq / (t_att * 1e-6), 1), unit="query rows/s", n_gpus=1, steps=reps, higher_is_better=True,
                  dtype="bf16", data="synthetic", vs_baseline=None,
@@ -668,7 +674,7 @@ def attend_mode(args, tdk, wl, np, torch, dev):
                              listed_pages=n_pert, workspace_bytes=nbytes),
                  us_per_layer=round(t_att, 2), kernels_avg_us=us,
                  roofline=dict(bound="hbm", kernel="tdk_attend_shared (all its launches)", achieved=round(ach, 1), peak=HBM_PEAK_GBPS,
-                               unit="GB/s", frac=round(ach / HBM_PEAK_GBPS, 4), traffic=None, algorithmic_bytes_per_launch=alg),
+                               unit="GB/s", frac=round(ach / HBM_PEAK_GBPS, 4), traffic=traffic, algorithmic_bytes_per_launch=alg),
                  mfma_TFLOPs=round(flops / (t_att * 1e-6) / 1e12, 2),
                  restore_first=dict(decode_us=round(t_dec, 2), read_restored_caches_us=round(t_read, 2),
                                     speedup=round((t_dec + t_read) / t_att, 2)),
@@ -677,9 +683,9 @@ def attend_mode(args, tdk, wl, np, torch, dev):
     r.destroy()
 
 
-def read_traffic(workload, kernel):
+def read_traffic(workload, kernel, prefix="hbm_traffic"):
     """HBM bytes per launch of `kernel` from the committed rocprofv3 counter summary (None if absent)."""
-    path = os.path.join(ROOT, "profiles", f"hbm_traffic_{workload}.txt")
+    path = os.path.join(ROOT, "profiles", f"{prefix}_{workload}.txt")
     try:
         for line in open(path):
             f = line.split()
