@@ -50,8 +50,8 @@ _lib: Optional[C.CDLL] = None
 def lib() -> C.CDLL:
     global _lib
     if _lib is None:
-        build()
-        L = C.CDLL(_SO)
+        # TDO_LIBRARY: another build of the same source (the sanitizer test's instrumented one)
+        L = C.CDLL(os.environ.get("TDO_LIBRARY") or build())
         for name in ("tdo_dense_bytes", "tdo_diff_bytes", "tdo_mirror_ratio", "tdo_family_cost"):
             getattr(L, name).restype = C.c_double
         L.tdo_dense_bytes.argtypes = [C.POINTER(Geom), C.c_int64]
