@@ -62,3 +62,50 @@ def test_step_captured_in_a_graph_replays_exactly(tdo):
         for g in runs[1:]:
             g.r.destroy()
         runs[0].close()
+
+
+@pytest.mark.parametrize("n_q", [1, 7])
+def test_attention_call_captured_in_a_graph_replays_exactly(tdo, n_q):
+    """tdk_attend_shared only enqueues kernels too (one launch for both passes with one query token, the separate
+    kernels with seven); every replay, with the workspace and the outputs wiped in between, gives the eager bits."""
+    import torch
+    from paper_2604_03143_amd import tdk
+    import gpu_helpers as gh
+    if not torch.cuda.is_available():
+        pytest.fail("GPU tests need a GPU")
+    spec = wl.RoundSpec("graph2", 59, 1, 4, 128, 16, 1.0e6, 2, 5, 4, 90, 3, 400, 0.25)
+    rnd = wl.make_round(spec)
+    g = gh.GpuRun(rnd, layer=0)
+    try:
+        g.rerotate()
+        wl.perturb_device(rnd, 0, g.pk, g.pv)
+        d = g.encode()
+        Hq = 12
+        gen = torch.Generator(device="cuda"); gen.manual_seed(5)
+        q = torch.randn((rnd.n_agents, n_q, Hq, 128), generator=gen, device="cuda").to(torch.bfloat16).view(torch.int16)
+        nbytes = tdk.tdk_attend_workspace_bytes(g.r, n_q, Hq)
+        ws = torch.empty(nbytes, dtype=torch.uint8, device="cuda")
+        out = torch.empty((rnd.n_agents, n_q, Hq, 128), dtype=torch.float32, device="cuda")
+        lse = torch.empty((rnd.n_agents, n_q, Hq), dtype=torch.float32, device="cuda")
+        a = tdk.attend_io(q, n_q, Hq, 0.09, out, lse, ws, nbytes)
+        tdk.tdk_attend_shared(g.r, 0, g.io, d.c, a, g.stream)
+        torch.cuda.synchronize()
+        want_o, want_l = out.clone(), lse.clone()
+        assert torch.isfinite(want_o).all() and torch.isfinite(want_l).all()
+        side = torch.cuda.Stream()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.stream(side):
+            tdk.tdk_attend_shared(g.r, 0, g.io, d.c, a, side.cuda_stream)
+            side.synchronize()
+            with torch.cuda.graph(graph, stream=side):
+                tdk.tdk_attend_shared(g.r, 0, g.io, d.c, a, torch.cuda.current_stream().cuda_stream)
+        torch.cuda.synchronize()
+        for rep in range(3):
+            ws.fill_(0xFF); out.fill_(float("nan")); lse.fill_(float("nan"))
+            torch.cuda.synchronize()
+            graph.replay()
+            torch.cuda.synchronize()
+            assert torch.equal(out, want_o) and torch.equal(lse, want_l), rep
+    finally:
+        torch.cuda.synchronize()
+        g.close()
