@@ -859,15 +859,27 @@ __global__ __launch_bounds__(kBlock) void tdk_select_kernel(const RoundDev rd, c
       if (key != 0u && (key & mask) == prefix) atomicAdd(&hist[(key >> shift) & 255u], 1u);
     }
     __syncthreads();
-    if (threadIdx.x == 0) {
-      uint32_t need = s_need, cum = 0u;
-      int b = 255;
-      for (; b > 0; --b) {
-        if (cum + hist[b] >= need) break;
-        cum += hist[b];
+    {
+      // the bin that holds the need-th largest key: thread t looks after bin t and knows, from a suffix scan
+      // over the 256 counts, how many keys lie in the bins above it; exactly one bin has above < need <= above + own
+      const uint32_t need = s_need, own = hist[threadIdx.x];
+      const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
+      uint32_t inc = own;                                   // own + the higher bins of this wavefront
+#pragma unroll
+      for (int sft = 1; sft < 64; sft <<= 1) {
+        const uint32_t v = __shfl_down(inc, sft);
+        if (lane + sft < 64) inc += v;
       }
-      s_need = need - cum;
-      s_prefix = prefix | ((uint32_t)b << shift);
+      if (lane == 0) s_wave[wv] = (int)inc;                 // the wavefront's total
+      __syncthreads();
+      uint32_t above = inc - own;
+#pragma unroll
+      for (int q = 0; q < kWaves; ++q)
+        if (q > wv) above += (uint32_t)s_wave[q];
+      if (above < need && above + own >= need) {
+        s_need = need - above;
+        s_prefix = prefix | ((uint32_t)threadIdx.x << shift);
+      }
     }
     mask |= 255u << shift;
     __syncthreads();
