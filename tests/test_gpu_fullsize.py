@@ -1,6 +1,7 @@
 """Parity at the full sizes of the benchmark configurations, one layer, in the launch shape bench.py
 times (automatic agent groups, default flags): sampled agents against the oracle bit for bit, and
-properties that hold at any size for everything else."""
+properties that hold at any size for everything else; then the attention call over the same mirrors, the
+sampled agents against the oracle by tolerance."""
 import numpy as np
 import pytest
 
@@ -96,4 +97,24 @@ def test_full_size_layer(tdo, name):
     tdo.diff_decode(g, hr, hmk, hmv, dk, dv, od)
     assert np.array_equal(pk2[srows].cpu().numpy().view(np.uint16)[shared], dk[shared])
     assert np.array_equal(pv2[srows].cpu().numpy().view(np.uint16)[shared], dv[shared])
+
+    # --- attention over the never-restored mirrors (one query token, 5 query heads per KV head: the shape
+    # bench.py --mode attend times), the sampled agents against the oracle by the tolerances of test_gpu_attend.py
+    n_q, Hq, D = 1, 5 * spec.num_kv_heads, spec.head_dim
+    gen = torch.Generator(device=dev); gen.manual_seed(11)
+    q = torch.randn((A, n_q, Hq, D), generator=gen, device=dev).to(torch.bfloat16).view(torch.int16)
+    out = torch.full((A, n_q, Hq, D), float("nan"), dtype=torch.float32, device=dev)
+    lse = torch.full((A, n_q, Hq), float("nan"), dtype=torch.float32, device=dev)
+    nbytes = tdk.tdk_attend_workspace_bytes(r, n_q, Hq)
+    ws = torch.empty(nbytes, dtype=torch.uint8, device=dev)
+    scale = 1.0 / float(np.sqrt(D))
+    tdk.tdk_attend_shared(r, layer, io, d, tdk.attend_io(q, n_q, Hq, scale, out, lse, ws, nbytes), st)
+    torch.cuda.synchronize()
+    assert bool(torch.isfinite(out).all()) and bool(torch.isfinite(lse).all())
+    pick_d = torch.tensor(pick, device=dev)
+    want_o, want_l = tdo.attend_shared(g, hr, hmk, hmv, od, q[pick_d].cpu().numpy().view(np.uint16), n_q, Hq, scale)
+    err_o = float(np.max(np.abs(out[pick_d].cpu().numpy().astype(np.float64) - want_o)))
+    err_l = float(np.max(np.abs(lse[pick_d].cpu().numpy().astype(np.float64) - want_l)))
+    vmax = float(np.max(np.abs(wl.bf16_bits_to_f32(hmv))))
+    assert err_o <= 1e-2 * max(1.0, vmax) and err_l <= 5e-3, (err_o, err_l)
     r.destroy()
