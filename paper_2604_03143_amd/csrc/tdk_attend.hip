@@ -1022,7 +1022,7 @@ __global__ __launch_bounds__(kBlock) void tdk_attend_merge_kernel(const RoundDev
     if (lo < 0) lo = 0;
     if (hi > d.capacity) hi = d.capacity;
     const int64_t n_tok = hi > lo ? (hi - lo) * rd.page_tokens : 0;
-    pieces = (int)((n_tok + at.piece_tokens - 1) / at.piece_tokens);
+    pieces = (int)min<int64_t>((n_tok + at.piece_tokens - 1) / at.piece_tokens, at.n_pieces);   // (a count beyond the session's pages)
   }
   const int used = chunks + pieces;
   const int64_t base = row * at.n_parts;
