@@ -757,12 +757,12 @@ bool attend_plan(const tdk_round* r, int32_t n_q, int32_t n_q_heads, AttendPlan&
   p.rows = (int64_t)r->n_agents * n_q * n_q_heads;
   // Tokens per workgroup of the master pass.  A workgroup walks its chunk in steps of 64 tokens; two
   // workgroups fit a compute unit at a time, so the pass takes about ceil(workgroups / slots) rounds of
-  // (steps per chunk + a fixed start-up cost of about two steps).  Of the chunk sizes that a 64-bit page
+  // (steps per chunk + a fixed start-up cost of about two steps).  Of the chunk sizes that the 128-bit page
   // mask per query row can cover, the one with the lowest such cost wins; ties go to the larger chunk
   // (fewer partial results to merge).
   const int64_t row_blocks = std::max<int64_t>(1, (max_rows + 127) / 128);
   const int64_t slots = 2 * (int64_t)r->n_cus;
-  const int32_t max_chunk = std::min<int32_t>(64 * r->model.page_tokens, 2048);
+  const int32_t max_chunk = std::min<int32_t>(128 * r->model.page_tokens, 4096);
   int32_t chunk = 64;
   int64_t best = -1;
   for (int32_t c = max_chunk; c >= 64; c -= 64) {

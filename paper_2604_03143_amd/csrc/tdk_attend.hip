@@ -388,7 +388,8 @@ __global__ __launch_bounds__(kBlock) void tdk_attend_qrot_kernel(const RoundDev 
 // grid: x = KV head, y = session * n_chunks + chunk, z = block of 128 query rows
 // ---------------------------------------------------------------------------------------------
 constexpr int kMasterKs = kBigTile * kKsStride, kMasterVs = kBigTile * kVsStride;      // bf16 elements of the two tiles
-constexpr int kMasterLds = (kMasterKs + kMasterVs) * 2 + kRowsPerBlock * 8;            // bytes, with the page masks
+constexpr int kMaskWords = 2;                                                          // 64-bit words of a row's page mask: 128 pages per chunk
+constexpr int kMasterLds = (kMasterKs + kMasterVs) * 2 + kRowsPerBlock * kMaskWords * 8;   // bytes, with the page masks
 
 // One workgroup of the master pass: KV head h, chunk number `sc` = session * n_chunks + chunk, row block zb.
 // lds: kMasterLds bytes, 16-byte aligned.
@@ -415,7 +416,7 @@ __device__ __forceinline__ void attend_master_body(const RoundDev& rd, const Lay
 
   // which pages of this chunk each row's agent lists in its diff (those tokens belong to the other kernel)
   if (threadIdx.x < kRowsPerBlock) {
-    uint64_t mask = 0;
+    uint64_t mask[kMaskWords] = {0, 0};
     const RowRef rr = row_ref(rd, sd, at, h, row_begin + threadIdx.x);
     if (rr.agent >= 0) {
       int64_t lo = d.offset[rr.agent], hi = lo + d.count[rr.agent];
@@ -430,10 +431,12 @@ __device__ __forceinline__ void attend_master_body(const RoundDev& rd, const Lay
       for (; a < hi; ++a) {
         const int p = d.idx[a];
         if (p > pg1 || p < pg0) break;
-        mask |= (uint64_t)1 << (p - pg0);
+        const int rel_p = p - pg0;
+        if (rel_p < 64) mask[0] |= (uint64_t)1 << rel_p; else mask[1] |= (uint64_t)1 << (rel_p - 64);
       }
     }
-    s_mask[threadIdx.x] = mask;
+    s_mask[kMaskWords * threadIdx.x] = mask[0];
+    s_mask[kMaskWords * threadIdx.x + 1] = mask[1];
   }
 
   // this lane's query row: its B operands (8 steps of 16 along the head dimension) stay in registers.
@@ -514,7 +517,7 @@ __device__ __forceinline__ void attend_master_body(const RoundDev& rd, const Lay
     for (int kk = 0; kk < 8; ++kk) qf[kk] = __builtin_bit_cast(bf16x8, rot[kk]);
   }
   __syncthreads();
-  const uint64_t my_mask = s_mask[wave * kRowsPerWave + n];
+  const uint64_t* my_masks = s_mask + kMaskWords * (wave * kRowsPerWave + n);   // (read per step: two registers less)
 
   RowState rs;
   row_state_init(rs);
@@ -575,9 +578,11 @@ __device__ __forceinline__ void attend_master_body(const RoundDev& rd, const Lay
     {
       const uint32_t rel = (uint32_t)(t0 - tok_begin);
       if (T == 16) {
-        m4 = ~(uint32_t)(my_mask >> (rel >> 4)) & 0xfu;                      // four pages of 16 tokens
+        const uint32_t pg = rel >> 4;                                        // four pages of 16 tokens
+        m4 = ~(uint32_t)(my_masks[pg >> 6] >> (pg & 63u)) & 0xfu;
       } else {
-        const uint32_t m2 = ~(uint32_t)(my_mask >> (rel >> 5)) & 0x3u;       // two pages of 32 tokens
+        const uint32_t pg = rel >> 5;                                        // two pages of 32 tokens
+        const uint32_t m2 = ~(uint32_t)(my_masks[pg >> 6] >> (pg & 63u)) & 0x3u;
         m4 = ((m2 & 1u) ? 0x3u : 0u) | ((m2 & 2u) ? 0xcu : 0u);
       }
       if (mine.agent < 0) m4 = 0;

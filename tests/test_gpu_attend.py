@@ -80,7 +80,7 @@ def test_negative_zero_and_large_scales(tdo, scale):
 
 def test_long_span_with_chunks_above_512_tokens(tdo):
     """Four sessions of 10280 tokens on 8 KV heads: on a 256-CU device the planner gives every workgroup of the
-    master pass 704 tokens = 44 pages (the page mask of a row is 64 bits wide)."""
+    master pass 704 tokens = 44 pages (more than one 64-bit word of a row's page mask)."""
     spec = wl.RoundSpec("att7", 67, 1, 8, 128, 16, 1.0e6, 4, 3, 40, 257, 5, 900, 0.1)
     _case(tdo, spec, 1, 8)
 
