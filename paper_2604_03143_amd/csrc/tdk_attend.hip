@@ -234,7 +234,8 @@ __device__ __forceinline__ void softmax_pv64_groups(const uint16_t* Vs, const f3
   for (int i = 0; i < 16; ++i) {
     p[i] = on[i >> 3] ? s0[i] : -INFINITY;
     p[16 + i] = on[2 + (i >> 3)] ? s1[i] : -INFINITY;
-    mx = fmaxf(mx, fmaxf(p[i], p[16 + i]));
+    // (the NaN-propagating maximum: v_maximum3_f32, with no quieting of its operands first)
+    mx = __builtin_elementwise_maximum(mx, __builtin_elementwise_maximum(p[i], p[16 + i]));
   }
   mx = fmaxf(mx, __shfl_xor(mx, 32)) * scale;
   constexpr float kLazy = 8.f;
