@@ -386,7 +386,7 @@ __global__ __launch_bounds__(kBlock) void tdk_attend_qrot_kernel(const RoundDev 
 
 // ---------------------------------------------------------------------------------------------
 // master pass: S^T = K Q'^T and O^T += V^T P^T per 32-token tile, online softmax per query row
-// grid: x = KV head, y = session * n_chunks + chunk, z = block of 128 query rows
+// grid: x = KV head, y = block of 128 query rows, z = session * n_chunks + chunk
 // ---------------------------------------------------------------------------------------------
 constexpr int kMasterKs = kBigTile * kKsStride, kMasterVs = kBigTile * kVsStride;      // bf16 elements of the two tiles
 constexpr int kMaskWords = 2;                                                          // 64-bit words of a row's page mask: 128 pages per chunk
@@ -651,7 +651,7 @@ template <bool SEG>
 __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(2, 2))) void tdk_attend_master_kernel(const RoundDev rd, const LayerDev io, const DiffDev d,
                                                                    const AttendDev at) {
   __shared__ __attribute__((aligned(16))) unsigned char lds[kMasterLds];
-  attend_master_body<SEG>(rd, io, d, at, lds, blockIdx.x, blockIdx.y, blockIdx.z);
+  attend_master_body<SEG>(rd, io, d, at, lds, blockIdx.x, blockIdx.z, blockIdx.y);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -976,7 +976,7 @@ __global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2, 2))) void
 // wavefronts = four KV heads of one agent's piece; the pieces past 0, most of which leave at once, come last.
 struct FusedGrid {
   int32_t n_master;      // workgroups of the master pass: heads * (sessions * chunks) * row blocks
-  int32_t master_y;      // sessions * chunks
+  int32_t row_blocks;    // blocks of 128 query rows per session and KV head
   int32_t n_diff0;       // workgroups of the listed-pages pass per piece: agents * head_groups
   int32_t head_groups;   // ceil(heads / 4)
 };
@@ -1000,7 +1000,9 @@ __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(2, 2))) 
   }
   if (m_id >= 0) {
     const int h = m_id % rd.heads, rest = m_id / rd.heads;
-    attend_master_body<false, true>(rd, io, d, at, lds, h, rest % fg.master_y, rest / fg.master_y);
+    // the row blocks of one (chunk, KV head) get ids 8 apart: same XCD, one after the other, so the second
+    // finds the tiles in that XCD's L2
+    attend_master_body<false, true>(rd, io, d, at, lds, h, rest / fg.row_blocks, rest % fg.row_blocks);
   } else {
     const int piece = d_id / fg.n_diff0, rem = d_id - piece * fg.n_diff0;
     const int agent = rem / fg.head_groups, h = (rem - agent * fg.head_groups) * kWaves + (threadIdx.x >> 6);
@@ -1091,8 +1093,9 @@ hipError_t launch_attend_master(const RoundDev& rd, const LayerDev& io, const Di
   if (rd.n_sessions == 0 || at.n_chunks == 0 || max_rows == 0) return hipSuccess;
   // the KV heads of one chunk get consecutive workgroup ids: they start together and read neighbouring
   // 256-byte pieces of the same master rows
-  const dim3 grid((unsigned)rd.heads, (unsigned)(rd.n_sessions * at.n_chunks),
-                  (unsigned)((max_rows + kRowsPerBlock - 1) / kRowsPerBlock));
+  // and the row blocks of a chunk follow each other (the second finds the tiles in L2)
+  const dim3 grid((unsigned)rd.heads, (unsigned)((max_rows + kRowsPerBlock - 1) / kRowsPerBlock),
+                  (unsigned)(rd.n_sessions * at.n_chunks));
   if (rd.seg) hipLaunchKernelGGL(tdk_attend_master_kernel<true>, grid, dim3(kBlock), 0, st, rd, io, d, at);
   else hipLaunchKernelGGL(tdk_attend_master_kernel<false>, grid, dim3(kBlock), 0, st, rd, io, d, at);
   return hipGetLastError();
@@ -1116,8 +1119,8 @@ int attend_piece_tokens() { return kPieceTiles * kTile; }
 hipError_t launch_attend_fused(const RoundDev& rd, const LayerDev& io, const DiffDev& d, const AttendDev& at,
                                int max_rows, hipStream_t st) {
   FusedGrid fg;
-  fg.master_y = rd.n_sessions * at.n_chunks;
-  fg.n_master = rd.heads * fg.master_y * ((max_rows + kRowsPerBlock - 1) / kRowsPerBlock);
+  fg.row_blocks = (max_rows + kRowsPerBlock - 1) / kRowsPerBlock;
+  fg.n_master = rd.heads * rd.n_sessions * at.n_chunks * fg.row_blocks;
   fg.head_groups = (rd.heads + kWaves - 1) / kWaves;
   fg.n_diff0 = rd.n_agents * fg.head_groups;
   const int64_t blocks = (int64_t)fg.n_master + (int64_t)fg.n_diff0 * at.n_pieces;
