@@ -857,7 +857,7 @@ tdk_status tdk_attend_shared(tdk_round* r, int32_t layer, const tdk_layer_io* io
     // blocks of the two passes share one launch when the round allows it (timed as the master pass)
     const int64_t fused_blocks = (int64_t)r->model.num_kv_heads * r->rd.n_sessions * p.n_chunks * ((p.max_rows + 127) / 128) +
                                  (int64_t)r->n_agents * ((r->model.num_kv_heads + 3) / 4) * p.n_pieces;
-    if (!r->rd.seg && !r->diff_moved && (int64_t)a->n_q * at.group <= 16 && r->total_master_rows > 0 && fused_blocks < (1 << 30)) {
+    if (!r->rd.seg && !r->diff_moved && (int64_t)a->n_q * at.group <= 32 && r->total_master_rows > 0 && fused_blocks < (1 << 30)) {
       // (this launch rotates the query rows itself: no qrot kernel)
       TDK_LAUNCH(r, TDK_KERNEL_ATTEND_MASTER, s, launch_attend_fused(r->rd, l, d, at, p.max_rows, s));
     } else {

@@ -664,11 +664,11 @@ __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(2, 2))) 
 // ---------------------------------------------------------------------------------------------
 constexpr int kPieceTiles = 16;                // 512 listed tokens per piece
 
-template <bool SEGMOVED>
-__global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2, 2))) void tdk_attend_diff_kernel(const RoundDev rd, const DiffDev d, const AttendDev at) {
-  __shared__ __attribute__((aligned(16))) uint16_t Vs[kTile * kVsStride];
-
-  const int h = blockIdx.x, agent = blockIdx.y, piece = blockIdx.z;
+// Vs: this wavefront's V tile, kTile * kVsStride bf16 elements; lane: 0..63.  QDIRECT (stored diffs not moved):
+// the listed pages meet the caller's rows as they are (but for the sign), no copies from the qrot kernel.
+template <bool SEGMOVED, bool QDIRECT = false>
+__device__ __forceinline__ void attend_diff32_body(const RoundDev& rd, const DiffDev& d, const AttendDev& at, uint16_t* Vs,
+                                                   int h, int agent, int piece, int lane) {
   const int T = rd.page_tokens;
   int64_t lo = d.offset[agent], hi = lo + d.count[agent];
   if (lo < 0) lo = 0;
@@ -680,7 +680,7 @@ __global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2, 2))) void
   const int per_agent = at.n_q * at.group;
   const AgentDev ad = rd.agents[agent];
   const SessionDev sd = rd.sess[ad.session];
-  const int lane = threadIdx.x, n = lane & 31, hh = lane >> 5;
+  const int n = lane & 31, hh = lane >> 5;
   const int64_t row_e = (int64_t)rd.heads * kHeadDim, page_e = (int64_t)T * row_e;
   const uint16_t* pay = reinterpret_cast<const uint16_t*>(d.payload);
   const int seg_base = SEGMOVED ? rd.seg_off[agent] : 0;
@@ -699,13 +699,15 @@ __global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2, 2))) void
     const int64_t out = ((int64_t)agent * at.n_q + qi) * at.n_q_heads + h * at.group + g;
     bf16x8 qf[8];
     auto load_q = [&](int k) {
-      const u32x4* qp = reinterpret_cast<const u32x4*>(reinterpret_cast<const uint16_t*>(at.qdiff) +
-                                                         (out * at.diff_seg + k) * kHeadDim);
+      const u32x4* qp = QDIRECT ? reinterpret_cast<const u32x4*>(reinterpret_cast<const uint16_t*>(at.q) + out * kHeadDim)
+                                : reinterpret_cast<const u32x4*>(reinterpret_cast<const uint16_t*>(at.qdiff) +
+                                                                 (out * at.diff_seg + k) * kHeadDim);
+      const uint32_t flip = QDIRECT && at.q_flip ? 0x80008000u : 0u;
 #pragma unroll
       for (int kk = 0; kk < 8; ++kk) {
         u32x4 v = {0, 0, 0, 0};
         if (row_ok) v = qp[2 * kk + hh];
-        qf[kk] = __builtin_bit_cast(bf16x8, v);
+        qf[kk] = __builtin_bit_cast(bf16x8, u32x4{v.x ^ flip, v.y ^ flip, v.z ^ flip, v.w ^ flip});
       }
     };
     if (!SEGMOVED) load_q(0);
@@ -809,6 +811,12 @@ __global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2, 2))) void
     }
     wave_sync();                                 // before the next block's first tile overwrites the V tile
   }
+}
+
+template <bool SEGMOVED>
+__global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2, 2))) void tdk_attend_diff_kernel(const RoundDev rd, const DiffDev d, const AttendDev at) {
+  __shared__ __attribute__((aligned(16))) uint16_t Vs[kTile * kVsStride];
+  attend_diff32_body<SEGMOVED>(rd, d, at, Vs, blockIdx.x, blockIdx.y, blockIdx.z, threadIdx.x);
 }
 
 // The same pass with 16 query rows per wavefront: used when an agent brings at most 16 rows per KV head
@@ -983,6 +991,7 @@ struct FusedGrid {
 
 constexpr int kFusedLds = kMasterLds > kWaves * kTile * kVsStride * 2 ? kMasterLds : kWaves * kTile * kVsStride * 2;
 
+template <bool ROWS32>    // the listed-pages kind with 32-row tiles (17 to 32 rows per agent and KV head) or 16-row tiles
 __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(2, 2))) void tdk_attend_fused_kernel(const RoundDev rd, const LayerDev io, const DiffDev d,
                                                                   const AttendDev at, const FusedGrid fg) {
   __shared__ __attribute__((aligned(16))) unsigned char lds[kFusedLds];
@@ -1008,7 +1017,8 @@ __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(2, 2))) 
     const int agent = rem / fg.head_groups, h = (rem - agent * fg.head_groups) * kWaves + (threadIdx.x >> 6);
     if (h >= rd.heads) return;
     uint16_t* Vs = reinterpret_cast<uint16_t*>(lds) + (threadIdx.x >> 6) * (kTile * kVsStride);
-    attend_diff16_body<false, true>(rd, d, at, Vs, h, agent, piece, threadIdx.x & 63);
+    if (ROWS32) attend_diff32_body<false, true>(rd, d, at, Vs, h, agent, piece, threadIdx.x & 63);
+    else attend_diff16_body<false, true>(rd, d, at, Vs, h, agent, piece, threadIdx.x & 63);
   }
 }
 
@@ -1125,7 +1135,8 @@ hipError_t launch_attend_fused(const RoundDev& rd, const LayerDev& io, const Dif
   fg.n_diff0 = rd.n_agents * fg.head_groups;
   const int64_t blocks = (int64_t)fg.n_master + (int64_t)fg.n_diff0 * at.n_pieces;
   if (blocks == 0) return hipSuccess;
-  hipLaunchKernelGGL(tdk_attend_fused_kernel, dim3((unsigned)blocks), dim3(kBlock), 0, st, rd, io, d, at, fg);
+  if (at.n_q * at.group > 16) hipLaunchKernelGGL(tdk_attend_fused_kernel<true>, dim3((unsigned)blocks), dim3(kBlock), 0, st, rd, io, d, at, fg);
+  else hipLaunchKernelGGL(tdk_attend_fused_kernel<false>, dim3((unsigned)blocks), dim3(kBlock), 0, st, rd, io, d, at, fg);
   return hipGetLastError();
 }
 
