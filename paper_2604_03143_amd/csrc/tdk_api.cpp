@@ -763,9 +763,14 @@ bool attend_plan(const tdk_round* r, int32_t n_q, int32_t n_q_heads, AttendPlan&
   const int64_t row_blocks = std::max<int64_t>(1, (max_rows + 127) / 128);
   const int64_t slots = 2 * (int64_t)r->n_cus;
   const int32_t max_chunk = std::min<int32_t>(128 * r->model.page_tokens, 4096);
-  int32_t chunk = 64;
+  // Chunks shorter than 512 tokens are not tried (unless the span is): a workgroup's start-up (page masks,
+  // query rotation, first rows) costs about as much as three steps, every chunk adds a partial result per row
+  // for the merge, and rounds small enough to consider such chunks are bounded by the listed-pages pass anyway
+  // (one session of 25 agents: 44 us with chunks of 128 tokens, 32 us with 512).
+  const int32_t min_chunk = (int32_t)std::min<int64_t>(512, (max_span + 63) / 64 * 64);
+  int32_t chunk = std::max(min_chunk, 64);
   int64_t best = -1;
-  for (int32_t c = max_chunk; c >= 64; c -= 64) {
+  for (int32_t c = max_chunk; c >= std::max(min_chunk, 64); c -= 64) {
     int64_t wgs = 0;
     for (const auto& hs : r->sessions)
       if (!hs.agents.empty()) wgs += ((int64_t)hs.span + c - 1) / c;
