@@ -786,7 +786,7 @@ bool attend_plan(const tdk_round* r, int32_t n_q, int32_t n_q_heads, AttendPlan&
     int64_t max_pages = 0;
     for (const auto& hs : r->sessions)
       if (!hs.agents.empty()) max_pages = std::max<int64_t>(max_pages, hs.pages);
-    p.piece_tokens = attend_piece_tokens();
+    p.piece_tokens = attend_piece_tokens((int64_t)r->n_agents * r->model.num_kv_heads);
     p.n_pieces = (int32_t)std::max<int64_t>(1, (max_pages * r->model.page_tokens + p.piece_tokens - 1) / p.piece_tokens);
   }
   p.n_parts = p.n_chunks + p.n_pieces;
@@ -850,6 +850,9 @@ tdk_status tdk_attend_shared(tdk_round* r, int32_t layer, const tdk_layer_io* io
     at.n_parts = p.n_parts;
     at.n_pieces = p.n_pieces;
     at.piece_tokens = p.piece_tokens;
+    // most lists are far shorter than a whole session's pages: a few wavefronts per list walk its pieces in turn,
+    // instead of one launched wavefront per possible piece (nearly all of which would find nothing)
+    at.piece_grid = std::min<int32_t>(p.n_pieces, 4);
     // the kernels take a positive scale: the sign travels with the query copies, and a zero scale (uniform
     // weights) becomes one so small that every scaled score rounds to zero
     at.scale = std::fmax(std::fabs(a->scale), 1e-30f);
@@ -861,7 +864,7 @@ tdk_status tdk_attend_shared(tdk_round* r, int32_t layer, const tdk_layer_io* io
     const DiffDev d = diff_dev(in);
     // blocks of the two passes share one launch when the round allows it (timed as the master pass)
     const int64_t fused_blocks = (int64_t)r->model.num_kv_heads * r->rd.n_sessions * p.n_chunks * ((p.max_rows + 127) / 128) +
-                                 (int64_t)r->n_agents * ((r->model.num_kv_heads + 3) / 4) * p.n_pieces;
+                                 (int64_t)r->n_agents * ((r->model.num_kv_heads + 3) / 4) * std::min<int32_t>(p.n_pieces, 4);
     if (!r->rd.seg && !r->diff_moved && (int64_t)a->n_q * at.group <= 32 && r->total_master_rows > 0 && fused_blocks < (1 << 30)) {
       // (this launch rotates the query rows itself: no qrot kernel)
       TDK_LAUNCH(r, TDK_KERNEL_ATTEND_MASTER, s, launch_attend_fused(r->rd, l, d, at, p.max_rows, s));

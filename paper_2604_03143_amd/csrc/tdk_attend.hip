@@ -656,18 +656,18 @@ __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(2, 2))) 
 
 // ---------------------------------------------------------------------------------------------
 // diff pass: the pages an agent's diff lists, from the payload (the "correct" half of skip-or-correct).
-// One wavefront per (agent, KV head, piece): a piece is kPieceTiles consecutive 32-token tiles of the agent's
+// One wavefront per (agent, KV head, piece): a piece is piece_tokens / 32 consecutive 32-token tiles of the agent's
 // listed tokens and has its own partial result, so there is nothing to combine inside the kernel; workgroups
 // whose piece lies past the end of the agent's list leave at once (the merge knows how many pieces an agent
 // has).  The K rows go straight from the payload into the MFMA operand registers, the V rows through one
 // row-major tile in LDS.  32 query rows at a time; more rows walk the piece again.
 // ---------------------------------------------------------------------------------------------
-constexpr int kPieceTiles = 16;                // 512 listed tokens per piece
+constexpr int kPieceTiles = 16;                // 512 listed tokens per piece at most (small rounds use shorter pieces)
 
 // Vs: this wavefront's V tile, kTile * kVsStride bf16 elements; lane: 0..63.  QDIRECT (stored diffs not moved):
 // the listed pages meet the caller's rows as they are (but for the sign), no copies from the qrot kernel.
 template <bool SEGMOVED, bool QDIRECT = false>
-__device__ __forceinline__ void attend_diff32_body(const RoundDev& rd, const DiffDev& d, const AttendDev& at, uint16_t* Vs,
+__device__ __forceinline__ bool attend_diff32_piece(const RoundDev& rd, const DiffDev& d, const AttendDev& at, uint16_t* Vs,
                                                    int h, int agent, int piece, int lane) {
   const int T = rd.page_tokens;
   int64_t lo = d.offset[agent], hi = lo + d.count[agent];
@@ -675,8 +675,9 @@ __device__ __forceinline__ void attend_diff32_body(const RoundDev& rd, const Dif
   if (hi > d.capacity) hi = d.capacity;
   const int n_tok = hi > lo ? (int)((hi - lo) * T) : 0;
   const int n_tiles = (n_tok + kTile - 1) / kTile;
-  const int tile_begin = piece * kPieceTiles, tile_end = min(n_tiles, tile_begin + kPieceTiles);
-  if (tile_begin >= tile_end) return;
+  const int piece_tiles = at.piece_tokens / kTile;
+  const int tile_begin = piece * piece_tiles, tile_end = min(n_tiles, tile_begin + piece_tiles);
+  if (tile_begin >= tile_end) return false;     // past the end of the list: so are the pieces after this one
   const int per_agent = at.n_q * at.group;
   const AgentDev ad = rd.agents[agent];
   const SessionDev sd = rd.sess[ad.session];
@@ -811,6 +812,15 @@ __device__ __forceinline__ void attend_diff32_body(const RoundDev& rd, const Dif
     }
     wave_sync();                                 // before the next block's first tile overwrites the V tile
   }
+  return true;
+}
+
+// the pieces z, z + piece_grid, ... of one list, until one lies past its end
+template <bool SEGMOVED, bool QDIRECT = false>
+__device__ __forceinline__ void attend_diff32_body(const RoundDev& rd, const DiffDev& d, const AttendDev& at, uint16_t* Vs,
+                                                   int h, int agent, int piece0, int lane) {
+  for (int piece = piece0; piece < at.n_pieces; piece += at.piece_grid)
+    if (!attend_diff32_piece<SEGMOVED, QDIRECT>(rd, d, at, Vs, h, agent, piece, lane)) break;
 }
 
 template <bool SEGMOVED>
@@ -825,7 +835,7 @@ __global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2, 2))) void
 // Vs: this wavefront's V tile, kTile * kVsStride bf16 elements (the K rows go straight from the payload into
 // the MFMA operand registers); lane: 0..63
 template <bool SEGMOVED, bool QDIRECT = false>
-__device__ __forceinline__ void attend_diff16_body(const RoundDev& rd, const DiffDev& d, const AttendDev& at, uint16_t* Vs,
+__device__ __forceinline__ bool attend_diff16_piece(const RoundDev& rd, const DiffDev& d, const AttendDev& at, uint16_t* Vs,
                                                    int h, int agent, int piece, int lane) {
   const int T = rd.page_tokens;
   int64_t lo = d.offset[agent], hi = lo + d.count[agent];
@@ -833,8 +843,9 @@ __device__ __forceinline__ void attend_diff16_body(const RoundDev& rd, const Dif
   if (hi > d.capacity) hi = d.capacity;
   const int n_tok = hi > lo ? (int)((hi - lo) * T) : 0;
   const int n_tiles = (n_tok + kTile - 1) / kTile;
-  const int tile_begin = piece * kPieceTiles, tile_end = min(n_tiles, tile_begin + kPieceTiles);
-  if (tile_begin >= tile_end) return;
+  const int piece_tiles = at.piece_tokens / kTile;
+  const int tile_begin = piece * piece_tiles, tile_end = min(n_tiles, tile_begin + piece_tiles);
+  if (tile_begin >= tile_end) return false;     // past the end of the list: so are the pieces after this one
   const int per_agent = at.n_q * at.group;     // at most 16: one row block
   const AgentDev ad = rd.agents[agent];
   const SessionDev sd = rd.sess[ad.session];
@@ -970,6 +981,15 @@ __device__ __forceinline__ void attend_diff16_body(const RoundDev& rd, const Dif
     for (int b = 0; b < 8; ++b) po[4 * b + g4] = make_float4(rs.oacc[b][0], rs.oacc[b][1], rs.oacc[b][2], rs.oacc[b][3]);
     if (g4 == 0) { at.part_m[slot] = rs.m_run; at.part_l[slot] = l_tot; }
   }
+  return true;
+}
+
+// the pieces z, z + piece_grid, ... of one list, until one lies past its end
+template <bool SEGMOVED, bool QDIRECT = false>
+__device__ __forceinline__ void attend_diff16_body(const RoundDev& rd, const DiffDev& d, const AttendDev& at, uint16_t* Vs,
+                                                   int h, int agent, int piece0, int lane) {
+  for (int piece = piece0; piece < at.n_pieces; piece += at.piece_grid)
+    if (!attend_diff16_piece<SEGMOVED, QDIRECT>(rd, d, at, Vs, h, agent, piece, lane)) break;
 }
 
 template <bool SEGMOVED>
@@ -1113,7 +1133,7 @@ hipError_t launch_attend_master(const RoundDev& rd, const LayerDev& io, const Di
 
 hipError_t launch_attend_diff(const RoundDev& rd, const DiffDev& d, const AttendDev& at, hipStream_t st) {
   if (rd.n_agents == 0) return hipSuccess;
-  const dim3 grid((unsigned)rd.heads, (unsigned)rd.n_agents, (unsigned)at.n_pieces);    // one wavefront per piece of a list
+  const dim3 grid((unsigned)rd.heads, (unsigned)rd.n_agents, (unsigned)at.piece_grid);   // wavefront z of a list: pieces z, z + piece_grid, ...
   if (at.n_q * at.group <= 16) {
     if (at.diff_seg > 1) hipLaunchKernelGGL(tdk_attend_diff16_kernel<true>, grid, dim3(64), 0, st, rd, d, at);
     else hipLaunchKernelGGL(tdk_attend_diff16_kernel<false>, grid, dim3(64), 0, st, rd, d, at);
@@ -1124,7 +1144,13 @@ hipError_t launch_attend_diff(const RoundDev& rd, const DiffDev& d, const Attend
   return hipGetLastError();
 }
 
-int attend_piece_tokens() { return kPieceTiles * kTile; }
+int attend_piece_tokens(int64_t lists) {
+  // lists = agents x KV heads.  A piece is 512 tokens, unless the round is so small (at most one list per compute
+  // unit of a 256-CU chip) that its few wavefronts would each walk ten or more tiles one after another while most
+  // of the chip idles: then 128.  (Shorter pieces in larger rounds cost more in start-up than they gain: the
+  // 100-agent long round 138 -> 162 us with pieces of 256 tokens.)
+  return (lists > 256 ? kPieceTiles : kPieceTiles / 4) * kTile;
+}
 
 hipError_t launch_attend_fused(const RoundDev& rd, const LayerDev& io, const DiffDev& d, const AttendDev& at,
                                int max_rows, hipStream_t st) {
@@ -1133,7 +1159,7 @@ hipError_t launch_attend_fused(const RoundDev& rd, const LayerDev& io, const Dif
   fg.n_master = rd.heads * rd.n_sessions * at.n_chunks * fg.row_blocks;
   fg.head_groups = (rd.heads + kWaves - 1) / kWaves;
   fg.n_diff0 = rd.n_agents * fg.head_groups;
-  const int64_t blocks = (int64_t)fg.n_master + (int64_t)fg.n_diff0 * at.n_pieces;
+  const int64_t blocks = (int64_t)fg.n_master + (int64_t)fg.n_diff0 * at.piece_grid;
   if (blocks == 0) return hipSuccess;
   if (at.n_q * at.group > 16) hipLaunchKernelGGL(tdk_attend_fused_kernel<true>, dim3((unsigned)blocks), dim3(kBlock), 0, st, rd, io, d, at, fg);
   else hipLaunchKernelGGL(tdk_attend_fused_kernel<false>, dim3((unsigned)blocks), dim3(kBlock), 0, st, rd, io, d, at, fg);

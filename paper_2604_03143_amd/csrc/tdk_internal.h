@@ -113,6 +113,7 @@ struct AttendDev {
   int32_t n_parts;                   // n_chunks + n_pieces: the chunks' partial results, then those of the listed pages
   int32_t n_pieces;                  // partial results of the listed-pages pass per query row
   int32_t piece_tokens;              // listed tokens per piece
+  int32_t piece_grid;                // wavefronts launched per list: wavefront z takes the pieces z, z + piece_grid, ...
   int32_t max_seg;                   // copies of every query row in qrot: one per segment of its agent's layout
   int32_t diff_seg;                  // copies of every query row in qdiff: max_seg if a segmented round's stored
                                      // diffs sit at other positions (each segment moved by its own distance), else 1
@@ -142,7 +143,7 @@ hipError_t launch_attend_merge(const RoundDev& rd, const DiffDev& d, const Atten
 // master pass and listed-pages pass in one launch (identity layouts, stored diffs not moved, few rows per agent)
 hipError_t launch_attend_fused(const RoundDev& rd, const LayerDev& io, const DiffDev& d, const AttendDev& at,
                                int max_rows, hipStream_t st);
-int attend_piece_tokens();   // listed tokens per piece of the listed-pages pass
+int attend_piece_tokens(int64_t lists);   // listed tokens per piece of the listed-pages pass; lists = agents x KV heads
 
 hipError_t launch_page_fill(u32x4* dst, const int32_t* ids, int n_pages, int page_u4, uint32_t word, hipStream_t st);
 hipError_t launch_page_read(const u32x4* src, const int32_t* ids, int n_pages, int page_u4, u32x4* sink, hipStream_t st);
