@@ -78,6 +78,15 @@ def test_negative_zero_and_large_scales(tdo, scale):
     _case(tdo, spec, 2, 6, scale=scale)
 
 
+@pytest.mark.parametrize("n_q,Hq", [(1, 6), (9, 6)])
+def test_every_page_listed(tdo, n_q, Hq):
+    """Every page of every mirror differs from the master: the master pass has nothing left to do (all its
+    scores are switched off), the lists are 44 pages long = six pieces of 128 listed tokens, more than the four
+    wavefronts launched per list (the pieces are walked in turn); 3 and 27 rows per agent and KV head."""
+    spec = wl.RoundSpec("att8", 68, 1, 2, 128, 16, 1.0e6, 1, 3, 7, 100, 0, 90, 1.0)
+    _case(tdo, spec, n_q, Hq)
+
+
 def test_long_span_with_chunks_above_512_tokens(tdo):
     """Four sessions of 10280 tokens on 8 KV heads: on a 256-CU device the planner gives every workgroup of the
     master pass 704 tokens = 44 pages (more than one 64-bit word of a row's page mask)."""
