@@ -7,9 +7,12 @@
 // agents of a session then attend to the SAME un-rotated master keys.  The query rows of a session
 // (agents x query tokens x query heads of one KV head) become the N side of one dense product with
 // the master's K and V tiles, which is MFMA work, and the master is read once per session instead of
-// once per agent.  Pages that an agent's diff lists are masked out of that product for that agent's
-// rows and handled by a second kernel from the payload (the "correct" half) with the same tile code; a
-// last kernel merges the partial results with their log-sum-exp weights.
+// once per agent (the master pass).  Pages that an agent's diff lists are masked out of that product for
+// that agent's rows and come from the payload instead, with the same tile arithmetic (the listed-pages
+// pass, the "correct" half); a last kernel merges the partial results with their log-sum-exp weights.
+// For the decode case (identity layouts, stored diffs not moved, at most 32 rows per agent and KV head)
+// the two passes share one launch, which also rotates the query rows itself; other rounds run
+// tdk_attend_qrot_kernel, tdk_attend_master_kernel and tdk_attend_diff(16)_kernel one after another.
 #include "tdk_internal.h"
 
 #include <type_traits>
