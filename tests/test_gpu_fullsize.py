@@ -107,14 +107,18 @@ def test_full_size_layer(tdo, name):
     lse = torch.full((A, n_q, Hq), float("nan"), dtype=torch.float32, device=dev)
     nbytes = tdk.tdk_attend_workspace_bytes(r, n_q, Hq)
     ws = torch.empty(nbytes, dtype=torch.uint8, device=dev)
-    scale = 1.0 / float(np.sqrt(D))
-    tdk.tdk_attend_shared(r, layer, io, d, tdk.attend_io(q, n_q, Hq, scale, out, lse, ws, nbytes), st)
-    torch.cuda.synchronize()
-    assert bool(torch.isfinite(out).all()) and bool(torch.isfinite(lse).all())
     pick_d = torch.tensor(pick, device=dev)
-    want_o, want_l = tdo.attend_shared(g, hr, hmk, hmv, od, q[pick_d].cpu().numpy().view(np.uint16), n_q, Hq, scale)
-    err_o = float(np.max(np.abs(out[pick_d].cpu().numpy().astype(np.float64) - want_o)))
-    err_l = float(np.max(np.abs(lse[pick_d].cpu().numpy().astype(np.float64) - want_l)))
     vmax = float(np.max(np.abs(wl.bf16_bits_to_f32(hmv))))
-    assert err_o <= 1e-2 * max(1.0, vmax) and err_l <= 5e-3, (err_o, err_l)
+    # the usual scale, then scale 1 (near one-hot weights: any token dropped, doubled or taken from the wrong
+    # source moves the rows it dominates far above the bound; bounds as derived in test_gpu_attend.py)
+    for scale, lse_tol in ((1.0 / float(np.sqrt(D)), 5e-3), (1.0, 8e-3)):
+        k = scale * float(np.sqrt(D))
+        out.fill_(float("nan")); lse.fill_(float("nan"))
+        tdk.tdk_attend_shared(r, layer, io, d, tdk.attend_io(q, n_q, Hq, scale, out, lse, ws, nbytes), st)
+        torch.cuda.synchronize()
+        assert bool(torch.isfinite(out).all()) and bool(torch.isfinite(lse).all())
+        want_o, want_l = tdo.attend_shared(g, hr, hmk, hmv, od, q[pick_d].cpu().numpy().view(np.uint16), n_q, Hq, scale)
+        err_o = float(np.max(np.abs(out[pick_d].cpu().numpy().astype(np.float64) - want_o)))
+        err_l = float(np.max(np.abs(lse[pick_d].cpu().numpy().astype(np.float64) - want_l)))
+        assert err_o <= k * 1e-2 * max(1.0, vmax) and err_l <= k * lse_tol, (scale, err_o, err_l)
     r.destroy()
