@@ -15,7 +15,7 @@ pytestmark = pytest.mark.gpu
 OUT_TOL, LSE_TOL = 1e-2, 5e-3
 
 
-def _case(tdo, spec, n_q, Hq, style=0, grow=None, seed=3, scale=None, lse_tol=None):
+def _case(tdo, spec, n_q, Hq, style=0, grow=None, seed=3, scale=None, lse_tol=None, perturb=True):
     import torch
     from paper_2604_03143_amd import tdk
     import gpu_helpers as gh
@@ -23,7 +23,9 @@ def _case(tdo, spec, n_q, Hq, style=0, grow=None, seed=3, scale=None, lse_tol=No
         pytest.fail("GPU tests need a GPU")
     old = wl.make_round(spec)
     o = OracleRun(tdo, old, style=style)
-    o.rerotate(); o.perturb()
+    o.rerotate()
+    if perturb:
+        o.perturb()
     d = o.encode()
     rnd, diff_pos0 = old, None
     if grow is not None:
@@ -89,6 +91,14 @@ def test_sharp_weights_on_several_sessions_and_moved_diffs(tdo):
     # 2^-8 (std ~1.6e-3), gives a score error of std |q||k| / sqrt(D) * 1.6e-3 * scale*sqrt(D) ~ 1.6e-3 * 11.3 = 0.018
     # at scale 1; the largest of a few hundred rows reaches 4 sigma.  Bound: 5 sigma = 0.09 = 8e-3 * scale * sqrt(D).
     _case(tdo, spec, 1, 40, scale=1.0, grow=[0, 16, 7, 250, 1, 31, 1000, 64], lse_tol=8e-3)
+
+
+@pytest.mark.parametrize("n_q,Hq", [(1, 6), (9, 6)])
+def test_no_page_listed(tdo, n_q, Hq):
+    """Mirrors identical to the rotated master: empty diffs (capacity 0), the listed-pages pass finds nothing and
+    the merge takes the master pass's parts alone."""
+    spec = wl.RoundSpec("att10", 70, 1, 2, 128, 16, 1.0e6, 2, 3, 5, 60, 0, 90, 0.2)
+    _case(tdo, spec, n_q, Hq, perturb=False)
 
 
 @pytest.mark.parametrize("n_q,Hq", [(1, 6), (9, 6)])
