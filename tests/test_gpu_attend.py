@@ -117,7 +117,10 @@ def test_long_span_with_chunks_above_512_tokens(tdo):
     _case(tdo, spec, 1, 8)
 
 
-@pytest.mark.parametrize("H,Hq,T,style,n_q", [(4, 28, 16, 0, 3), (8, 8, 32, 0, 2), (2, 4, 16, 1, 5), (1, 7, 16, 0, 1)])
+# (the last two: 48 and 40 rows per agent and KV head, past the shared launch: the three kernels one after another,
+#  the listed-pages pass walking its pieces once per block of 32 rows)
+@pytest.mark.parametrize("H,Hq,T,style,n_q", [(4, 28, 16, 0, 3), (8, 8, 32, 0, 2), (2, 4, 16, 1, 5), (1, 7, 16, 0, 1),
+                                               (2, 8, 16, 0, 12), (1, 5, 32, 1, 8)])
 def test_head_counts_page_sizes_styles_and_several_query_tokens(tdo, H, Hq, T, style, n_q):
     spec = wl.RoundSpec("att2", 62, 1, H, 128, T, 1.0e6, 1, 4, 3, 50, 0, 500, 0.3)
     _case(tdo, spec, n_q, Hq, style=style)
