@@ -786,7 +786,7 @@ bool attend_plan(const tdk_round* r, int32_t n_q, int32_t n_q_heads, AttendPlan&
     int64_t max_pages = 0;
     for (const auto& hs : r->sessions)
       if (!hs.agents.empty()) max_pages = std::max<int64_t>(max_pages, hs.pages);
-    p.piece_tokens = attend_piece_tokens((int64_t)r->n_agents * r->model.num_kv_heads);
+    p.piece_tokens = attend_piece_tokens((int64_t)r->n_agents * r->model.num_kv_heads, r->n_cus);
     p.n_pieces = (int32_t)std::max<int64_t>(1, (max_pages * r->model.page_tokens + p.piece_tokens - 1) / p.piece_tokens);
   }
   p.n_parts = p.n_chunks + p.n_pieces;

@@ -389,7 +389,7 @@ __global__ __launch_bounds__(kBlock) void tdk_attend_qrot_kernel(const RoundDev 
 
 // ---------------------------------------------------------------------------------------------
 // master pass: S^T = K Q'^T and O^T += V^T P^T per 32-token tile, online softmax per query row
-// grid: x = KV head, y = block of 128 query rows, z = session * n_chunks + chunk
+// grid: one linear id = KV head + heads * (block of 128 query rows + row blocks * (session * n_chunks + chunk))
 // ---------------------------------------------------------------------------------------------
 constexpr int kMasterKs = kBigTile * kKsStride, kMasterVs = kBigTile * kVsStride;      // bf16 elements of the two tiles
 constexpr int kMaskWords = 2;                                                          // 64-bit words of a row's page mask: 128 pages per chunk
@@ -652,9 +652,11 @@ __device__ __forceinline__ void attend_master_body(const RoundDev& rd, const Lay
 
 template <bool SEG>
 __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(2, 2))) void tdk_attend_master_kernel(const RoundDev rd, const LayerDev io, const DiffDev d,
-                                                                   const AttendDev at) {
+                                                                   const AttendDev at, const int row_blocks) {
   __shared__ __attribute__((aligned(16))) unsigned char lds[kMasterLds];
-  attend_master_body<SEG>(rd, io, d, at, lds, blockIdx.x, blockIdx.z, blockIdx.y);
+  // one linear id (grid dimensions y and z stop at 65535): KV head fastest, then the row block, then the chunk
+  const int h = blockIdx.x % rd.heads, rest = blockIdx.x / rd.heads;
+  attend_master_body<SEG>(rd, io, d, at, lds, h, rest / row_blocks, rest % row_blocks);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -829,7 +831,9 @@ __device__ __forceinline__ void attend_diff32_body(const RoundDev& rd, const Dif
 template <bool SEGMOVED>
 __global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2, 2))) void tdk_attend_diff_kernel(const RoundDev rd, const DiffDev d, const AttendDev at) {
   __shared__ __attribute__((aligned(16))) uint16_t Vs[kTile * kVsStride];
-  attend_diff32_body<SEGMOVED>(rd, d, at, Vs, blockIdx.x, blockIdx.y, blockIdx.z, threadIdx.x);
+  // one linear id: KV head fastest, then the agent, then the wavefront's number among those of its list
+  const int h = blockIdx.x % rd.heads, rest = blockIdx.x / rd.heads;
+  attend_diff32_body<SEGMOVED>(rd, d, at, Vs, h, rest % rd.n_agents, rest / rd.n_agents, threadIdx.x);
 }
 
 // The same pass with 16 query rows per wavefront: used when an agent brings at most 16 rows per KV head
@@ -998,7 +1002,9 @@ __device__ __forceinline__ void attend_diff16_body(const RoundDev& rd, const Dif
 template <bool SEGMOVED>
 __global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2, 2))) void tdk_attend_diff16_kernel(const RoundDev rd, const DiffDev d, const AttendDev at) {
   __shared__ __attribute__((aligned(16))) uint16_t Vs[kTile * kVsStride];
-  attend_diff16_body<SEGMOVED>(rd, d, at, Vs, blockIdx.x, blockIdx.y, blockIdx.z, threadIdx.x);
+  // one linear id: KV head fastest, then the agent, then the wavefront's number among those of its list
+  const int h = blockIdx.x % rd.heads, rest = blockIdx.x / rd.heads;
+  attend_diff16_body<SEGMOVED>(rd, d, at, Vs, h, rest % rd.n_agents, rest / rd.n_agents, threadIdx.x);
 }
 
 // Both passes in one launch, for rounds with identity layouts whose stored diffs have not moved and few query
@@ -1127,16 +1133,21 @@ hipError_t launch_attend_master(const RoundDev& rd, const LayerDev& io, const Di
   // the KV heads of one chunk get consecutive workgroup ids: they start together and read neighbouring
   // 256-byte pieces of the same master rows
   // and the row blocks of a chunk follow each other (the second finds the tiles in L2)
-  const dim3 grid((unsigned)rd.heads, (unsigned)((max_rows + kRowsPerBlock - 1) / kRowsPerBlock),
-                  (unsigned)(rd.n_sessions * at.n_chunks));
-  if (rd.seg) hipLaunchKernelGGL(tdk_attend_master_kernel<true>, grid, dim3(kBlock), 0, st, rd, io, d, at);
-  else hipLaunchKernelGGL(tdk_attend_master_kernel<false>, grid, dim3(kBlock), 0, st, rd, io, d, at);
+  const int row_blocks = (max_rows + kRowsPerBlock - 1) / kRowsPerBlock;
+  const int64_t blocks = (int64_t)rd.heads * row_blocks * rd.n_sessions * at.n_chunks;
+  if (blocks >= ((int64_t)1 << 31)) return hipErrorInvalidConfiguration;
+  const dim3 grid((unsigned)blocks);
+  if (rd.seg) hipLaunchKernelGGL(tdk_attend_master_kernel<true>, grid, dim3(kBlock), 0, st, rd, io, d, at, row_blocks);
+  else hipLaunchKernelGGL(tdk_attend_master_kernel<false>, grid, dim3(kBlock), 0, st, rd, io, d, at, row_blocks);
   return hipGetLastError();
 }
 
 hipError_t launch_attend_diff(const RoundDev& rd, const DiffDev& d, const AttendDev& at, hipStream_t st) {
   if (rd.n_agents == 0) return hipSuccess;
-  const dim3 grid((unsigned)rd.heads, (unsigned)rd.n_agents, (unsigned)at.piece_grid);   // wavefront z of a list: pieces z, z + piece_grid, ...
+  // piece_grid wavefronts per list (agent, KV head): wavefront z takes the pieces z, z + piece_grid, ...
+  const int64_t blocks = (int64_t)rd.heads * rd.n_agents * at.piece_grid;
+  if (blocks >= ((int64_t)1 << 31)) return hipErrorInvalidConfiguration;
+  const dim3 grid((unsigned)blocks);
   if (at.n_q * at.group <= 16) {
     if (at.diff_seg > 1) hipLaunchKernelGGL(tdk_attend_diff16_kernel<true>, grid, dim3(64), 0, st, rd, d, at);
     else hipLaunchKernelGGL(tdk_attend_diff16_kernel<false>, grid, dim3(64), 0, st, rd, d, at);
@@ -1147,12 +1158,12 @@ hipError_t launch_attend_diff(const RoundDev& rd, const DiffDev& d, const Attend
   return hipGetLastError();
 }
 
-int attend_piece_tokens(int64_t lists) {
+int attend_piece_tokens(int64_t lists, int n_cus) {
   // lists = agents x KV heads.  A piece is 512 tokens, unless the round is so small (at most one list per compute
-  // unit of a 256-CU chip) that its few wavefronts would each walk ten or more tiles one after another while most
+  // unit) that its few wavefronts would each walk ten or more tiles one after another while most
   // of the chip idles: then 128.  (Shorter pieces in larger rounds cost more in start-up than they gain: the
   // 100-agent long round 138 -> 162 us with pieces of 256 tokens.)
-  return (lists > 256 ? kPieceTiles : kPieceTiles / 4) * kTile;
+  return (lists > n_cus ? kPieceTiles : kPieceTiles / 4) * kTile;
 }
 
 hipError_t launch_attend_fused(const RoundDev& rd, const LayerDev& io, const DiffDev& d, const AttendDev& at,

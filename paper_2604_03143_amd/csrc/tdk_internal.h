@@ -143,7 +143,7 @@ hipError_t launch_attend_merge(const RoundDev& rd, const DiffDev& d, const Atten
 // master pass and listed-pages pass in one launch (identity layouts, stored diffs not moved, few rows per agent)
 hipError_t launch_attend_fused(const RoundDev& rd, const LayerDev& io, const DiffDev& d, const AttendDev& at,
                                int max_rows, hipStream_t st);
-int attend_piece_tokens(int64_t lists);   // listed tokens per piece of the listed-pages pass; lists = agents x KV heads
+int attend_piece_tokens(int64_t lists, int n_cus);   // listed tokens per piece of the listed-pages pass; lists = agents x KV heads
 
 hipError_t launch_page_fill(u32x4* dst, const int32_t* ids, int n_pages, int page_u4, uint32_t word, hipStream_t st);
 hipError_t launch_page_read(const u32x4* src, const int32_t* ids, int n_pages, int page_u4, u32x4* sink, hipStream_t st);
