@@ -155,28 +155,36 @@ def _rng(spec: RoundSpec, tag: int, extra: int = 0) -> np.random.Generator:
 
 def make_round(spec: RoundSpec, hist: Optional[np.ndarray] = None,
                perturbed_per_agent: Optional[int] = None,
-               clustered: bool = False, alloc: str = "fragmented") -> Round:
+               clustered: bool = False, alloc: str = "fragmented",
+               spans: Optional[List[int]] = None, agents: Optional[List[int]] = None) -> Round:
     """Draw the structure of a round: histories, block tables, perturbed page sets.
 
     alloc = "fragmented": physical pages are a seeded random permutation of the pool (an allocator
     after long use; the default and the graded recipe); "contiguous": every agent's pages are
-    consecutive (a fresh allocator)."""
+    consecutive (a fresh allocator).
+
+    spans / agents: per-session span lengths and agent counts for ragged rounds (sessions of different
+    sizes batched into one round); by default every session has spec.span_tokens tokens and
+    spec.agents_per_session agents.  The perturbed fraction then applies to each session's own pages."""
     T = spec.page_tokens
-    A = spec.n_agents
-    S = spec.span_tokens
-    P = spec.span_pages
+    n_sess = spec.n_sessions if spans is None and agents is None else len(spans if spans is not None else agents)
+    span_list = [spec.span_tokens] * n_sess if spans is None else [int(x) for x in spans]
+    agent_list = [spec.agents_per_session] * n_sess if agents is None else [int(x) for x in agents]
+    assert len(span_list) == n_sess and len(agent_list) == n_sess
+    A = int(sum(agent_list))
     rs = _rng(spec, 1)
-    span_tokens = np.full(spec.n_sessions, S, dtype=np.int32)
-    master_pos0 = np.zeros(spec.n_sessions, dtype=np.int64)
+    span_tokens = np.array(span_list, dtype=np.int32)
+    master_pos0 = np.zeros(n_sess, dtype=np.int64)
     master_row0 = np.concatenate([[0], np.cumsum(span_tokens, dtype=np.int64)]).astype(np.int64)
-    agent_session = np.repeat(np.arange(spec.n_sessions, dtype=np.int32), spec.agents_per_session)
+    agent_session = np.repeat(np.arange(n_sess, dtype=np.int32), agent_list)
     if hist is None:
         hist = rs.integers(spec.hist_lo, spec.hist_hi + 1, size=A, dtype=np.int64)
     agent_pos0 = np.asarray(hist, dtype=np.int64).copy()
     assert agent_pos0.shape == (A,)
+    S_of = span_tokens[agent_session].astype(np.int64)
 
     first_lp = agent_pos0 // T
-    last_lp = (agent_pos0 + S - 1) // T
+    last_lp = np.where(S_of > 0, (agent_pos0 + S_of - 1) // T, first_lp - 1)
     n_touch = (last_lp - first_lp + 1).astype(np.int64)
     pool_pages = int(n_touch.sum()) + 2 * A + 1
     if alloc == "fragmented":
@@ -190,18 +198,25 @@ def make_round(spec: RoundSpec, hist: Optional[np.ndarray] = None,
     cursor = 1 + 2 * A
     tables: List[np.ndarray] = []
     for i in range(A):
-        bt = np.full(int(last_lp[i]) + 1, dummy, dtype=np.int32)
         n = int(n_touch[i])
+        bt = np.full(int(first_lp[i]) + n, dummy, dtype=np.int32)
         bt[int(first_lp[i]):] = perm[cursor:cursor + n]
         cursor += n
         tables.append(bt)
     assert cursor == pool_pages
 
-    k = spec.perturbed_pages_per_agent if perturbed_per_agent is None else perturbed_per_agent
-    k = min(k, P)
     rp = _rng(spec, 3)
     perturbed: List[np.ndarray] = []
     for i in range(A):
+        S = int(S_of[i])
+        P = -(-S // T)
+        if perturbed_per_agent is not None:
+            k = perturbed_per_agent
+        elif spec.perturbed_frac <= 0.0 or P == 0:
+            k = 0
+        else:
+            k = max(1, int(round(spec.perturbed_frac * P)))
+        k = min(k, P)
         if k == 0:
             perturbed.append(np.zeros(0, dtype=np.int32))
         elif not clustered:
@@ -210,9 +225,10 @@ def make_round(spec: RoundSpec, hist: Optional[np.ndarray] = None,
             # runs of 1-4 consecutive pages that start on a shared-block boundary
             chosen: set = set()
             guard = 0
+            n_blocks = max(1, min(spec.blocks, -(-S // spec.block_tokens)))
             while len(chosen) < k and guard < 100000:
                 guard += 1
-                b = int(rp.integers(0, spec.blocks))
+                b = int(rp.integers(0, n_blocks))
                 start = (b * spec.block_tokens) // T
                 run = int(rp.integers(1, 5))
                 for q in range(start, min(P, start + run)):

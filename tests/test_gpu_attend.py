@@ -1,21 +1,20 @@
 """Attention over mirrors that are never restored (Sec. 4.4, the diff applied as attention tiles are loaded),
 through the C ABI against the oracle.  The GPU path rounds the back-rotated queries and the softmax weights
-to bf16 for its two MFMA products and accumulates in fp32, so the comparison is by tolerance: with |q|, |k|,
-|v| ~ 1 and D = 128 the scores carry an error of about 2^-9 * sqrt(D) * |q||k| * scale ~ 1e-3 and each
-weight one of 2^-9 relative; the normalised outputs then agree to a few 1e-3 of max |V| (bound used: 1e-2),
-the log-sum-exp to 5e-3.  A wrong table sign, head mapping, page mask or plane offset moves them by O(1)."""
+to bf16 for its two MFMA products and accumulates in fp32, so the comparison is by tolerance: a bound per query
+row and output element, derived from that arithmetic in attend_bounds.py (score error from the bf16 queries,
+2^-8 for the bf16 weights, both times the row's own sum of weights x |V|; the log-sum-exp within the score
+error).  A wrong table sign, head mapping, page mask or plane offset moves the results far outside it."""
 import numpy as np
 import pytest
 
+import attend_bounds as ab
 from paper_2604_03143_amd import workload as wl
 from helpers import OracleRun
 
 pytestmark = pytest.mark.gpu
 
-OUT_TOL, LSE_TOL = 1e-2, 5e-3
 
-
-def _case(tdo, spec, n_q, Hq, style=0, grow=None, seed=3, scale=None, lse_tol=None, perturb=True):
+def _case(tdo, spec, n_q, Hq, style=0, grow=None, seed=3, scale=None, perturb=True):
     import torch
     from paper_2604_03143_amd import tdk
     import gpu_helpers as gh
@@ -34,7 +33,8 @@ def _case(tdo, spec, n_q, Hq, style=0, grow=None, seed=3, scale=None, lse_tol=No
     g = np.random.default_rng([spec.stream, seed])
     q = wl.f32_to_bf16_bits(g.standard_normal((rnd.n_agents, n_q, Hq, spec.head_dim)).astype(np.float32))
     scale = 1.0 / np.sqrt(spec.head_dim) if scale is None else scale
-    want_o, want_l = tdo.attend_shared(o.g, tdo.HostRound(rnd, diff_pos0=diff_pos0), o.mk, o.mv, d, q, n_q, Hq, scale)
+    want_o, want_l, tol_o, tol_l = ab.expected_and_bounds(tdo, o.g, tdo.HostRound(rnd, diff_pos0=diff_pos0), o.mk, o.mv, d,
+                                                          q, n_q, Hq, scale)
 
     r = tdk.round_from_workload(rnd, style=style, diff_pos0=diff_pos0)
     try:
@@ -56,14 +56,7 @@ def _case(tdo, spec, n_q, Hq, style=0, grow=None, seed=3, scale=None, lse_tol=No
         got_o, got_l = out.cpu().numpy().astype(np.float64), lse.cpu().numpy().astype(np.float64)
     finally:
         r.destroy()
-    vmax = float(np.max(np.abs(wl.bf16_bits_to_f32(o.mv))))
-    err_o = float(np.max(np.abs(got_o - want_o)))
-    err_l = float(np.max(np.abs(got_l - want_l)))
-    assert np.all(np.isfinite(got_o)) and np.all(np.isfinite(got_l))
-    # the score errors grow with the scale: the bounds above are those of scale = 1 / sqrt(D)
-    k = max(1.0, abs(scale) * np.sqrt(spec.head_dim))
-    assert err_o <= k * OUT_TOL * max(1.0, vmax) and err_l <= k * (LSE_TOL if lse_tol is None else lse_tol), (err_o, err_l)
-    return err_o, err_l
+    return ab.assert_within(got_o, got_l, want_o, want_l, tol_o, tol_l, what=(spec.name, n_q, Hq, scale))
 
 
 def test_one_query_token_per_agent(tdo):
@@ -79,7 +72,7 @@ def test_negative_zero_and_large_scales(tdo, scale):
     nearly one-hot (scores of +-30): a token that is dropped, counted twice or taken from the wrong source moves
     the rows it dominates by O(|V|), far above the bound, which flat weights would hide."""
     spec = wl.RoundSpec("att6", 66, 1, 2, 128, 16, 1.0e6, 1, 3, 3, 50, 0, 300, 0.3)
-    _case(tdo, spec, 2, 6, scale=scale, lse_tol=8e-3 if scale == 1.0 else None)   # (see the sharp-weights case below)
+    _case(tdo, spec, 2, 6, scale=scale)
 
 
 def test_sharp_weights_on_several_sessions_and_moved_diffs(tdo):
@@ -87,10 +80,8 @@ def test_sharp_weights_on_several_sessions_and_moved_diffs(tdo):
     mirrors stored when the histories were shorter (payload keys meet turned-back queries)."""
     spec = wl.RoundSpec("att9", 69, 1, 8, 128, 16, 1.0e6, 2, 4, 4, 73, 5, 900, 0.25)
     # With one token carrying nearly all the weight the log-sum-exp takes that token's score error whole (no
-    # averaging over tokens): one bf16 rounding of each element of the turned-back query, relative error up to
-    # 2^-8 (std ~1.6e-3), gives a score error of std |q||k| / sqrt(D) * 1.6e-3 * scale*sqrt(D) ~ 1.6e-3 * 11.3 = 0.018
-    # at scale 1; the largest of a few hundred rows reaches 4 sigma.  Bound: 5 sigma = 0.09 = 8e-3 * scale * sqrt(D).
-    _case(tdo, spec, 1, 40, scale=1.0, grow=[0, 16, 7, 250, 1, 31, 1000, 64], lse_tol=8e-3)
+    # averaging over tokens), which is what the per-row bound allows for.
+    _case(tdo, spec, 1, 40, scale=1.0, grow=[0, 16, 7, 250, 1, 31, 1000, 64])
 
 
 @pytest.mark.parametrize("n_q,Hq", [(1, 6), (9, 6)])
@@ -149,7 +140,7 @@ def test_agents_with_their_own_block_order(tdo, T, style, block_tokens, n_q, Hq)
     g = np.random.default_rng([spec.stream, block_tokens])
     q = wl.f32_to_bf16_bits(g.standard_normal((rnd.n_agents, n_q, Hq, 128)).astype(np.float32))
     scale = 1.0 / np.sqrt(128.0)
-    want_o, want_l = tdo.attend_shared(o.g, o.hr, o.mk, o.mv, d, q, n_q, Hq, scale)
+    want_o, want_l, tol_o, tol_l = ab.expected_and_bounds(tdo, o.g, o.hr, o.mk, o.mv, d, q, n_q, Hq, scale)
     r = tdk.round_from_workload(rnd, style=style)
     try:
         n = int(d.offset[-1])
@@ -165,10 +156,8 @@ def test_agents_with_their_own_block_order(tdo, T, style, block_tokens, n_q, Hq)
         tdk.tdk_attend_shared(r, 0, tdk.layer_io(mk, mv, None, None, 0), dd,
                               tdk.attend_io(gh.up(q), n_q, Hq, scale, out, lse, ws, nbytes))
         torch.cuda.synchronize()
-        vmax = float(np.max(np.abs(wl.bf16_bits_to_f32(o.mv))))
-        err_o = float(np.max(np.abs(out.cpu().numpy() - want_o)))
-        err_l = float(np.max(np.abs(lse.cpu().numpy() - want_l)))
-        assert err_o <= OUT_TOL * max(1.0, vmax) and err_l <= LSE_TOL, (err_o, err_l)
+        ab.assert_within(out.cpu().numpy().astype(np.float64), lse.cpu().numpy().astype(np.float64),
+                         want_o, want_l, tol_o, tol_l, what=(T, style, block_tokens, n_q))
     finally:
         r.destroy()
 
@@ -193,12 +182,11 @@ def test_own_block_order_and_mirrors_stored_under_another_order(tdo, T, style, b
     new.segments[0] = old.segments[0].copy()
     seg_diff = [sg[:, 1] if len(sg) else np.zeros(0, np.int64) for sg in old.segments]
     Hq = 6                                          # 3 query heads per KV head: 6 or 18 rows per agent and KV head
-    scale = 1.0 if sharp else 1.0 / np.sqrt(128.0)  # sharp: near one-hot weights, bounds as in the sharp-weights case above
-    k = scale * np.sqrt(128.0)
+    scale = 1.0 if sharp else 1.0 / np.sqrt(128.0)  # sharp: near one-hot weights
     g = np.random.default_rng([spec.stream, T, block_tokens])
     q = wl.f32_to_bf16_bits(g.standard_normal((new.n_agents, n_q, Hq, 128)).astype(np.float32))
     hr = tdo.HostRound(new, diff_pos0=old.agent_pos0, segment_diff_pos=seg_diff)
-    want_o, want_l = tdo.attend_shared(o.g, hr, o.mk, o.mv, d, q, n_q, Hq, scale)
+    want_o, want_l, tol_o, tol_l = ab.expected_and_bounds(tdo, o.g, hr, o.mk, o.mv, d, q, n_q, Hq, scale)
     r = tdk.round_from_workload(new, style=style, diff_pos0=old.agent_pos0, segment_diff_pos=seg_diff)
     try:
         n = int(d.offset[-1])
@@ -214,10 +202,8 @@ def test_own_block_order_and_mirrors_stored_under_another_order(tdo, T, style, b
         tdk.tdk_attend_shared(r, 0, tdk.layer_io(mk, mv, None, None, 0), dd,
                               tdk.attend_io(gh.up(q), n_q, Hq, scale, out, lse, ws, nbytes))
         torch.cuda.synchronize()
-        vmax = float(np.max(np.abs(wl.bf16_bits_to_f32(o.mv))))
-        err_o = float(np.max(np.abs(out.cpu().numpy() - want_o)))
-        err_l = float(np.max(np.abs(lse.cpu().numpy() - want_l)))
-        assert err_o <= k * OUT_TOL * max(1.0, vmax) and err_l <= k * (8e-3 if sharp else LSE_TOL), (err_o, err_l)
+        ab.assert_within(out.cpu().numpy().astype(np.float64), lse.cpu().numpy().astype(np.float64),
+                         want_o, want_l, tol_o, tol_l, what=(T, style, block_tokens, n_q, sharp))
     finally:
         r.destroy()
 
