@@ -50,7 +50,8 @@ typedef enum {
   TDK_OK = 0,
   TDK_ERR_INVALID_ARG = 1,   /* NULL, out-of-range or inconsistent argument           */
   TDK_ERR_UNSUPPORTED = 2,   /* a valid request this build has no kernel for          */
-  TDK_ERR_CAPACITY = 3,      /* reserved: capacity problems are reported on the device */
+  TDK_ERR_CAPACITY = 3,      /* the round exceeds a fixed limit of the call (tdk_diff_encode_static); a diff
+                                buffer that is too small is reported on the device (tdk_diff.overflow)  */
   TDK_ERR_HIP = 4,           /* a HIP runtime call failed (no GPU, launch error, ...)  */
   TDK_ERR_NOMEM = 5          /* host or device allocation failed                      */
 } tdk_status;
@@ -185,6 +186,18 @@ tdk_status tdk_rerotate_round(tdk_round* r, int32_t layer, const tdk_layer_io* i
  * Reads the pool, writes *out.  Errors as above plus INVALID_ARG for eps or NULL diff members. */
 tdk_status tdk_diff_encode(tdk_round* r, int32_t layer, const tdk_layer_io* io, float eps,
                            const tdk_diff* out, void* hip_stream);
+
+/* tdk_diff_encode for callers that cannot let the library own device allocations of its own choosing at
+ * call time: code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same
+ * arguments, same kernels and bit-identical results, but the per-(agent, page) flag bytes live in a static
+ * device array inside the library (TDK_STATIC_SCRATCH_BYTES per GPU, held until the process ends) instead of
+ * the round's allocation.  Calls no hipMalloc / hipFree and takes no timing events.  A round with more than
+ * TDK_STATIC_SCRATCH_BYTES (agent, page) pairs is refused with TDK_ERR_CAPACITY before anything is enqueued.
+ * All calls on one GPU share the array (the compare kernel rewrites every flag of its round, so earlier
+ * contents never matter): calls that overlap in time on one GPU race, whatever their rounds or streams. */
+#define TDK_STATIC_SCRATCH_BYTES (4u << 20)
+tdk_status tdk_diff_encode_static(tdk_round* r, int32_t layer, const tdk_layer_io* io, float eps,
+                                  const tdk_diff* out, void* hip_stream);
 
 /* Writes every agent's shared span: pages listed in the diff from the payload, all others from the
  * re-rotated master.  `in` must hold what tdk_diff_encode produced for this round (ascending

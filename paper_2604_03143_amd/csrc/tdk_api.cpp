@@ -5,6 +5,7 @@
 #include <cstdio>
 #include <cstring>
 #include <memory>
+#include <mutex>
 #include <new>
 #include <string>
 #include <vector>
@@ -13,9 +14,18 @@
 
 using namespace tdk;
 
+// Flag scratch of tdk_diff_encode_static: one byte per (agent, master page) of the round being encoded.
+// Every GPU the library runs on holds its own copy of this array until the process ends.  In host code
+// the name is only a handle for hipGetSymbolAddress; kernels get the address that call returns.
+static __device__ __align__(256) unsigned char scratch[TDK_STATIC_SCRATCH_BYTES];
+
 namespace {
 
 thread_local std::string g_last_error;
+
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+void* g_scratch_ptr[kMaxDevices] = {nullptr};     // device address of `scratch` on each device, once resolved
 
 tdk_status fail(tdk_status st, const std::string& msg) {
   g_last_error = msg;
@@ -643,14 +653,20 @@ tdk_status tdk_rerotate_round(tdk_round* r, int32_t layer, const tdk_layer_io* i
   });
 }
 
+static tdk_status check_encode(const tdk_round* r, int32_t layer, const tdk_layer_io* io, float eps, const tdk_diff* out) {
+  tdk_status st = check_step(r, layer, io);
+  if (st != TDK_OK) return st;
+  st = check_diff(r, out, true);
+  if (st != TDK_OK) return st;
+  if (!(eps >= 0.0f) || !std::isfinite(eps)) return fail(TDK_ERR_INVALID_ARG, "eps must be finite and >= 0");
+  return TDK_OK;
+}
+
 static tdk_status encode_planes(tdk_round* r, int32_t layer, const tdk_layer_io* io, float eps, int planes,
                                 const tdk_diff* out, void* hip_stream) {
   return guarded([&]() -> tdk_status {
-    tdk_status st = check_step(r, layer, io);
+    tdk_status st = check_encode(r, layer, io, eps, out);
     if (st != TDK_OK) return st;
-    st = check_diff(r, out, true);
-    if (st != TDK_OK) return st;
-    if (!(eps >= 0.0f) || !std::isfinite(eps)) return fail(TDK_ERR_INVALID_ARG, "eps must be finite and >= 0");
     hipStream_t s = static_cast<hipStream_t>(hip_stream);
     const LayerDev l = layer_dev(io);
     const DiffDev d = diff_dev(out);
@@ -660,6 +676,49 @@ static tdk_status encode_planes(tdk_round* r, int32_t layer, const tdk_layer_io*
     // the number of listed pages is known on the device only: a fixed grid strides over them
     const int grid = (int)std::min<int64_t>(std::min<int64_t>(out->capacity_pages, r->total_pages), 1 << 20);
     TDK_LAUNCH(r, TDK_KERNEL_GATHER, s, launch_gather(r->rd, l, d, planes, grid, s));
+    return TDK_OK;
+  });
+}
+
+// Device address of the static flag scratch on the current device, resolved once per device.
+static tdk_status static_scratch(int device, void** out) {
+  if (device < 0 || device >= kMaxDevices) return fail(TDK_ERR_UNSUPPORTED, "device ordinal beyond the static scratch table");
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (!g_scratch_ptr[device]) {
+    void* p = nullptr;
+    hipError_t e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+    if (e != hipSuccess || !p) return hip_fail(e, "hipGetSymbolAddress(scratch)");
+    g_scratch_ptr[device] = p;
+  }
+  *out = g_scratch_ptr[device];
+  return TDK_OK;
+}
+
+tdk_status tdk_diff_encode_static(tdk_round* r, int32_t layer, const tdk_layer_io* io, float eps,
+                                  const tdk_diff* out, void* hip_stream) {
+  return guarded([&]() -> tdk_status {
+    tdk_status st = check_encode(r, layer, io, eps, out);     // includes: the round's device is the current one
+    if (st != TDK_OK) return st;
+    if (r->total_pages > (int64_t)TDK_STATIC_SCRATCH_BYTES)
+      return fail(TDK_ERR_CAPACITY, "round has more (agent, page) pairs than TDK_STATIC_SCRATCH_BYTES");
+    void* flags = nullptr;
+    st = static_scratch(r->device, &flags);
+    if (st != TDK_OK) return st;
+    // the same kernels as tdk_diff_encode, their flag bytes in the static array instead of the round's own
+    // allocation; the compare kernel writes the flag of every (agent, page) of the round before compaction
+    // reads any, so nothing of an earlier call is ever read and nothing needs clearing
+    RoundDev rd = r->rd;
+    rd.flags = static_cast<uint8_t*>(flags);
+    hipStream_t s = static_cast<hipStream_t>(hip_stream);
+    const LayerDev l = layer_dev(io);
+    const DiffDev d = diff_dev(out);
+    const int planes = TDK_PLANE_K | TDK_PLANE_V;
+    hipError_t e = launch_flag(rd, l, eps, planes, s);
+    if (e == hipSuccess) e = launch_count(rd, d, s);
+    if (e == hipSuccess) e = launch_index(rd, d, s);
+    const int grid = (int)std::min<int64_t>(std::min<int64_t>(out->capacity_pages, r->total_pages), 1 << 20);
+    if (e == hipSuccess) e = launch_gather(rd, l, d, planes, grid, s);
+    if (e != hipSuccess) return hip_fail(e, "kernel launch (tdk_diff_encode_static)");
     return TDK_OK;
   });
 }

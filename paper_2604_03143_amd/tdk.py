@@ -24,11 +24,12 @@ PLANE_K, PLANE_V = 1, 2
  KERNEL_ATTEND_MERGE) = range(14)
 KERNEL_KINDS = 14
 TUNE_ALL, TUNE_DEFAULT = 127, 63
+STATIC_SCRATCH_BYTES = 4 << 20
 
 EXPORTS = (
     "tdk_status_str", "tdk_last_error", "tdk_version", "tdk_kernel_name",
     "tdk_round_create", "tdk_round_destroy", "tdk_scratch_bytes", "tdk_round_tune",
-    "tdk_rerotate_round", "tdk_diff_encode", "tdk_diff_decode", "tdk_restore_layers", "tdk_check_layer",
+    "tdk_rerotate_round", "tdk_diff_encode", "tdk_diff_encode_static", "tdk_diff_decode", "tdk_restore_layers", "tdk_check_layer",
     "tdk_diff_encode_plane", "tdk_diff_decode_plane", "tdk_attend_workspace_bytes", "tdk_attend_shared",
     "tdk_prompt_plan_create", "tdk_prompt_plan_destroy", "tdk_prompt_plan_n_sessions", "tdk_prompt_plan_span",
     "tdk_prompt_plan_session_of", "tdk_prompt_plan_segments",
@@ -120,6 +121,7 @@ def load() -> C.CDLL:
     L.tdk_round_tune.argtypes = [C.c_void_p, C.c_int32, C.c_int32]
     L.tdk_rerotate_round.argtypes = [C.c_void_p, C.c_int32, C.POINTER(LayerIO), C.c_void_p]
     L.tdk_diff_encode.argtypes = [C.c_void_p, C.c_int32, C.POINTER(LayerIO), C.c_float, C.POINTER(Diff), C.c_void_p]
+    L.tdk_diff_encode_static.argtypes = L.tdk_diff_encode.argtypes
     L.tdk_diff_decode.argtypes = [C.c_void_p, C.c_int32, C.POINTER(LayerIO), C.POINTER(Diff), C.c_void_p]
     L.tdk_diff_encode_plane.argtypes = [C.c_void_p, C.c_int32, C.POINTER(LayerIO), C.c_float, C.c_int32, C.POINTER(Diff), C.c_void_p]
     L.tdk_diff_decode_plane.argtypes = [C.c_void_p, C.c_int32, C.POINTER(LayerIO), C.c_int32, C.POINTER(Diff), C.c_void_p]
@@ -275,6 +277,11 @@ def tdk_rerotate_round(r: Round, layer: int, io: LayerIO, stream: int = 0) -> No
 def tdk_diff_encode(r: Round, layer: int, io: LayerIO, eps: float, out: Diff, stream: int = 0) -> None:
     _check(load().tdk_diff_encode(r.handle, layer, C.byref(io), C.c_float(eps), C.byref(out),
                                   C.c_void_p(stream)), "tdk_diff_encode")
+
+
+def tdk_diff_encode_static(r: Round, layer: int, io: LayerIO, eps: float, out: Diff, stream: int = 0) -> None:
+    _check(load().tdk_diff_encode_static(r.handle, layer, C.byref(io), C.c_float(eps), C.byref(out),
+                                         C.c_void_p(stream)), "tdk_diff_encode_static")
 
 
 def tdk_diff_decode(r: Round, layer: int, io: LayerIO, d: Diff, stream: int = 0) -> None:
