@@ -29,7 +29,7 @@ def parse():
     ap.add_argument("--workload", default="batched250")
     ap.add_argument("--ring", type=int, default=0, help="resident layer buffers (0 = automatic)")
     ap.add_argument("--group", type=int, default=0, help="agents per work item (0 = automatic)")
-    ap.add_argument("--flags", type=int, default=63, help="cache-policy bits (TDK_TUNE_*), default 63")
+    ap.add_argument("--flags", type=int, default=-1, help="tuning bits (TDK_TUNE_*), default: the library's")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-check", action="store_true")
     ap.add_argument("--graph", action="store_true",
@@ -38,17 +38,37 @@ def parse():
                     help="physical page placement of the synthetic pool (fragmented = the graded recipe)")
     ap.add_argument("--layout", default="identity", choices=["identity", "permuted"],
                     help="order of the shared blocks in every agent's prompt (identity = the graded recipe)")
-    ap.add_argument("--mode", default="step", choices=["step", "restore", "check", "planes", "attend"],
+    ap.add_argument("--mode", default="step", choices=["step", "restore", "check", "planes", "attend", "timeline"],
                     help="step: the whole hot path (default, the headline metric); restore: layerwise ping-pong "
                          "restore from pinned host memory (Alg. 1) against a dense restore")
     ap.add_argument("--n-q", type=int, default=1, help="attend mode: query tokens per agent")
     ap.add_argument("--q-heads", type=int, default=0, help="attend mode: query heads (0 = 5 per KV head)")
     ap.add_argument("--layers", type=int, default=0, help="override the layer count (for profiling runs only)")
+    ap.add_argument("--sessions", type=int, default=0, help="override the number of sessions of the workload (experiments only; "
+                    "the line then names the change in config.workload)")
+    ap.add_argument("--agents", type=int, default=0, help="override the agents per session (experiments only)")
+    ap.add_argument("--csrc-hash", action="store_true", help="print the hash of the kernel sources (the one the "
+                    "counter summaries under profiles/ carry) and exit")
     return ap.parse_args()
+
+
+def csrc_hash():
+    """sha256 over the sources the library is built from: ties a counter summary under profiles/ to the kernels it measured."""
+    import hashlib
+    h = hashlib.sha256()
+    files = []
+    for d in (os.path.join(ROOT, "paper_2604_03143_amd", "csrc"), os.path.join(ROOT, "include")):
+        files += [os.path.join(d, f) for f in sorted(os.listdir(d)) if f.endswith((".hip", ".cpp", ".h"))]
+    for f in files:
+        h.update(os.path.basename(f).encode() + b"\0" + open(f, "rb").read())
+    return h.hexdigest()[:16]
 
 
 def main():
     args = parse()
+    if args.csrc_hash:
+        print(csrc_hash())
+        return
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this path runs on one GPU only (every session, layer and KV head is independent; "
               "no multi-GPU figure is produced).  Use --gpus 1.", file=sys.stderr)
@@ -74,8 +94,15 @@ def main():
         return planes_mode(args, tdk, wl, np, torch, dev)
     if args.mode == "attend":
         return attend_mode(args, tdk, wl, np, torch, dev)
+    if args.mode == "timeline":
+        return timeline_mode(args, tdk, wl, np, torch, dev)
 
     spec = wl.CONFIGS[args.workload]
+    if args.sessions or args.agents:
+        import dataclasses
+        spec = dataclasses.replace(spec, n_sessions=args.sessions or spec.n_sessions,
+                                   agents_per_session=args.agents or spec.agents_per_session)
+        args.workload = f"{args.workload}[sessions={spec.n_sessions},agents={spec.agents_per_session}]"
     L = args.layers or spec.num_layers
     rnd = wl.make_round(spec, alloc=args.alloc)
     if args.layout == "permuted":
@@ -92,8 +119,8 @@ def main():
     ring = min(ring, L)
 
     r = tdk.round_from_workload(rnd)
-    if args.group or args.flags != 63:
-        tdk.tdk_round_tune(r, args.group, args.flags)
+    if args.group or args.flags >= 0:
+        tdk.tdk_round_tune(r, args.group, args.flags if args.flags >= 0 else tdk.TUNE_DEFAULT)
 
     def new_diff():
         d = dict(count=torch.zeros(A, dtype=torch.int32, device=dev),
@@ -160,8 +187,7 @@ def main():
             g.replay()
         torch.cuda.synchronize()
         g_ms = (time.perf_counter() - t0) * 1e3 / args.steps
-        graph_out = dict(ms_per_step=round(g_ms, 3), value=round(agent_tokens / (g_ms * 1e-3), 1),
-                         kernels_per_graph=7 * L)
+        graph_out = dict(ms_per_step=round(g_ms, 3), value=round(agent_tokens / (g_ms * 1e-3), 1))
         del g
 
     # the same steps once more with every kernel launch bracketed by HIP events on the launch stream
@@ -216,13 +242,15 @@ def main():
         return nbytes / (us * 1e-6) / 1e9 if us > 0 else 0.0
 
     us = {k.replace("tdk_", "").replace("_kernel", ""): v["avg_us"] for k, v in kt.items()}
-    enc_us = us["flag"] + us["count"] + us["index"] + us["gather"]
+    enc_us = us["flag"] + us["compact"] + us["gather"]
     dec_us = us["decode"] + us["scatter"]
     rates = dict(rerotate_GBps=gbps(alg["rerotate"], us["rerotate"]),
                  encode_GBps=gbps(alg["encode"], enc_us),
                  decode_GBps=gbps(alg["decode"], dec_us),
                  encode_decode_GBps=gbps(alg["encode"] + alg["decode"], enc_us + dec_us))
+    by_slot = {k: [round(float(np.median(v.reshape(args.steps, L)[:, q::ring])), 1) for q in range(ring)] for k, v in call_us.items()}
     calls = {k: dict(median_us=round(float(np.median(v)), 2), min_us=round(float(v.min()), 2), n=int(v.size),
+                     median_us_by_ring_slot=by_slot[k],
                      GBps_at_median=round(gbps(alg[k], float(np.median(v))), 1),
                      pct_hbm_peak_at_median=round(100 * gbps(alg[k], float(np.median(v))) / HBM_PEAK_GBPS, 2))
              for k, v in call_us.items()}
@@ -239,6 +267,7 @@ def main():
                          "one), so the pipeline figure is the robust one")
     roofline = dict(bound="hbm", kernel=f"tdk_{dom}_kernel", achieved=round(achieved, 1), peak=HBM_PEAK_GBPS,
                     unit="GB/s", frac=round(achieved / HBM_PEAK_GBPS, 4), traffic=traffic,
+                    traffic_source=traffic_note(args.workload),
                     algorithmic_bytes_per_launch=dom_bytes, avg_launch_us=round(us[dom], 2))
 
     # ---- what HBM delivers on this machine for the bare access patterns (no arithmetic) ---------------
@@ -269,7 +298,20 @@ def main():
             lambda: tdk.tdk_util_page_fill(src, ids, n_pg, page_b, 5, stream)) / 1e9, 1)
         ceil[f"{nm}_page_read_GBps"] = round(n_pg * page_b / timed(
             lambda: tdk.tdk_util_page_read(src, ids, n_pg, page_b, sink, stream)) / 1e9, 1)
-    del src
+    # the same in the page kernels' own access form (K and V planes, four wavefronts on interleaved rows, streaming
+    # stores / non-temporal loads, a group of pages per workgroup): what the product's traversal can reach at best
+    half = n_pg // 2
+    plane_k, plane_v = src[:half * page_b], src[half * page_b:2 * half * page_b]
+    ids_half = {"sequential": torch.arange(half, dtype=torch.int32, device=dev),
+                "scattered": torch.from_numpy(np.random.default_rng(8).permutation(half).astype(np.int32)).to(dev)}
+    grp = r_group(tdk, r, args)
+    for nm, ids in ids_half.items():
+        ceil[f"{nm}_page_write_product_form_GBps"] = round(2 * half * page_b / timed(
+            lambda: tdk.tdk_util_page_fill_product(plane_k, plane_v, ids, half, grp, spec.num_kv_heads, T, 5, stream)) / 1e9, 1)
+        ceil[f"{nm}_page_read_product_form_GBps"] = round(2 * half * page_b / timed(
+            lambda: tdk.tdk_util_page_read_product(plane_k, plane_v, ids, half, grp, spec.num_kv_heads, T, sink, stream)) / 1e9, 1)
+    ceil["product_form_pages_per_workgroup"] = grp
+    del src, plane_k, plane_v
 
     # ---- correctness at full size, outside the timed region ---------------------------------------
     check = {}
@@ -295,6 +337,7 @@ def main():
                value=round(value, 1), unit="tokens/s", n_gpus=1, steps=args.steps, warmup=args.warmup,
                ms_per_step=round(ms_per_step, 3), higher_is_better=True, scaling="weak", vs_baseline=None,
                dtype="bf16", data="synthetic",
+               pool_addresses=[dict(pk=hex(s["pk"].data_ptr()), pv=hex(s["pv"].data_ptr()), mk=hex(s["mk"].data_ptr())) for s in slots],
                config=dict(workload=args.workload, layers=L, agents=A, sessions=rnd.n_sessions,
                            span_tokens=int(spec.span_tokens), page_tokens=T, perturbed_pages=n_pert,
                            ring_layers=ring, alloc=args.alloc, layout=args.layout, agents_per_group="auto" if not args.group else args.group,
@@ -433,8 +476,8 @@ def check_mode(args, tdk, wl, np, torch, dev):
     rows = rnd.pool_pages * T
     st = torch.cuda.current_stream().cuda_stream
     r = tdk.round_from_workload(rnd)
-    if args.group or args.flags != 63:
-        tdk.tdk_round_tune(r, args.group, args.flags)
+    if args.group or args.flags >= 0:
+        tdk.tdk_round_tune(r, args.group, args.flags if args.flags >= 0 else tdk.TUNE_DEFAULT)
     ring = args.ring or 4
     ratio = 0.15
     n_tok = rnd.agent_tokens()
@@ -683,17 +726,142 @@ def attend_mode(args, tdk, wl, np, torch, dev):
     r.destroy()
 
 
+def timeline_mode(args, tdk, wl, np, torch, dev):
+    """Workgroup timeline of the three page kernels (rerotate, decode, compare) inside the step's own sequence:
+    when every workgroup of a launch started and ended (device clock, 10 ns ticks).  Shows how long the launch
+    takes to fill the chip, how many workgroups run at a time, and how long the chip drains after the last
+    workgroup has started (the tail that a coarse work list would leave)."""
+    spec = wl.CONFIGS[args.workload]
+    rnd = wl.make_round(spec, alloc=args.alloc)
+    A, T, RE = rnd.n_agents, spec.page_tokens, spec.row_elems
+    rows = rnd.pool_pages * T
+    st = torch.cuda.current_stream().cuda_stream
+    r = tdk.round_from_workload(rnd)
+    if args.group or args.flags >= 0:
+        tdk.tdk_round_tune(r, args.group, args.flags if args.flags >= 0 else tdk.TUNE_DEFAULT)
+    n_pert = sum(len(p) for p in rnd.perturbed)
+    cap = n_pert + 64
+    slots = []
+    pert_rows = torch.from_numpy(wl.perturbed_rows(rnd)).to(dev)
+    for s_ in range(2):
+        mk, mv = wl.master_device(rnd, s_, dev)
+        pk = torch.zeros((rows, RE), dtype=torch.int16, device=dev)
+        pv = torch.zeros((rows, RE), dtype=torch.int16, device=dev)
+        io = tdk.layer_io(mk, mv, pk, pv, rnd.pool_pages)
+        d = dict(count=torch.zeros(A, dtype=torch.int32, device=dev), offset=torch.zeros(A + 1, dtype=torch.int64, device=dev),
+                 idx=torch.full((cap,), -1, dtype=torch.int32, device=dev),
+                 payload=torch.zeros((cap, 2 * T * RE), dtype=torch.int16, device=dev),
+                 overflow=torch.zeros(1, dtype=torch.int32, device=dev))
+        d["c"] = tdk.diff(d["count"], d["offset"], d["idx"], d["payload"], cap, d["overflow"])
+        tdk.tdk_rerotate_round(r, s_, io, st)
+        wl.perturb_device(rnd, s_, pk, pv, rows=pert_rows)
+        tdk.tdk_diff_encode(r, s_, io, spec.eps, d["c"], st)
+        slots.append(dict(io=io, d=d, keep=(mk, mv, pk, pv)))
+    torch.cuda.synchronize()
+    nbytes = tdk.tdk_timeline_bytes(r)
+    stamps = torch.zeros(nbytes // 8, dtype=torch.int64, device=dev)
+
+    calls = [("rerotate", lambda s_: tdk.tdk_rerotate_round(r, 0, s_["io"], st)),
+             ("decode", lambda s_: tdk.tdk_diff_decode(r, 0, s_["io"], s_["d"]["c"], st)),
+             ("encode", lambda s_: tdk.tdk_diff_encode(r, 0, s_["io"], spec.eps, s_["d"]["c"], st))]
+
+    def sequence(upto, stamped):
+        """The step's sequence on both slots; the launch to look at is call `stamped` on slot 1."""
+        for k, s_ in enumerate(slots):
+            for j, (nm, fn) in enumerate(calls):
+                on = k == 1 and j == stamped
+                if on:
+                    tdk.tdk_timeline_set(r, stamps, nbytes)
+                fn(s_)
+                if on:
+                    tdk.tdk_timeline_set(r, None, 0)
+
+    out_k = {}
+    for j, (nm, _) in enumerate(calls):
+        sequence(None, -1)
+        torch.cuda.synchronize()
+        stamps.zero_()
+        sequence(None, j)
+        torch.cuda.synchronize()
+        h4 = stamps.cpu().numpy().reshape(-1, 4)
+        h4 = h4[h4[:, 0] > 0]
+        h = h4[:, :2]
+        xcd = (h[:, 0] & 15).astype(np.int64)
+        s0, e0 = (h[:, 0] & ~15).astype(np.float64) * 1e-2, h[:, 1].astype(np.float64) * 1e-2      # us
+        t0 = s0.min()
+        s0 -= t0; e0 -= t0
+        span = float(e0.max())
+        # workgroups running at time t
+        ev = np.concatenate([np.stack([s0, np.ones_like(s0)], 1), np.stack([e0, -np.ones_like(e0)], 1)])
+        ev = ev[np.argsort(ev[:, 0], kind="stable")]
+        active = np.cumsum(ev[:, 1])
+        tt = ev[:, 0]
+        mid = (tt > 0.2 * span) & (tt < 0.8 * span)
+        steady = float(np.median(active[mid])) if mid.any() else float(active.max())
+        full = np.nonzero(active >= 0.9 * steady)[0]
+        ramp = float(tt[full[0]]) if full.size else 0.0
+        last_start = float(s0.max())
+        below = np.nonzero(active >= 0.5 * steady)[0]
+        half_until = float(tt[below[-1]]) if below.size else span
+        dur = e0 - s0
+        out_k[nm] = dict(workgroups=int(h.shape[0]), span_us=round(span, 2), running_at_a_time=steady,
+                         us_until_90pct_running=round(ramp, 2),
+                         us_after_last_start=round(span - last_start, 2),
+                         us_below_half_running_at_end=round(span - half_until, 2),
+                         workgroup_us=dict(median=round(float(np.median(dur)), 2), p99=round(float(np.percentile(dur, 99)), 2),
+                                           max=round(float(dur.max()), 2)),
+                         first_end_us=round(float(e0.min()), 2),
+                         us_from_item_taken=None if not (h4[:, 2] > 0).all() else dict(
+                             staged_median=round(float(np.median((h4[:, 2] - (h4[:, 0] & ~15)) * 1e-2)), 2),
+                             first_agent_written_median=round(float(np.median((h4[:, 3] - (h4[:, 0] & ~15)) * 1e-2)), 2),
+                             staged_p90=round(float(np.percentile((h4[:, 2] - (h4[:, 0] & ~15)) * 1e-2, 90)), 2),
+                             first_agent_written_p90=round(float(np.percentile((h4[:, 3] - (h4[:, 0] & ~15)) * 1e-2, 90)), 2)),
+                         running_every_2pct=[int(active[np.searchsorted(tt, q * span / 50, side="right") - 1]) for q in range(1, 50)],
+                         finished_per_2pct=np.histogram(e0, bins=50, range=(0, span))[0].tolist(),
+                         per_xcd=dict(workgroups=np.bincount(xcd, minlength=8).tolist(),
+                                      last_end_us=[round(float(e0[xcd == x].max()), 1) if (xcd == x).any() else None for x in range(8)],
+                                      last_start_us=[round(float(s0[xcd == x].max()), 1) if (xcd == x).any() else None for x in range(8)]))
+    print(json.dumps(dict(metric="workgroup timeline of the page kernels", unit="us", n_gpus=1, data="synthetic",
+                          config=dict(workload=args.workload, agents=A, agents_per_group=tdk.tdk_round_agents_per_group(r)),
+                          kernels=out_k)))
+    r.destroy()
+
+
+def r_group(tdk, r, args):
+    """Agents per work item of the round (what the product-form probes use as pages per workgroup)."""
+    return tdk.tdk_round_agents_per_group(r)
+
+
 def read_traffic(workload, kernel, prefix="hbm_traffic"):
-    """HBM bytes per launch of `kernel` from the committed rocprofv3 counter summary (None if absent)."""
+    """HBM bytes per launch of `kernel` from the committed rocprofv3 counter summary, or None: if there is no
+    summary, or if it was taken from other kernel sources than the ones this run uses (its `csrc_sha256` line)."""
     path = os.path.join(ROOT, "profiles", f"{prefix}_{workload}.txt")
+    value, tagged = None, None
     try:
         for line in open(path):
             f = line.split()
+            if len(f) >= 2 and f[0].lstrip("# ") == "csrc_sha256":
+                tagged = f[-1]
             if len(f) == 4 and f[0] == kernel:
-                return float(f[3])
+                value = float(f[3])
     except OSError:
-        pass
-    return None
+        return None
+    return value if tagged == csrc_hash() else None
+
+
+def traffic_note(workload, prefix="hbm_traffic"):
+    path = os.path.join(ROOT, "profiles", f"{prefix}_{workload}.txt")
+    if not os.path.exists(path):
+        return "no counter summary for this workload under profiles/"
+    tagged = None
+    for line in open(path):
+        f = line.split()
+        if len(f) >= 2 and f[0].lstrip("# ") == "csrc_sha256":
+            tagged = f[-1]
+    if tagged != csrc_hash():
+        return (f"profiles/{prefix}_{workload}.txt was taken from kernel sources {tagged}, this run uses {csrc_hash()}: "
+                "traffic withheld")
+    return f"from profiles/{prefix}_{workload}.txt (rocprofv3 --pmc, same kernel sources {tagged})"
 
 
 def cpu_baseline(rnd, slot, r, stream, L, tdk, wl, np, torch):
@@ -774,7 +942,16 @@ def cpu_baseline(rnd, slot, r, stream, L, tdk, wl, np, torch):
     tdo.diff_decode(g, hr, mk, mv, dk, dv, od)
     one_thread_s = time.perf_counter() - t0
     tdo.set_threads(threads)
+    model = "unknown"
+    try:
+        for line in open("/proc/cpuinfo"):
+            if line.startswith("model name"):
+                model = line.split(":", 1)[1].strip()
+                break
+    except OSError:
+        pass
     cpu = dict(value=round(toks / (layer_step_s * L), 1), unit="tokens/s", cores=threads, kind="oracle",
+               affinity_cores=len(os.sched_getaffinity(0)), cpu_model=model,
                sample=f"layer 0, session 0 ({n} agents x {int(sub.span_tokens[0])} tokens): rerotate+encode+decode, "
                       f"{reps} repetitions, {spent:.1f} s; scaled to {L} layers",
                layer_step_s=round(layer_step_s, 3),

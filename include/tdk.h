@@ -143,9 +143,18 @@ size_t     tdk_scratch_bytes(const tdk_round* r);       /* device bytes the roun
                                             memory-side cache before anything is written           */
 #define TDK_TUNE_PREFETCH_MASTER_DECODE 64 /* the same in decode: worth 5 % when its masters were not just
                                             read by another kernel, costs 0.6 % when they were    */
-#define TDK_TUNE_ALL                127
-#define TDK_TUNE_DEFAULT            63
+#define TDK_TUNE_XCD_QUEUES         128  /* page kernels: resident workgroups take work items from one queue per XCD
+                                            and, when theirs is empty, from the others' (the XCDs do not write at the
+                                            same rate); off: one workgroup per item, fixed to an XCD by its number */
+#define TDK_TUNE_XCD_QUEUES_READ    256  /* the same for the kernels that only read the pool (compare, key difference) */
+#define TDK_TUNE_TAPER              512  /* work list: smaller agent groups for the last pages, so that a launch does not
+                                            end with a few long items on an otherwise idle chip                      */
+#define TDK_TUNE_QUEUES_ANY_SIZE    1024 /* queues also for rounds with fewer than four items per resident workgroup
+                                            (by default such launches stay static: it is faster there)             */
+#define TDK_TUNE_ALL                2047
+#define TDK_TUNE_DEFAULT            191
 tdk_status tdk_round_tune(tdk_round* r, int32_t agents_per_group, int32_t flags);
+int32_t    tdk_round_agents_per_group(const tdk_round* r);   /* the value in use (resolved if automatic); 0 for NULL */
 
 /* Per-layer views, all DEV.
  *   master_k/v  [sum_s S_s][H][D] bf16, sessions concatenated in order (token-major rows)
@@ -332,46 +341,10 @@ tdk_status tdk_restore_layers(tdk_round* r, int32_t first_layer, int32_t n_layer
                               const tdk_layer_io* io, const tdk_diff* diffs, const tdk_pingpong* pp,
                               void* compute_stream, void* copy_stream);
 
-/* Kernel timing with HIP events on the caller's stream (off by default).  When on, every kernel
- * launch of the step calls is bracketed by two events; tdk_timing_read waits for them. */
-#define TDK_KERNEL_REROTATE 0
-#define TDK_KERNEL_FLAG     1
-#define TDK_KERNEL_COUNT    2
-#define TDK_KERNEL_INDEX    3
-#define TDK_KERNEL_GATHER   4
-#define TDK_KERNEL_DECODE   5
-#define TDK_KERNEL_SCATTER  6
-#define TDK_KERNEL_KEYDIFF  7
-#define TDK_KERNEL_SELECT   8
-#define TDK_KERNEL_MASTER   9
-#define TDK_KERNEL_ATTEND_QROT   10
-#define TDK_KERNEL_ATTEND_MASTER 11   /* also the launch that holds the master and the listed-pages pass together */
-#define TDK_KERNEL_ATTEND_DIFF   12   /* (no launches of its own when that shared launch is used)                  */
-#define TDK_KERNEL_ATTEND_MERGE  13
-#define TDK_KERNEL_KINDS    14
-tdk_status tdk_timing_enable(tdk_round* r, int32_t on);
-tdk_status tdk_timing_read(tdk_round* r, int32_t kernel, double* total_ms, int64_t* launches);
-tdk_status tdk_timing_reset(tdk_round* r);
-const char* tdk_kernel_name(int32_t kernel);   /* device symbol name prefix, for profiler output */
-
 /* Storage arithmetic of Sec. 6.4 (host only). */
 double tdk_dense_bytes(const tdk_model* m, int64_t span_tokens);   /* one layer of one cache      */
 double tdk_diff_bytes(const tdk_model* m, int64_t diff_pages);     /* values + idx + count/offset */
 double tdk_family_cost(int64_t n_agents, double ratio);            /* 1 + (N-1)/R full caches     */
-
-/* Plain device copy / fill of `bytes` (multiple of 16) with 16-byte accesses: the measured HBM
- * ceiling the step kernels are compared with, and the known-size reference for traffic counters. */
-tdk_status tdk_util_copy(void* dst, const void* src, size_t bytes, void* hip_stream);
-tdk_status tdk_util_fill(void* dst, uint32_t word, size_t bytes, void* hip_stream);
-
-/* Access-pattern probes: one workgroup per page fills (reads) page_bytes (multiple of 16) at
- * dst + page_ids[i] * page_bytes for i < n_pages; page_ids is DEV.  With a permuted id list this is
- * the page kernels' access pattern with no arithmetic.  The caller guarantees every id is in range.
- * sink16: 16 DEV bytes that are never written in practice (they keep the loads alive). */
-tdk_status tdk_util_page_fill(void* dst, const int32_t* page_ids, int32_t n_pages, size_t page_bytes,
-                              uint32_t word, void* hip_stream);
-tdk_status tdk_util_page_read(const void* src, const int32_t* page_ids, int32_t n_pages, size_t page_bytes,
-                              void* sink16, void* hip_stream);
 
 #ifdef __cplusplus
 }

@@ -10,7 +10,7 @@ ROOT = os.path.dirname(PKG)
 CSRC = os.path.join(PKG, "csrc")
 LIB = os.path.join(PKG, "libtdk.so")
 SOURCES = [os.path.join(CSRC, "tdk_kernels.hip"), os.path.join(CSRC, "tdk_attend.hip"), os.path.join(CSRC, "tdk_api.cpp"), os.path.join(CSRC, "tdk_prompt.cpp")]
-HEADERS = [os.path.join(CSRC, "tdk_internal.h"), os.path.join(ROOT, "include", "tdk.h")]
+HEADERS = [os.path.join(CSRC, "tdk_internal.h"), os.path.join(ROOT, "include", "tdk.h"), os.path.join(ROOT, "include", "tdk_bench.h")]
 
 
 def hipcc_command(out: str = LIB, extra=()):

@@ -11,6 +11,7 @@
 #include <vector>
 
 #include "tdk_internal.h"
+#include "tdk_bench.h"
 
 using namespace tdk;
 
@@ -104,38 +105,41 @@ namespace {
 // Work list: one item per (master page, agent group).  Items that share a master page are given
 // workgroup ids that are congruent modulo 8, so that (with round-robin dispatch of workgroups to
 // the 8 XCDs) they run on the same XCD and the re-read of the master page hits that XCD's L2.
-void build_work(const tdk_round& r, int group, std::vector<WorkItem>& work) {
+// taper: the pages at the end of the list are cut into smaller groups (a third of the group size over
+// the last tenth of the work, single agents over the last fiftieth), so that the launch does not end
+// with a few long items running on an otherwise idle chip.
+void build_work(const tdk_round& r, int group, bool taper, std::vector<WorkItem>& work) {
   work.clear();
-  struct PageRef { int32_t session, page; };
-  std::vector<PageRef> pages;
   std::vector<int32_t> order_begin(r.sessions.size(), 0);
   int32_t cursor = 0;
+  int64_t total = 0, done = 0;
   for (size_t s = 0; s < r.sessions.size(); ++s) {
     order_begin[s] = cursor;
     cursor += (int32_t)r.sessions[s].agents.size();
-  }
-  // group the pages by their session's group count so that every block of 8 pages has one count
-  std::vector<int> ngroups(r.sessions.size(), 0);
-  for (size_t s = 0; s < r.sessions.size(); ++s) {
-    const int n = (int)r.sessions[s].agents.size();
-    ngroups[s] = n ? (n + group - 1) / group : 0;
+    total += (int64_t)r.sessions[s].pages * (int64_t)r.sessions[s].agents.size();
   }
   for (size_t s = 0; s < r.sessions.size(); ++s) {
-    if (!ngroups[s]) continue;
-    pages.clear();
-    for (int32_t p = 0; p < r.sessions[s].pages; ++p) pages.push_back({(int32_t)s, p});
     const int n = (int)r.sessions[s].agents.size();
-    const int G = ngroups[s];
-    for (size_t q0 = 0; q0 < pages.size(); q0 += 8) {
-      const size_t qn = std::min<size_t>(8, pages.size() - q0);
+    if (!n) continue;
+    const int32_t pages = r.sessions[s].pages;
+    for (int32_t q0 = 0; q0 < pages; q0 += 8) {
+      const int32_t qn = std::min<int32_t>(8, pages - q0);
+      // every block of 8 pages has one group count
+      int g_eff = group;
+      if (taper && total > 0) {
+        if (done * 50 >= total * 49) g_eff = 1;
+        else if (done * 10 >= total * 9) g_eff = std::max(1, (group + 2) / 3);
+      }
+      const int G = (n + g_eff - 1) / g_eff;
       for (int g = 0; g < G; ++g) {
         // balanced split: the first (n % G) groups get one agent more
         const int base = n / G, extra = n % G;
         const int begin = g * base + std::min(g, extra);
         const int cnt = base + (g < extra ? 1 : 0);
-        for (size_t q = 0; q < qn; ++q)
-          work.push_back({pages[q0 + q].session, pages[q0 + q].page, order_begin[s] + begin, cnt});
+        for (int32_t q = 0; q < qn; ++q)
+          work.push_back({(int32_t)s, q0 + q, order_begin[s] + begin, cnt});
       }
+      done += (int64_t)qn * n;
     }
   }
 }
@@ -160,11 +164,21 @@ int auto_group(const tdk_round& r) {
 
 tdk_status upload_work(tdk_round* r, int group) {
   std::vector<WorkItem> work;
-  build_work(*r, group, work);
+  build_work(*r, group, (r->flags & TDK_TUNE_TAPER) != 0, work);
   if (work.size() > r->work_capacity) return fail(TDK_ERR_INVALID_ARG, "work list larger than reserved");
+  // one queue per XCD: the items the round-robin dispatch of a static launch runs there, in the same order
+  std::vector<WorkItem> queued;
+  queued.reserve(work.size());
+  for (int x = 0; x < 8; ++x) {
+    r->rd.q_begin[x] = (int32_t)queued.size();
+    for (size_t i = x; i < work.size(); i += 8) queued.push_back(work[i]);
+  }
+  r->rd.q_begin[8] = (int32_t)queued.size();
   if (!work.empty()) {
     hipError_t e = hipMemcpy(const_cast<WorkItem*>(r->rd.work), work.data(), work.size() * sizeof(WorkItem),
                              hipMemcpyHostToDevice);
+    if (e == hipSuccess) e = hipMemcpy(const_cast<WorkItem*>(r->rd.qwork), queued.data(), queued.size() * sizeof(WorkItem),
+                                       hipMemcpyHostToDevice);
     if (e != hipSuccess) return hip_fail(e, "hipMemcpy(work list)");
   }
   r->rd.n_work = (int32_t)work.size();
@@ -304,8 +318,7 @@ const char* tdk_kernel_name(int32_t kernel) {
   switch (kernel) {
     case TDK_KERNEL_REROTATE: return "tdk_rerotate_kernel";
     case TDK_KERNEL_FLAG: return "tdk_flag_kernel";
-    case TDK_KERNEL_COUNT: return "tdk_count_kernel";
-    case TDK_KERNEL_INDEX: return "tdk_index_kernel";
+    case TDK_KERNEL_COMPACT: return "tdk_compact_kernel";
     case TDK_KERNEL_GATHER: return "tdk_gather_kernel";
     case TDK_KERNEL_DECODE: return "tdk_decode_kernel";
     case TDK_KERNEL_SCATTER: return "tdk_scatter_kernel";
@@ -529,6 +542,7 @@ tdk_status round_create(const tdk_model* model, const tdk_session* sessions, int
   size_t off = 0;
   auto place = [&](size_t bytes) { size_t o = off; off = align_up(off + bytes, 256); return o; };
   const size_t o_work = place(work_cap * sizeof(WorkItem));
+  const size_t o_qwork = place(work_cap * sizeof(WorkItem));
   const size_t o_sess = place(sess_dev.size() * sizeof(SessionDev));
   const size_t o_agents = place(agent_dev.size() * sizeof(AgentDev));
   const size_t o_order = place(order.size() * sizeof(int32_t));
@@ -542,6 +556,7 @@ tdk_status round_create(const tdk_model* model, const tdk_session* sessions, int
   const size_t o_seg_off = place(any_segments ? seg_off.size() * sizeof(int32_t) : 0);
   const size_t o_seg_src = place(any_segments ? seg_src.size() * sizeof(int32_t) : 0);
   const size_t o_flags = place((size_t)flag_off);
+  const size_t o_qstate = place(16 * sizeof(int32_t));
   r->blob_bytes = std::max<size_t>(off, 256);
 
   hipError_t e = hipGetDevice(&r->device);
@@ -569,9 +584,11 @@ tdk_status round_create(const tdk_model* model, const tdk_session* sessions, int
   if (e == hipSuccess && any_segments) e = up(o_seg_off, seg_off.data(), seg_off.size() * sizeof(int32_t));
   if (e == hipSuccess && any_segments) e = up(o_seg_src, seg_src.data(), seg_src.size() * sizeof(int32_t));
   if (e == hipSuccess && flag_off) e = hipMemset(base + o_flags, 0, (size_t)flag_off);
+  if (e == hipSuccess) e = hipMemset(base + o_qstate, 0, 16 * sizeof(int32_t));
   if (e != hipSuccess) return hip_fail(e, "upload of round descriptors");
 
   r->rd.work = reinterpret_cast<const WorkItem*>(base + o_work);
+  r->rd.qwork = reinterpret_cast<const WorkItem*>(base + o_qwork);
   r->rd.sess = reinterpret_cast<const SessionDev*>(base + o_sess);
   r->rd.agents = reinterpret_cast<const AgentDev*>(base + o_agents);
   r->rd.order = reinterpret_cast<const int32_t*>(base + o_order);
@@ -579,6 +596,8 @@ tdk_status round_create(const tdk_model* model, const tdk_session* sessions, int
   r->rd.tab = reinterpret_cast<const float*>(base + o_tab);
   r->rd.tab_diff = reinterpret_cast<const float*>(base + o_tab_diff);
   r->rd.flags = reinterpret_cast<uint8_t*>(base + o_flags);
+  r->rd.q_state = reinterpret_cast<int32_t*>(base + o_qstate);
+  r->rd.n_cus = r->n_cus;
   r->rd.seg = any_segments ? 1 : 0;
   r->rd.rowmap = any_segments ? reinterpret_cast<const int32_t*>(base + o_rowmap) : nullptr;
   r->rd.pagetab = any_segments ? reinterpret_cast<const int4*>(base + o_pagetab) : nullptr;
@@ -602,6 +621,16 @@ tdk_status round_create(const tdk_model* model, const tdk_session* sessions, int
   }
   if (e != hipSuccess) return hip_fail(e, "hipEventCreate");
   *out = holder.release();
+  return TDK_OK;
+}
+
+// The two halves of skip-or-correct: the page kernel writes every page that no diff lists from the re-rotated
+// master, the slot kernel copies the listed pages from the payload.
+tdk_status launch_restore(tdk_round* r, const LayerDev& l, const DiffDev& d, int planes, int64_t capacity_pages, hipStream_t s) {
+  // the number of listed pages is known on the device only: a fixed number of workgroups strides over them
+  const int slots = (int)std::min<int64_t>(std::min<int64_t>(capacity_pages, r->total_pages), 1 << 20);
+  TDK_LAUNCH(r, TDK_KERNEL_DECODE, s, launch_decode(r->rd, l, d, planes, s));
+  TDK_LAUNCH(r, TDK_KERNEL_SCATTER, s, launch_scatter(r->rd, l, d, planes, slots, s));
   return TDK_OK;
 }
 
@@ -643,6 +672,8 @@ tdk_status tdk_round_tune(tdk_round* r, int32_t agents_per_group, int32_t flags)
   });
 }
 
+int32_t tdk_round_agents_per_group(const tdk_round* r) { return r ? r->group : 0; }
+
 tdk_status tdk_rerotate_round(tdk_round* r, int32_t layer, const tdk_layer_io* io, void* hip_stream) {
   return guarded([&]() -> tdk_status {
     tdk_status st = check_step(r, layer, io);
@@ -671,8 +702,7 @@ static tdk_status encode_planes(tdk_round* r, int32_t layer, const tdk_layer_io*
     const LayerDev l = layer_dev(io);
     const DiffDev d = diff_dev(out);
     TDK_LAUNCH(r, TDK_KERNEL_FLAG, s, launch_flag(r->rd, l, eps, planes, s));
-    TDK_LAUNCH(r, TDK_KERNEL_COUNT, s, launch_count(r->rd, d, s));
-    TDK_LAUNCH(r, TDK_KERNEL_INDEX, s, launch_index(r->rd, d, s));
+    TDK_LAUNCH(r, TDK_KERNEL_COMPACT, s, launch_compact(r->rd, d, s));
     // the number of listed pages is known on the device only: a fixed grid strides over them
     const int grid = (int)std::min<int64_t>(std::min<int64_t>(out->capacity_pages, r->total_pages), 1 << 20);
     TDK_LAUNCH(r, TDK_KERNEL_GATHER, s, launch_gather(r->rd, l, d, planes, grid, s));
@@ -714,8 +744,7 @@ tdk_status tdk_diff_encode_static(tdk_round* r, int32_t layer, const tdk_layer_i
     const DiffDev d = diff_dev(out);
     const int planes = TDK_PLANE_K | TDK_PLANE_V;
     hipError_t e = launch_flag(rd, l, eps, planes, s);
-    if (e == hipSuccess) e = launch_count(rd, d, s);
-    if (e == hipSuccess) e = launch_index(rd, d, s);
+    if (e == hipSuccess) e = launch_compact(rd, d, s);
     const int grid = (int)std::min<int64_t>(std::min<int64_t>(out->capacity_pages, r->total_pages), 1 << 20);
     if (e == hipSuccess) e = launch_gather(rd, l, d, planes, grid, s);
     if (e != hipSuccess) return hip_fail(e, "kernel launch (tdk_diff_encode_static)");
@@ -733,10 +762,8 @@ static tdk_status decode_planes(tdk_round* r, int32_t layer, const tdk_layer_io*
     hipStream_t s = static_cast<hipStream_t>(hip_stream);
     const LayerDev l = layer_dev(io);
     const DiffDev d = diff_dev(in);
-    TDK_LAUNCH(r, TDK_KERNEL_DECODE, s, launch_decode(r->rd, l, d, planes, s));
-    const int grid = (int)std::min<int64_t>(std::min<int64_t>(in->capacity_pages, r->total_pages), 1 << 20);
-    TDK_LAUNCH(r, TDK_KERNEL_SCATTER, s, launch_scatter(r->rd, l, d, planes, grid, s));
-    return TDK_OK;
+    st = launch_restore(r, l, d, planes, in->capacity_pages, s);
+    return st;
   });
 }
 
@@ -991,9 +1018,8 @@ tdk_status tdk_restore_layers(tdk_round* r, int32_t first_layer, int32_t n_layer
       if (e != hipSuccess) return hip_fail(e, "hipStreamWaitEvent(loaded)");
       const LayerDev l = layer_dev(&lio[k]);
       const DiffDev d = diff_dev(&diffs[k]);
-      TDK_LAUNCH(r, TDK_KERNEL_DECODE, cs, launch_decode(r->rd, l, d, 3, cs));
-      const int grid = (int)std::min<int64_t>(std::min<int64_t>(diffs[k].capacity_pages, r->total_pages), 1 << 20);
-      TDK_LAUNCH(r, TDK_KERNEL_SCATTER, cs, launch_scatter(r->rd, l, d, 3, grid, cs));
+      tdk_status rs = launch_restore(r, l, d, 3, diffs[k].capacity_pages, cs);
+      if (rs != TDK_OK) return rs;
       e = hipEventRecord(r->ev_free[b], cs);
       if (e != hipSuccess) return hip_fail(e, "hipEventRecord(free)");
       r->free_recorded[b] = true;
@@ -1089,6 +1115,40 @@ tdk_status tdk_util_page_read(const void* src, const int32_t* page_ids, int32_t 
   hipError_t e = launch_page_read(static_cast<const u32x4*>(src), page_ids, n_pages, (int)(page_bytes / 16),
                                   static_cast<u32x4*>(sink16), static_cast<hipStream_t>(hip_stream));
   return e == hipSuccess ? TDK_OK : hip_fail(e, "page read kernel");
+}
+
+tdk_status tdk_util_page_fill_product(void* plane_k, void* plane_v, const int32_t* page_ids, int32_t n_pages, int32_t group,
+                                      int32_t num_kv_heads, int32_t page_tokens, uint32_t word, void* hip_stream) {
+  if (n_pages < 0 || group < 1 || num_kv_heads < 1 || num_kv_heads > 8 || (page_tokens != 16 && page_tokens != 32) ||
+      (n_pages && (!plane_k || !plane_v || !page_ids)) || (((uintptr_t)plane_k | (uintptr_t)plane_v) & 15))
+    return fail(TDK_ERR_INVALID_ARG, "page_fill_product: NULL, misaligned or bad shape");
+  hipError_t e = launch_page_fill_product(static_cast<u32x4*>(plane_k), static_cast<u32x4*>(plane_v), page_ids, n_pages, group,
+                                          num_kv_heads, page_tokens, word, static_cast<hipStream_t>(hip_stream));
+  return e == hipSuccess ? TDK_OK : hip_fail(e, "page fill kernel (product form)");
+}
+
+tdk_status tdk_util_page_read_product(const void* plane_k, const void* plane_v, const int32_t* page_ids, int32_t n_pages,
+                                      int32_t group, int32_t num_kv_heads, int32_t page_tokens, void* sink16, void* hip_stream) {
+  if (n_pages < 0 || group < 1 || num_kv_heads < 1 || num_kv_heads > 8 || (page_tokens != 16 && page_tokens != 32) ||
+      (n_pages && (!plane_k || !plane_v || !page_ids || !sink16)) ||
+      (((uintptr_t)plane_k | (uintptr_t)plane_v | (uintptr_t)sink16) & 15))
+    return fail(TDK_ERR_INVALID_ARG, "page_read_product: NULL, misaligned or bad shape");
+  hipError_t e = launch_page_read_product(static_cast<const u32x4*>(plane_k), static_cast<const u32x4*>(plane_v), page_ids, n_pages,
+                                          group, num_kv_heads, page_tokens, static_cast<u32x4*>(sink16),
+                                          static_cast<hipStream_t>(hip_stream));
+  return e == hipSuccess ? TDK_OK : hip_fail(e, "page read kernel (product form)");
+}
+
+size_t tdk_timeline_bytes(const tdk_round* r) {
+  return r ? 32 * ((size_t)r->rd.n_work + 1) : 0;
+}
+
+tdk_status tdk_timeline_set(tdk_round* r, void* stamps, size_t bytes) {
+  if (!r) return fail(TDK_ERR_INVALID_ARG, "round is NULL");
+  if (stamps && (bytes < tdk_timeline_bytes(r) || ((uintptr_t)stamps & 7)))
+    return fail(TDK_ERR_INVALID_ARG, "stamp buffer smaller than tdk_timeline_bytes() or misaligned");
+  r->rd.stamps = static_cast<unsigned long long*>(stamps);
+  return TDK_OK;
 }
 
 }  // extern "C"

@@ -44,7 +44,8 @@ struct AgentDev {
 };
 
 struct RoundDev {
-  const WorkItem*   work;
+  const WorkItem*   work;    // one item per workgroup of a static launch: item i runs on XCD i % 8
+  const WorkItem*   qwork;   // the same items grouped by that XCD: the queues of a queued launch
   const SessionDev* sess;
   const AgentDev*   agents;
   const int32_t*    order;   // agent ids grouped by session
@@ -60,6 +61,10 @@ struct RoundDev {
   const int32_t*    seg_off;   // [n_agents + 1]: agent i's segments (and tables) are seg_off[i] .. seg_off[i + 1]
   const int32_t*    seg_src;   // first master token of each segment (ascending within an agent, first is 0)
   uint8_t*          flags;   // [sum_i pages_i] scratch of encode
+  unsigned long long* stamps;  // measurement only: [2 x work items] start / end clock of every work item, or NULL
+  int32_t*          q_state; // [9] work queues: next item of each XCD's queue, workgroups that have left; all zero between launches
+  int32_t           q_begin[9];  // XCD x's queue is work[q_begin[x] .. q_begin[x + 1])
+  int32_t           n_cus;
   int32_t n_work, n_agents, n_sessions;
   int32_t heads;             // H
   int32_t page_tokens;       // T
@@ -124,8 +129,7 @@ struct AttendDev {
 // launchers (tdk_kernels.hip); each enqueues exactly one kernel
 hipError_t launch_rerotate(const RoundDev& rd, const LayerDev& io, hipStream_t st);
 hipError_t launch_flag(const RoundDev& rd, const LayerDev& io, float eps, int planes, hipStream_t st);
-hipError_t launch_count(const RoundDev& rd, const DiffDev& d, hipStream_t st);
-hipError_t launch_index(const RoundDev& rd, const DiffDev& d, hipStream_t st);
+hipError_t launch_compact(const RoundDev& rd, const DiffDev& d, hipStream_t st);
 hipError_t launch_gather(const RoundDev& rd, const LayerDev& io, const DiffDev& d, int planes, int grid, hipStream_t st);
 hipError_t launch_decode(const RoundDev& rd, const LayerDev& io, const DiffDev& d, int planes, hipStream_t st);
 hipError_t launch_scatter(const RoundDev& rd, const LayerDev& io, const DiffDev& d, int planes, int grid, hipStream_t st);
@@ -147,5 +151,9 @@ int attend_piece_tokens(int64_t lists, int n_cus);   // listed tokens per piece 
 
 hipError_t launch_page_fill(u32x4* dst, const int32_t* ids, int n_pages, int page_u4, uint32_t word, hipStream_t st);
 hipError_t launch_page_read(const u32x4* src, const int32_t* ids, int n_pages, int page_u4, u32x4* sink, hipStream_t st);
+hipError_t launch_page_fill_product(u32x4* pk, u32x4* pv, const int32_t* ids, int n_pages, int group, int heads, int page_tokens,
+                                    uint32_t word, hipStream_t st);
+hipError_t launch_page_read_product(const u32x4* pk, const u32x4* pv, const int32_t* ids, int n_pages, int group, int heads,
+                                    int page_tokens, u32x4* sink, hipStream_t st);
 
 }  // namespace tdk

@@ -13,6 +13,9 @@
 //     pair sit in the same lane and each load/store instruction covers whole 128-byte segments.
 #include "tdk_internal.h"
 
+#include <algorithm>
+#include <map>
+#include <mutex>
 #include <type_traits>
 
 namespace tdk {
@@ -257,39 +260,139 @@ __device__ __forceinline__ void sweep_masters(const RoundDev& rd, const LayerDev
   asm volatile("" : : "v"(acc));      // keeps the loads alive; the values are not used
 }
 
+// Optional timeline of a launch (measurement only): when the round carries a stamp buffer, the clock is
+// recorded when a work item is taken up and when the last wavefront has issued its last access for it.
+__device__ __forceinline__ int xcd_id() { return (int)(__builtin_amdgcn_s_getreg((3 << 11) | 20) & 7u); }   // XCC_ID, bits 3:0
+
+__device__ __forceinline__ void stamp_begin(const RoundDev& rd, int item) {
+  // (the low four bits carry the XCD the workgroup runs on)
+  if (rd.stamps && threadIdx.x == 0) rd.stamps[4 * (size_t)item] = (wall_clock64() & ~15ull) | (unsigned)xcd_id();
+}
+__device__ __forceinline__ void stamp_end(const RoundDev& rd, int item) {
+  if (rd.stamps && (threadIdx.x & 63) == 0) atomicMax(&rd.stamps[4 * (size_t)item + 1], (unsigned long long)wall_clock64());
+}
+// which = 2: the item's staging is in LDS; which = 3: the first wavefront has handled its rows of the first agent
+__device__ __forceinline__ void stamp_mid(const RoundDev& rd, int item, int which) {
+  if (rd.stamps && threadIdx.x == 0) rd.stamps[4 * (size_t)item + which] = wall_clock64();
+}
+
+// Which work items a workgroup processes.
+//   Static: workgroup b owns item b, dispatched by the hardware round-robin over the XCDs.
+//   Queued (TDK_TUNE_XCD_QUEUES for the kernels that write, TDK_TUNE_XCD_QUEUES_READ for those that read): the launch holds only as many workgroups as the device keeps resident, and each
+//   takes items until none is left: first from the queue of the XCD it runs on (the items that the static form
+//   would have run there, so re-reads of a master page still meet in that XCD's L2), then from the other XCDs'
+//   queues.  The XCDs do not write to memory at the same rate (measured: four of the eight finish a static
+//   rerotate launch 15 % earlier and then idle); with queues the fast ones take over what the slow ones have left.
+// Queue state in device memory: next[8], then the count of workgroups that have left the loop; the last one to
+// leave puts everything back to zero, so every launch finds the state as the round's creation left it.
+// Barrier for data exchanged through LDS only: waits for this wavefront's LDS traffic, not for its global stores
+// (__syncthreads() would also wait until every store issued so far has been acknowledged by memory, which stalls
+// a wavefront for microseconds at every item border while the chip is writing at full rate).
+__device__ __forceinline__ void lds_barrier() { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory"); }
+
+struct Items {
+  int home, k, ahead;
+  bool queued;
+  __device__ __forceinline__ Items(const RoundDev& rd, bool q) : home(xcd_id()), k(0), ahead(-1), queued(q) {}
+
+  // The first item of every workgroup is fixed by its number (workgroup b starts with entry b / 8 of queue b % 8, the
+  // XCD the hardware places it on): no atomic stands between the launch and the first access, and the queues hand
+  // out what lies behind those entries.
+  __device__ __forceinline__ int reserved(int x) const { return ((int)gridDim.x - x + 7) >> 3; }   // workgroups b with b % 8 == x
+
+  // thread 0 only: the next item for this workgroup, or -1 when every queue is empty
+  __device__ __forceinline__ int fetch(const RoundDev& rd) {
+    while (k < 8) {
+      const int x = (home + k) & 7;
+      const int n = rd.q_begin[x + 1] - rd.q_begin[x] - reserved(x);
+      const int i = n > 0 ? atomicAdd(&rd.q_state[x], 1) : 0;
+      if (i < n) return rd.q_begin[x] + reserved(x) + i;
+      ++k;             // that queue is empty for good
+    }
+    return -1;
+  }
+
+  // Asks for the item after the current one (thread 0; an atomic whose answer is a round trip to memory among
+  // the writes).  Called once per item, after the item's own loads have been issued: answers come back in issue
+  // order, so a load issued behind the atomic would wait for it, while the stores of the data phase do not.
+  __device__ __forceinline__ void prefetch(const RoundDev& rd) {
+    if (queued && threadIdx.x == 0) ahead = fetch(rd);
+  }
+
+  // Hands the prefetched item to the whole workgroup.
+  __device__ __forceinline__ int publish(int* s_item) {
+    lds_barrier();     // every wavefront is through with the previous item: its staging in LDS may be replaced
+    if (threadIdx.x == 0) *s_item = ahead;
+    lds_barrier();
+    return *s_item;
+  }
+
+  __device__ __forceinline__ int first(const RoundDev& rd, int* s_item) {
+    if (!queued) return (int)blockIdx.x < rd.n_work ? (int)blockIdx.x : -1;
+    const int x = (int)blockIdx.x & 7, i = (int)blockIdx.x >> 3;
+    return i < rd.q_begin[x + 1] - rd.q_begin[x] ? rd.q_begin[x] + i : -1;
+  }
+  __device__ __forceinline__ int next(const RoundDev& rd, int* s_item) {
+    if (!queued) return -1;
+    return publish(s_item);
+  }
+  __device__ __forceinline__ const WorkItem& at(const RoundDev& rd, int item) const { return queued ? rd.qwork[item] : rd.work[item]; }
+  __device__ __forceinline__ void leave(const RoundDev& rd) {
+    if (queued && threadIdx.x == 0) {
+      const int gone = atomicAdd(&rd.q_state[8], 1);
+      if (gone == (int)gridDim.x - 1) {       // nobody takes items any more
+#pragma unroll
+        for (int x = 0; x < 8; ++x) atomicExch(&rd.q_state[x], 0);
+        __threadfence();
+        atomicExch(&rd.q_state[8], 0);
+      }
+    }
+  }
+};
+
 template <int RPW, bool IL, bool NT, bool SEG>
 __global__ __launch_bounds__(kBlock) void tdk_rerotate_kernel(const RoundDev rd, const LayerDev io) {
   constexpr int T = RPW * kWaves;
   __shared__ std::conditional_t<SEG, GroupSharedSeg, GroupShared> sh;
-  const WorkItem w = rd.work[blockIdx.x];
+  __shared__ int s_item;
   const Lane L = lane_geometry(rd.heads);
   if (rd.nontemporal & 32) sweep_masters(rd, io, true, true);
-  stage_group<T>(rd, w, sh);
-  MasterRows<RPW> M;
-  load_master<RPW>(rd, io, w, L, M);
-  __syncthreads();
   const int wave = threadIdx.x >> 6;
   const int64_t row_u4 = (int64_t)rd.heads * 16;
   u32x4* pk = io.pool_k;
   u32x4* pv = io.pool_v;
-  for (int g = 0; g < w.ag_count; ++g) {
-    float c[8], s[8];
-    if (!SEG) load_tab<IL>(sh, g, 0, L.jb, c, s);
+  Items items(rd, (rd.nontemporal & 128) != 0);
+  for (int item = items.first(rd, &s_item); item >= 0; item = items.next(rd, &s_item)) {
+    stamp_begin(rd, item);
+    const WorkItem w = items.at(rd, item);
+    stage_group<T>(rd, w, sh);
+    MasterRows<RPW> M;
+    load_master<RPW>(rd, io, w, L, M);
+    lds_barrier();
+    items.prefetch(rd);
+    stamp_mid(rd, item, 2);
+    for (int g = 0; g < w.ag_count; ++g) {
+      if (g == 1) stamp_mid(rd, item, 3);
+      float c[8], s[8];
+      if (!SEG) load_tab<IL>(sh, g, 0, L.jb, c, s);
 #pragma unroll
-    for (int k = 0; k < RPW; ++k) {
-      if (!M.valid[k]) continue;
-      const int64_t base = dest_row<T>(sh, g, wave + kWaves * k) * row_u4;
-      if (L.kok) {
-        if (SEG) load_tab<IL>(sh, g, wave + kWaves * k, L.jb, c, s);
-        u32x4 olo, ohi;
-        rotate16<IL>(M.kl[k], M.kh[k], c, s, olo, ohi);
-        st16<NT>(pk + base + L.klo, olo);
-        st16<NT>(pk + base + L.khi, ohi);
+      for (int k = 0; k < RPW; ++k) {
+        if (!M.valid[k]) continue;
+        const int64_t base = dest_row<T>(sh, g, wave + kWaves * k) * row_u4;
+        if (L.kok) {
+          if (SEG) load_tab<IL>(sh, g, wave + kWaves * k, L.jb, c, s);
+          u32x4 olo, ohi;
+          rotate16<IL>(M.kl[k], M.kh[k], c, s, olo, ohi);
+          st16<NT>(pk + base + L.klo, olo);
+          st16<NT>(pk + base + L.khi, ohi);
+        }
+        if (L.v0ok) st16<NT>(pv + base + L.v0, M.v0[k]);
+        if (L.v1ok) st16<NT>(pv + base + L.v1, M.v1[k]);
       }
-      if (L.v0ok) st16<NT>(pv + base + L.v0, M.v0[k]);
-      if (L.v1ok) st16<NT>(pv + base + L.v1, M.v1[k]);
     }
+    stamp_end(rd, item);
   }
+  items.leave(rd);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -332,8 +435,16 @@ __global__ __launch_bounds__(kBlock) void tdk_flag_kernel(const RoundDev rd, con
   constexpr int T = RPW * kWaves;
   constexpr bool DOK = (PM & 1) != 0, DOV = (PM & 2) != 0;
   __shared__ std::conditional_t<SEG, GroupSharedSeg, GroupShared> sh;
-  const WorkItem w = rd.work[blockIdx.x];
+  __shared__ int s_item;
   const Lane L = lane_geometry(rd.heads);
+  const int wave = threadIdx.x >> 6;
+  const int64_t row_u4 = (int64_t)rd.heads * 16;
+  const u32x4* pk = io.pool_k;
+  const u32x4* pv = io.pool_v;
+  Items items(rd, (rd.nontemporal & 256) != 0);
+  for (int item = items.first(rd, &s_item); item >= 0; item = items.next(rd, &s_item)) {
+  stamp_begin(rd, item);
+  const WorkItem w = items.at(rd, item);
   stage_group<T>(rd, w, sh);
   MasterRows<RPW> M;
   load_master<RPW, DOV, DOK>(rd, io, w, L, M);
@@ -341,11 +452,8 @@ __global__ __launch_bounds__(kBlock) void tdk_flag_kernel(const RoundDev rd, con
 #pragma unroll
   for (int k = 0; k < RPW; ++k)
     special[k] = ((int)chunk_special(M.kl[k]) | (int)chunk_special(M.kh[k]) | (int)chunk_special(M.v0[k]) | (int)chunk_special(M.v1[k])) != 0;
-  __syncthreads();
-  const int wave = threadIdx.x >> 6;
-  const int64_t row_u4 = (int64_t)rd.heads * 16;
-  const u32x4* pk = io.pool_k;
-  const u32x4* pv = io.pool_v;
+  lds_barrier();
+  items.prefetch(rd);
   for (int g = 0; g < w.ag_count; ++g) {
     float c[8], s[8];
     if (DOK && !SEG) load_tab<IL>(sh, g, 0, L.jb, c, s);
@@ -382,53 +490,80 @@ __global__ __launch_bounds__(kBlock) void tdk_flag_kernel(const RoundDev rd, con
     }
     if (__any(differs) && (threadIdx.x & 63) == 0) atomicOr(&sh.aux[g], 1);
   }
-  __syncthreads();
+  lds_barrier();
   if (threadIdx.x < w.ag_count) {
     const AgentDev ad = rd.agents[sh.agent[threadIdx.x]];
     rd.flags[ad.flag_off + w.page] = (uint8_t)sh.aux[threadIdx.x];
   }
+  stamp_end(rd, item);
+  }
+  items.leave(rd);
 }
 
 // ---------------------------------------------------------------------------------------------
 // compaction: count, exclusive prefix, ascending index list                [Sec. 5]
-// One wavefront per agent: ballot over 64 page flags at a time, popcount, prefix by lane mask.
+// One launch.  A workgroup of 16 wavefronts takes 16 consecutive agents, one per wavefront: ballot over
+// 64 page flags at a time, popcount, prefix by lane mask.  The flag bytes of all agents lie one after
+// another in agent order, so the number of listed pages of all earlier agents (the exclusive prefix the
+// offsets need) is the number of non-zero bytes before the workgroup's first agent: every workgroup
+// counts that range itself with 16-byte loads (the flags of a round are a few hundred KB, L2-resident),
+// and no workgroup waits for another.
 // ---------------------------------------------------------------------------------------------
 
-__global__ __launch_bounds__(kBlock) void tdk_count_kernel(const RoundDev rd, int32_t* __restrict__ count) {
-  const int a = blockIdx.x * kWaves + (threadIdx.x >> 6);
-  const int lane = threadIdx.x & 63;
-  if (a >= rd.n_agents) return;
-  const AgentDev ad = rd.agents[a];
-  const int P = rd.sess[ad.session].pages;
-  int n = 0;
-  for (int p0 = 0; p0 < P; p0 += 64) {
-    const int p = p0 + lane;
-    const bool f = p < P && rd.flags[ad.flag_off + p] != 0;
-    n += __popcll(__ballot(f));
-  }
-  if (lane == 0) count[a] = n;
+constexpr int kCompactBlock = 1024;
+constexpr int kCompactWaves = kCompactBlock / 64;
+
+__device__ __forceinline__ int nonzero_bytes(uint32_t w) {
+  const uint32_t t = (((w & 0x7f7f7f7fu) + 0x7f7f7f7fu) | w) & 0x80808080u;
+  return __popc(t);
 }
 
-__global__ __launch_bounds__(kBlock) void tdk_index_kernel(const RoundDev rd, const DiffDev d) {
-  const int a = blockIdx.x * kWaves + (threadIdx.x >> 6);
-  const int lane = threadIdx.x & 63;
+__global__ __launch_bounds__(kCompactBlock) void tdk_compact_kernel(const RoundDev rd, const DiffDev d) {
+  __shared__ int64_t s_part[kCompactWaves];
+  __shared__ int32_t s_cnt[kCompactWaves];
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
   if (rd.n_agents == 0) {
     if (blockIdx.x == 0 && threadIdx.x == 0) { d.offset[0] = 0; d.overflow[0] = 0; }
     return;
   }
-  if (a >= rd.n_agents) return;
-  // exclusive prefix of the counts of all earlier agents
+  const int a0 = blockIdx.x * kCompactWaves;
+  const int a = a0 + wave;
+  // listed pages of all agents before a0: non-zero bytes of flags[0, flag_off(a0))
+  const int64_t n_before = rd.agents[a0].flag_off;
+  const uint8_t* fl = rd.flags;
   int64_t part = 0;
-  for (int b = lane; b < a; b += 64) part += d.count[b];
+  const int64_t n16 = n_before >> 4;
+  for (int64_t i = threadIdx.x; i < n16; i += kCompactBlock) {
+    const u32x4 w = reinterpret_cast<const u32x4*>(fl)[i];
+    part += nonzero_bytes(w[0]) + nonzero_bytes(w[1]) + nonzero_bytes(w[2]) + nonzero_bytes(w[3]);
+  }
+  for (int64_t i = (n16 << 4) + threadIdx.x; i < n_before; i += kCompactBlock) part += fl[i] != 0;
 #pragma unroll
   for (int sft = 32; sft > 0; sft >>= 1) part += __shfl_xor(part, sft);
-  const int64_t base = part;
-  const AgentDev ad = rd.agents[a];
-  const int P = rd.sess[ad.session].pages;
+  // this wavefront's agent: its count
+  int n = 0;
+  int P = 0, flag_off = 0;
+  if (a < rd.n_agents) {
+    const AgentDev ad = rd.agents[a];
+    P = rd.sess[ad.session].pages;
+    flag_off = ad.flag_off;
+    for (int p0 = 0; p0 < P; p0 += 64) {
+      const int p = p0 + lane;
+      const bool f = p < P && fl[flag_off + p] != 0;
+      n += __popcll(__ballot(f));
+    }
+  }
+  if (lane == 0) { s_part[wave] = part; s_cnt[wave] = n; }
+  __syncthreads();
+  int64_t base = 0;
+#pragma unroll
+  for (int q = 0; q < kCompactWaves; ++q) { base += s_part[q]; if (q < wave) base += s_cnt[q]; }
+  if (a >= rd.n_agents) return;
   if (lane == 0) {
+    d.count[a] = n;
     d.offset[a] = base;
     if (a == rd.n_agents - 1) {
-      const int64_t total = base + d.count[a];
+      const int64_t total = base + n;
       d.offset[a + 1] = total;
       d.overflow[0] = total > d.capacity ? 1 : 0;
     }
@@ -436,7 +571,7 @@ __global__ __launch_bounds__(kBlock) void tdk_index_kernel(const RoundDev rd, co
   int64_t run = base;
   for (int p0 = 0; p0 < P; p0 += 64) {
     const int p = p0 + lane;
-    const bool f = p < P && rd.flags[ad.flag_off + p] != 0;
+    const bool f = p < P && fl[flag_off + p] != 0;
     const uint64_t b = __ballot(f);
     const int rank = __popcll(b & ((1ull << lane) - 1ull));
     if (f && run + rank < d.capacity) d.idx[run + rank] = p;
@@ -530,68 +665,23 @@ __global__ __launch_bounds__(kBlock) void tdk_gather_kernel(const RoundDev rd, c
 // decode: diff pages from the payload, all others from the re-rotated master   [Sec. 4.4, Alg. 1]
 // ---------------------------------------------------------------------------------------------
 
-template <int RPW, bool IL, bool NT, int PM, bool SEG>
-__global__ __launch_bounds__(kBlock) void tdk_decode_kernel(const RoundDev rd, const LayerDev io, const DiffDev d) {
-  constexpr int T = RPW * kWaves;
-  __shared__ std::conditional_t<SEG, GroupSharedSeg, GroupShared> sh;
-  const WorkItem w = rd.work[blockIdx.x];
-  const Lane L = lane_geometry(rd.heads);
-  stage_group<T>(rd, w, sh);
-  MasterRows<RPW> M;
-  constexpr bool DOK = (PM & 1) != 0, DOV = (PM & 2) != 0;
-  if (rd.nontemporal & 64) sweep_masters(rd, io, DOK, DOV);
-  load_master<RPW, DOV, DOK>(rd, io, w, L, M);
-  if (threadIdx.x < w.ag_count) {
-    // skip-or-correct decision per block: is this page in the agent's index list?
-    const int a = rd.order[w.ag_begin + threadIdx.x];
-    int64_t lo = d.offset[a];
-    int64_t hi = lo + d.count[a];
-    if (lo < 0) lo = 0;
-    if (hi > d.capacity) hi = d.capacity;
-    int64_t slot = -1;
-    while (lo < hi) {
-      const int64_t mid = (lo + hi) >> 1;
-      const int v = d.idx[mid];
-      if (v == w.page) { slot = mid; break; }
-      if (v < w.page) lo = mid + 1; else hi = mid;
-    }
-    sh.aux[threadIdx.x] = (int32_t)slot;
-  }
-  __syncthreads();
-  const int wave = threadIdx.x >> 6;
-  const int64_t row_u4 = (int64_t)rd.heads * 16;
-  u32x4* pk = io.pool_k;
-  u32x4* pv = io.pool_v;
-  for (int g = 0; g < w.ag_count; ++g) {
-    if (sh.aux[g] >= 0) continue;   // listed in the diff: the scatter kernel writes this page
-    float c[8], s[8];
-    if (DOK && !SEG) load_tab<IL>(sh, g, 0, L.jb, c, s);
-#pragma unroll
-    for (int k = 0; k < RPW; ++k) {
-      if (!M.valid[k]) continue;
-      const int64_t base = dest_row<T>(sh, g, wave + kWaves * k) * row_u4;
-      if (DOK && L.kok) {
-        if (SEG) load_tab<IL>(sh, g, wave + kWaves * k, L.jb, c, s);
-        u32x4 olo, ohi;
-        rotate16<IL>(M.kl[k], M.kh[k], c, s, olo, ohi);
-        st16<NT>(pk + base + L.klo, olo);
-        st16<NT>(pk + base + L.khi, ohi);
-      }
-      if (DOV && L.v0ok) st16<NT>(pv + base + L.v0, M.v0[k]);
-      if (DOV && L.v1ok) st16<NT>(pv + base + L.v1, M.v1[k]);
-    }
-  }
-}
-
 // The "correct" half of skip-or-correct: pages listed in a diff are copied from the payload to the
 // agent's rows (the mirror image of the gather kernel).  Every pool row is written exactly once by
 // either this kernel or the page kernel above, so their order does not matter.
+struct ScatterShared {
+  SlotShared sh;
+  float s_tab[2][2 * kHalf];    // cos/sin of the payload re-rotation: up to two segments meet a page
+  uint32_t s_sel, s_moved;      // bit r of s_sel: row r uses table 1; bit t of s_moved: table t is not the identity
+};
+
+// Workgroup `first` of `stride` workgroups: walks the payload slots first, first + stride, ...
 template <bool IL>
-__global__ __launch_bounds__(kBlock) void tdk_scatter_kernel(const RoundDev rd, const LayerDev io, const DiffDev d,
-                                                             const int planes) {
-  __shared__ SlotShared sh;
-  __shared__ float s_tab[2][2 * kHalf];    // cos/sin of the payload re-rotation: up to two segments meet a page
-  __shared__ uint32_t s_sel, s_moved;      // bit r of s_sel: row r uses table 1; bit t of s_moved: table t is not the identity
+__device__ __forceinline__ void scatter_slots(const RoundDev& rd, const LayerDev& io, const DiffDev& d, const int planes,
+                                              ScatterShared& ss, const int64_t first, const int64_t stride) {
+  SlotShared& sh = ss.sh;
+  float (&s_tab)[2][2 * kHalf] = ss.s_tab;
+  uint32_t& s_sel = ss.s_sel;
+  uint32_t& s_moved = ss.s_moved;
   const int T = rd.page_tokens;
   const int A = rd.n_agents;
   if (A == 0) return;
@@ -600,7 +690,7 @@ __global__ __launch_bounds__(kBlock) void tdk_scatter_kernel(const RoundDev rd, 
   const int row_u4 = rd.heads * 16;
   const int page_u4 = T * row_u4;
   const Lane L = lane_geometry(rd.heads);
-  for (int64_t slot = blockIdx.x; slot < total; slot += gridDim.x) {
+  for (int64_t slot = first; slot < total; slot += stride) {
     if (threadIdx.x == 0) sh.owner = -1;
     __syncthreads();
     find_owner(d, A, slot, sh);
@@ -706,6 +796,74 @@ __global__ __launch_bounds__(kBlock) void tdk_scatter_kernel(const RoundDev rd, 
   }
 }
 
+template <bool IL>
+__global__ __launch_bounds__(kBlock) void tdk_scatter_kernel(const RoundDev rd, const LayerDev io, const DiffDev d,
+                                                             const int planes) {
+  __shared__ ScatterShared ss;
+  scatter_slots<IL>(rd, io, d, planes, ss, blockIdx.x, gridDim.x);
+}
+
+template <int RPW, bool IL, bool NT, int PM, bool SEG>
+__global__ __launch_bounds__(kBlock) void tdk_decode_kernel(const RoundDev rd, const LayerDev io, const DiffDev d) {
+  constexpr int T = RPW * kWaves;
+  __shared__ std::conditional_t<SEG, GroupSharedSeg, GroupShared> sh;
+  __shared__ int s_item;
+  constexpr bool DOK = (PM & 1) != 0, DOV = (PM & 2) != 0;
+  const Lane L = lane_geometry(rd.heads);
+  if (rd.nontemporal & 64) sweep_masters(rd, io, DOK, DOV);
+  const int wave = threadIdx.x >> 6;
+  const int64_t row_u4 = (int64_t)rd.heads * 16;
+  u32x4* pk = io.pool_k;
+  u32x4* pv = io.pool_v;
+  Items items(rd, (rd.nontemporal & 128) != 0);
+  for (int item = items.first(rd, &s_item); item >= 0; item = items.next(rd, &s_item)) {
+    stamp_begin(rd, item);
+    const WorkItem w = items.at(rd, item);
+    stage_group<T>(rd, w, sh);
+    MasterRows<RPW> M;
+    load_master<RPW, DOV, DOK>(rd, io, w, L, M);
+    if (threadIdx.x < w.ag_count) {
+      // skip-or-correct decision per block: is this page in the agent's index list?
+      const int a = rd.order[w.ag_begin + threadIdx.x];
+      int64_t lo = d.offset[a];
+      int64_t hi = lo + d.count[a];
+      if (lo < 0) lo = 0;
+      if (hi > d.capacity) hi = d.capacity;
+      int64_t slot = -1;
+      while (lo < hi) {
+        const int64_t mid = (lo + hi) >> 1;
+        const int v = d.idx[mid];
+        if (v == w.page) { slot = mid; break; }
+        if (v < w.page) lo = mid + 1; else hi = mid;
+      }
+      sh.aux[threadIdx.x] = (int32_t)slot;
+    }
+    lds_barrier();
+    items.prefetch(rd);
+    for (int g = 0; g < w.ag_count; ++g) {
+      if (sh.aux[g] >= 0) continue;   // listed in the diff: the scatter kernel writes this page
+      float c[8], s[8];
+      if (DOK && !SEG) load_tab<IL>(sh, g, 0, L.jb, c, s);
+#pragma unroll
+      for (int k = 0; k < RPW; ++k) {
+        if (!M.valid[k]) continue;
+        const int64_t base = dest_row<T>(sh, g, wave + kWaves * k) * row_u4;
+        if (DOK && L.kok) {
+          if (SEG) load_tab<IL>(sh, g, wave + kWaves * k, L.jb, c, s);
+          u32x4 olo, ohi;
+          rotate16<IL>(M.kl[k], M.kh[k], c, s, olo, ohi);
+          st16<NT>(pk + base + L.klo, olo);
+          st16<NT>(pk + base + L.khi, ohi);
+        }
+        if (DOV && L.v0ok) st16<NT>(pv + base + L.v0, M.v0[k]);
+        if (DOV && L.v1ok) st16<NT>(pv + base + L.v1, M.v1[k]);
+      }
+    }
+    stamp_end(rd, item);
+  }
+  items.leave(rd);
+}
+
 // ---------------------------------------------------------------------------------------------
 // plain copy / fill (bandwidth ceiling and traffic-counter reference)
 // ---------------------------------------------------------------------------------------------
@@ -749,15 +907,19 @@ template <int RPW, bool IL, bool SEG, bool NTL>
 __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(RPW == 4 ? 4 : 1))) void tdk_keydiff_kernel(const RoundDev rd, const LayerDev io, const PlanDev pl) {
   constexpr int T = RPW * kWaves;
   __shared__ std::conditional_t<SEG, GroupSharedSeg, GroupShared> sh;
-  const WorkItem w = rd.work[blockIdx.x];
+  __shared__ int s_item;
   const Lane L = lane_geometry(rd.heads);
-  stage_group<T>(rd, w, sh);
-  MasterRows<RPW> M;
-  load_master<RPW, false>(rd, io, w, L, M);
-  __syncthreads();
   const int wave = threadIdx.x >> 6;
   const int64_t row_u4 = (int64_t)rd.heads * 16;
   const u32x4* pk = io.pool_k;
+  Items items(rd, (rd.nontemporal & 256) != 0);
+  for (int item = items.first(rd, &s_item); item >= 0; item = items.next(rd, &s_item)) {
+  const WorkItem w = items.at(rd, item);
+  stage_group<T>(rd, w, sh);
+  MasterRows<RPW> M;
+  load_master<RPW, false>(rd, io, w, L, M);
+  lds_barrier();
+  items.prefetch(rd);
   for (int g = 0; g < w.ag_count; ++g) {
     float c[8], s[8];
     if (!SEG) load_tab<IL>(sh, g, 0, L.jb, c, s);
@@ -791,6 +953,8 @@ __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(RPW == 4
       if ((threadIdx.x & 63) == 63) pl.score[score_off + w.page * T + wave + kWaves * k] = acc;
     }
   }
+  }
+  items.leave(rd);
 }
 
 // rank of a set flag among the set flags of the workgroup (threads in order) and their total
@@ -813,6 +977,7 @@ __device__ __forceinline__ int block_rank(bool f, int* s_wave, int& total) {
 // Radix select on the fp32 bit patterns (non-negative floats order like unsigned integers; NaN sorts
 // above everything), then an ordered compaction.  Also the agent's total deviation.
 __global__ __launch_bounds__(kBlock) void tdk_select_kernel(const RoundDev rd, const PlanDev pl) {
+  static_assert(kBlock == 256, "one thread per radix bin: hist[threadIdx.x] and the suffix scan assume 256 threads");
   __shared__ uint32_t hist[256];
   __shared__ int s_wave[kWaves];
   __shared__ float s_sum[kWaves];
@@ -927,9 +1092,8 @@ __global__ __launch_bounds__(kBlock) void tdk_master_kernel(const RoundDev rd, c
   if (lane == 0) pl.master[s] = sd.n_agents ? best_i : -1;
 }
 
-// One workgroup per page: fills (or reads) page_u4 16-byte words of page ids[blockIdx.x].  With a
-// permuted id list this is the bare access pattern of the page kernels (whole pages at scattered
-// addresses) without any arithmetic: the bandwidth ceiling they are compared with.
+// Access-pattern probes: the page kernels' memory accesses with no arithmetic and no master.
+// Plain form: one workgroup per page, contiguous 4 KB per step, ordinary stores / dependent loads.
 __global__ __launch_bounds__(kBlock) void tdk_page_fill_kernel(u32x4* __restrict__ dst, const int32_t* __restrict__ ids,
                                                               int page_u4, uint32_t word) {
   const u32x4 v = {word, word, word, word};
@@ -946,9 +1110,93 @@ __global__ __launch_bounds__(kBlock) void tdk_page_read_kernel(const u32x4* __re
   if (acc[0] == 0x9e3779b9u && acc[1] == 0x7f4a7c15u) sink[0] = acc;
 }
 
+// Product form: exactly the traversal of the page kernels.  A workgroup takes `group` pages of the id list (as
+// a work item takes a group of agents); its four wavefronts own interleaved rows; a lane touches the two
+// halves of a head row in the K plane and two chunks 1 KB apart in the V plane; streaming stores / non-temporal
+// loads; all 16 accesses of a wavefront's rows of one page are issued before anything waits for them.
+template <int RPW>
+__global__ __launch_bounds__(kBlock) void tdk_page_fill_product_kernel(u32x4* __restrict__ pk, u32x4* __restrict__ pv,
+                                                                      const int32_t* __restrict__ ids, int n_pages, int group,
+                                                                      int heads, uint32_t word) {
+  constexpr int T = RPW * kWaves;
+  const Lane L = lane_geometry(heads);
+  const int wave = threadIdx.x >> 6;
+  const int64_t row_u4 = (int64_t)heads * 16;
+  const u32x4 v = {word, word ^ threadIdx.x, word, blockIdx.x};
+  for (int g = 0; g < group; ++g) {
+    const int64_t q = (int64_t)blockIdx.x * group + g;
+    if (q >= n_pages) break;
+    const int64_t page = ids[q];
+#pragma unroll
+    for (int k = 0; k < RPW; ++k) {
+      const int64_t base = (page * T + wave + kWaves * k) * row_u4;
+      if (L.kok) { st16<true>(pk + base + L.klo, v); st16<true>(pk + base + L.khi, v); }
+      if (L.v0ok) st16<true>(pv + base + L.v0, v);
+      if (L.v1ok) st16<true>(pv + base + L.v1, v);
+    }
+  }
+}
+
+template <int RPW>
+__global__ __launch_bounds__(kBlock) void tdk_page_read_product_kernel(const u32x4* __restrict__ pk, const u32x4* __restrict__ pv,
+                                                                      const int32_t* __restrict__ ids, int n_pages, int group,
+                                                                      int heads, u32x4* __restrict__ sink) {
+  constexpr int T = RPW * kWaves;
+  const Lane L = lane_geometry(heads);
+  const int wave = threadIdx.x >> 6;
+  const int64_t row_u4 = (int64_t)heads * 16;
+  u32x4 acc = {0, 0, 0, 0};
+  for (int g = 0; g < group; ++g) {
+    const int64_t q = (int64_t)blockIdx.x * group + g;
+    if (q >= n_pages) break;
+    const int64_t page = ids[q];
+    u32x4 a[RPW][4];
+    const u32x4 z = {0, 0, 0, 0};
+#pragma unroll
+    for (int k = 0; k < RPW; ++k) {
+      const int64_t base = (page * T + wave + kWaves * k) * row_u4;
+      a[k][0] = z; a[k][1] = z; a[k][2] = z; a[k][3] = z;
+      if (L.kok) { a[k][0] = ld16<true>(pk + base + L.klo); a[k][1] = ld16<true>(pk + base + L.khi); }
+      if (L.v0ok) a[k][2] = ld16<true>(pv + base + L.v0);
+      if (L.v1ok) a[k][3] = ld16<true>(pv + base + L.v1);
+    }
+#pragma unroll
+    for (int k = 0; k < RPW; ++k) acc ^= a[k][0] ^ a[k][1] ^ a[k][2] ^ a[k][3];
+  }
+  if (acc[0] == 0x9e3779b9u && acc[1] == 0x7f4a7c15u) sink[0] = acc;
+}
+
 // ---------------------------------------------------------------------------------------------
 // launchers
 // ---------------------------------------------------------------------------------------------
+
+// Launch of a page kernel.  Static distribution: one workgroup per work item.  Queued (the round's tuning flag
+// `queue_bit`, and only when every resident workgroup gets at least four items: below that the launch is over
+// before an imbalance between the XCDs can build up, and the hardware's own dispatch of fresh workgroups fills
+// freed wavefront slots sooner than a looping workgroup does): as many workgroups as the device keeps resident.
+template <class Kernel, class... Args>
+static void launch_pages(RoundDev rd, Kernel kernel, int queue_bit, hipStream_t st, Args... args) {
+  unsigned grid = (unsigned)rd.n_work;
+  if (rd.nontemporal & queue_bit) {
+    static std::mutex mu;
+    static std::map<const void*, int> per_cu;
+    int n = 0;
+    {
+      std::lock_guard<std::mutex> lock(mu);
+      auto it = per_cu.find(reinterpret_cast<const void*>(kernel));
+      if (it == per_cu.end()) {
+        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, kernel, kBlock, 0) != hipSuccess || n < 1) n = 2;
+        per_cu[reinterpret_cast<const void*>(kernel)] = n;
+      } else {
+        n = it->second;
+      }
+    }
+    const int64_t resident = (int64_t)n * std::max(rd.n_cus, 1);
+    if ((int64_t)rd.n_work >= 4 * resident || (rd.nontemporal & 1024)) grid = (unsigned)std::min<int64_t>(rd.n_work, resident);
+    else rd.nontemporal &= ~queue_bit;
+  }
+  hipLaunchKernelGGL(kernel, dim3(grid), dim3(kBlock), 0, st, rd, args...);
+}
 
 template <int V> using ic = std::integral_constant<int, V>;
 
@@ -960,11 +1208,10 @@ template <class F> static void with_planes(int planes, F f) {
 
 hipError_t launch_rerotate(const RoundDev& rd, const LayerDev& io, hipStream_t st) {
   if (rd.n_work == 0) return hipSuccess;
-  const dim3 grid(rd.n_work);
   with_rpw(rd.page_tokens, [&](auto rpw) { with_bool(rd.interleaved != 0, [&](auto il) { with_bool((rd.nontemporal & 1) != 0, [&](auto nt) {
     with_bool(rd.seg != 0, [&](auto sg) {
-      hipLaunchKernelGGL((tdk_rerotate_kernel<decltype(rpw)::value, decltype(il)::value, decltype(nt)::value, decltype(sg)::value>),
-                         grid, dim3(kBlock), 0, st, rd, io);
+      auto kernel = tdk_rerotate_kernel<decltype(rpw)::value, decltype(il)::value, decltype(nt)::value, decltype(sg)::value>;
+      launch_pages(rd, kernel, 128, st, io);
     });
   }); }); });
   return hipGetLastError();
@@ -972,26 +1219,18 @@ hipError_t launch_rerotate(const RoundDev& rd, const LayerDev& io, hipStream_t s
 
 hipError_t launch_flag(const RoundDev& rd, const LayerDev& io, float eps, int planes, hipStream_t st) {
   if (rd.n_work == 0) return hipSuccess;
-  const dim3 grid(rd.n_work);
   with_rpw(rd.page_tokens, [&](auto rpw) { with_bool(rd.interleaved != 0, [&](auto il) { with_planes(planes, [&](auto pm) {
     with_bool(rd.seg != 0, [&](auto sg) { with_bool((rd.nontemporal & 4) != 0, [&](auto ntl) {
-      hipLaunchKernelGGL((tdk_flag_kernel<decltype(rpw)::value, decltype(il)::value, decltype(pm)::value, decltype(sg)::value,
-                                          decltype(ntl)::value>), grid, dim3(kBlock), 0, st, rd, io, eps);
+      auto kernel = tdk_flag_kernel<decltype(rpw)::value, decltype(il)::value, decltype(pm)::value, decltype(sg)::value, decltype(ntl)::value>;
+      launch_pages(rd, kernel, 256, st, io, eps);
     }); });
   }); }); });
   return hipGetLastError();
 }
 
-hipError_t launch_count(const RoundDev& rd, const DiffDev& d, hipStream_t st) {
-  if (rd.n_agents == 0) return hipSuccess;
-  const dim3 grid((rd.n_agents + kWaves - 1) / kWaves);
-  hipLaunchKernelGGL(tdk_count_kernel, grid, dim3(kBlock), 0, st, rd, d.count);
-  return hipGetLastError();
-}
-
-hipError_t launch_index(const RoundDev& rd, const DiffDev& d, hipStream_t st) {
-  const dim3 grid(rd.n_agents ? (rd.n_agents + kWaves - 1) / kWaves : 1);
-  hipLaunchKernelGGL(tdk_index_kernel, grid, dim3(kBlock), 0, st, rd, d);
+hipError_t launch_compact(const RoundDev& rd, const DiffDev& d, hipStream_t st) {
+  const dim3 grid(rd.n_agents ? (rd.n_agents + kCompactWaves - 1) / kCompactWaves : 1);
+  hipLaunchKernelGGL(tdk_compact_kernel, grid, dim3(kCompactBlock), 0, st, rd, d);
   return hipGetLastError();
 }
 
@@ -1003,11 +1242,10 @@ hipError_t launch_gather(const RoundDev& rd, const LayerDev& io, const DiffDev& 
 
 hipError_t launch_decode(const RoundDev& rd, const LayerDev& io, const DiffDev& d, int planes, hipStream_t st) {
   if (rd.n_work == 0) return hipSuccess;
-  const dim3 grid(rd.n_work);
   with_rpw(rd.page_tokens, [&](auto rpw) { with_bool(rd.interleaved != 0, [&](auto il) { with_bool((rd.nontemporal & 2) != 0, [&](auto nt) {
     with_planes(planes, [&](auto pm) { with_bool(rd.seg != 0, [&](auto sg) {
-      hipLaunchKernelGGL((tdk_decode_kernel<decltype(rpw)::value, decltype(il)::value, decltype(nt)::value, decltype(pm)::value,
-                                            decltype(sg)::value>), grid, dim3(kBlock), 0, st, rd, io, d);
+      auto kernel = tdk_decode_kernel<decltype(rpw)::value, decltype(il)::value, decltype(nt)::value, decltype(pm)::value, decltype(sg)::value>;
+      launch_pages(rd, kernel, 128, st, io, d);
     }); });
   }); }); });
   return hipGetLastError();
@@ -1022,11 +1260,10 @@ hipError_t launch_scatter(const RoundDev& rd, const LayerDev& io, const DiffDev&
 
 hipError_t launch_keydiff(const RoundDev& rd, const LayerDev& io, const PlanDev& pl, hipStream_t st) {
   if (rd.n_work == 0) return hipSuccess;
-  const dim3 grid(rd.n_work);
   with_rpw(rd.page_tokens, [&](auto rpw) { with_bool(rd.interleaved != 0, [&](auto il) { with_bool(rd.seg != 0, [&](auto sg) {
     with_bool((rd.nontemporal & 4) != 0, [&](auto ntl) {
-      hipLaunchKernelGGL((tdk_keydiff_kernel<decltype(rpw)::value, decltype(il)::value, decltype(sg)::value, decltype(ntl)::value>),
-                         grid, dim3(kBlock), 0, st, rd, io, pl);
+      auto kernel = tdk_keydiff_kernel<decltype(rpw)::value, decltype(il)::value, decltype(sg)::value, decltype(ntl)::value>;
+      launch_pages(rd, kernel, 256, st, io, pl);
     });
   }); }); });
   return hipGetLastError();
@@ -1073,6 +1310,24 @@ hipError_t launch_page_fill(u32x4* dst, const int32_t* ids, int n_pages, int pag
 hipError_t launch_page_read(const u32x4* src, const int32_t* ids, int n_pages, int page_u4, u32x4* sink, hipStream_t st) {
   if (n_pages <= 0) return hipSuccess;
   hipLaunchKernelGGL(tdk_page_read_kernel, dim3(n_pages), dim3(kBlock), 0, st, src, ids, page_u4, sink);
+  return hipGetLastError();
+}
+
+hipError_t launch_page_fill_product(u32x4* pk, u32x4* pv, const int32_t* ids, int n_pages, int group, int heads, int page_tokens,
+                                    uint32_t word, hipStream_t st) {
+  if (n_pages <= 0) return hipSuccess;
+  const dim3 grid((n_pages + group - 1) / group);
+  if (page_tokens == 16) hipLaunchKernelGGL(tdk_page_fill_product_kernel<4>, grid, dim3(kBlock), 0, st, pk, pv, ids, n_pages, group, heads, word);
+  else hipLaunchKernelGGL(tdk_page_fill_product_kernel<8>, grid, dim3(kBlock), 0, st, pk, pv, ids, n_pages, group, heads, word);
+  return hipGetLastError();
+}
+
+hipError_t launch_page_read_product(const u32x4* pk, const u32x4* pv, const int32_t* ids, int n_pages, int group, int heads,
+                                    int page_tokens, u32x4* sink, hipStream_t st) {
+  if (n_pages <= 0) return hipSuccess;
+  const dim3 grid((n_pages + group - 1) / group);
+  if (page_tokens == 16) hipLaunchKernelGGL(tdk_page_read_product_kernel<4>, grid, dim3(kBlock), 0, st, pk, pv, ids, n_pages, group, heads, sink);
+  else hipLaunchKernelGGL(tdk_page_read_product_kernel<8>, grid, dim3(kBlock), 0, st, pk, pv, ids, n_pages, group, heads, sink);
   return hipGetLastError();
 }
 

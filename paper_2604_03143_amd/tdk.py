@@ -19,16 +19,18 @@ OK, ERR_INVALID_ARG, ERR_UNSUPPORTED, ERR_CAPACITY, ERR_HIP, ERR_NOMEM = range(6
 BF16 = 0
 ROPE_HALF, ROPE_INTERLEAVED = 0, 1
 PLANE_K, PLANE_V = 1, 2
-(KERNEL_REROTATE, KERNEL_FLAG, KERNEL_COUNT, KERNEL_INDEX, KERNEL_GATHER, KERNEL_DECODE, KERNEL_SCATTER,
+(KERNEL_REROTATE, KERNEL_FLAG, KERNEL_COMPACT, KERNEL_GATHER, KERNEL_DECODE, KERNEL_SCATTER,
  KERNEL_KEYDIFF, KERNEL_SELECT, KERNEL_MASTER, KERNEL_ATTEND_QROT, KERNEL_ATTEND_MASTER, KERNEL_ATTEND_DIFF,
- KERNEL_ATTEND_MERGE) = range(14)
-KERNEL_KINDS = 14
-TUNE_ALL, TUNE_DEFAULT = 127, 63
+ KERNEL_ATTEND_MERGE) = range(13)
+KERNEL_KINDS = 13
+TUNE_XCD_QUEUES, TUNE_XCD_QUEUES_READ, TUNE_TAPER = 128, 256, 512
+TUNE_QUEUES_ANY_SIZE = 1024
+TUNE_ALL, TUNE_DEFAULT = 2047, 191
 STATIC_SCRATCH_BYTES = 4 << 20
 
 EXPORTS = (
     "tdk_status_str", "tdk_last_error", "tdk_version", "tdk_kernel_name",
-    "tdk_round_create", "tdk_round_destroy", "tdk_scratch_bytes", "tdk_round_tune",
+    "tdk_round_create", "tdk_round_destroy", "tdk_scratch_bytes", "tdk_round_tune", "tdk_round_agents_per_group",
     "tdk_rerotate_round", "tdk_diff_encode", "tdk_diff_encode_static", "tdk_diff_decode", "tdk_restore_layers", "tdk_check_layer",
     "tdk_diff_encode_plane", "tdk_diff_decode_plane", "tdk_attend_workspace_bytes", "tdk_attend_shared",
     "tdk_prompt_plan_create", "tdk_prompt_plan_destroy", "tdk_prompt_plan_n_sessions", "tdk_prompt_plan_span",
@@ -36,6 +38,7 @@ EXPORTS = (
     "tdk_timing_enable", "tdk_timing_read", "tdk_timing_reset",
     "tdk_dense_bytes", "tdk_diff_bytes", "tdk_family_cost",
     "tdk_util_copy", "tdk_util_fill", "tdk_util_page_fill", "tdk_util_page_read",
+    "tdk_util_page_fill_product", "tdk_util_page_read_product", "tdk_timeline_bytes", "tdk_timeline_set",
 )
 
 
@@ -119,6 +122,7 @@ def load() -> C.CDLL:
     L.tdk_scratch_bytes.argtypes = [C.c_void_p]
     L.tdk_scratch_bytes.restype = C.c_size_t
     L.tdk_round_tune.argtypes = [C.c_void_p, C.c_int32, C.c_int32]
+    L.tdk_round_agents_per_group.argtypes = [C.c_void_p]
     L.tdk_rerotate_round.argtypes = [C.c_void_p, C.c_int32, C.POINTER(LayerIO), C.c_void_p]
     L.tdk_diff_encode.argtypes = [C.c_void_p, C.c_int32, C.POINTER(LayerIO), C.c_float, C.POINTER(Diff), C.c_void_p]
     L.tdk_diff_encode_static.argtypes = L.tdk_diff_encode.argtypes
@@ -151,6 +155,13 @@ def load() -> C.CDLL:
     L.tdk_util_fill.argtypes = [C.c_void_p, C.c_uint32, C.c_size_t, C.c_void_p]
     L.tdk_util_page_fill.argtypes = [C.c_void_p, C.c_void_p, C.c_int32, C.c_size_t, C.c_uint32, C.c_void_p]
     L.tdk_util_page_read.argtypes = [C.c_void_p, C.c_void_p, C.c_int32, C.c_size_t, C.c_void_p, C.c_void_p]
+    L.tdk_util_page_fill_product.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_int32,
+                                             C.c_uint32, C.c_void_p]
+    L.tdk_util_page_read_product.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_int32,
+                                             C.c_void_p, C.c_void_p]
+    L.tdk_timeline_bytes.argtypes = [C.c_void_p]
+    L.tdk_timeline_bytes.restype = C.c_size_t
+    L.tdk_timeline_set.argtypes = [C.c_void_p, C.c_void_p, C.c_size_t]
     _lib = L
     return L
 
@@ -260,6 +271,10 @@ def tdk_scratch_bytes(r: Round) -> int:
 
 def tdk_round_tune(r: Round, agents_per_group: int = 0, flags: int = TUNE_DEFAULT) -> None:
     _check(load().tdk_round_tune(r.handle, agents_per_group, flags), "tdk_round_tune")
+
+
+def tdk_round_agents_per_group(r: Round) -> int:
+    return int(load().tdk_round_agents_per_group(r.handle))
 
 
 def layer_io(master_k, master_v, pool_k, pool_v, pool_pages: int) -> LayerIO:
@@ -408,3 +423,25 @@ def tdk_util_page_fill(dst, page_ids, n_pages: int, page_bytes: int, word: int =
 def tdk_util_page_read(src, page_ids, n_pages: int, page_bytes: int, sink16, stream: int = 0) -> None:
     _check(load().tdk_util_page_read(_ptr(src), _ptr(page_ids), int(n_pages), int(page_bytes), _ptr(sink16),
                                      C.c_void_p(stream)), "tdk_util_page_read")
+
+
+def tdk_util_page_fill_product(plane_k, plane_v, page_ids, n_pages: int, group: int, num_kv_heads: int, page_tokens: int,
+                               word: int = 0, stream: int = 0) -> None:
+    _check(load().tdk_util_page_fill_product(_ptr(plane_k), _ptr(plane_v), _ptr(page_ids), int(n_pages), int(group),
+                                             int(num_kv_heads), int(page_tokens), int(word) & 0xFFFFFFFF,
+                                             C.c_void_p(stream)), "tdk_util_page_fill_product")
+
+
+def tdk_util_page_read_product(plane_k, plane_v, page_ids, n_pages: int, group: int, num_kv_heads: int, page_tokens: int,
+                               sink16, stream: int = 0) -> None:
+    _check(load().tdk_util_page_read_product(_ptr(plane_k), _ptr(plane_v), _ptr(page_ids), int(n_pages), int(group),
+                                             int(num_kv_heads), int(page_tokens), _ptr(sink16), C.c_void_p(stream)),
+           "tdk_util_page_read_product")
+
+
+def tdk_timeline_bytes(r: Round) -> int:
+    return int(load().tdk_timeline_bytes(r.handle))
+
+
+def tdk_timeline_set(r: Round, stamps, nbytes: int = 0) -> None:
+    _check(load().tdk_timeline_set(r.handle, _ptr(stamps), int(nbytes)), "tdk_timeline_set")

@@ -21,7 +21,7 @@ def lib():
 
 
 def test_exports_match_header(lib):
-    hdr = open(os.path.join(ROOT, "include", "tdk.h")).read()
+    hdr = open(os.path.join(ROOT, "include", "tdk.h")).read() + open(os.path.join(ROOT, "include", "tdk_bench.h")).read()
     hdr = re.sub(r"/\*.*?\*/", "", hdr, flags=re.S)
     declared = set(re.findall(r"\b(tdk_[a-z_0-9]+)\s*\(", hdr))
     assert declared == set(tdk.EXPORTS)

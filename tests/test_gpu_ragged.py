@@ -20,11 +20,12 @@ def ragged_round(T=16, H=8, frac=0.2, spans=SPANS, agents=AGENTS, stream=88):
     return wl.make_round(spec, spans=spans, agents=agents)
 
 
-@pytest.mark.parametrize("group", [0, 1, 3, 32])
-def test_pipeline_on_ragged_sessions(tdo, group):
+@pytest.mark.parametrize("group,flags", [(0, None), (1, 191 + 256 + 1024), (3, None), (32, 2047), (2, 63 + 512)])
+def test_pipeline_on_ragged_sessions(tdo, group, flags):
+    """(flags: the work items handed out statically, from the per-XCD queues whatever the round's size, tapered)"""
     from test_gpu_parity import run_pipeline
     rnd = ragged_round()
-    o, od = run_pipeline(tdo, rnd, group=group)
+    o, od = run_pipeline(tdo, rnd, group=group, flags=flags)
     for i, lst in enumerate(lists_of(od, rnd.n_agents)):
         assert np.array_equal(lst, rnd.perturbed[i]), i
 
