@@ -52,22 +52,25 @@ def parse():
     return ap.parse_args()
 
 
-def csrc_hash():
-    """sha256 over the sources the library is built from: ties a counter summary under profiles/ to the kernels it measured."""
+KERNEL_SOURCES = {"hbm_traffic": ("tdk_kernels.hip", "tdk_internal.h", "tdk_types.h"),
+                  "hbm_traffic_attend": ("tdk_attend.hip", "tdk_internal.h", "tdk_types.h")}
+
+
+def csrc_hash(prefix="hbm_traffic"):
+    """sha256 over the kernel sources a counter summary under profiles/ (named by its prefix) was taken from: ties
+    the traffic figures to the kernels that ran."""
     import hashlib
     h = hashlib.sha256()
-    files = []
-    for d in (os.path.join(ROOT, "paper_2604_03143_amd", "csrc"), os.path.join(ROOT, "include")):
-        files += [os.path.join(d, f) for f in sorted(os.listdir(d)) if f.endswith((".hip", ".cpp", ".h"))]
-    for f in files:
-        h.update(os.path.basename(f).encode() + b"\0" + open(f, "rb").read())
+    for f in KERNEL_SOURCES[prefix]:
+        h.update(f.encode() + b"\0" + open(os.path.join(ROOT, "paper_2604_03143_amd", "csrc", f), "rb").read())
     return h.hexdigest()[:16]
 
 
 def main():
     args = parse()
     if args.csrc_hash:
-        print(csrc_hash())
+        for k in KERNEL_SOURCES:
+            print(k, csrc_hash(k))
         return
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this path runs on one GPU only (every session, layer and KV head is independent; "
@@ -846,7 +849,7 @@ def read_traffic(workload, kernel, prefix="hbm_traffic"):
                 value = float(f[3])
     except OSError:
         return None
-    return value if tagged == csrc_hash() else None
+    return value if tagged == csrc_hash(prefix) else None
 
 
 def traffic_note(workload, prefix="hbm_traffic"):
@@ -858,8 +861,8 @@ def traffic_note(workload, prefix="hbm_traffic"):
         f = line.split()
         if len(f) >= 2 and f[0].lstrip("# ") == "csrc_sha256":
             tagged = f[-1]
-    if tagged != csrc_hash():
-        return (f"profiles/{prefix}_{workload}.txt was taken from kernel sources {tagged}, this run uses {csrc_hash()}: "
+    if tagged != csrc_hash(prefix):
+        return (f"profiles/{prefix}_{workload}.txt was taken from kernel sources {tagged}, this run uses {csrc_hash(prefix)}: "
                 "traffic withheld")
     return f"from profiles/{prefix}_{workload}.txt (rocprofv3 --pmc, same kernel sources {tagged})"
 

@@ -9,8 +9,8 @@ PKG = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(PKG)
 CSRC = os.path.join(PKG, "csrc")
 LIB = os.path.join(PKG, "libtdk.so")
-SOURCES = [os.path.join(CSRC, "tdk_kernels.hip"), os.path.join(CSRC, "tdk_attend.hip"), os.path.join(CSRC, "tdk_api.cpp"), os.path.join(CSRC, "tdk_prompt.cpp")]
-HEADERS = [os.path.join(CSRC, "tdk_internal.h"), os.path.join(ROOT, "include", "tdk.h"), os.path.join(ROOT, "include", "tdk_bench.h")]
+SOURCES = [os.path.join(CSRC, "tdk_kernels.hip"), os.path.join(CSRC, "tdk_attend.hip"), os.path.join(CSRC, "tdk_api.cpp"), os.path.join(CSRC, "tdk_plan.cpp"), os.path.join(CSRC, "tdk_prompt.cpp")]
+HEADERS = [os.path.join(CSRC, "tdk_internal.h"), os.path.join(CSRC, "tdk_types.h"), os.path.join(CSRC, "tdk_plan.h"), os.path.join(ROOT, "include", "tdk.h"), os.path.join(ROOT, "include", "tdk_bench.h")]
 
 
 def hipcc_command(out: str = LIB, extra=()):

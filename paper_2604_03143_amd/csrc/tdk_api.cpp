@@ -12,6 +12,7 @@
 
 #include "tdk_internal.h"
 #include "tdk_bench.h"
+#include "tdk_plan.h"
 
 using namespace tdk;
 
@@ -53,11 +54,7 @@ tdk_status guarded(F&& body) {
   }
 }
 
-struct HostSession {
-  int32_t span, pages;
-  int64_t master_pos0, master_row0;
-  std::vector<int32_t> agents;   // ids of its agents, in descriptor order
-};
+using HostSession = tdk::PlanSession;
 
 struct EventPair {
   hipEvent_t start, stop;
@@ -102,78 +99,12 @@ struct tdk_round {
 
 namespace {
 
-// Work list: one item per (master page, agent group).  Items that share a master page are given
-// workgroup ids that are congruent modulo 8, so that (with round-robin dispatch of workgroups to
-// the 8 XCDs) they run on the same XCD and the re-read of the master page hits that XCD's L2.
-// taper: the pages at the end of the list are cut into smaller groups (a third of the group size over
-// the last tenth of the work, single agents over the last fiftieth), so that the launch does not end
-// with a few long items running on an otherwise idle chip.
-void build_work(const tdk_round& r, int group, bool taper, std::vector<WorkItem>& work) {
-  work.clear();
-  std::vector<int32_t> order_begin(r.sessions.size(), 0);
-  int32_t cursor = 0;
-  int64_t total = 0, done = 0;
-  for (size_t s = 0; s < r.sessions.size(); ++s) {
-    order_begin[s] = cursor;
-    cursor += (int32_t)r.sessions[s].agents.size();
-    total += (int64_t)r.sessions[s].pages * (int64_t)r.sessions[s].agents.size();
-  }
-  for (size_t s = 0; s < r.sessions.size(); ++s) {
-    const int n = (int)r.sessions[s].agents.size();
-    if (!n) continue;
-    const int32_t pages = r.sessions[s].pages;
-    for (int32_t q0 = 0; q0 < pages; q0 += 8) {
-      const int32_t qn = std::min<int32_t>(8, pages - q0);
-      // every block of 8 pages has one group count
-      int g_eff = group;
-      if (taper && total > 0) {
-        if (done * 50 >= total * 49) g_eff = 1;
-        else if (done * 10 >= total * 9) g_eff = std::max(1, (group + 2) / 3);
-      }
-      const int G = (n + g_eff - 1) / g_eff;
-      for (int g = 0; g < G; ++g) {
-        // balanced split: the first (n % G) groups get one agent more
-        const int base = n / G, extra = n % G;
-        const int begin = g * base + std::min(g, extra);
-        const int cnt = base + (g < extra ? 1 : 0);
-        for (int32_t q = 0; q < qn; ++q)
-          work.push_back({(int32_t)s, q0 + q, order_begin[s] + begin, cnt});
-      }
-      done += (int64_t)qn * n;
-    }
-  }
-}
-
-int auto_group(const tdk_round& r) {
-  // Measured on MI355X: about 9 agents per work item is the best trade between re-reads of the
-  // master page (one per work item, served by the XCD's L2) and the number of work items; rounds
-  // too small to give ~900 items that way are split further.
-  const int64_t target = 900;
-  int best = 9;
-  for (int g = 9; g >= 1; --g) {
-    int64_t items = 0;
-    for (const auto& s : r.sessions) {
-      const int n = (int)s.agents.size();
-      if (n) items += (int64_t)s.pages * ((n + g - 1) / g);
-    }
-    best = g;
-    if (items >= target) break;
-  }
-  return best;
-}
-
 tdk_status upload_work(tdk_round* r, int group) {
   std::vector<WorkItem> work;
-  build_work(*r, group, (r->flags & TDK_TUNE_TAPER) != 0, work);
+  plan_work(r->sessions, group, (r->flags & TDK_TUNE_TAPER) != 0, work);
   if (work.size() > r->work_capacity) return fail(TDK_ERR_INVALID_ARG, "work list larger than reserved");
-  // one queue per XCD: the items the round-robin dispatch of a static launch runs there, in the same order
   std::vector<WorkItem> queued;
-  queued.reserve(work.size());
-  for (int x = 0; x < 8; ++x) {
-    r->rd.q_begin[x] = (int32_t)queued.size();
-    for (size_t i = x; i < work.size(); i += 8) queued.push_back(work[i]);
-  }
-  r->rd.q_begin[8] = (int32_t)queued.size();
+  plan_queues(work, queued, r->rd.q_begin);
   if (!work.empty()) {
     hipError_t e = hipMemcpy(const_cast<WorkItem*>(r->rd.work), work.data(), work.size() * sizeof(WorkItem),
                              hipMemcpyHostToDevice);
@@ -183,22 +114,6 @@ tdk_status upload_work(tdk_round* r, int group) {
   }
   r->rd.n_work = (int32_t)work.size();
   r->group = group;
-  return TDK_OK;
-}
-
-tdk_status check_model(const tdk_model* m) {
-  if (!m) return fail(TDK_ERR_INVALID_ARG, "model is NULL");
-  if (m->num_layers <= 0 || m->num_kv_heads <= 0 || m->head_dim <= 0 || m->page_tokens <= 0)
-    return fail(TDK_ERR_INVALID_ARG, "model: sizes must be positive");
-  if (!(m->rope_theta > 0.0) || !std::isfinite(m->rope_theta))
-    return fail(TDK_ERR_INVALID_ARG, "model: rope_theta must be positive and finite");
-  if (m->rope_style != TDK_ROPE_HALF && m->rope_style != TDK_ROPE_INTERLEAVED)
-    return fail(TDK_ERR_INVALID_ARG, "model: unknown rope_style");
-  if (m->dtype != TDK_BF16) return fail(TDK_ERR_UNSUPPORTED, "model: only bf16 caches are supported");
-  if (m->head_dim != kHeadDim) return fail(TDK_ERR_UNSUPPORTED, "model: only head_dim 128 is supported");
-  if (m->num_kv_heads > 8) return fail(TDK_ERR_UNSUPPORTED, "model: at most 8 KV heads per device are supported");
-  if (m->page_tokens != 16 && m->page_tokens != 32)
-    return fail(TDK_ERR_UNSUPPORTED, "model: page_tokens must be 16 or 32");
   return TDK_OK;
 }
 
@@ -345,198 +260,45 @@ tdk_status round_create(const tdk_model* model, const tdk_session* sessions, int
                         const tdk_agent* agents, int32_t n_agents, tdk_round** out) {
   if (!out) return fail(TDK_ERR_INVALID_ARG, "out is NULL");
   *out = nullptr;
-  tdk_status st = check_model(model);
-  if (st != TDK_OK) return st;
-  if (n_sessions < 0 || n_agents < 0) return fail(TDK_ERR_INVALID_ARG, "negative session or agent count");
-  if ((n_sessions && !sessions) || (n_agents && !agents)) return fail(TDK_ERR_INVALID_ARG, "sessions / agents is NULL");
-
-  const int T = model->page_tokens;
+  tdk_status st = TDK_OK;
   std::unique_ptr<tdk_round, RoundDeleter> holder(new tdk_round());   // released on every early return
   tdk_round* r = holder.get();
+
+  // ---- host-side validation and planning (tdk_plan.cpp; no HIP call before this block is through) ----
+  RoundPlan p;
+  {
+    std::string err;
+    const tdk_status ps = plan_round(model, sessions, n_sessions, agents, n_agents, p, err);
+    if (ps != TDK_OK) return fail(ps, err);
+  }
+  r->sessions = p.sessions;
+  r->max_phys_page = p.max_phys_page;
+  r->total_pages = p.total_pages;
+  r->total_master_pages = p.total_master_pages;
+  r->total_master_rows = p.total_master_rows;
+  r->total_tokens = p.total_tokens;
+  r->max_segments = p.max_segments;
+  r->seg_moved = p.seg_moved;
+  r->diff_moved = p.diff_moved;
+  r->work_capacity = p.work_capacity;
   r->model = *model;
   r->n_agents = n_agents;
-
-  // ---- host-side validation and planning (no HIP call before this block is through) ----
-  std::vector<SessionDev> sess_dev(n_sessions);
-  std::vector<AgentDev> agent_dev(n_agents);
-  std::vector<int32_t> bt;
-  std::vector<float> tab((size_t)n_agents * 2 * kHalf);
-  std::vector<float> tab_diff((size_t)n_agents * 2 * kHalf);
-  r->sessions.resize(n_sessions);
-  int64_t row0 = 0;
-  for (int32_t s = 0; s < n_sessions; ++s) {
-    if (sessions[s].span_tokens < 0) { return fail(TDK_ERR_INVALID_ARG, "session: negative span_tokens"); }
-    if (sessions[s].master_pos0 < 0) { return fail(TDK_ERR_INVALID_ARG, "session: negative master_pos0"); }
-    HostSession& hs = r->sessions[s];
-    hs.span = sessions[s].span_tokens;
-    hs.pages = (hs.span + T - 1) / T;
-    hs.master_pos0 = sessions[s].master_pos0;
-    hs.master_row0 = row0;
-    row0 += hs.span;
-    sess_dev[s] = {hs.master_row0, hs.span, hs.pages, 0, 0};
-    r->total_master_pages += hs.pages;
-  }
-  r->total_master_rows = row0;
-  int64_t flag_off = 0, score_off = 0;
-  bool any_segments = false;
-  for (int32_t i = 0; i < n_agents; ++i) any_segments |= agents[i].n_segments > 0;
-  std::vector<int32_t> rowmap;
-  std::vector<int4> pagetab;
-  std::vector<float> segtab, segtab_diff;
-  std::vector<int32_t> seg_off, seg_src;   // per agent the range of its segments (= its tables in segtab), their first master tokens
-  bool seg_moved = false;                  // some segment's stored diff sits at another position
-  for (int32_t i = 0; i < n_agents; ++i) {
-    const tdk_agent& a = agents[i];
-    if (a.session < 0 || a.session >= n_sessions) { return fail(TDK_ERR_INVALID_ARG, "agent: session index out of range"); }
-    if (a.dst_pos0 < 0) { return fail(TDK_ERR_INVALID_ARG, "agent: negative dst_pos0"); }
-    if (a.dst_pos0 >= (int64_t)1 << 31) { return fail(TDK_ERR_INVALID_ARG, "agent: positions beyond 2^31"); }
-    HostSession& hs = r->sessions[a.session];
-    const int64_t S = hs.span;
-    if (a.n_segments < 0 || (a.n_segments > 0 && !a.segments)) { return fail(TDK_ERR_INVALID_ARG, "agent: bad segment list"); }
-    // the logical pages the shared span touches: one range for the identity layout, the hull of the
-    // segments otherwise
-    int64_t pos_lo = a.dst_pos0, pos_hi = a.dst_pos0 + S;   // [lo, hi)
-    if (a.n_segments > 0) {
-      int64_t next = 0;
-      pos_lo = INT64_MAX; pos_hi = 0;
-      for (int32_t q = 0; q < a.n_segments; ++q) {
-        const tdk_segment& sg = a.segments[q];
-        if (sg.diff_pos < 0 || sg.diff_pos >= (int64_t)1 << 31) { return fail(TDK_ERR_INVALID_ARG, "agent: segment diff_pos out of range"); }
-        if (sg.src_tok != next || sg.len <= 0 || sg.dst_pos < 0) { return fail(TDK_ERR_INVALID_ARG, "agent: segments must be sorted, contiguous in the master and non-empty"); }
-        for (int32_t o = 0; o < q; ++o) {
-          const tdk_segment& og = a.segments[o];
-          if (sg.dst_pos < og.dst_pos + og.len && og.dst_pos < sg.dst_pos + sg.len) { return fail(TDK_ERR_INVALID_ARG, "agent: segment destinations overlap"); }
-        }
-        next += sg.len;
-        pos_lo = std::min<int64_t>(pos_lo, sg.dst_pos);
-        pos_hi = std::max<int64_t>(pos_hi, sg.dst_pos + sg.len);
-      }
-      if (next != S) { return fail(TDK_ERR_INVALID_ARG, "agent: segments do not cover the span"); }
-    }
-    if (pos_hi + T >= (int64_t)1 << 31) { return fail(TDK_ERR_INVALID_ARG, "agent: positions beyond 2^31"); }
-    const int64_t lp_first = S > 0 ? pos_lo / T : a.dst_pos0 / T;
-    const int64_t lp_last = S > 0 ? (pos_hi - 1) / T : lp_first - 1;
-    if (S > 0) {
-      if (!a.block_table) { return fail(TDK_ERR_INVALID_ARG, "agent: block_table is NULL"); }
-      if ((int64_t)a.block_table_len <= lp_last) { return fail(TDK_ERR_INVALID_ARG, "agent: block_table too short for its span"); }
-    }
-    AgentDev& ad = agent_dev[i];
-    ad.pos0 = (int32_t)a.dst_pos0;
-    ad.bt_off = (int32_t)bt.size();
-    ad.lp_first = (int32_t)lp_first;
-    ad.bt_len = (int32_t)(lp_last - lp_first + 1);
-    ad.session = a.session;
-    ad.flag_off = (int32_t)flag_off;
-    ad.score_off = (int32_t)score_off;
-    if (a.n_segments == 0 && a.diff_pos0 < 0) { return fail(TDK_ERR_INVALID_ARG, "agent: negative diff_pos0"); }
-    ad.diff_rot = a.n_segments ? 0 : a.diff_pos0 != a.dst_pos0;
-    for (int32_t q = 0; q < a.n_segments; ++q) ad.diff_rot |= a.segments[q].diff_pos != a.segments[q].dst_pos;
-    if (ad.diff_rot) r->diff_moved = true;
-    score_off += S;
-    {
-      // only pages that hold shared tokens count (the hull of a permuted layout may contain others)
-      auto touch = [&](int64_t lo, int64_t hi) -> bool {
-        for (int64_t lp = lo / T; lp <= (hi - 1) / T; ++lp) {
-          if (a.block_table[lp] < 0) return false;
-          r->max_phys_page = std::max<int64_t>(r->max_phys_page, a.block_table[lp]);
-        }
-        return true;
-      };
-      bool ok = true;
-      if (S > 0 && a.n_segments == 0) ok = touch(pos_lo, pos_hi);
-      for (int32_t q = 0; q < a.n_segments && ok; ++q) ok = touch(a.segments[q].dst_pos, a.segments[q].dst_pos + a.segments[q].len);
-      if (!ok) { return fail(TDK_ERR_INVALID_ARG, "agent: negative page number in block_table"); }
-    }
-    for (int64_t lp = lp_first; lp <= lp_last; ++lp) bt.push_back(a.block_table[lp]);
-    // layout tables (only if some agent of the round has segments)
-    if (any_segments) {
-      tdk_segment whole{0, (int32_t)S, a.dst_pos0, a.diff_pos0};
-      const tdk_segment* segs = a.n_segments ? a.segments : &whole;
-      const int32_t nseg = a.n_segments ? a.n_segments : (S > 0 ? 1 : 0);
-      const int32_t tab0 = (int32_t)(segtab.size() / (2 * kHalf));
-      seg_off.push_back(tab0);
-      for (int32_t q = 0; q < nseg; ++q) {
-        seg_src.push_back(segs[q].src_tok);
-        seg_moved |= segs[q].dst_pos != segs[q].diff_pos;
-        const double delta = (double)(segs[q].dst_pos - (hs.master_pos0 + segs[q].src_tok));
-        for (int j = 0; j < kHalf; ++j) {
-          const double inv_freq = std::pow(model->rope_theta, -(double)(2 * j) / (double)model->head_dim);
-          segtab.push_back((float)std::cos(delta * inv_freq));
-        }
-        for (int j = 0; j < kHalf; ++j) {
-          const double inv_freq = std::pow(model->rope_theta, -(double)(2 * j) / (double)model->head_dim);
-          segtab.push_back((float)std::sin(delta * inv_freq));
-        }
-        const double moved = (double)(segs[q].dst_pos - segs[q].diff_pos);
-        for (int j = 0; j < kHalf; ++j) {
-          const double inv_freq = std::pow(model->rope_theta, -(double)(2 * j) / (double)model->head_dim);
-          segtab_diff.push_back((float)std::cos(moved * inv_freq));
-        }
-        for (int j = 0; j < kHalf; ++j) {
-          const double inv_freq = std::pow(model->rope_theta, -(double)(2 * j) / (double)model->head_dim);
-          segtab_diff.push_back((float)std::sin(moved * inv_freq));
-        }
-        for (int32_t m = segs[q].src_tok; m < segs[q].src_tok + segs[q].len; ++m) {
-          const int64_t pos = segs[q].dst_pos + (m - segs[q].src_tok);
-          rowmap.push_back((int32_t)((int64_t)a.block_table[pos / T] * T + pos % T));
-        }
-      }
-      int32_t q = 0;
-      for (int32_t p = 0; p < hs.pages; ++p) {
-        const int32_t m_lo = p * T, m_hi = (int32_t)std::min<int64_t>(S, (int64_t)(p + 1) * T);
-        while (segs[q].src_tok + segs[q].len <= m_lo) ++q;
-        int4 e = make_int4(tab0 + q, tab0 + q, 0, 0);
-        int32_t q2 = q;
-        for (int32_t m = m_lo; m < m_hi; ++m) {
-          while (segs[q2].src_tok + segs[q2].len <= m) ++q2;
-          if (q2 > q + 1) { return fail(TDK_ERR_UNSUPPORTED, "agent: a master page meets more than two segments"); }
-          if (q2 == q + 1) { e.y = tab0 + q2; e.z |= 1 << (m - m_lo); }
-        }
-        // which of the two runs sat elsewhere when the stored diff was encoded
-        e.w = (segs[e.x - tab0].dst_pos != segs[e.x - tab0].diff_pos ? 1 : 0) |
-              (segs[e.y - tab0].dst_pos != segs[e.y - tab0].diff_pos ? 2 : 0);
-        pagetab.push_back(e);
-      }
-    }
-    flag_off += hs.pages;
-    if (flag_off >= (int64_t)1 << 31 || score_off >= (int64_t)1 << 31 || bt.size() >= (size_t)1 << 31) { return fail(TDK_ERR_UNSUPPORTED, "round too large"); }
-    hs.agents.push_back(i);
-
-    // rotation tables of this agent: master frame -> its offset, and the frame its stored diff values
-    // were encoded in -> its offset.  Angles in double, one rounding to fp32.
-    const double deltas[2] = {(double)(a.dst_pos0 - hs.master_pos0), (double)(a.dst_pos0 - a.diff_pos0)};
-    float* tabs[2] = {tab.data() + (size_t)i * 2 * kHalf, tab_diff.data() + (size_t)i * 2 * kHalf};
-    for (int which = 0; which < 2; ++which) {
-      float* c = tabs[which];
-      float* sn = c + kHalf;
-      for (int j = 0; j < kHalf; ++j) {
-        const double inv_freq = std::pow(model->rope_theta, -(double)(2 * j) / (double)model->head_dim);
-        const double phi = deltas[which] * inv_freq;
-        c[j] = (float)std::cos(phi);
-        sn[j] = (float)std::sin(phi);
-      }
-    }
-  }
-  r->total_pages = flag_off;
-  if (any_segments) seg_off.push_back((int32_t)seg_src.size());
-  r->seg_moved = seg_moved;
-  for (int32_t i = 0; any_segments && i < n_agents; ++i) r->max_segments = std::max(r->max_segments, seg_off[i + 1] - seg_off[i]);
-  if (any_segments && (r->max_phys_page + 1) * T >= (int64_t)1 << 31)
-    return fail(TDK_ERR_UNSUPPORTED, "segmented layouts address pool rows with 32 bits: page numbers too large");
-  std::vector<int32_t> order;
-  order.reserve(n_agents);
-  for (size_t q = 0; q < r->sessions.size(); ++q) {
-    const auto& hs = r->sessions[q];
-    sess_dev[q].order_begin = (int32_t)order.size();
-    sess_dev[q].n_agents = (int32_t)hs.agents.size();
-    order.insert(order.end(), hs.agents.begin(), hs.agents.end());
-  }
-  r->total_tokens = score_off;
-
-  // worst case for the work list: every agent its own group
-  size_t work_cap = 0;
-  for (const auto& hs : r->sessions) work_cap += (size_t)hs.pages * hs.agents.size();
-  r->work_capacity = work_cap;
+  const int T = model->page_tokens;
+  const bool any_segments = p.any_segments;
+  const size_t work_cap = p.work_capacity;
+  const int64_t flag_off = p.total_pages;
+  const auto& sess_dev = p.sess;
+  const auto& agent_dev = p.agents;
+  const auto& order = p.order;
+  const auto& bt = p.bt;
+  const auto& tab = p.tab;
+  const auto& tab_diff = p.tab_diff;
+  const auto& rowmap = p.rowmap;
+  const auto& pagetab = p.pagetab;
+  const auto& segtab = p.segtab;
+  const auto& segtab_diff = p.segtab_diff;
+  const auto& seg_off = p.seg_off;
+  const auto& seg_src = p.seg_src;
 
   // ---- device memory: one allocation ----
   size_t off = 0;
@@ -550,7 +312,7 @@ tdk_status round_create(const tdk_model* model, const tdk_session* sessions, int
   const size_t o_tab = place(tab.size() * sizeof(float));
   const size_t o_tab_diff = place(tab_diff.size() * sizeof(float));
   const size_t o_rowmap = place(any_segments ? rowmap.size() * sizeof(int32_t) : 0);
-  const size_t o_pagetab = place(any_segments ? pagetab.size() * sizeof(int4) : 0);
+  const size_t o_pagetab = place(any_segments ? pagetab.size() * sizeof(PageTab) : 0);
   const size_t o_segtab = place(any_segments ? segtab.size() * sizeof(float) : 0);
   const size_t o_segtab_diff = place(any_segments ? segtab_diff.size() * sizeof(float) : 0);
   const size_t o_seg_off = place(any_segments ? seg_off.size() * sizeof(int32_t) : 0);
@@ -578,7 +340,7 @@ tdk_status round_create(const tdk_model* model, const tdk_session* sessions, int
   if (e == hipSuccess) e = up(o_tab, tab.data(), tab.size() * sizeof(float));
   if (e == hipSuccess) e = up(o_tab_diff, tab_diff.data(), tab_diff.size() * sizeof(float));
   if (e == hipSuccess && any_segments) e = up(o_rowmap, rowmap.data(), rowmap.size() * sizeof(int32_t));
-  if (e == hipSuccess && any_segments) e = up(o_pagetab, pagetab.data(), pagetab.size() * sizeof(int4));
+  if (e == hipSuccess && any_segments) e = up(o_pagetab, pagetab.data(), pagetab.size() * sizeof(PageTab));
   if (e == hipSuccess && any_segments) e = up(o_segtab, segtab.data(), segtab.size() * sizeof(float));
   if (e == hipSuccess && any_segments) e = up(o_segtab_diff, segtab_diff.data(), segtab_diff.size() * sizeof(float));
   if (e == hipSuccess && any_segments) e = up(o_seg_off, seg_off.data(), seg_off.size() * sizeof(int32_t));
@@ -600,7 +362,7 @@ tdk_status round_create(const tdk_model* model, const tdk_session* sessions, int
   r->rd.n_cus = r->n_cus;
   r->rd.seg = any_segments ? 1 : 0;
   r->rd.rowmap = any_segments ? reinterpret_cast<const int32_t*>(base + o_rowmap) : nullptr;
-  r->rd.pagetab = any_segments ? reinterpret_cast<const int4*>(base + o_pagetab) : nullptr;
+  r->rd.pagetab = any_segments ? reinterpret_cast<const PageTab*>(base + o_pagetab) : nullptr;
   r->rd.segtab = any_segments ? reinterpret_cast<const float*>(base + o_segtab) : nullptr;
   r->rd.segtab_diff = any_segments ? reinterpret_cast<const float*>(base + o_segtab_diff) : nullptr;
   r->rd.seg_off = any_segments ? reinterpret_cast<const int32_t*>(base + o_seg_off) : nullptr;
@@ -613,7 +375,7 @@ tdk_status round_create(const tdk_model* model, const tdk_session* sessions, int
   r->rd.interleaved = model->rope_style == TDK_ROPE_INTERLEAVED;
   r->rd.nontemporal = r->flags & TDK_TUNE_ALL;
 
-  st = upload_work(r, auto_group(*r));
+  st = upload_work(r, plan_auto_group(r->sessions));
   if (st != TDK_OK) return st;
   for (int b = 0; b < 2 && e == hipSuccess; ++b) {
     e = hipEventCreateWithFlags(&r->ev_loaded[b], hipEventDisableTiming);
@@ -668,7 +430,7 @@ tdk_status tdk_round_tune(tdk_round* r, int32_t agents_per_group, int32_t flags)
     if (e != hipSuccess) return hip_fail(e, "hipDeviceSynchronize");
     r->flags = flags;
     r->rd.nontemporal = flags & TDK_TUNE_ALL;
-    return upload_work(r, agents_per_group ? agents_per_group : auto_group(*r));
+    return upload_work(r, agents_per_group ? agents_per_group : plan_auto_group(r->sessions));
   });
 }
 

@@ -5,44 +5,11 @@
 #include <stdint.h>
 
 #include "tdk.h"
+#include "tdk_types.h"
 
 namespace tdk {
 
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));   // one 16-byte access
-
-constexpr int kMaxGroup = 32;     // agents that share one read of a master page
-constexpr int kBlock = 256;       // threads per workgroup (4 wavefronts of 64)
-constexpr int kWaves = kBlock / 64;
-constexpr int kHeadDim = 128;
-constexpr int kHalf = kHeadDim / 2;
-
-// One unit of work of the page kernels: a master page and a group of agents of its session.
-struct WorkItem {
-  int32_t session;
-  int32_t page;        // master page number
-  int32_t ag_begin;    // range in RoundDev::order
-  int32_t ag_count;    // 1..kMaxGroup
-};
-
-struct SessionDev {
-  int64_t master_row0;  // first row of this session in master_k / master_v
-  int32_t span;         // S
-  int32_t pages;        // ceil(S / T)
-  int32_t order_begin;  // its agents are RoundDev::order[order_begin .. order_begin + n_agents)
-  int32_t n_agents;
-};
-
-struct AgentDev {
-  int32_t pos0;         // dst_pos0 (validated < 2^31)
-  int32_t bt_off;       // start of this agent's block-table slice in RoundDev::bt
-  int32_t lp_first;     // logical page number of slice entry 0 (= pos0 / T)
-  int32_t bt_len;       // entries in the slice
-  int32_t session;
-  int32_t flag_off;     // start of this agent's per-page flags in the flag scratch
-  int32_t score_off;    // start of this agent's per-token scores (sum of the spans of earlier agents)
-  int32_t diff_rot;     // 1: payload K rows of this agent were stored at another position (re-rotate on restore)
-};
-
 struct RoundDev {
   const WorkItem*   work;    // one item per workgroup of a static launch: item i runs on XCD i % 8
   const WorkItem*   qwork;   // the same items grouped by that XCD: the queues of a queued launch
@@ -54,7 +21,7 @@ struct RoundDev {
   const float*      tab_diff;  // [n_agents][2][64]: same for dst_pos0 - diff_pos0 (payload re-rotation)
   // general block layouts (some agent has its own order of the shared blocks); all NULL otherwise
   const int32_t*    rowmap;    // [sum_i S_i]: pool row of (agent, master token), agents in order
-  const int4*       pagetab;   // [sum_i pages_i]: {first table, second table, row mask of the second,
+  const PageTab*    pagetab;   // [sum_i pages_i]: {first table, second table, row mask of the second,
                                //  bit t: table t's run moved since the stored diff was encoded}
   const float*      segtab;    // [n tables][2][64]: cos then sin, one table per (agent, segment)
   const float*      segtab_diff;  // same indexing: dst_pos - diff_pos of the segment (payload re-rotation)

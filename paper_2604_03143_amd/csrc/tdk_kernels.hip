@@ -113,7 +113,7 @@ __device__ __forceinline__ void stage_group(const RoundDev& rd, const WorkItem& 
   for (int i = tid; i < w.ag_count * 64; i += kBlock) {
     const int g = i >> 6, which = (i >> 5) & 1, q = i & 31;
     const AgentDev ad = rd.agents[rd.order[w.ag_begin + g]];
-    const int4 pt = rd.pagetab[ad.flag_off + w.page];
+    const PageTab pt = rd.pagetab[ad.flag_off + w.page];
     const int t = which ? pt.y : pt.x;
     reinterpret_cast<float4*>(sh.tab[g][which])[q] =
         reinterpret_cast<const float4*>(rd.segtab + (size_t)t * (2 * kHalf))[q];
@@ -707,7 +707,7 @@ __device__ __forceinline__ void scatter_slots(const RoundDev& rd, const LayerDev
       if (rd.seg) {
         moved = 0;
         if (p >= 0 && p < rd.sess[ad.session].pages) {
-          const int4 pt = rd.pagetab[ad.flag_off + p];
+          const PageTab pt = rd.pagetab[ad.flag_off + p];
           t0 = pt.x; t1 = pt.y; sel = (uint32_t)pt.z; moved = (uint32_t)pt.w;
           tabs = rd.segtab_diff;
         }

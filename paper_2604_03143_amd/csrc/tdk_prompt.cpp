@@ -6,6 +6,7 @@
 #include <algorithm>
 #include <cstring>
 #include <map>
+#include <memory>
 #include <new>
 #include <string>
 #include <unordered_map>
@@ -99,7 +100,7 @@ tdk_status tdk_prompt_plan_create(const tdk_prompt* prompts, int32_t n_prompts, 
       if (kv.second.size() >= 2) groups.push_back(&kv.second);
     std::sort(groups.begin(), groups.end(), [](const std::vector<int32_t>* a, const std::vector<int32_t>* b) { return (*a)[0] < (*b)[0]; });
     // 4. master order = shared blocks in the order of the group's first prompt; segments of every member
-    tdk_prompt_plan* plan = new tdk_prompt_plan();
+    std::unique_ptr<tdk_prompt_plan> plan(new tdk_prompt_plan());   // freed if anything below throws
     plan->session_of.assign(n_prompts, -1);
     plan->segments.resize(n_prompts);
     std::vector<int32_t> src(reps.size(), -1);
@@ -113,7 +114,7 @@ tdk_status tdk_prompt_plan_create(const tdk_prompt* prompts, int32_t n_prompts, 
           order.push_back(b.content);
           at += b.len;
         }
-      if (at >= (int64_t)1 << 31) { delete plan; return TDK_ERR_UNSUPPORTED; }
+      if (at >= (int64_t)1 << 31) return TDK_ERR_UNSUPPORTED;
       plan->span.push_back((int32_t)at);
       for (int32_t i : m) {
         plan->session_of[i] = (int32_t)s;
@@ -128,7 +129,7 @@ tdk_status tdk_prompt_plan_create(const tdk_prompt* prompts, int32_t n_prompts, 
       }
       for (int32_t c : order) src[c] = -1;
     }
-    *out = plan;
+    *out = plan.release();
     return TDK_OK;
   } catch (const std::bad_alloc&) {
     return TDK_ERR_NOMEM;

@@ -1,6 +1,6 @@
-"""Host code under the sanitizers (no GPU): the prompt plan (C++, AddressSanitizer + UBSan, a native driver with
-seeded random prompt sets) and the oracle (C, UBSan, its own pins run once more against the instrumented build).
-A finding aborts the instrumented program, which fails the test."""
+"""Host code under the sanitizers (no GPU): the round planner and the prompt plan (C++, AddressSanitizer + UBSan,
+native drivers with seeded random inputs) and the oracle (C, UBSan, its own pins run once more against the
+instrumented build).  A finding aborts the instrumented program, which fails the test."""
 import os
 import subprocess
 import sys
@@ -16,6 +16,19 @@ def test_prompt_plan_under_asan_and_ubsan(tmp_path):
            os.path.join(ROOT, "paper_2604_03143_amd", "csrc", "tdk_prompt.cpp"), "-o", exe]
     subprocess.run(cmd, check=True)
     run = subprocess.run([exe], capture_output=True, text=True, timeout=120)
+    assert run.returncode == 0, run.stdout + run.stderr
+    assert "clean" in run.stdout
+
+
+def test_round_planner_under_asan_and_ubsan(tmp_path):
+    """tdk_round_create's validation and index arithmetic (block-table slices, row map, page table, rotation
+    tables, work list, per-XCD queues) live in csrc/tdk_plan.cpp, which needs no HIP."""
+    exe = str(tmp_path / "plan_fuzz")
+    csrc = os.path.join(ROOT, "paper_2604_03143_amd", "csrc")
+    cmd = ["g++", "-std=c++17", "-O1", "-g", *SAN, "-I", os.path.join(ROOT, "include"), "-I", csrc,
+           os.path.join(ROOT, "tests", "plan_fuzz.cpp"), os.path.join(csrc, "tdk_plan.cpp"), "-o", exe]
+    subprocess.run(cmd, check=True)
+    run = subprocess.run([exe], capture_output=True, text=True, timeout=300)
     assert run.returncode == 0, run.stdout + run.stderr
     assert "clean" in run.stdout
 
