@@ -146,12 +146,11 @@ size_t     tdk_scratch_bytes(const tdk_round* r);       /* device bytes the roun
 #define TDK_TUNE_XCD_QUEUES         128  /* page kernels: resident workgroups take work items from one queue per XCD
                                             and, when theirs is empty, from the others' (the XCDs do not write at the
                                             same rate); off: one workgroup per item, fixed to an XCD by its number */
-#define TDK_TUNE_XCD_QUEUES_READ    256  /* the same for the kernels that only read the pool (compare, key difference) */
-#define TDK_TUNE_TAPER              512  /* work list: smaller agent groups for the last pages, so that a launch does not
+#define TDK_TUNE_TAPER              256  /* work list: smaller agent groups for the last pages, so that a launch does not
                                             end with a few long items on an otherwise idle chip                      */
-#define TDK_TUNE_QUEUES_ANY_SIZE    1024 /* queues also for rounds with fewer than four items per resident workgroup
+#define TDK_TUNE_QUEUES_ANY_SIZE    512  /* queues also for rounds with fewer than four items per resident workgroup
                                             (by default such launches stay static: it is faster there)             */
-#define TDK_TUNE_ALL                2047
+#define TDK_TUNE_ALL                1023
 #define TDK_TUNE_DEFAULT            191
 tdk_status tdk_round_tune(tdk_round* r, int32_t agents_per_group, int32_t flags);
 int32_t    tdk_round_agents_per_group(const tdk_round* r);   /* the value in use (resolved if automatic); 0 for NULL */

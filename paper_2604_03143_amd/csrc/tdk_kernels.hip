@@ -278,7 +278,7 @@ __device__ __forceinline__ void stamp_mid(const RoundDev& rd, int item, int whic
 
 // Which work items a workgroup processes.
 //   Static: workgroup b owns item b, dispatched by the hardware round-robin over the XCDs.
-//   Queued (TDK_TUNE_XCD_QUEUES for the kernels that write, TDK_TUNE_XCD_QUEUES_READ for those that read): the launch holds only as many workgroups as the device keeps resident, and each
+//   Queued (TDK_TUNE_XCD_QUEUES, the kernels that write): the launch holds only as many workgroups as the device keeps resident, and each
 //   takes items until none is left: first from the queue of the XCD it runs on (the items that the static form
 //   would have run there, so re-reads of a master page still meet in that XCD's L2), then from the other XCDs'
 //   queues.  The XCDs do not write to memory at the same rate (measured: four of the eight finish a static
@@ -290,10 +290,10 @@ __device__ __forceinline__ void stamp_mid(const RoundDev& rd, int item, int whic
 // a wavefront for microseconds at every item border while the chip is writing at full rate).
 __device__ __forceinline__ void lds_barrier() { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory"); }
 
+template <bool queued>
 struct Items {
   int home, k, ahead;
-  bool queued;
-  __device__ __forceinline__ Items(const RoundDev& rd, bool q) : home(xcd_id()), k(0), ahead(-1), queued(q) {}
+  __device__ __forceinline__ Items() : home(queued ? xcd_id() : 0), k(0), ahead(-1) {}
 
   // The first item of every workgroup is fixed by its number (workgroup b starts with entry b / 8 of queue b % 8, the
   // XCD the hardware places it on): no atomic stands between the launch and the first access, and the queues hand
@@ -316,7 +316,7 @@ struct Items {
   // the writes).  Called once per item, after the item's own loads have been issued: answers come back in issue
   // order, so a load issued behind the atomic would wait for it, while the stores of the data phase do not.
   __device__ __forceinline__ void prefetch(const RoundDev& rd) {
-    if (queued && threadIdx.x == 0) ahead = fetch(rd);
+    if (queued) { if (threadIdx.x == 0) ahead = fetch(rd); }
   }
 
   // Hands the prefetched item to the whole workgroup.
@@ -338,7 +338,7 @@ struct Items {
   }
   __device__ __forceinline__ const WorkItem& at(const RoundDev& rd, int item) const { return queued ? rd.qwork[item] : rd.work[item]; }
   __device__ __forceinline__ void leave(const RoundDev& rd) {
-    if (queued && threadIdx.x == 0) {
+    if (queued) if (threadIdx.x == 0) {
       const int gone = atomicAdd(&rd.q_state[8], 1);
       if (gone == (int)gridDim.x - 1) {       // nobody takes items any more
 #pragma unroll
@@ -350,7 +350,7 @@ struct Items {
   }
 };
 
-template <int RPW, bool IL, bool NT, bool SEG>
+template <int RPW, bool IL, bool NT, bool SEG, bool Q>
 __global__ __launch_bounds__(kBlock) void tdk_rerotate_kernel(const RoundDev rd, const LayerDev io) {
   constexpr int T = RPW * kWaves;
   __shared__ std::conditional_t<SEG, GroupSharedSeg, GroupShared> sh;
@@ -361,7 +361,7 @@ __global__ __launch_bounds__(kBlock) void tdk_rerotate_kernel(const RoundDev rd,
   const int64_t row_u4 = (int64_t)rd.heads * 16;
   u32x4* pk = io.pool_k;
   u32x4* pv = io.pool_v;
-  Items items(rd, (rd.nontemporal & 128) != 0);
+  Items<Q> items;
   for (int item = items.first(rd, &s_item); item >= 0; item = items.next(rd, &s_item)) {
     stamp_begin(rd, item);
     const WorkItem w = items.at(rd, item);
@@ -435,16 +435,14 @@ __global__ __launch_bounds__(kBlock) void tdk_flag_kernel(const RoundDev rd, con
   constexpr int T = RPW * kWaves;
   constexpr bool DOK = (PM & 1) != 0, DOV = (PM & 2) != 0;
   __shared__ std::conditional_t<SEG, GroupSharedSeg, GroupShared> sh;
-  __shared__ int s_item;
   const Lane L = lane_geometry(rd.heads);
   const int wave = threadIdx.x >> 6;
   const int64_t row_u4 = (int64_t)rd.heads * 16;
   const u32x4* pk = io.pool_k;
   const u32x4* pv = io.pool_v;
-  Items items(rd, (rd.nontemporal & 256) != 0);
-  for (int item = items.first(rd, &s_item); item >= 0; item = items.next(rd, &s_item)) {
+  const int item = blockIdx.x;
   stamp_begin(rd, item);
-  const WorkItem w = items.at(rd, item);
+  const WorkItem w = rd.work[item];
   stage_group<T>(rd, w, sh);
   MasterRows<RPW> M;
   load_master<RPW, DOV, DOK>(rd, io, w, L, M);
@@ -453,7 +451,6 @@ __global__ __launch_bounds__(kBlock) void tdk_flag_kernel(const RoundDev rd, con
   for (int k = 0; k < RPW; ++k)
     special[k] = ((int)chunk_special(M.kl[k]) | (int)chunk_special(M.kh[k]) | (int)chunk_special(M.v0[k]) | (int)chunk_special(M.v1[k])) != 0;
   lds_barrier();
-  items.prefetch(rd);
   for (int g = 0; g < w.ag_count; ++g) {
     float c[8], s[8];
     if (DOK && !SEG) load_tab<IL>(sh, g, 0, L.jb, c, s);
@@ -496,8 +493,6 @@ __global__ __launch_bounds__(kBlock) void tdk_flag_kernel(const RoundDev rd, con
     rd.flags[ad.flag_off + w.page] = (uint8_t)sh.aux[threadIdx.x];
   }
   stamp_end(rd, item);
-  }
-  items.leave(rd);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -803,7 +798,7 @@ __global__ __launch_bounds__(kBlock) void tdk_scatter_kernel(const RoundDev rd, 
   scatter_slots<IL>(rd, io, d, planes, ss, blockIdx.x, gridDim.x);
 }
 
-template <int RPW, bool IL, bool NT, int PM, bool SEG>
+template <int RPW, bool IL, bool NT, int PM, bool SEG, bool Q>
 __global__ __launch_bounds__(kBlock) void tdk_decode_kernel(const RoundDev rd, const LayerDev io, const DiffDev d) {
   constexpr int T = RPW * kWaves;
   __shared__ std::conditional_t<SEG, GroupSharedSeg, GroupShared> sh;
@@ -815,7 +810,7 @@ __global__ __launch_bounds__(kBlock) void tdk_decode_kernel(const RoundDev rd, c
   const int64_t row_u4 = (int64_t)rd.heads * 16;
   u32x4* pk = io.pool_k;
   u32x4* pv = io.pool_v;
-  Items items(rd, (rd.nontemporal & 128) != 0);
+  Items<Q> items;
   for (int item = items.first(rd, &s_item); item >= 0; item = items.next(rd, &s_item)) {
     stamp_begin(rd, item);
     const WorkItem w = items.at(rd, item);
@@ -907,19 +902,16 @@ template <int RPW, bool IL, bool SEG, bool NTL>
 __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(RPW == 4 ? 4 : 1))) void tdk_keydiff_kernel(const RoundDev rd, const LayerDev io, const PlanDev pl) {
   constexpr int T = RPW * kWaves;
   __shared__ std::conditional_t<SEG, GroupSharedSeg, GroupShared> sh;
-  __shared__ int s_item;
   const Lane L = lane_geometry(rd.heads);
   const int wave = threadIdx.x >> 6;
   const int64_t row_u4 = (int64_t)rd.heads * 16;
   const u32x4* pk = io.pool_k;
-  Items items(rd, (rd.nontemporal & 256) != 0);
-  for (int item = items.first(rd, &s_item); item >= 0; item = items.next(rd, &s_item)) {
-  const WorkItem w = items.at(rd, item);
+  const WorkItem w = rd.work[blockIdx.x];
   stage_group<T>(rd, w, sh);
   MasterRows<RPW> M;
   load_master<RPW, false>(rd, io, w, L, M);
+  if (threadIdx.x < w.ag_count) sh.aux[threadIdx.x] = rd.agents[sh.agent[threadIdx.x]].score_off;   // (own entry of sh.agent)
   lds_barrier();
-  items.prefetch(rd);
   for (int g = 0; g < w.ag_count; ++g) {
     float c[8], s[8];
     if (!SEG) load_tab<IL>(sh, g, 0, L.jb, c, s);
@@ -932,7 +924,7 @@ __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(RPW == 4
       const int64_t base = dest_row<T>(sh, g, wave + kWaves * k) * row_u4;
       akl[k] = ld16<NTL>(pk + base + L.klo); akh[k] = ld16<NTL>(pk + base + L.khi);
     }
-    const int score_off = rd.agents[sh.agent[g]].score_off;
+    const int score_off = sh.aux[g];
 #pragma unroll
     for (int k = 0; k < RPW; ++k) {
       if (!M.valid[k]) continue;
@@ -953,8 +945,6 @@ __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(RPW == 4
       if ((threadIdx.x & 63) == 63) pl.score[score_off + w.page * T + wave + kWaves * k] = acc;
     }
   }
-  }
-  items.leave(rd);
 }
 
 // rank of a set flag among the set flags of the workgroup (threads in order) and their total
@@ -1170,32 +1160,35 @@ __global__ __launch_bounds__(kBlock) void tdk_page_read_product_kernel(const u32
 // launchers
 // ---------------------------------------------------------------------------------------------
 
-// Launch of a page kernel.  Static distribution: one workgroup per work item.  Queued (the round's tuning flag
-// `queue_bit`, and only when every resident workgroup gets at least four items: below that the launch is over
-// before an imbalance between the XCDs can build up, and the hardware's own dispatch of fresh workgroups fills
-// freed wavefront slots sooner than a looping workgroup does): as many workgroups as the device keeps resident.
-template <class Kernel, class... Args>
-static void launch_pages(RoundDev rd, Kernel kernel, int queue_bit, hipStream_t st, Args... args) {
-  unsigned grid = (unsigned)rd.n_work;
-  if (rd.nontemporal & queue_bit) {
-    static std::mutex mu;
-    static std::map<const void*, int> per_cu;
+// Launch of a page kernel that writes (rerotate, decode).  Static distribution: one workgroup per work item.
+// Queued (TDK_TUNE_XCD_QUEUES, and only when every resident workgroup gets at least four items: below that the
+// launch is over before an imbalance between the XCDs can build up, and the hardware's own dispatch of fresh
+// workgroups fills freed wavefront slots sooner than a looping workgroup does): as many workgroups as the device
+// keeps resident.  `pick(queued)` returns the kernel instantiation for either form.
+template <class KernelQ, class KernelS, class... Args>
+static void launch_write_pages(const RoundDev& rd, KernelQ queued_kernel, KernelS static_kernel, hipStream_t st, Args... args) {
+  if (rd.nontemporal & 128) {
     int n = 0;
     {
+      static std::mutex mu;
+      static std::map<const void*, int> per_cu;
       std::lock_guard<std::mutex> lock(mu);
-      auto it = per_cu.find(reinterpret_cast<const void*>(kernel));
+      const void* id = reinterpret_cast<const void*>(queued_kernel);
+      auto it = per_cu.find(id);
       if (it == per_cu.end()) {
-        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, kernel, kBlock, 0) != hipSuccess || n < 1) n = 2;
-        per_cu[reinterpret_cast<const void*>(kernel)] = n;
+        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, queued_kernel, kBlock, 0) != hipSuccess || n < 1) n = 2;
+        per_cu[id] = n;
       } else {
         n = it->second;
       }
     }
     const int64_t resident = (int64_t)n * std::max(rd.n_cus, 1);
-    if ((int64_t)rd.n_work >= 4 * resident || (rd.nontemporal & 1024)) grid = (unsigned)std::min<int64_t>(rd.n_work, resident);
-    else rd.nontemporal &= ~queue_bit;
+    if ((int64_t)rd.n_work >= 4 * resident || (rd.nontemporal & 512)) {
+      hipLaunchKernelGGL(queued_kernel, dim3((unsigned)std::min<int64_t>(rd.n_work, resident)), dim3(kBlock), 0, st, rd, args...);
+      return;
+    }
   }
-  hipLaunchKernelGGL(kernel, dim3(grid), dim3(kBlock), 0, st, rd, args...);
+  hipLaunchKernelGGL(static_kernel, dim3((unsigned)rd.n_work), dim3(kBlock), 0, st, rd, args...);
 }
 
 template <int V> using ic = std::integral_constant<int, V>;
@@ -1210,8 +1203,8 @@ hipError_t launch_rerotate(const RoundDev& rd, const LayerDev& io, hipStream_t s
   if (rd.n_work == 0) return hipSuccess;
   with_rpw(rd.page_tokens, [&](auto rpw) { with_bool(rd.interleaved != 0, [&](auto il) { with_bool((rd.nontemporal & 1) != 0, [&](auto nt) {
     with_bool(rd.seg != 0, [&](auto sg) {
-      auto kernel = tdk_rerotate_kernel<decltype(rpw)::value, decltype(il)::value, decltype(nt)::value, decltype(sg)::value>;
-      launch_pages(rd, kernel, 128, st, io);
+      launch_write_pages(rd, tdk_rerotate_kernel<decltype(rpw)::value, decltype(il)::value, decltype(nt)::value, decltype(sg)::value, true>,
+                         tdk_rerotate_kernel<decltype(rpw)::value, decltype(il)::value, decltype(nt)::value, decltype(sg)::value, false>, st, io);
     });
   }); }); });
   return hipGetLastError();
@@ -1221,8 +1214,8 @@ hipError_t launch_flag(const RoundDev& rd, const LayerDev& io, float eps, int pl
   if (rd.n_work == 0) return hipSuccess;
   with_rpw(rd.page_tokens, [&](auto rpw) { with_bool(rd.interleaved != 0, [&](auto il) { with_planes(planes, [&](auto pm) {
     with_bool(rd.seg != 0, [&](auto sg) { with_bool((rd.nontemporal & 4) != 0, [&](auto ntl) {
-      auto kernel = tdk_flag_kernel<decltype(rpw)::value, decltype(il)::value, decltype(pm)::value, decltype(sg)::value, decltype(ntl)::value>;
-      launch_pages(rd, kernel, 256, st, io, eps);
+      hipLaunchKernelGGL((tdk_flag_kernel<decltype(rpw)::value, decltype(il)::value, decltype(pm)::value, decltype(sg)::value, decltype(ntl)::value>),
+                         dim3(rd.n_work), dim3(kBlock), 0, st, rd, io, eps);
     }); });
   }); }); });
   return hipGetLastError();
@@ -1244,8 +1237,8 @@ hipError_t launch_decode(const RoundDev& rd, const LayerDev& io, const DiffDev& 
   if (rd.n_work == 0) return hipSuccess;
   with_rpw(rd.page_tokens, [&](auto rpw) { with_bool(rd.interleaved != 0, [&](auto il) { with_bool((rd.nontemporal & 2) != 0, [&](auto nt) {
     with_planes(planes, [&](auto pm) { with_bool(rd.seg != 0, [&](auto sg) {
-      auto kernel = tdk_decode_kernel<decltype(rpw)::value, decltype(il)::value, decltype(nt)::value, decltype(pm)::value, decltype(sg)::value>;
-      launch_pages(rd, kernel, 128, st, io, d);
+      launch_write_pages(rd, tdk_decode_kernel<decltype(rpw)::value, decltype(il)::value, decltype(nt)::value, decltype(pm)::value, decltype(sg)::value, true>,
+                         tdk_decode_kernel<decltype(rpw)::value, decltype(il)::value, decltype(nt)::value, decltype(pm)::value, decltype(sg)::value, false>, st, io, d);
     }); });
   }); }); });
   return hipGetLastError();
@@ -1262,8 +1255,8 @@ hipError_t launch_keydiff(const RoundDev& rd, const LayerDev& io, const PlanDev&
   if (rd.n_work == 0) return hipSuccess;
   with_rpw(rd.page_tokens, [&](auto rpw) { with_bool(rd.interleaved != 0, [&](auto il) { with_bool(rd.seg != 0, [&](auto sg) {
     with_bool((rd.nontemporal & 4) != 0, [&](auto ntl) {
-      auto kernel = tdk_keydiff_kernel<decltype(rpw)::value, decltype(il)::value, decltype(sg)::value, decltype(ntl)::value>;
-      launch_pages(rd, kernel, 256, st, io, pl);
+      hipLaunchKernelGGL((tdk_keydiff_kernel<decltype(rpw)::value, decltype(il)::value, decltype(sg)::value, decltype(ntl)::value>),
+                         dim3(rd.n_work), dim3(kBlock), 0, st, rd, io, pl);
     });
   }); }); });
   return hipGetLastError();

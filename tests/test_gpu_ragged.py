@@ -20,7 +20,7 @@ def ragged_round(T=16, H=8, frac=0.2, spans=SPANS, agents=AGENTS, stream=88):
     return wl.make_round(spec, spans=spans, agents=agents)
 
 
-@pytest.mark.parametrize("group,flags", [(0, None), (1, 191 + 256 + 1024), (3, None), (32, 2047), (2, 63 + 512)])
+@pytest.mark.parametrize("group,flags", [(0, None), (1, 191 + 512), (3, None), (32, 1023), (2, 63 + 256)])
 def test_pipeline_on_ragged_sessions(tdo, group, flags):
     """(flags: the work items handed out statically, from the per-XCD queues whatever the round's size, tapered)"""
     from test_gpu_parity import run_pipeline
