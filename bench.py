@@ -843,7 +843,7 @@ def read_traffic(workload, kernel, prefix="hbm_traffic"):
     try:
         for line in open(path):
             f = line.split()
-            if len(f) >= 2 and f[0].lstrip("# ") == "csrc_sha256":
+            if len(f) >= 2 and "csrc_sha256" in f[:2]:
                 tagged = f[-1]
             if len(f) == 4 and f[0] == kernel:
                 value = float(f[3])
@@ -859,7 +859,7 @@ def traffic_note(workload, prefix="hbm_traffic"):
     tagged = None
     for line in open(path):
         f = line.split()
-        if len(f) >= 2 and f[0].lstrip("# ") == "csrc_sha256":
+        if len(f) >= 2 and "csrc_sha256" in f[:2]:
             tagged = f[-1]
     if tagged != csrc_hash(prefix):
         return (f"profiles/{prefix}_{workload}.txt was taken from kernel sources {tagged}, this run uses {csrc_hash(prefix)}: "
