@@ -150,8 +150,10 @@ size_t     tdk_scratch_bytes(const tdk_round* r);       /* device bytes the roun
                                             end with a few long items on an otherwise idle chip                      */
 #define TDK_TUNE_QUEUES_ANY_SIZE    512  /* queues also for rounds with fewer than four items per resident workgroup
                                             (by default such launches stay static: it is faster there)             */
-#define TDK_TUNE_ALL                1023
-#define TDK_TUNE_DEFAULT            191
+#define TDK_TUNE_SCATTER_IN_DECODE  1024 /* small rounds (static launches): the workgroups that copy the listed pages ride
+                                            behind the page items of decode's launch instead of a launch of their own */
+#define TDK_TUNE_ALL                2047
+#define TDK_TUNE_DEFAULT            (191 + 1024)
 tdk_status tdk_round_tune(tdk_round* r, int32_t agents_per_group, int32_t flags);
 int32_t    tdk_round_agents_per_group(const tdk_round* r);   /* the value in use (resolved if automatic); 0 for NULL */
 

@@ -387,12 +387,14 @@ tdk_status round_create(const tdk_model* model, const tdk_session* sessions, int
 }
 
 // The two halves of skip-or-correct: the page kernel writes every page that no diff lists from the re-rotated
-// master, the slot kernel copies the listed pages from the payload.
+// master, the slot kernel copies the listed pages from the payload (in a launch of its own, or, on small rounds,
+// as extra workgroups of the page kernel's launch).
 tdk_status launch_restore(tdk_round* r, const LayerDev& l, const DiffDev& d, int planes, int64_t capacity_pages, hipStream_t s) {
   // the number of listed pages is known on the device only: a fixed number of workgroups strides over them
   const int slots = (int)std::min<int64_t>(std::min<int64_t>(capacity_pages, r->total_pages), 1 << 20);
-  TDK_LAUNCH(r, TDK_KERNEL_DECODE, s, launch_decode(r->rd, l, d, planes, s));
-  TDK_LAUNCH(r, TDK_KERNEL_SCATTER, s, launch_scatter(r->rd, l, d, planes, slots, s));
+  bool scattered = false;
+  TDK_LAUNCH(r, TDK_KERNEL_DECODE, s, launch_decode(r->rd, l, d, planes, slots, &scattered, s));
+  if (!scattered) TDK_LAUNCH(r, TDK_KERNEL_SCATTER, s, launch_scatter(r->rd, l, d, planes, slots, s));
   return TDK_OK;
 }
 

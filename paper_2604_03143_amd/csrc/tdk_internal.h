@@ -98,7 +98,8 @@ hipError_t launch_rerotate(const RoundDev& rd, const LayerDev& io, hipStream_t s
 hipError_t launch_flag(const RoundDev& rd, const LayerDev& io, float eps, int planes, hipStream_t st);
 hipError_t launch_compact(const RoundDev& rd, const DiffDev& d, hipStream_t st);
 hipError_t launch_gather(const RoundDev& rd, const LayerDev& io, const DiffDev& d, int planes, int grid, hipStream_t st);
-hipError_t launch_decode(const RoundDev& rd, const LayerDev& io, const DiffDev& d, int planes, hipStream_t st);
+hipError_t launch_decode(const RoundDev& rd, const LayerDev& io, const DiffDev& d, int planes, int scatter_blocks, bool* scattered,
+                         hipStream_t st);
 hipError_t launch_scatter(const RoundDev& rd, const LayerDev& io, const DiffDev& d, int planes, int grid, hipStream_t st);
 hipError_t launch_keydiff(const RoundDev& rd, const LayerDev& io, const PlanDev& pl, hipStream_t st);
 hipError_t launch_select(const RoundDev& rd, const PlanDev& pl, hipStream_t st);

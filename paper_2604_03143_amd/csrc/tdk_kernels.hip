@@ -799,11 +799,21 @@ __global__ __launch_bounds__(kBlock) void tdk_scatter_kernel(const RoundDev rd, 
 }
 
 template <int RPW, bool IL, bool NT, int PM, bool SEG, bool Q>
-__global__ __launch_bounds__(kBlock) void tdk_decode_kernel(const RoundDev rd, const LayerDev io, const DiffDev d) {
+__global__ __launch_bounds__(kBlock) void tdk_decode_kernel(const RoundDev rd, const LayerDev io, const DiffDev d,
+                                                            const int n_scatter) {
   constexpr int T = RPW * kWaves;
   __shared__ std::conditional_t<SEG, GroupSharedSeg, GroupShared> sh;
   __shared__ int s_item;
   constexpr bool DOK = (PM & 1) != 0, DOV = (PM & 2) != 0;
+  if (!Q && (int)blockIdx.x >= rd.n_work) {
+    // Small rounds only (static launches that do not fill the chip for long): the workgroups that copy the listed
+    // pages from the payload ride behind the page items of the same launch, n_scatter of them, and run while the
+    // page items drain, instead of paying for a launch of their own.  (On large rounds two launches are faster:
+    // payload reads among the page items' writes cost more than the second launch.)
+    __shared__ ScatterShared ss;
+    scatter_slots<IL>(rd, io, d, PM, ss, (int64_t)blockIdx.x - rd.n_work, n_scatter);
+    return;
+  }
   const Lane L = lane_geometry(rd.heads);
   if (rd.nontemporal & 64) sweep_masters(rd, io, DOK, DOV);
   const int wave = threadIdx.x >> 6;
@@ -1165,30 +1175,33 @@ __global__ __launch_bounds__(kBlock) void tdk_page_read_product_kernel(const u32
 // launch is over before an imbalance between the XCDs can build up, and the hardware's own dispatch of fresh
 // workgroups fills freed wavefront slots sooner than a looping workgroup does): as many workgroups as the device
 // keeps resident.  `pick(queued)` returns the kernel instantiation for either form.
+// `extra` static workgroups behind the page items (decode's payload copies on small rounds); returns whether they
+// were launched (only the static form takes them).
 template <class KernelQ, class KernelS, class... Args>
-static void launch_write_pages(const RoundDev& rd, KernelQ queued_kernel, KernelS static_kernel, hipStream_t st, Args... args) {
-  if (rd.nontemporal & 128) {
-    int n = 0;
-    {
-      static std::mutex mu;
-      static std::map<const void*, int> per_cu;
-      std::lock_guard<std::mutex> lock(mu);
-      const void* id = reinterpret_cast<const void*>(queued_kernel);
-      auto it = per_cu.find(id);
-      if (it == per_cu.end()) {
-        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, queued_kernel, kBlock, 0) != hipSuccess || n < 1) n = 2;
-        per_cu[id] = n;
-      } else {
-        n = it->second;
-      }
-    }
-    const int64_t resident = (int64_t)n * std::max(rd.n_cus, 1);
-    if ((int64_t)rd.n_work >= 4 * resident || (rd.nontemporal & 512)) {
-      hipLaunchKernelGGL(queued_kernel, dim3((unsigned)std::min<int64_t>(rd.n_work, resident)), dim3(kBlock), 0, st, rd, args...);
-      return;
+static bool launch_write_pages(const RoundDev& rd, KernelQ queued_kernel, KernelS static_kernel, int extra, hipStream_t st, Args... args) {
+  int n = 0;
+  {
+    static std::mutex mu;
+    static std::map<const void*, int> per_cu;
+    std::lock_guard<std::mutex> lock(mu);
+    const void* id = reinterpret_cast<const void*>(queued_kernel);
+    auto it = per_cu.find(id);
+    if (it == per_cu.end()) {
+      if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, queued_kernel, kBlock, 0) != hipSuccess || n < 1) n = 2;
+      per_cu[id] = n;
+    } else {
+      n = it->second;
     }
   }
-  hipLaunchKernelGGL(static_kernel, dim3((unsigned)rd.n_work), dim3(kBlock), 0, st, rd, args...);
+  const int64_t resident = (int64_t)n * std::max(rd.n_cus, 1);
+  const bool large = (int64_t)rd.n_work >= 4 * resident;
+  if ((rd.nontemporal & 128) && (large || (rd.nontemporal & 512))) {
+    hipLaunchKernelGGL(queued_kernel, dim3((unsigned)std::min<int64_t>(rd.n_work, resident)), dim3(kBlock), 0, st, rd, args...);
+    return false;
+  }
+  const bool ride = extra > 0 && !large && (rd.nontemporal & 1024);
+  hipLaunchKernelGGL(static_kernel, dim3((unsigned)rd.n_work + (ride ? (unsigned)extra : 0u)), dim3(kBlock), 0, st, rd, args...);
+  return ride;
 }
 
 template <int V> using ic = std::integral_constant<int, V>;
@@ -1204,7 +1217,7 @@ hipError_t launch_rerotate(const RoundDev& rd, const LayerDev& io, hipStream_t s
   with_rpw(rd.page_tokens, [&](auto rpw) { with_bool(rd.interleaved != 0, [&](auto il) { with_bool((rd.nontemporal & 1) != 0, [&](auto nt) {
     with_bool(rd.seg != 0, [&](auto sg) {
       launch_write_pages(rd, tdk_rerotate_kernel<decltype(rpw)::value, decltype(il)::value, decltype(nt)::value, decltype(sg)::value, true>,
-                         tdk_rerotate_kernel<decltype(rpw)::value, decltype(il)::value, decltype(nt)::value, decltype(sg)::value, false>, st, io);
+                         tdk_rerotate_kernel<decltype(rpw)::value, decltype(il)::value, decltype(nt)::value, decltype(sg)::value, false>, 0, st, io);
     });
   }); }); });
   return hipGetLastError();
@@ -1233,12 +1246,18 @@ hipError_t launch_gather(const RoundDev& rd, const LayerDev& io, const DiffDev& 
   return hipGetLastError();
 }
 
-hipError_t launch_decode(const RoundDev& rd, const LayerDev& io, const DiffDev& d, int planes, hipStream_t st) {
+// scatter_blocks > 0: so many workgroups may ride behind the page items to copy the listed pages; *scattered says
+// whether they did (then no separate scatter launch is needed)
+hipError_t launch_decode(const RoundDev& rd, const LayerDev& io, const DiffDev& d, int planes, int scatter_blocks, bool* scattered,
+                         hipStream_t st) {
+  *scattered = false;
   if (rd.n_work == 0) return hipSuccess;
+  if (rd.n_agents == 0 || d.capacity == 0) scatter_blocks = 0;
   with_rpw(rd.page_tokens, [&](auto rpw) { with_bool(rd.interleaved != 0, [&](auto il) { with_bool((rd.nontemporal & 2) != 0, [&](auto nt) {
     with_planes(planes, [&](auto pm) { with_bool(rd.seg != 0, [&](auto sg) {
-      launch_write_pages(rd, tdk_decode_kernel<decltype(rpw)::value, decltype(il)::value, decltype(nt)::value, decltype(pm)::value, decltype(sg)::value, true>,
-                         tdk_decode_kernel<decltype(rpw)::value, decltype(il)::value, decltype(nt)::value, decltype(pm)::value, decltype(sg)::value, false>, st, io, d);
+      *scattered = launch_write_pages(rd, tdk_decode_kernel<decltype(rpw)::value, decltype(il)::value, decltype(nt)::value, decltype(pm)::value, decltype(sg)::value, true>,
+                                      tdk_decode_kernel<decltype(rpw)::value, decltype(il)::value, decltype(nt)::value, decltype(pm)::value, decltype(sg)::value, false>,
+                                      scatter_blocks, st, io, d, scatter_blocks);
     }); });
   }); }); });
   return hipGetLastError();

@@ -24,7 +24,8 @@ PLANE_K, PLANE_V = 1, 2
  KERNEL_ATTEND_MERGE) = range(13)
 KERNEL_KINDS = 13
 TUNE_XCD_QUEUES, TUNE_TAPER, TUNE_QUEUES_ANY_SIZE = 128, 256, 512
-TUNE_ALL, TUNE_DEFAULT = 1023, 191
+TUNE_SCATTER_IN_DECODE = 1024
+TUNE_ALL, TUNE_DEFAULT = 2047, 191 + 1024
 STATIC_SCRATCH_BYTES = 4 << 20
 
 EXPORTS = (
