@@ -905,13 +905,15 @@ __device__ __forceinline__ float wave_sum_to_lane63(float v) {
 }
 
 // Per (agent, token): sum over the row of (fresh K - rotated cached K)^2, fp32.  Same traversal as
-// the compare kernel, K plane only; one float per row leaves each wavefront.  Only half a page per
-// agent is in flight per workgroup here, so the kernel needs occupancy to cover the memory latency:
-// with 16-token pages the register budget is held to 128 (4 waves per SIMD; 518 -> 478 us measured).
+// the compare kernel, K plane only.  Twice the arithmetic per byte of the compare kernel and only half a
+// page per agent in flight, so the loads of one agent must overlap the arithmetic of the one before: see the
+// rolling requests below (482 -> 415 us on 250 agents x 5000 tokens; at a budget of 128 registers the compiler
+// spills, and a reload from scratch waits for every load issued before it, so the kernel runs at 3 waves per SIMD).
 template <int RPW, bool IL, bool SEG, bool NTL>
-__global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(RPW == 4 ? 4 : 1))) void tdk_keydiff_kernel(const RoundDev rd, const LayerDev io, const PlanDev pl) {
+__global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(RPW == 4 ? 3 : 1))) void tdk_keydiff_kernel(const RoundDev rd, const LayerDev io, const PlanDev pl) {
   constexpr int T = RPW * kWaves;
   __shared__ std::conditional_t<SEG, GroupSharedSeg, GroupShared> sh;
+  __shared__ float s_score[kMaxGroup][T];
   const Lane L = lane_geometry(rd.heads);
   const int wave = threadIdx.x >> 6;
   const int64_t row_u4 = (int64_t)rd.heads * 16;
@@ -922,38 +924,49 @@ __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(RPW == 4
   load_master<RPW, false>(rd, io, w, L, M);
   if (threadIdx.x < w.ag_count) sh.aux[threadIdx.x] = rd.agents[sh.agent[threadIdx.x]].score_off;   // (own entry of sh.agent)
   lds_barrier();
+  // Rolling requests: row k of the next agent is asked for as soon as row k of this one has been used, into the
+  // registers that just became free, so a wavefront keeps its eight 16-byte loads per lane in flight all the
+  // time instead of only between two arithmetic phases.  The loop body has no branch around a load: a request
+  // that has nothing to fetch (a row past the span, a lane past the heads, the agent after the last) reads the
+  // first row of the master page instead, and its result is not used; with straight-line code the compiler
+  // counts the outstanding loads exactly and waits for the oldest pair only.
+  const u32x4* idle = io.master_k + (rd.sess[w.session].master_row0 + (int64_t)w.page * T) * row_u4 + L.jb;
+  u32x4 akl[RPW], akh[RPW];
+  auto request = [&](int g, int k) {
+    const int64_t base = dest_row<T>(sh, max(min(g, w.ag_count - 1), 0), wave + kWaves * k) * row_u4;
+    const bool ok = g < w.ag_count && M.valid[k] && L.kok;
+    const u32x4* lo = ok ? pk + base + L.klo : idle;
+    const u32x4* hi = ok ? pk + base + L.khi : idle + 8;
+    akl[k] = ld16<NTL>(lo); akh[k] = ld16<NTL>(hi);
+  };
+#pragma unroll
+  for (int k = 0; k < RPW; ++k) { request(0, k); __builtin_amdgcn_sched_barrier(0); }   // in the order the loop uses them
   for (int g = 0; g < w.ag_count; ++g) {
     float c[8], s[8];
     if (!SEG) load_tab<IL>(sh, g, 0, L.jb, c, s);
-    u32x4 akl[RPW], akh[RPW];
-    const u32x4 z = {0, 0, 0, 0};
 #pragma unroll
     for (int k = 0; k < RPW; ++k) {
-      akl[k] = z; akh[k] = z;
-      if (!M.valid[k] || !L.kok) continue;
-      const int64_t base = dest_row<T>(sh, g, wave + kWaves * k) * row_u4;
-      akl[k] = ld16<NTL>(pk + base + L.klo); akh[k] = ld16<NTL>(pk + base + L.khi);
-    }
-    const int score_off = sh.aux[g];
-#pragma unroll
-    for (int k = 0; k < RPW; ++k) {
-      if (!M.valid[k]) continue;
+      if (SEG) load_tab<IL>(sh, g, wave + kWaves * k, L.jb, c, s);
+      u32x4 rlo, rhi;
+      rotate16<IL>(M.kl[k], M.kh[k], c, s, rlo, rhi);
       float acc = 0.f;
-      if (L.kok) {
-        if (SEG) load_tab<IL>(sh, g, wave + kWaves * k, L.jb, c, s);
-        u32x4 rlo, rhi;
-        rotate16<IL>(M.kl[k], M.kh[k], c, s, rlo, rhi);
 #pragma unroll
-        for (int q = 0; q < 4; ++q) {
-          float d0 = bf_lo(akl[k][q]) - bf_lo(rlo[q]), d1 = bf_hi(akl[k][q]) - bf_hi(rlo[q]);
-          float d2 = bf_lo(akh[k][q]) - bf_lo(rhi[q]), d3 = bf_hi(akh[k][q]) - bf_hi(rhi[q]);
-          acc = __builtin_fmaf(d0, d0, acc); acc = __builtin_fmaf(d1, d1, acc);
-          acc = __builtin_fmaf(d2, d2, acc); acc = __builtin_fmaf(d3, d3, acc);
-        }
+      for (int q = 0; q < 4; ++q) {
+        float d0 = bf_lo(akl[k][q]) - bf_lo(rlo[q]), d1 = bf_hi(akl[k][q]) - bf_hi(rlo[q]);
+        float d2 = bf_lo(akh[k][q]) - bf_lo(rhi[q]), d3 = bf_hi(akh[k][q]) - bf_hi(rhi[q]);
+        acc = __builtin_fmaf(d0, d0, acc); acc = __builtin_fmaf(d1, d1, acc);
+        acc = __builtin_fmaf(d2, d2, acc); acc = __builtin_fmaf(d3, d3, acc);
       }
-      acc = wave_sum_to_lane63(acc);
-      if ((threadIdx.x & 63) == 63) pl.score[score_off + w.page * T + wave + kWaves * k] = acc;
+      request(g + 1, k);
+      acc = wave_sum_to_lane63(L.kok ? acc : 0.f);
+      if ((threadIdx.x & 63) == 63) s_score[g][wave + kWaves * k] = acc;   // (no store to memory among the loads: the count of outstanding accesses stays exact)
     }
+  }
+  lds_barrier();
+  const int rows = min(T, rd.sess[w.session].span - w.page * T);
+  for (int i = threadIdx.x; i < w.ag_count * T; i += kBlock) {
+    const int g = i / T, r = i - g * T;
+    if (r < rows) pl.score[sh.aux[g] + w.page * T + r] = s_score[g][r];
   }
 }
 
