@@ -451,39 +451,53 @@ __global__ __launch_bounds__(kBlock) void tdk_flag_kernel(const RoundDev rd, con
   for (int k = 0; k < RPW; ++k)
     special[k] = ((int)chunk_special(M.kl[k]) | (int)chunk_special(M.kh[k]) | (int)chunk_special(M.v0[k]) | (int)chunk_special(M.v1[k])) != 0;
   lds_barrier();
+  // Rolling requests (see tdk_keydiff_kernel): the rows of the next agent are asked for as the rows of this one
+  // are used up; no branch stands around a load, a request with nothing to fetch reads the first row of the
+  // master page and its result is ignored.
+  const int64_t first_row = (rd.sess[w.session].master_row0 + (int64_t)w.page * T) * row_u4;
+  const u32x4* idle_k = DOK ? io.master_k + first_row + L.jb : nullptr;
+  const u32x4* idle_v = DOV ? io.master_v + first_row + (threadIdx.x & 15) : nullptr;
+  const u32x4 z = {0, 0, 0, 0};
+  u32x4 akl[RPW], akh[RPW], av0[RPW], av1[RPW];
+  auto request = [&](int g, int k) {
+    const int64_t base = dest_row<T>(sh, max(min(g, w.ag_count - 1), 0), wave + kWaves * k) * row_u4;
+    const bool ok = g < w.ag_count && M.valid[k];
+    akl[k] = z; akh[k] = z; av0[k] = z; av1[k] = z;
+    if (DOK) {
+      akl[k] = ld16<NTL>(ok && L.kok ? pk + base + L.klo : idle_k);
+      akh[k] = ld16<NTL>(ok && L.kok ? pk + base + L.khi : idle_k + 8);
+    }
+    if (DOV) {
+      av0[k] = ld16<NTL>(ok && L.v0ok ? pv + base + L.v0 : idle_v);
+      av1[k] = ld16<NTL>(ok && L.v1ok ? pv + base + L.v1 : idle_v);
+    }
+  };
+#pragma unroll
+  for (int k = 0; k < RPW; ++k) { request(0, k); __builtin_amdgcn_sched_barrier(0); }   // in the order the loop uses them
   for (int g = 0; g < w.ag_count; ++g) {
     float c[8], s[8];
     if (DOK && !SEG) load_tab<IL>(sh, g, 0, L.jb, c, s);
-    u32x4 akl[RPW], akh[RPW], av0[RPW], av1[RPW];
-    const u32x4 z = {0, 0, 0, 0};
-#pragma unroll
-    for (int k = 0; k < RPW; ++k) {
-      akl[k] = z; akh[k] = z; av0[k] = z; av1[k] = z;
-      if (!M.valid[k]) continue;
-      const int64_t base = dest_row<T>(sh, g, wave + kWaves * k) * row_u4;
-      if (DOK && L.kok) { akl[k] = ld16<NTL>(pk + base + L.klo); akh[k] = ld16<NTL>(pk + base + L.khi); }
-      if (DOV && L.v0ok) av0[k] = ld16<NTL>(pv + base + L.v0);
-      if (DOV && L.v1ok) av1[k] = ld16<NTL>(pv + base + L.v1);
-    }
     bool differs = false;
 #pragma unroll
     for (int k = 0; k < RPW; ++k) {
-      if (!M.valid[k]) continue;
-      u32x4 rlo = z, rhi = z;
-      if (DOK && SEG) load_tab<IL>(sh, g, wave + kWaves * k, L.jb, c, s);
-      if (DOK && L.kok) rotate16<IL>(M.kl[k], M.kh[k], c, s, rlo, rhi);
-      // rows whose bits all match the reference (the common case) need no fp32 compare
-      uint32_t x = 0;
-      if (DOV) x |= chunk_xor(av0[k], M.v0[k]) | chunk_xor(av1[k], M.v1[k]);
-      if (DOK && L.kok) x |= chunk_xor(akl[k], rlo) | chunk_xor(akh[k], rhi);
-      if (__any((int)(x != 0) | (int)special[k])) {
-        if (DOK && L.kok) {
-          differs |= chunk_differs(akl[k], rlo, eps);
-          differs |= chunk_differs(akh[k], rhi, eps);
+      if (M.valid[k]) {
+        u32x4 rlo = z, rhi = z;
+        if (DOK && SEG) load_tab<IL>(sh, g, wave + kWaves * k, L.jb, c, s);
+        if (DOK) rotate16<IL>(M.kl[k], M.kh[k], c, s, rlo, rhi);
+        // rows whose bits all match the reference (the common case) need no fp32 compare
+        uint32_t x = 0;
+        if (DOV) x |= (L.v0ok ? chunk_xor(av0[k], M.v0[k]) : 0u) | (L.v1ok ? chunk_xor(av1[k], M.v1[k]) : 0u);
+        if (DOK) x |= L.kok ? chunk_xor(akl[k], rlo) | chunk_xor(akh[k], rhi) : 0u;
+        if (__any((int)(x != 0) | (int)special[k])) {
+          if (DOK && L.kok) {
+            differs |= chunk_differs(akl[k], rlo, eps);
+            differs |= chunk_differs(akh[k], rhi, eps);
+          }
+          if (DOV && L.v0ok) differs |= chunk_differs(av0[k], M.v0[k], eps);
+          if (DOV && L.v1ok) differs |= chunk_differs(av1[k], M.v1[k], eps);
         }
-        if (DOV && L.v0ok) differs |= chunk_differs(av0[k], M.v0[k], eps);
-        if (DOV && L.v1ok) differs |= chunk_differs(av1[k], M.v1[k], eps);
       }
+      request(g + 1, k);
     }
     if (__any(differs) && (threadIdx.x & 63) == 0) atomicOr(&sh.aux[g], 1);
   }
