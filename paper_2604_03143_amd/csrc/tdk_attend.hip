@@ -1008,9 +1008,17 @@ __global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2, 2))) void
 }
 
 // Both passes in one launch, for rounds with identity layouts whose stored diffs have not moved and few query
-// rows per agent: the master pass is bound by arithmetic and LDS latency, the listed-pages pass by HBM, and
-// sharing the compute units lets each fill the other's gaps.  A workgroup of the listed-pages kind = four
+// rows per agent: one ramp and one drain instead of two, and the listed-pages pass (bound by HBM) streams while
+// the master pass (bound by arithmetic and LDS latency) computes.  A workgroup of the listed-pages kind = four
 // wavefronts = four KV heads of one agent's piece; the pieces past 0, most of which leave at once, come last.
+// Where the kinds run (measured with clock stamps and the hardware ids of the compute units): the device deals
+// consecutive workgroup ids to the 8 XCDs, inside an XCD to its 4 shader engines in turn, inside an engine to its
+// compute units in turn, and the two slots of a compute unit receive ids 256 apart.  With the kinds alternating
+// in groups of 8 ids every engine holds one kind only; alternating in blocks of 32 puts both kinds on every
+// engine but still never on one compute unit; blocks of 256 pair one workgroup of each kind on every compute
+// unit.  The launch takes the same time in all three (the master workgroups slow down by what the listed ones
+// gain: both wait for memory, whose latency under this launch's own 60 MB in flight is 5 to 9 us), so the
+// simplest form stays.
 struct FusedGrid {
   int32_t n_master;      // workgroups of the master pass: heads * (sessions * chunks) * row blocks
   int32_t row_blocks;    // blocks of 128 query rows per session and KV head
@@ -1026,7 +1034,8 @@ __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(2, 2))) 
   __shared__ __attribute__((aligned(16))) unsigned char lds[kFusedLds];
   const int bid = blockIdx.x;
   // ids alternate between the kinds in groups of eight while both last (consecutive ids go to different XCDs,
-  // so both kinds reach every XCD), then come the master workgroups that are left, then the other kind's
+  // so both kinds reach every XCD, on different shader engines), then come the master workgroups that are left,
+  // then the other kind's
   const int groups = min(fg.n_master, fg.n_diff0) >> 3;
   int m_id = -1, d_id = -1;
   if (bid < 16 * groups) {
