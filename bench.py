@@ -57,12 +57,18 @@ KERNEL_SOURCES = {"hbm_traffic": ("tdk_kernels.hip", "tdk_internal.h", "tdk_type
 
 
 def csrc_hash(prefix="hbm_traffic"):
-    """sha256 over the kernel sources a counter summary under profiles/ (named by its prefix) was taken from: ties
-    the traffic figures to the kernels that ran."""
+    """sha256 over the kernel sources (comments and whitespace left out) a counter summary under profiles/ (named by
+    its prefix) was taken from: ties the traffic figures to the kernels that ran."""
     import hashlib
+    import re
     h = hashlib.sha256()
     for f in KERNEL_SOURCES[prefix]:
-        h.update(f.encode() + b"\0" + open(os.path.join(ROOT, "paper_2604_03143_amd", "csrc", f), "rb").read())
+        text = open(os.path.join(ROOT, "paper_2604_03143_amd", "csrc", f), "r", encoding="utf-8").read()
+        # the code alone: comments and layout do not change what ran (no string literal in these files holds "//")
+        text = re.sub(r"/\*.*?\*/", " ", text, flags=re.S)
+        text = re.sub(r"//[^\n]*", " ", text)
+        text = " ".join(text.split())
+        h.update(f.encode() + b"\0" + text.encode())
     return h.hexdigest()[:16]
 
 

@@ -143,17 +143,21 @@ size_t     tdk_scratch_bytes(const tdk_round* r);       /* device bytes the roun
                                             memory-side cache before anything is written           */
 #define TDK_TUNE_PREFETCH_MASTER_DECODE 64 /* the same in decode: worth 5 % when its masters were not just
                                             read by another kernel, costs 0.6 % when they were    */
-#define TDK_TUNE_XCD_QUEUES         128  /* page kernels: resident workgroups take work items from one queue per XCD
-                                            and, when theirs is empty, from the others' (the XCDs do not write at the
-                                            same rate); off: one workgroup per item, fixed to an XCD by its number */
+#define TDK_TUNE_XCD_QUEUES         128  /* the page kernels that write: two looping workgroups per compute unit take work
+                                            items from one queue per XCD and, when theirs is empty, from the others' (the
+                                            XCDs do not write at the same rate); off: one workgroup per item, fixed to an
+                                            XCD by its number */
 #define TDK_TUNE_TAPER              256  /* work list: smaller agent groups for the last pages, so that a launch does not
                                             end with a few long items on an otherwise idle chip                      */
 #define TDK_TUNE_QUEUES_ANY_SIZE    512  /* queues also for rounds with fewer than four items per resident workgroup
                                             (by default such launches stay static: it is faster there)             */
 #define TDK_TUNE_SCATTER_IN_DECODE  1024 /* small rounds (static launches): the workgroups that copy the listed pages ride
                                             behind the page items of decode's launch instead of a launch of their own */
-#define TDK_TUNE_ALL                2047
-#define TDK_TUNE_DEFAULT            (191 + 1024)
+#define TDK_TUNE_SHARED_TAIL        2048 /* static launches of the kernels that write: the last fifth of the work items goes
+                                            to whichever of the launch's last workgroups start first (an XCD that writes
+                                            faster takes more of it) instead of to fixed workgroups                     */
+#define TDK_TUNE_ALL                4095
+#define TDK_TUNE_DEFAULT            (191 + 1024 + 2048)
 tdk_status tdk_round_tune(tdk_round* r, int32_t agents_per_group, int32_t flags);
 int32_t    tdk_round_agents_per_group(const tdk_round* r);   /* the value in use (resolved if automatic); 0 for NULL */
 

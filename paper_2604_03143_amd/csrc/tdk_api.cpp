@@ -113,6 +113,8 @@ tdk_status upload_work(tdk_round* r, int group) {
     if (e != hipSuccess) return hip_fail(e, "hipMemcpy(work list)");
   }
   r->rd.n_work = (int32_t)work.size();
+  r->rd.dyn_begin = r->rd.n_work;   // (a launch that shares its tail sets these in its own copy)
+  r->rd.dyn_count = 0;
   r->group = group;
   return TDK_OK;
 }

@@ -278,7 +278,7 @@ __device__ __forceinline__ void stamp_mid(const RoundDev& rd, int item, int whic
 
 // Which work items a workgroup processes.
 //   Static: workgroup b owns item b, dispatched by the hardware round-robin over the XCDs.
-//   Queued (TDK_TUNE_XCD_QUEUES, the kernels that write): the launch holds only as many workgroups as the device keeps resident, and each
+//   Queued (TDK_TUNE_XCD_QUEUES, the kernels that write): the launch holds two workgroups per compute unit, and each
 //   takes items until none is left: first from the queue of the XCD it runs on (the items that the static form
 //   would have run there, so re-reads of a master page still meet in that XCD's L2), then from the other XCDs'
 //   queues.  The XCDs do not write to memory at the same rate (measured: four of the eight finish a static
@@ -328,7 +328,24 @@ struct Items {
   }
 
   __device__ __forceinline__ int first(const RoundDev& rd, int* s_item) {
-    if (!queued) return (int)blockIdx.x < rd.n_work ? (int)blockIdx.x : -1;
+    if (!queued) {
+      // Static launch: workgroup b owns item b, except for a shared tail (TDK_TUNE_SHARED_TAIL): the last items
+      // go, in order, to whichever of the launch's last workgroups start first (there are twice as many of those
+      // as items left, the late ones leave at once).  An XCD that writes faster gets through its share of the
+      // workgroup ids sooner and so takes more of the tail, which evens out the end of a launch too short for
+      // the looping form.  Every such workgroup does one atomic; the one that draws the last ticket puts the
+      // counter back to zero.
+      const int b = (int)blockIdx.x;
+      if (b < rd.dyn_begin) return b;
+      if (b >= rd.dyn_begin + rd.dyn_count) return -1;
+      if (threadIdx.x == 0) {
+        const int i = atomicAdd(&rd.q_state[12], 1);
+        if (i == rd.dyn_count - 1) atomicExch(&rd.q_state[12], 0);
+        *s_item = rd.dyn_begin + i < rd.n_work ? rd.dyn_begin + i : -1;
+      }
+      lds_barrier();
+      return *s_item;
+    }
     const int x = (int)blockIdx.x & 7, i = (int)blockIdx.x >> 3;
     return i < rd.q_begin[x + 1] - rd.q_begin[x] ? rd.q_begin[x] + i : -1;
   }
@@ -819,13 +836,13 @@ __global__ __launch_bounds__(kBlock) void tdk_decode_kernel(const RoundDev rd, c
   __shared__ std::conditional_t<SEG, GroupSharedSeg, GroupShared> sh;
   __shared__ int s_item;
   constexpr bool DOK = (PM & 1) != 0, DOV = (PM & 2) != 0;
-  if (!Q && (int)blockIdx.x >= rd.n_work) {
+  if (!Q && (int)blockIdx.x >= rd.dyn_begin + rd.dyn_count) {
     // Small rounds only (static launches that do not fill the chip for long): the workgroups that copy the listed
     // pages from the payload ride behind the page items of the same launch, n_scatter of them, and run while the
     // page items drain, instead of paying for a launch of their own.  (On large rounds two launches are faster:
     // payload reads among the page items' writes cost more than the second launch.)
     __shared__ ScatterShared ss;
-    scatter_slots<IL>(rd, io, d, PM, ss, (int64_t)blockIdx.x - rd.n_work, n_scatter);
+    scatter_slots<IL>(rd, io, d, PM, ss, (int64_t)blockIdx.x - (rd.dyn_begin + rd.dyn_count), n_scatter);
     return;
   }
   const Lane L = lane_geometry(rd.heads);
@@ -1200,8 +1217,8 @@ __global__ __launch_bounds__(kBlock) void tdk_page_read_product_kernel(const u32
 // Launch of a page kernel that writes (rerotate, decode).  Static distribution: one workgroup per work item.
 // Queued (TDK_TUNE_XCD_QUEUES, and only when every resident workgroup gets at least four items: below that the
 // launch is over before an imbalance between the XCDs can build up, and the hardware's own dispatch of fresh
-// workgroups fills freed wavefront slots sooner than a looping workgroup does): as many workgroups as the device
-// keeps resident.  `pick(queued)` returns the kernel instantiation for either form.
+// workgroups fills freed wavefront slots sooner than a looping workgroup does): two workgroups per compute unit
+// that loop over the items (see below).  `queued_kernel` / `static_kernel` are the two instantiations.
 // `extra` static workgroups behind the page items (decode's payload copies on small rounds); returns whether they
 // were launched (only the static form takes them).
 template <class KernelQ, class KernelS, class... Args>
@@ -1231,7 +1248,16 @@ static bool launch_write_pages(const RoundDev& rd, KernelQ queued_kernel, Kernel
     return false;
   }
   const bool ride = extra > 0 && !large && (rd.nontemporal & 1024);
-  hipLaunchKernelGGL(static_kernel, dim3((unsigned)rd.n_work + (ride ? (unsigned)extra : 0u)), dim3(kBlock), 0, st, rd, args...);
+  RoundDev rs = rd;
+  rs.dyn_begin = rd.n_work;
+  rs.dyn_count = 0;
+  if ((rd.nontemporal & 2048) && rd.n_work >= 64) {
+    // the last fifth of the items is shared (see Items::first); twice as many workgroups as items stand by for it
+    const int tail = rd.n_work / 5;
+    rs.dyn_begin = rd.n_work - tail;
+    rs.dyn_count = 2 * tail;
+  }
+  hipLaunchKernelGGL(static_kernel, dim3((unsigned)(rs.dyn_begin + rs.dyn_count) + (ride ? (unsigned)extra : 0u)), dim3(kBlock), 0, st, rs, args...);
   return ride;
 }
 

@@ -25,7 +25,8 @@ PLANE_K, PLANE_V = 1, 2
 KERNEL_KINDS = 13
 TUNE_XCD_QUEUES, TUNE_TAPER, TUNE_QUEUES_ANY_SIZE = 128, 256, 512
 TUNE_SCATTER_IN_DECODE = 1024
-TUNE_ALL, TUNE_DEFAULT = 2047, 191 + 1024
+TUNE_SHARED_TAIL = 2048
+TUNE_ALL, TUNE_DEFAULT = 4095, 191 + 1024 + 2048
 STATIC_SCRATCH_BYTES = 4 << 20
 
 EXPORTS = (

@@ -98,7 +98,7 @@ def test_theta_5e5_and_large_positions(tdo):
     run_pipeline(tdo, wl.make_round(spec_of(theta=5.0e5, hist=(18000, 33600))))
 
 
-@pytest.mark.parametrize("group,flags", [(1, 1), (2, 0), (5, 6), (32, 15), (9, 8), (9, 31), (4, 16), (9, 127), (3, 96), (9, 191), (2, 255), (32, 128), (9, 191 + 512), (5, 1023), (9, 447 + 512), (1, 896), (9, 447), (9, 1215), (3, 2047), (7, 1024 + 63)])
+@pytest.mark.parametrize("group,flags", [(1, 1), (2, 0), (5, 6), (32, 15), (9, 8), (9, 31), (4, 16), (9, 127), (3, 96), (9, 191), (2, 255), (32, 128), (9, 191 + 512), (5, 1023), (9, 447 + 512), (1, 896), (9, 447), (9, 1215), (3, 2047), (7, 1024 + 63), (9, 191 + 1024 + 2048), (3, 4095), (5, 2048 + 63), (32, 2048 + 1024)])
 def test_launch_shapes_give_identical_results(tdo, group, flags):
     rnd = wl.make_round(spec_of(sessions=3, agents=7, blocks=3, block_tokens=50))
     run_pipeline(tdo, rnd, group=group, flags=flags)
@@ -374,7 +374,7 @@ def test_step_argument_errors(tdo):
         with pytest.raises(tdk.TdkError):
             tdk.tdk_round_tune(g.r, 33, 1)
         with pytest.raises(tdk.TdkError):
-            tdk.tdk_round_tune(g.r, 4, 2048)
+            tdk.tdk_round_tune(g.r, 4, 4096)
         assert tdk.tdk_scratch_bytes(g.r) > 0
     finally:
         g.close()

@@ -24,7 +24,7 @@ def _draw(case: int):
     spec = wl.RoundSpec(f"rnd{case}", 300 + case, 1, H, 128, T, float(g.choice([1.0e4, 5.0e5, 1.0e6])),
                         sessions, agents, blocks, block_tokens, lo, hi, frac)
     return dict(spec=spec, style=int(g.integers(0, 2)), group=int(g.choice([0, 1, 3, 7, 32])),
-                flags=int(g.integers(0, 128)) | (128 if case % 2 else 0) | (256 if case % 4 < 2 else 0) | (512 if case % 3 else 1024), permuted=bool(g.integers(0, 3) == 0), clustered=bool(g.integers(0, 2)))
+                flags=int(g.integers(0, 128)) | (128 if case % 2 else 0) | (256 if case % 4 < 2 else 0) | (512 if case % 3 else 1024) | (2048 if case % 5 < 3 else 0), permuted=bool(g.integers(0, 3) == 0), clustered=bool(g.integers(0, 2)))
 
 
 @pytest.mark.parametrize("case", range(24))
