@@ -51,7 +51,7 @@ class Piece:
 
 
 @pytest.mark.parametrize("which", ["layer0", "seeded"])
-@pytest.mark.parametrize("name", ["batched250", "long", "llama70b"])
+@pytest.mark.parametrize("name", ["session", "batched250", "long", "llama70b"])
 def test_every_agent_against_the_oracle(tdo, name, which):
     import torch
     from paper_2604_03143_amd import tdk
