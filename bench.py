@@ -411,13 +411,15 @@ def restore_mode(args, tdk, wl, np, torch, dev):
         for _ in range(3):          # the runtime builds its cross-stream signals during the first calls
             fn()
         torch.cuda.synchronize()
-        t0 = time.perf_counter()
-        for _ in range(reps):
+        ts = []
+        for _ in range(reps):       # every repetition on its own clock: the median is robust against a disturbed one
+            t0 = time.perf_counter()
             fn()
-        torch.cuda.synchronize()
-        return (time.perf_counter() - t0) / reps
+            torch.cuda.synchronize()
+            ts.append(time.perf_counter() - t0)
+        return float(np.median(ts))
 
-    reps = max(1, args.steps)
+    reps = max(20, args.steps)
     dc = [d["c"] for d in diffs]
     t_pp = wall(lambda: tdk.tdk_restore_layers(r, 0, hk, hv, ios, dc, pp, comp.cuda_stream, copy.cuda_stream), reps)
     # layer L-1 was restored last: check layer 0 separately below; serial = both roles on one stream

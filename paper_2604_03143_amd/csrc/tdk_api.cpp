@@ -276,6 +276,7 @@ tdk_status round_create(const tdk_model* model, const tdk_session* sessions, int
   r->sessions = p.sessions;
   r->max_phys_page = p.max_phys_page;
   r->total_pages = p.total_pages;
+  r->rd.agent_pages = p.total_pages;
   r->total_master_pages = p.total_master_pages;
   r->total_master_rows = p.total_master_rows;
   r->total_tokens = p.total_tokens;

@@ -1238,7 +1238,9 @@ static bool launch_write_pages(const RoundDev& rd, KernelQ queued_kernel, Kernel
     }
   }
   const int64_t resident = (int64_t)n * std::max(rd.n_cus, 1);
-  const bool large = (int64_t)rd.n_work >= 4 * resident;
+  // long enough for the looping form: at least four items and at least 32 (agent, page) pairs per resident
+  // workgroup (a round cut into many small items, such as one agent per item, is no longer than its pairs)
+  const bool large = (int64_t)rd.n_work >= 4 * resident && rd.agent_pages >= 32 * resident;
   if ((rd.nontemporal & 128) && (large || (rd.nontemporal & 512))) {
     // Two looping workgroups per compute unit, although three fit: memory is saturated with one per unit already,
     // and the fewer pages are being written at a time, the better DRAM takes it (batched250: decode 876 us with
