@@ -107,7 +107,8 @@ def test_many_exact_ties_and_zeros(tdo):
     run_case(tdo, wl.make_round(spec_of(frac=0.0)), 0.2, 0.0, fill=fill)
 
 
-@pytest.mark.parametrize("kw,style", [(dict(H=4), 0), (dict(T=32), 0), (dict(H=8), 1), (dict(hist=(5000, 30000), theta=5.0e5), 0)])
+@pytest.mark.parametrize("kw,style", [(dict(H=4), 0), (dict(T=32), 0), (dict(H=8), 1), (dict(hist=(5000, 30000), theta=5.0e5), 0),
+                                      (dict(H=1), 0), (dict(H=3, T=32), 1), (dict(H=2, agents=33, sessions=1), 0)])
 def test_geometries(tdo, kw, style):
     run_case(tdo, wl.make_round(spec_of(**kw)), 0.15, 0.0, noise_everywhere=0.02, style=style)
 
