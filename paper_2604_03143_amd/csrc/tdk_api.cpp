@@ -99,10 +99,12 @@ struct tdk_round {
 
 namespace {
 
-tdk_status upload_work(tdk_round* r, int group) {
-  std::vector<WorkItem> work;
+// group: agents per work item; read_group: the same for the kernels that only read (equal when the caller named one)
+tdk_status upload_work(tdk_round* r, int group, int read_group) {
+  std::vector<WorkItem> work, rwork;
   plan_work(r->sessions, group, (r->flags & TDK_TUNE_TAPER) != 0, work);
-  if (work.size() > r->work_capacity) return fail(TDK_ERR_INVALID_ARG, "work list larger than reserved");
+  plan_work(r->sessions, read_group, false, rwork);
+  if (work.size() > r->work_capacity || rwork.size() > r->work_capacity) return fail(TDK_ERR_INVALID_ARG, "work list larger than reserved");
   std::vector<WorkItem> queued;
   plan_queues(work, queued, r->rd.q_begin);
   if (!work.empty()) {
@@ -110,9 +112,12 @@ tdk_status upload_work(tdk_round* r, int group) {
                              hipMemcpyHostToDevice);
     if (e == hipSuccess) e = hipMemcpy(const_cast<WorkItem*>(r->rd.qwork), queued.data(), queued.size() * sizeof(WorkItem),
                                        hipMemcpyHostToDevice);
+    if (e == hipSuccess) e = hipMemcpy(const_cast<WorkItem*>(r->rd.rwork), rwork.data(), rwork.size() * sizeof(WorkItem),
+                                       hipMemcpyHostToDevice);
     if (e != hipSuccess) return hip_fail(e, "hipMemcpy(work list)");
   }
   r->rd.n_work = (int32_t)work.size();
+  r->rd.n_rwork = (int32_t)rwork.size();
   r->rd.dyn_begin = r->rd.n_work;   // (a launch that shares its tail sets these in its own copy)
   r->rd.dyn_count = 0;
   r->group = group;
@@ -308,6 +313,7 @@ tdk_status round_create(const tdk_model* model, const tdk_session* sessions, int
   auto place = [&](size_t bytes) { size_t o = off; off = align_up(off + bytes, 256); return o; };
   const size_t o_work = place(work_cap * sizeof(WorkItem));
   const size_t o_qwork = place(work_cap * sizeof(WorkItem));
+  const size_t o_rwork = place(work_cap * sizeof(WorkItem));
   const size_t o_sess = place(sess_dev.size() * sizeof(SessionDev));
   const size_t o_agents = place(agent_dev.size() * sizeof(AgentDev));
   const size_t o_order = place(order.size() * sizeof(int32_t));
@@ -354,6 +360,7 @@ tdk_status round_create(const tdk_model* model, const tdk_session* sessions, int
 
   r->rd.work = reinterpret_cast<const WorkItem*>(base + o_work);
   r->rd.qwork = reinterpret_cast<const WorkItem*>(base + o_qwork);
+  r->rd.rwork = reinterpret_cast<const WorkItem*>(base + o_rwork);
   r->rd.sess = reinterpret_cast<const SessionDev*>(base + o_sess);
   r->rd.agents = reinterpret_cast<const AgentDev*>(base + o_agents);
   r->rd.order = reinterpret_cast<const int32_t*>(base + o_order);
@@ -378,7 +385,7 @@ tdk_status round_create(const tdk_model* model, const tdk_session* sessions, int
   r->rd.interleaved = model->rope_style == TDK_ROPE_INTERLEAVED;
   r->rd.nontemporal = r->flags & TDK_TUNE_ALL;
 
-  st = upload_work(r, plan_auto_group(r->sessions));
+  st = upload_work(r, plan_auto_group(r->sessions), plan_auto_group(r->sessions, true));
   if (st != TDK_OK) return st;
   for (int b = 0; b < 2 && e == hipSuccess; ++b) {
     e = hipEventCreateWithFlags(&r->ev_loaded[b], hipEventDisableTiming);
@@ -435,7 +442,8 @@ tdk_status tdk_round_tune(tdk_round* r, int32_t agents_per_group, int32_t flags)
     if (e != hipSuccess) return hip_fail(e, "hipDeviceSynchronize");
     r->flags = flags;
     r->rd.nontemporal = flags & TDK_TUNE_ALL;
-    return upload_work(r, agents_per_group ? agents_per_group : plan_auto_group(r->sessions));
+    return upload_work(r, agents_per_group ? agents_per_group : plan_auto_group(r->sessions),
+                       agents_per_group ? agents_per_group : plan_auto_group(r->sessions, true));
   });
 }
 

@@ -31,6 +31,8 @@ struct RoundDev {
   unsigned long long* stamps;  // measurement only: [2 x work items] start / end clock of every work item, or NULL
   int32_t*          q_state; // [16] work queues: [0..7] next item of each XCD's queue, [8] workgroups that have left, [12] next item of a static launch's shared tail; all zero between launches
   int64_t           agent_pages;           // sum over agents of their session's page count: the length of a page-kernel launch
+  const WorkItem*   rwork;                 // the work list of the kernels that only read (compare, key difference): it may be coarser
+  int32_t           n_rwork;
   int32_t           dyn_begin, dyn_count;  // static launches of the write kernels: workgroups [dyn_begin, dyn_begin + dyn_count) take the items from dyn_begin on in the order they start (set per launch; dyn_begin = n_work, dyn_count = 0: none)
   int32_t           q_begin[9];  // XCD x's queue is work[q_begin[x] .. q_begin[x + 1])
   int32_t           n_cus;

@@ -459,7 +459,7 @@ __global__ __launch_bounds__(kBlock) void tdk_flag_kernel(const RoundDev rd, con
   const u32x4* pv = io.pool_v;
   const int item = blockIdx.x;
   stamp_begin(rd, item);
-  const WorkItem w = rd.work[item];
+  const WorkItem w = rd.rwork[item];
   stage_group<T>(rd, w, sh);
   MasterRows<RPW> M;
   load_master<RPW, DOV, DOK>(rd, io, w, L, M);
@@ -949,7 +949,7 @@ __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(RPW == 4
   const int wave = threadIdx.x >> 6;
   const int64_t row_u4 = (int64_t)rd.heads * 16;
   const u32x4* pk = io.pool_k;
-  const WorkItem w = rd.work[blockIdx.x];
+  const WorkItem w = rd.rwork[blockIdx.x];
   stage_group<T>(rd, w, sh);
   MasterRows<RPW> M;
   load_master<RPW, false>(rd, io, w, L, M);
@@ -1287,7 +1287,7 @@ hipError_t launch_flag(const RoundDev& rd, const LayerDev& io, float eps, int pl
   with_rpw(rd.page_tokens, [&](auto rpw) { with_bool(rd.interleaved != 0, [&](auto il) { with_planes(planes, [&](auto pm) {
     with_bool(rd.seg != 0, [&](auto sg) { with_bool((rd.nontemporal & 4) != 0, [&](auto ntl) {
       hipLaunchKernelGGL((tdk_flag_kernel<decltype(rpw)::value, decltype(il)::value, decltype(pm)::value, decltype(sg)::value, decltype(ntl)::value>),
-                         dim3(rd.n_work), dim3(kBlock), 0, st, rd, io, eps);
+                         dim3(rd.n_rwork), dim3(kBlock), 0, st, rd, io, eps);
     }); });
   }); }); });
   return hipGetLastError();
@@ -1334,7 +1334,7 @@ hipError_t launch_keydiff(const RoundDev& rd, const LayerDev& io, const PlanDev&
   with_rpw(rd.page_tokens, [&](auto rpw) { with_bool(rd.interleaved != 0, [&](auto il) { with_bool(rd.seg != 0, [&](auto sg) {
     with_bool((rd.nontemporal & 4) != 0, [&](auto ntl) {
       hipLaunchKernelGGL((tdk_keydiff_kernel<decltype(rpw)::value, decltype(il)::value, decltype(sg)::value, decltype(ntl)::value>),
-                         dim3(rd.n_work), dim3(kBlock), 0, st, rd, io, pl);
+                         dim3(rd.n_rwork), dim3(kBlock), 0, st, rd, io, pl);
     });
   }); }); });
   return hipGetLastError();

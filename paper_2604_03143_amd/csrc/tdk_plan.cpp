@@ -253,13 +253,16 @@ void plan_work(const std::vector<PlanSession>& sessions, int group, bool taper, 
   }
 }
 
-int plan_auto_group(const std::vector<PlanSession>& sessions) {
+int plan_auto_group(const std::vector<PlanSession>& sessions, bool read_kernels) {
   // Measured on MI355X: about 9 agents per work item is the best trade between re-reads of the
   // master page (one per work item, served by the XCD's L2) and the number of work items; rounds
   // too small to give ~2800 items that way are split further (a launch of one workgroup per item then runs
   // three to four rounds of the chip's workgroup slots instead of one and a bit: the 25-agent session
   // steps in 15.31 ms with 3 agents per item, 2817 items, against 15.48 ms with 9 agents, 939 items).
-  const int64_t target = 2800;
+  // The kernels that only read have their own list: every item re-reads its master page, which costs them more
+  // than the coarser end of their launch (the same session: compare kernel 87 us with 9 agents per item, 91 with 3),
+  // so they stop splitting at ~900 items.
+  const int64_t target = read_kernels ? 900 : 2800;
   int best = 9;
   for (int g = 9; g >= 1; --g) {
     int64_t items = 0;

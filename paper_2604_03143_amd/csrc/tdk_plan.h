@@ -53,6 +53,6 @@ tdk_status plan_round(const tdk_model* model, const tdk_session* sessions, int32
 // items grouped by that XCD (queue x = queued[q_begin[x] .. q_begin[x + 1])).
 void plan_work(const std::vector<PlanSession>& sessions, int group, bool taper, std::vector<WorkItem>& work);
 void plan_queues(const std::vector<WorkItem>& work, std::vector<WorkItem>& queued, int32_t (&q_begin)[9]);
-int  plan_auto_group(const std::vector<PlanSession>& sessions);
+int  plan_auto_group(const std::vector<PlanSession>& sessions, bool read_kernels = false);   // agents per work item when the caller names none
 
 }  // namespace tdk

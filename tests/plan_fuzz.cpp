@@ -183,8 +183,8 @@ int main() {
     }
     REQUIRE(p.total_pages == pages_sum && p.total_tokens == tokens_sum && p.max_phys_page == max_page);
     // work lists: every (agent, page) exactly once, whatever the group size; the queues hold the same items
-    for (int trial = 0; trial < 3; ++trial) {
-      const int group = trial == 0 ? plan_auto_group(p.sessions) : (int)between(1, kMaxGroup);
+    for (int trial = 0; trial < 4; ++trial) {
+      const int group = trial == 0 ? plan_auto_group(p.sessions) : trial == 1 ? plan_auto_group(p.sessions, true) : (int)between(1, kMaxGroup);
       REQUIRE(group >= 1 && group <= kMaxGroup);
       std::vector<WorkItem> work, queued;
       plan_work(p.sessions, group, rnd() % 2, work);
