@@ -8,7 +8,10 @@ from paper_2604_03143_amd import workload as wl
 pytestmark = pytest.mark.gpu
 
 
-def test_step_captured_in_a_graph_replays_exactly(tdo):
+@pytest.mark.parametrize("queues", [False, True])
+def test_step_captured_in_a_graph_replays_exactly(tdo, queues):
+    """queues: the write kernels in their looping form (work queues whose counters the kernels put back to zero
+    themselves); otherwise static launches with a shared tail (one more such counter)."""
     import torch
     from paper_2604_03143_amd import tdk
     import gpu_helpers as gh
@@ -19,6 +22,8 @@ def test_step_captured_in_a_graph_replays_exactly(tdo):
     L = spec.num_layers
     runs = [gh.GpuRun(rnd, layer=l) for l in range(L)]
     r = runs[0].r
+    if queues:
+        tdk.tdk_round_tune(r, 0, tdk.TUNE_DEFAULT | tdk.TUNE_QUEUES_ANY_SIZE)
     stored, fresh = [], []
     for l, g in enumerate(runs):                     # eager set-up: the mirrors each layer stores
         tdk.tdk_rerotate_round(r, l, g.io, g.stream)
